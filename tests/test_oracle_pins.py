@@ -1,0 +1,459 @@
+"""Pins for the CPU oracle: everything the paper and the mathematics fix about
+AD-PSGD's per-event update, checked against the oracle alone (no GPU).
+
+Each test is chosen so that a plausible mistake in the oracle (a dropped term, a
+wrong sign or index, a transposed operand, reading the wrong snapshot) fails it.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from workloads import ring_graph, random_regular4_graph, lsq_data, logreg_data
+
+LSQ, LOGREG, SYNTH, MLP = oracle.MODEL_LSQ, oracle.MODEL_LOGREG, oracle.MODEL_SYNTH, oracle.MODEL_MLP
+
+
+# --------------------------------------------------------------------------- generator
+def test_philox_known_answers(golden_dir):
+    rows = [l.split() for l in open(os.path.join(golden_dir, "philox4x32_10_kat.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        w = [int(t, 16) for t in r]
+        out = oracle.philox4x32_10(w[0:4], w[4:6])
+        assert [int(v) for v in out] == w[6:10]
+
+
+def test_schedule_ranges_and_laws():
+    n, K, M, T = 8, 40000, 4, 3
+    g = ring_graph(n)
+    rows = np.arange(10, 10 + n)
+    s = oracle.make_schedule(g, K, seed=5, T_max=T, M=M, rows=rows)
+    w, j, tau, b = s["worker"], s["neighbour"], s["tau"], s["batch_idx"]
+    assert w.min() == 0 and w.max() == n - 1
+    # neighbour is a ring neighbour of the worker
+    assert np.all((j == (w - 1) % n) | (j == (w + 1) % n))
+    # staleness within bounds and never beyond the events available
+    assert tau.min() == 0 and tau.max() == T and np.all(tau <= np.arange(K))
+    # minibatch indices address the worker's own rows
+    assert np.all(b >= 0) and np.all(b < rows[w][:, None])
+    # uniform laws (5-sigma binomial bands)
+    for counts, p in ((np.bincount(w, minlength=n), 1 / n),
+                      (np.bincount(tau[100:], minlength=T + 1), 1 / (T + 1))):
+        tot = counts.sum()
+        assert np.all(np.abs(counts - tot * p) < 5 * np.sqrt(tot * p * (1 - p)))
+    left = np.mean(j == (w - 1) % n)
+    assert abs(left - 0.5) < 5 * 0.5 / np.sqrt(K)
+    # events are a pure function of (seed, k): a later window repeats the same draws
+    s2 = oracle.make_schedule(g, 100, seed=5, k_begin=1000, T_max=T, M=M, rows=rows)
+    assert np.array_equal(s2["worker"], w[1000:1100])
+    assert np.array_equal(s2["neighbour"], j[1000:1100])
+    assert np.array_equal(s2["batch_idx"], b[1000:1100])
+    assert np.array_equal(s2["tau"][T:], tau[1000 + T:1100])
+    # a different seed gives a different stream
+    s3 = oracle.make_schedule(g, K, seed=6, T_max=T, M=M, rows=rows)
+    assert np.mean(s3["worker"] == w) < 0.2
+
+
+def test_schedule_weighted_workers_and_geometric_staleness():
+    n, K = 6, 60000
+    g = random_regular4_graph(n, seed=1)
+    weight = np.array([10, 10, 1, 10, 1, 10])
+    num = np.where(weight == 1, 20, 2)
+    den = np.where(weight == 1, 21, 3)
+    s = oracle.make_schedule(g, K, seed=3, T_max=400, tau_mode=1, weight=weight,
+                             tau_num=num, tau_den=den)
+    w, tau = s["worker"], s["tau"]
+    p = weight / weight.sum()
+    counts = np.bincount(w, minlength=n)
+    assert np.all(np.abs(counts - K * p) < 5 * np.sqrt(K * p * (1 - p)))
+    # P(tau >= t) = q^t  =>  mean q / (1 - q): 2 for the fast class, 20 for the slow one
+    late = np.arange(K) > 2000
+    fast, slow = tau[late & (weight[w] == 10)], tau[late & (weight[w] == 1)]
+    assert abs(fast.mean() - 2.0) < 5 * np.sqrt(6.0 / fast.size)       # var = q/(1-q)^2 = 6
+    assert abs(slow.mean() - 20.0) < 5 * np.sqrt(420.0 / slow.size)    # var = 420
+    assert abs(np.mean(fast >= 3) - (2 / 3) ** 3) < 0.01
+    # cap
+    s = oracle.make_schedule(g, 5000, seed=3, T_max=7, tau_mode=1, weight=weight,
+                             tau_num=num, tau_den=den)
+    assert s["tau"].max() == 7
+
+
+def test_synthetic_gradient_is_standard_normal():
+    from scipy import stats
+    coords = np.arange(200000)
+    z = oracle.synth_grad(7, 3, 1.0, coords).astype(np.float64)
+    assert abs(z.mean()) < 5 / np.sqrt(z.size)
+    assert abs(z.var() - 1.0) < 5 * np.sqrt(2.0 / z.size)
+    assert stats.kstest(z, "norm").pvalue > 1e-3
+    assert abs(stats.kurtosis(z)) < 0.1
+    # the four values of one generator call, and neighbouring events, are uncorrelated
+    q = z.reshape(-1, 4)
+    c = np.corrcoef(q.T)
+    assert np.max(np.abs(c - np.eye(4))) < 0.03
+    z2 = oracle.synth_grad(7, 4, 1.0, coords).astype(np.float64)
+    assert abs(np.corrcoef(z, z2)[0, 1]) < 0.02
+    # scaling by std and addressing by coordinate: a subset reproduces the same entries
+    sub = np.array([5, 17, 4096, 199999])
+    assert np.array_equal(oracle.synth_grad(7, 3, 1.0, sub), z[sub].astype(np.float32))
+    g = oracle.synth_grad(7, 3, 0.25, coords)
+    assert np.allclose(g, 0.25 * z, rtol=1e-6, atol=0)
+
+
+# --------------------------------------------------------------------------- gradients
+def test_lsq_gradient_matches_normal_equations():
+    rng = np.random.default_rng(0)
+    rows, d, M = 50, 33, 16
+    A = rng.standard_normal((rows, d)).astype(np.float32)
+    b = rng.standard_normal(rows).astype(np.float32)
+    x = rng.standard_normal(d).astype(np.float32)
+    idx = rng.integers(0, rows, M)
+    g, loss = oracle.minibatch_gradient(LSQ, x, A, b, idx, 1.0 / M)
+    Ab, bb = A[idx].astype(np.float64), b[idx].astype(np.float64)
+    r = Ab @ x.astype(np.float64) - bb
+    assert np.allclose(g, Ab.T @ r / M, rtol=1e-6, atol=1e-6)
+    assert np.isclose(loss, 0.5 * np.mean(r * r), rtol=1e-12)
+    # the paper's literal sum over the minibatch is M times the mean
+    gs, ls = oracle.minibatch_gradient(LSQ, x, A, b, idx, 1.0)
+    assert np.allclose(gs, M * (Ab.T @ r / M), rtol=1e-6, atol=1e-5)
+
+
+def test_logreg_loss_and_gradient():
+    rng = np.random.default_rng(1)
+    rows, d, M, lam = 40, 21, 12, 0.3
+    A = rng.standard_normal((rows, d)).astype(np.float32)
+    y = np.where(rng.standard_normal(rows) > 0, 1.0, -1.0).astype(np.float32)
+    x = (0.5 * rng.standard_normal(d)).astype(np.float32)
+    idx = rng.integers(0, rows, M)
+    g, loss = oracle.minibatch_gradient(LOGREG, x, A, y, idx, 1.0 / M, lam=lam)
+    x64 = x.astype(np.float64)
+    margins = y[idx] * (A[idx].astype(np.float64) @ x64)
+    assert np.isclose(loss, np.mean(np.logaddexp(0.0, -margins)) + 0.5 * lam * x64 @ x64, rtol=1e-12)
+
+    # the gradient is the derivative of the returned loss: central differences
+    def loss_at(v):
+        return oracle.minibatch_gradient(LOGREG, v.astype(np.float32), A, y, idx, 1.0 / M, lam=lam)[1]
+    h = 2.0 ** -8          # exactly representable steps so that x +- h e is exact in fp32
+    xq = np.round(x * 256) / 256
+    gq, _ = oracle.minibatch_gradient(LOGREG, xq.astype(np.float32), A, y, idx, 1.0 / M, lam=lam)
+    for e in range(d):
+        step = np.zeros(d)
+        step[e] = h
+        fd = (loss_at(xq + step) - loss_at(xq - step)) / (2 * h)
+        assert abs(fd - gq[e]) < 1e-4
+
+
+def test_mlp_gradient_matches_autograd_with_same_roundings():
+    torch = pytest.importorskip("torch")
+    from workloads import mixture_data, mlp_init, bf16_bits_to_f32
+    I, H, O, M, rows = 20, 24, 5, 8, 30
+    feats, labels, _ = mixture_data(1, rows, din=I, classes=O, seed=2)
+    x0 = mlp_init(I, H, O, seed=2)
+    rng = np.random.default_rng(3)
+    x0 = (x0 + 0.05 * rng.standard_normal(x0.size)).astype(np.float32)   # non-zero biases
+    idx = rng.integers(0, rows, M)
+    g, loss = oracle.minibatch_gradient(MLP, x0, feats[0], labels[0], idx, 1.0 / M, mlp=(I, H, O))
+
+    def bf(t):   # round-to-nearest-even to bf16, kept in fp64
+        return t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+    class RoundGrad(torch.autograd.Function):      # identity forward, bf16-rounded backward
+        @staticmethod
+        def forward(ctx, t):
+            return t
+        @staticmethod
+        def backward(ctx, gr):
+            return bf(gr)
+
+    p = torch.tensor(bf16_round_np(x0), dtype=torch.float64, requires_grad=True)
+    W1 = p[:I * H].view(I, H); b1 = p[I * H:I * H + H]
+    W2 = p[I * H + H:I * H + H + H * O].view(H, O); b2 = p[I * H + H + H * O:]
+    Xb = torch.tensor(bf16_bits_to_f32(feats[0][idx]), dtype=torch.float64)
+    pre = (Xb @ W1 + b1).to(torch.float32).to(torch.float64)
+    pre = RoundGrad.apply(pre)
+    hid = torch.relu(pre)
+    hid = hid + (bf(hid) - hid).detach()           # forward sees the bf16-rounded activation
+    logits = hid @ W2 + b2
+    lt = torch.nn.functional.cross_entropy(logits, torch.tensor(labels[0][idx], dtype=torch.long),
+                                           reduction="mean")
+    lt.backward()
+    ref = p.grad.numpy()
+    assert np.isclose(loss, lt.item(), rtol=1e-9)
+    # layer-2 and bias terms agree to rounding; layer-1 terms agree up to the bf16 rounding of
+    # the back-propagated error (the oracle rounds after the 1/M scale, autograd before it is
+    # scaled identically, so they agree exactly too)
+    assert np.allclose(g, ref, rtol=2e-6, atol=1e-7)
+
+
+def bf16_round_np(x):
+    return oracle.round_bf16(x)
+
+
+def test_bf16_rounding_is_nearest_even():
+    import torch
+    rng = np.random.default_rng(4)
+    x = np.concatenate([rng.standard_normal(5000), [0.0, 1.0, 1.00390625, 1.01171875, -3.0e38, 1e-40]]
+                       ).astype(np.float32)
+    ref = torch.tensor(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(oracle.round_bf16(x), ref)
+
+
+# --------------------------------------------------------------------------- the event
+def _unit_quadratic_data(n, diag):
+    """f_i(x) = sum_e diag[e] x_e^2 / 2 written as least squares: row e = sqrt(diag[e]) e_e, b = 0;
+    a 'minibatch' listing every row once with scale 1 is the full gradient diag * x."""
+    d = len(diag)
+    A = np.diag(np.sqrt(np.asarray(diag, dtype=np.float64))).astype(np.float32)
+    b = np.zeros(d, dtype=np.float32)
+    return [A] * n, [b] * n
+
+
+def test_hand_expanded_two_workers(golden_dir):
+    cases = [l.split() for l in open(os.path.join(golden_dir, "alg1_two_workers_d1.txt"))
+             if l.strip() and not l.startswith("#")]
+    feats, targs = _unit_quadratic_data(2, [1.0])
+    for name, i0, j0, t0, i1, j1, t1, e0, e1 in cases:
+        for mode in (0, 1):
+            X = np.array([[1.0], [3.0]], dtype=np.float32)
+            sched = {"worker": [int(i0), int(i1)], "neighbour": [int(j0), int(j1)],
+                     "tau": [int(t0), int(t1)], "batch_idx": np.zeros((2, 1), np.int32)}
+            oracle.run_events(X, sched, LSQ, 0.5, M=1, gscale=1.0, features=feats, targets=targs, mode=mode)
+            assert X[0, 0] == float(e0) and X[1, 0] == float(e1), name
+
+
+def _matrix_form_bruteforce(X0, diag, gamma, sched):
+    """X_{k+1} = X_k W_k - gamma dg(X^_k) in exact rational arithmetic, with W_k and dg as
+    explicit matrices and the whole history kept (columns = workers, as in the paper)."""
+    n = len(X0)
+    d = len(X0[0])
+    Xk = [[Fraction(X0[i][e]) for i in range(n)] for e in range(d)]      # d x n
+    hist = []
+    for k, (i, j, tau) in enumerate(zip(sched["worker"], sched["neighbour"], sched["tau"])):
+        hist.append([row[:] for row in Xk])
+        W = [[Fraction(int(a == b)) for b in range(n)] for a in range(n)]
+        if i != j:
+            for a in (i, j):
+                for b in (i, j):
+                    W[a][b] -= Fraction(1, 2) * (1 if a == b else -1)
+        XW = [[sum(Xk[e][a] * W[a][b] for a in range(n)) for b in range(n)] for e in range(d)]
+        old = hist[k - tau]
+        dg = [[Fraction(0)] * n for _ in range(d)]
+        for e in range(d):
+            dg[e][i] = Fraction(diag[e]) * old[e][i]
+        Xk = [[XW[e][b] - Fraction(gamma) * dg[e][b] for b in range(n)] for e in range(d)]
+    return [[float(Xk[e][i]) for e in range(d)] for i in range(n)]
+
+
+@pytest.mark.parametrize("n", [2, 3])
+def test_bruteforce_matrix_form_d4(n):
+    diag = [1.0, 4.0, 0.25, 16.0]
+    gamma = 0.0625
+    X0 = [[1.0, -2.0, 3.0, 0.5], [3.0, 1.0, -1.0, 2.0], [-4.0, 0.25, 8.0, -1.0]][:n]
+    if n == 2:
+        sched = {"worker": [0, 1, 1, 0, 1], "neighbour": [1, 0, 0, 1, 0], "tau": [0, 1, 2, 0, 3]}
+    else:
+        sched = {"worker": [0, 2, 1, 1, 0, 2], "neighbour": [1, 1, 0, 2, 2, 0], "tau": [0, 1, 0, 3, 2, 4]}
+    expect = _matrix_form_bruteforce(X0, diag, gamma, sched)
+    feats, targs = _unit_quadratic_data(n, diag)
+    full = dict(sched, batch_idx=np.tile(np.arange(4, dtype=np.int32), (len(sched["tau"]), 1)))
+    for mode in (0, 1):
+        X = np.array(X0, dtype=np.float32)
+        oracle.run_events(X, full, LSQ, gamma, M=4, gscale=1.0, features=feats, targets=targs, mode=mode)
+        assert np.array_equal(X.astype(np.float64), np.array(expect)), mode   # dyadic values: exact
+
+
+def _random_problem(n, d, rows, K, M, T, seed, model=LSQ):
+    g = ring_graph(n) if seed % 2 == 0 else random_regular4_graph(max(n, 5), seed)
+    n = len(g[0]) - 1
+    if model == LSQ:
+        feats, targs, _ = lsq_data(n, rows, d, seed=seed)
+    else:
+        feats, targs, _ = logreg_data(n, rows, d, seed=seed)
+    sched = oracle.make_schedule(g, K, seed=seed, T_max=T, M=M, rows=np.full(n, rows))
+    rng = np.random.default_rng(seed + 100)
+    X0 = rng.standard_normal((n, d)).astype(np.float32)
+    return n, feats, targs, sched, X0
+
+
+@pytest.mark.parametrize("model,seed", [(LSQ, 0), (LSQ, 1), (LOGREG, 2), (LOGREG, 3)])
+def test_literal_history_equals_parked_gradients(model, seed):
+    n, feats, targs, sched, X0 = _random_problem(6, 19, 12, 300, 5, 7, seed, model)
+    Xa, Xb = X0.copy(), X0.copy()
+    ra = oracle.run_events(Xa, sched, model, 0.01, M=5, gscale=0.2, lam=0.01, features=feats,
+                           targets=targs, mode=0, want_loss=True, want_g=True)
+    rb = oracle.run_events(Xb, sched, model, 0.01, M=5, gscale=0.2, lam=0.01, features=feats,
+                           targets=targs, mode=1, want_loss=True, want_g=True)
+    assert np.array_equal(Xa, Xb)
+    assert np.array_equal(ra["g"], rb["g"]) and np.array_equal(ra["loss"], rb["loss"])
+    assert sched["tau"].max() == 7      # the stale path was exercised
+    # and staleness matters: forcing tau = 0 changes the result
+    Xc = X0.copy()
+    oracle.run_events(Xc, dict(sched, tau=np.zeros_like(sched["tau"])), model, 0.01, M=5, gscale=0.2,
+                      lam=0.01, features=feats, targets=targs, mode=0)
+    assert not np.array_equal(Xa, Xc)
+
+
+def test_zero_staleness_equals_naive_loop():
+    """tau = 0 for every event: x^ is the worker's current row, read before the average."""
+    n, feats, targs, sched, X0 = _random_problem(6, 17, 10, 200, 4, 0, 4)
+    X = X0.copy()
+    oracle.run_events(X, sched, LSQ, 0.02, M=4, gscale=0.25, features=feats, targets=targs, mode=0)
+    Y = X0.copy()
+    for k in range(200):
+        i, j = sched["worker"][k], sched["neighbour"][k]
+        g, _ = oracle.minibatch_gradient(LSQ, Y[i], feats[i], targs[i], sched["batch_idx"][k], 0.25)
+        avg = (Y[i] + Y[j]) * np.float32(0.5)
+        Y[j] = avg
+        Y[i] = avg - np.float32(0.02) * g
+    assert np.array_equal(X, Y)
+
+
+def test_per_event_postconditions_and_telescoping_sum():
+    n, feats, targs, sched, X0 = _random_problem(6, 23, 12, 400, 5, 5, 6)
+    gamma = 0.01
+    X = X0.copy()
+    total_g = np.zeros(23)
+    for k in range(400):
+        one = {key: (val[:k + 1] if val is not None else None) for key, val in sched.items()}
+        before = X.copy()
+        # replay the prefix so that stale reads see the true history, keep only the last event
+        Y = X0.copy()
+        r = oracle.run_events(Y, one, LSQ, gamma, M=5, gscale=0.2, features=feats, targets=targs,
+                              mode=0, want_g=True)
+        g = r["g"][k]
+        i, j = sched["worker"][k], sched["neighbour"][k]
+        X = Y
+        others = [r_ for r_ in range(n) if r_ not in (i, j)]
+        assert np.array_equal(X[others], before[others])                 # untouched rows bit-identical
+        avg = (before[i].astype(np.float64) + before[j]) / 2
+        assert np.allclose(X[j], avg, rtol=1e-6, atol=1e-7)                # both rows took the average
+        assert np.allclose(X[i].astype(np.float64) - X[j], -gamma * g.astype(np.float64),
+                           rtol=1e-5, atol=2e-7)                           # x_i - x_j = -gamma g_k
+        # averaging preserves the sum over workers: the sum moves only by -gamma g_k
+        assert np.allclose(X.sum(0, dtype=np.float64), before.sum(0, dtype=np.float64) - gamma * g,
+                           rtol=0, atol=5e-6)
+        total_g += g
+        if k > 40:
+            break
+    Xf = X0.copy()
+    r = oracle.run_events(Xf, sched, LSQ, gamma, M=5, gscale=0.2, features=feats, targets=targs,
+                          mode=1, want_g=True)
+    lhs = Xf.sum(0, dtype=np.float64)
+    rhs = X0.sum(0, dtype=np.float64) - gamma * r["g"].sum(0, dtype=np.float64)
+    assert np.allclose(lhs, rhs, rtol=0, atol=2e-5)
+
+
+def test_pairwise_W_is_symmetric_doubly_stochastic_projection_and_oracle_applies_it():
+    n, d = 5, 7
+    rng = np.random.default_rng(8)
+    X0 = rng.integers(-64, 64, (n, d)).astype(np.float32)   # integers: averages are exact
+    for i in range(n):
+        for j in range(n):
+            if i == j:
+                continue
+            e = np.zeros((n, 1)); e[i] = 1; e[j] = -1
+            W = np.eye(n) - 0.5 * (e @ e.T)
+            assert np.array_equal(W, W.T) and np.all(W >= 0)
+            assert np.allclose(W.sum(0), 1) and np.allclose(W.sum(1), 1)
+            assert np.allclose(W @ W, W)
+            X = X0.copy()
+            sched = {"worker": [i], "neighbour": [j], "tau": [0]}
+            oracle.run_events(X, sched, SYNTH, 0.0, synth_std=0.0)       # g = 0: pure X <- X W
+            assert np.array_equal(X.astype(np.float64), W @ X0.astype(np.float64))
+
+
+def test_equal_initial_models_gossip_is_a_noop():
+    n, d = 8, 16
+    x0 = np.random.default_rng(9).standard_normal(d).astype(np.float32)
+    X = np.tile(x0, (n, 1))
+    sched = oracle.make_schedule(ring_graph(n), 500, seed=1)
+    oracle.run_events(X, sched, SYNTH, 0.0, synth_std=1.0, synth_seed=3)   # gamma = 0
+    assert np.array_equal(X, np.tile(x0, (n, 1)))
+
+
+def test_gossip_only_expectation_and_contraction_on_a_ring():
+    """gamma = 0, X_0 = I: X_K = W_K ... W_1.  Independence gives E X_K = (E W)^K with
+    E W = I - L/(2n) on a ring with uniform worker and neighbour (L = ring Laplacian), and the
+    consensus lemma bounds E |1/n - prod W e_i|^2 by (n-1)/n rho^K, rho = lambda_2(E W^T W)
+    = 1 - (1 - cos(2 pi/n))/n because W^T W = W for a pairwise average."""
+    n, K, S = 8, 30, 3000
+    L = 2 * np.eye(n) - np.roll(np.eye(n), 1, 0) - np.roll(np.eye(n), -1, 0)
+    EW = np.eye(n) - L / (2 * n)
+    rho = 1 - (1 - np.cos(2 * np.pi / n)) / n
+    assert abs(rho - 0.963388) < 1e-6
+    assert np.isclose(np.sort(np.linalg.eigvalsh(EW))[-2], rho)
+    acc = np.zeros((n, n))
+    dist = 0.0
+    g = ring_graph(n)
+    for s in range(S):
+        X = np.eye(n, dtype=np.float32)
+        oracle.run_events(X, oracle.make_schedule(g, K, seed=1000 + s), SYNTH, 0.0, synth_std=0.0)
+        acc += X
+        dist += np.sum((X.astype(np.float64) - 1.0 / n) ** 2)
+        assert np.allclose(X.sum(0), 1.0) and np.allclose(X.sum(1), 1.0)    # product stays doubly stochastic
+    mean = acc / S
+    expect = np.linalg.matrix_power(EW, K)
+    assert np.max(np.abs(mean - expect)) < 5 * 0.35 / np.sqrt(S)
+    # sum over the n columns of the lemma's bound
+    assert dist / S <= (n - 1) * rho ** K * 1.0 + 1e-9
+    assert dist / S > 0.1 * (n - 1) * rho ** K          # and the bound is not vacuous here
+
+
+def test_single_worker_is_vanilla_minibatch_sgd():
+    """n = 1, T = 0: no neighbour, the update is x <- x - gamma * (1/M) sum_m grad F(x; xi_m)."""
+    rows, d, M, K, gamma = 30, 9, 6, 150, 0.05
+    feats, targs, _ = lsq_data(1, rows, d, seed=3)
+    g = ring_graph(1)
+    sched = oracle.make_schedule(g, K, seed=2, T_max=0, M=M, rows=[rows])
+    assert np.all(sched["neighbour"] == 0) and np.all(sched["tau"] == 0)
+    X = np.zeros((1, d), dtype=np.float32)
+    oracle.run_events(X, sched, LSQ, gamma, M=M, gscale=1.0 / M, features=feats, targets=targs)
+    x = np.zeros(d)
+    A, b = feats[0].astype(np.float64), targs[0].astype(np.float64)
+    for k in range(K):
+        idx = sched["batch_idx"][k]
+        x = x - gamma * A[idx].T @ (A[idx] @ x - b[idx]) / M
+    assert np.allclose(X[0], x, rtol=1e-4, atol=1e-5)
+
+
+def test_zero_noise_quadratic_reaches_the_closed_form_optimum():
+    """All workers hold the same consistent system b = A x*, full batch, bounded staleness:
+    consensus at x* is a fixed point of both steps and every replica converges to it."""
+    n, rows, d = 6, 24, 8
+    feats, targs, xstar = lsq_data(n, rows, d, seed=5, noise=0.0, shared=True)
+    sol = np.linalg.lstsq(feats[0].astype(np.float64), targs[0].astype(np.float64), rcond=None)[0]
+    assert np.allclose(sol, xstar, atol=1e-5)
+    K = 6000
+    sched = oracle.make_schedule(ring_graph(n), K, seed=4, T_max=3)
+    sched["batch_idx"] = np.tile(np.arange(rows, dtype=np.int32), (K, 1))
+    X = np.zeros((n, d), dtype=np.float32)
+    oracle.run_events(X, sched, LSQ, 0.02, M=rows, gscale=1.0 / rows, features=feats, targets=targs)
+    assert np.max(np.abs(X - sol[None, :])) < 1e-4
+    assert oracle.consensus_distance(X) < 1e-9
+
+
+def test_diagnostics_against_numpy():
+    rng = np.random.default_rng(10)
+    X = rng.standard_normal((7, 13)).astype(np.float32)
+    mu = X.astype(np.float64).mean(0)
+    assert np.allclose(oracle.mean_model(X), mu, rtol=1e-14)
+    assert np.isclose(oracle.consensus_distance(X), np.mean(np.sum((X - mu) ** 2, axis=1)), rtol=1e-12)
+
+
+def test_coordinate_subset_of_synthetic_workload_follows_the_full_run():
+    n, d, K = 8, 64, 300
+    sched = oracle.make_schedule(ring_graph(n), K, seed=11, T_max=5)
+    X = np.zeros((n, d), dtype=np.float32)
+    oracle.run_events(X, sched, SYNTH, 0.1, synth_std=0.03, synth_seed=9, event_base=17)
+    coords = np.array([0, 3, 5, 22, 63])
+    Y = np.zeros((n, coords.size), dtype=np.float32)
+    oracle.run_events(Y, sched, SYNTH, 0.1, synth_std=0.03, synth_seed=9, event_base=17, coords=coords)
+    assert np.array_equal(Y, X[:, coords])
+    # tau cannot matter when g ignores x
+    Z = np.zeros((n, d), dtype=np.float32)
+    oracle.run_events(Z, dict(sched, tau=np.zeros(K, np.int32)), SYNTH, 0.1, synth_std=0.03,
+                      synth_seed=9, event_base=17)
+    assert np.array_equal(Z, X)
