@@ -1,0 +1,219 @@
+/*
+ * adpsgd.h -- C ABI of the MI355X-native AD-PSGD worker-update engine.
+ *
+ * The library simulates the n worker replicas of asynchronous decentralized
+ * parallel SGD as an n x d fp32 matrix X in one GPU's memory (row i = worker
+ * i's model x^i; the paper stores the replicas as the columns of an N x n
+ * matrix) and executes a seeded schedule of update events.  One event k is the
+ * loop body of Algorithm 1 ("AD-PSGD, logical view"), in the matrix form given
+ * at the start of the theory section:
+ *
+ *     X_{k+1} = X_k W_k - gamma * dg(X^_k; xi_k, i_k),   X^_k = X_{k - tau_k}
+ *
+ *   - worker i_k computes a minibatch gradient g_k at a stale read x^ of its
+ *     own model (row i_k as it was before event k - tau_k);
+ *   - W_k averages worker i_k with one graph neighbour j_k: both rows become
+ *     (x^i + x^j)/2  (Sec. 3.2 "Averaging"; W_k = I - (e_i-e_j)(e_i-e_j)^T/2 is
+ *     symmetric and doubly stochastic, assumption 2 of the theory section);
+ *   - row i_k then takes the step  x^i <- x^i - gamma * g_k.
+ *
+ * Events whose rows are disjoint commute, so the library reorders the schedule
+ * into rounds of row-disjoint operations; the result is identical, bit for
+ * bit, to executing the events one after another.
+ *
+ * General conventions
+ *   - Every function returns ADPSGD_OK (0) or a negative ADPSGD_ERR_* code and
+ *     never throws.  adpsgd_last_error() gives a message for the last failure
+ *     on a handle.  A call that fails validation changes no state.
+ *   - "host" / "device" is stated for every pointer.  The library never frees
+ *     caller memory.  Device pointers handed to the library stay BORROWED for
+ *     the life of the handle (the caller, e.g. a tensor library, owns them).
+ *   - A handle is not thread safe.  All GPU work of a handle is enqueued on the
+ *     stream given at creation; calls are asynchronous unless stated.
+ *   - All floating-point state is fp32; gradients accumulate in fp32.
+ */
+#ifndef ADPSGD_H
+#define ADPSGD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct adpsgd adpsgd_t;
+
+enum {
+    ADPSGD_OK = 0,
+    ADPSGD_ERR_ARG = -1,      /* null pointer, bad size, misaligned buffer      */
+    ADPSGD_ERR_GRAPH = -2,    /* graph not symmetric / simple / connected       */
+    ADPSGD_ERR_SCHEDULE = -3, /* schedule violates a documented constraint      */
+    ADPSGD_ERR_STATE = -4,    /* call not valid in the handle's current state   */
+    ADPSGD_ERR_HIP = -5       /* a HIP runtime call failed                      */
+};
+
+/* Local loss F_i(x; xi) of the problem statement  min_x sum_i p_i E_xi F_i(x; xi)
+ * (Sec. 3.1).  The paper leaves F abstract; these are the workloads built in. */
+enum {
+    ADPSGD_MODEL_LSQ = 0,    /* F = (a.x - b)^2 / 2                               */
+    ADPSGD_MODEL_LOGREG = 1, /* F = log(1 + exp(-y a.x)) + lambda |x|^2 / 2        */
+    ADPSGD_MODEL_SYNTH = 2,  /* no data: g_k[e] = synth_std * N(0,1)(seed, k, e)   */
+    ADPSGD_MODEL_MLP = 3     /* in -> hidden (ReLU) -> out, softmax cross-entropy, */
+                             /* bf16 weights/inputs, fp32 master and accumulation  */
+};
+
+enum {
+    ADPSGD_FLAG_PROFILE = 1  /* time every kernel launch with HIP events (see adpsgd_get_stats) */
+};
+
+/* Undirected communication graph (V, E) of Sec. 3.1 as CSR adjacency lists.
+ * host memory, copied by adpsgd_create.  Must be symmetric, without self loops
+ * or duplicate edges, and connected. */
+typedef struct {
+    int32_t n;             /* number of workers                                  */
+    const int32_t* rowptr; /* host, n + 1 entries, rowptr[0] = 0                  */
+    const int32_t* col;    /* host, rowptr[n] entries: neighbours of each worker  */
+} adpsgd_graph_t;
+
+typedef struct {
+    int32_t model;       /* ADPSGD_MODEL_*                                        */
+    int32_t M;           /* minibatch size (ignored for SYNTH)                    */
+    float gamma;         /* step size, used when a schedule carries no per-event gamma */
+    float lambda;        /* L2 coefficient (LOGREG)                               */
+    int32_t grad_sum;    /* 0: g = (1/M) sum_m grad F  (mean);  1: the paper's literal sum */
+    int32_t T_max;       /* bound T on the staleness tau_k (assumption 7)         */
+    float synth_std;     /* SYNTH: standard deviation of every gradient entry     */
+    uint64_t synth_seed; /* SYNTH: seed of the counter-based generator            */
+    int32_t mlp_in, mlp_hidden, mlp_out; /* MLP layer sizes; d must equal
+                            in*hidden + hidden + hidden*out + out, parameters flattened as
+                            [W1 (in x hidden, row-major), b1, W2 (hidden x out), b2] */
+    float* X;            /* device, n x ldx fp32, 16-byte aligned, caller-owned    */
+    int64_t ldx;         /* leading dimension in floats, >= d, multiple of 4; entries
+                            [d, ldx) of every row must be zero and stay zero        */
+    uint16_t* Xbf16;     /* device, n x ldx bf16 shadow of X (MLP only, else NULL)  */
+    void* workspace;     /* device, 16-byte aligned: pending-gradient slots, each
+                            ldx floats.  NULL allowed for SYNTH                    */
+    int64_t workspace_bytes; /* >= (T_max + 1) * ldx * 4 for the data models; more
+                            slots let more events run per round                    */
+    void* stream;        /* hipStream_t on the current device; NULL = default stream */
+    int32_t flags;       /* ADPSGD_FLAG_*                                         */
+} adpsgd_opts_t;
+
+/* A batch of K events, all arrays in host memory, read during the call only.
+ * Constraints (else ADPSGD_ERR_SCHEDULE, with no state change):
+ *   0 <= worker[k] < n;  neighbour[k] is a graph neighbour of worker[k]
+ *   (or equals worker[k] when that worker has no neighbour: plain SGD step);
+ *   0 <= tau[k] <= min(k, T_max): a call is self-contained, staleness never
+ *   reaches behind the first event of the call;
+ *   0 <= batch_idx[k*M + m] < rows loaded for worker[k]. */
+typedef struct {
+    int64_t K;
+    const int32_t* worker;    /* i_k                                             */
+    const int32_t* neighbour; /* j_k: fixes W_k                                  */
+    const int32_t* tau;       /* tau_k                                           */
+    const int32_t* batch_idx; /* K x M sample indices xi_k (NULL for SYNTH)      */
+    const float* gamma;       /* K per-event step sizes, or NULL                 */
+} adpsgd_schedule_t;
+
+/* Parameters of the built-in schedule generator (all host memory). */
+typedef struct {
+    adpsgd_graph_t graph;
+    const int32_t* weight;  /* n integer update frequencies (p_i = weight_i / sum), NULL = uniform */
+    int32_t tau_mode;       /* 0: tau ~ Uniform{0..T_max};  1: geometric P(tau >= t) = (num_i/den_i)^t, capped at T_max */
+    int32_t T_max;
+    const int32_t* tau_num; /* n entries (tau_mode 1) */
+    const int32_t* tau_den; /* n entries (tau_mode 1) */
+    int32_t M;              /* minibatch size, 0 = no batch indices */
+    const int32_t* rows;    /* n local sample counts (M > 0) */
+} adpsgd_sched_params_t;
+
+typedef struct {
+    int64_t events;          /* events executed since creation                    */
+    int64_t rounds;          /* conflict-free rounds they were packed into        */
+    int64_t fused_launches;  /* launches of the gossip-average + apply kernel     */
+    int64_t grad_launches;   /* launches of gradient kernels                      */
+    int64_t max_round_pairs; /* most update events in one round                   */
+    int64_t slots;           /* pending-gradient slots available                  */
+    double fused_ms;         /* summed kernel time, only with ADPSGD_FLAG_PROFILE */
+    double grad_ms;
+} adpsgd_stats_t;
+
+/* Create an engine for n = graph->n workers and d parameters.
+ * Algorithm 1 requires equal initial models: call adpsgd_set_models before the
+ * first event.  Validates the graph (ADPSGD_ERR_GRAPH) and the buffers
+ * (ADPSGD_ERR_ARG).  *out is NULL on failure. */
+int adpsgd_create(adpsgd_t** out, const adpsgd_graph_t* graph, int64_t d, const adpsgd_opts_t* opts);
+
+void adpsgd_destroy(adpsgd_t* h);
+
+/* Message for the last error on h (h may be NULL: message of the last failed create). */
+const char* adpsgd_last_error(const adpsgd_t* h);
+
+/* Local data of one worker: D_i is the uniform distribution over its rows
+ * (Strategy-2 of the remark in Sec. 3.1).
+ *   features: device, rows x ld elements, 16-byte aligned, ld a multiple of 4 (fp32)
+ *             or of 8 (bf16); fp32 for LSQ/LOGREG (ld >= d), bf16 for MLP (ld >= mlp_in);
+ *   targets:  device, rows entries: fp32 b (LSQ), fp32 y in {-1,+1} (LOGREG), int32 class (MLP).
+ * Both borrowed until adpsgd_destroy. */
+int adpsgd_load_data(adpsgd_t* h, int32_t worker, const void* features, int64_t rows, int64_t ld,
+                     const void* targets);
+
+/* Set the models.  ld_in = 0: x holds d floats, broadcast to every worker (the
+ * equal initialisation of Algorithm 1); otherwise x is n x ld_in.  x is host
+ * (on_device = 0) or device (1) memory.  Synchronous. */
+int adpsgd_set_models(adpsgd_t* h, const float* x, int64_t ld_in, int32_t on_device);
+
+/* Execute the events of s in order semantics (Algorithm 1, one loop iteration
+ * per event).  loss (device, K floats, or NULL) receives the minibatch loss at
+ * x^_k of every event (data models only).  Asynchronous on the stream, but the
+ * schedule arrays may be reused as soon as the call returns. */
+int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float* loss);
+
+/* Copy the n x d models to out (host or device, leading dimension ld_out >= d).
+ * Synchronises the stream. */
+int adpsgd_get_models(adpsgd_t* h, float* out, int64_t ld_out, int32_t on_device);
+
+/* Algorithm 1's output: the average of all workers' models (d floats). Synchronous. */
+int adpsgd_get_mean_model(adpsgd_t* h, float* out, int32_t on_device);
+
+/* Consensus distance (1/n) sum_i |mean - x^i|^2: the quantity M_k of the proofs
+ * appendix with uniform p.  *out is host memory.  Synchronous. */
+int adpsgd_consensus_distance(adpsgd_t* h, double* out);
+
+/* MLP only: copy the n x d bf16 shadow weights (bit patterns). Synchronous. */
+int adpsgd_get_bf16_models(adpsgd_t* h, uint16_t* out, int64_t ld_out, int32_t on_device);
+
+int adpsgd_get_stats(adpsgd_t* h, adpsgd_stats_t* out);
+
+/* Host-only helpers (no GPU needed) ------------------------------------------ */
+
+/* The random choices of Algorithm 1 for events k_begin .. k_begin + K - 1 of the
+ * stream identified by seed: worker i_k ~ p, neighbour j_k uniform over the
+ * neighbours of i_k, staleness tau_k (clipped to the events available in this
+ * window: tau_k <= k - k_begin), and M minibatch indices drawn with replacement.
+ * Integer arithmetic on a counter-based generator (Philox4x32-10) only; outputs
+ * are caller-allocated host arrays (batch_idx: K*M, may be NULL when M = 0). */
+int adpsgd_make_schedule(const adpsgd_sched_params_t* p, uint64_t seed, uint64_t k_begin, int64_t K,
+                         int32_t* worker, int32_t* neighbour, int32_t* tau, int32_t* batch_idx);
+
+/* The round planner on its own: assigns every event a round for its stale read /
+ * gradient (r_round, -1 when with_gradients = 0), a round for its update
+ * (u_round) and a pending-gradient slot, such that within a round no model row
+ * is written twice or read and written in the wrong order, and executing the
+ * rounds in order (reads of a round before its updates) equals executing the
+ * events one by one.  Outputs are host arrays of K entries; *n_rounds receives
+ * the number of rounds.  Returns ADPSGD_ERR_SCHEDULE for tau[k] > k or
+ * n_slots <= max tau. */
+int adpsgd_plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
+                       const int32_t* tau, int32_t n_slots, int32_t with_gradients,
+                       int32_t* r_round, int32_t* u_round, int32_t* slot, int32_t* n_rounds);
+
+/* Fill a device buffer with the synthetic gradient g_k[0..d) of global event k
+ * (ADPSGD_MODEL_SYNTH's generator), on `stream`.  For tests of the generator. */
+int adpsgd_synth_gradient(uint64_t seed, uint64_t k, float std, int64_t d, float* out_device,
+                          void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADPSGD_H */

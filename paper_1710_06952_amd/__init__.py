@@ -1,0 +1,9 @@
+"""MI355X-native AD-PSGD worker-update engine: Python face of libadpsgd.so.
+
+``binding`` mirrors the C ABI of include/adpsgd.h one to one; ``Engine`` adds
+only what a caller needs around it: device buffers and a stream from PyTorch.
+"""
+from .binding import (AdpsgdError, Handle, adpsgd_make_schedule, adpsgd_plan_rounds,  # noqa: F401
+                      adpsgd_synth_gradient, lib, EXPORTS, LIB_PATH, MODEL_LSQ, MODEL_LOGREG,
+                      MODEL_SYNTH, MODEL_MLP, FLAG_PROFILE)
+from .engine import Engine  # noqa: F401

@@ -1,0 +1,222 @@
+"""ctypes binding of libadpsgd.so: the same entry points as include/adpsgd.h,
+argument marshalling only.  Every step of the update path runs in the HIP
+library; there is no fallback: a missing library raises at import of the symbol
+table, a failing call raises AdpsgdError with the library's message.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+LIB_PATH = _HERE / "libadpsgd.so"
+
+OK, ERR_ARG, ERR_GRAPH, ERR_SCHEDULE, ERR_STATE, ERR_HIP = 0, -1, -2, -3, -4, -5
+MODEL_LSQ, MODEL_LOGREG, MODEL_SYNTH, MODEL_MLP = 0, 1, 2, 3
+FLAG_PROFILE = 1
+
+EXPORTS = [
+    "adpsgd_create", "adpsgd_destroy", "adpsgd_last_error", "adpsgd_load_data", "adpsgd_set_models",
+    "adpsgd_run_events", "adpsgd_get_models", "adpsgd_get_mean_model", "adpsgd_consensus_distance",
+    "adpsgd_get_bf16_models", "adpsgd_get_stats", "adpsgd_make_schedule", "adpsgd_plan_rounds",
+    "adpsgd_synth_gradient",
+]
+
+
+class AdpsgdError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("adpsgd error %d: %s" % (code, msg))
+        self.code = code
+
+
+class Graph(C.Structure):
+    _fields_ = [("n", C.c_int32), ("rowptr", C.POINTER(C.c_int32)), ("col", C.POINTER(C.c_int32))]
+
+
+class Opts(C.Structure):
+    _fields_ = [("model", C.c_int32), ("M", C.c_int32), ("gamma", C.c_float), ("lambda_", C.c_float),
+                ("grad_sum", C.c_int32), ("T_max", C.c_int32), ("synth_std", C.c_float),
+                ("synth_seed", C.c_uint64), ("mlp_in", C.c_int32), ("mlp_hidden", C.c_int32),
+                ("mlp_out", C.c_int32), ("X", C.c_void_p), ("ldx", C.c_int64), ("Xbf16", C.c_void_p),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64), ("stream", C.c_void_p),
+                ("flags", C.c_int32)]
+
+
+class Schedule(C.Structure):
+    _fields_ = [("K", C.c_int64), ("worker", C.POINTER(C.c_int32)), ("neighbour", C.POINTER(C.c_int32)),
+                ("tau", C.POINTER(C.c_int32)), ("batch_idx", C.POINTER(C.c_int32)),
+                ("gamma", C.POINTER(C.c_float))]
+
+
+class SchedParams(C.Structure):
+    _fields_ = [("graph", Graph), ("weight", C.POINTER(C.c_int32)), ("tau_mode", C.c_int32),
+                ("T_max", C.c_int32), ("tau_num", C.POINTER(C.c_int32)), ("tau_den", C.POINTER(C.c_int32)),
+                ("M", C.c_int32), ("rows", C.POINTER(C.c_int32))]
+
+
+class Stats(C.Structure):
+    _fields_ = [("events", C.c_int64), ("rounds", C.c_int64), ("fused_launches", C.c_int64),
+                ("grad_launches", C.c_int64), ("max_round_pairs", C.c_int64), ("slots", C.c_int64),
+                ("fused_ms", C.c_double), ("grad_ms", C.c_double)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libadpsgd.so (built in-tree by paper_1710_06952_amd.build).  Fails loudly."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise ImportError("%s is missing: run `python -m paper_1710_06952_amd.build` "
+                              "(there is no CPU fallback)" % LIB_PATH)
+        L = C.CDLL(str(LIB_PATH))
+        vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
+        P = C.POINTER
+        L.adpsgd_create.argtypes = [P(vp), P(Graph), i64, P(Opts)]
+        L.adpsgd_destroy.argtypes = [vp]
+        L.adpsgd_destroy.restype = None
+        L.adpsgd_last_error.argtypes = [vp]
+        L.adpsgd_last_error.restype = C.c_char_p
+        L.adpsgd_load_data.argtypes = [vp, i32, vp, i64, i64, vp]
+        L.adpsgd_set_models.argtypes = [vp, vp, i64, i32]
+        L.adpsgd_run_events.argtypes = [vp, P(Schedule), vp]
+        L.adpsgd_get_models.argtypes = [vp, vp, i64, i32]
+        L.adpsgd_get_mean_model.argtypes = [vp, vp, i32]
+        L.adpsgd_consensus_distance.argtypes = [vp, P(C.c_double)]
+        L.adpsgd_get_bf16_models.argtypes = [vp, vp, i64, i32]
+        L.adpsgd_get_stats.argtypes = [vp, P(Stats)]
+        L.adpsgd_make_schedule.argtypes = [P(SchedParams), u64, u64, i64, P(i32), P(i32), P(i32), P(i32)]
+        L.adpsgd_plan_rounds.argtypes = [i32, i64, P(i32), P(i32), P(i32), i32, i32, P(i32), P(i32), P(i32), P(i32)]
+        L.adpsgd_synth_gradient.argtypes = [u64, u64, C.c_float, i64, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _i32p(a):
+    return None if a is None else a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def _as_i32(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _graph_struct(graph):
+    rowptr, col = _as_i32(graph[0]), _as_i32(graph[1])
+    return Graph(rowptr.size - 1, _i32p(rowptr), _i32p(col)), (rowptr, col)
+
+
+def _check(h, rc):
+    if rc != OK:
+        raise AdpsgdError(rc, (lib().adpsgd_last_error(h) or b"").decode())
+
+
+def adpsgd_make_schedule(graph, K, seed=0, k_begin=0, T_max=0, tau_mode=0, weight=None, tau_num=None,
+                         tau_den=None, M=0, rows=None):
+    """Host-only: the random choices of Algorithm 1 for K events (see adpsgd.h)."""
+    g, keep = _graph_struct(graph)
+    weight, tau_num, tau_den, rows = map(_as_i32, (weight, tau_num, tau_den, rows))
+    p = SchedParams(g, _i32p(weight), tau_mode, T_max, _i32p(tau_num), _i32p(tau_den), M, _i32p(rows))
+    worker, nbr, tau = (np.zeros(K, np.int32) for _ in range(3))
+    batch = np.zeros((K, M), np.int32) if M > 0 else None
+    rc = lib().adpsgd_make_schedule(C.byref(p), seed, k_begin, K, _i32p(worker), _i32p(nbr), _i32p(tau), _i32p(batch))
+    if rc != OK:
+        raise AdpsgdError(rc, "adpsgd_make_schedule: bad argument")
+    del keep
+    return {"worker": worker, "neighbour": nbr, "tau": tau, "batch_idx": batch}
+
+
+def adpsgd_plan_rounds(n, worker, neighbour, tau, n_slots, with_gradients=True):
+    """Host-only: the round planner on its own; returns (r_round, u_round, slot, n_rounds)."""
+    worker, neighbour, tau = map(_as_i32, (worker, neighbour, tau))
+    K = worker.size
+    r, u, s = (np.zeros(K, np.int32) for _ in range(3))
+    nr = C.c_int32(0)
+    rc = lib().adpsgd_plan_rounds(n, K, _i32p(worker), _i32p(neighbour), _i32p(tau), n_slots,
+                                  1 if with_gradients else 0, _i32p(r), _i32p(u), _i32p(s), C.byref(nr))
+    if rc != OK:
+        raise AdpsgdError(rc, "adpsgd_plan_rounds failed")
+    return r, u, s, nr.value
+
+
+def adpsgd_synth_gradient(seed, k, std, d, out_ptr, stream=0):
+    rc = lib().adpsgd_synth_gradient(seed, k, std, d, out_ptr, stream)
+    if rc != OK:
+        raise AdpsgdError(rc, "adpsgd_synth_gradient failed")
+
+
+class Handle:
+    """Owns one adpsgd_t*.  Methods mirror the C entry points one to one; device
+    pointers are plain integers (e.g. ``tensor.data_ptr()``)."""
+
+    def __init__(self, graph, d, *, model, X_ptr, ldx, M=0, gamma=0.0, lam=0.0, grad_sum=False, T_max=0,
+                 synth_std=0.0, synth_seed=0, mlp=(0, 0, 0), Xbf16_ptr=None, workspace_ptr=None,
+                 workspace_bytes=0, stream=0, flags=0):
+        g, keep = _graph_struct(graph)
+        o = Opts(model, M, gamma, lam, 1 if grad_sum else 0, T_max, synth_std, synth_seed, mlp[0], mlp[1], mlp[2],
+                 X_ptr, ldx, Xbf16_ptr, workspace_ptr, workspace_bytes, stream or None, flags)
+        self._h = C.c_void_p()
+        self.n, self.d, self.M, self.model = g.n, d, M, model
+        rc = lib().adpsgd_create(C.byref(self._h), C.byref(g), d, C.byref(o))
+        del keep
+        if rc != OK:
+            self._h = None
+            raise AdpsgdError(rc, (lib().adpsgd_last_error(None) or b"").decode())
+
+    def destroy(self):
+        if getattr(self, "_h", None):
+            lib().adpsgd_destroy(self._h)
+            self._h = None
+
+    __del__ = destroy
+
+    def load_data(self, worker, features_ptr, rows, ld, targets_ptr):
+        _check(self._h, lib().adpsgd_load_data(self._h, worker, features_ptr, rows, ld, targets_ptr))
+
+    def set_models(self, x, ld_in=0, on_device=False):
+        """x: numpy fp32 array (host) or an integer device pointer (on_device=True)."""
+        if on_device:
+            ptr = x
+        else:
+            x = np.ascontiguousarray(x, dtype=np.float32)
+            ptr = x.ctypes.data
+        _check(self._h, lib().adpsgd_set_models(self._h, ptr, ld_in, 1 if on_device else 0))
+
+    def run_events(self, schedule, loss_ptr=None):
+        worker, nbr, tau = (_as_i32(schedule[k]) for k in ("worker", "neighbour", "tau"))
+        batch = _as_i32(schedule.get("batch_idx"))
+        gam = schedule.get("gamma")
+        gam = None if gam is None else np.ascontiguousarray(gam, dtype=np.float32)
+        s = Schedule(worker.size, _i32p(worker), _i32p(nbr), _i32p(tau), _i32p(batch),
+                     None if gam is None else gam.ctypes.data_as(C.POINTER(C.c_float)))
+        _check(self._h, lib().adpsgd_run_events(self._h, C.byref(s), loss_ptr))
+
+    def get_models(self, out=None, ld_out=None, on_device=False):
+        if on_device:
+            _check(self._h, lib().adpsgd_get_models(self._h, out, ld_out, 1))
+            return None
+        res = np.empty((self.n, self.d), dtype=np.float32)
+        _check(self._h, lib().adpsgd_get_models(self._h, res.ctypes.data, self.d, 0))
+        return res
+
+    def get_bf16_models(self):
+        res = np.empty((self.n, self.d), dtype=np.uint16)
+        _check(self._h, lib().adpsgd_get_bf16_models(self._h, res.ctypes.data, self.d, 0))
+        return res
+
+    def get_mean_model(self):
+        res = np.empty(self.d, dtype=np.float32)
+        _check(self._h, lib().adpsgd_get_mean_model(self._h, res.ctypes.data, 0))
+        return res
+
+    def consensus_distance(self):
+        out = C.c_double(0.0)
+        _check(self._h, lib().adpsgd_consensus_distance(self._h, C.byref(out)))
+        return out.value
+
+    def get_stats(self):
+        st = Stats()
+        _check(self._h, lib().adpsgd_get_stats(self._h, C.byref(st)))
+        return {name: getattr(st, name) for name, _ in Stats._fields_}

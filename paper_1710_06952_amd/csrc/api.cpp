@@ -1,0 +1,531 @@
+// C-ABI entry points of libadpsgd: handle life cycle, validation, per-call
+// planning and the per-round launch loop.  See include/adpsgd.h for the contract.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <memory>
+
+#include "internal.hpp"
+
+namespace adpsgd_impl {
+
+hipError_t DevBuf::reserve(size_t bytes) {
+    if (bytes <= cap) return hipSuccess;
+    if (p) {
+        // kernels enqueued earlier may still read the old buffer
+        hipError_t e = hipDeviceSynchronize();
+        if (e == hipSuccess) e = hipFree(p);
+        p = nullptr;
+        cap = 0;
+        if (e != hipSuccess) return e;
+    }
+    size_t want = std::max<size_t>(bytes, 256);
+    hipError_t e = hipMalloc(&p, want);
+    if (e != hipSuccess) { p = nullptr; return e; }
+    cap = want;
+    return hipSuccess;
+}
+void DevBuf::release() {
+    if (p) (void)hipFree(p);
+    p = nullptr;
+    cap = 0;
+}
+
+namespace {
+
+// Pinned host staging buffer (grow-only).
+struct HostBuf {
+    void* p = nullptr;
+    size_t cap = 0;
+    hipError_t reserve(size_t bytes) {
+        if (bytes <= cap) return hipSuccess;
+        if (p) (void)hipHostFree(p);
+        p = nullptr;
+        cap = 0;
+        size_t want = std::max<size_t>(bytes, 4096);
+        hipError_t e = hipHostMalloc(&p, want, hipHostMallocDefault);
+        if (e != hipSuccess) { p = nullptr; return e; }
+        cap = want;
+        return hipSuccess;
+    }
+    void release() {
+        if (p) (void)hipHostFree(p);
+        p = nullptr;
+        cap = 0;
+    }
+};
+
+// The tables of one adpsgd_run_events call; two sets alternate so that planning
+// call c+1 can overlap the kernels of call c.
+struct TableSet {
+    HostBuf stage;
+    DevBuf dev;
+    hipEvent_t done = nullptr;   // recorded after the last kernel that reads the tables
+    bool in_flight = false;
+};
+
+constexpr int64_t kCacheBytes = 192ll << 20;   // gathered rows of a gradient group should stay cache resident
+constexpr int64_t kStreamingThreshold = 256ll << 20;
+constexpr int32_t kMaxSlots = 4096;
+
+thread_local std::string g_create_error;
+
+}  // namespace
+}  // namespace adpsgd_impl
+
+using namespace adpsgd_impl;
+
+struct adpsgd {
+    int32_t n = 0;
+    int64_t d = 0;
+    adpsgd_opts_t o{};
+    std::vector<int32_t> rowptr, col;
+    std::vector<WorkerData> data;
+    bool data_dirty = true;
+    DevBuf data_dev;
+    int32_t n_slots = 0;
+    hipStream_t stream = nullptr;
+    bool streaming = false;
+    uint64_t events_done = 0;
+    TableSet tables[2];
+    int next_table = 0;
+    DevBuf grad_scratch;     // dots partials + coefficients / MLP activations
+    DevBuf diag;             // consensus partials, result, mean / broadcast staging
+    adpsgd_stats_t stats{};
+    std::vector<hipEvent_t> ev_pool;                       // profiling events
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> ev_fused, ev_grad;
+    std::string err;
+};
+
+namespace {
+
+int fail(adpsgd_t* h, int code, const std::string& msg) {
+    if (h) h->err = msg;
+    else g_create_error = msg;
+    return code;
+}
+int hip_fail(adpsgd_t* h, hipError_t e, const char* what) {
+    return fail(h, ADPSGD_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+#define HIP_TRY(h, expr)                                           \
+    do {                                                           \
+        hipError_t e__ = (expr);                                   \
+        if (e__ != hipSuccess) return hip_fail((h), e__, #expr);   \
+    } while (0)
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool is_neighbour(const adpsgd_t* h, int32_t i, int32_t j) {
+    const int32_t b = h->rowptr[i], e = h->rowptr[i + 1];
+    if (b == e) return j == i;
+    for (int32_t t = b; t < e; ++t)
+        if (h->col[t] == j) return true;
+    return false;
+}
+
+hipEvent_t take_event(adpsgd_t* h) {
+    if (!h->ev_pool.empty()) {
+        hipEvent_t e = h->ev_pool.back();
+        h->ev_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+// Fold the timings of finished launches into the statistics (synchronises the stream).
+int drain_profile(adpsgd_t* h) {
+    if (h->ev_fused.empty() && h->ev_grad.empty()) return ADPSGD_OK;
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    for (int which = 0; which < 2; ++which) {
+        auto& list = which == 0 ? h->ev_fused : h->ev_grad;
+        double& total = which == 0 ? h->stats.fused_ms : h->stats.grad_ms;
+        for (auto& pr : list) {
+            float ms = 0.0f;
+            HIP_TRY(h, hipEventElapsedTime(&ms, pr.first, pr.second));
+            total += ms;
+            h->ev_pool.push_back(pr.first);
+            h->ev_pool.push_back(pr.second);
+        }
+        list.clear();
+    }
+    return ADPSGD_OK;
+}
+
+}  // namespace
+
+extern "C" const char* adpsgd_last_error(const adpsgd_t* h) { return h ? h->err.c_str() : g_create_error.c_str(); }
+
+extern "C" int adpsgd_create(adpsgd_t** out, const adpsgd_graph_t* graph, int64_t d, const adpsgd_opts_t* opts) {
+    if (!out) return fail(nullptr, ADPSGD_ERR_ARG, "create: out is NULL");
+    *out = nullptr;
+    if (!graph || !opts) return fail(nullptr, ADPSGD_ERR_ARG, "create: graph or opts is NULL");
+    std::string msg;
+    if (!graph_ok(graph, msg)) return fail(nullptr, ADPSGD_ERR_GRAPH, msg);
+    const int32_t n = graph->n;
+    if (n > 65535) return fail(nullptr, ADPSGD_ERR_ARG, "create: at most 65535 workers");
+    if (d < 1) return fail(nullptr, ADPSGD_ERR_ARG, "create: d < 1");
+    const adpsgd_opts_t& o = *opts;
+    if (o.model < ADPSGD_MODEL_LSQ || o.model > ADPSGD_MODEL_MLP) return fail(nullptr, ADPSGD_ERR_ARG, "create: unknown model");
+    if (!o.X || !aligned16(o.X)) return fail(nullptr, ADPSGD_ERR_ARG, "create: X is NULL or not 16-byte aligned");
+    if (o.ldx < d || (o.ldx & 3)) return fail(nullptr, ADPSGD_ERR_ARG, "create: ldx must be >= d and a multiple of 4");
+    if (o.T_max < 0) return fail(nullptr, ADPSGD_ERR_ARG, "create: T_max < 0");
+    if (!std::isfinite(o.gamma)) return fail(nullptr, ADPSGD_ERR_ARG, "create: gamma not finite");
+    int32_t n_slots = 0;
+    if (o.model != ADPSGD_MODEL_SYNTH) {
+        if (o.M < 1 || o.M > 65536) return fail(nullptr, ADPSGD_ERR_ARG, "create: minibatch size M outside [1, 65536]");
+        if (!o.workspace || !aligned16(o.workspace)) return fail(nullptr, ADPSGD_ERR_ARG, "create: workspace is NULL or misaligned");
+        const int64_t slot_bytes = o.ldx * 4;
+        const int64_t have = o.workspace_bytes / slot_bytes;
+        if (have < static_cast<int64_t>(o.T_max) + 1)
+            return fail(nullptr, ADPSGD_ERR_ARG, "create: workspace smaller than (T_max + 1) gradient slots");
+        n_slots = static_cast<int32_t>(std::min<int64_t>(have, kMaxSlots));
+    }
+    if (o.model == ADPSGD_MODEL_MLP) {
+        if (o.mlp_in < 1 || o.mlp_hidden < 1 || o.mlp_out < 1 ||
+            d != static_cast<int64_t>(o.mlp_in) * o.mlp_hidden + o.mlp_hidden +
+                     static_cast<int64_t>(o.mlp_hidden) * o.mlp_out + o.mlp_out)
+            return fail(nullptr, ADPSGD_ERR_ARG, "create: d does not match the MLP layer sizes");
+        if (!o.Xbf16 || !aligned16(o.Xbf16)) return fail(nullptr, ADPSGD_ERR_ARG, "create: Xbf16 is NULL or misaligned");
+        if (o.ldx & 7) return fail(nullptr, ADPSGD_ERR_ARG, "create: ldx must be a multiple of 8 for the MLP");
+        if (mlp_scratch_bytes(1, o.M, o.mlp_in, o.mlp_hidden, o.mlp_out) == 0)
+            return fail(nullptr, ADPSGD_ERR_ARG, "create: MLP shape not supported by the gradient kernel");
+    }
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || count < 1)
+        return fail(nullptr, ADPSGD_ERR_HIP, "create: no HIP device available");
+
+    std::unique_ptr<adpsgd> h(new (std::nothrow) adpsgd);
+    if (!h) return fail(nullptr, ADPSGD_ERR_ARG, "create: out of host memory");
+    h->n = n;
+    h->d = d;
+    h->o = o;
+    h->rowptr.assign(graph->rowptr, graph->rowptr + n + 1);
+    h->col.assign(graph->col, graph->col + graph->rowptr[n]);
+    h->data.resize(n);
+    h->n_slots = n_slots;
+    h->stream = static_cast<hipStream_t>(o.stream);
+    h->streaming = static_cast<int64_t>(n) * o.ldx * 4 > kStreamingThreshold;
+    h->stats.slots = n_slots;
+    for (auto& t : h->tables) {
+        hipError_t e = hipEventCreateWithFlags(&t.done, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            for (auto& u : h->tables)
+                if (u.done) (void)hipEventDestroy(u.done);
+            return hip_fail(nullptr, e, "create: hipEventCreate");
+        }
+    }
+    *out = h.release();
+    return ADPSGD_OK;
+}
+
+extern "C" void adpsgd_destroy(adpsgd_t* h) {
+    if (!h) return;
+    (void)hipStreamSynchronize(h->stream);
+    for (auto& t : h->tables) {
+        t.stage.release();
+        t.dev.release();
+        if (t.done) (void)hipEventDestroy(t.done);
+    }
+    for (auto& pr : h->ev_fused) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
+    for (auto& pr : h->ev_grad) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
+    for (auto e : h->ev_pool) (void)hipEventDestroy(e);
+    h->data_dev.release();
+    h->grad_scratch.release();
+    h->diag.release();
+    delete h;
+}
+
+extern "C" int adpsgd_load_data(adpsgd_t* h, int32_t worker, const void* features, int64_t rows, int64_t ld,
+                                const void* targets) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (h->o.model == ADPSGD_MODEL_SYNTH) return fail(h, ADPSGD_ERR_STATE, "load_data: the synthetic-gradient model takes no data");
+    if (worker < 0 || worker >= h->n) return fail(h, ADPSGD_ERR_ARG, "load_data: worker out of range");
+    if (!features || !targets || rows < 1 || rows > 0x7FFFFFFF) return fail(h, ADPSGD_ERR_ARG, "load_data: null data or bad row count");
+    if (!aligned16(features)) return fail(h, ADPSGD_ERR_ARG, "load_data: features not 16-byte aligned");
+    if (h->o.model == ADPSGD_MODEL_MLP) {
+        if (ld < h->o.mlp_in || (ld & 7)) return fail(h, ADPSGD_ERR_ARG, "load_data: ld must be >= mlp_in and a multiple of 8");
+    } else {
+        if (ld < h->d || (ld & 3)) return fail(h, ADPSGD_ERR_ARG, "load_data: ld must be >= d and a multiple of 4");
+    }
+    WorkerData& w = h->data[worker];
+    w.features = features;
+    w.targets = targets;
+    w.rows = rows;
+    w.ld = ld;
+    h->data_dirty = true;
+    return ADPSGD_OK;
+}
+
+extern "C" int adpsgd_set_models(adpsgd_t* h, const float* x, int64_t ld_in, int32_t on_device) {
+    if (!h || !x) return h ? fail(h, ADPSGD_ERR_ARG, "set_models: x is NULL") : ADPSGD_ERR_ARG;
+    if (ld_in != 0 && ld_in < h->d) return fail(h, ADPSGD_ERR_ARG, "set_models: ld_in < d");
+    const hipMemcpyKind kind = on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+    if (ld_in == 0) {
+        const float* src = x;
+        if (!on_device) {
+            HIP_TRY(h, hipStreamSynchronize(h->stream));
+            HIP_TRY(h, h->diag.reserve(static_cast<size_t>(h->d) * 4));
+            HIP_TRY(h, hipMemcpy(h->diag.p, x, static_cast<size_t>(h->d) * 4, hipMemcpyHostToDevice));
+            src = static_cast<const float*>(h->diag.p);
+        }
+        HIP_TRY(h, launch_broadcast_rows(h->o.X, h->o.ldx, h->d, h->n, src, h->stream));
+    } else {
+        HIP_TRY(h, hipMemsetAsync(h->o.X, 0, static_cast<size_t>(h->n) * h->o.ldx * 4, h->stream));
+        HIP_TRY(h, hipMemcpy2DAsync(h->o.X, static_cast<size_t>(h->o.ldx) * 4, x, static_cast<size_t>(ld_in) * 4,
+                                    static_cast<size_t>(h->d) * 4, h->n, kind, h->stream));
+    }
+    if (h->o.model == ADPSGD_MODEL_MLP)
+        HIP_TRY(h, launch_refresh_bf16(h->o.X, h->o.Xbf16, h->o.ldx, h->n, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return ADPSGD_OK;
+}
+
+extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float* loss) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (!s || s->K < 0) return fail(h, ADPSGD_ERR_ARG, "run_events: schedule is NULL or K < 0");
+    const int64_t K = s->K;
+    if (K == 0) return ADPSGD_OK;
+    if (K > 0x7FFFFFF0) return fail(h, ADPSGD_ERR_ARG, "run_events: at most 2^31 - 16 events per call");
+    if (!s->worker || !s->neighbour || !s->tau) return fail(h, ADPSGD_ERR_ARG, "run_events: null schedule array");
+    const bool with_grad = h->o.model != ADPSGD_MODEL_SYNTH;
+    const int32_t M = with_grad ? h->o.M : 0;
+    if (with_grad && !s->batch_idx) return fail(h, ADPSGD_ERR_ARG, "run_events: batch_idx is NULL");
+
+    // ---- validation: nothing is launched and no state changes on failure ----
+    for (int64_t k = 0; k < K; ++k) {
+        const int32_t i = s->worker[k], j = s->neighbour[k];
+        if (i < 0 || i >= h->n || j < 0 || j >= h->n)
+            return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: worker or neighbour out of range at event " + std::to_string(k));
+        if (!is_neighbour(h, i, j))
+            return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: neighbour is not adjacent to worker at event " + std::to_string(k));
+        if (s->tau[k] < 0 || s->tau[k] > k || s->tau[k] > h->o.T_max)
+            return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: tau outside [0, min(k, T_max)] at event " + std::to_string(k));
+        if (s->gamma && !std::isfinite(s->gamma[k]))
+            return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: gamma not finite at event " + std::to_string(k));
+        if (with_grad) {
+            const WorkerData& w = h->data[i];
+            if (!w.features) return fail(h, ADPSGD_ERR_STATE, "run_events: no data loaded for worker " + std::to_string(i));
+            const int32_t* b = s->batch_idx + k * static_cast<int64_t>(M);
+            for (int32_t m = 0; m < M; ++m)
+                if (b[m] < 0 || b[m] >= w.rows)
+                    return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: batch index out of range at event " + std::to_string(k));
+        }
+    }
+
+    // ---- plan ----
+    Plan plan;
+    std::string perr;
+    int rc = plan_rounds(h->n, K, s->worker, s->neighbour, s->tau, h->n_slots, with_grad, plan, perr);
+    if (rc != ADPSGD_OK) return fail(h, rc, perr);
+    const int32_t R = plan.n_rounds;
+
+    // counting sort of the operations by round
+    std::vector<int64_t> u_off(static_cast<size_t>(R) + 1, 0), r_off(static_cast<size_t>(R) + 1, 0);
+    for (int64_t k = 0; k < K; ++k) {
+        ++u_off[plan.u_round[k] + 1];
+        if (with_grad) ++r_off[plan.r_round[k] + 1];
+    }
+    for (int32_t r = 0; r < R; ++r) { u_off[r + 1] += u_off[r]; r_off[r + 1] += r_off[r]; }
+
+    // ---- tables: [PairOp x K][GradOp x K][batch_idx K x M][WorkerDataDev x n] ----
+    const size_t bytes_u = static_cast<size_t>(K) * sizeof(PairOp);
+    const size_t bytes_r = with_grad ? static_cast<size_t>(K) * sizeof(GradOp) : 0;
+    const size_t bytes_b = with_grad ? static_cast<size_t>(K) * M * sizeof(int32_t) : 0;
+    const size_t off_r = bytes_u, off_b = (off_r + bytes_r + 15) & ~size_t(15);
+    const size_t total = off_b + bytes_b;
+
+    TableSet& T = h->tables[h->next_table];
+    h->next_table ^= 1;
+    if (T.in_flight) {
+        HIP_TRY(h, hipEventSynchronize(T.done));
+        T.in_flight = false;
+    }
+    HIP_TRY(h, T.stage.reserve(total));
+    HIP_TRY(h, T.dev.reserve(total));
+    char* stage = static_cast<char*>(T.stage.p);
+    PairOp* uops = reinterpret_cast<PairOp*>(stage);
+    GradOp* rops = reinterpret_cast<GradOp*>(stage + off_r);
+    {
+        std::vector<int64_t> u_fill(u_off.begin(), u_off.end() - 1), r_fill(r_off.begin(), r_off.end() - 1);
+        for (int64_t k = 0; k < K; ++k) {
+            const uint64_t gk = h->events_done + static_cast<uint64_t>(k);
+            PairOp& u = uops[u_fill[plan.u_round[k]]++];
+            u.i = s->worker[k];
+            u.j = s->neighbour[k];
+            u.k_lo = static_cast<uint32_t>(gk);
+            u.k_hi = static_cast<uint32_t>(gk >> 32);
+            u.gamma = s->gamma ? s->gamma[k] : h->o.gamma;
+            u.slot = with_grad ? plan.slot[k] : 0;
+            u.pad0 = u.pad1 = 0;
+            if (with_grad) {
+                GradOp& g = rops[r_fill[plan.r_round[k]]++];
+                g.worker = s->worker[k];
+                g.slot = plan.slot[k];
+                g.event = static_cast<int32_t>(k);
+                g.pad = 0;
+            }
+        }
+    }
+    if (with_grad) std::memcpy(stage + off_b, s->batch_idx, bytes_b);
+    HIP_TRY(h, hipMemcpyAsync(T.dev.p, T.stage.p, total, hipMemcpyHostToDevice, h->stream));
+    const char* dev = static_cast<const char*>(T.dev.p);
+    const PairOp* d_uops = reinterpret_cast<const PairOp*>(dev);
+    const GradOp* d_rops = reinterpret_cast<const GradOp*>(dev + off_r);
+    const int32_t* d_batch = reinterpret_cast<const int32_t*>(dev + off_b);
+
+    if (with_grad && h->data_dirty) {
+        std::vector<WorkerDataDev> tab(h->n);
+        for (int32_t i = 0; i < h->n; ++i) tab[i] = {h->data[i].features, h->data[i].targets, h->data[i].ld};
+        HIP_TRY(h, hipStreamSynchronize(h->stream));
+        HIP_TRY(h, h->data_dev.reserve(tab.size() * sizeof(WorkerDataDev)));
+        HIP_TRY(h, hipMemcpy(h->data_dev.p, tab.data(), tab.size() * sizeof(WorkerDataDev), hipMemcpyHostToDevice));
+        h->data_dirty = false;
+    }
+
+    // ---- gradient groups: keep the gathered rows of a group cache resident ----
+    int32_t group = 1;
+    size_t off_coef = 0;
+    if (with_grad) {
+        int64_t max_r = 0;
+        for (int32_t r = 0; r < R; ++r) max_r = std::max(max_r, r_off[r + 1] - r_off[r]);
+        if (h->o.model == ADPSGD_MODEL_MLP) {
+            group = static_cast<int32_t>(std::min<int64_t>(std::max<int64_t>(max_r, 1), 64));
+            HIP_TRY(h, h->grad_scratch.reserve(mlp_scratch_bytes(group, M, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out)));
+        } else {
+            const int64_t op_bytes = static_cast<int64_t>(M) * h->d * 4;
+            group = static_cast<int32_t>(std::min<int64_t>(std::max<int64_t>(kCacheBytes / op_bytes, 1), std::max<int64_t>(max_r, 1)));
+            group = std::min(group, 65535);
+            const size_t partial_bytes = static_cast<size_t>(group) * (M + 1) * linear_grad_chunks(h->d) * 4;
+            off_coef = (partial_bytes + 255) & ~size_t(255);
+            HIP_TRY(h, h->grad_scratch.reserve(off_coef + static_cast<size_t>(group) * M * 4));
+        }
+    }
+
+    // ---- rounds ----
+    const bool profile = (h->o.flags & ADPSGD_FLAG_PROFILE) != 0;
+    float* slots = static_cast<float*>(h->o.workspace);
+    const float gscale = h->o.grad_sum ? 1.0f : 1.0f / static_cast<float>(std::max(M, 1));
+    for (int32_t r = 0; r < R; ++r) {
+        for (int64_t g0 = r_off[r]; g0 < r_off[r + 1]; g0 += group) {
+            const int32_t cnt = static_cast<int32_t>(std::min<int64_t>(group, r_off[r + 1] - g0));
+            hipEvent_t e0 = nullptr, e1 = nullptr;
+            if (profile) {
+                e0 = take_event(h);
+                e1 = take_event(h);
+                if (!e0 || !e1) return fail(h, ADPSGD_ERR_HIP, "run_events: hipEventCreate failed");
+                HIP_TRY(h, hipEventRecord(e0, h->stream));
+            }
+            int launches = 0;
+            if (h->o.model == ADPSGD_MODEL_MLP) {
+                MlpGradArgs a{h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, d_rops + g0, cnt, M,
+                              d_batch, static_cast<const WorkerDataDev*>(h->data_dev.p), slots, gscale, loss,
+                              h->grad_scratch.p};
+                HIP_TRY(h, launch_mlp_gradient(a, h->stream, &launches));
+            } else {
+                LinearGradArgs a{h->o.model, h->o.X, h->o.ldx, h->d, d_rops + g0, cnt, M, d_batch,
+                                 static_cast<const WorkerDataDev*>(h->data_dev.p), slots, gscale, h->o.lambda,
+                                 static_cast<float*>(h->grad_scratch.p),
+                                 reinterpret_cast<float*>(static_cast<char*>(h->grad_scratch.p) + off_coef), loss};
+                HIP_TRY(h, launch_linear_gradient(a, h->stream, &launches));
+            }
+            h->stats.grad_launches += launches;
+            if (profile) {
+                HIP_TRY(h, hipEventRecord(e1, h->stream));
+                h->ev_grad.push_back({e0, e1});
+            }
+        }
+        const int64_t nu = u_off[r + 1] - u_off[r];
+        if (nu > 0) {
+            hipEvent_t e0 = nullptr, e1 = nullptr;
+            if (profile) {
+                e0 = take_event(h);
+                e1 = take_event(h);
+                if (!e0 || !e1) return fail(h, ADPSGD_ERR_HIP, "run_events: hipEventCreate failed");
+                HIP_TRY(h, hipEventRecord(e0, h->stream));
+            }
+            FusedArgs a{h->o.X, h->o.ldx, h->d, d_uops + u_off[r], static_cast<int32_t>(nu), slots,
+                        h->o.model == ADPSGD_MODEL_MLP ? h->o.Xbf16 : nullptr, h->o.synth_std, h->o.synth_seed,
+                        !with_grad, h->streaming};
+            HIP_TRY(h, launch_fused_gossip_apply(a, h->stream));
+            ++h->stats.fused_launches;
+            h->stats.max_round_pairs = std::max<int64_t>(h->stats.max_round_pairs, nu);
+            if (profile) {
+                HIP_TRY(h, hipEventRecord(e1, h->stream));
+                h->ev_fused.push_back({e0, e1});
+            }
+        }
+    }
+    HIP_TRY(h, hipEventRecord(T.done, h->stream));
+    T.in_flight = true;
+    h->events_done += static_cast<uint64_t>(K);
+    h->stats.events += K;
+    h->stats.rounds += R;
+    return ADPSGD_OK;
+}
+
+extern "C" int adpsgd_get_models(adpsgd_t* h, float* out, int64_t ld_out, int32_t on_device) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (!out || ld_out < h->d) return fail(h, ADPSGD_ERR_ARG, "get_models: out is NULL or ld_out < d");
+    HIP_TRY(h, hipMemcpy2DAsync(out, static_cast<size_t>(ld_out) * 4, h->o.X, static_cast<size_t>(h->o.ldx) * 4,
+                                static_cast<size_t>(h->d) * 4, h->n,
+                                on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return ADPSGD_OK;
+}
+
+extern "C" int adpsgd_get_bf16_models(adpsgd_t* h, uint16_t* out, int64_t ld_out, int32_t on_device) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (h->o.model != ADPSGD_MODEL_MLP) return fail(h, ADPSGD_ERR_STATE, "get_bf16_models: only the MLP model keeps a bf16 shadow");
+    if (!out || ld_out < h->d) return fail(h, ADPSGD_ERR_ARG, "get_bf16_models: out is NULL or ld_out < d");
+    HIP_TRY(h, hipMemcpy2DAsync(out, static_cast<size_t>(ld_out) * 2, h->o.Xbf16, static_cast<size_t>(h->o.ldx) * 2,
+                                static_cast<size_t>(h->d) * 2, h->n,
+                                on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return ADPSGD_OK;
+}
+
+extern "C" int adpsgd_get_mean_model(adpsgd_t* h, float* out, int32_t on_device) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (!out) return fail(h, ADPSGD_ERR_ARG, "get_mean_model: out is NULL");
+    float* dst = out;
+    if (!on_device) {
+        HIP_TRY(h, hipStreamSynchronize(h->stream));
+        HIP_TRY(h, h->diag.reserve(static_cast<size_t>(h->d) * 4));
+        dst = static_cast<float*>(h->diag.p);
+    }
+    HIP_TRY(h, launch_mean_model(h->o.X, h->o.ldx, h->d, h->n, dst, h->stream));
+    if (!on_device)
+        HIP_TRY(h, hipMemcpyAsync(out, dst, static_cast<size_t>(h->d) * 4, hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return ADPSGD_OK;
+}
+
+extern "C" int adpsgd_consensus_distance(adpsgd_t* h, double* out) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (!out) return fail(h, ADPSGD_ERR_ARG, "consensus_distance: out is NULL");
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    const int32_t blocks = consensus_blocks(h->d);
+    HIP_TRY(h, h->diag.reserve(static_cast<size_t>(blocks + 1) * sizeof(double)));
+    double* partial = static_cast<double*>(h->diag.p);
+    HIP_TRY(h, launch_consensus(h->o.X, h->o.ldx, h->d, h->n, partial, partial + blocks, h->stream));
+    HIP_TRY(h, hipMemcpyAsync(out, partial + blocks, sizeof(double), hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return ADPSGD_OK;
+}
+
+extern "C" int adpsgd_get_stats(adpsgd_t* h, adpsgd_stats_t* out) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (!out) return fail(h, ADPSGD_ERR_ARG, "get_stats: out is NULL");
+    const int rc = drain_profile(h);
+    if (rc != ADPSGD_OK) return rc;
+    *out = h->stats;
+    return ADPSGD_OK;
+}
+
+extern "C" int adpsgd_synth_gradient(uint64_t seed, uint64_t k, float std, int64_t d, float* out_device, void* stream) {
+    if (!out_device || d < 0) return ADPSGD_ERR_ARG;
+    const hipError_t e = launch_synth_gradient(seed, k, std, d, out_device, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? ADPSGD_OK : ADPSGD_ERR_HIP;
+}

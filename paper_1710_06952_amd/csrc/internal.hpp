@@ -1,0 +1,128 @@
+// Internal declarations shared by the host-side translation units of libadpsgd.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "adpsgd.h"
+
+namespace adpsgd_impl {
+
+// One update event as the fused gossip-average + apply kernel sees it.
+struct alignas(32) PairOp {
+    int32_t i;        // worker i_k (takes the gradient step)
+    int32_t j;        // neighbour j_k (i == j: no partner, plain SGD step)
+    uint32_t k_lo;    // global event number (addresses the synthetic-gradient generator)
+    uint32_t k_hi;
+    float gamma;
+    int32_t slot;     // pending-gradient slot holding g_k (data models)
+    int32_t pad0, pad1;
+};
+
+// One stale read / gradient evaluation as the gradient kernels see it.
+struct GradOp {
+    int32_t worker;   // row read, and owner of the local data
+    int32_t slot;     // where g_k goes
+    int32_t event;    // index into the call's batch_idx / loss arrays
+    int32_t pad;
+};
+
+struct WorkerData {
+    const void* features = nullptr;
+    const void* targets = nullptr;
+    int64_t rows = 0;
+    int64_t ld = 0;
+};
+
+// Device-side table of the workers' local data (array of n entries).
+struct WorkerDataDev {
+    const void* features;
+    const void* targets;
+    int64_t ld;
+};
+
+struct Plan {
+    std::vector<int32_t> r_round, u_round, slot;
+    int32_t n_rounds = 0;
+};
+
+// Grow-only device buffer owned by the library (small tables only).
+struct DevBuf {
+    void* p = nullptr;
+    size_t cap = 0;
+    hipError_t reserve(size_t bytes);
+    void release();
+};
+
+// ---- host logic ------------------------------------------------------------
+void philox4x32_10_host(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
+                const int32_t* tau, int32_t n_slots, bool with_gradients, Plan& plan,
+                std::string& err);
+bool graph_ok(const adpsgd_graph_t* g, std::string& err);
+
+// ---- kernel launchers (each returns the hipError_t of the launch) ------------
+struct FusedArgs {
+    float* X;
+    int64_t ld;
+    int64_t d;
+    const PairOp* ops;   // device
+    int32_t n_ops;
+    const float* slots;  // device, slot s at slots + s * ld (data models)
+    uint16_t* Xbf16;     // device bf16 shadow or nullptr
+    float synth_std;
+    uint64_t synth_seed;
+    bool synth;
+    bool streaming;      // rows do not fit the caches: bypass them
+};
+hipError_t launch_fused_gossip_apply(const FusedArgs& a, hipStream_t st);
+
+struct LinearGradArgs {
+    int model;              // LSQ or LOGREG
+    const float* X;
+    int64_t ld;
+    int64_t d;
+    const GradOp* ops;      // device, this group's ops
+    int32_t n_ops;
+    int32_t M;
+    const int32_t* batch_idx;  // device, K x M
+    const WorkerDataDev* data; // device, n entries
+    float* slots;
+    float gscale;           // 1/M or 1
+    float lambda;
+    float* partial;         // device scratch: n_ops x (M + 1) x n_chunks
+    float* coef;            // device scratch: n_ops x M
+    float* loss;            // device, indexed by event, or nullptr
+};
+int64_t linear_grad_chunks(int64_t d);
+hipError_t launch_linear_gradient(const LinearGradArgs& a, hipStream_t st, int* n_launches);
+
+struct MlpGradArgs {
+    const uint16_t* Xbf16;  // device bf16 shadow, n x ld
+    int64_t ld;
+    int32_t in, hid, out;
+    const GradOp* ops;
+    int32_t n_ops;
+    int32_t M;
+    const int32_t* batch_idx;
+    const WorkerDataDev* data;
+    float* slots;
+    float gscale;
+    float* loss;
+    void* scratch;          // device scratch, mlp_scratch_bytes(n_ops, ...)
+};
+size_t mlp_scratch_bytes(int32_t n_ops, int32_t M, int32_t in, int32_t hid, int32_t out);
+hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_launches);
+
+hipError_t launch_broadcast_rows(float* X, int64_t ld, int64_t d, int32_t n, const float* x0, hipStream_t st);
+hipError_t launch_refresh_bf16(const float* X, uint16_t* Xb, int64_t ld, int32_t n, hipStream_t st);
+hipError_t launch_mean_model(const float* X, int64_t ld, int64_t d, int32_t n, float* out, hipStream_t st);
+int32_t consensus_blocks(int64_t d);
+hipError_t launch_consensus(const float* X, int64_t ld, int64_t d, int32_t n, double* partial,
+                            double* result, hipStream_t st);
+hipError_t launch_synth_gradient(uint64_t seed, uint64_t k, float std, int64_t d, float* out, hipStream_t st);
+
+}  // namespace adpsgd_impl

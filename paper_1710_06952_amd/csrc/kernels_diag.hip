@@ -1,0 +1,127 @@
+// Model initialisation and diagnostics: equal initial models (Algorithm 1's
+// requirement), the bf16 shadow of the master weights, the mean model (the
+// algorithm's output) and the consensus distance (1/n) sum_i |mean - x^i|^2
+// (M_k of the proofs appendix with uniform p), reduced with wavefront shuffles.
+#include "device_common.hpp"
+#include "internal.hpp"
+
+namespace adpsgd_impl {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int kConsensusBlocksMax = 2048;
+
+// grid = (ceil(ld/4 / kThreads), n): every row <- x0 on [0, d), zero on [d, ld)
+__global__ __launch_bounds__(kThreads) void broadcast_rows_kernel(float* X, int64_t ld, int64_t d, const float* x0) {
+    const int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (4 * v >= ld) return;
+    v4f val;
+    float t[4];
+    for (int c = 0; c < 4; ++c) t[c] = (4 * v + c < d) ? x0[4 * v + c] : 0.0f;
+    val.x = t[0]; val.y = t[1]; val.z = t[2]; val.w = t[3];
+    *reinterpret_cast<v4f*>(X + static_cast<int64_t>(blockIdx.y) * ld + 4 * v) = val;
+}
+
+__global__ __launch_bounds__(kThreads) void refresh_bf16_kernel(const float* X, uint16_t* Xb, int64_t ld) {
+    const int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (4 * v >= ld) return;
+    const int64_t off = static_cast<int64_t>(blockIdx.y) * ld + 4 * v;
+    const v4f x = *reinterpret_cast<const v4f*>(X + off);
+    v4h h = {bf16_rne(x.x), bf16_rne(x.y), bf16_rne(x.z), bf16_rne(x.w)};
+    *reinterpret_cast<v4h*>(Xb + off) = h;
+}
+
+// one thread per float4 of d: column sums over the n rows in a fixed order
+__global__ __launch_bounds__(kThreads) void mean_model_kernel(const float* X, int64_t ld, int64_t d, int32_t n, float* out) {
+    const int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (4 * v >= d) return;
+    double s[4] = {0, 0, 0, 0};
+    for (int32_t i = 0; i < n; ++i) {
+        const v4f x = *reinterpret_cast<const v4f*>(X + static_cast<int64_t>(i) * ld + 4 * v);
+        s[0] += x.x; s[1] += x.y; s[2] += x.z; s[3] += x.w;
+    }
+    for (int c = 0; c < 4; ++c)
+        if (4 * v + c < d) out[4 * v + c] = static_cast<float>(s[c] / n);
+}
+
+// Per column e: sum_i (x_i - mean)^2 = sum_i t_i^2 - (sum_i t_i)^2 / n with t_i = x_i - x_0
+// (shifting by row 0 keeps the subtraction exact when the replicas are close).
+// Grid-stride over float4 columns, fp64 accumulation, wavefront reduction, one
+// partial per block; a second single-block launch sums the partials in order.
+__global__ __launch_bounds__(kThreads) void consensus_partial_kernel(const float* X, int64_t ld, int64_t d, int32_t n,
+                                                                    double* partial) {
+    __shared__ double red[kWaves];
+    const int64_t n_vec = (d + 3) / 4;
+    double acc = 0.0;
+    for (int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; v < n_vec;
+         v += static_cast<int64_t>(gridDim.x) * kThreads) {
+        const v4f x0 = *reinterpret_cast<const v4f*>(X + 4 * v);
+        double s1[4] = {0, 0, 0, 0}, s2[4] = {0, 0, 0, 0};
+        for (int32_t i = 1; i < n; ++i) {
+            const v4f x = *reinterpret_cast<const v4f*>(X + static_cast<int64_t>(i) * ld + 4 * v);
+            const float t[4] = {x.x - x0.x, x.y - x0.y, x.z - x0.z, x.w - x0.w};
+            for (int c = 0; c < 4; ++c) {
+                s1[c] += t[c];
+                s2[c] += static_cast<double>(t[c]) * t[c];
+            }
+        }
+        for (int c = 0; c < 4; ++c)
+            if (4 * v + c < d) acc += s2[c] - s1[c] * s1[c] / n;
+    }
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ __launch_bounds__(kThreads) void consensus_final_kernel(const double* partial, int32_t count, int32_t n,
+                                                                  double* result) {
+    __shared__ double red[kWaves];
+    double acc = 0.0;
+    for (int32_t b = threadIdx.x; b < count; b += kThreads) acc += partial[b];
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) *result = ((red[0] + red[1]) + (red[2] + red[3])) / n;
+}
+
+}  // namespace
+
+hipError_t launch_broadcast_rows(float* X, int64_t ld, int64_t d, int32_t n, const float* x0, hipStream_t st) {
+    const int64_t blocks = (ld / 4 + kThreads - 1) / kThreads;
+    if (blocks > 0x7FFFFFFF || n > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(broadcast_rows_kernel, dim3(static_cast<uint32_t>(blocks), n), dim3(kThreads), 0, st, X, ld, d, x0);
+    return hipGetLastError();
+}
+
+hipError_t launch_refresh_bf16(const float* X, uint16_t* Xb, int64_t ld, int32_t n, hipStream_t st) {
+    const int64_t blocks = (ld / 4 + kThreads - 1) / kThreads;
+    if (blocks > 0x7FFFFFFF || n > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(refresh_bf16_kernel, dim3(static_cast<uint32_t>(blocks), n), dim3(kThreads), 0, st, X, Xb, ld);
+    return hipGetLastError();
+}
+
+hipError_t launch_mean_model(const float* X, int64_t ld, int64_t d, int32_t n, float* out, hipStream_t st) {
+    const int64_t blocks = ((d + 3) / 4 + kThreads - 1) / kThreads;
+    if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(mean_model_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, st, X, ld, d, n, out);
+    return hipGetLastError();
+}
+
+int32_t consensus_blocks(int64_t d) {
+    const int64_t want = ((d + 3) / 4 + kThreads - 1) / kThreads;
+    return static_cast<int32_t>(want < kConsensusBlocksMax ? (want < 1 ? 1 : want) : kConsensusBlocksMax);
+}
+
+hipError_t launch_consensus(const float* X, int64_t ld, int64_t d, int32_t n, double* partial, double* result,
+                            hipStream_t st) {
+    const int32_t blocks = consensus_blocks(d);
+    hipLaunchKernelGGL(consensus_partial_kernel, dim3(blocks), dim3(kThreads), 0, st, X, ld, d, n, partial);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, st, partial, blocks, n, result);
+    return hipGetLastError();
+}
+
+}  // namespace adpsgd_impl

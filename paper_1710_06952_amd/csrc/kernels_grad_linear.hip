@@ -1,0 +1,206 @@
+// Batched per-worker minibatch gradient for the linear models (Algorithm 1,
+// gradient step: g_k = gscale * sum_m grad F(x^_k; xi_{k,m}), evaluated at the
+// stale read x^_k = row i_k of X at the round the planner chose).
+//
+//   least squares        grad F = a (a.x - b)
+//   logistic regression  grad F = -y sigmoid(-y a.x) a + lambda x
+//
+// Three launches per group of gradient operations:
+//   1. dots:     partial z[op][m][chunk] = A[idx_m, chunk] . x^[chunk]   (batched GEMV, HBM bound)
+//   2. finalize: z -> per-sample coefficient c_m and the minibatch loss
+//   3. combine:  g[chunk] = sum_m c_m A[idx_m, chunk] (+ reg * x^[chunk]) into the pending slot
+// The gathered rows are read twice; the group size is chosen by the host so
+// that the second read is served from the memory-side cache.  Partial sums are
+// combined in a fixed order: results do not depend on scheduling.
+#include "device_common.hpp"
+#include "internal.hpp"
+
+namespace adpsgd_impl {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int kDotUnroll = 4;                                // float4 per thread per row
+constexpr int64_t kDotChunk = kThreads * kDotUnroll * 4;     // 4096 floats of d per block
+constexpr int kRowsPerBlock = 8;                             // minibatch rows per dots block
+
+struct LinParams {
+    int model;
+    const float* X;
+    int64_t ld;
+    int64_t d;
+    int64_t n_vec;
+    int64_t n_chunks;   // dots chunks per row
+    const GradOp* ops;
+    int32_t M;
+    const int32_t* batch_idx;
+    const WorkerDataDev* data;
+    float* slots;
+    float gscale;
+    float lambda;
+    float* partial;     // [op][M + 1][n_chunks]
+    float* coef;        // [op][M]
+    float* loss;
+};
+
+__device__ __forceinline__ v4f zero_beyond(v4f v, int64_t e, int64_t d) {
+    if (e + 4 > d) {
+        if (e + 1 >= d) v.y = 0.0f;
+        if (e + 2 >= d) v.z = 0.0f;
+        if (e + 3 >= d) v.w = 0.0f;
+        if (e >= d) v.x = 0.0f;
+    }
+    return v;
+}
+__device__ __forceinline__ float dot4(v4f a, v4f b) { return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w; }
+
+// grid = (n_chunks, ceil((M+1) / kRowsPerBlock), n_ops); "row" M is x^ itself (|x^|^2 for the regulariser)
+__global__ __launch_bounds__(kThreads) void linear_dots_kernel(const LinParams p) {
+    __shared__ float red[kWaves][kRowsPerBlock];
+    const GradOp op = p.ops[blockIdx.z];
+    const WorkerDataDev wd = p.data[op.worker];
+    const float* __restrict__ A = static_cast<const float*>(wd.features);
+    const float* __restrict__ xrow = p.X + static_cast<int64_t>(op.worker) * p.ld;
+    const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
+    const int64_t v0 = static_cast<int64_t>(blockIdx.x) * (kDotChunk / 4) + threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    v4f xh[kDotUnroll];
+#pragma unroll
+    for (int u = 0; u < kDotUnroll; ++u) {
+        const int64_t v = v0 + static_cast<int64_t>(u) * kThreads;
+        xh[u] = v < p.n_vec ? zero_beyond(*reinterpret_cast<const v4f*>(xrow + 4 * v), 4 * v, p.d) : v4f{0, 0, 0, 0};
+    }
+    const int m_begin = blockIdx.y * kRowsPerBlock;
+#pragma unroll 2
+    for (int r = 0; r < kRowsPerBlock; ++r) {
+        const int m = m_begin + r;
+        if (m > p.M) break;
+        if (m == p.M && p.model != ADPSGD_MODEL_LOGREG) break;
+        const float* __restrict__ row = m < p.M ? A + static_cast<int64_t>(idx[m]) * wd.ld : xrow;
+        float acc = 0.0f;
+#pragma unroll
+        for (int u = 0; u < kDotUnroll; ++u) {
+            const int64_t v = v0 + static_cast<int64_t>(u) * kThreads;
+            if (v < p.n_vec) acc += dot4(zero_beyond(*reinterpret_cast<const v4f*>(row + 4 * v), 4 * v, p.d), xh[u]);
+        }
+        acc = wave_sum(acc);
+        if (lane == 0) red[wave][r] = acc;
+    }
+    __syncthreads();
+    if (threadIdx.x < kRowsPerBlock) {
+        const int m = m_begin + threadIdx.x;
+        if (m < p.M || (m == p.M && p.model == ADPSGD_MODEL_LOGREG)) {
+            float s = red[0][threadIdx.x];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) s += red[w][threadIdx.x];
+            p.partial[(static_cast<int64_t>(blockIdx.z) * (p.M + 1) + m) * p.n_chunks + blockIdx.x] = s;
+        }
+    }
+}
+
+// grid = n_ops; one thread per minibatch sample (strided)
+__global__ __launch_bounds__(kThreads) void linear_finalize_kernel(const LinParams p) {
+    __shared__ float red[kWaves];
+    const GradOp op = p.ops[blockIdx.x];
+    const WorkerDataDev wd = p.data[op.worker];
+    const float* __restrict__ tg = static_cast<const float*>(wd.targets);
+    const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
+    const float* __restrict__ part = p.partial + static_cast<int64_t>(blockIdx.x) * (p.M + 1) * p.n_chunks;
+    float reg_loss = 0.0f;
+    if (p.model == ADPSGD_MODEL_LOGREG) {
+        float xn = 0.0f;
+        for (int64_t c = 0; c < p.n_chunks; ++c) xn += part[static_cast<int64_t>(p.M) * p.n_chunks + c];
+        reg_loss = 0.5f * p.lambda * xn;
+    }
+    float loss = 0.0f;
+    for (int m = threadIdx.x; m < p.M; m += kThreads) {
+        float z = 0.0f;
+        for (int64_t c = 0; c < p.n_chunks; ++c) z += part[static_cast<int64_t>(m) * p.n_chunks + c];
+        const float t = tg[idx[m]];
+        float c_m;
+        if (p.model == ADPSGD_MODEL_LSQ) {
+            const float r = z - t;              // a.x - b
+            loss += 0.5f * r * r;
+            c_m = r;
+        } else {
+            const float s = -t * z;             // F = log(1 + e^s) + reg
+            loss += (s > 0.0f ? s + log1pf(expf(-s)) : log1pf(expf(s))) + reg_loss;
+            c_m = -t / (1.0f + expf(-s));       // -y sigmoid(s)
+        }
+        p.coef[static_cast<int64_t>(blockIdx.x) * p.M + m] = c_m * p.gscale;
+    }
+    loss = wave_sum(loss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = loss;
+    __syncthreads();
+    if (threadIdx.x == 0 && p.loss) {
+        float s = red[0];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) s += red[w];
+        p.loss[op.event] = s * p.gscale;
+    }
+}
+
+// grid = (ceil(n_vec / kThreads), n_ops)
+__global__ __launch_bounds__(kThreads) void linear_combine_kernel(const LinParams p) {
+    const GradOp op = p.ops[blockIdx.y];
+    const int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (v >= p.n_vec) return;
+    const WorkerDataDev wd = p.data[op.worker];
+    const float* __restrict__ A = static_cast<const float*>(wd.features);
+    const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
+    const float* __restrict__ cf = p.coef + static_cast<int64_t>(blockIdx.y) * p.M;
+    v4f acc = {0, 0, 0, 0};
+#pragma unroll 8
+    for (int m = 0; m < p.M; ++m) {
+        const v4f a = *reinterpret_cast<const v4f*>(A + static_cast<int64_t>(idx[m]) * wd.ld + 4 * v);
+        acc += a * cf[m];
+    }
+    if (p.model == ADPSGD_MODEL_LOGREG) {
+        const v4f xh = *reinterpret_cast<const v4f*>(p.X + static_cast<int64_t>(op.worker) * p.ld + 4 * v);
+        acc += xh * (p.lambda * p.gscale * static_cast<float>(p.M));
+    }
+    acc = zero_beyond(acc, 4 * v, p.d);
+    *reinterpret_cast<v4f*>(p.slots + static_cast<int64_t>(op.slot) * p.ld + 4 * v) = acc;
+}
+
+}  // namespace
+
+int64_t linear_grad_chunks(int64_t d) { return (d + kDotChunk - 1) / kDotChunk; }
+
+hipError_t launch_linear_gradient(const LinearGradArgs& a, hipStream_t st, int* n_launches) {
+    if (a.n_ops <= 0) return hipSuccess;
+    LinParams p;
+    p.model = a.model;
+    p.X = a.X;
+    p.ld = a.ld;
+    p.d = a.d;
+    p.n_vec = (a.d + 3) / 4;
+    p.n_chunks = linear_grad_chunks(a.d);
+    p.ops = a.ops;
+    p.M = a.M;
+    p.batch_idx = a.batch_idx;
+    p.data = a.data;
+    p.slots = a.slots;
+    p.gscale = a.gscale;
+    p.lambda = a.lambda;
+    p.partial = a.partial;
+    p.coef = a.coef;
+    p.loss = a.loss;
+    const int64_t out_blocks = (p.n_vec + kThreads - 1) / kThreads;
+    if (p.n_chunks > 0x7FFFFFFF || out_blocks > 0x7FFFFFFF || a.n_ops > 65535) return hipErrorInvalidValue;
+    const uint32_t row_groups = static_cast<uint32_t>((a.M + 1 + kRowsPerBlock - 1) / kRowsPerBlock);
+    if (row_groups > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(linear_dots_kernel, dim3(static_cast<uint32_t>(p.n_chunks), row_groups, a.n_ops), dim3(kThreads),
+                       0, st, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(linear_finalize_kernel, dim3(a.n_ops), dim3(kThreads), 0, st, p);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(linear_combine_kernel, dim3(static_cast<uint32_t>(out_blocks), a.n_ops), dim3(kThreads), 0, st, p);
+    if (n_launches) *n_launches += 3;
+    return hipGetLastError();
+}
+
+}  // namespace adpsgd_impl

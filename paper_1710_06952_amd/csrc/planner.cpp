@@ -1,0 +1,107 @@
+// Round planner: turns the serial event order of Algorithm 1 into rounds of
+// operations that touch disjoint model rows.
+//
+// Event k contributes two operations:
+//   R_k  reads row i_k as it was before event s_k = k - tau_k (the stale model
+//        x^_k = column i_k of X_{k - tau_k}) and evaluates g_k into a slot;
+//   U_k  averages rows i_k, j_k and applies -gamma g_k to row i_k.
+// A round executes all its R operations first, then all its U operations.
+// Per row the plan keeps: the U operations in event order; R_k after every U_m
+// with m < s_k on row i_k and not after any U_m with m >= s_k on that row
+// (the same round is allowed, because reads precede updates inside a round);
+// a slot is reused only in a later round than the update that consumed it.
+// Disjoint pairwise averages commute, so executing the rounds in order gives
+// exactly the serial result.
+#include <algorithm>
+#include <queue>
+
+#include "internal.hpp"
+
+namespace adpsgd_impl {
+
+int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
+                const int32_t* tau, int32_t n_slots, bool with_gradients, Plan& plan,
+                std::string& err) {
+    plan.r_round.assign(static_cast<size_t>(K), -1);
+    plan.u_round.assign(static_cast<size_t>(K), -1);
+    plan.slot.assign(static_cast<size_t>(K), -1);
+    plan.n_rounds = 0;
+
+    // rounds are numbered from 1 while planning (0 = "never touched"), shifted to 0 at the end
+    std::vector<int32_t> last_write(n, 0);  // round of the last U on the row
+    std::vector<int32_t> last_read(n, 0);   // latest round of an R on the row
+
+    // events grouped by the logical time of their read, s_k = k - tau_k
+    std::vector<int64_t> head(static_cast<size_t>(K) + 1, -1), next(static_cast<size_t>(K), -1);
+    int32_t tau_max = 0;
+    if (with_gradients) {
+        for (int64_t k = K - 1; k >= 0; --k) {
+            if (tau[k] < 0 || tau[k] > k) { err = "plan: tau[k] outside [0, k]"; return ADPSGD_ERR_SCHEDULE; }
+            tau_max = std::max(tau_max, tau[k]);
+            const int64_t s = k - tau[k];
+            next[k] = head[s];
+            head[s] = k;
+        }
+        if (n_slots <= tau_max) {
+            err = "plan: need more pending-gradient slots than the largest staleness";
+            return ADPSGD_ERR_SCHEDULE;
+        }
+    }
+    // free slots ordered by the round after which they may be rewritten
+    using Free = std::pair<int32_t, int32_t>;  // (round of the consuming update, slot)
+    std::priority_queue<Free, std::vector<Free>, std::greater<Free>> free_slots;
+    if (with_gradients)
+        for (int32_t s = 0; s < n_slots; ++s) free_slots.push({0, s});
+
+    int32_t rounds = 0;
+    for (int64_t t = 0; t < K; ++t) {
+        if (with_gradients) {
+            for (int64_t k = head[t]; k >= 0; k = next[k]) {
+                const int32_t i = worker[k];
+                if (free_slots.empty()) { err = "plan: internal error, no free slot"; return ADPSGD_ERR_STATE; }
+                const Free f = free_slots.top();
+                free_slots.pop();
+                const int32_t r = std::max(last_write[i], f.first) + 1;
+                plan.r_round[k] = r;
+                plan.slot[k] = f.second;
+                last_read[i] = std::max(last_read[i], r);
+            }
+        }
+        const int32_t i = worker[t], j = neighbour[t];
+        int32_t u = std::max(last_write[i], last_write[j]) + 1;
+        u = std::max(u, std::max(last_read[i], last_read[j]));
+        if (with_gradients) u = std::max(u, plan.r_round[t]);
+        plan.u_round[t] = u;
+        last_write[i] = last_write[j] = u;
+        rounds = std::max(rounds, u);
+        if (with_gradients) free_slots.push({u, plan.slot[t]});
+    }
+    for (int64_t k = 0; k < K; ++k) {
+        plan.u_round[k] -= 1;
+        if (with_gradients) plan.r_round[k] -= 1;
+    }
+    plan.n_rounds = rounds;
+    return ADPSGD_OK;
+}
+
+}  // namespace adpsgd_impl
+
+using namespace adpsgd_impl;
+
+extern "C" int adpsgd_plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
+                                  const int32_t* tau, int32_t n_slots, int32_t with_gradients,
+                                  int32_t* r_round, int32_t* u_round, int32_t* slot, int32_t* n_rounds) {
+    if (n < 1 || K < 0 || !worker || !neighbour || !tau || !r_round || !u_round || !slot || !n_rounds)
+        return ADPSGD_ERR_ARG;
+    for (int64_t k = 0; k < K; ++k)
+        if (worker[k] < 0 || worker[k] >= n || neighbour[k] < 0 || neighbour[k] >= n) return ADPSGD_ERR_SCHEDULE;
+    Plan plan;
+    std::string err;
+    const int rc = plan_rounds(n, K, worker, neighbour, tau, n_slots, with_gradients != 0, plan, err);
+    if (rc != ADPSGD_OK) return rc;
+    std::copy(plan.r_round.begin(), plan.r_round.end(), r_round);
+    std::copy(plan.u_round.begin(), plan.u_round.end(), u_round);
+    std::copy(plan.slot.begin(), plan.slot.end(), slot);
+    *n_rounds = plan.n_rounds;
+    return ADPSGD_OK;
+}

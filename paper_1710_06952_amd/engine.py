@@ -1,0 +1,106 @@
+"""Device-memory plumbing around the C-ABI handle: PyTorch allocates the model
+matrix, the pending-gradient workspace and the workers' data on the GPU and
+lends a stream; every computation happens inside libadpsgd.so."""
+from __future__ import annotations
+
+import numpy as np
+
+from . import binding as B
+
+_MODELS = {"lsq": B.MODEL_LSQ, "logreg": B.MODEL_LOGREG, "synth": B.MODEL_SYNTH, "mlp": B.MODEL_MLP}
+
+
+def _pad(d, mult=64):
+    return (d + mult - 1) // mult * mult
+
+
+class Engine:
+    def __init__(self, graph, d, model, *, M=0, gamma=0.0, lam=0.0, grad_sum=False, T_max=0, synth_std=0.0,
+                 synth_seed=0, mlp=(0, 0, 0), n_slots=None, profile=False, device="cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("Engine needs a GPU: the HIP library is the only implementation")
+        self.torch = torch
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.n = len(graph[0]) - 1
+        self.d = d
+        self.ld = _pad(d)
+        self.model = _MODELS[model] if isinstance(model, str) else model
+        self.M = M
+        self.X = torch.zeros((self.n, self.ld), dtype=torch.float32, device=self.device)
+        self.Xbf16 = None
+        self.workspace = None
+        ws_ptr, ws_bytes = None, 0
+        if self.model != B.MODEL_SYNTH:
+            if n_slots is None:
+                n_slots = max(T_max + 1, min(4 * self.n, 256))
+                budget = 8 << 30                         # keep the slots within 8 GiB by default
+                n_slots = max(T_max + 1, min(n_slots, budget // (self.ld * 4)))
+            self.workspace = torch.empty((n_slots, self.ld), dtype=torch.float32, device=self.device)
+            ws_ptr, ws_bytes = self.workspace.data_ptr(), n_slots * self.ld * 4
+        if self.model == B.MODEL_MLP:
+            self.Xbf16 = torch.zeros((self.n, self.ld), dtype=torch.bfloat16, device=self.device)
+        self.stream = torch.cuda.current_stream(self.device)
+        self.h = B.Handle(graph, d, model=self.model, X_ptr=self.X.data_ptr(), ldx=self.ld, M=M, gamma=gamma,
+                          lam=lam, grad_sum=grad_sum, T_max=T_max, synth_std=synth_std, synth_seed=synth_seed,
+                          mlp=mlp, Xbf16_ptr=None if self.Xbf16 is None else self.Xbf16.data_ptr(),
+                          workspace_ptr=ws_ptr, workspace_bytes=ws_bytes, stream=self.stream.cuda_stream,
+                          flags=B.FLAG_PROFILE if profile else 0)
+        self._data = []
+        self.loss = None
+
+    def load_data(self, features, targets):
+        """features/targets: per-worker numpy arrays (host) or torch tensors already on the GPU."""
+        torch = self.torch
+        for i, (f, t) in enumerate(zip(features, targets)):
+            if isinstance(f, np.ndarray):
+                rows, cols = f.shape
+                mult = 8 if f.dtype == np.uint16 else 4
+                ld = _pad(cols, mult)
+                if f.dtype == np.uint16:
+                    ft = torch.zeros((rows, ld), dtype=torch.bfloat16, device=self.device)
+                    ft[:, :cols] = torch.from_numpy(f.view(np.int16)).to(self.device).view(torch.bfloat16)
+                else:
+                    ft = torch.zeros((rows, ld), dtype=torch.float32, device=self.device)
+                    ft[:, :cols] = torch.from_numpy(f).to(self.device)
+                tt = torch.from_numpy(np.ascontiguousarray(t)).to(self.device)
+            else:
+                ft, tt = f, t
+                rows, ld = ft.shape[0], ft.stride(0)
+            self._data.append((ft, tt))
+            self.h.load_data(i, ft.data_ptr(), rows, ld, tt.data_ptr())
+        torch.cuda.synchronize(self.device)
+
+    def set_models(self, x, broadcast=True):
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        self.h.set_models(x, 0 if broadcast else x.shape[1])
+
+    def run_events(self, schedule, want_loss=False):
+        loss_ptr = None
+        if want_loss:
+            self.loss = self.torch.zeros(len(schedule["worker"]), dtype=self.torch.float32, device=self.device)
+            loss_ptr = self.loss.data_ptr()
+        self.h.run_events(schedule, loss_ptr)
+
+    def get_loss(self):
+        self.torch.cuda.synchronize(self.device)
+        return self.loss.cpu().numpy()
+
+    def get_models(self):
+        return self.h.get_models()
+
+    def get_bf16_models(self):
+        return self.h.get_bf16_models()
+
+    def get_mean_model(self):
+        return self.h.get_mean_model()
+
+    def consensus_distance(self):
+        return self.h.consensus_distance()
+
+    def get_stats(self):
+        return self.h.get_stats()
+
+    def close(self):
+        self.h.destroy()

@@ -1,0 +1,200 @@
+"""CPU-side tests of the HIP library's host logic (no GPU needed): the shared
+library loads and exports every declared symbol, its schedule generator agrees
+bit for bit with the oracle's own, and the round planner keeps serial semantics.
+"""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_1710_06952_amd as P
+from paper_1710_06952_amd import binding as B
+from workloads import get_config, hop_ring_graph, lsq_data, random_regular4_graph, ring_graph
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "adpsgd.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(adpsgd_[a-z0-9_]+)\s*\(", header)))
+    assert len(declared) >= 14
+    L = P.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert sorted(P.EXPORTS) == declared
+    # the four calls the method is specified by
+    for name in ("adpsgd_create", "adpsgd_load_data", "adpsgd_run_events", "adpsgd_get_models"):
+        assert name in declared
+
+
+def _graph_for(cfg):
+    return {"ring": ring_graph, "hopring": hop_ring_graph}.get(cfg["graph"], lambda n: random_regular4_graph(n, cfg["seed"]))(cfg["n"])
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_schedule_generators_agree_bit_for_bit(idx):
+    cfg = get_config(idx)
+    g = _graph_for(cfg)
+    n, K = cfg["n"], min(cfg["K"], 5000)
+    kw = dict(seed=cfg["seed"], T_max=cfg["T_max"], M=cfg["M"], rows=[max(cfg["rows"], 1)] * n)
+    if cfg["tau_mode"] == "geometric":
+        slow = np.arange(n) < cfg["n_slow"]
+        kw.update(tau_mode=1, weight=np.where(slow, cfg["weight_slow"], cfg["weight_fast"]),
+                  tau_num=np.where(slow, cfg["tau_slow"][0], cfg["tau_fast"][0]),
+                  tau_den=np.where(slow, cfg["tau_slow"][1], cfg["tau_fast"][1]))
+    for k_begin in (0, 123456789012):
+        a = P.adpsgd_make_schedule(g, K, k_begin=k_begin, **kw)
+        b = oracle.make_schedule(g, K, k_begin=k_begin, **kw)
+        for key in ("worker", "neighbour", "tau"):
+            assert np.array_equal(a[key], b[key]), key
+        if cfg["M"] > 0:
+            assert np.array_equal(a["batch_idx"], b["batch_idx"])
+
+
+def test_schedule_generator_rejects_bad_arguments():
+    g = ring_graph(4)
+    with pytest.raises(P.AdpsgdError):
+        P.adpsgd_make_schedule(g, 10, M=4, rows=[0, 1, 1, 1])
+    with pytest.raises(P.AdpsgdError):
+        P.adpsgd_make_schedule(g, 10, tau_mode=1, T_max=3)          # geometric without (num, den)
+    with pytest.raises(P.AdpsgdError):
+        P.adpsgd_make_schedule(g, 10, weight=[0, 0, 0, 0])
+
+
+def test_create_validates_graph_and_buffers_before_touching_the_gpu():
+    L = P.lib()
+
+    def create(rowptr, col, d=8, **kw):
+        rowptr, col = np.asarray(rowptr, np.int32), np.asarray(col, np.int32)
+        g = B.Graph(rowptr.size - 1, rowptr.ctypes.data_as(C.POINTER(C.c_int32)), col.ctypes.data_as(C.POINTER(C.c_int32)))
+        o = B.Opts()
+        o.model, o.X, o.ldx = B.MODEL_SYNTH, 4096, 8
+        for k, v in kw.items():
+            setattr(o, k, v)
+        h = C.c_void_p()
+        rc = L.adpsgd_create(C.byref(h), C.byref(g), d, C.byref(o))
+        assert rc != 0 and not h.value
+        return rc, L.adpsgd_last_error(None).decode()
+
+    assert create([0, 1, 2, 2], [1, 0])[0] == B.ERR_GRAPH             # vertex 2 unreachable
+    assert create([0, 1, 1], [1])[0] == B.ERR_GRAPH                   # not symmetric
+    assert create([0, 1, 2], [0, 1])[0] == B.ERR_GRAPH                # self loops
+    assert create([0, 2, 4], [1, 1, 0, 0])[0] == B.ERR_GRAPH          # duplicate edge
+    rc, msg = create([0, 1, 2], [1, 0], X=4100)
+    assert rc == B.ERR_ARG and "aligned" in msg
+    assert create([0, 1, 2], [1, 0], ldx=6)[0] == B.ERR_ARG           # ldx < d
+    assert create([0, 1, 2], [1, 0], model=B.MODEL_LSQ, M=4)[0] == B.ERR_ARG   # no workspace
+
+
+# ----------------------------------------------------------------------------- planner
+def _check_plan(n, sched, n_slots, with_grad=True):
+    w, j, tau = sched["worker"], sched["neighbour"], sched["tau"]
+    K = len(w)
+    r_round, u_round, slot, R = P.adpsgd_plan_rounds(n, w, j, tau, n_slots, with_grad)
+    assert u_round.min() >= 0 and u_round.max() == R - 1
+    # serial reference: version of every row as seen by each read, order of updates per row
+    version = np.zeros(n, np.int64)
+    seen_serial = np.zeros(K, np.int64)
+    by_s = [[] for _ in range(K + 1)]
+    for k in range(K):
+        by_s[k - tau[k]].append(k)
+    for t in range(K):
+        for k in by_s[t]:
+            seen_serial[k] = version[w[k]]
+        version[w[t]] += 1
+        if j[t] != w[t]:
+            version[j[t]] += 1
+    # planned execution: reads of a round, then its updates
+    version[:] = 0
+    order_u = np.argsort(u_round, kind="stable")
+    order_r = np.argsort(r_round, kind="stable") if with_grad else []
+    pu = pr = 0
+    last_u_event = -np.ones(n, np.int64)
+    for r in range(R):
+        while with_grad and pr < K and r_round[order_r[pr]] == r:
+            k = order_r[pr]
+            assert version[w[k]] == seen_serial[k], "stale read sees the wrong state"
+            assert r_round[k] <= u_round[k]
+            pr += 1
+        touched = set()
+        while pu < K and u_round[order_u[pu]] == r:
+            k = order_u[pu]
+            rows = {w[k], j[k]}
+            assert not (rows & touched), "two updates of one round share a row"
+            touched |= rows
+            for row in rows:
+                assert last_u_event[row] < k, "updates of a row out of event order"
+                last_u_event[row] = k
+                version[row] += 1
+            pu += 1
+    assert pu == K
+    if with_grad:
+        assert slot.min() >= 0 and slot.max() < n_slots
+        for s in range(n_slots):
+            ks = np.where(slot == s)[0]
+            ks = ks[np.argsort(r_round[ks], kind="stable")]
+            for a, b in zip(ks[:-1], ks[1:]):
+                assert r_round[b] > u_round[a], "slot rewritten before its gradient was consumed"
+    return R
+
+
+@pytest.mark.parametrize("n,T,graph", [(8, 3, "ring"), (64, 8, "ring"), (16, 4, "reg4"), (6, 0, "ring"), (1, 0, "ring")])
+def test_planner_keeps_serial_semantics(n, T, graph):
+    g = ring_graph(n) if graph == "ring" else random_regular4_graph(n, 1)
+    sched = oracle.make_schedule(g, 3000, seed=n, T_max=T)
+    R_min = _check_plan(n, sched, T + 1)
+    R_more = _check_plan(n, sched, 4 * (T + 1) + 8)
+    assert R_more <= R_min
+    _check_plan(n, sched, 0, with_grad=False)
+    if T > 0:      # fewer slots than the largest staleness + 1 cannot hold the in-flight gradients
+        with pytest.raises(P.AdpsgdError):
+            P.adpsgd_plan_rounds(n, sched["worker"], sched["neighbour"], sched["tau"], T)
+
+
+def test_planner_packs_many_pairs_per_round_on_the_large_ring():
+    n = 128
+    sched = oracle.make_schedule(ring_graph(n), 20000, seed=0, T_max=16)
+    _, u_round, _, R = P.adpsgd_plan_rounds(n, sched["worker"], sched["neighbour"], sched["tau"], 0, False)
+    assert 20000 / R > 15          # far from one event per launch
+    assert np.bincount(u_round).max() <= n // 2
+
+
+def test_planner_with_heterogeneous_geometric_staleness():
+    cfg = get_config(5)
+    n = cfg["n"]
+    g = random_regular4_graph(n, 0)
+    slow = np.arange(n) < cfg["n_slow"]
+    sched = oracle.make_schedule(g, 4000, seed=0, T_max=cfg["T_max"], tau_mode=1,
+                                 weight=np.where(slow, 1, 10), tau_num=np.where(slow, 20, 2),
+                                 tau_den=np.where(slow, 21, 3))
+    assert sched["tau"].max() > 40
+    _check_plan(n, sched, cfg["T_max"] + 1)
+
+
+def test_planned_rounds_reproduce_the_oracle_bit_for_bit():
+    """Execute the plan on the CPU (gradients from the oracle's own routine, updates in
+    numpy fp32) and compare with the oracle's serial run: reordering into rounds is exact."""
+    n, d, rows, K, M, T = 8, 24, 16, 600, 4, 5
+    g = ring_graph(n)
+    feats, targs, _ = lsq_data(n, rows, d, seed=1)
+    sched = oracle.make_schedule(g, K, seed=2, T_max=T, M=M, rows=[rows] * n)
+    X_ref = np.zeros((n, d), np.float32)
+    X_ref[:] = np.random.default_rng(0).standard_normal(d).astype(np.float32)
+    X = X_ref.copy()
+    oracle.run_events(X_ref, sched, oracle.MODEL_LSQ, 0.02, M=M, gscale=1.0 / M, features=feats, targets=targs, mode=0)
+    w, j, tau = sched["worker"], sched["neighbour"], sched["tau"]
+    r_round, u_round, slot, R = P.adpsgd_plan_rounds(n, w, j, tau, T + 3, True)
+    slots = {}
+    for r in range(R):
+        for k in np.where(r_round == r)[0]:
+            slots[slot[k]] = oracle.minibatch_gradient(oracle.MODEL_LSQ, X[w[k]], feats[w[k]], targs[w[k]],
+                                                       sched["batch_idx"][k], 1.0 / M)[0]
+        for k in np.random.default_rng(r).permutation(np.where(u_round == r)[0]):   # any order inside a round
+            avg = (X[w[k]] + X[j[k]]) * np.float32(0.5)
+            X[j[k]] = avg
+            X[w[k]] = avg - np.float32(0.02) * slots[slot[k]]
+    assert np.array_equal(X, X_ref)
