@@ -65,6 +65,19 @@ class Stats(C.Structure):
 _lib = None
 
 
+def _preload_hip_runtime():
+    """One process must use ONE HIP runtime: device pointers and streams handed over by PyTorch
+    belong to the libamdhip64 that PyTorch bundles.  Load that copy first (same SONAME as the one
+    libadpsgd.so was linked against), so the dynamic loader resolves our dependency to it."""
+    import importlib.util
+    spec = importlib.util.find_spec("torch")
+    if spec is None or not spec.submodule_search_locations:
+        return
+    cand = Path(list(spec.submodule_search_locations)[0]) / "lib" / "libamdhip64.so"
+    if cand.exists():
+        C.CDLL(str(cand), mode=C.RTLD_GLOBAL)
+
+
 def lib():
     """Load libadpsgd.so (built in-tree by paper_1710_06952_amd.build).  Fails loudly."""
     global _lib
@@ -72,6 +85,7 @@ def lib():
         if not LIB_PATH.exists():
             raise ImportError("%s is missing: run `python -m paper_1710_06952_amd.build` "
                               "(there is no CPU fallback)" % LIB_PATH)
+        _preload_hip_runtime()
         L = C.CDLL(str(LIB_PATH))
         vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
         P = C.POINTER
