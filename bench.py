@@ -30,11 +30,11 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 
 def traffic_from_profiles():
-    """HBM bytes per launch of the fused kernel measured with rocprofv3 --pmc (FETCH_SIZE and
+    """HBM bytes per event of the fused kernel measured with rocprofv3 --pmc (FETCH_SIZE and
     WRITE_SIZE runs, scaled by a copy kernel of known size); kept as text under profiles/."""
     path = os.path.join(ROOT, "profiles", "fused_gossip_apply_cfg3_pmc.txt")
     try:
-        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        m = re.search(r"^traffic_bytes_per_event:\s*([0-9.eE+]+)", open(path).read(), re.M)
         return float(m.group(1)) if m else None
     except OSError:
         return None
@@ -61,6 +61,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--events-per-step", type=int, default=10000)
     ap.add_argument("--cpu-events", type=int, default=16, help="events the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
     ap.add_argument("--d", type=int, default=0, help="override d (debugging only; the result is then not the headline)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -84,6 +86,12 @@ def main():
     scheds = [P.adpsgd_make_schedule(graph, E, seed=cfg["seed"], k_begin=s * E, T_max=cfg["T_max"])
               for s in range(args.warmup + args.steps)]
 
+    if args.calibrate_copy:        # 2^28 floats read + 2^28 floats written by an elementwise copy kernel
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for s in range(args.warmup):
         eng.run_events(scheds[s])
     torch.cuda.synchronize()
@@ -116,7 +124,11 @@ def main():
     events_per_launch = ps["events"] / ps["fused_launches"]
     avg_launch_s = ps["fused_ms"] * 1e-3 / ps["fused_launches"]
     achieved = bytes_per_event * events_per_launch / avg_launch_s / 1e9
-    traffic = traffic_from_profiles()
+    traffic = traffic_from_profiles()          # measured bytes per event (rocprofv3 counters) ...
+    if traffic is not None and d == 25_600_000:
+        traffic *= events_per_launch           # ... per launch, like `achieved`
+    else:
+        traffic = None
 
     out = {
         "metric": "worker updates/sec and gossip+update HBM GB/s (% of peak) at n=128, d=25.6M",

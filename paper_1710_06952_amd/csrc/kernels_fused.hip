@@ -13,8 +13,14 @@
 namespace adpsgd_impl {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kUnroll = 4;                        // float4 per thread, per row, per tile
+#ifndef ADPSGD_FUSED_THREADS
+#define ADPSGD_FUSED_THREADS 256
+#endif
+#ifndef ADPSGD_FUSED_UNROLL
+#define ADPSGD_FUSED_UNROLL 4
+#endif
+constexpr int kThreads = ADPSGD_FUSED_THREADS;
+constexpr int kUnroll = ADPSGD_FUSED_UNROLL;      // float4 per thread, per row, per tile
 constexpr int64_t kTileVec = kThreads * kUnroll;  // 1024 float4 = 16 KiB of each row
 
 struct FusedParams {
@@ -63,8 +69,12 @@ __global__ __launch_bounds__(kThreads) void fused_gossip_apply_kernel(const Fuse
         const int64_t v = v0 + static_cast<int64_t>(u) * kThreads;
         if (v >= p.n_vec) continue;
         if (SYNTH) {
+#ifdef ADPSGD_EXPERIMENT_NO_RNG
+            g[u] = v4f{1.0f, 1.0f, 1.0f, 1.0f} * p.synth_std;
+#else
             g[u] = synth_normals4(static_cast<uint32_t>(v), static_cast<uint32_t>(v >> 32), op.k_lo, op.k_hi,
                                   p.key0, p.key1) * p.synth_std;
+#endif
         }
         if (4 * v + 4 > p.d) {   // ragged tail: entries at and beyond d stay zero
             const int64_t e = 4 * v;
