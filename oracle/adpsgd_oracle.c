@@ -273,34 +273,41 @@ static double grad_mlp(const grad_spec* s, const float* xhat, const uint16_t* Xi
                        const int32_t* label, const int32_t* idx, double* gacc)
 {
     const int I = s->mlp_in, H = s->mlp_hid, O = s->mlp_out, M = s->M;
-    const float* W1 = xhat;
-    const float* b1 = W1 + (int64_t)I * H;
-    const float* W2 = b1 + H;
-    const float* b2 = W2 + (int64_t)H * O;
+    const float *W1, *b1, *W2, *b2;   /* point into the bf16-rounded copy of xhat, below */
     double* gW1 = gacc;
     double* gb1 = gW1 + (int64_t)I * H;
     double* gW2 = gb1 + H;
     double* gb2 = gW2 + (int64_t)H * O;
     float* hid = (float*)malloc(sizeof(float) * (size_t)H);      /* relu output, bf16-rounded */
     double* dhid = (double*)malloc(sizeof(double) * (size_t)H);
+    double* pre = (double*)malloc(sizeof(double) * (size_t)H);
     double* logit = (double*)malloc(sizeof(double) * (size_t)O);
     double* dlogit = (double*)malloc(sizeof(double) * (size_t)O);
+    /* the bf16 shadow of the weights, rounded once (the same value wherever it is used) */
+    float* wq = (float*)malloc(sizeof(float) * (size_t)s->d);
+    for (int64_t t = 0; t < s->d; ++t) wq[t] = round_bf16(xhat[t]);
+    W1 = wq;
+    b1 = W1 + (int64_t)I * H;
+    W2 = b1 + H;
+    b2 = W2 + (int64_t)H * O;
     double loss = 0.0;
     for (int m = 0; m < M; ++m) {
         const uint16_t* xin = Xin + (int64_t)idx[m] * ldin;
-        /* forward, layer 1 */
+        /* forward, layer 1: pre[h] = sum_i x[i] W1[i][h], terms added in increasing i */
+        for (int h = 0; h < H; ++h) pre[h] = 0.0;
+        for (int i = 0; i < I; ++i) {
+            const double xi = (double)bf16_to_f32(xin[i]);
+            for (int h = 0; h < H; ++h) pre[h] += xi * (double)W1[(int64_t)i * H + h];
+        }
         for (int h = 0; h < H; ++h) {
-            double acc = 0.0;
-            for (int i = 0; i < I; ++i)
-                acc += (double)bf16_to_f32(xin[i]) * (double)round_bf16(W1[(int64_t)i * H + h]);
-            float pre = (float)(acc + (double)round_bf16(b1[h]));
-            hid[h] = round_bf16(pre > 0.0f ? pre : 0.0f);
+            float a = (float)(pre[h] + (double)b1[h]);
+            hid[h] = round_bf16(a > 0.0f ? a : 0.0f);
         }
         /* forward, layer 2 + softmax cross-entropy */
         double zmax = -INFINITY;
         for (int o = 0; o < O; ++o) {
-            double acc = (double)round_bf16(b2[o]);
-            for (int h = 0; h < H; ++h) acc += (double)hid[h] * (double)round_bf16(W2[(int64_t)h * O + o]);
+            double acc = (double)b2[o];
+            for (int h = 0; h < H; ++h) acc += (double)hid[h] * (double)W2[(int64_t)h * O + o];
             logit[o] = acc;
             if (acc > zmax) zmax = acc;
         }
@@ -315,7 +322,7 @@ static double grad_mlp(const grad_spec* s, const float* xhat, const uint16_t* Xi
             double acc = 0.0;
             for (int o = 0; o < O; ++o) {
                 gW2[(int64_t)h * O + o] += (double)hid[h] * dlogit[o];
-                acc += dlogit[o] * (double)round_bf16(W2[(int64_t)h * O + o]);
+                acc += dlogit[o] * (double)W2[(int64_t)h * O + o];
             }
             /* error at the hidden pre-activation, scaled by gscale BEFORE the bf16
              * rounding so that the rounded operand of the large product already
@@ -332,7 +339,7 @@ static double grad_mlp(const grad_spec* s, const float* xhat, const uint16_t* Xi
     /* layer-1 terms already carry gscale (inside dhid); scale the layer-2 terms */
     for (int64_t t = 0; t < (int64_t)H * O; ++t) gW2[t] *= s->gscale;
     for (int o = 0; o < O; ++o) gb2[o] *= s->gscale;
-    free(hid); free(dhid); free(logit); free(dlogit);
+    free(hid); free(dhid); free(pre); free(logit); free(dlogit); free(wq);
     return loss * s->gscale;
 }
 

@@ -1,12 +1,300 @@
-// Minibatch gradient of the two-layer perceptron (placeholder until the MFMA
-// kernels land: creation of an MLP engine fails with a clear message).
+// Minibatch gradient of the two-layer perceptron  in -> hid (ReLU) -> out with
+// softmax cross-entropy (Algorithm 1, gradient step, for the dense-network
+// workload).  Parameters are flattened as [W1 (in x hid) | b1 | W2 (hid x out) | b2];
+// the gradient reads the bf16 shadow of the stale model and bf16 inputs, and
+// accumulates in fp32.  The two large products are dense contractions and run
+// on the matrix cores (v_mfma_f32_16x16x32_bf16, 64-lane wavefronts):
+//   forward   H  = relu(Xb W1 + b1)        M x in  times  in x hid
+//   backward  dW1 = Xb^T dH                in x M  times  M x hid
+// The hidden activations and their back-propagated error are rounded to bf16
+// before they enter those products.  The second layer (hid x out, out <= 16) is
+// small and stays on the vector ALUs in fp32.
+//
+// Four launches per group of gradient operations; every reduction has a fixed
+// order, so results do not depend on scheduling.
 #include "device_common.hpp"
 #include "internal.hpp"
 
 namespace adpsgd_impl {
+namespace {
 
-size_t mlp_scratch_bytes(int32_t, int32_t, int32_t, int32_t, int32_t) { return 0; }
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef uint16_t v8h __attribute__((ext_vector_type(8)));
 
-hipError_t launch_mlp_gradient(const MlpGradArgs&, hipStream_t, int*) { return hipErrorNotSupported; }
+constexpr int kT = 256;          // 4 wavefronts
+constexpr int kMaxM = 64;        // minibatch rows held by one block (4 MFMA row tiles)
+constexpr int kMaxOut = 16;
+constexpr int kTileH = 64;       // hidden columns per block: 16 per wavefront
+
+struct MlpParams {
+    const uint16_t* Xb;
+    int64_t ld;
+    int in, hid, out;
+    const GradOp* ops;
+    int M;
+    const int32_t* batch_idx;
+    const WorkerDataDev* data;
+    float* slots;
+    float gscale;
+    float* loss;
+    uint16_t* Hb;    // [op][kMaxM][hid]  relu output, bf16
+    uint16_t* dHb;   // [op][kMaxM][hid]  error at the hidden pre-activation, bf16, rows >= M zero
+    float* dlogit;   // [op][kMaxM][kMaxOut]  softmax - onehot
+    float* loss_m;   // [op][kMaxM]
+};
+
+__device__ __forceinline__ v4f mfma_bf16(v8h a, v8h b, v4f c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+}
+
+// Operand layout of v_mfma_f32_16x16x32_bf16 (D = A B + C, A 16x32, B 32x16):
+//   lane l supplies A[l % 16][8 (l / 16) .. +7] and B[8 (l / 16) .. +7][l % 16];
+//   lane l receives D[4 (l / 16) + v][l % 16] in element v of its 4 results.
+
+// ---- 1. forward: H = relu(Xb W1 + b1), grid = (hid / 64, n_ops) ----------------------
+__global__ __launch_bounds__(kT) void mlp_forward_kernel(const MlpParams p) {
+    __shared__ __attribute__((aligned(16))) uint16_t Bt[kTileH][40];   // W1 tile transposed: [h][k], 32 k + pad
+    const GradOp op = p.ops[blockIdx.y];
+    const WorkerDataDev wd = p.data[op.worker];
+    const uint16_t* __restrict__ feat = static_cast<const uint16_t*>(wd.features);
+    const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
+    const uint16_t* __restrict__ W1 = p.Xb + static_cast<int64_t>(op.worker) * p.ld;
+    const uint16_t* __restrict__ b1 = W1 + static_cast<int64_t>(p.in) * p.hid;
+    const int h0 = blockIdx.x * kTileH;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int li = lane & 15, kb = 8 * (lane >> 4);
+
+    const uint16_t* rowp[4];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+        const int m = 16 * mt + li;
+        rowp[mt] = m < p.M ? feat + static_cast<int64_t>(idx[m]) * wd.ld : nullptr;
+    }
+    v4f acc[4];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) acc[mt] = v4f{0, 0, 0, 0};
+
+    const int skk = threadIdx.x >> 3, shh = (threadIdx.x & 7) * 8;   // staging role: one k, 8 columns
+    for (int k0 = 0; k0 < p.in; k0 += 32) {
+        v8h wv = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (k0 + skk < p.in) wv = *reinterpret_cast<const v8h*>(W1 + static_cast<int64_t>(k0 + skk) * p.hid + h0 + shh);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) Bt[shh + e][skk] = wv[e];
+        __syncthreads();
+        const v8h bfrag = *reinterpret_cast<const v8h*>(&Bt[16 * wave + li][kb]);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+            v8h afrag = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (rowp[mt] && k0 + kb < p.in) afrag = *reinterpret_cast<const v8h*>(rowp[mt] + k0 + kb);
+            acc[mt] = mfma_bf16(afrag, bfrag, acc[mt]);
+        }
+        __syncthreads();
+    }
+    const int h = h0 + 16 * wave + li;
+    const float bias = bf16_to_float(b1[h]);
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int m = 16 * mt + 4 * (lane >> 4) + v;
+            if (m < p.M) {
+                const float pre = acc[mt][v] + bias;
+                p.Hb[(static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h] = bf16_rne(pre > 0.0f ? pre : 0.0f);
+            }
+        }
+    }
+}
+
+// ---- 2. logits, softmax, loss: grid = (M, n_ops), one block per sample ----------------
+__global__ __launch_bounds__(kT) void mlp_softmax_kernel(const MlpParams p) {
+    __shared__ float red[kT / 64][kMaxOut];
+    const GradOp op = p.ops[blockIdx.y];
+    const WorkerDataDev wd = p.data[op.worker];
+    const int m = blockIdx.x;
+    const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
+    const uint16_t* __restrict__ W = p.Xb + static_cast<int64_t>(op.worker) * p.ld;
+    const uint16_t* __restrict__ W2 = W + static_cast<int64_t>(p.in) * p.hid + p.hid;
+    const uint16_t* __restrict__ b2 = W2 + static_cast<int64_t>(p.hid) * p.out;
+    const uint16_t* __restrict__ hrow = p.Hb + (static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid;
+    float acc[kMaxOut];
+#pragma unroll
+    for (int o = 0; o < kMaxOut; ++o) acc[o] = 0.0f;
+    for (int h = threadIdx.x; h < p.hid; h += kT) {
+        const float hv = bf16_to_float(hrow[h]);
+#pragma unroll
+        for (int o = 0; o < kMaxOut; ++o)
+            if (o < p.out) acc[o] += hv * bf16_to_float(W2[static_cast<int64_t>(h) * p.out + o]);
+    }
+#pragma unroll
+    for (int o = 0; o < kMaxOut; ++o) {
+        const float s = wave_sum(acc[o]);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6][o] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float logit[kMaxOut];
+        float zmax = -INFINITY;
+        for (int o = 0; o < p.out; ++o) {
+            logit[o] = ((red[0][o] + red[1][o]) + (red[2][o] + red[3][o])) + bf16_to_float(b2[o]);
+            zmax = fmaxf(zmax, logit[o]);
+        }
+        float zsum = 0.0f;
+        for (int o = 0; o < p.out; ++o) zsum += expf(logit[o] - zmax);
+        const int label = static_cast<const int32_t*>(wd.targets)[idx[m]];
+        float* dl = p.dlogit + (static_cast<int64_t>(blockIdx.y) * kMaxM + m) * kMaxOut;
+        for (int o = 0; o < p.out; ++o) dl[o] = expf(logit[o] - zmax) / zsum - (o == label ? 1.0f : 0.0f);
+        p.loss_m[static_cast<int64_t>(blockIdx.y) * kMaxM + m] = -(logit[label] - zmax - logf(zsum));
+    }
+}
+
+// ---- 3. second-layer gradients and the hidden error: grid = (hid / 256, n_ops) --------
+__global__ __launch_bounds__(kT) void mlp_backward_small_kernel(const MlpParams p) {
+    const GradOp op = p.ops[blockIdx.y];
+    const int h = blockIdx.x * kT + threadIdx.x;
+    const uint16_t* __restrict__ W = p.Xb + static_cast<int64_t>(op.worker) * p.ld;
+    const uint16_t* __restrict__ W2 = W + static_cast<int64_t>(p.in) * p.hid + p.hid;
+    float* __restrict__ g = p.slots + static_cast<int64_t>(op.slot) * p.ld;
+    float* __restrict__ gb1 = g + static_cast<int64_t>(p.in) * p.hid;
+    float* __restrict__ gW2 = gb1 + p.hid;
+    float* __restrict__ gb2 = gW2 + static_cast<int64_t>(p.hid) * p.out;
+    const float* __restrict__ dl0 = p.dlogit + static_cast<int64_t>(blockIdx.y) * kMaxM * kMaxOut;
+    if (h < p.hid) {
+        float w2[kMaxOut], gw2[kMaxOut];
+#pragma unroll
+        for (int o = 0; o < kMaxOut; ++o) {
+            w2[o] = o < p.out ? bf16_to_float(W2[static_cast<int64_t>(h) * p.out + o]) : 0.0f;
+            gw2[o] = 0.0f;
+        }
+        float sum_dh = 0.0f;
+        for (int m = 0; m < p.M; ++m) {
+            const int64_t at = (static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h;
+            const float hv = bf16_to_float(p.Hb[at]);
+            const float* __restrict__ dl = dl0 + m * kMaxOut;
+            float back = 0.0f;
+#pragma unroll
+            for (int o = 0; o < kMaxOut; ++o)
+                if (o < p.out) {
+                    gw2[o] += hv * dl[o];
+                    back += dl[o] * w2[o];
+                }
+            const uint16_t dh = bf16_rne(hv > 0.0f ? back * p.gscale : 0.0f);
+            p.dHb[at] = dh;
+            sum_dh += bf16_to_float(dh);
+        }
+        for (int m = p.M; m < kMaxM; ++m) p.dHb[(static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h] = 0;
+        gb1[h] = sum_dh;
+#pragma unroll
+        for (int o = 0; o < kMaxOut; ++o)
+            if (o < p.out) gW2[static_cast<int64_t>(h) * p.out + o] = gw2[o] * p.gscale;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < p.out) {
+        float s = 0.0f;
+        for (int m = 0; m < p.M; ++m) s += dl0[m * kMaxOut + threadIdx.x];
+        gb2[threadIdx.x] = s * p.gscale;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 64 && p.loss) {
+        float s = 0.0f;
+        for (int m = 0; m < p.M; ++m) s += p.loss_m[static_cast<int64_t>(blockIdx.y) * kMaxM + m];
+        p.loss[op.event] = s * p.gscale;
+    }
+}
+
+// ---- 4. dW1 = Xb^T dH: grid = (hid / 64, ceil(in / 64), n_ops) -------------------------
+__global__ __launch_bounds__(kT) void mlp_dw1_kernel(const MlpParams p) {
+    __shared__ __attribute__((aligned(16))) uint16_t At[64][72];   // inputs transposed:  [i][m], 64 m + pad
+    __shared__ __attribute__((aligned(16))) uint16_t Bt[64][72];   // hidden error transposed: [h][m]
+    const GradOp op = p.ops[blockIdx.z];
+    const WorkerDataDev wd = p.data[op.worker];
+    const uint16_t* __restrict__ feat = static_cast<const uint16_t*>(wd.features);
+    const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
+    const int h0 = blockIdx.x * kTileH, i0 = blockIdx.y * 64;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int li = lane & 15, kb = 8 * (lane >> 4);
+
+    {   // stage: thread handles one minibatch row m and 16 consecutive columns
+        const int m = threadIdx.x >> 2, seg = (threadIdx.x & 3) * 16;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int c = seg + 8 * half;
+            v8h xv = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (m < p.M && i0 + c < p.in) xv = *reinterpret_cast<const v8h*>(feat + static_cast<int64_t>(idx[m]) * wd.ld + i0 + c);
+            const v8h dv = *reinterpret_cast<const v8h*>(p.dHb + (static_cast<int64_t>(blockIdx.z) * kMaxM + m) * p.hid + h0 + c);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                At[c + e][m] = xv[e];
+                Bt[c + e][m] = dv[e];
+            }
+        }
+    }
+    __syncthreads();
+    v4f acc[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) acc[it] = v4f{0, 0, 0, 0};
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        const v8h bfrag = *reinterpret_cast<const v8h*>(&Bt[16 * wave + li][32 * ks + kb]);
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const v8h afrag = *reinterpret_cast<const v8h*>(&At[16 * it + li][32 * ks + kb]);
+            acc[it] = mfma_bf16(afrag, bfrag, acc[it]);
+        }
+    }
+    float* __restrict__ g = p.slots + static_cast<int64_t>(op.slot) * p.ld;
+    const int h = h0 + 16 * wave + li;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int i = i0 + 16 * it + 4 * (lane >> 4) + v;
+            if (i < p.in) g[static_cast<int64_t>(i) * p.hid + h] = acc[it][v];
+        }
+    }
+}
+
+size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+}  // namespace
+
+size_t mlp_scratch_bytes(int32_t n_ops, int32_t M, int32_t in, int32_t hid, int32_t out) {
+    if (n_ops < 1 || M < 1 || M > kMaxM || in < 8 || (in & 7) || hid < kTileH || (hid % kTileH) || out < 1 || out > kMaxOut)
+        return 0;
+    const size_t act = align256(static_cast<size_t>(n_ops) * kMaxM * hid * sizeof(uint16_t));
+    return 2 * act + align256(static_cast<size_t>(n_ops) * kMaxM * kMaxOut * 4) + align256(static_cast<size_t>(n_ops) * kMaxM * 4);
+}
+
+hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_launches) {
+    if (a.n_ops <= 0) return hipSuccess;
+    if (mlp_scratch_bytes(a.n_ops, a.M, a.in, a.hid, a.out) == 0 || a.n_ops > 65535) return hipErrorInvalidValue;
+    MlpParams p;
+    p.Xb = a.Xbf16;
+    p.ld = a.ld;
+    p.in = a.in;
+    p.hid = a.hid;
+    p.out = a.out;
+    p.ops = a.ops;
+    p.M = a.M;
+    p.batch_idx = a.batch_idx;
+    p.data = a.data;
+    p.slots = a.slots;
+    p.gscale = a.gscale;
+    p.loss = a.loss;
+    char* s = static_cast<char*>(a.scratch);
+    const size_t act = align256(static_cast<size_t>(a.n_ops) * kMaxM * a.hid * sizeof(uint16_t));
+    p.Hb = reinterpret_cast<uint16_t*>(s);
+    p.dHb = reinterpret_cast<uint16_t*>(s + act);
+    p.dlogit = reinterpret_cast<float*>(s + 2 * act);
+    p.loss_m = reinterpret_cast<float*>(s + 2 * act + align256(static_cast<size_t>(a.n_ops) * kMaxM * kMaxOut * 4));
+    const uint32_t hb = static_cast<uint32_t>(a.hid / kTileH);
+    hipLaunchKernelGGL(mlp_forward_kernel, dim3(hb, a.n_ops), dim3(kT), 0, st, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(mlp_softmax_kernel, dim3(a.M, a.n_ops), dim3(kT), 0, st, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(mlp_backward_small_kernel, dim3((a.hid + kT - 1) / kT, a.n_ops), dim3(kT), 0, st, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(mlp_dw1_kernel, dim3(hb, (a.in + 63) / 64, a.n_ops), dim3(kT), 0, st, p);
+    if (n_launches) *n_launches += 4;
+    return hipGetLastError();
+}
 
 }  // namespace adpsgd_impl

@@ -254,3 +254,76 @@ def test_config3_full_size_sampled_coordinates(P):
     st = eng.get_stats()
     assert st["events"] == K and st["max_round_pairs"] <= n // 2
     eng.close()
+
+
+# ------------------------------------------------------------------ two-layer perceptron (bf16 + MFMA)
+# Tolerances.  The hidden activations and their back-propagated error are rounded to bf16 before the
+# two matrix-core products.  The oracle accumulates the pre-activations in fp64, the kernel in fp32
+# inside the MFMA unit; whenever the two sums straddle a bf16 rounding boundary the rounded value
+# differs by one bf16 ulp (2^-8 relative), about 5e-4 of all activations per event.  Those flips,
+# not fp32 rounding, bound the agreement: the task's bound for this workload is 2e-2 on the bf16
+# weights; the fp32 master is held to 2e-3 on these short runs, and a single gradient to 1e-3.
+MLP_TOL_BF16 = 2e-2
+MLP_TOL_MASTER = 2e-3
+
+
+def _run_mlp(P, n, dims, rows, K, M, T, gamma, seed, graph):
+    from workloads import mixture_data, mlp_init
+    I, H, O = dims
+    d = I * H + H + H * O + O
+    g = ring_graph(n) if graph == "ring" else random_regular4_graph(n, seed)
+    feats, labels, _ = mixture_data(n, rows, din=I, classes=O, seed=seed)
+    x0 = mlp_init(I, H, O, seed=seed)
+    sched = oracle.make_schedule(g, K, seed=seed, T_max=T, M=M, rows=[rows] * n)
+    eng = P.Engine(g, d, "mlp", M=M, gamma=gamma, T_max=T, mlp=dims)
+    eng.load_data(feats, labels)
+    eng.set_models(x0)
+    eng.run_events(sched, want_loss=True)
+    Xg, Xb, lg = eng.get_models(), eng.get_bf16_models(), eng.get_loss()
+    Xr = np.tile(x0, (n, 1))
+    r = oracle.run_events(Xr, sched, oracle.MODEL_MLP, gamma, M=M, gscale=1.0 / M, mlp=dims, features=feats,
+                          targets=labels, mode=1, want_loss=True)
+    eng.close()
+    return Xg, Xb, lg, Xr, r["loss"], x0
+
+
+@pytest.mark.parametrize("n,dims,rows,K,M,T,graph", [(5, (24, 64, 5), 40, 200, 16, 2, "reg4"),
+                                                      (6, (40, 128, 10), 50, 300, 13, 4, "ring"),
+                                                      (5, (8, 64, 16), 9, 60, 1, 0, "ring"),
+                                                      (7, (72, 192, 3), 70, 150, 64, 3, "reg4")])
+def test_mlp_small_shapes(P, n, dims, rows, K, M, T, graph):
+    from workloads import bf16_bits_to_f32
+    _say("mlp n=%d dims=%s K=%d M=%d" % (n, dims, K, M))
+    Xg, Xb, lg, Xr, lr, _ = _run_mlp(P, n, dims, rows, K, M, T, 0.05, 1, graph)
+    assert rel_err(Xg, Xr) <= MLP_TOL_MASTER
+    assert np.array_equal(bf16_bits_to_f32(Xb), oracle.round_bf16(Xg))       # shadow = RNE(master), always
+    assert rel_err(bf16_bits_to_f32(Xb), oracle.round_bf16(Xr)) <= MLP_TOL_BF16
+    assert np.allclose(lg, lr, rtol=5e-3, atol=5e-4)
+    assert lr[-20:].mean() < lr[:20].mean()                                   # and it trains
+
+
+def test_mlp_single_gradient_config4_shape(P):
+    """One event from identical states isolates the gradient kernels (forward MFMA product, softmax,
+    second-layer terms, dW1 MFMA product): x_i - x_j = -gamma g afterwards."""
+    _say("mlp single gradient 784-1024-10, M=64")
+    dims, gamma = (784, 1024, 10), 0.05
+    Xg, Xb, lg, Xr, lr, x0 = _run_mlp(P, 16, dims, 128, 1, 64, 0, gamma, 0, "reg4")
+    i = int(np.argmax(np.abs(Xr - x0[None, :]).sum(1) > 0))
+    rows = np.where(np.abs(Xr - x0[None, :]).sum(1) > 0)[0]
+    assert rows.size == 1                       # equal initial models: only x_i moves
+    gg = (x0 - Xg[rows[0]]).astype(np.float64) / gamma
+    gr = (x0 - Xr[rows[0]]).astype(np.float64) / gamma
+    scale = np.max(np.abs(gr))
+    assert np.max(np.abs(gg - gr)) <= 1e-3 * scale
+    assert np.mean(np.abs(gg - gr) <= 1e-5 * scale) > 0.99
+    assert abs(lg[0] - lr[0]) <= 1e-5 * abs(lr[0])
+
+
+def test_config4_mlp_full_shape_short_run(P):
+    from workloads import bf16_bits_to_f32
+    c = get_config(4)
+    _say("config 4 full shape, 400 events: %s" % c["name"])
+    Xg, Xb, lg, Xr, lr, _ = _run_mlp(P, c["n"], c["mlp"], c["rows"], 400, c["M"], c["T_max"], c["gamma"], c["seed"], "reg4")
+    assert rel_err(Xg, Xr) <= MLP_TOL_MASTER
+    assert rel_err(bf16_bits_to_f32(Xb), oracle.round_bf16(Xr)) <= MLP_TOL_BF16
+    assert np.allclose(lg, lr, rtol=5e-3, atol=5e-4)
