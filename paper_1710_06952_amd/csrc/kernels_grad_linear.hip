@@ -99,7 +99,17 @@ __global__ __launch_bounds__(kThreads) void linear_dots_kernel(const LinParams p
     }
 }
 
-// grid = n_ops; one thread per minibatch sample (strided)
+// Sum of the n_chunks partials of one dot product by a 16-lane group: lane t adds the
+// partials t, t + 16, ... in order, then the 16 lane sums are combined by a fixed butterfly.
+__device__ __forceinline__ float sum_chunks16(const float* __restrict__ part, int64_t n_chunks, int sub) {
+    float s = 0.0f;
+    for (int64_t c = sub; c < n_chunks; c += 16) s += part[c];
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    return s;
+}
+
+// grid = n_ops; 16 lanes per minibatch sample, 16 samples per pass of the block
 __global__ __launch_bounds__(kThreads) void linear_finalize_kernel(const LinParams p) {
     __shared__ float red[kWaves];
     const GradOp op = p.ops[blockIdx.x];
@@ -107,28 +117,29 @@ __global__ __launch_bounds__(kThreads) void linear_finalize_kernel(const LinPara
     const float* __restrict__ tg = static_cast<const float*>(wd.targets);
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const float* __restrict__ part = p.partial + static_cast<int64_t>(blockIdx.x) * (p.M + 1) * p.n_chunks;
+    const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
     float reg_loss = 0.0f;
-    if (p.model == ADPSGD_MODEL_LOGREG) {
-        float xn = 0.0f;
-        for (int64_t c = 0; c < p.n_chunks; ++c) xn += part[static_cast<int64_t>(p.M) * p.n_chunks + c];
-        reg_loss = 0.5f * p.lambda * xn;
-    }
+    if (p.model == ADPSGD_MODEL_LOGREG)
+        reg_loss = 0.5f * p.lambda * sum_chunks16(part + static_cast<int64_t>(p.M) * p.n_chunks, p.n_chunks, sub);
     float loss = 0.0f;
-    for (int m = threadIdx.x; m < p.M; m += kThreads) {
-        float z = 0.0f;
-        for (int64_t c = 0; c < p.n_chunks; ++c) z += part[static_cast<int64_t>(m) * p.n_chunks + c];
-        const float t = tg[idx[m]];
-        float c_m;
-        if (p.model == ADPSGD_MODEL_LSQ) {
-            const float r = z - t;              // a.x - b
-            loss += 0.5f * r * r;
-            c_m = r;
-        } else {
-            const float s = -t * z;             // F = log(1 + e^s) + reg
-            loss += (s > 0.0f ? s + log1pf(expf(-s)) : log1pf(expf(s))) + reg_loss;
-            c_m = -t / (1.0f + expf(-s));       // -y sigmoid(s)
+    for (int m0 = 0; m0 < p.M; m0 += kThreads / 16) {     // uniform trip count: shuffles stay converged
+        const int m = m0 + grp;
+        const bool live = m < p.M;
+        const float z = sum_chunks16(part + static_cast<int64_t>(live ? m : 0) * p.n_chunks, p.n_chunks, sub);
+        if (live && sub == 0) {
+            const float t = tg[idx[m]];
+            float c_m;
+            if (p.model == ADPSGD_MODEL_LSQ) {
+                const float r = z - t;              // a.x - b
+                loss += 0.5f * r * r;
+                c_m = r;
+            } else {
+                const float s = -t * z;             // F = log(1 + e^s) + reg
+                loss += (s > 0.0f ? s + log1pf(expf(-s)) : log1pf(expf(s))) + reg_loss;
+                c_m = -t / (1.0f + expf(-s));       // -y sigmoid(s)
+            }
+            p.coef[static_cast<int64_t>(blockIdx.x) * p.M + m] = c_m * p.gscale;
         }
-        p.coef[static_cast<int64_t>(blockIdx.x) * p.M + m] = c_m * p.gscale;
     }
     loss = wave_sum(loss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = loss;

@@ -51,18 +51,32 @@ __device__ __forceinline__ v4f mfma_bf16(v8h a, v8h b, v4f c) {
 //   lane l supplies A[l % 16][8 (l / 16) .. +7] and B[8 (l / 16) .. +7][l % 16];
 //   lane l receives D[4 (l / 16) + v][l % 16] in element v of its 4 results.
 
-// ---- 1. forward: H = relu(Xb W1 + b1), grid = (hid / 64, n_ops) ----------------------
+// ---- 1. forward: H = relu(Xb W1 + b1), grid = (hid / 32, n_ops) ----------------------
+// One block owns a 64 (minibatch) x 32 (hidden) tile of H.  The contraction over the input
+// features is split across the four wavefronts (k-steps of 32, step s goes to wavefront s % 4),
+// each with its own transposed W1 tile in LDS; the next step's operands are fetched into
+// registers while the current step's MFMAs run.  The four partial tiles are then added in a
+// fixed order through LDS.
+constexpr int kFwdTileH = 32;
+
+struct FwdOperands {
+    v8h w[2];   // W1 tile 32 (k) x 32 (h): lane holds 2 rows k, 8 columns each
+    v8h a[4];   // input fragments of the four 16-row minibatch tiles
+};
+
 __global__ __launch_bounds__(kT) void mlp_forward_kernel(const MlpParams p) {
-    __shared__ __attribute__((aligned(16))) uint16_t Bt[kTileH][40];   // W1 tile transposed: [h][k], 32 k + pad
+    __shared__ __attribute__((aligned(16))) unsigned char smem[16384];
     const GradOp op = p.ops[blockIdx.y];
     const WorkerDataDev wd = p.data[op.worker];
     const uint16_t* __restrict__ feat = static_cast<const uint16_t*>(wd.features);
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const uint16_t* __restrict__ W1 = p.Xb + static_cast<int64_t>(op.worker) * p.ld;
     const uint16_t* __restrict__ b1 = W1 + static_cast<int64_t>(p.in) * p.hid;
-    const int h0 = blockIdx.x * kTileH;
+    const int h0 = blockIdx.x * kFwdTileH;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int li = lane & 15, kb = 8 * (lane >> 4);
+    uint16_t(*Bt)[40] = reinterpret_cast<uint16_t(*)[40]>(smem + wave * (kFwdTileH * 40 * 2));   // [h][k]
+    float* red = reinterpret_cast<float*>(smem);
 
     const uint16_t* rowp[4];
 #pragma unroll
@@ -70,37 +84,86 @@ __global__ __launch_bounds__(kT) void mlp_forward_kernel(const MlpParams p) {
         const int m = 16 * mt + li;
         rowp[mt] = m < p.M ? feat + static_cast<int64_t>(idx[m]) * wd.ld : nullptr;
     }
-    v4f acc[4];
+    const int skk = lane >> 2, shh = (lane & 3) * 8;   // staging role inside the wavefront
+    auto fetch = [&](int step, FwdOperands& f) {
+        const int k0 = 32 * step;
+        const v8h zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) acc[mt] = v4f{0, 0, 0, 0};
-
-    const int skk = threadIdx.x >> 3, shh = (threadIdx.x & 7) * 8;   // staging role: one k, 8 columns
-    for (int k0 = 0; k0 < p.in; k0 += 32) {
-        v8h wv = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (k0 + skk < p.in) wv = *reinterpret_cast<const v8h*>(W1 + static_cast<int64_t>(k0 + skk) * p.hid + h0 + shh);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) Bt[shh + e][skk] = wv[e];
-        __syncthreads();
-        const v8h bfrag = *reinterpret_cast<const v8h*>(&Bt[16 * wave + li][kb]);
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-            v8h afrag = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (rowp[mt] && k0 + kb < p.in) afrag = *reinterpret_cast<const v8h*>(rowp[mt] + k0 + kb);
-            acc[mt] = mfma_bf16(afrag, bfrag, acc[mt]);
+        for (int r = 0; r < 2; ++r) {
+            const int k = k0 + skk + 16 * r;
+            f.w[r] = k < p.in ? *reinterpret_cast<const v8h*>(W1 + static_cast<int64_t>(k) * p.hid + h0 + shh) : zero;
         }
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+            f.a[mt] = (rowp[mt] && k0 + kb < p.in) ? *reinterpret_cast<const v8h*>(rowp[mt] + k0 + kb) : zero;
+    };
+
+    v4f acc[4][2];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int ht = 0; ht < 2; ++ht) acc[mt][ht] = v4f{0, 0, 0, 0};
+
+    const int steps = (p.in + 31) / 32, iters = (steps + 3) / 4;   // same trip count for every wavefront
+    FwdOperands cur, nxt;
+    fetch(wave, cur);            // steps beyond the last one fetch zeros
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) Bt[shh + e][skk + 16 * r] = cur.w[r][e];
+        if (it + 1 < iters) fetch(wave + 4 * (it + 1), nxt);
         __syncthreads();
+        v8h bfrag[2];
+#pragma unroll
+        for (int ht = 0; ht < 2; ++ht) bfrag[ht] = *reinterpret_cast<const v8h*>(&Bt[16 * ht + li][kb]);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int ht = 0; ht < 2; ++ht) acc[mt][ht] = mfma_bf16(cur.a[mt], bfrag[ht], acc[mt][ht]);
+        __syncthreads();
+        cur = nxt;
     }
-    const int h = h0 + 16 * wave + li;
-    const float bias = bf16_to_float(b1[h]);
+
+    // (wave0 + wave2) + (wave1 + wave3), element q of lane l at red[half][q][l]
+    auto spill = [&](int half) {
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
+        for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int m = 16 * mt + 4 * (lane >> 4) + v;
-            if (m < p.M) {
-                const float pre = acc[mt][v] + bias;
-                p.Hb[(static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h] = bf16_rne(pre > 0.0f ? pre : 0.0f);
-            }
+            for (int ht = 0; ht < 2; ++ht)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) red[(half * 32 + (mt * 2 + ht) * 4 + v) * 64 + lane] = acc[mt][ht][v];
+    };
+    auto absorb = [&](int half) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int ht = 0; ht < 2; ++ht)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[mt][ht][v] += red[(half * 32 + (mt * 2 + ht) * 4 + v) * 64 + lane];
+    };
+    if (wave >= 2) spill(wave - 2);
+    __syncthreads();
+    if (wave < 2) absorb(wave);
+    __syncthreads();
+    if (wave == 1) spill(0);
+    __syncthreads();
+    if (wave == 0) {
+        absorb(0);
+#pragma unroll
+        for (int ht = 0; ht < 2; ++ht) {
+            const int h = h0 + 16 * ht + li;
+            const float bias = bf16_to_float(b1[h]);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int m = 16 * mt + 4 * (lane >> 4) + v;
+                    if (m < p.M) {
+                        const float pre = acc[mt][ht][v] + bias;
+                        p.Hb[(static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h] = bf16_rne(pre > 0.0f ? pre : 0.0f);
+                    }
+                }
         }
     }
 }
@@ -147,10 +210,15 @@ __global__ __launch_bounds__(kT) void mlp_softmax_kernel(const MlpParams p) {
     }
 }
 
-// ---- 3. second-layer gradients and the hidden error: grid = (hid / 256, n_ops) --------
+// ---- 3. second-layer gradients and the hidden error: grid = (hid / 64, n_ops) ---------
+// Thread (hl, mg): hidden unit h = 64 blockIdx.x + hl, minibatch rows [16 mg, 16 mg + 16).
+// Sums over the minibatch are finished across the four row groups in a fixed order.
 __global__ __launch_bounds__(kT) void mlp_backward_small_kernel(const MlpParams p) {
+    __shared__ float dl_s[kMaxM][kMaxOut];
+    __shared__ float red[4][kMaxOut + 1][64];
     const GradOp op = p.ops[blockIdx.y];
-    const int h = blockIdx.x * kT + threadIdx.x;
+    const int hl = threadIdx.x & 63, mg = threadIdx.x >> 6;
+    const int h = blockIdx.x * 64 + hl;
     const uint16_t* __restrict__ W = p.Xb + static_cast<int64_t>(op.worker) * p.ld;
     const uint16_t* __restrict__ W2 = W + static_cast<int64_t>(p.in) * p.hid + p.hid;
     float* __restrict__ g = p.slots + static_cast<int64_t>(op.slot) * p.ld;
@@ -158,44 +226,56 @@ __global__ __launch_bounds__(kT) void mlp_backward_small_kernel(const MlpParams 
     float* __restrict__ gW2 = gb1 + p.hid;
     float* __restrict__ gb2 = gW2 + static_cast<int64_t>(p.hid) * p.out;
     const float* __restrict__ dl0 = p.dlogit + static_cast<int64_t>(blockIdx.y) * kMaxM * kMaxOut;
-    if (h < p.hid) {
-        float w2[kMaxOut], gw2[kMaxOut];
+    for (int t = threadIdx.x; t < kMaxM * kMaxOut; t += kT) {
+        const int m = t / kMaxOut, o = t % kMaxOut;
+        dl_s[m][o] = (m < p.M && o < p.out) ? dl0[t] : 0.0f;
+    }
+    __syncthreads();
+    float w2[kMaxOut], gw2[kMaxOut];
 #pragma unroll
-        for (int o = 0; o < kMaxOut; ++o) {
-            w2[o] = o < p.out ? bf16_to_float(W2[static_cast<int64_t>(h) * p.out + o]) : 0.0f;
-            gw2[o] = 0.0f;
-        }
-        float sum_dh = 0.0f;
-        for (int m = 0; m < p.M; ++m) {
-            const int64_t at = (static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h;
+    for (int o = 0; o < kMaxOut; ++o) {
+        w2[o] = o < p.out ? bf16_to_float(W2[static_cast<int64_t>(h) * p.out + o]) : 0.0f;
+        gw2[o] = 0.0f;
+    }
+    float sum_dh = 0.0f;
+#pragma unroll 4
+    for (int r = 0; r < 16; ++r) {
+        const int m = 16 * mg + r;
+        const int64_t at = (static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h;
+        uint16_t dh = 0;
+        if (m < p.M) {
             const float hv = bf16_to_float(p.Hb[at]);
-            const float* __restrict__ dl = dl0 + m * kMaxOut;
             float back = 0.0f;
 #pragma unroll
-            for (int o = 0; o < kMaxOut; ++o)
-                if (o < p.out) {
-                    gw2[o] += hv * dl[o];
-                    back += dl[o] * w2[o];
-                }
-            const uint16_t dh = bf16_rne(hv > 0.0f ? back * p.gscale : 0.0f);
-            p.dHb[at] = dh;
+            for (int o = 0; o < kMaxOut; ++o) {     // entries o >= out are zero in dl_s and w2
+                gw2[o] += hv * dl_s[m][o];
+                back += dl_s[m][o] * w2[o];
+            }
+            dh = bf16_rne(hv > 0.0f ? back * p.gscale : 0.0f);
             sum_dh += bf16_to_float(dh);
         }
-        for (int m = p.M; m < kMaxM; ++m) p.dHb[(static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h] = 0;
-        gb1[h] = sum_dh;
+        p.dHb[at] = dh;                              // rows m >= M are the zero padding of the dW1 product
+    }
+#pragma unroll
+    for (int o = 0; o < kMaxOut; ++o) red[mg][o][hl] = gw2[o];
+    red[mg][kMaxOut][hl] = sum_dh;
+    __syncthreads();
+    if (mg == 0) {
 #pragma unroll
         for (int o = 0; o < kMaxOut; ++o)
-            if (o < p.out) gW2[static_cast<int64_t>(h) * p.out + o] = gw2[o] * p.gscale;
+            if (o < p.out)
+                gW2[static_cast<int64_t>(h) * p.out + o] = ((red[0][o][hl] + red[1][o][hl]) + (red[2][o][hl] + red[3][o][hl])) * p.gscale;
+        gb1[h] = (red[0][kMaxOut][hl] + red[1][kMaxOut][hl]) + (red[2][kMaxOut][hl] + red[3][kMaxOut][hl]);
     }
-    if (blockIdx.x == 0 && threadIdx.x < p.out) {
-        float s = 0.0f;
-        for (int m = 0; m < p.M; ++m) s += dl0[m * kMaxOut + threadIdx.x];
-        gb2[threadIdx.x] = s * p.gscale;
+    if (blockIdx.x == 0 && mg == 1 && hl < p.out) {
+        float sdl = 0.0f;
+        for (int m = 0; m < p.M; ++m) sdl += dl_s[m][hl];
+        gb2[hl] = sdl * p.gscale;
     }
-    if (blockIdx.x == 0 && threadIdx.x == 64 && p.loss) {
-        float s = 0.0f;
-        for (int m = 0; m < p.M; ++m) s += p.loss_m[static_cast<int64_t>(blockIdx.y) * kMaxM + m];
-        p.loss[op.event] = s * p.gscale;
+    if (blockIdx.x == 0 && threadIdx.x == 128 && p.loss) {
+        float sl = 0.0f;
+        for (int m = 0; m < p.M; ++m) sl += p.loss_m[static_cast<int64_t>(blockIdx.y) * kMaxM + m];
+        p.loss[op.event] = sl * p.gscale;
     }
 }
 
@@ -285,12 +365,12 @@ hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_laun
     p.dlogit = reinterpret_cast<float*>(s + 2 * act);
     p.loss_m = reinterpret_cast<float*>(s + 2 * act + align256(static_cast<size_t>(a.n_ops) * kMaxM * kMaxOut * 4));
     const uint32_t hb = static_cast<uint32_t>(a.hid / kTileH);
-    hipLaunchKernelGGL(mlp_forward_kernel, dim3(hb, a.n_ops), dim3(kT), 0, st, p);
+    hipLaunchKernelGGL(mlp_forward_kernel, dim3(a.hid / kFwdTileH, a.n_ops), dim3(kT), 0, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(mlp_softmax_kernel, dim3(a.M, a.n_ops), dim3(kT), 0, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(mlp_backward_small_kernel, dim3((a.hid + kT - 1) / kT, a.n_ops), dim3(kT), 0, st, p);
+    hipLaunchKernelGGL(mlp_backward_small_kernel, dim3(a.hid / 64, a.n_ops), dim3(kT), 0, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(mlp_dw1_kernel, dim3(hb, (a.in + 63) / 64, a.n_ops), dim3(kT), 0, st, p);
     if (n_launches) *n_launches += 4;
