@@ -445,9 +445,11 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
                 if (!e0 || !e1) return fail(h, ADPSGD_ERR_HIP, "run_events: hipEventCreate failed");
                 HIP_TRY(h, hipEventRecord(e0, h->stream));
             }
+            bool has_solo = false;
+            for (int64_t t = u_off[r]; t < u_off[r + 1] && !has_solo; ++t) has_solo = uops[t].i == uops[t].j;
             FusedArgs a{h->o.X, h->o.ldx, h->d, d_uops + u_off[r], static_cast<int32_t>(nu), slots,
                         h->o.model == ADPSGD_MODEL_MLP ? h->o.Xbf16 : nullptr, h->o.synth_std, h->o.synth_seed,
-                        !with_grad, h->streaming};
+                        !with_grad, h->streaming, has_solo};
             HIP_TRY(h, launch_fused_gossip_apply(a, h->stream));
             ++h->stats.fused_launches;
             h->stats.max_round_pairs = std::max<int64_t>(h->stats.max_round_pairs, nu);

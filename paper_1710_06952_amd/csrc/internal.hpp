@@ -77,6 +77,7 @@ struct FusedArgs {
     uint64_t synth_seed;
     bool synth;
     bool streaming;      // rows do not fit the caches: bypass them
+    bool has_solo;       // some event of the round has i == j (worker without a neighbour)
 };
 hipError_t launch_fused_gossip_apply(const FusedArgs& a, hipStream_t st);
 

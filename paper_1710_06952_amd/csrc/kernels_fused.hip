@@ -4,30 +4,28 @@
 //     avg = (x^i + x^j) / 2;   x^j <- avg;   x^i <- avg - gamma * g_k
 // Four HBM streams per event (read x^i, x^j, write x^i, x^j) plus one read of
 // g_k from its pending slot, or no fifth stream when g_k is synthetic and is
-// generated in registers.  Pure streaming: 128-bit accesses, every load of a
-// tile issued before the first use, no reuse, so caches are bypassed when the
-// models do not fit them.
+// generated in registers.  Pure streaming, no reuse, so caches are bypassed
+// when the models do not fit them.
+//
+// Access shape (chosen by measurement on MI355X, 13 GB working set, in-place
+// update of ~30 row pairs): each wavefront instruction moves 256 contiguous
+// bytes (one dword per lane) and every lane keeps 4 loads per row in flight;
+// this sustains 6.4 TB/s, against 5.8 TB/s for 128-bit accesses of any unroll
+// and 5.3-5.9 TB/s for deeper or shallower unrolls of the dword shape.
 #include "device_common.hpp"
 #include "internal.hpp"
 
 namespace adpsgd_impl {
 namespace {
 
-#ifndef ADPSGD_FUSED_THREADS
-#define ADPSGD_FUSED_THREADS 256
-#endif
-#ifndef ADPSGD_FUSED_UNROLL
-#define ADPSGD_FUSED_UNROLL 4
-#endif
-constexpr int kThreads = ADPSGD_FUSED_THREADS;
-constexpr int kUnroll = ADPSGD_FUSED_UNROLL;      // float4 per thread, per row, per tile
-constexpr int64_t kTileVec = kThreads * kUnroll;  // 1024 float4 = 16 KiB of each row
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;                          // dwords per thread, per row, per tile
+constexpr int64_t kTileElems = kThreads * kUnroll;  // 1024 floats = 4 KiB of each row
 
 struct FusedParams {
     float* X;
     int64_t ld;
     int64_t d;
-    int64_t n_vec;      // ceil(d / 4)
     const PairOp* ops;
     const float* slots;
     uint16_t* Xbf16;
@@ -35,64 +33,88 @@ struct FusedParams {
     uint32_t key0, key1;
 };
 
+template <bool STREAM>
+__device__ __forceinline__ float load1(const float* p) {
+    return STREAM ? __builtin_nontemporal_load(p) : *p;
+}
+template <bool STREAM>
+__device__ __forceinline__ void store1(float* p, float v) {
+    if (STREAM) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
 // The three fp32 operations of the update keep their separate roundings: the
 // product gamma*g and the subtraction must not be contracted into an FMA.
-__device__ __forceinline__ void average_then_apply(v4f a, v4f b, v4f g, float gamma, v4f& new_i, v4f& new_j) {
+__device__ __forceinline__ void average_then_apply(float a, float b, float g, float gamma, float& new_i, float& new_j) {
 #pragma clang fp contract(off)
-    const v4f avg = (a + b) * 0.5f;
-    const v4f step = g * gamma;
+    const float avg = (a + b) * 0.5f;
+    const float step = g * gamma;
     new_j = avg;
     new_i = avg - step;
 }
 
-template <bool SYNTH, bool SHADOW, bool STREAM>
+// grid = (ceil(d / 1024), events of the round).  Pass u of thread t touches element
+// 1024 blockIdx.x + 256 u + t of both rows.
+// SOLO = the round contains an event without a partner (i == j: a worker with no neighbour takes a
+// plain SGD step); all other rounds run the variant without the per-store test (1.3 % faster).
+template <bool SYNTH, bool SHADOW, bool STREAM, bool SOLO>
 __global__ __launch_bounds__(kThreads) void fused_gossip_apply_kernel(const FusedParams p) {
-    const PairOp op = p.ops[blockIdx.y];   // uniform address: scalar loads
+    __shared__ __attribute__((aligned(16))) float zs[SYNTH ? kTileElems : 4];
+    const PairOp op = p.ops[blockIdx.y];   // uniform address: scalar loads, no LDS staging needed
     float* __restrict__ xi = p.X + static_cast<int64_t>(op.i) * p.ld;
     float* __restrict__ xj = p.X + static_cast<int64_t>(op.j) * p.ld;
     const float* __restrict__ gs = SYNTH ? nullptr : p.slots + static_cast<int64_t>(op.slot) * p.ld;
-    const bool pair = op.i != op.j;
-    const int64_t v0 = static_cast<int64_t>(blockIdx.x) * kTileVec + threadIdx.x;
+    const bool pair = !SOLO || op.i != op.j;
+    const int64_t tile = static_cast<int64_t>(blockIdx.x) * kTileElems;
+    const int64_t e0 = tile + threadIdx.x;
 
-    v4f a[kUnroll], b[kUnroll], g[kUnroll];
+    float a[kUnroll], b[kUnroll], g[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-        const int64_t v = v0 + static_cast<int64_t>(u) * kThreads;
-        if (v < p.n_vec) {
-            a[u] = load4<STREAM>(xi + 4 * v);
-            b[u] = load4<STREAM>(xj + 4 * v);
-            if (!SYNTH) g[u] = load4<STREAM>(gs + 4 * v);
+        const int64_t e = e0 + u * kThreads;
+        if (e < p.d) {     // (no default values: initialising a/b/g costs 3.5 % of the bandwidth)
+            a[u] = load1<STREAM>(xi + e);
+            b[u] = load1<STREAM>(xj + e);
+            if (!SYNTH) g[u] = load1<STREAM>(gs + e);
         }
+    }
+#ifdef ADPSGD_EXPERIMENT_NO_LDS
+    if (SYNTH) { for (int u = 0; u < kUnroll; ++u) g[u] = p.synth_std; } else
+#endif
+    if (SYNTH) {
+        // One generator call yields the gradient of 4 consecutive elements.  Lane c of wavefront w
+        // produces the c-th of the 64 quads that wavefront touches (quad c lies in pass c / 16) and
+        // parks it in LDS in element order, so that pass u of lane l finds its value at 64 u + l.
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int64_t eq = tile + (lane >> 4) * kThreads + 64 * wave + 4 * (lane & 15);
+        const int64_t q = eq >> 2;
+#ifdef ADPSGD_EXPERIMENT_NO_RNG
+        const v4f z = v4f{1.0f, 1.0f, 1.0f, 1.0f} * p.synth_std;
+#else
+        const v4f z = synth_normals4(static_cast<uint32_t>(q), static_cast<uint32_t>(q >> 32), op.k_lo, op.k_hi,
+                                     p.key0, p.key1) * p.synth_std;
+#endif
+        *reinterpret_cast<v4f*>(&zs[wave * 256 + 4 * lane]) = z;
+#ifdef ADPSGD_EXPERIMENT_WAVE_SYNC
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#else
+        __syncthreads();
+#endif
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) g[u] = zs[wave * 256 + 64 * u + lane];
     }
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-        const int64_t v = v0 + static_cast<int64_t>(u) * kThreads;
-        if (v >= p.n_vec) continue;
-        if (SYNTH) {
-#ifdef ADPSGD_EXPERIMENT_NO_RNG
-            g[u] = v4f{1.0f, 1.0f, 1.0f, 1.0f} * p.synth_std;
-#else
-            g[u] = synth_normals4(static_cast<uint32_t>(v), static_cast<uint32_t>(v >> 32), op.k_lo, op.k_hi,
-                                  p.key0, p.key1) * p.synth_std;
-#endif
-        }
-        if (4 * v + 4 > p.d) {   // ragged tail: entries at and beyond d stay zero
-            const int64_t e = 4 * v;
-            if (e + 1 >= p.d) g[u].y = 0.0f;
-            if (e + 2 >= p.d) g[u].z = 0.0f;
-            if (e + 3 >= p.d) g[u].w = 0.0f;
-        }
-        v4f ni, nj;
+        const int64_t e = e0 + u * kThreads;
+        if (e >= p.d) continue;            // entries at and beyond d are never touched: they stay zero
+        float ni, nj;
         average_then_apply(a[u], b[u], g[u], op.gamma, ni, nj);
-        store4<STREAM>(xi + 4 * v, ni);
-        if (pair) store4<STREAM>(xj + 4 * v, nj);
+        store1<STREAM>(xi + e, ni);
+        if (pair) store1<STREAM>(xj + e, nj);
         if (SHADOW) {
-            v4h hi = {bf16_rne(ni.x), bf16_rne(ni.y), bf16_rne(ni.z), bf16_rne(ni.w)};
-            *reinterpret_cast<v4h*>(p.Xbf16 + static_cast<int64_t>(op.i) * p.ld + 4 * v) = hi;
-            if (pair) {
-                v4h hj = {bf16_rne(nj.x), bf16_rne(nj.y), bf16_rne(nj.z), bf16_rne(nj.w)};
-                *reinterpret_cast<v4h*>(p.Xbf16 + static_cast<int64_t>(op.j) * p.ld + 4 * v) = hj;
-            }
+            p.Xbf16[static_cast<int64_t>(op.i) * p.ld + e] = bf16_rne(ni);
+            if (pair) p.Xbf16[static_cast<int64_t>(op.j) * p.ld + e] = bf16_rne(nj);
         }
     }
 }
@@ -107,11 +129,16 @@ __global__ __launch_bounds__(kThreads) void synth_gradient_kernel(float* out, in
         if (4 * v + t < d) out[4 * v + t] = gv[t];
 }
 
-template <bool SYNTH, bool SHADOW>
-hipError_t launch_variant(const FusedParams& p, dim3 grid, bool streaming, hipStream_t st) {
-    if (streaming) hipLaunchKernelGGL((fused_gossip_apply_kernel<SYNTH, SHADOW, true>), grid, dim3(kThreads), 0, st, p);
-    else hipLaunchKernelGGL((fused_gossip_apply_kernel<SYNTH, SHADOW, false>), grid, dim3(kThreads), 0, st, p);
+template <bool SYNTH, bool SHADOW, bool STREAM>
+hipError_t launch_solo(const FusedParams& p, dim3 grid, bool solo, hipStream_t st) {
+    if (solo) hipLaunchKernelGGL((fused_gossip_apply_kernel<SYNTH, SHADOW, STREAM, true>), grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((fused_gossip_apply_kernel<SYNTH, SHADOW, STREAM, false>), grid, dim3(kThreads), 0, st, p);
     return hipGetLastError();
+}
+template <bool SYNTH, bool SHADOW>
+hipError_t launch_variant(const FusedParams& p, dim3 grid, bool streaming, bool solo, hipStream_t st) {
+    if (streaming) return launch_solo<SYNTH, SHADOW, true>(p, grid, solo, st);
+    return launch_solo<SYNTH, SHADOW, false>(p, grid, solo, st);
 }
 
 }  // namespace
@@ -122,19 +149,18 @@ hipError_t launch_fused_gossip_apply(const FusedArgs& a, hipStream_t st) {
     p.X = a.X;
     p.ld = a.ld;
     p.d = a.d;
-    p.n_vec = (a.d + 3) / 4;
     p.ops = a.ops;
     p.slots = a.slots;
     p.Xbf16 = a.Xbf16;
     p.synth_std = a.synth_std;
     p.key0 = static_cast<uint32_t>(a.synth_seed);
     p.key1 = static_cast<uint32_t>(a.synth_seed >> 32);
-    const int64_t tiles = (p.n_vec + kTileVec - 1) / kTileVec;
+    const int64_t tiles = (p.d + kTileElems - 1) / kTileElems;
     if (tiles > 0x7FFFFFFF || a.n_ops > 65535) return hipErrorInvalidValue;
     const dim3 grid(static_cast<uint32_t>(tiles), static_cast<uint32_t>(a.n_ops));
-    if (a.synth) return launch_variant<true, false>(p, grid, a.streaming, st);
-    if (a.Xbf16) return launch_variant<false, true>(p, grid, a.streaming, st);
-    return launch_variant<false, false>(p, grid, a.streaming, st);
+    if (a.synth) return launch_variant<true, false>(p, grid, a.streaming, a.has_solo, st);
+    if (a.Xbf16) return launch_variant<false, true>(p, grid, a.streaming, a.has_solo, st);
+    return launch_variant<false, false>(p, grid, a.streaming, a.has_solo, st);
 }
 
 hipError_t launch_synth_gradient(uint64_t seed, uint64_t k, float std, int64_t d, float* out, hipStream_t st) {
