@@ -327,3 +327,56 @@ def test_config4_mlp_full_shape_short_run(P):
     assert rel_err(Xg, Xr) <= MLP_TOL_MASTER
     assert rel_err(bf16_bits_to_f32(Xb), oracle.round_bf16(Xr)) <= MLP_TOL_BF16
     assert np.allclose(lg, lr, rtol=5e-3, atol=5e-4)
+
+
+# ------------------------------------------------------------------ full shapes of configurations 2 and 5
+def _full_shape_linear(P, cfg_idx, K, sched_kw=None):
+    """Full n, d, rows, M of the configuration, data generated in GPU memory and copied to the host
+    for the oracle, first K events of the configuration's schedule."""
+    import torch
+    from workloads import linear_data_on_device
+    c = get_config(cfg_idx)
+    n, d, rows, M = c["n"], c["d"], c["rows"], c["M"]
+    g = ring_graph(n) if c["graph"] == "ring" else random_regular4_graph(n, c["seed"])
+    _say("config %d full shape: generating %.1f GB of data on the GPU" % (cfg_idx, n * rows * d * 4 / 1e9))
+    feats, targs = linear_data_on_device(c["model"], n, rows, d, seed=c["seed"])
+    sched = oracle.make_schedule(g, K, seed=c["seed"], T_max=c["T_max"], M=M, rows=[rows] * n, **(sched_kw or {}))
+    lib_sched = P.adpsgd_make_schedule(g, K, seed=c["seed"], T_max=c["T_max"], M=M, rows=[rows] * n, **(sched_kw or {}))
+    assert all(np.array_equal(sched[k], lib_sched[k]) for k in sched)
+    eng = P.Engine(g, d, c["model"], M=M, gamma=c["gamma"], lam=c["lam"], T_max=c["T_max"])
+    eng.load_data(feats, targs)
+    eng.set_models(np.zeros(d, np.float32))
+    _say("config %d full shape: %d events on the GPU" % (cfg_idx, K))
+    eng.run_events(lib_sched, want_loss=True)
+    Xg, lg = eng.get_models(), eng.get_loss()
+    st = eng.get_stats()
+    eng.close()
+    _say("config %d full shape: copying data to the host" % cfg_idx)
+    hf = [f.cpu().numpy() for f in feats]
+    ht = [t.cpu().numpy() for t in targs]
+    del feats, targs, eng
+    torch.cuda.empty_cache()
+    _say("config %d full shape: oracle" % cfg_idx)
+    Xr = np.zeros((n, d), np.float32)
+    r = oracle.run_events(Xr, sched, oracle.MODEL_LSQ if c["model"] == "lsq" else oracle.MODEL_LOGREG, c["gamma"],
+                          M=M, gscale=1.0 / M, lam=c["lam"], features=hf, targets=ht, mode=1, want_loss=True)
+    return Xg, Xr, lg, r["loss"], st, sched
+
+
+def test_config2_full_shape(P):
+    Xg, Xr, lg, lr, st, _ = _full_shape_linear(P, 2, 1200)
+    assert rel_err(Xg, Xr) <= TOL
+    assert np.allclose(lg, lr, rtol=2e-5, atol=1e-6)
+    assert st["rounds"] < 1200 // 4
+
+
+def test_config5_full_shape(P):
+    c = get_config(5)
+    slow = np.arange(c["n"]) < c["n_slow"]
+    kw = dict(tau_mode=1, weight=np.where(slow, c["weight_slow"], c["weight_fast"]),
+              tau_num=np.where(slow, c["tau_slow"][0], c["tau_fast"][0]),
+              tau_den=np.where(slow, c["tau_slow"][1], c["tau_fast"][1]))
+    Xg, Xr, lg, lr, st, sched = _full_shape_linear(P, 5, 400, kw)
+    assert sched["tau"].max() > 20
+    assert rel_err(Xg, Xr) <= TOL
+    assert np.allclose(lg, lr, rtol=2e-4, atol=1e-7)

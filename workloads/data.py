@@ -81,3 +81,25 @@ def mlp_init(din=784, hid=1024, out=10, seed=0):
     w2 = rng.standard_normal((hid, out)).astype(np.float32) / np.float32(np.sqrt(hid))
     return np.concatenate([w1.ravel(), np.zeros(hid, np.float32), w2.ravel(),
                            np.zeros(out, np.float32)]).astype(np.float32)
+
+
+def linear_data_on_device(model, n, rows, d, seed=0, noise=0.1, feature_var=None, device="cuda:0"):
+    """Large linear-model datasets generated directly in GPU memory (PyTorch's seeded device
+    generator), for the full-size configurations whose data (tens of GB) would take minutes to draw
+    on the host.  Same recipe as lsq_data / logreg_data: features ~ N(0, feature_var) (default 1/d),
+    one x* ~ N(0,1), targets A x* + noise N(0,1) (least squares) or their sign (logistic).
+    Returns per-worker lists of device tensors (features rows x d fp32, targets rows fp32)."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(1000003 * seed + 17)
+    var = (1.0 / d) if feature_var is None else feature_var
+    xstar = torch.randn(d, device=device, generator=gen)
+    feats, targs = [], []
+    for _ in range(n):
+        A = torch.randn((rows, d), device=device, generator=gen)
+        if var != 1.0:
+            A *= var ** 0.5
+        z = A @ xstar + noise * torch.randn(rows, device=device, generator=gen)
+        feats.append(A)
+        targs.append(z if model == "lsq" else torch.where(z >= 0, 1.0, -1.0).to(torch.float32))
+    return feats, targs
