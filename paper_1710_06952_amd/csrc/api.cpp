@@ -64,7 +64,6 @@ struct TableSet {
     bool in_flight = false;
 };
 
-constexpr int64_t kCacheBytes = 192ll << 20;   // gathered rows of a gradient group should stay cache resident
 constexpr int64_t kStreamingThreshold = 256ll << 20;
 constexpr int32_t kMaxSlots = 4096;
 
@@ -384,7 +383,7 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
         h->data_dirty = false;
     }
 
-    // ---- gradient groups: keep the gathered rows of a group cache resident ----
+    // ---- gradient groups ----
     int32_t group = 1;
     size_t off_coef = 0;
     if (with_grad) {
@@ -394,9 +393,9 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
             group = static_cast<int32_t>(std::min<int64_t>(std::max<int64_t>(max_r, 1), 64));
             HIP_TRY(h, h->grad_scratch.reserve(mlp_scratch_bytes(group, M, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out)));
         } else {
-            const int64_t op_bytes = static_cast<int64_t>(M) * h->d * 4;
-            group = static_cast<int32_t>(std::min<int64_t>(std::max<int64_t>(kCacheBytes / op_bytes, 1), std::max<int64_t>(max_r, 1)));
-            group = std::min(group, 65535);
+            // all gradients of a round go into one set of launches (measured: splitting a round so
+            // that the gathered rows stay within the memory-side cache only adds launches)
+            group = static_cast<int32_t>(std::min<int64_t>(std::max<int64_t>(max_r, 1), 65535));
             const size_t partial_bytes = static_cast<size_t>(group) * (M + 1) * linear_grad_chunks(h->d) * 4;
             off_coef = (partial_bytes + 255) & ~size_t(255);
             HIP_TRY(h, h->grad_scratch.reserve(off_coef + static_cast<size_t>(group) * M * 4));

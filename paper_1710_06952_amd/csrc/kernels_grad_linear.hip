@@ -99,35 +99,45 @@ __global__ __launch_bounds__(kThreads) void linear_dots_kernel(const LinParams p
     }
 }
 
-// Sum of the n_chunks partials of one dot product by a 16-lane group: lane t adds the
-// partials t, t + 16, ... in order, then the 16 lane sums are combined by a fixed butterfly.
-__device__ __forceinline__ float sum_chunks16(const float* __restrict__ part, int64_t n_chunks, int sub) {
+// Sum of the n_chunks partials of one dot product by a group of L lanes (L a power of two):
+// lane t adds the partials t, t + L, ... in order, 8 independent loads in flight, then the L lane
+// sums are combined by a fixed butterfly.
+__device__ __forceinline__ float sum_chunks(const float* __restrict__ part, int64_t n_chunks, int sub, int L) {
     float s = 0.0f;
-    for (int64_t c = sub; c < n_chunks; c += 16) s += part[c];
+    for (int64_t c0 = sub; c0 < n_chunks; c0 += 8 * L) {
+        float vbuf[8];
 #pragma unroll
-    for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+        for (int t = 0; t < 8; ++t) {
+            const int64_t c = c0 + static_cast<int64_t>(t) * L;
+            vbuf[t] = c < n_chunks ? part[c] : 0.0f;
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) s += vbuf[t];
+    }
+    for (int off = L >> 1; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
     return s;
 }
 
-// grid = n_ops; 16 lanes per minibatch sample, 16 samples per pass of the block
-__global__ __launch_bounds__(kThreads) void linear_finalize_kernel(const LinParams p) {
+// grid = n_ops; L = lanes_per_row lanes per minibatch sample (host: largest power of two with
+// L * M <= 256, at most 64), so that M <= 256 is finished in one pass of the block
+__global__ __launch_bounds__(kThreads) void linear_finalize_kernel(const LinParams p, const int L) {
     __shared__ float red[kWaves];
     const GradOp op = p.ops[blockIdx.x];
     const WorkerDataDev wd = p.data[op.worker];
     const float* __restrict__ tg = static_cast<const float*>(wd.targets);
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const float* __restrict__ part = p.partial + static_cast<int64_t>(blockIdx.x) * (p.M + 1) * p.n_chunks;
-    const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int sub = threadIdx.x & (L - 1), grp = threadIdx.x / L, groups = kThreads / L;
     float reg_loss = 0.0f;
     if (p.model == ADPSGD_MODEL_LOGREG)
-        reg_loss = 0.5f * p.lambda * sum_chunks16(part + static_cast<int64_t>(p.M) * p.n_chunks, p.n_chunks, sub);
+        reg_loss = 0.5f * p.lambda * sum_chunks(part + static_cast<int64_t>(p.M) * p.n_chunks, p.n_chunks, sub, L);
     float loss = 0.0f;
-    for (int m0 = 0; m0 < p.M; m0 += kThreads / 16) {     // uniform trip count: shuffles stay converged
+    for (int m0 = 0; m0 < p.M; m0 += groups) {     // uniform trip count: shuffles stay converged
         const int m = m0 + grp;
         const bool live = m < p.M;
-        const float z = sum_chunks16(part + static_cast<int64_t>(live ? m : 0) * p.n_chunks, p.n_chunks, sub);
+        const float t = live ? tg[idx[m]] : 0.0f;   // issued before the partial sums are waited for
+        const float z = sum_chunks(part + static_cast<int64_t>(live ? m : 0) * p.n_chunks, p.n_chunks, sub, L);
         if (live && sub == 0) {
-            const float t = tg[idx[m]];
             float c_m;
             if (p.model == ADPSGD_MODEL_LSQ) {
                 const float r = z - t;              // a.x - b
@@ -206,7 +216,9 @@ hipError_t launch_linear_gradient(const LinearGradArgs& a, hipStream_t st, int* 
                        0, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(linear_finalize_kernel, dim3(a.n_ops), dim3(kThreads), 0, st, p);
+    int lanes_per_row = 64;
+    while (lanes_per_row > 1 && lanes_per_row * a.M > kThreads) lanes_per_row >>= 1;
+    hipLaunchKernelGGL(linear_finalize_kernel, dim3(a.n_ops), dim3(kThreads), 0, st, p, lanes_per_row);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(linear_combine_kernel, dim3(static_cast<uint32_t>(out_blocks), a.n_ops), dim3(kThreads), 0, st, p);
