@@ -20,9 +20,21 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr int kDotUnroll = 4;                                // float4 per thread per row
-constexpr int64_t kDotChunk = kThreads * kDotUnroll * 4;     // 4096 floats of d per block
-constexpr int kRowsPerBlock = 8;                             // minibatch rows per dots block
+#ifndef ADPSGD_DOT_UNROLL
+#define ADPSGD_DOT_UNROLL 4
+#endif
+#ifndef ADPSGD_DOT_ROWS
+#define ADPSGD_DOT_ROWS 8
+#endif
+#ifndef ADPSGD_DOT_ROWUNROLL
+#define ADPSGD_DOT_ROWUNROLL 2
+#endif
+#ifndef ADPSGD_COMBINE_UNROLL
+#define ADPSGD_COMBINE_UNROLL 8
+#endif
+constexpr int kDotUnroll = ADPSGD_DOT_UNROLL;                // float4 per thread per row
+constexpr int64_t kDotChunk = kThreads * kDotUnroll * 4;     // floats of d per block
+constexpr int kRowsPerBlock = ADPSGD_DOT_ROWS;               // minibatch rows per dots block
 
 struct LinParams {
     int model;
@@ -55,6 +67,9 @@ __device__ __forceinline__ v4f zero_beyond(v4f v, int64_t e, int64_t d) {
 __device__ __forceinline__ float dot4(v4f a, v4f b) { return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w; }
 
 // grid = (n_chunks, ceil((M+1) / kRowsPerBlock), n_ops); "row" M is x^ itself (|x^|^2 for the regulariser)
+// STREAM: the gathered rows exceed the L2 (they are read once per kernel): non-temporal loads,
+// 7.0 instead of 6.2 TB/s on a read-only stream.
+template <bool STREAM>
 __global__ __launch_bounds__(kThreads) void linear_dots_kernel(const LinParams p) {
     __shared__ float red[kWaves][kRowsPerBlock];
     const GradOp op = p.ops[blockIdx.z];
@@ -72,7 +87,7 @@ __global__ __launch_bounds__(kThreads) void linear_dots_kernel(const LinParams p
         xh[u] = v < p.n_vec ? zero_beyond(*reinterpret_cast<const v4f*>(xrow + 4 * v), 4 * v, p.d) : v4f{0, 0, 0, 0};
     }
     const int m_begin = blockIdx.y * kRowsPerBlock;
-#pragma unroll 2
+#pragma unroll ADPSGD_DOT_ROWUNROLL
     for (int r = 0; r < kRowsPerBlock; ++r) {
         const int m = m_begin + r;
         if (m > p.M) break;
@@ -82,7 +97,7 @@ __global__ __launch_bounds__(kThreads) void linear_dots_kernel(const LinParams p
 #pragma unroll
         for (int u = 0; u < kDotUnroll; ++u) {
             const int64_t v = v0 + static_cast<int64_t>(u) * kThreads;
-            if (v < p.n_vec) acc += dot4(zero_beyond(*reinterpret_cast<const v4f*>(row + 4 * v), 4 * v, p.d), xh[u]);
+            if (v < p.n_vec) acc += dot4(zero_beyond(load4<STREAM>(row + 4 * v), 4 * v, p.d), xh[u]);
         }
         acc = wave_sum(acc);
         if (lane == 0) red[wave][r] = acc;
@@ -163,6 +178,7 @@ __global__ __launch_bounds__(kThreads) void linear_finalize_kernel(const LinPara
 }
 
 // grid = (ceil(n_vec / kThreads), n_ops)
+template <bool STREAM>
 __global__ __launch_bounds__(kThreads) void linear_combine_kernel(const LinParams p) {
     const GradOp op = p.ops[blockIdx.y];
     const int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
@@ -172,9 +188,9 @@ __global__ __launch_bounds__(kThreads) void linear_combine_kernel(const LinParam
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const float* __restrict__ cf = p.coef + static_cast<int64_t>(blockIdx.y) * p.M;
     v4f acc = {0, 0, 0, 0};
-#pragma unroll 8
+#pragma unroll ADPSGD_COMBINE_UNROLL
     for (int m = 0; m < p.M; ++m) {
-        const v4f a = *reinterpret_cast<const v4f*>(A + static_cast<int64_t>(idx[m]) * wd.ld + 4 * v);
+        const v4f a = load4<STREAM>(A + static_cast<int64_t>(idx[m]) * wd.ld + 4 * v);
         acc += a * cf[m];
     }
     if (p.model == ADPSGD_MODEL_LOGREG) {
@@ -212,8 +228,10 @@ hipError_t launch_linear_gradient(const LinearGradArgs& a, hipStream_t st, int* 
     if (p.n_chunks > 0x7FFFFFFF || out_blocks > 0x7FFFFFFF || a.n_ops > 65535) return hipErrorInvalidValue;
     const uint32_t row_groups = static_cast<uint32_t>((a.M + 1 + kRowsPerBlock - 1) / kRowsPerBlock);
     if (row_groups > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(linear_dots_kernel, dim3(static_cast<uint32_t>(p.n_chunks), row_groups, a.n_ops), dim3(kThreads),
-                       0, st, p);
+    const bool stream_rows = static_cast<int64_t>(a.M) * a.d * 4 > (8ll << 20);
+    const dim3 dots_grid(static_cast<uint32_t>(p.n_chunks), row_groups, a.n_ops);
+    if (stream_rows) hipLaunchKernelGGL(linear_dots_kernel<true>, dots_grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL(linear_dots_kernel<false>, dots_grid, dim3(kThreads), 0, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     int lanes_per_row = 64;
@@ -221,7 +239,9 @@ hipError_t launch_linear_gradient(const LinearGradArgs& a, hipStream_t st, int* 
     hipLaunchKernelGGL(linear_finalize_kernel, dim3(a.n_ops), dim3(kThreads), 0, st, p, lanes_per_row);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(linear_combine_kernel, dim3(static_cast<uint32_t>(out_blocks), a.n_ops), dim3(kThreads), 0, st, p);
+    const dim3 comb_grid(static_cast<uint32_t>(out_blocks), a.n_ops);
+    if (stream_rows) hipLaunchKernelGGL(linear_combine_kernel<true>, comb_grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL(linear_combine_kernel<false>, comb_grid, dim3(kThreads), 0, st, p);
     if (n_launches) *n_launches += 3;
     return hipGetLastError();
 }
