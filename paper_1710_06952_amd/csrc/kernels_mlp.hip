@@ -40,6 +40,7 @@ struct MlpParams {
     uint16_t* Hb;    // [op][kMaxM][hid]  relu output, bf16
     uint16_t* dHb;   // [op][kMaxM][hid]  error at the hidden pre-activation, bf16, rows >= M zero
     float* dlogit;   // [op][kMaxM][kMaxOut]  softmax - onehot
+    float* logit_part;  // [op][hid / 32][kMaxM][kMaxOut]  second-layer products of one forward tile
     float* loss_m;   // [op][kMaxM]
 };
 
@@ -66,6 +67,7 @@ struct FwdOperands {
 
 __global__ __launch_bounds__(kT) void mlp_forward_kernel(const MlpParams p) {
     __shared__ __attribute__((aligned(16))) unsigned char smem[16384];
+    __shared__ float W2s[kFwdTileH][kMaxOut];     // this tile's rows of W2, zero beyond `out`
     const GradOp op = p.ops[blockIdx.y];
     const WorkerDataDev wd = p.data[op.worker];
     const uint16_t* __restrict__ feat = static_cast<const uint16_t*>(wd.features);
@@ -73,6 +75,13 @@ __global__ __launch_bounds__(kT) void mlp_forward_kernel(const MlpParams p) {
     const uint16_t* __restrict__ W1 = p.Xb + static_cast<int64_t>(op.worker) * p.ld;
     const uint16_t* __restrict__ b1 = W1 + static_cast<int64_t>(p.in) * p.hid;
     const int h0 = blockIdx.x * kFwdTileH;
+    {
+        const uint16_t* __restrict__ W2 = b1 + p.hid;
+        for (int t = threadIdx.x; t < kFwdTileH * kMaxOut; t += kT) {
+            const int hh = t / kMaxOut, o = t % kMaxOut;
+            W2s[hh][o] = o < p.out ? bf16_to_float(W2[static_cast<int64_t>(h0 + hh) * p.out + o]) : 0.0f;
+        }
+    }
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int li = lane & 15, kb = 8 * (lane >> 4);
     uint16_t(*Bt)[40] = reinterpret_cast<uint16_t(*)[40]>(smem + wave * (kFwdTileH * 40 * 2));   // [h][k]
@@ -148,6 +157,7 @@ __global__ __launch_bounds__(kT) void mlp_forward_kernel(const MlpParams p) {
     __syncthreads();
     if (wave == 1) spill(0);
     __syncthreads();
+    float(*Hs)[kFwdTileH + 1] = reinterpret_cast<float(*)[kFwdTileH + 1]>(smem);   // the finished tile, as the next layer sees it
     if (wave == 0) {
         absorb(0);
 #pragma unroll
@@ -159,54 +169,83 @@ __global__ __launch_bounds__(kT) void mlp_forward_kernel(const MlpParams p) {
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const int m = 16 * mt + 4 * (lane >> 4) + v;
+                    float hval = 0.0f;
                     if (m < p.M) {
                         const float pre = acc[mt][ht][v] + bias;
-                        p.Hb[(static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h] = bf16_rne(pre > 0.0f ? pre : 0.0f);
+                        const uint16_t hb = bf16_rne(pre > 0.0f ? pre : 0.0f);
+                        p.Hb[(static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h] = hb;
+                        hval = bf16_to_float(hb);
                     }
+                    Hs[m][16 * ht + li] = hval;
                 }
         }
     }
+    __syncthreads();
+    // this tile's share of the logits: thread (m, oq) sums over the 32 hidden units in order
+    {
+        const int m = threadIdx.x >> 2, oq = threadIdx.x & 3;
+        float part[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 8
+        for (int hh = 0; hh < kFwdTileH; ++hh) {
+            const float hv = Hs[m][hh];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) part[q] += hv * W2s[hh][oq + 4 * q];
+        }
+        float* __restrict__ dst = p.logit_part + ((static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * kMaxM + m) * kMaxOut;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) dst[oq + 4 * q] = part[q];
+    }
 }
 
-// ---- 2. logits, softmax, loss: grid = (M, n_ops), one block per sample ----------------
+// ---- 2. logits, softmax, loss: grid = n_ops, one block per gradient --------------------
+// Thread (m, oq) adds the hid / 32 tile contributions of logits oq, oq + 4, oq + 8, oq + 12 of sample
+// m in tile order; one thread per sample then does the softmax.
 __global__ __launch_bounds__(kT) void mlp_softmax_kernel(const MlpParams p) {
-    __shared__ float red[kT / 64][kMaxOut];
-    const GradOp op = p.ops[blockIdx.y];
+    __shared__ float logit_s[kMaxM][kMaxOut + 1];
+    const GradOp op = p.ops[blockIdx.x];
     const WorkerDataDev wd = p.data[op.worker];
-    const int m = blockIdx.x;
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const uint16_t* __restrict__ W = p.Xb + static_cast<int64_t>(op.worker) * p.ld;
-    const uint16_t* __restrict__ W2 = W + static_cast<int64_t>(p.in) * p.hid + p.hid;
-    const uint16_t* __restrict__ b2 = W2 + static_cast<int64_t>(p.hid) * p.out;
-    const uint16_t* __restrict__ hrow = p.Hb + (static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid;
-    float acc[kMaxOut];
+    const uint16_t* __restrict__ b2 = W + static_cast<int64_t>(p.in) * p.hid + p.hid + static_cast<int64_t>(p.hid) * p.out;
+    const int tiles = p.hid / kFwdTileH;
+    {
+        const int m = threadIdx.x >> 2, oq = threadIdx.x & 3;
+        const float* __restrict__ src = p.logit_part + (static_cast<int64_t>(blockIdx.x) * tiles * kMaxM + m) * kMaxOut + oq;
+        float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int t0 = 0; t0 < tiles; t0 += 8) {
+            float buf[8][4];
 #pragma unroll
-    for (int o = 0; o < kMaxOut; ++o) acc[o] = 0.0f;
-    for (int h = threadIdx.x; h < p.hid; h += kT) {
-        const float hv = bf16_to_float(hrow[h]);
+            for (int t = 0; t < 8; ++t)
 #pragma unroll
-        for (int o = 0; o < kMaxOut; ++o)
-            if (o < p.out) acc[o] += hv * bf16_to_float(W2[static_cast<int64_t>(h) * p.out + o]);
-    }
+                for (int q = 0; q < 4; ++q)
+                    buf[t][q] = (t0 + t < tiles) ? src[static_cast<int64_t>(t0 + t) * kMaxM * kMaxOut + 4 * q] : 0.0f;
 #pragma unroll
-    for (int o = 0; o < kMaxOut; ++o) {
-        const float s = wave_sum(acc[o]);
-        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6][o] = s;
+            for (int t = 0; t < 8; ++t)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[q] += buf[t][q];
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) logit_s[m][oq + 4 * q] = acc[q];
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (threadIdx.x < p.M) {
+        const int m = threadIdx.x;
         float logit[kMaxOut];
         float zmax = -INFINITY;
         for (int o = 0; o < p.out; ++o) {
-            logit[o] = ((red[0][o] + red[1][o]) + (red[2][o] + red[3][o])) + bf16_to_float(b2[o]);
+            logit[o] = logit_s[m][o] + bf16_to_float(b2[o]);
             zmax = fmaxf(zmax, logit[o]);
         }
         float zsum = 0.0f;
         for (int o = 0; o < p.out; ++o) zsum += expf(logit[o] - zmax);
         const int label = static_cast<const int32_t*>(wd.targets)[idx[m]];
-        float* dl = p.dlogit + (static_cast<int64_t>(blockIdx.y) * kMaxM + m) * kMaxOut;
-        for (int o = 0; o < p.out; ++o) dl[o] = expf(logit[o] - zmax) / zsum - (o == label ? 1.0f : 0.0f);
-        p.loss_m[static_cast<int64_t>(blockIdx.y) * kMaxM + m] = -(logit[label] - zmax - logf(zsum));
+        float* dl = p.dlogit + (static_cast<int64_t>(blockIdx.x) * kMaxM + m) * kMaxOut;
+        float lsel = 0.0f;
+        for (int o = 0; o < p.out; ++o) {
+            dl[o] = expf(logit[o] - zmax) / zsum - (o == label ? 1.0f : 0.0f);
+            if (o == label) lsel = logit[o];
+        }
+        p.loss_m[static_cast<int64_t>(blockIdx.x) * kMaxM + m] = -(lsel - zmax - logf(zsum));
     }
 }
 
@@ -238,13 +277,19 @@ __global__ __launch_bounds__(kT) void mlp_backward_small_kernel(const MlpParams 
         gw2[o] = 0.0f;
     }
     float sum_dh = 0.0f;
-#pragma unroll 4
+    uint16_t hraw[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {      // all 16 activations of this thread in flight at once
+        const int m = 16 * mg + r;
+        hraw[r] = m < p.M ? p.Hb[(static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h] : static_cast<uint16_t>(0);
+    }
+#pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int m = 16 * mg + r;
         const int64_t at = (static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h;
         uint16_t dh = 0;
         if (m < p.M) {
-            const float hv = bf16_to_float(p.Hb[at]);
+            const float hv = bf16_to_float(hraw[r]);
             float back = 0.0f;
 #pragma unroll
             for (int o = 0; o < kMaxOut; ++o) {     // entries o >= out are zero in dl_s and w2
@@ -339,7 +384,8 @@ size_t mlp_scratch_bytes(int32_t n_ops, int32_t M, int32_t in, int32_t hid, int3
     if (n_ops < 1 || M < 1 || M > kMaxM || in < 8 || (in & 7) || hid < kTileH || (hid % kTileH) || out < 1 || out > kMaxOut)
         return 0;
     const size_t act = align256(static_cast<size_t>(n_ops) * kMaxM * hid * sizeof(uint16_t));
-    return 2 * act + align256(static_cast<size_t>(n_ops) * kMaxM * kMaxOut * 4) + align256(static_cast<size_t>(n_ops) * kMaxM * 4);
+    const size_t lp = align256(static_cast<size_t>(n_ops) * (hid / kFwdTileH) * kMaxM * kMaxOut * 4);
+    return 2 * act + align256(static_cast<size_t>(n_ops) * kMaxM * kMaxOut * 4) + align256(static_cast<size_t>(n_ops) * kMaxM * 4) + lp;
 }
 
 hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_launches) {
@@ -364,11 +410,13 @@ hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_laun
     p.dHb = reinterpret_cast<uint16_t*>(s + act);
     p.dlogit = reinterpret_cast<float*>(s + 2 * act);
     p.loss_m = reinterpret_cast<float*>(s + 2 * act + align256(static_cast<size_t>(a.n_ops) * kMaxM * kMaxOut * 4));
+    p.logit_part = reinterpret_cast<float*>(s + 2 * act + align256(static_cast<size_t>(a.n_ops) * kMaxM * kMaxOut * 4) +
+                                            align256(static_cast<size_t>(a.n_ops) * kMaxM * 4));
     const uint32_t hb = static_cast<uint32_t>(a.hid / kTileH);
     hipLaunchKernelGGL(mlp_forward_kernel, dim3(a.hid / kFwdTileH, a.n_ops), dim3(kT), 0, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(mlp_softmax_kernel, dim3(a.M, a.n_ops), dim3(kT), 0, st, p);
+    hipLaunchKernelGGL(mlp_softmax_kernel, dim3(a.n_ops), dim3(kT), 0, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(mlp_backward_small_kernel, dim3(a.hid / 64, a.n_ops), dim3(kT), 0, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
