@@ -1,16 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the AD-PSGD per-event worker update on one MI355X.
 
-A step is one adpsgd_run_events call on a slice of the seeded event schedule of
-the headline configuration (n = 128 workers on a ring, d = 25.6 M fp32
-parameters per replica, synthetic N(0, 1e-3) gradients, tau ~ U{0..16}); the
-default 10 steps x 10 000 events are exactly that configuration's 100 000
-events.  Inputs (the 13.1 GB model matrix) are resident in HBM before the timed
-region; the schedule slices are generated on the host beforehand.
+Default (the headline): configuration 3 -- n = 128 workers on a ring, d = 25.6 M fp32
+parameters per replica, synthetic N(0, 1e-3) gradients, tau ~ U{0..16}.  A step is one
+adpsgd_run_events call on a slice of the seeded event schedule; the default 10 steps x
+10 000 events are exactly that configuration's 100 000 events.  Inputs (the 13.1 GB
+model matrix) are resident in HBM before the timed region; the schedule slices are
+generated on the host beforehand.
 
-Prints ONE JSON line: worker updates/s, plus the HBM roofline of the fused
-gossip-average + apply kernel (algorithmic bytes = 16 B per parameter per event:
-read and write the two averaged rows) and the CPU oracle timed on this host.
+Prints ONE JSON line: worker updates/s, plus the HBM roofline of the dominant kernel
+(config 3: fused gossip-average + apply, algorithmic bytes = 16 B per parameter per
+event: read and write the two averaged rows) and the CPU oracle timed on this host.
+
+``--config 1|2|4|5`` times the other configurations the same way (data generated in GPU
+memory; a step is a tenth of the configuration's events); those lines are context for the
+gradient kernels, not the headline.
 """
 from __future__ import annotations
 
@@ -40,7 +44,7 @@ def traffic_from_profiles():
         return None
 
 
-def cpu_baseline(cfg, graph, schedule, events):
+def cpu_baseline_synth(cfg, schedule, events):
     """The serial oracle, as it stands, on the first `events` events at full d (one host thread)."""
     import oracle
     sub = {k: (v[:events] if v is not None else None) for k, v in schedule.items()}
@@ -54,13 +58,59 @@ def cpu_baseline(cfg, graph, schedule, events):
                       % (events, cfg["n"], cfg["d"], dt)}
 
 
+def cpu_baseline_data(cfg, schedule, events, feats, targs, x0):
+    """Oracle on the first `events` events of a data configuration (data copied to the host)."""
+    import oracle
+    import torch
+    model = {"lsq": oracle.MODEL_LSQ, "logreg": oracle.MODEL_LOGREG, "mlp": oracle.MODEL_MLP}[cfg["model"]]
+    if cfg["model"] == "mlp":
+        din = cfg["mlp"][0]
+        hf = [np.ascontiguousarray(f[:, :din].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)) for f in feats]
+    else:
+        hf = [f.cpu().numpy() for f in feats]
+    ht = [t.cpu().numpy() for t in targs]
+    sub = {k: (v[:events] if v is not None else None) for k, v in schedule.items()}
+    X = np.tile(x0, (cfg["n"], 1))
+    t0 = time.perf_counter()
+    oracle.run_events(X, sub, model, cfg["gamma"], M=cfg["M"], gscale=1.0 / cfg["M"], lam=cfg["lam"],
+                      mlp=cfg.get("mlp", (0, 0, 0)), features=hf, targets=ht, mode=1)
+    dt = time.perf_counter() - t0
+    return {"value": events / dt, "unit": "worker updates/s", "cores": 1, "kind": "oracle",
+            "sample": "first %d events of the same schedule at full size, %.1f s" % (events, dt)}
+
+
+def schedule_kwargs(cfg):
+    n = cfg["n"]
+    kw = dict(seed=cfg["seed"], T_max=cfg["T_max"], M=cfg["M"], rows=[max(cfg["rows"], 1)] * n)
+    if cfg["tau_mode"] == "geometric":
+        slow = np.arange(n) < cfg["n_slow"]
+        kw.update(tau_mode=1, weight=np.where(slow, cfg["weight_slow"], cfg["weight_fast"]),
+                  tau_num=np.where(slow, cfg["tau_slow"][0], cfg["tau_fast"][0]),
+                  tau_den=np.where(slow, cfg["tau_slow"][1], cfg["tau_fast"][1]))
+    return kw
+
+
+def algorithmic_bytes_per_event(cfg):
+    """The method's own traffic per event: rows of both replicas read and written (16 B per
+    parameter), plus for the data models the gradient written and read once (8 B), the stale
+    model read (4 B, or 2 B of bf16 shadow plus two bf16 shadow writes) and the minibatch rows read once."""
+    d = cfg["d"]
+    if cfg["model"] == "synth":
+        return 16.0 * d
+    if cfg["model"] == "mlp":
+        return 16.0 * d + 8.0 * d + 2.0 * d + 4.0 * d + cfg["M"] * cfg["mlp"][0] * 2.0
+    return 16.0 * d + 8.0 * d + 4.0 * d + 4.0 * cfg["M"] * d
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--events-per-step", type=int, default=10000)
-    ap.add_argument("--cpu-events", type=int, default=16, help="events the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--events-per-step", type=int, default=0, help="default: a tenth of the configuration's events")
+    ap.add_argument("--cpu-events", type=int, default=-1,
+                    help="events the CPU oracle is timed on (0 = skip; default 16 for config 3, 0 otherwise)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
     ap.add_argument("--d", type=int, default=0, help="override d (debugging only; the result is then not the headline)")
@@ -71,22 +121,38 @@ def main():
 
     import torch
     import paper_1710_06952_amd as P
-    from workloads import get_config, ring_graph
+    from workloads import (get_config, ring_graph, random_regular4_graph, linear_data_on_device,
+                           mixture_data_on_device, mlp_init)
 
-    cfg = get_config(3)
+    cfg = get_config(args.config)
     if args.d:
         cfg["d"] = args.d
-    n, d = cfg["n"], cfg["d"]
-    graph = ring_graph(n)
-    std = float(np.float32(cfg["synth_std"]))
-    E = args.events_per_step
+    n, d, M = cfg["n"], cfg["d"], cfg["M"]
+    graph = ring_graph(n) if cfg["graph"] == "ring" else random_regular4_graph(n, cfg["seed"])
+    E = args.events_per_step or max(cfg["K"] // 10, 1)
+    cpu_events = args.cpu_events if args.cpu_events >= 0 else (16 if args.config == 3 else 0)
+    synth = cfg["model"] == "synth"
+    std = float(np.float32(cfg.get("synth_std", 0.0)))
 
-    eng = P.Engine(graph, d, "synth", gamma=cfg["gamma"], T_max=cfg["T_max"], synth_std=std, synth_seed=cfg["seed"])
-    eng.set_models(np.zeros(d, np.float32))
-    scheds = [P.adpsgd_make_schedule(graph, E, seed=cfg["seed"], k_begin=s * E, T_max=cfg["T_max"])
-              for s in range(args.warmup + args.steps)]
+    feats = targs = None
+    x0 = np.zeros(d, np.float32)
+    if synth:
+        eng = P.Engine(graph, d, "synth", gamma=cfg["gamma"], T_max=cfg["T_max"], synth_std=std, synth_seed=cfg["seed"])
+    elif cfg["model"] == "mlp":
+        feats, targs = mixture_data_on_device(n, cfg["rows"], din=cfg["mlp"][0], classes=cfg["mlp"][2], seed=cfg["seed"])
+        x0 = mlp_init(*cfg["mlp"], seed=cfg["seed"])
+        eng = P.Engine(graph, d, "mlp", M=M, gamma=cfg["gamma"], T_max=cfg["T_max"], mlp=cfg["mlp"])
+    else:
+        feats, targs = linear_data_on_device(cfg["model"], n, cfg["rows"], d, seed=cfg["seed"],
+                                             feature_var=cfg.get("feature_var"))
+        eng = P.Engine(graph, d, cfg["model"], M=M, gamma=cfg["gamma"], lam=cfg["lam"], T_max=cfg["T_max"])
+    if feats is not None:
+        eng.load_data(feats, targs)
+    eng.set_models(x0)
+    kw = schedule_kwargs(cfg)
+    scheds = [P.adpsgd_make_schedule(graph, E, k_begin=s * E, **kw) for s in range(args.warmup + args.steps)]
 
-    if args.calibrate_copy:        # 2^28 floats read + 2^28 floats written by an elementwise copy kernel
+    if args.calibrate_copy:        # 2^28 floats read + 2^28 floats written by a plain device copy
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
         dst = torch.empty_like(src)
         dst.copy_(src)
@@ -110,28 +176,48 @@ def main():
     events = st1["events"] - st0["events"]
     launches = st1["fused_launches"] - st0["fused_launches"]
 
-    # dominant kernel: per-launch duration from HIP events around every launch (second handle on
-    # the same buffers with per-launch timing enabled, two steps of the same schedule)
-    prof = P.Handle(graph, d, model=P.MODEL_SYNTH, X_ptr=eng.X.data_ptr(), ldx=eng.ld, gamma=cfg["gamma"],
-                    T_max=cfg["T_max"], synth_std=std, synth_seed=cfg["seed"],
+    # per-launch durations from HIP events around every launch: a second handle on the same
+    # buffers with per-launch timing enabled, two steps of the same schedule
+    prof = P.Handle(graph, d, model=eng.model, X_ptr=eng.X.data_ptr(), ldx=eng.ld, M=M, gamma=cfg["gamma"],
+                    lam=cfg["lam"], T_max=cfg["T_max"], synth_std=std, synth_seed=cfg["seed"],
+                    mlp=cfg.get("mlp", (0, 0, 0)), Xbf16_ptr=None if eng.Xbf16 is None else eng.Xbf16.data_ptr(),
+                    workspace_ptr=None if eng.workspace is None else eng.workspace.data_ptr(),
+                    workspace_bytes=0 if eng.workspace is None else eng.workspace.numel() * 4,
                     stream=torch.cuda.current_stream().cuda_stream, flags=P.FLAG_PROFILE)
+    if feats is not None:
+        for i, (f, t) in enumerate(eng._data):
+            prof.load_data(i, f.data_ptr(), f.shape[0], f.stride(0), t.data_ptr())
     n_prof = min(2, len(scheds))
     for s in range(n_prof):
         prof.run_events(scheds[s])
     ps = prof.get_stats()
     prof.destroy()
-    bytes_per_event = 16.0 * d                          # read x_i, x_j; write x_i, x_j (fp32)
+
     events_per_launch = ps["events"] / ps["fused_launches"]
-    avg_launch_s = ps["fused_ms"] * 1e-3 / ps["fused_launches"]
-    achieved = bytes_per_event * events_per_launch / avg_launch_s / 1e9
-    traffic = traffic_from_profiles()          # measured bytes per event (rocprofv3 counters) ...
-    if traffic is not None and d == 25_600_000:
-        traffic *= events_per_launch           # ... per launch, like `achieved`
+    if synth:
+        bytes_per_event = 16.0 * d                      # read x_i, x_j; write x_i, x_j (fp32)
+        avg_launch_s = ps["fused_ms"] * 1e-3 / ps["fused_launches"]
+        achieved = bytes_per_event * events_per_launch / avg_launch_s / 1e9
+        traffic = traffic_from_profiles()               # measured bytes per event (rocprofv3 counters) ...
+        traffic = traffic * events_per_launch if (traffic is not None and d == 25_600_000) else None   # ... per launch
+        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                "kernel": "fused_gossip_apply_kernel<synth>", "avg_launch_ms": avg_launch_s * 1e3,
+                "events_per_launch": events_per_launch, "bytes_per_event": bytes_per_event}
     else:
-        traffic = None
+        # dominant kernels: the gradient launch set (the minibatch rows are the bulk of the traffic)
+        grad_rows_bytes = (M * cfg["mlp"][0] * 2.0 + 2.0 * d) if cfg["model"] == "mlp" else 4.0 * M * d
+        per_grad_s = ps["grad_ms"] * 1e-3 / ps["events"]
+        achieved = grad_rows_bytes / per_grad_s / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "kernel": "gradient launch set (per gradient)", "avg_gradient_us": per_grad_s * 1e6,
+                "fused_us_per_event": ps["fused_ms"] * 1e3 / ps["events"],
+                "bytes_per_gradient": grad_rows_bytes, "events_per_launch": events_per_launch}
 
     out = {
-        "metric": "worker updates/sec and gossip+update HBM GB/s (% of peak) at n=128, d=25.6M",
+        "metric": "worker updates/sec and gossip+update HBM GB/s (% of peak) at n=128, d=25.6M" if args.config == 3
+                  else "worker updates/sec (configuration %d)" % args.config,
         "value": events / elapsed,
         "unit": "worker updates/s",
         "n_gpus": 1,
@@ -141,23 +227,28 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "bf16" if cfg["model"] == "mlp" else "f32",
         "data": "synthetic",
-        "config": {"workload": cfg["name"], "n": n, "d": d, "graph": "ring", "events_per_step": E,
-                   "events": events, "tau": "U{0..%d}" % cfg["T_max"], "gamma": cfg["gamma"],
-                   "gradient": "N(0,1e-3) Philox4x32-10 + Box-Muller, generated in registers",
+        "config": {"workload": cfg["name"], "n": n, "d": d, "graph": cfg["graph"], "events_per_step": E,
+                   "events": events, "M": M, "gamma": cfg["gamma"], "T_max": cfg["T_max"],
                    "rounds": st1["rounds"] - st0["rounds"], "fused_launches": launches,
-                   "algorithmic_GBs_whole_run": bytes_per_event * events / elapsed / 1e9},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "fused_gossip_apply_kernel<synth>", "avg_launch_ms": avg_launch_s * 1e3,
-                     "events_per_launch": events_per_launch, "bytes_per_event": bytes_per_event},
+                   "grad_launches": st1["grad_launches"] - st0["grad_launches"],
+                   "algorithmic_GBs_whole_run": algorithmic_bytes_per_event(cfg) * events / elapsed / 1e9},
+        "roofline": roof,
     }
-    eng.close()
-    del eng
-    torch.cuda.empty_cache()
-    if args.cpu_events > 0:
-        out["cpu_baseline"] = cpu_baseline(cfg, graph, scheds[0], min(args.cpu_events, E))
+    if synth:
+        out["config"]["gradient"] = "N(0,1e-3) Philox4x32-10 + Box-Muller, generated in registers"
+    if cpu_events > 0:
+        if synth:
+            eng.close()
+            del eng
+            torch.cuda.empty_cache()
+            out["cpu_baseline"] = cpu_baseline_synth(cfg, scheds[0], min(cpu_events, E))
+        else:
+            out["cpu_baseline"] = cpu_baseline_data(cfg, scheds[0], min(cpu_events, E), feats, targs, x0)
+            eng.close()
+    else:
+        eng.close()
     print(json.dumps(out), flush=True)
 
 

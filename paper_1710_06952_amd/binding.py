@@ -180,9 +180,12 @@ class Handle:
             raise AdpsgdError(rc, (lib().adpsgd_last_error(None) or b"").decode())
 
     def destroy(self):
-        if getattr(self, "_h", None):
-            lib().adpsgd_destroy(self._h)
-            self._h = None
+        h, self._h = getattr(self, "_h", None), None
+        if h:
+            try:
+                lib().adpsgd_destroy(h)
+            except TypeError:       # interpreter shutdown: the module globals are already gone
+                pass
 
     __del__ = destroy
 

@@ -7,5 +7,5 @@ are NOT made here: each side implements the same counter-based generator.
 """
 from .graphs import ring_graph, random_regular4_graph, hop_ring_graph, graph_is_valid  # noqa: F401
 from .data import (lsq_data, logreg_data, mixture_data, mlp_init, f32_to_bf16_bits,  # noqa: F401
-                   bf16_bits_to_f32, linear_data_on_device)
+                   bf16_bits_to_f32, linear_data_on_device, mixture_data_on_device)
 from .configs import CONFIGS, get_config  # noqa: F401

@@ -103,3 +103,21 @@ def linear_data_on_device(model, n, rows, d, seed=0, noise=0.1, feature_var=None
         feats.append(A)
         targs.append(z if model == "lsq" else torch.where(z >= 0, 1.0, -1.0).to(torch.float32))
     return feats, targs
+
+
+def mixture_data_on_device(n, rows, din=784, classes=10, seed=0, device="cuda:0"):
+    """Gaussian-mixture inputs of the perceptron workload generated in GPU memory (same recipe as
+    mixture_data): per worker bf16 features (rows x din, leading dimension padded to 8) and int32 labels."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(1000003 * seed + 19)
+    means = torch.randn((classes, din), device=device, generator=gen)
+    ld = (din + 7) // 8 * 8
+    feats, targs = [], []
+    for _ in range(n):
+        lab = torch.randint(0, classes, (rows,), device=device, generator=gen, dtype=torch.int32)
+        x = torch.zeros((rows, ld), dtype=torch.bfloat16, device=device)
+        x[:, :din] = (means[lab.long()] + torch.randn((rows, din), device=device, generator=gen)).to(torch.bfloat16)
+        feats.append(x)
+        targs.append(lab)
+    return feats, targs
