@@ -238,6 +238,18 @@ def main():
     }
     if synth:
         out["config"]["gradient"] = "N(0,1e-3) Philox4x32-10 + Box-Muller, generated in registers"
+    # diagnostics (outside the timed region): consensus distance and mean model each read X once
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    cd = eng.consensus_distance()
+    t1 = time.perf_counter()
+    mean_dev = torch.empty(d, dtype=torch.float32, device="cuda:0")
+    P.binding._check(eng.h._h, P.lib().adpsgd_get_mean_model(eng.h._h, mean_dev.data_ptr(), 1))
+    t2 = time.perf_counter()
+    xbytes = 4.0 * n * d
+    out["diagnostics"] = {"consensus_distance": cd, "consensus_ms": (t1 - t0) * 1e3, "consensus_GBs": xbytes / (t1 - t0) / 1e9,
+                          "mean_model_ms": (t2 - t1) * 1e3, "mean_model_GBs": xbytes / (t2 - t1) / 1e9}
+    del mean_dev
     if cpu_events > 0:
         if synth:
             eng.close()
