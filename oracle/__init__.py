@@ -122,10 +122,12 @@ def minibatch_gradient(model, xhat, features, targets, idx, gscale, lam=0.0, mlp
 
 def run_events(X, schedule, model, gamma, *, M=0, gscale=1.0, lam=0.0, mlp=(0, 0, 0),
                features=None, targets=None, gamma_k=None, synth_std=0.0, synth_seed=0,
-               event_base=0, coords=None, mode=1, want_loss=False, want_g=False):
+               event_base=0, coords=None, mode=1, want_loss=False, want_g=False,
+               momentum=0.0, weight_decay=0.0, V=None):
     """Run the events of ``schedule`` on X (n x d fp32, C-contiguous) IN PLACE.
 
     mode 0 = literal snapshot history, mode 1 = parked gradients (same values).
+    V (n x d fp32, updated in place) switches to the momentum / weight-decay form of the update.
     Returns a dict with optional 'loss' (K,) and 'g' (K, d)."""
     assert X.dtype == np.float32 and X.flags.c_contiguous and X.ndim == 2
     n, d = X.shape
@@ -151,6 +153,8 @@ def run_events(X, schedule, model, gamma, *, M=0, gscale=1.0, lam=0.0, mlp=(0, 0
         coords = np.ascontiguousarray(coords, dtype=np.int64)
         assert coords.size == d
     gk = None if gamma_k is None else np.ascontiguousarray(gamma_k, dtype=np.float32)
+    if V is not None:
+        assert V.dtype == np.float32 and V.flags.c_contiguous and V.shape == X.shape
     loss = np.zeros(K, dtype=np.float64) if want_loss else None
     glog = np.zeros((K, d), dtype=np.float32) if want_g else None
     rc = lib().oracle_run_events(
@@ -160,7 +164,8 @@ def run_events(X, schedule, model, gamma, *, M=0, gscale=1.0, lam=0.0, mlp=(0, 0
         C.c_double(synth_std), C.c_uint64(synth_seed), C.c_uint64(event_base),
         _p(coords, C.c_int64), C.c_int64(K), _p(worker, C.c_int32), _p(nbr, C.c_int32),
         _p(tau, C.c_int32), _p(batch, C.c_int32), C.c_int(mode), _p(loss, C.c_double),
-        _p(glog, C.c_float))
+        _p(glog, C.c_float), C.c_float(momentum), C.c_float(weight_decay), _p(V, C.c_float),
+        C.c_int64(d))
     del keep
     if rc != 0:
         raise ValueError("oracle_run_events failed with code %d" % rc)

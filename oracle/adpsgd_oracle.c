@@ -397,6 +397,28 @@ static void average_then_apply(float* xi, float* xj, const float* g, float gamma
     }
 }
 
+/* The same event with the optimizer the paper's experiments used (Sec. 5.2: momentum 0.9, weight
+ * decay 1e-4).  Algorithm 1 has neither; the reading taken: each worker keeps its own momentum
+ * buffer v^i (local optimizer state, never averaged), and momentum and weight decay act as in a
+ * standard SGD step on the parameters being updated, i.e. on the averaged model x_{k+1/2}^i:
+ *     u = g_k + wd * x_{k+1/2}^i ;   v^i <- mu * v^i + u ;   x_{k+1}^i = x_{k+1/2}^i - gamma * v^i
+ * (mu = wd = 0 gives back the plain event).  fp32, one rounding per operation. */
+static void average_then_apply_momentum(float* xi, float* xj, float* vi, const float* g, float gamma,
+                                        float mu, float wd, int64_t d)
+{
+    for (int64_t e = 0; e < d; ++e) {
+        float avg = (xi[e] + xj[e]) * 0.5f;
+        float decay = wd * avg;
+        float u = g[e] + decay;
+        float carried = mu * vi[e];
+        float v = carried + u;
+        float step = gamma * v;
+        vi[e] = v;
+        xj[e] = avg;
+        xi[e] = avg - step;
+    }
+}
+
 /* ------------------------------------------------------------------------- */
 /* The event loop.                                                            */
 /*   mode 0 ("literal"): keeps the last T+1 snapshots X_{k-T..k} and reads    */
@@ -418,7 +440,8 @@ int oracle_run_events(int32_t n, int64_t d, float* X, int64_t ldx, int model, in
                       double synth_std, uint64_t synth_seed, uint64_t event_base,
                       const int64_t* coords, int64_t K, const int32_t* worker,
                       const int32_t* neighbour, const int32_t* tau, const int32_t* batch_idx,
-                      int mode, double* loss, float* g_log)
+                      int mode, double* loss, float* g_log, float momentum, float weight_decay,
+                      float* V, int64_t ldv)
 {
     if (n < 1 || d < 1 || ldx < d || K < 0) return -1;
     grad_spec spec = { model, d, M, gscale, lambda, mlp_in, mlp_hid, mlp_out };
@@ -483,7 +506,10 @@ int oracle_run_events(int32_t n, int64_t d, float* X, int64_t ldx, int model, in
         const float gam = gamma_k ? gamma_k[k] : gamma;
         float* xi = X + (size_t)i * ldx;
         float* xj = X + (size_t)j * ldx;
-        average_then_apply(xi, xj, g, gam, d);   /* j == i (no neighbour) degenerates to x -= gamma g */
+        if (V)
+            average_then_apply_momentum(xi, xj, V + (size_t)i * ldv, g, gam, momentum, weight_decay, d);
+        else
+            average_then_apply(xi, xj, g, gam, d);   /* j == i (no neighbour) degenerates to x -= gamma g */
     }
     free(g); free(hist); free(parked); free(parked_loss); free(bucket_head); free(bucket_next);
     return 0;

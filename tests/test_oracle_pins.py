@@ -457,3 +457,72 @@ def test_coordinate_subset_of_synthetic_workload_follows_the_full_run():
     oracle.run_events(Z, dict(sched, tau=np.zeros(K, np.int32)), SYNTH, 0.1, synth_std=0.03,
                       synth_seed=9, event_base=17)
     assert np.array_equal(Z, X)
+
+
+# --------------------------------------------------------------------------- momentum / weight decay
+def test_momentum_with_zero_coefficients_is_the_plain_event():
+    n, feats, targs, sched, X0 = _random_problem(6, 19, 12, 200, 5, 4, 0, LSQ)
+    Xa, Xb = X0.copy(), X0.copy()
+    V = np.zeros_like(X0)
+    oracle.run_events(Xa, sched, LSQ, 0.01, M=5, gscale=0.2, features=feats, targets=targs)
+    r = oracle.run_events(Xb, sched, LSQ, 0.01, M=5, gscale=0.2, features=feats, targets=targs, V=V, want_g=True)
+    assert np.array_equal(Xa, Xb)
+    # with mu = 0 the buffer of a worker holds the last gradient it applied
+    last = {}
+    for k, i in enumerate(sched["worker"]):
+        last[i] = k
+    for i, k in last.items():
+        assert np.array_equal(V[i], r["g"][k])
+
+
+def test_single_worker_momentum_matches_library_sgd():
+    """n = 1, T = 0: the update is the textbook SGD step with momentum and weight decay; compare
+    with torch.optim.SGD fed the same minibatch gradients."""
+    torch = pytest.importorskip("torch")
+    rows, d, M, K, gamma, mu, wd = 30, 9, 6, 120, 0.05, 0.9, 0.01
+    feats, targs, _ = lsq_data(1, rows, d, seed=3)
+    sched = oracle.make_schedule(ring_graph(1), K, seed=2, T_max=0, M=M, rows=[rows])
+    X = np.zeros((1, d), dtype=np.float32)
+    V = np.zeros((1, d), dtype=np.float32)
+    oracle.run_events(X, sched, LSQ, gamma, M=M, gscale=1.0 / M, features=feats, targets=targs,
+                      momentum=mu, weight_decay=wd, V=V)
+    p = torch.zeros(d, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([p], lr=gamma, momentum=mu, weight_decay=wd)
+    A, b = torch.tensor(feats[0], dtype=torch.float64), torch.tensor(targs[0], dtype=torch.float64)
+    for k in range(K):
+        idx = torch.tensor(sched["batch_idx"][k], dtype=torch.long)
+        opt.zero_grad()
+        (0.5 * ((A[idx] @ p - b[idx]) ** 2).mean()).backward()
+        opt.step()
+    assert np.allclose(X[0], p.detach().numpy(), rtol=2e-4, atol=2e-5)
+
+
+def test_momentum_constant_gradient_closed_form_and_sum_identity():
+    """Synthetic gradient with std 0 and a constant offset is not available, so use gossip on a ring
+    with n = 4 and the telescoped identity: the sum over workers moves by -gamma v_k at event k, and
+    averaging never touches it; with wd = 0 the buffers obey v <- mu v + g exactly."""
+    n, feats, targs, sched, X0 = _random_problem(6, 11, 10, 150, 4, 3, 2, LSQ)
+    gamma, mu = 0.02, 0.8
+    X, V = X0.copy(), np.zeros_like(X0)
+    r = oracle.run_events(X, sched, LSQ, gamma, M=4, gscale=0.25, features=feats, targets=targs,
+                          momentum=mu, weight_decay=0.0, V=V, want_g=True)
+    Vref = np.zeros_like(X0, dtype=np.float64)
+    total = np.zeros(11)
+    for k, i in enumerate(sched["worker"]):
+        Vref[i] = mu * Vref[i] + r["g"][k]
+        total += Vref[i]
+    assert np.allclose(V, Vref, rtol=1e-5, atol=1e-6)
+    assert np.allclose(X.sum(0, dtype=np.float64), X0.sum(0, dtype=np.float64) - gamma * total, rtol=0, atol=5e-5)
+
+
+def test_weight_decay_acts_on_the_averaged_model():
+    """One event by hand: x_i = 2, x_j = 4, g = 0 (synthetic std 0): avg = 3, u = wd*3, v = u,
+    x_i = 3 - gamma*wd*3, x_j = 3."""
+    X = np.array([[2.0], [4.0]], dtype=np.float32)
+    V = np.zeros_like(X)
+    sched = {"worker": [0], "neighbour": [1], "tau": [0]}
+    oracle.run_events(X, sched, SYNTH, 0.5, synth_std=0.0, momentum=0.9, weight_decay=0.25, V=V)
+    assert X[1, 0] == 3.0 and V[0, 0] == 0.75 and X[0, 0] == 3.0 - 0.5 * 0.75 and V[1, 0] == 0.0
+    oracle.run_events(X, sched, SYNTH, 0.5, synth_std=0.0, momentum=0.5, weight_decay=0.0, V=V)
+    avg = (2.625 + 3.0) / 2
+    assert V[0, 0] == 0.375 and X[0, 0] == np.float32(avg - 0.5 * 0.375) and X[1, 0] == np.float32(avg)
