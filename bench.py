@@ -113,6 +113,9 @@ def main():
                     help="events the CPU oracle is timed on (0 = skip; default 16 for config 3, 0 otherwise)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
+    ap.add_argument("--momentum", type=float, default=0.0,
+                    help="config 3 only: run the events with per-worker momentum buffers (24 B per parameter per event)")
+    ap.add_argument("--weight-decay", type=float, default=0.0)
     ap.add_argument("--d", type=int, default=0, help="override d (debugging only; the result is then not the headline)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -137,7 +140,8 @@ def main():
     feats = targs = None
     x0 = np.zeros(d, np.float32)
     if synth:
-        eng = P.Engine(graph, d, "synth", gamma=cfg["gamma"], T_max=cfg["T_max"], synth_std=std, synth_seed=cfg["seed"])
+        eng = P.Engine(graph, d, "synth", gamma=cfg["gamma"], T_max=cfg["T_max"], synth_std=std, synth_seed=cfg["seed"],
+                       momentum=args.momentum, weight_decay=args.weight_decay)
     elif cfg["model"] == "mlp":
         feats, targs = mixture_data_on_device(n, cfg["rows"], din=cfg["mlp"][0], classes=cfg["mlp"][2], seed=cfg["seed"])
         x0 = mlp_init(*cfg["mlp"], seed=cfg["seed"])
@@ -183,7 +187,9 @@ def main():
                     mlp=cfg.get("mlp", (0, 0, 0)), Xbf16_ptr=None if eng.Xbf16 is None else eng.Xbf16.data_ptr(),
                     workspace_ptr=None if eng.workspace is None else eng.workspace.data_ptr(),
                     workspace_bytes=0 if eng.workspace is None else eng.workspace.numel() * 4,
-                    stream=torch.cuda.current_stream().cuda_stream, flags=P.FLAG_PROFILE)
+                    stream=torch.cuda.current_stream().cuda_stream, flags=P.FLAG_PROFILE,
+                    momentum=args.momentum if synth else 0.0, weight_decay=args.weight_decay if synth else 0.0,
+                    V_ptr=None if eng.V is None else eng.V.data_ptr())
     if feats is not None:
         for i, (f, t) in enumerate(eng._data):
             prof.load_data(i, f.data_ptr(), f.shape[0], f.stride(0), t.data_ptr())
@@ -195,11 +201,11 @@ def main():
 
     events_per_launch = ps["events"] / ps["fused_launches"]
     if synth:
-        bytes_per_event = 16.0 * d                      # read x_i, x_j; write x_i, x_j (fp32)
+        bytes_per_event = (24.0 if eng.V is not None else 16.0) * d   # read x_i, x_j; write x_i, x_j (+ v_i read and written)
         avg_launch_s = ps["fused_ms"] * 1e-3 / ps["fused_launches"]
         achieved = bytes_per_event * events_per_launch / avg_launch_s / 1e9
         traffic = traffic_from_profiles()               # measured bytes per event (rocprofv3 counters) ...
-        traffic = traffic * events_per_launch if (traffic is not None and d == 25_600_000) else None   # ... per launch
+        traffic = traffic * events_per_launch if (traffic is not None and d == 25_600_000 and eng.V is None) else None   # ... per launch
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                 "kernel": "fused_gossip_apply_kernel<synth>", "avg_launch_ms": avg_launch_s * 1e3,
@@ -238,6 +244,9 @@ def main():
     }
     if synth:
         out["config"]["gradient"] = "N(0,1e-3) Philox4x32-10 + Box-Muller, generated in registers"
+        if eng.V is not None:
+            out["config"]["optimizer"] = {"momentum": args.momentum, "weight_decay": args.weight_decay}
+            out["roofline"]["kernel"] = "fused_gossip_apply_kernel<synth, momentum>"
     # diagnostics (outside the timed region): consensus distance and mean model each read X once
     torch.cuda.synchronize()
     t0 = time.perf_counter()

@@ -97,6 +97,14 @@ typedef struct {
                             slots let more events run per round                    */
     void* stream;        /* hipStream_t on the current device; NULL = default stream */
     int32_t flags;       /* ADPSGD_FLAG_*                                         */
+    /* Optimizer of the paper's experiments (Sec. 5.2: momentum 0.9, weight decay 1e-4); Algorithm 1
+     * itself has neither (both 0: the plain event).  Each worker keeps its own momentum buffer v^i
+     * (local state, never averaged); both act on the model being updated, the averaged x_{k+1/2}^i:
+     *     u = g_k + weight_decay * x_{k+1/2}^i;  v^i <- momentum * v^i + u;  x^i <- x_{k+1/2}^i - gamma * v^i */
+    float momentum;
+    float weight_decay;
+    float* V;            /* device, n x ldx fp32 momentum buffers, caller-owned; required when momentum or
+                            weight_decay is non-zero, else NULL.  adpsgd_set_models zeroes it */
 } adpsgd_opts_t;
 
 /* A batch of K events, all arrays in host memory, read during the call only.
@@ -179,6 +187,9 @@ int adpsgd_get_mean_model(adpsgd_t* h, float* out, int32_t on_device);
 /* Consensus distance (1/n) sum_i |mean - x^i|^2: the quantity M_k of the proofs
  * appendix with uniform p.  *out is host memory.  Synchronous. */
 int adpsgd_consensus_distance(adpsgd_t* h, double* out);
+
+/* Copy the n x d momentum buffers (only when opts.V was given). Synchronises the stream. */
+int adpsgd_get_momentum(adpsgd_t* h, float* out, int64_t ld_out, int32_t on_device);
 
 /* MLP only: copy the n x d bf16 shadow weights (bit patterns). Synchronous. */
 int adpsgd_get_bf16_models(adpsgd_t* h, uint16_t* out, int64_t ld_out, int32_t on_device);

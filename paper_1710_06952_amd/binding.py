@@ -20,7 +20,7 @@ FLAG_PROFILE = 1
 EXPORTS = [
     "adpsgd_create", "adpsgd_destroy", "adpsgd_last_error", "adpsgd_load_data", "adpsgd_set_models",
     "adpsgd_run_events", "adpsgd_get_models", "adpsgd_get_mean_model", "adpsgd_consensus_distance",
-    "adpsgd_get_bf16_models", "adpsgd_get_stats", "adpsgd_make_schedule", "adpsgd_plan_rounds",
+    "adpsgd_get_bf16_models", "adpsgd_get_momentum", "adpsgd_get_stats", "adpsgd_make_schedule", "adpsgd_plan_rounds",
     "adpsgd_synth_gradient",
 ]
 
@@ -41,7 +41,7 @@ class Opts(C.Structure):
                 ("synth_seed", C.c_uint64), ("mlp_in", C.c_int32), ("mlp_hidden", C.c_int32),
                 ("mlp_out", C.c_int32), ("X", C.c_void_p), ("ldx", C.c_int64), ("Xbf16", C.c_void_p),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64), ("stream", C.c_void_p),
-                ("flags", C.c_int32)]
+                ("flags", C.c_int32), ("momentum", C.c_float), ("weight_decay", C.c_float), ("V", C.c_void_p)]
 
 
 class Schedule(C.Structure):
@@ -101,6 +101,7 @@ def lib():
         L.adpsgd_get_mean_model.argtypes = [vp, vp, i32]
         L.adpsgd_consensus_distance.argtypes = [vp, P(C.c_double)]
         L.adpsgd_get_bf16_models.argtypes = [vp, vp, i64, i32]
+        L.adpsgd_get_momentum.argtypes = [vp, vp, i64, i32]
         L.adpsgd_get_stats.argtypes = [vp, P(Stats)]
         L.adpsgd_make_schedule.argtypes = [P(SchedParams), u64, u64, i64, P(i32), P(i32), P(i32), P(i32)]
         L.adpsgd_plan_rounds.argtypes = [i32, i64, P(i32), P(i32), P(i32), i32, i32, P(i32), P(i32), P(i32), P(i32)]
@@ -167,10 +168,11 @@ class Handle:
 
     def __init__(self, graph, d, *, model, X_ptr, ldx, M=0, gamma=0.0, lam=0.0, grad_sum=False, T_max=0,
                  synth_std=0.0, synth_seed=0, mlp=(0, 0, 0), Xbf16_ptr=None, workspace_ptr=None,
-                 workspace_bytes=0, stream=0, flags=0):
+                 workspace_bytes=0, stream=0, flags=0, momentum=0.0, weight_decay=0.0, V_ptr=None):
         g, keep = _graph_struct(graph)
         o = Opts(model, M, gamma, lam, 1 if grad_sum else 0, T_max, synth_std, synth_seed, mlp[0], mlp[1], mlp[2],
-                 X_ptr, ldx, Xbf16_ptr, workspace_ptr, workspace_bytes, stream or None, flags)
+                 X_ptr, ldx, Xbf16_ptr, workspace_ptr, workspace_bytes, stream or None, flags,
+                 momentum, weight_decay, V_ptr)
         self._h = C.c_void_p()
         self.n, self.d, self.M, self.model = g.n, d, M, model
         rc = lib().adpsgd_create(C.byref(self._h), C.byref(g), d, C.byref(o))
@@ -221,6 +223,11 @@ class Handle:
     def get_bf16_models(self):
         res = np.empty((self.n, self.d), dtype=np.uint16)
         _check(self._h, lib().adpsgd_get_bf16_models(self._h, res.ctypes.data, self.d, 0))
+        return res
+
+    def get_momentum(self):
+        res = np.empty((self.n, self.d), dtype=np.float32)
+        _check(self._h, lib().adpsgd_get_momentum(self._h, res.ctypes.data, self.d, 0))
         return res
 
     def get_mean_model(self):

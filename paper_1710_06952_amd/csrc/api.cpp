@@ -191,6 +191,10 @@ extern "C" int adpsgd_create(adpsgd_t** out, const adpsgd_graph_t* graph, int64_
         if (mlp_scratch_bytes(1, o.M, o.mlp_in, o.mlp_hidden, o.mlp_out) == 0)
             return fail(nullptr, ADPSGD_ERR_ARG, "create: MLP shape not supported by the gradient kernel");
     }
+    if (!std::isfinite(o.momentum) || !std::isfinite(o.weight_decay))
+        return fail(nullptr, ADPSGD_ERR_ARG, "create: momentum or weight_decay not finite");
+    if ((o.momentum != 0.0f || o.weight_decay != 0.0f) && (!o.V || !aligned16(o.V)))
+        return fail(nullptr, ADPSGD_ERR_ARG, "create: momentum / weight decay need the buffer V (16-byte aligned)");
     int count = 0;
     if (hipGetDeviceCount(&count) != hipSuccess || count < 1)
         return fail(nullptr, ADPSGD_ERR_HIP, "create: no HIP device available");
@@ -277,6 +281,7 @@ extern "C" int adpsgd_set_models(adpsgd_t* h, const float* x, int64_t ld_in, int
     }
     if (h->o.model == ADPSGD_MODEL_MLP)
         HIP_TRY(h, launch_refresh_bf16(h->o.X, h->o.Xbf16, h->o.ldx, h->n, h->stream));
+    if (h->o.V) HIP_TRY(h, hipMemsetAsync(h->o.V, 0, static_cast<size_t>(h->n) * h->o.ldx * 4, h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     return ADPSGD_OK;
 }
@@ -448,7 +453,7 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
             for (int64_t t = u_off[r]; t < u_off[r + 1] && !has_solo; ++t) has_solo = uops[t].i == uops[t].j;
             FusedArgs a{h->o.X, h->o.ldx, h->d, d_uops + u_off[r], static_cast<int32_t>(nu), slots,
                         h->o.model == ADPSGD_MODEL_MLP ? h->o.Xbf16 : nullptr, h->o.synth_std, h->o.synth_seed,
-                        !with_grad, h->streaming, has_solo};
+                        !with_grad, h->streaming, has_solo, h->o.V, h->o.momentum, h->o.weight_decay};
             HIP_TRY(h, launch_fused_gossip_apply(a, h->stream));
             ++h->stats.fused_launches;
             h->stats.max_round_pairs = std::max<int64_t>(h->stats.max_round_pairs, nu);
@@ -470,6 +475,17 @@ extern "C" int adpsgd_get_models(adpsgd_t* h, float* out, int64_t ld_out, int32_
     if (!h) return ADPSGD_ERR_ARG;
     if (!out || ld_out < h->d) return fail(h, ADPSGD_ERR_ARG, "get_models: out is NULL or ld_out < d");
     HIP_TRY(h, hipMemcpy2DAsync(out, static_cast<size_t>(ld_out) * 4, h->o.X, static_cast<size_t>(h->o.ldx) * 4,
+                                static_cast<size_t>(h->d) * 4, h->n,
+                                on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return ADPSGD_OK;
+}
+
+extern "C" int adpsgd_get_momentum(adpsgd_t* h, float* out, int64_t ld_out, int32_t on_device) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (!h->o.V) return fail(h, ADPSGD_ERR_STATE, "get_momentum: the engine was created without momentum buffers");
+    if (!out || ld_out < h->d) return fail(h, ADPSGD_ERR_ARG, "get_momentum: out is NULL or ld_out < d");
+    HIP_TRY(h, hipMemcpy2DAsync(out, static_cast<size_t>(ld_out) * 4, h->o.V, static_cast<size_t>(h->o.ldx) * 4,
                                 static_cast<size_t>(h->d) * 4, h->n,
                                 on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));

@@ -78,6 +78,9 @@ struct FusedArgs {
     bool synth;
     bool streaming;      // rows do not fit the caches: bypass them
     bool has_solo;       // some event of the round has i == j (worker without a neighbour)
+    float* V;            // device momentum buffers (n x ld) or nullptr: plain event
+    float momentum;
+    float weight_decay;
 };
 hipError_t launch_fused_gossip_apply(const FusedArgs& a, hipStream_t st);
 

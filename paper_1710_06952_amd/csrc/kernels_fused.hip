@@ -31,6 +31,8 @@ struct FusedParams {
     uint16_t* Xbf16;
     float synth_std;
     uint32_t key0, key1;
+    float* V;
+    float momentum, weight_decay;
 };
 
 template <bool STREAM>
@@ -53,11 +55,27 @@ __device__ __forceinline__ void average_then_apply(float a, float b, float g, fl
     new_i = avg - step;
 }
 
+// The event with the experiments' optimizer (Sec. 5.2): per-worker momentum buffer v, weight decay on
+// the averaged model;  u = g + wd * avg;  v <- mu * v + u;  x^i <- avg - gamma * v.  One rounding per
+// operation, in this order.
+__device__ __forceinline__ void average_then_apply_momentum(float a, float b, float g, float v_old, float gamma, float mu,
+                                                            float wd, float& new_i, float& new_j, float& v_new) {
+#pragma clang fp contract(off)
+    const float avg = (a + b) * 0.5f;
+    const float decay = wd * avg;
+    const float u = g + decay;
+    const float carried = mu * v_old;
+    v_new = carried + u;
+    const float step = gamma * v_new;
+    new_j = avg;
+    new_i = avg - step;
+}
+
 // grid = (ceil(d / 1024), events of the round).  Pass u of thread t touches element
 // 1024 blockIdx.x + 256 u + t of both rows.
 // SOLO = the round contains an event without a partner (i == j: a worker with no neighbour takes a
 // plain SGD step); all other rounds run the variant without the per-store test (1.3 % faster).
-template <bool SYNTH, bool SHADOW, bool STREAM, bool SOLO>
+template <bool SYNTH, bool SHADOW, bool STREAM, bool SOLO, bool MOM>
 __global__ __launch_bounds__(kThreads) void fused_gossip_apply_kernel(const FusedParams p) {
     __shared__ __attribute__((aligned(16))) float zs[SYNTH ? kTileElems : 4];
     const PairOp op = p.ops[blockIdx.y];   // uniform address: scalar loads, no LDS staging needed
@@ -68,7 +86,8 @@ __global__ __launch_bounds__(kThreads) void fused_gossip_apply_kernel(const Fuse
     const int64_t tile = static_cast<int64_t>(blockIdx.x) * kTileElems;
     const int64_t e0 = tile + threadIdx.x;
 
-    float a[kUnroll], b[kUnroll], g[kUnroll];
+    float* __restrict__ vi = MOM ? p.V + static_cast<int64_t>(op.i) * p.ld : nullptr;
+    float a[kUnroll], b[kUnroll], g[kUnroll], vold[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
         const int64_t e = e0 + u * kThreads;
@@ -76,6 +95,7 @@ __global__ __launch_bounds__(kThreads) void fused_gossip_apply_kernel(const Fuse
             a[u] = load1<STREAM>(xi + e);
             b[u] = load1<STREAM>(xj + e);
             if (!SYNTH) g[u] = load1<STREAM>(gs + e);
+            if (MOM) vold[u] = load1<STREAM>(vi + e);
         }
     }
 #ifdef ADPSGD_EXPERIMENT_NO_LDS
@@ -109,7 +129,13 @@ __global__ __launch_bounds__(kThreads) void fused_gossip_apply_kernel(const Fuse
         const int64_t e = e0 + u * kThreads;
         if (e >= p.d) continue;            // entries at and beyond d are never touched: they stay zero
         float ni, nj;
-        average_then_apply(a[u], b[u], g[u], op.gamma, ni, nj);
+        if (MOM) {
+            float vnew;
+            average_then_apply_momentum(a[u], b[u], g[u], vold[u], op.gamma, p.momentum, p.weight_decay, ni, nj, vnew);
+            store1<STREAM>(vi + e, vnew);
+        } else {
+            average_then_apply(a[u], b[u], g[u], op.gamma, ni, nj);
+        }
         store1<STREAM>(xi + e, ni);
         if (pair) store1<STREAM>(xj + e, nj);
         if (SHADOW) {
@@ -129,11 +155,16 @@ __global__ __launch_bounds__(kThreads) void synth_gradient_kernel(float* out, in
         if (4 * v + t < d) out[4 * v + t] = gv[t];
 }
 
+template <bool SYNTH, bool SHADOW, bool STREAM, bool SOLO>
+hipError_t launch_mom(const FusedParams& p, dim3 grid, hipStream_t st) {
+    if (p.V) hipLaunchKernelGGL((fused_gossip_apply_kernel<SYNTH, SHADOW, STREAM, SOLO, true>), grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((fused_gossip_apply_kernel<SYNTH, SHADOW, STREAM, SOLO, false>), grid, dim3(kThreads), 0, st, p);
+    return hipGetLastError();
+}
 template <bool SYNTH, bool SHADOW, bool STREAM>
 hipError_t launch_solo(const FusedParams& p, dim3 grid, bool solo, hipStream_t st) {
-    if (solo) hipLaunchKernelGGL((fused_gossip_apply_kernel<SYNTH, SHADOW, STREAM, true>), grid, dim3(kThreads), 0, st, p);
-    else hipLaunchKernelGGL((fused_gossip_apply_kernel<SYNTH, SHADOW, STREAM, false>), grid, dim3(kThreads), 0, st, p);
-    return hipGetLastError();
+    if (solo) return launch_mom<SYNTH, SHADOW, STREAM, true>(p, grid, st);
+    return launch_mom<SYNTH, SHADOW, STREAM, false>(p, grid, st);
 }
 template <bool SYNTH, bool SHADOW>
 hipError_t launch_variant(const FusedParams& p, dim3 grid, bool streaming, bool solo, hipStream_t st) {
@@ -155,6 +186,9 @@ hipError_t launch_fused_gossip_apply(const FusedArgs& a, hipStream_t st) {
     p.synth_std = a.synth_std;
     p.key0 = static_cast<uint32_t>(a.synth_seed);
     p.key1 = static_cast<uint32_t>(a.synth_seed >> 32);
+    p.V = a.V;
+    p.momentum = a.momentum;
+    p.weight_decay = a.weight_decay;
     const int64_t tiles = (p.d + kTileElems - 1) / kTileElems;
     if (tiles > 0x7FFFFFFF || a.n_ops > 65535) return hipErrorInvalidValue;
     const dim3 grid(static_cast<uint32_t>(tiles), static_cast<uint32_t>(a.n_ops));

@@ -16,7 +16,8 @@ def _pad(d, mult=64):
 
 class Engine:
     def __init__(self, graph, d, model, *, M=0, gamma=0.0, lam=0.0, grad_sum=False, T_max=0, synth_std=0.0,
-                 synth_seed=0, mlp=(0, 0, 0), n_slots=None, profile=False, device="cuda:0"):
+                 synth_seed=0, mlp=(0, 0, 0), n_slots=None, profile=False, momentum=0.0, weight_decay=0.0,
+                 device="cuda:0"):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("Engine needs a GPU: the HIP library is the only implementation")
@@ -41,12 +42,16 @@ class Engine:
             ws_ptr, ws_bytes = self.workspace.data_ptr(), n_slots * self.ld * 4
         if self.model == B.MODEL_MLP:
             self.Xbf16 = torch.zeros((self.n, self.ld), dtype=torch.bfloat16, device=self.device)
+        self.V = None
+        if momentum != 0.0 or weight_decay != 0.0:
+            self.V = torch.zeros((self.n, self.ld), dtype=torch.float32, device=self.device)
         self.stream = torch.cuda.current_stream(self.device)
         self.h = B.Handle(graph, d, model=self.model, X_ptr=self.X.data_ptr(), ldx=self.ld, M=M, gamma=gamma,
                           lam=lam, grad_sum=grad_sum, T_max=T_max, synth_std=synth_std, synth_seed=synth_seed,
                           mlp=mlp, Xbf16_ptr=None if self.Xbf16 is None else self.Xbf16.data_ptr(),
                           workspace_ptr=ws_ptr, workspace_bytes=ws_bytes, stream=self.stream.cuda_stream,
-                          flags=B.FLAG_PROFILE if profile else 0)
+                          flags=B.FLAG_PROFILE if profile else 0, momentum=momentum, weight_decay=weight_decay,
+                          V_ptr=None if self.V is None else self.V.data_ptr())
         self._data = []
         self.loss = None
 
@@ -92,6 +97,9 @@ class Engine:
 
     def get_bf16_models(self):
         return self.h.get_bf16_models()
+
+    def get_momentum(self):
+        return self.h.get_momentum()
 
     def get_mean_model(self):
         return self.h.get_mean_model()

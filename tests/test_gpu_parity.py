@@ -380,3 +380,79 @@ def test_config5_full_shape(P):
     assert sched["tau"].max() > 20
     assert rel_err(Xg, Xr) <= TOL
     assert np.allclose(lg, lr, rtol=2e-4, atol=1e-7)
+
+
+# ------------------------------------------------------------------ momentum and weight decay in the fused apply
+@pytest.mark.parametrize("n,d,K,T,mu,wd", [(8, 5003, 500, 5, 0.9, 1e-4), (5, 1030, 300, 2, 0.5, 0.0), (4, 77, 200, 1, 0.0, 0.01)])
+def test_synth_workload_with_momentum_and_weight_decay(P, n, d, K, T, mu, wd):
+    _say("synth momentum n=%d d=%d mu=%g wd=%g" % (n, d, mu, wd))
+    g = ring_graph(n)
+    sched = oracle.make_schedule(g, K, seed=4, T_max=T)
+    std = float(np.float32(0.0316227766))
+    eng = P.Engine(g, d, "synth", gamma=0.1, T_max=T, synth_std=std, synth_seed=2, momentum=mu, weight_decay=wd)
+    x0 = np.random.default_rng(0).standard_normal(d).astype(np.float32)
+    eng.set_models(x0)
+    eng.run_events(sched)
+    Xg, Vg = eng.get_models(), eng.get_momentum()
+    Xr, Vr = np.tile(x0, (n, 1)), np.zeros((n, d), np.float32)
+    oracle.run_events(Xr, sched, oracle.MODEL_SYNTH, 0.1, synth_std=std, synth_seed=2, momentum=mu, weight_decay=wd, V=Vr)
+    assert rel_err(Xg, Xr) <= TOL and rel_err(Vg, Vr) <= TOL
+    assert float(eng.V[:, d:].abs().max().item()) == 0.0 if eng.ld > d else True
+    eng.set_models(x0)                                   # a fresh start clears the optimizer state
+    assert np.all(eng.get_momentum() == 0)
+    eng.close()
+
+
+def test_momentum_arithmetic_is_bit_exact_given_the_gradient(P):
+    import torch
+    n, d, K, gamma, std, mu, wd = 6, 1000, 40, 0.37, 1.7, 0.9, 0.013
+    g = ring_graph(n)
+    sched = oracle.make_schedule(g, K, seed=3, T_max=0)
+    eng = P.Engine(g, d, "synth", gamma=gamma, synth_std=std, synth_seed=4, momentum=mu, weight_decay=wd)
+    X0 = np.random.default_rng(1).standard_normal((n, d)).astype(np.float32)
+    eng.set_models(X0, broadcast=False)
+    eng.run_events(sched)
+    Xg, Vg = eng.get_models(), eng.get_momentum()
+    buf = torch.empty(d, dtype=torch.float32, device="cuda:0")
+    X, V = X0.copy(), np.zeros_like(X0)
+    f = np.float32
+    for k in range(K):
+        P.adpsgd_synth_gradient(4, k, std, d, buf.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        gk = buf.cpu().numpy()
+        i, j = sched["worker"][k], sched["neighbour"][k]
+        avg = (X[i] + X[j]) * f(0.5)
+        u = gk + f(wd) * avg
+        V[i] = f(mu) * V[i] + u
+        X[j] = avg
+        X[i] = avg - f(gamma) * V[i]
+    assert np.array_equal(Xg, X) and np.array_equal(Vg, V)
+    eng.close()
+
+
+def test_least_squares_with_momentum(P):
+    n, d, rows, K, M, T = 8, 3000, 40, 500, 8, 3
+    _say("lsq momentum n=%d d=%d" % (n, d))
+    g = ring_graph(n)
+    feats, targs, _ = lsq_data(n, rows, d, seed=5, feature_var=1.0 / d)
+    sched = oracle.make_schedule(g, K, seed=5, T_max=T, M=M, rows=[rows] * n)
+    eng = P.Engine(g, d, "lsq", M=M, gamma=0.2, T_max=T, momentum=0.9, weight_decay=1e-4)
+    eng.load_data(feats, targs)
+    eng.set_models(np.zeros(d, np.float32))
+    eng.run_events(sched, want_loss=True)
+    Xg, Vg, lg = eng.get_models(), eng.get_momentum(), eng.get_loss()
+    Xr, Vr = np.zeros((n, d), np.float32), np.zeros((n, d), np.float32)
+    r = oracle.run_events(Xr, sched, oracle.MODEL_LSQ, 0.2, M=M, gscale=1.0 / M, features=feats, targets=targs,
+                          momentum=0.9, weight_decay=1e-4, V=Vr, want_loss=True)
+    assert rel_err(Xg, Xr) <= TOL and rel_err(Vg, Vr) <= 5 * TOL
+    assert np.allclose(lg, r["loss"], rtol=2e-4, atol=1e-7)
+    assert r["loss"][-50:].mean() < 0.5 * r["loss"][:50].mean()
+    eng.close()
+
+
+def test_momentum_without_buffer_is_refused(P):
+    import torch
+    X = torch.zeros((4, 64), dtype=torch.float32, device="cuda:0")
+    with pytest.raises(P.AdpsgdError) as ei:
+        P.Handle(ring_graph(4), 64, model=P.MODEL_SYNTH, X_ptr=X.data_ptr(), ldx=64, gamma=0.1, momentum=0.9)
+    assert ei.value.code == -1
