@@ -123,11 +123,12 @@ def minibatch_gradient(model, xhat, features, targets, idx, gscale, lam=0.0, mlp
 def run_events(X, schedule, model, gamma, *, M=0, gscale=1.0, lam=0.0, mlp=(0, 0, 0),
                features=None, targets=None, gamma_k=None, synth_std=0.0, synth_seed=0,
                event_base=0, coords=None, mode=1, want_loss=False, want_g=False,
-               momentum=0.0, weight_decay=0.0, V=None):
+               momentum=0.0, weight_decay=0.0, V=None, extra_pairs=None):
     """Run the events of ``schedule`` on X (n x d fp32, C-contiguous) IN PLACE.
 
     mode 0 = literal snapshot history, mode 1 = parked gradients (same values).
     V (n x d fp32, updated in place) switches to the momentum / weight-decay form of the update.
+    extra_pairs = (ptr[K+1], a[], b[]): further disjoint pairs averaged by W_k in event k.
     Returns a dict with optional 'loss' (K,) and 'g' (K, d)."""
     assert X.dtype == np.float32 and X.flags.c_contiguous and X.ndim == 2
     n, d = X.shape
@@ -155,6 +156,12 @@ def run_events(X, schedule, model, gamma, *, M=0, gscale=1.0, lam=0.0, mlp=(0, 0
     gk = None if gamma_k is None else np.ascontiguousarray(gamma_k, dtype=np.float32)
     if V is not None:
         assert V.dtype == np.float32 and V.flags.c_contiguous and V.shape == X.shape
+    eptr = ea = eb = None
+    if extra_pairs is not None:
+        eptr = np.ascontiguousarray(extra_pairs[0], dtype=np.int64)
+        ea = np.ascontiguousarray(extra_pairs[1], dtype=np.int32)
+        eb = np.ascontiguousarray(extra_pairs[2], dtype=np.int32)
+        assert eptr.size == K + 1 and ea.size == eb.size == eptr[-1]
     loss = np.zeros(K, dtype=np.float64) if want_loss else None
     glog = np.zeros((K, d), dtype=np.float32) if want_g else None
     rc = lib().oracle_run_events(
@@ -165,7 +172,7 @@ def run_events(X, schedule, model, gamma, *, M=0, gscale=1.0, lam=0.0, mlp=(0, 0
         _p(coords, C.c_int64), C.c_int64(K), _p(worker, C.c_int32), _p(nbr, C.c_int32),
         _p(tau, C.c_int32), _p(batch, C.c_int32), C.c_int(mode), _p(loss, C.c_double),
         _p(glog, C.c_float), C.c_float(momentum), C.c_float(weight_decay), _p(V, C.c_float),
-        C.c_int64(d))
+        C.c_int64(d), _p(eptr, C.c_int64), _p(ea, C.c_int32), _p(eb, C.c_int32))
     del keep
     if rc != 0:
         raise ValueError("oracle_run_events failed with code %d" % rc)

@@ -441,7 +441,8 @@ int oracle_run_events(int32_t n, int64_t d, float* X, int64_t ldx, int model, in
                       const int64_t* coords, int64_t K, const int32_t* worker,
                       const int32_t* neighbour, const int32_t* tau, const int32_t* batch_idx,
                       int mode, double* loss, float* g_log, float momentum, float weight_decay,
-                      float* V, int64_t ldv)
+                      float* V, int64_t ldv, const int64_t* extra_ptr, const int32_t* extra_a,
+                      const int32_t* extra_b)
 {
     if (n < 1 || d < 1 || ldx < d || K < 0) return -1;
     grad_spec spec = { model, d, M, gscale, lambda, mlp_in, mlp_hid, mlp_out };
@@ -503,6 +504,20 @@ int oracle_run_events(int32_t n, int64_t d, float* X, int64_t ldx, int model, in
         if (loss) loss[k] = lk;
         if (g_log) memcpy(g_log + (size_t)k * d, g, sizeof(float) * (size_t)d);
 
+        /* general averaging matrix: W_k may average further disjoint pairs of workers in the same
+         * event (Sec. 3.2: "W can be an arbitrary doubly stochastic matrix"); a product of disjoint
+         * pairwise averagings is symmetric and doubly stochastic.  Those pairs carry no gradient. */
+        if (extra_ptr) {
+            for (int64_t q = extra_ptr[k]; q < extra_ptr[k + 1]; ++q) {
+                float* xa = X + (size_t)extra_a[q] * ldx;
+                float* xb = X + (size_t)extra_b[q] * ldx;
+                for (int64_t e = 0; e < d; ++e) {
+                    float avg = (xa[e] + xb[e]) * 0.5f;
+                    xa[e] = avg;
+                    xb[e] = avg;
+                }
+            }
+        }
         const float gam = gamma_k ? gamma_k[k] : gamma;
         float* xi = X + (size_t)i * ldx;
         float* xj = X + (size_t)j * ldx;

@@ -526,3 +526,75 @@ def test_weight_decay_acts_on_the_averaged_model():
     oracle.run_events(X, sched, SYNTH, 0.5, synth_std=0.0, momentum=0.5, weight_decay=0.0, V=V)
     avg = (2.625 + 3.0) / 2
     assert V[0, 0] == 0.375 and X[0, 0] == np.float32(avg - 0.5 * 0.375) and X[1, 0] == np.float32(avg)
+
+
+# --------------------------------------------------------------------------- general averaging matrix W_k
+def test_multi_pair_W_is_doubly_stochastic_and_oracle_applies_it():
+    """W_k = product of disjoint pairwise averagings: symmetric, doubly stochastic, idempotent;
+    with g = 0 the oracle computes exactly X <- W X."""
+    from workloads import random_extra_pairs
+    n, d, K = 9, 5, 12
+    g = random_regular4_graph(n, 3)
+    sched = oracle.make_schedule(g, K, seed=6)
+    extra = random_extra_pairs(g, sched["worker"], sched["neighbour"], max_extra=3, seed=1)
+    assert extra[0][-1] > K // 2                       # the extension is exercised
+    X0 = np.random.default_rng(2).integers(-512, 512, (n, d)).astype(np.float32) * 2.0 ** 20   # 12 exact halvings
+    X = X0.copy()
+    oracle.run_events(X, sched, SYNTH, 0.0, synth_std=0.0, extra_pairs=extra)
+    ref = X0.astype(np.float64)
+    for k in range(K):
+        W = np.eye(n)
+        pairs = [(sched["worker"][k], sched["neighbour"][k])] + [(extra[1][q], extra[2][q]) for q in range(extra[0][k], extra[0][k + 1])]
+        rows = [r for pr in pairs for r in pr]
+        assert len(set(rows)) == len(rows)             # disjoint
+        for a, b in pairs:
+            e = np.zeros((n, 1)); e[a] = 1; e[b] = -1
+            W = W @ (np.eye(n) - 0.5 * e @ e.T)
+        assert np.allclose(W, W.T) and np.all(W >= 0) and np.allclose(W.sum(0), 1) and np.allclose(W @ W, W)
+        ref = W @ ref
+    assert np.array_equal(X.astype(np.float64), ref)
+
+
+def test_multi_pair_events_keep_the_gradient_semantics():
+    """Extra pairs change only the averaging: the sum over workers still moves by -gamma g_k per event,
+    literal and parked forms agree, and dropping the extras changes the result."""
+    from workloads import random_extra_pairs
+    n, feats, targs, sched, X0 = _random_problem(6, 13, 10, 200, 4, 3, 1, LSQ)   # seed 1: 4-regular graph
+    g = random_regular4_graph(6, 1)
+    extra = random_extra_pairs(g, sched["worker"], sched["neighbour"], max_extra=2, seed=2)
+    Xa, Xb, Xc = X0.copy(), X0.copy(), X0.copy()
+    ra = oracle.run_events(Xa, sched, LSQ, 0.02, M=4, gscale=0.25, features=feats, targets=targs, mode=0,
+                           extra_pairs=extra, want_g=True)
+    oracle.run_events(Xb, sched, LSQ, 0.02, M=4, gscale=0.25, features=feats, targets=targs, mode=1, extra_pairs=extra)
+    oracle.run_events(Xc, sched, LSQ, 0.02, M=4, gscale=0.25, features=feats, targets=targs, mode=0)
+    assert np.array_equal(Xa, Xb) and not np.array_equal(Xa, Xc)
+    assert np.allclose(Xa.sum(0, dtype=np.float64), X0.sum(0, dtype=np.float64) - 0.02 * ra["g"].sum(0, dtype=np.float64),
+                       rtol=0, atol=2e-5)
+
+
+def test_hop_ring_mixes_faster_than_the_ring():
+    """The ring with extra 2^i + 1 hop links (Sec. 3.3.2) has a smaller rho = lambda_2(E W): closed
+    form from the circulant Laplacian, and the oracle's gossip-only runs follow (E W)^K."""
+    from workloads import hop_ring_graph
+    n, K, S = 16, 40, 1500
+    def expected_W(graph):
+        rowptr, col = graph
+        EW = np.zeros((n, n))
+        for i in range(n):
+            nb = col[rowptr[i]:rowptr[i + 1]]
+            for j in nb:
+                e = np.zeros((n, 1)); e[i] = 1; e[j] = -1
+                EW += (np.eye(n) - 0.5 * e @ e.T) / (n * len(nb))
+        return EW
+    rho = {}
+    for name, graph in (("ring", ring_graph(n)), ("hop", hop_ring_graph(n))):
+        EW = expected_W(graph)
+        rho[name] = np.sort(np.linalg.eigvalsh(EW))[-2]
+        acc = np.zeros((n, n))
+        for s in range(S):
+            X = np.eye(n, dtype=np.float32)
+            oracle.run_events(X, oracle.make_schedule(graph, K, seed=500 + s), SYNTH, 0.0, synth_std=0.0)
+            acc += X
+        assert np.max(np.abs(acc / S - np.linalg.matrix_power(EW, K))) < 5 * 0.35 / np.sqrt(S)
+    assert np.isclose(rho["ring"], 1 - (1 - np.cos(2 * np.pi / n)) / n)
+    assert rho["hop"] < rho["ring"] - 0.02
