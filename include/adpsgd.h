@@ -121,6 +121,14 @@ typedef struct {
     const int32_t* tau;       /* tau_k                                           */
     const int32_t* batch_idx; /* K x M sample indices xi_k (NULL for SYNTH)      */
     const float* gamma;       /* K per-event step sizes, or NULL                 */
+    /* General averaging matrix (Sec. 3.2: W may be any doubly stochastic matrix): event k may
+     * average further pairs of neighbours (extra_a[q], extra_b[q]), extra_ptr[k] <= q < extra_ptr[k+1],
+     * in the same W_k.  All rows of one event (worker, neighbour, extras) must be distinct and every
+     * extra pair must be an edge of the graph; W_k is then the product of disjoint pairwise
+     * averagings (symmetric, doubly stochastic).  Extra pairs carry no gradient.  NULL = none. */
+    const int64_t* extra_ptr; /* K + 1 entries, extra_ptr[0] = 0                  */
+    const int32_t* extra_a;
+    const int32_t* extra_b;
 } adpsgd_schedule_t;
 
 /* Parameters of the built-in schedule generator (all host memory). */
@@ -213,11 +221,13 @@ int adpsgd_make_schedule(const adpsgd_sched_params_t* p, uint64_t seed, uint64_t
  * is written twice or read and written in the wrong order, and executing the
  * rounds in order (reads of a round before its updates) equals executing the
  * events one by one.  Outputs are host arrays of K entries; *n_rounds receives
- * the number of rounds.  Returns ADPSGD_ERR_SCHEDULE for tau[k] > k or
+ * the number of rounds.  extra_* as in adpsgd_schedule_t (NULL = none): the extra pairs of
+ * event k run in round u_round[k].  Returns ADPSGD_ERR_SCHEDULE for tau[k] > k or
  * n_slots <= max tau. */
 int adpsgd_plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
                        const int32_t* tau, int32_t n_slots, int32_t with_gradients,
-                       int32_t* r_round, int32_t* u_round, int32_t* slot, int32_t* n_rounds);
+                       int32_t* r_round, int32_t* u_round, int32_t* slot, int32_t* n_rounds,
+                       const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b);
 
 /* Fill a device buffer with the synthetic gradient g_k[0..d) of global event k
  * (ADPSGD_MODEL_SYNTH's generator), on `stream`.  For tests of the generator. */

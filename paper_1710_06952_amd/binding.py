@@ -47,7 +47,8 @@ class Opts(C.Structure):
 class Schedule(C.Structure):
     _fields_ = [("K", C.c_int64), ("worker", C.POINTER(C.c_int32)), ("neighbour", C.POINTER(C.c_int32)),
                 ("tau", C.POINTER(C.c_int32)), ("batch_idx", C.POINTER(C.c_int32)),
-                ("gamma", C.POINTER(C.c_float))]
+                ("gamma", C.POINTER(C.c_float)), ("extra_ptr", C.POINTER(C.c_int64)),
+                ("extra_a", C.POINTER(C.c_int32)), ("extra_b", C.POINTER(C.c_int32))]
 
 
 class SchedParams(C.Structure):
@@ -104,7 +105,8 @@ def lib():
         L.adpsgd_get_momentum.argtypes = [vp, vp, i64, i32]
         L.adpsgd_get_stats.argtypes = [vp, P(Stats)]
         L.adpsgd_make_schedule.argtypes = [P(SchedParams), u64, u64, i64, P(i32), P(i32), P(i32), P(i32)]
-        L.adpsgd_plan_rounds.argtypes = [i32, i64, P(i32), P(i32), P(i32), i32, i32, P(i32), P(i32), P(i32), P(i32)]
+        L.adpsgd_plan_rounds.argtypes = [i32, i64, P(i32), P(i32), P(i32), i32, i32, P(i32), P(i32), P(i32), P(i32),
+                                         P(i64), P(i32), P(i32)]
         L.adpsgd_synth_gradient.argtypes = [u64, u64, C.c_float, i64, vp, vp]
         _lib = L
     return _lib
@@ -143,14 +145,22 @@ def adpsgd_make_schedule(graph, K, seed=0, k_begin=0, T_max=0, tau_mode=0, weigh
     return {"worker": worker, "neighbour": nbr, "tau": tau, "batch_idx": batch}
 
 
-def adpsgd_plan_rounds(n, worker, neighbour, tau, n_slots, with_gradients=True):
+def _extra_arrays(extra_pairs):
+    if extra_pairs is None:
+        return None, None, None
+    return (np.ascontiguousarray(extra_pairs[0], dtype=np.int64), _as_i32(extra_pairs[1]), _as_i32(extra_pairs[2]))
+
+
+def adpsgd_plan_rounds(n, worker, neighbour, tau, n_slots, with_gradients=True, extra_pairs=None):
     """Host-only: the round planner on its own; returns (r_round, u_round, slot, n_rounds)."""
     worker, neighbour, tau = map(_as_i32, (worker, neighbour, tau))
     K = worker.size
     r, u, s = (np.zeros(K, np.int32) for _ in range(3))
     nr = C.c_int32(0)
+    ep, ea, eb = _extra_arrays(extra_pairs)
     rc = lib().adpsgd_plan_rounds(n, K, _i32p(worker), _i32p(neighbour), _i32p(tau), n_slots,
-                                  1 if with_gradients else 0, _i32p(r), _i32p(u), _i32p(s), C.byref(nr))
+                                  1 if with_gradients else 0, _i32p(r), _i32p(u), _i32p(s), C.byref(nr),
+                                  None if ep is None else ep.ctypes.data_as(C.POINTER(C.c_int64)), _i32p(ea), _i32p(eb))
     if rc != OK:
         raise AdpsgdError(rc, "adpsgd_plan_rounds failed")
     return r, u, s, nr.value
@@ -208,8 +218,10 @@ class Handle:
         batch = _as_i32(schedule.get("batch_idx"))
         gam = schedule.get("gamma")
         gam = None if gam is None else np.ascontiguousarray(gam, dtype=np.float32)
+        ep, ea, eb = _extra_arrays(schedule.get("extra_pairs"))
         s = Schedule(worker.size, _i32p(worker), _i32p(nbr), _i32p(tau), _i32p(batch),
-                     None if gam is None else gam.ctypes.data_as(C.POINTER(C.c_float)))
+                     None if gam is None else gam.ctypes.data_as(C.POINTER(C.c_float)),
+                     None if ep is None else ep.ctypes.data_as(C.POINTER(C.c_int64)), _i32p(ea), _i32p(eb))
         _check(self._h, lib().adpsgd_run_events(self._h, C.byref(s), loss_ptr))
 
     def get_models(self, out=None, ld_out=None, on_device=False):

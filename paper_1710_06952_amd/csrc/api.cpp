@@ -298,6 +298,26 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
     if (with_grad && !s->batch_idx) return fail(h, ADPSGD_ERR_ARG, "run_events: batch_idx is NULL");
 
     // ---- validation: nothing is launched and no state changes on failure ----
+    const int64_t n_extra = s->extra_ptr ? s->extra_ptr[K] : 0;
+    if (s->extra_ptr) {
+        if (s->extra_ptr[0] != 0 || n_extra < 0 || (n_extra > 0 && (!s->extra_a || !s->extra_b)))
+            return fail(h, ADPSGD_ERR_ARG, "run_events: malformed extra-pair arrays");
+        std::vector<int64_t> stamp(h->n, -1);
+        for (int64_t k = 0; k < K; ++k) {
+            if (s->extra_ptr[k + 1] < s->extra_ptr[k] || s->extra_ptr[k + 1] > n_extra)
+                return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: extra_ptr not monotone at event " + std::to_string(k));
+            if (s->worker[k] >= 0 && s->worker[k] < h->n) stamp[s->worker[k]] = k;
+            if (s->neighbour[k] >= 0 && s->neighbour[k] < h->n) stamp[s->neighbour[k]] = k;
+            for (int64_t q = s->extra_ptr[k]; q < s->extra_ptr[k + 1]; ++q) {
+                const int32_t a = s->extra_a[q], b = s->extra_b[q];
+                if (a < 0 || a >= h->n || b < 0 || b >= h->n || a == b || !is_neighbour(h, a, b))
+                    return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: extra pair is not an edge of the graph at event " + std::to_string(k));
+                if (stamp[a] == k || stamp[b] == k)
+                    return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: the pairs of one event must be disjoint (event " + std::to_string(k) + ")");
+                stamp[a] = stamp[b] = k;
+            }
+        }
+    }
     for (int64_t k = 0; k < K; ++k) {
         const int32_t i = s->worker[k], j = s->neighbour[k];
         if (i < 0 || i >= h->n || j < 0 || j >= h->n)
@@ -321,20 +341,21 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
     // ---- plan ----
     Plan plan;
     std::string perr;
-    int rc = plan_rounds(h->n, K, s->worker, s->neighbour, s->tau, h->n_slots, with_grad, plan, perr);
+    int rc = plan_rounds(h->n, K, s->worker, s->neighbour, s->tau, h->n_slots, with_grad, plan, perr,
+                         s->extra_ptr, s->extra_a, s->extra_b);
     if (rc != ADPSGD_OK) return fail(h, rc, perr);
     const int32_t R = plan.n_rounds;
 
     // counting sort of the operations by round
     std::vector<int64_t> u_off(static_cast<size_t>(R) + 1, 0), r_off(static_cast<size_t>(R) + 1, 0);
     for (int64_t k = 0; k < K; ++k) {
-        ++u_off[plan.u_round[k] + 1];
+        u_off[plan.u_round[k] + 1] += 1 + (s->extra_ptr ? s->extra_ptr[k + 1] - s->extra_ptr[k] : 0);
         if (with_grad) ++r_off[plan.r_round[k] + 1];
     }
     for (int32_t r = 0; r < R; ++r) { u_off[r + 1] += u_off[r]; r_off[r + 1] += r_off[r]; }
 
     // ---- tables: [PairOp x K][GradOp x K][batch_idx K x M][WorkerDataDev x n] ----
-    const size_t bytes_u = static_cast<size_t>(K) * sizeof(PairOp);
+    const size_t bytes_u = static_cast<size_t>(K + n_extra) * sizeof(PairOp);
     const size_t bytes_r = with_grad ? static_cast<size_t>(K) * sizeof(GradOp) : 0;
     const size_t bytes_b = with_grad ? static_cast<size_t>(K) * M * sizeof(int32_t) : 0;
     const size_t off_r = bytes_u, off_b = (off_r + bytes_r + 15) & ~size_t(15);
@@ -362,7 +383,13 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
             u.k_hi = static_cast<uint32_t>(gk >> 32);
             u.gamma = s->gamma ? s->gamma[k] : h->o.gamma;
             u.slot = with_grad ? plan.slot[k] : 0;
-            u.pad0 = u.pad1 = 0;
+            u.flags = u.pad1 = 0;
+            if (s->extra_ptr) {
+                for (int64_t q = s->extra_ptr[k]; q < s->extra_ptr[k + 1]; ++q) {
+                    PairOp& x = uops[u_fill[plan.u_round[k]]++];
+                    x = PairOp{s->extra_a[q], s->extra_b[q], 0u, 0u, 0.0f, 0, 1, 0};
+                }
+            }
             if (with_grad) {
                 GradOp& g = rops[r_fill[plan.r_round[k]]++];
                 g.worker = s->worker[k];

@@ -19,7 +19,8 @@ struct alignas(32) PairOp {
     uint32_t k_hi;
     float gamma;
     int32_t slot;     // pending-gradient slot holding g_k (data models)
-    int32_t pad0, pad1;
+    int32_t flags;    // bit 0: average only (an extra pair of a general W_k): no gradient, no step
+    int32_t pad1;
 };
 
 // One stale read / gradient evaluation as the gradient kernels see it.
@@ -61,7 +62,8 @@ struct DevBuf {
 void philox4x32_10_host(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
 int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
                 const int32_t* tau, int32_t n_slots, bool with_gradients, Plan& plan,
-                std::string& err);
+                std::string& err, const int64_t* extra_ptr = nullptr, const int32_t* extra_a = nullptr,
+                const int32_t* extra_b = nullptr);
 bool graph_ok(const adpsgd_graph_t* g, std::string& err);
 
 // ---- kernel launchers (each returns the hipError_t of the launch) ------------

@@ -83,6 +83,7 @@ __global__ __launch_bounds__(kThreads) void fused_gossip_apply_kernel(const Fuse
     float* __restrict__ xj = p.X + static_cast<int64_t>(op.j) * p.ld;
     const float* __restrict__ gs = SYNTH ? nullptr : p.slots + static_cast<int64_t>(op.slot) * p.ld;
     const bool pair = !SOLO || op.i != op.j;
+    const bool average_only = (op.flags & 1) != 0;   // extra pair of a general W_k: no gradient, no step
     const int64_t tile = static_cast<int64_t>(blockIdx.x) * kTileElems;
     const int64_t e0 = tile + threadIdx.x;
 
@@ -94,13 +95,25 @@ __global__ __launch_bounds__(kThreads) void fused_gossip_apply_kernel(const Fuse
         if (e < p.d) {     // (no default values: initialising a/b/g costs 3.5 % of the bandwidth)
             a[u] = load1<STREAM>(xi + e);
             b[u] = load1<STREAM>(xj + e);
-            if (!SYNTH) g[u] = load1<STREAM>(gs + e);
-            if (MOM) vold[u] = load1<STREAM>(vi + e);
+            if (!SYNTH && !average_only) g[u] = load1<STREAM>(gs + e);
+            if (MOM && !average_only) vold[u] = load1<STREAM>(vi + e);
         }
     }
-#ifdef ADPSGD_EXPERIMENT_NO_LDS
-    if (SYNTH) { for (int u = 0; u < kUnroll; ++u) g[u] = p.synth_std; } else
-#endif
+    if (average_only) {       // uniform over the block
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t e = e0 + u * kThreads;
+            if (e >= p.d) continue;
+            const float avg = (a[u] + b[u]) * 0.5f;
+            store1<STREAM>(xi + e, avg);
+            store1<STREAM>(xj + e, avg);
+            if (SHADOW) {
+                p.Xbf16[static_cast<int64_t>(op.i) * p.ld + e] = bf16_rne(avg);
+                p.Xbf16[static_cast<int64_t>(op.j) * p.ld + e] = bf16_rne(avg);
+            }
+        }
+        return;
+    }
     if (SYNTH) {
         // One generator call yields the gradient of 4 consecutive elements.  Lane c of wavefront w
         // produces the c-th of the 64 quads that wavefront touches (quad c lies in pass c / 16) and

@@ -21,7 +21,7 @@ namespace adpsgd_impl {
 
 int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
                 const int32_t* tau, int32_t n_slots, bool with_gradients, Plan& plan,
-                std::string& err) {
+                std::string& err, const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b) {
     plan.r_round.assign(static_cast<size_t>(K), -1);
     plan.u_round.assign(static_cast<size_t>(K), -1);
     plan.slot.assign(static_cast<size_t>(K), -1);
@@ -71,6 +71,14 @@ int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neig
         int32_t u = std::max(last_write[i], last_write[j]) + 1;
         u = std::max(u, std::max(last_read[i], last_read[j]));
         if (with_gradients) u = std::max(u, plan.r_round[t]);
+        if (extra_ptr) {      // every pair of W_t runs in the event's round
+            for (int64_t q = extra_ptr[t]; q < extra_ptr[t + 1]; ++q) {
+                const int32_t a = extra_a[q], b = extra_b[q];
+                u = std::max(u, std::max(last_write[a], last_write[b]) + 1);
+                u = std::max(u, std::max(last_read[a], last_read[b]));
+            }
+            for (int64_t q = extra_ptr[t]; q < extra_ptr[t + 1]; ++q) last_write[extra_a[q]] = last_write[extra_b[q]] = u;
+        }
         plan.u_round[t] = u;
         last_write[i] = last_write[j] = u;
         rounds = std::max(rounds, u);
@@ -90,14 +98,22 @@ using namespace adpsgd_impl;
 
 extern "C" int adpsgd_plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
                                   const int32_t* tau, int32_t n_slots, int32_t with_gradients,
-                                  int32_t* r_round, int32_t* u_round, int32_t* slot, int32_t* n_rounds) {
+                                  int32_t* r_round, int32_t* u_round, int32_t* slot, int32_t* n_rounds,
+                                  const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b) {
     if (n < 1 || K < 0 || !worker || !neighbour || !tau || !r_round || !u_round || !slot || !n_rounds)
         return ADPSGD_ERR_ARG;
     for (int64_t k = 0; k < K; ++k)
         if (worker[k] < 0 || worker[k] >= n || neighbour[k] < 0 || neighbour[k] >= n) return ADPSGD_ERR_SCHEDULE;
+    if (extra_ptr) {
+        if (!extra_a || !extra_b || extra_ptr[0] != 0) return ADPSGD_ERR_ARG;
+        for (int64_t k = 0; k < K; ++k)
+            if (extra_ptr[k + 1] < extra_ptr[k]) return ADPSGD_ERR_SCHEDULE;
+        for (int64_t q = 0; q < extra_ptr[K]; ++q)
+            if (extra_a[q] < 0 || extra_a[q] >= n || extra_b[q] < 0 || extra_b[q] >= n) return ADPSGD_ERR_SCHEDULE;
+    }
     Plan plan;
     std::string err;
-    const int rc = plan_rounds(n, K, worker, neighbour, tau, n_slots, with_gradients != 0, plan, err);
+    const int rc = plan_rounds(n, K, worker, neighbour, tau, n_slots, with_gradients != 0, plan, err, extra_ptr, extra_a, extra_b);
     if (rc != ADPSGD_OK) return rc;
     std::copy(plan.r_round.begin(), plan.r_round.end(), r_round);
     std::copy(plan.u_round.begin(), plan.u_round.end(), u_round);

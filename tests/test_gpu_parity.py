@@ -456,3 +456,69 @@ def test_momentum_without_buffer_is_refused(P):
     with pytest.raises(P.AdpsgdError) as ei:
         P.Handle(ring_graph(4), 64, model=P.MODEL_SYNTH, X_ptr=X.data_ptr(), ldx=64, gamma=0.1, momentum=0.9)
     assert ei.value.code == -1
+
+
+# ------------------------------------------------------------------ other topologies and general W_k
+def test_hop_ring_topology(P):
+    """The ring with the paper's extra 2^i + 1 hop links (Sec. 3.3.2) is just another graph."""
+    from workloads import hop_ring_graph
+    n, d, K, T = 16, 3000, 500, 4
+    g = hop_ring_graph(n)
+    assert all(g[0][i + 1] - g[0][i] >= 6 for i in range(n))
+    sched = P.adpsgd_make_schedule(g, K, seed=7, T_max=T)
+    ref = oracle.make_schedule(g, K, seed=7, T_max=T)
+    assert all(np.array_equal(sched[k], ref[k]) for k in ("worker", "neighbour", "tau"))
+    assert np.any(np.abs(sched["worker"] - sched["neighbour"]) % n > 1)       # long links are used
+    std = float(np.float32(0.03))
+    eng = P.Engine(g, d, "synth", gamma=0.1, T_max=T, synth_std=std, synth_seed=1)
+    eng.set_models(np.zeros(d, np.float32))
+    eng.run_events(sched)
+    Xr = np.zeros((n, d), np.float32)
+    oracle.run_events(Xr, ref, oracle.MODEL_SYNTH, 0.1, synth_std=std, synth_seed=1)
+    assert rel_err(eng.get_models(), Xr) <= TOL
+    assert np.isclose(eng.consensus_distance(), oracle.consensus_distance(Xr), rtol=1e-4)
+    eng.close()
+
+
+@pytest.mark.parametrize("model", ["synth", "lsq", "synth_momentum"])
+def test_multi_pair_averaging_matrix(P, model):
+    """W_k averages up to 4 disjoint pairs per event."""
+    from workloads import random_extra_pairs
+    n, d, rows, K, M, T = 12, 2500, 20, 400, 4, 3
+    _say("multi-pair W_k, %s" % model)
+    g = random_regular4_graph(n, 5)
+    sched = oracle.make_schedule(g, K, seed=8, T_max=T, M=M if model == "lsq" else 0, rows=[rows] * n)
+    extra = random_extra_pairs(g, sched["worker"], sched["neighbour"], max_extra=3, seed=9)
+    gsched = dict(sched, extra_pairs=extra)
+    x0 = np.random.default_rng(3).standard_normal(d).astype(np.float32)
+    if model == "lsq":
+        feats, targs, _ = lsq_data(n, rows, d, seed=6, feature_var=1.0 / d)
+        eng = P.Engine(g, d, "lsq", M=M, gamma=0.5, T_max=T)
+        eng.load_data(feats, targs)
+        eng.set_models(x0)
+        eng.run_events(gsched)
+        Xr = np.tile(x0, (n, 1))
+        oracle.run_events(Xr, sched, oracle.MODEL_LSQ, 0.5, M=M, gscale=1.0 / M, features=feats, targets=targs, extra_pairs=extra)
+        assert rel_err(eng.get_models(), Xr) <= TOL
+    else:
+        mu, wd = (0.9, 1e-3) if model == "synth_momentum" else (0.0, 0.0)
+        eng = P.Engine(g, d, "synth", gamma=0.1, T_max=T, synth_std=0.5, synth_seed=3, momentum=mu, weight_decay=wd)
+        eng.set_models(x0)
+        eng.run_events(gsched)
+        Xr = np.tile(x0, (n, 1))
+        Vr = np.zeros((n, d), np.float32) if mu else None
+        oracle.run_events(Xr, sched, oracle.MODEL_SYNTH, 0.1, synth_std=0.5, synth_seed=3, extra_pairs=extra,
+                          momentum=mu, weight_decay=wd, V=Vr)
+        assert rel_err(eng.get_models(), Xr) <= TOL
+        if mu:
+            assert rel_err(eng.get_momentum(), Vr) <= TOL
+    st = eng.get_stats()
+    assert st["events"] == K
+    # malformed extras are refused: overlapping rows, and a pair that is not an edge
+    before = eng.get_models()
+    bad = dict(sched, extra_pairs=(np.array([0, 1] + [1] * (K - 1)), [sched["worker"][0]], [sched["neighbour"][0]]))
+    with pytest.raises(P.AdpsgdError) as ei:
+        eng.run_events(bad)
+    assert ei.value.code == -3
+    assert np.array_equal(eng.get_models(), before)
+    eng.close()

@@ -198,3 +198,39 @@ def test_planned_rounds_reproduce_the_oracle_bit_for_bit():
             X[j[k]] = avg
             X[w[k]] = avg - np.float32(0.02) * slots[slot[k]]
     assert np.array_equal(X, X_ref)
+
+
+def test_planner_with_multi_pair_events_reproduces_the_oracle():
+    """Events whose W_k averages several disjoint pairs: execute the plan on the CPU (every pair of an
+    event in the event's round) and compare with the oracle bit for bit."""
+    from workloads import random_extra_pairs
+    n, d, rows, K, M, T = 10, 16, 12, 500, 3, 4
+    g = random_regular4_graph(n, 2)
+    feats, targs, _ = lsq_data(n, rows, d, seed=1)
+    sched = oracle.make_schedule(g, K, seed=3, T_max=T, M=M, rows=[rows] * n)
+    extra = random_extra_pairs(g, sched["worker"], sched["neighbour"], max_extra=3, seed=4)
+    X_ref = np.tile(np.random.default_rng(0).standard_normal(d).astype(np.float32), (n, 1))
+    X = X_ref.copy()
+    oracle.run_events(X_ref, sched, oracle.MODEL_LSQ, 0.02, M=M, gscale=1.0 / M, features=feats, targets=targs,
+                      mode=0, extra_pairs=extra)
+    w, j, tau = sched["worker"], sched["neighbour"], sched["tau"]
+    r_round, u_round, slot, R = P.adpsgd_plan_rounds(n, w, j, tau, T + 2, True, extra_pairs=extra)
+    R_plain = P.adpsgd_plan_rounds(n, w, j, tau, T + 2, True)[3]
+    assert R >= R_plain                       # more rows per event can only lengthen the chains
+    slots = {}
+    for r in range(R):
+        for k in np.where(r_round == r)[0]:
+            slots[slot[k]] = oracle.minibatch_gradient(oracle.MODEL_LSQ, X[w[k]], feats[w[k]], targs[w[k]],
+                                                       sched["batch_idx"][k], 1.0 / M)[0]
+        touched = set()
+        for k in np.where(u_round == r)[0]:
+            pairs = [(w[k], j[k])] + [(extra[1][q], extra[2][q]) for q in range(extra[0][k], extra[0][k + 1])]
+            for a, b in pairs:
+                assert a not in touched and b not in touched
+                touched.update((a, b))
+            for a, b in pairs[1:]:
+                X[a] = X[b] = (X[a] + X[b]) * np.float32(0.5)
+            avg = (X[w[k]] + X[j[k]]) * np.float32(0.5)
+            X[j[k]] = avg
+            X[w[k]] = avg - np.float32(0.02) * slots[slot[k]]
+    assert np.array_equal(X, X_ref)
