@@ -123,12 +123,14 @@ def minibatch_gradient(model, xhat, features, targets, idx, gscale, lam=0.0, mlp
 def run_events(X, schedule, model, gamma, *, M=0, gscale=1.0, lam=0.0, mlp=(0, 0, 0),
                features=None, targets=None, gamma_k=None, synth_std=0.0, synth_seed=0,
                event_base=0, coords=None, mode=1, want_loss=False, want_g=False,
-               momentum=0.0, weight_decay=0.0, V=None, extra_pairs=None):
+               momentum=0.0, weight_decay=0.0, V=None, extra_pairs=None, local_compensation=False):
     """Run the events of ``schedule`` on X (n x d fp32, C-contiguous) IN PLACE.
 
     mode 0 = literal snapshot history, mode 1 = parked gradients (same values).
     V (n x d fp32, updated in place) switches to the momentum / weight-decay form of the update.
     extra_pairs = (ptr[K+1], a[], b[]): further disjoint pairs averaged by W_k in event k.
+    local_compensation: the wait-free variant (a worker applies its own pending gradient to the
+    copy it reads before computing the next one).
     Returns a dict with optional 'loss' (K,) and 'g' (K, d)."""
     assert X.dtype == np.float32 and X.flags.c_contiguous and X.ndim == 2
     n, d = X.shape
@@ -172,7 +174,8 @@ def run_events(X, schedule, model, gamma, *, M=0, gscale=1.0, lam=0.0, mlp=(0, 0
         _p(coords, C.c_int64), C.c_int64(K), _p(worker, C.c_int32), _p(nbr, C.c_int32),
         _p(tau, C.c_int32), _p(batch, C.c_int32), C.c_int(mode), _p(loss, C.c_double),
         _p(glog, C.c_float), C.c_float(momentum), C.c_float(weight_decay), _p(V, C.c_float),
-        C.c_int64(d), _p(eptr, C.c_int64), _p(ea, C.c_int32), _p(eb, C.c_int32))
+        C.c_int64(d), _p(eptr, C.c_int64), _p(ea, C.c_int32), _p(eb, C.c_int32),
+        C.c_int(1 if local_compensation else 0))
     del keep
     if rc != 0:
         raise ValueError("oracle_run_events failed with code %d" % rc)

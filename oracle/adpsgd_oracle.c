@@ -93,6 +93,8 @@ int oracle_make_schedule(int32_t n, const int32_t* rowptr, const int32_t* col,
                          int32_t* worker, int32_t* neighbour, int32_t* tau, int32_t* batch_idx)
 {
     if (n < 1 || K < 0 || T_max < 0 || M < 0) return -1;
+    if (tau_mode != 0 && (!tau_num || !tau_den)) return -1;
+    if (M > 0 && !rows) return -1;
     uint64_t wtotal = 0;
     if (weight) {
         for (int32_t i = 0; i < n; ++i) {
@@ -419,6 +421,17 @@ static void average_then_apply_momentum(float* xi, float* xj, float* vi, const f
     }
 }
 
+/* wait-free variant: the pulled copy with the worker's own pending gradient applied (fp32, the
+ * same two roundings as the update itself) */
+static const float* compensate(float* out, const float* row, const float* g_pending, float gamma, int64_t d)
+{
+    for (int64_t e = 0; e < d; ++e) {
+        float step = gamma * g_pending[e];
+        out[e] = row[e] - step;
+    }
+    return out;
+}
+
 /* ------------------------------------------------------------------------- */
 /* The event loop.                                                            */
 /*   mode 0 ("literal"): keeps the last T+1 snapshots X_{k-T..k} and reads    */
@@ -442,7 +455,7 @@ int oracle_run_events(int32_t n, int64_t d, float* X, int64_t ldx, int model, in
                       const int32_t* neighbour, const int32_t* tau, const int32_t* batch_idx,
                       int mode, double* loss, float* g_log, float momentum, float weight_decay,
                       float* V, int64_t ldv, const int64_t* extra_ptr, const int32_t* extra_a,
-                      const int32_t* extra_b)
+                      const int32_t* extra_b, int local_compensation)
 {
     if (n < 1 || d < 1 || ldx < d || K < 0) return -1;
     grad_spec spec = { model, d, M, gscale, lambda, mlp_in, mlp_hid, mlp_out };
@@ -479,6 +492,26 @@ int oracle_run_events(int32_t n, int64_t d, float* X, int64_t ldx, int model, in
         }
     }
 
+    /* wait-free variant: prev[k] = latest earlier event of the same worker whose gradient is pending
+     * (computed, not yet applied) when event k reads its model; g_keep[k'] keeps that gradient */
+    int64_t* prev = NULL;
+    float** g_keep = NULL;
+    float* xcomp = NULL;
+    if (local_compensation && model != MODEL_SYNTH) {
+        prev = (int64_t*)malloc(sizeof(int64_t) * ((size_t)K + 1));
+        g_keep = (float**)calloc((size_t)K + 1, sizeof(float*));
+        xcomp = (float*)malloc(sizeof(float) * (size_t)d);
+        int64_t* last_of = (int64_t*)malloc(sizeof(int64_t) * (size_t)n);
+        for (int32_t r = 0; r < n; ++r) last_of[r] = -1;
+        for (int64_t k = 0; k < K; ++k) {
+            const int64_t kp = last_of[worker[k]], s = k - tau[k];
+            prev[k] = (kp >= 0 && kp - tau[kp] <= s && s <= kp) ? kp : -1;
+            last_of[worker[k]] = k;
+        }
+        free(last_of);
+    }
+#define COMPENSATED(row, k_) (prev && prev[k_] >= 0 ? compensate(xcomp, (row), g_keep[prev[k_]], gamma_k ? gamma_k[prev[k_]] : gamma, d) : (row))
+
     for (int64_t k = 0; k < K; ++k) {
         const int32_t i = worker[k], j = neighbour[k];
         double lk = 0.0;
@@ -489,12 +522,16 @@ int oracle_run_events(int32_t n, int64_t d, float* X, int64_t ldx, int model, in
             float* snap = hist + (size_t)(k % (T + 1)) * (size_t)n * (size_t)d;
             for (int32_t r = 0; r < n; ++r) memcpy(snap + (size_t)r * d, X + (size_t)r * ldx, sizeof(float) * (size_t)d);
             const float* old = hist + (size_t)((k - tau[k]) % (T + 1)) * (size_t)n * (size_t)d;
-            lk = minibatch_gradient(&spec, &data, i, old + (size_t)i * d, batch_idx + k * (int64_t)M, g);
+            lk = minibatch_gradient(&spec, &data, i, COMPENSATED(old + (size_t)i * d, k), batch_idx + k * (int64_t)M, g);
         } else {
             for (int64_t q = bucket_head[k]; q >= 0; q = bucket_next[q]) {
                 parked[q] = (float*)malloc(sizeof(float) * (size_t)d);
-                parked_loss[q] = minibatch_gradient(&spec, &data, worker[q], X + (size_t)worker[q] * ldx,
+                parked_loss[q] = minibatch_gradient(&spec, &data, worker[q], COMPENSATED(X + (size_t)worker[q] * ldx, q),
                                                     batch_idx + q * (int64_t)M, parked[q]);
+                if (g_keep) {   /* a later read of this worker may need it before event q applies it */
+                    g_keep[q] = (float*)malloc(sizeof(float) * (size_t)d);
+                    memcpy(g_keep[q], parked[q], sizeof(float) * (size_t)d);
+                }
             }
             memcpy(g, parked[k], sizeof(float) * (size_t)d);
             lk = parked_loss[k];
@@ -503,6 +540,10 @@ int oracle_run_events(int32_t n, int64_t d, float* X, int64_t ldx, int model, in
         }
         if (loss) loss[k] = lk;
         if (g_log) memcpy(g_log + (size_t)k * d, g, sizeof(float) * (size_t)d);
+        if (g_keep && mode == 0) {   /* literal mode evaluates g_k at event k: keep it for later stale reads */
+            g_keep[k] = (float*)malloc(sizeof(float) * (size_t)d);
+            memcpy(g_keep[k], g, sizeof(float) * (size_t)d);
+        }
 
         /* general averaging matrix: W_k may average further disjoint pairs of workers in the same
          * event (Sec. 3.2: "W can be an arbitrary doubly stochastic matrix"); a product of disjoint
@@ -526,6 +567,8 @@ int oracle_run_events(int32_t n, int64_t d, float* X, int64_t ldx, int model, in
         else
             average_then_apply(xi, xj, g, gam, d);   /* j == i (no neighbour) degenerates to x -= gamma g */
     }
+    if (g_keep) for (int64_t k = 0; k < K; ++k) free(g_keep[k]);
+    free(g_keep); free(prev); free(xcomp);
     free(g); free(hist); free(parked); free(parked_loss); free(bucket_head); free(bucket_next);
     return 0;
 }

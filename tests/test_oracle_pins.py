@@ -224,6 +224,79 @@ def test_hand_expanded_two_workers(golden_dir):
             assert X[0, 0] == float(e0) and X[1, 0] == float(e1), name
 
 
+def test_waitfree_hand_expanded(golden_dir):
+    """Local compensation of the wait-free variant: values worked out by hand in the fixture."""
+    cases = [l.split() for l in open(os.path.join(golden_dir, "waitfree_two_workers_d1.txt"))
+             if l.strip() and not l.startswith("#")]
+    feats, targs = _unit_quadratic_data(2, [1.0])
+    assert len(cases) == 3
+    for c in cases:
+        name, comp, K = c[0], int(c[1]), int(c[2])
+        taus = [int(t) for t in c[3:3 + K]]
+        e0, e1 = float(c[3 + K]), float(c[4 + K])
+        for mode in (0, 1):
+            X = np.array([[1.0], [3.0]], dtype=np.float32)
+            sched = {"worker": [0] * K, "neighbour": [1] * K, "tau": taus,
+                     "batch_idx": np.zeros((K, 1), np.int32)}
+            oracle.run_events(X, sched, LSQ, 0.5, M=1, gscale=1.0, features=feats, targets=targs,
+                              mode=mode, local_compensation=bool(comp))
+            assert (X[0, 0], X[1, 0]) == (e0, e1), (name, mode, X.ravel())
+
+
+@pytest.mark.parametrize("model", [LSQ, LOGREG])
+def test_waitfree_single_worker_is_fresh_sgd(model):
+    """One worker, no neighbour, every gradient one event stale: the compensated read
+    X_{k-1} - gamma g_{k-1} IS X_k, so the wait-free variant must reproduce SGD without any
+    staleness bit for bit, while plain Algorithm 1 with the same schedule must not."""
+    d, rows, M, K = 24, 64, 4, 60
+    if model == LSQ:
+        feats, targs, _ = lsq_data(1, rows, d, seed=11)
+    else:
+        feats, targs, _ = logreg_data(1, rows, d, seed=11)
+    rng = np.random.default_rng(5)
+    batch = rng.integers(0, rows, size=(K, M)).astype(np.int32)
+    X0 = rng.standard_normal((1, d)).astype(np.float32)
+    base = {"worker": np.zeros(K, np.int32), "neighbour": np.zeros(K, np.int32), "batch_idx": batch}
+    stale = dict(base, tau=np.array([0] + [1] * (K - 1), np.int32))
+    fresh = dict(base, tau=np.zeros(K, np.int32))
+    kw = dict(M=M, gscale=1.0 / M, lam=0.01, features=feats, targets=targs)
+    ref = X0.copy()
+    oracle.run_events(ref, fresh, model, 0.05, **kw)
+    for mode in (0, 1):
+        X = X0.copy()
+        oracle.run_events(X, stale, model, 0.05, mode=mode, local_compensation=True, **kw)
+        assert np.array_equal(X, ref)
+        # with no staleness nothing is ever pending: the switch must change nothing
+        X = X0.copy()
+        oracle.run_events(X, fresh, model, 0.05, mode=mode, local_compensation=True, **kw)
+        assert np.array_equal(X, ref)
+    X = X0.copy()
+    oracle.run_events(X, stale, model, 0.05, **kw)
+    assert not np.array_equal(X, ref)
+
+
+def test_waitfree_modes_agree_on_random_schedule():
+    """Literal snapshot history and parked gradients give the same bits with compensation on,
+    with per-event step sizes (the compensation uses the pending event's own gamma)."""
+    n, d, rows, M, K = 6, 20, 32, 2, 300
+    graph = ring_graph(n)
+    feats, targs, _ = lsq_data(n, rows, d, seed=3)
+    sched = oracle.make_schedule(graph, K, seed=17, T_max=5, tau_mode=0, M=M, rows=[rows] * n)
+    gk = (0.02 + 0.01 * (np.arange(K) % 7)).astype(np.float32)
+    rng = np.random.default_rng(2)
+    X0 = rng.standard_normal((n, d)).astype(np.float32)
+    out = []
+    for mode in (0, 1):
+        X = X0.copy()
+        oracle.run_events(X, sched, LSQ, 0.0, M=M, gscale=1.0 / M, features=feats, targets=targs,
+                          gamma_k=gk, mode=mode, local_compensation=True)
+        out.append(X)
+    assert np.array_equal(out[0], out[1])
+    X = X0.copy()
+    oracle.run_events(X, sched, LSQ, 0.0, M=M, gscale=1.0 / M, features=feats, targets=targs, gamma_k=gk)
+    assert not np.array_equal(X, out[0])
+
+
 def _matrix_form_bruteforce(X0, diag, gamma, sched):
     """X_{k+1} = X_k W_k - gamma dg(X^_k) in exact rational arithmetic, with W_k and dg as
     explicit matrices and the whole history kept (columns = workers, as in the paper)."""
