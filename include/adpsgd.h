@@ -105,6 +105,15 @@ typedef struct {
     float weight_decay;
     float* V;            /* device, n x ldx fp32 momentum buffers, caller-owned; required when momentum or
                             weight_decay is non-zero, else NULL.  adpsgd_set_models zeroes it */
+    /* Wait-free variant (appendix "Wait-free (continuous) training and communication", the
+     * computation thread): a worker applies its own gradient that is computed but not yet applied
+     * to the copy it reads, and evaluates the next gradient there:
+     *     x^_k = X_{k - tau_k}[i_k] - gamma_k' g_k'
+     * where k' is the latest earlier event of worker i_k in the same call, taken when
+     * k' - tau_k' <= k - tau_k <= k' (else no compensation).  Linear models only (LSQ, LOGREG;
+     * ignored by SYNTH, whose gradients do not depend on the model); not with momentum or weight
+     * decay (ADPSGD_ERR_ARG). */
+    int32_t local_compensation;
 } adpsgd_opts_t;
 
 /* A batch of K events, all arrays in host memory, read during the call only.
@@ -222,12 +231,15 @@ int adpsgd_make_schedule(const adpsgd_sched_params_t* p, uint64_t seed, uint64_t
  * rounds in order (reads of a round before its updates) equals executing the
  * events one by one.  Outputs are host arrays of K entries; *n_rounds receives
  * the number of rounds.  extra_* as in adpsgd_schedule_t (NULL = none): the extra pairs of
- * event k run in round u_round[k].  Returns ADPSGD_ERR_SCHEDULE for tau[k] > k or
- * n_slots <= max tau. */
+ * event k run in round u_round[k].  local_compensation != 0 plans the wait-free variant
+ * (see adpsgd_opts_t): the gradient of event k then also waits for the gradient of the
+ * event k' it compensates with, and prev (K entries, may be NULL) receives k' or -1.
+ * Returns ADPSGD_ERR_SCHEDULE for tau[k] > k or n_slots <= max tau. */
 int adpsgd_plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
                        const int32_t* tau, int32_t n_slots, int32_t with_gradients,
                        int32_t* r_round, int32_t* u_round, int32_t* slot, int32_t* n_rounds,
-                       const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b);
+                       const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b,
+                       int32_t local_compensation, int64_t* prev);
 
 /* Fill a device buffer with the synthetic gradient g_k[0..d) of global event k
  * (ADPSGD_MODEL_SYNTH's generator), on `stream`.  For tests of the generator. */

@@ -41,7 +41,8 @@ class Opts(C.Structure):
                 ("synth_seed", C.c_uint64), ("mlp_in", C.c_int32), ("mlp_hidden", C.c_int32),
                 ("mlp_out", C.c_int32), ("X", C.c_void_p), ("ldx", C.c_int64), ("Xbf16", C.c_void_p),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_int64), ("stream", C.c_void_p),
-                ("flags", C.c_int32), ("momentum", C.c_float), ("weight_decay", C.c_float), ("V", C.c_void_p)]
+                ("flags", C.c_int32), ("momentum", C.c_float), ("weight_decay", C.c_float), ("V", C.c_void_p),
+                ("local_compensation", C.c_int32)]
 
 
 class Schedule(C.Structure):
@@ -106,7 +107,7 @@ def lib():
         L.adpsgd_get_stats.argtypes = [vp, P(Stats)]
         L.adpsgd_make_schedule.argtypes = [P(SchedParams), u64, u64, i64, P(i32), P(i32), P(i32), P(i32)]
         L.adpsgd_plan_rounds.argtypes = [i32, i64, P(i32), P(i32), P(i32), i32, i32, P(i32), P(i32), P(i32), P(i32),
-                                         P(i64), P(i32), P(i32)]
+                                         P(i64), P(i32), P(i32), i32, P(i64)]
         L.adpsgd_synth_gradient.argtypes = [u64, u64, C.c_float, i64, vp, vp]
         _lib = L
     return _lib
@@ -151,18 +152,24 @@ def _extra_arrays(extra_pairs):
     return (np.ascontiguousarray(extra_pairs[0], dtype=np.int64), _as_i32(extra_pairs[1]), _as_i32(extra_pairs[2]))
 
 
-def adpsgd_plan_rounds(n, worker, neighbour, tau, n_slots, with_gradients=True, extra_pairs=None):
-    """Host-only: the round planner on its own; returns (r_round, u_round, slot, n_rounds)."""
+def adpsgd_plan_rounds(n, worker, neighbour, tau, n_slots, with_gradients=True, extra_pairs=None,
+                       local_compensation=False):
+    """Host-only: the round planner on its own; returns (r_round, u_round, slot, n_rounds), and with
+    local_compensation also prev (the event whose pending gradient each read is compensated with)."""
     worker, neighbour, tau = map(_as_i32, (worker, neighbour, tau))
     K = worker.size
     r, u, s = (np.zeros(K, np.int32) for _ in range(3))
     nr = C.c_int32(0)
+    prev = np.zeros(K, np.int64)
     ep, ea, eb = _extra_arrays(extra_pairs)
     rc = lib().adpsgd_plan_rounds(n, K, _i32p(worker), _i32p(neighbour), _i32p(tau), n_slots,
                                   1 if with_gradients else 0, _i32p(r), _i32p(u), _i32p(s), C.byref(nr),
-                                  None if ep is None else ep.ctypes.data_as(C.POINTER(C.c_int64)), _i32p(ea), _i32p(eb))
+                                  None if ep is None else ep.ctypes.data_as(C.POINTER(C.c_int64)), _i32p(ea), _i32p(eb),
+                                  1 if local_compensation else 0, prev.ctypes.data_as(C.POINTER(C.c_int64)))
     if rc != OK:
         raise AdpsgdError(rc, "adpsgd_plan_rounds failed")
+    if local_compensation:
+        return r, u, s, nr.value, prev
     return r, u, s, nr.value
 
 
@@ -178,11 +185,12 @@ class Handle:
 
     def __init__(self, graph, d, *, model, X_ptr, ldx, M=0, gamma=0.0, lam=0.0, grad_sum=False, T_max=0,
                  synth_std=0.0, synth_seed=0, mlp=(0, 0, 0), Xbf16_ptr=None, workspace_ptr=None,
-                 workspace_bytes=0, stream=0, flags=0, momentum=0.0, weight_decay=0.0, V_ptr=None):
+                 workspace_bytes=0, stream=0, flags=0, momentum=0.0, weight_decay=0.0, V_ptr=None,
+                 local_compensation=False):
         g, keep = _graph_struct(graph)
         o = Opts(model, M, gamma, lam, 1 if grad_sum else 0, T_max, synth_std, synth_seed, mlp[0], mlp[1], mlp[2],
                  X_ptr, ldx, Xbf16_ptr, workspace_ptr, workspace_bytes, stream or None, flags,
-                 momentum, weight_decay, V_ptr)
+                 momentum, weight_decay, V_ptr, 1 if local_compensation else 0)
         self._h = C.c_void_p()
         self.n, self.d, self.M, self.model = g.n, d, M, model
         rc = lib().adpsgd_create(C.byref(self._h), C.byref(g), d, C.byref(o))

@@ -195,6 +195,12 @@ extern "C" int adpsgd_create(adpsgd_t** out, const adpsgd_graph_t* graph, int64_
         return fail(nullptr, ADPSGD_ERR_ARG, "create: momentum or weight_decay not finite");
     if ((o.momentum != 0.0f || o.weight_decay != 0.0f) && (!o.V || !aligned16(o.V)))
         return fail(nullptr, ADPSGD_ERR_ARG, "create: momentum / weight decay need the buffer V (16-byte aligned)");
+    if (o.local_compensation) {
+        if (o.model == ADPSGD_MODEL_MLP)
+            return fail(nullptr, ADPSGD_ERR_ARG, "create: local_compensation is implemented for the linear models only");
+        if (o.momentum != 0.0f || o.weight_decay != 0.0f)
+            return fail(nullptr, ADPSGD_ERR_ARG, "create: local_compensation cannot be combined with momentum or weight decay");
+    }
     int count = 0;
     if (hipGetDeviceCount(&count) != hipSuccess || count < 1)
         return fail(nullptr, ADPSGD_ERR_HIP, "create: no HIP device available");
@@ -342,7 +348,7 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
     Plan plan;
     std::string perr;
     int rc = plan_rounds(h->n, K, s->worker, s->neighbour, s->tau, h->n_slots, with_grad, plan, perr,
-                         s->extra_ptr, s->extra_a, s->extra_b);
+                         s->extra_ptr, s->extra_a, s->extra_b, h->o.local_compensation != 0);
     if (rc != ADPSGD_OK) return fail(h, rc, perr);
     const int32_t R = plan.n_rounds;
 
@@ -395,7 +401,10 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
                 g.worker = s->worker[k];
                 g.slot = plan.slot[k];
                 g.event = static_cast<int32_t>(k);
-                g.pad = 0;
+                const int64_t kp = plan.prev[k];
+                g.comp_slot = kp >= 0 ? plan.slot[kp] : -1;
+                g.comp_gamma = kp >= 0 ? (s->gamma ? s->gamma[kp] : h->o.gamma) : 0.0f;
+                g.pad[0] = g.pad[1] = g.pad[2] = 0;
             }
         }
     }

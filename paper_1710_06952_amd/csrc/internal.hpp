@@ -28,7 +28,9 @@ struct GradOp {
     int32_t worker;   // row read, and owner of the local data
     int32_t slot;     // where g_k goes
     int32_t event;    // index into the call's batch_idx / loss arrays
-    int32_t pad;
+    int32_t comp_slot;   // wait-free variant: slot of the worker's own pending gradient g_k', or -1
+    float comp_gamma;    // its step size: the read is x^ = row - comp_gamma * g_k'
+    int32_t pad[3];
 };
 
 struct WorkerData {
@@ -47,6 +49,7 @@ struct WorkerDataDev {
 
 struct Plan {
     std::vector<int32_t> r_round, u_round, slot;
+    std::vector<int64_t> prev;   // wait-free variant: event whose pending gradient compensates the read, or -1
     int32_t n_rounds = 0;
 };
 
@@ -63,7 +66,7 @@ void philox4x32_10_host(const uint32_t ctr[4], const uint32_t key[2], uint32_t o
 int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
                 const int32_t* tau, int32_t n_slots, bool with_gradients, Plan& plan,
                 std::string& err, const int64_t* extra_ptr = nullptr, const int32_t* extra_a = nullptr,
-                const int32_t* extra_b = nullptr);
+                const int32_t* extra_b = nullptr, bool local_compensation = false);
 bool graph_ok(const adpsgd_graph_t* g, std::string& err);
 
 // ---- kernel launchers (each returns the hipError_t of the launch) ------------

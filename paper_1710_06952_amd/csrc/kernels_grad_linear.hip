@@ -5,6 +5,10 @@
 //   least squares        grad F = a (a.x - b)
 //   logistic regression  grad F = -y sigmoid(-y a.x) a + lambda x
 //
+// Wait-free variant (computation thread of the appendix on wait-free training): an operation
+// may carry the slot of the worker's own pending gradient g_k'; the point of evaluation is then
+// x^ = row - gamma_k' g_k' (two fp32 roundings, the same as the update itself).
+//
 // Three launches per group of gradient operations:
 //   1. dots:     partial z[op][m][chunk] = A[idx_m, chunk] . x^[chunk]   (batched GEMV, HBM bound)
 //   2. finalize: z -> per-sample coefficient c_m and the minibatch loss
@@ -64,6 +68,17 @@ __device__ __forceinline__ v4f zero_beyond(v4f v, int64_t e, int64_t d) {
     }
     return v;
 }
+// the stale read of one operation, four elements at vector index v (v < n_vec)
+__device__ __forceinline__ v4f read_xhat(const LinParams& p, const GradOp& op, int64_t v) {
+#pragma clang fp contract(off)
+    v4f x = *reinterpret_cast<const v4f*>(p.X + static_cast<int64_t>(op.worker) * p.ld + 4 * v);
+    if (op.comp_slot >= 0) {
+        const v4f g = *reinterpret_cast<const v4f*>(p.slots + static_cast<int64_t>(op.comp_slot) * p.ld + 4 * v);
+        const v4f step = g * op.comp_gamma;
+        x = x - step;
+    }
+    return x;
+}
 __device__ __forceinline__ float dot4(v4f a, v4f b) { return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w; }
 
 // grid = (n_chunks, ceil((M+1) / kRowsPerBlock), n_ops); "row" M is x^ itself (|x^|^2 for the regulariser)
@@ -75,7 +90,6 @@ __global__ __launch_bounds__(kThreads) void linear_dots_kernel(const LinParams p
     const GradOp op = p.ops[blockIdx.z];
     const WorkerDataDev wd = p.data[op.worker];
     const float* __restrict__ A = static_cast<const float*>(wd.features);
-    const float* __restrict__ xrow = p.X + static_cast<int64_t>(op.worker) * p.ld;
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const int64_t v0 = static_cast<int64_t>(blockIdx.x) * (kDotChunk / 4) + threadIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -84,7 +98,7 @@ __global__ __launch_bounds__(kThreads) void linear_dots_kernel(const LinParams p
 #pragma unroll
     for (int u = 0; u < kDotUnroll; ++u) {
         const int64_t v = v0 + static_cast<int64_t>(u) * kThreads;
-        xh[u] = v < p.n_vec ? zero_beyond(*reinterpret_cast<const v4f*>(xrow + 4 * v), 4 * v, p.d) : v4f{0, 0, 0, 0};
+        xh[u] = v < p.n_vec ? zero_beyond(read_xhat(p, op, v), 4 * v, p.d) : v4f{0, 0, 0, 0};
     }
     const int m_begin = blockIdx.y * kRowsPerBlock;
 #pragma unroll ADPSGD_DOT_ROWUNROLL
@@ -92,12 +106,17 @@ __global__ __launch_bounds__(kThreads) void linear_dots_kernel(const LinParams p
         const int m = m_begin + r;
         if (m > p.M) break;
         if (m == p.M && p.model != ADPSGD_MODEL_LOGREG) break;
-        const float* __restrict__ row = m < p.M ? A + static_cast<int64_t>(idx[m]) * wd.ld : xrow;
         float acc = 0.0f;
+        if (m < p.M) {
+            const float* __restrict__ row = A + static_cast<int64_t>(idx[m]) * wd.ld;
 #pragma unroll
-        for (int u = 0; u < kDotUnroll; ++u) {
-            const int64_t v = v0 + static_cast<int64_t>(u) * kThreads;
-            if (v < p.n_vec) acc += dot4(zero_beyond(load4<STREAM>(row + 4 * v), 4 * v, p.d), xh[u]);
+            for (int u = 0; u < kDotUnroll; ++u) {
+                const int64_t v = v0 + static_cast<int64_t>(u) * kThreads;
+                if (v < p.n_vec) acc += dot4(zero_beyond(load4<STREAM>(row + 4 * v), 4 * v, p.d), xh[u]);
+            }
+        } else {   // |x^|^2 of this chunk
+#pragma unroll
+            for (int u = 0; u < kDotUnroll; ++u) acc += dot4(xh[u], xh[u]);
         }
         acc = wave_sum(acc);
         if (lane == 0) red[wave][r] = acc;
@@ -194,7 +213,7 @@ __global__ __launch_bounds__(kThreads) void linear_combine_kernel(const LinParam
         acc += a * cf[m];
     }
     if (p.model == ADPSGD_MODEL_LOGREG) {
-        const v4f xh = *reinterpret_cast<const v4f*>(p.X + static_cast<int64_t>(op.worker) * p.ld + 4 * v);
+        const v4f xh = read_xhat(p, op, v);
         acc += xh * (p.lambda * p.gscale * static_cast<float>(p.M));
     }
     acc = zero_beyond(acc, 4 * v, p.d);

@@ -21,10 +21,12 @@ namespace adpsgd_impl {
 
 int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
                 const int32_t* tau, int32_t n_slots, bool with_gradients, Plan& plan,
-                std::string& err, const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b) {
+                std::string& err, const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b,
+                bool local_compensation) {
     plan.r_round.assign(static_cast<size_t>(K), -1);
     plan.u_round.assign(static_cast<size_t>(K), -1);
     plan.slot.assign(static_cast<size_t>(K), -1);
+    plan.prev.assign(static_cast<size_t>(K), -1);
     plan.n_rounds = 0;
 
     // rounds are numbered from 1 while planning (0 = "never touched"), shifted to 0 at the end
@@ -47,6 +49,18 @@ int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neig
             return ADPSGD_ERR_SCHEDULE;
         }
     }
+    // Wait-free variant: R_k also reads the pending gradient of the worker's previous event k' when
+    // that gradient exists at the time of the read and is not applied yet (s_k' <= s_k <= k').
+    // R_k then runs after R_k'; it cannot run after U_k' (it reads row i_k before that update), and
+    // the slot of k' is rewritten only in a later round than U_k', so the slot is still intact.
+    if (with_gradients && local_compensation) {
+        std::vector<int64_t> last_of(n, -1);
+        for (int64_t k = 0; k < K; ++k) {
+            const int64_t kp = last_of[worker[k]], s = k - tau[k];
+            if (kp >= 0 && kp - tau[kp] <= s && s <= kp) plan.prev[k] = kp;
+            last_of[worker[k]] = k;
+        }
+    }
     // free slots ordered by the round after which they may be rewritten
     using Free = std::pair<int32_t, int32_t>;  // (round of the consuming update, slot)
     std::priority_queue<Free, std::vector<Free>, std::greater<Free>> free_slots;
@@ -61,7 +75,8 @@ int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neig
                 if (free_slots.empty()) { err = "plan: internal error, no free slot"; return ADPSGD_ERR_STATE; }
                 const Free f = free_slots.top();
                 free_slots.pop();
-                const int32_t r = std::max(last_write[i], f.first) + 1;
+                int32_t r = std::max(last_write[i], f.first) + 1;
+                if (plan.prev[k] >= 0) r = std::max(r, plan.r_round[plan.prev[k]] + 1);
                 plan.r_round[k] = r;
                 plan.slot[k] = f.second;
                 last_read[i] = std::max(last_read[i], r);
@@ -99,7 +114,8 @@ using namespace adpsgd_impl;
 extern "C" int adpsgd_plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
                                   const int32_t* tau, int32_t n_slots, int32_t with_gradients,
                                   int32_t* r_round, int32_t* u_round, int32_t* slot, int32_t* n_rounds,
-                                  const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b) {
+                                  const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b,
+                                  int32_t local_compensation, int64_t* prev) {
     if (n < 1 || K < 0 || !worker || !neighbour || !tau || !r_round || !u_round || !slot || !n_rounds)
         return ADPSGD_ERR_ARG;
     for (int64_t k = 0; k < K; ++k)
@@ -113,11 +129,13 @@ extern "C" int adpsgd_plan_rounds(int32_t n, int64_t K, const int32_t* worker, c
     }
     Plan plan;
     std::string err;
-    const int rc = plan_rounds(n, K, worker, neighbour, tau, n_slots, with_gradients != 0, plan, err, extra_ptr, extra_a, extra_b);
+    const int rc = plan_rounds(n, K, worker, neighbour, tau, n_slots, with_gradients != 0, plan, err, extra_ptr, extra_a, extra_b,
+                               local_compensation != 0);
     if (rc != ADPSGD_OK) return rc;
     std::copy(plan.r_round.begin(), plan.r_round.end(), r_round);
     std::copy(plan.u_round.begin(), plan.u_round.end(), u_round);
     std::copy(plan.slot.begin(), plan.slot.end(), slot);
+    if (prev) std::copy(plan.prev.begin(), plan.prev.end(), prev);
     *n_rounds = plan.n_rounds;
     return ADPSGD_OK;
 }

@@ -522,3 +522,52 @@ def test_multi_pair_averaging_matrix(P, model):
     assert ei.value.code == -3
     assert np.array_equal(eng.get_models(), before)
     eng.close()
+
+
+# ------------------------------------------------------------------ wait-free variant (local compensation)
+@pytest.mark.parametrize("model,n,d,rows,K,M,T,gamma,lam", [("lsq", 4, 5003, 24, 400, 4, 6, 0.3, 0.0),
+                                                              ("logreg", 6, 4097, 32, 400, 8, 5, 8.0, 1e-3),
+                                                              ("lsq", 1, 130, 16, 100, 2, 3, 0.2, 0.0)])
+def test_waitfree_local_compensation(P, model, n, d, rows, K, M, T, gamma, lam):
+    """Appendix, wait-free training: the worker applies its own pending gradient to the copy it reads.
+    Few workers and long staleness, so that most reads are compensated."""
+    _say("wait-free variant, %s n=%d d=%d" % (model, n, d))
+    g = ring_graph(n)
+    if model == "lsq":
+        feats, targs, _ = lsq_data(n, rows, d, seed=12, feature_var=1.0 / d)
+        omodel = oracle.MODEL_LSQ
+    else:
+        feats, targs, _ = logreg_data(n, rows, d, seed=12)
+        omodel = oracle.MODEL_LOGREG
+    sched = oracle.make_schedule(g, K, seed=13, T_max=T, M=M, rows=[rows] * n)
+    sched["gamma"] = (gamma * (1.0 + 0.25 * (np.arange(K) % 3))).astype(np.float32)
+    x0 = np.random.default_rng(4).standard_normal(d).astype(np.float32)
+    eng = P.Engine(g, d, model, M=M, gamma=gamma, lam=lam, T_max=T, local_compensation=True)
+    eng.load_data(feats, targs)
+    eng.set_models(x0)
+    eng.run_events(sched, want_loss=True)
+    Xg, loss_g = eng.get_models(), eng.get_loss()
+    kw = dict(M=M, gscale=1.0 / M, lam=lam, features=feats, targets=targs, gamma_k=sched["gamma"], want_loss=True)
+    Xr = np.tile(x0, (n, 1))
+    r = oracle.run_events(Xr, sched, omodel, gamma, local_compensation=True, **kw)
+    assert rel_err(Xg, Xr) <= TOL
+    assert np.allclose(loss_g, r["loss"], rtol=2e-4, atol=1e-6)
+    Xp = np.tile(x0, (n, 1))
+    oracle.run_events(Xp, sched, omodel, gamma, **kw)
+    assert rel_err(Xg, Xp) > 20 * TOL          # the compensation is not a no-op on this schedule
+    # a second call continues from the state of the first (nothing is pending across calls)
+    eng.run_events(sched)
+    oracle.run_events(Xr, sched, omodel, gamma, local_compensation=True, **kw)
+    assert rel_err(eng.get_models(), Xr) <= TOL
+    eng.close()
+
+
+def test_waitfree_variant_is_refused_where_it_is_not_defined(P):
+    import torch
+    X = torch.zeros((4, 64), device="cuda")
+    V = torch.zeros((4, 64), device="cuda")
+    W = torch.zeros((4, 64), device="cuda")
+    with pytest.raises(P.AdpsgdError) as ei:
+        P.Handle(ring_graph(4), 64, model=P.MODEL_LSQ, X_ptr=X.data_ptr(), ldx=64, M=2, gamma=0.1, momentum=0.9,
+                 V_ptr=V.data_ptr(), workspace_ptr=W.data_ptr(), workspace_bytes=4 * 64 * 4, local_compensation=True)
+    assert ei.value.code == -1

@@ -234,3 +234,46 @@ def test_planner_with_multi_pair_events_reproduces_the_oracle():
             X[j[k]] = avg
             X[w[k]] = avg - np.float32(0.02) * slots[slot[k]]
     assert np.array_equal(X, X_ref)
+
+
+def test_planner_for_the_waitfree_variant_reproduces_the_oracle():
+    """Wait-free variant: a read may be compensated with the worker's own pending gradient.  Execute
+    the plan on the CPU -- the gradients of a round all see the slots as they were when the round
+    began, so a gradient planned into the same round as the one it depends on would be caught -- and
+    compare with the oracle's serial run bit for bit."""
+    n, d, rows, K, M, T = 4, 20, 16, 500, 3, 6
+    g = ring_graph(n)
+    feats, targs, _ = lsq_data(n, rows, d, seed=1)
+    sched = oracle.make_schedule(g, K, seed=5, T_max=T, M=M, rows=[rows] * n)
+    gam = (0.01 + 0.005 * (np.arange(K) % 5)).astype(np.float32)
+    X_ref = np.tile(np.random.default_rng(0).standard_normal(d).astype(np.float32), (n, 1))
+    X = X_ref.copy()
+    oracle.run_events(X_ref, sched, oracle.MODEL_LSQ, 0.0, M=M, gscale=1.0 / M, features=feats, targets=targs,
+                      gamma_k=gam, mode=0, local_compensation=True)
+    w, j, tau = sched["worker"], sched["neighbour"], sched["tau"]
+    r_round, u_round, slot, R, prev = P.adpsgd_plan_rounds(n, w, j, tau, T + 2, True, local_compensation=True)
+    # the pending event, recomputed here from its definition
+    last = {}
+    for k in range(K):
+        kp = last.get(w[k], -1)
+        want = kp if kp >= 0 and kp - tau[kp] <= k - tau[k] <= kp else -1
+        assert prev[k] == want
+        last[w[k]] = k
+    assert (prev >= 0).sum() > K // 10          # the case under test really occurs
+    slots = {}
+    for r in range(R):
+        at_start = dict(slots)
+        for k in np.where(r_round == r)[0]:
+            xh = X[w[k]]
+            if prev[k] >= 0:
+                assert r_round[prev[k]] < r <= u_round[prev[k]]
+                xh = xh - gam[prev[k]] * at_start[slot[prev[k]]]
+            slots[slot[k]] = oracle.minibatch_gradient(oracle.MODEL_LSQ, xh, feats[w[k]], targs[w[k]],
+                                                       sched["batch_idx"][k], 1.0 / M)[0]
+        for k in np.where(u_round == r)[0]:
+            avg = (X[w[k]] + X[j[k]]) * np.float32(0.5)
+            X[j[k]] = avg
+            X[w[k]] = avg - gam[k] * slots[slot[k]]
+    assert np.array_equal(X, X_ref)
+    # without the switch the plan ignores the extra dependency
+    assert len(P.adpsgd_plan_rounds(n, w, j, tau, T + 2, True)) == 4
