@@ -182,6 +182,60 @@ def run_events(X, schedule, model, gamma, *, M=0, gscale=1.0, lam=0.0, mlp=(0, 0
     return {"loss": loss, "g": glog}
 
 
+def run_sync_steps(X, batch_idx, W, model, gamma, *, M=0, gscale=1.0, lam=0.0, mlp=(0, 0, 0),
+                   features=None, targets=None, gamma_s=None, synth_std=0.0, synth_seed=0,
+                   event_base=0, coords=None, steps=None, want_loss=False, want_g=False):
+    """Synchronous comparison schedule (D-PSGD): X <- W X - gamma G(X), IN PLACE, for ``steps``
+    iterations (default: batch_idx.shape[0]).  batch_idx is (S, n, M); W is n x n, symmetric and
+    doubly stochastic.  Returns a dict with optional 'loss' (S, n) and 'g' (S, n, d)."""
+    assert X.dtype == np.float32 and X.flags.c_contiguous and X.ndim == 2
+    n, d = X.shape
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    assert W.shape == (n, n)
+    fptr = ldf = tptr = None
+    keep = []
+    if model != MODEL_SYNTH:
+        batch_idx = np.ascontiguousarray(batch_idx, dtype=np.int32)
+        S = batch_idx.shape[0] if steps is None else steps
+        assert batch_idx.shape == (S, n, M)
+        for f in features:
+            assert f.flags.c_contiguous and f.ndim == 2
+        keep = [list(features), list(targets)]
+        fptr = _ptr_array(features)
+        tptr = _ptr_array(targets)
+        ldf = np.array([f.shape[1] for f in features], dtype=np.int64)
+    else:
+        S = steps
+        batch_idx = None
+    if coords is not None:
+        coords = np.ascontiguousarray(coords, dtype=np.int64)
+        assert coords.size == d
+    gs = None if gamma_s is None else np.ascontiguousarray(gamma_s, dtype=np.float32)
+    loss = np.zeros((S, n), dtype=np.float64) if want_loss else None
+    glog = np.zeros((S, n, d), dtype=np.float32) if want_g else None
+    rc = lib().oracle_run_sync_steps(
+        C.c_int32(n), C.c_int64(d), _p(X, C.c_float), C.c_int64(d), C.c_int(model), C.c_int(M),
+        C.c_double(gscale), C.c_double(lam), C.c_int(mlp[0]), C.c_int(mlp[1]), C.c_int(mlp[2]),
+        fptr, _p(ldf, C.c_int64), tptr, C.c_float(gamma), _p(gs, C.c_float),
+        C.c_double(synth_std), C.c_uint64(synth_seed), C.c_uint64(event_base),
+        _p(coords, C.c_int64), C.c_int64(S), _p(batch_idx, C.c_int32), _p(W, C.c_float),
+        _p(loss, C.c_double), _p(glog, C.c_float))
+    del keep
+    if rc != 0:
+        raise ValueError("oracle_run_sync_steps failed with code %d" % rc)
+    return {"loss": loss, "g": glog}
+
+
+def metropolis_weights(graph):
+    rowptr = np.ascontiguousarray(graph[0], dtype=np.int32)
+    col = np.ascontiguousarray(graph[1], dtype=np.int32)
+    n = rowptr.size - 1
+    W = np.zeros((n, n), dtype=np.float32)
+    if lib().oracle_metropolis_weights(C.c_int32(n), _p(rowptr, C.c_int32), _p(col, C.c_int32), _p(W, C.c_float)) != 0:
+        raise ValueError("oracle_metropolis_weights: bad graph")
+    return W
+
+
 def mean_model(X):
     n, d = X.shape
     out = np.zeros(d, dtype=np.float64)

@@ -601,3 +601,84 @@ double oracle_consensus_distance(int32_t n, int64_t d, const float* X, int64_t l
     }
     return total / (double)n;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Synchronous comparison schedule: decentralized parallel SGD (D-PSGD) as    */
+/* the related-work section describes it -- in each iteration every worker    */
+/* computes a stochastic gradient at its own current model and, at the same   */
+/* time, averages its model with its neighbours; then the gradient is applied */
+/* to the averaged model:                                                     */
+/*     X_{t+1}[i] = sum_j W[i][j] X_t[j] - gamma * g_i(X_t[i]; xi_{t,i})      */
+/* W (n x n, row-major) is symmetric and doubly stochastic.  The mixing sum   */
+/* is accumulated in fp64 and rounded once to fp32; gamma * g and the         */
+/* subtraction are fp32 operations with separate roundings, as in an event.   */
+/* Synthetic gradients: worker i at step t uses event number                  */
+/* event_base + t * n + i.  batch_idx is S x n x M; loss (S x n) and g_log    */
+/* (S x n x d) may be NULL.                                                   */
+/* ------------------------------------------------------------------------- */
+int oracle_run_sync_steps(int32_t n, int64_t d, float* X, int64_t ldx, int model, int M,
+                          double gscale, double lambda, int mlp_in, int mlp_hid, int mlp_out,
+                          const void* const* features, const int64_t* ldf,
+                          const void* const* targets, float gamma, const float* gamma_s,
+                          double synth_std, uint64_t synth_seed, uint64_t event_base,
+                          const int64_t* coords, int64_t S, const int32_t* batch_idx,
+                          const float* W, double* loss, float* g_log)
+{
+    if (n < 1 || d < 1 || ldx < d || S < 0 || !W) return -1;
+    grad_spec spec = { model, d, M, gscale, lambda, mlp_in, mlp_hid, mlp_out };
+    data_spec data = { features, ldf, targets };
+    float* G = (float*)malloc(sizeof(float) * (size_t)n * (size_t)d);
+    float* Xnew = (float*)malloc(sizeof(float) * (size_t)n * (size_t)d);
+    if (!G || !Xnew) { free(G); free(Xnew); return -2; }
+    for (int64_t t = 0; t < S; ++t) {
+        /* all gradients at the models the iteration starts from */
+        for (int32_t i = 0; i < n; ++i) {
+            float* gi = G + (size_t)i * d;
+            double li = 0.0;
+            if (model == MODEL_SYNTH)
+                oracle_synth_grad(synth_seed, event_base + (uint64_t)t * (uint64_t)n + (uint64_t)i, synth_std, d, coords, gi);
+            else
+                li = minibatch_gradient(&spec, &data, i, X + (size_t)i * ldx,
+                                        batch_idx + ((int64_t)t * n + i) * (int64_t)M, gi);
+            if (loss) loss[t * n + i] = li;
+            if (g_log) memcpy(g_log + ((size_t)t * n + i) * d, gi, sizeof(float) * (size_t)d);
+        }
+        const float gam = gamma_s ? gamma_s[t] : gamma;
+        for (int32_t i = 0; i < n; ++i) {
+            for (int64_t e = 0; e < d; ++e) {
+                double mix = 0.0;
+                for (int32_t j = 0; j < n; ++j) mix += (double)W[(size_t)i * n + j] * (double)X[(size_t)j * ldx + e];
+                float mixed = (float)mix;
+                float step = gam * G[(size_t)i * d + e];
+                Xnew[(size_t)i * d + e] = mixed - step;
+            }
+        }
+        for (int32_t i = 0; i < n; ++i) memcpy(X + (size_t)i * ldx, Xnew + (size_t)i * d, sizeof(float) * (size_t)d);
+    }
+    free(G); free(Xnew);
+    return 0;
+}
+
+/* Mixing weights when none are given: W[i][j] = 1 / (1 + max(deg i, deg j)) on the edges,      */
+/* W[i][i] = 1 - sum_j W[i][j] (the Metropolis rule: symmetric and doubly stochastic on any     */
+/* undirected graph; on a regular graph of degree q it is the plain average over the worker and */
+/* its neighbours, 1 / (q + 1)).  Computed in fp64, rounded once to fp32.                       */
+int oracle_metropolis_weights(int32_t n, const int32_t* rowptr, const int32_t* col, float* W)
+{
+    if (n < 1 || !rowptr || !col || !W) return -1;
+    for (size_t t = 0; t < (size_t)n * (size_t)n; ++t) W[t] = 0.0f;
+    for (int32_t i = 0; i < n; ++i) {
+        double self = 1.0;
+        const int32_t di = rowptr[i + 1] - rowptr[i];
+        for (int32_t q = rowptr[i]; q < rowptr[i + 1]; ++q) {
+            const int32_t j = col[q];
+            if (j < 0 || j >= n || j == i) return -1;
+            const int32_t dj = rowptr[j + 1] - rowptr[j];
+            const double w = 1.0 / (1.0 + (double)(di > dj ? di : dj));
+            W[(size_t)i * n + j] = (float)w;
+            self -= w;
+        }
+        W[(size_t)i * n + i] = (float)self;
+    }
+    return 0;
+}

@@ -671,3 +671,127 @@ def test_hop_ring_mixes_faster_than_the_ring():
         assert np.max(np.abs(acc / S - np.linalg.matrix_power(EW, K))) < 5 * 0.35 / np.sqrt(S)
     assert np.isclose(rho["ring"], 1 - (1 - np.cos(2 * np.pi / n)) / n)
     assert rho["hop"] < rho["ring"] - 0.02
+
+
+# ------------------------------------------------------------------ synchronous comparison schedule (D-PSGD)
+def test_dpsgd_hand_expanded(golden_dir):
+    cases = [l.split() for l in open(os.path.join(golden_dir, "dpsgd_two_workers_d1.txt"))
+             if l.strip() and not l.startswith("#")]
+    feats, targs = _unit_quadratic_data(2, [1.0])
+    assert len(cases) == 5
+    for a, S, e0, e1 in cases:
+        a, S = float(a), int(S)
+        X = np.array([[1.0], [3.0]], dtype=np.float32)
+        W = np.array([[a, 1 - a], [1 - a, a]], np.float32)
+        oracle.run_sync_steps(X, np.zeros((S, 2, 1), np.int32), W, LSQ, 0.5, M=1, gscale=1.0,
+                              features=feats, targets=targs)
+        assert (X[0, 0], X[1, 0]) == (float(e0), float(e1)), (a, S, X.ravel())
+
+
+def test_dpsgd_identity_mixing_is_n_independent_sgd_runs():
+    """W = I: worker i is plain minibatch SGD on its own data -- the single-worker case of the event
+    oracle (itself pinned against a textbook loop), bit for bit."""
+    n, d, rows, M, S = 3, 12, 20, 4, 40
+    feats, targs, _ = lsq_data(n, rows, d, seed=4)
+    rng = np.random.default_rng(1)
+    batch = rng.integers(0, rows, size=(S, n, M)).astype(np.int32)
+    X0 = rng.standard_normal((n, d)).astype(np.float32)
+    X = X0.copy()
+    oracle.run_sync_steps(X, batch, np.eye(n, dtype=np.float32), LSQ, 0.05, M=M, gscale=1.0 / M,
+                          features=feats, targets=targs)
+    for i in range(n):
+        xi = X0[i:i + 1].copy()
+        sched = {"worker": np.zeros(S, np.int32), "neighbour": np.zeros(S, np.int32), "tau": np.zeros(S, np.int32),
+                 "batch_idx": np.ascontiguousarray(batch[:, i, :])}
+        oracle.run_events(xi, sched, LSQ, 0.05, M=M, gscale=1.0 / M, features=[feats[i]], targets=[targs[i]])
+        assert np.array_equal(xi[0], X[i])
+
+
+def _path_plus_chord_graph():
+    """A small irregular connected graph: path 0-1-2-3-4 plus the edges 1-3 and 1-4 (degrees 1..4)."""
+    edges = [(0, 1), (1, 2), (2, 3), (3, 4), (1, 3), (1, 4)]
+    nb = [[] for _ in range(5)]
+    for a, b in edges:
+        nb[a].append(b)
+        nb[b].append(a)
+    rowptr = np.cumsum([0] + [len(v) for v in nb]).astype(np.int32)
+    col = np.array([j for v in nb for j in sorted(v)], np.int32)
+    return rowptr, col
+
+
+def test_metropolis_weights_are_symmetric_doubly_stochastic():
+    g = _path_plus_chord_graph()
+    W = oracle.metropolis_weights(g).astype(np.float64)
+    assert np.array_equal(W, W.T) and (W >= 0).all()
+    assert np.allclose(W.sum(0), 1, atol=1e-7) and np.allclose(W.sum(1), 1, atol=1e-7)
+    assert W[0, 1] == np.float32(1 / 5) and W[2, 3] == np.float32(1 / 4) and W[0, 2] == 0   # 1/(1+max deg)
+    ring = oracle.metropolis_weights(ring_graph(8))
+    assert np.allclose(ring[ring > 0], 1 / 3, atol=1e-7) and (ring > 0).sum() == 24
+    # second-largest eigenvalue modulus below one: repeated mixing reaches consensus
+    assert np.sort(np.abs(np.linalg.eigvalsh(W)))[-2] < 1 - 1e-3
+
+
+def test_dpsgd_gossip_only_is_a_matrix_power():
+    """gamma = 0: X_S = W^S X_0 (numpy, fp64), and the mean of the workers does not move."""
+    g = _path_plus_chord_graph()
+    W = oracle.metropolis_weights(g)
+    n, d, S = 5, 7, 25
+    X0 = np.random.default_rng(3).standard_normal((n, d)).astype(np.float32)
+    X = X0.copy()
+    oracle.run_sync_steps(X, None, W, oracle.MODEL_SYNTH, 0.0, synth_std=1.0, steps=S)
+    ref = np.linalg.matrix_power(W.astype(np.float64), S) @ X0.astype(np.float64)
+    assert np.allclose(X, ref, rtol=0, atol=2e-6)
+    assert np.allclose(X.mean(0), X0.mean(0), atol=1e-6)
+    assert oracle.consensus_distance(X) < 0.05 * oracle.consensus_distance(X0)
+
+
+def test_dpsgd_mean_moves_by_the_mean_gradient():
+    """Doubly stochastic W: mean_{t+1} = mean_t - gamma * mean_i g_i, so after S steps the mean has moved
+    by -sum_t gamma_t mean_i g_{t,i} (gradients logged), whatever the topology."""
+    n, d, rows, M, S = 6, 10, 16, 3, 30
+    W = oracle.metropolis_weights(random_regular4_graph(n, 1))
+    feats, targs, _ = logreg_data(n, rows, d, seed=2)
+    rng = np.random.default_rng(0)
+    batch = rng.integers(0, rows, size=(S, n, M)).astype(np.int32)
+    gam = (0.5 / (1 + np.arange(S) / 10)).astype(np.float32)
+    X0 = rng.standard_normal((n, d)).astype(np.float32)
+    X = X0.copy()
+    r = oracle.run_sync_steps(X, batch, W, LOGREG, 0.0, M=M, gscale=1.0 / M, lam=0.01, features=feats,
+                              targets=targs, gamma_s=gam, want_g=True, want_loss=True)
+    moved = -(gam.astype(np.float64)[:, None, None] * r["g"].astype(np.float64)).sum(0).mean(0)
+    assert np.allclose(X.astype(np.float64).mean(0) - X0.astype(np.float64).mean(0), moved, atol=5e-6)
+    assert np.abs(moved).max() > 1e-2
+    # the logged gradient of step 0 is the gradient at X_0, not at the mixed model
+    g00, l00 = oracle.minibatch_gradient(LOGREG, X0[2], feats[2], targs[2], batch[0, 2], 1.0 / M, lam=0.01)
+    assert np.array_equal(g00, r["g"][0, 2]) and l00 == r["loss"][0, 2]
+
+
+def test_dpsgd_full_averaging_same_data_keeps_workers_equal():
+    """W = 11^T / n (n = 4, exact in binary), every worker with the same data, minibatch and initial
+    model: all replicas stay identical and follow single-worker SGD exactly."""
+    n, d, rows, M, S = 4, 9, 12, 3, 25
+    f1, t1, _ = lsq_data(1, rows, d, seed=8)
+    feats, targs = [f1[0]] * n, [t1[0]] * n
+    rng = np.random.default_rng(5)
+    b1 = rng.integers(0, rows, size=(S, 1, M)).astype(np.int32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    X = np.tile(x0, (n, 1))
+    oracle.run_sync_steps(X, np.repeat(b1, n, axis=1), np.full((n, n), 0.25, np.float32), LSQ, 0.1, M=M,
+                          gscale=1.0 / M, features=feats, targets=targs)
+    ref = x0[None].copy()
+    oracle.run_sync_steps(ref, b1, np.ones((1, 1), np.float32), LSQ, 0.1, M=M, gscale=1.0 / M,
+                          features=f1, targets=t1)
+    assert all(np.array_equal(X[i], ref[0]) for i in range(n))
+
+
+def test_dpsgd_synthetic_gradients_use_the_event_counter():
+    """Worker i at step t draws event number base + t n + i of the synthetic generator."""
+    n, d, S = 3, 8, 2
+    X = np.zeros((n, d), np.float32)
+    oracle.run_sync_steps(X, None, np.eye(n, dtype=np.float32), oracle.MODEL_SYNTH, 1.0, synth_std=0.5,
+                          synth_seed=9, event_base=100, steps=S)
+    for i in range(n):
+        want = np.zeros(d, np.float32)
+        for t in range(S):
+            want = want - oracle.synth_grad(9, 100 + t * n + i, 0.5, np.arange(d))
+        assert np.array_equal(X[i], want)
