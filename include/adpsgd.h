@@ -194,6 +194,33 @@ int adpsgd_set_models(adpsgd_t* h, const float* x, int64_t ld_in, int32_t on_dev
  * schedule arrays may be reused as soon as the call returns. */
 int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float* loss);
 
+/* Synchronous comparison schedule: S iterations of decentralized parallel SGD as the paper's
+ * related-work section describes it (every worker computes a stochastic gradient at its current
+ * model while the models are averaged with the neighbours; then the gradients are applied):
+ *     X_{t+1}[i] = w_self[i] X_t[i] + sum_{j in N(i)} w_edge[i,j] X_t[j] - gamma_t g_i(X_t[i]; xi_{t,i})
+ * One iteration counts as n worker updates; the synthetic gradient of worker i in iteration t is
+ * that of event number (events executed so far on the handle) + t n + i.  All arrays are host
+ * memory, read during the call only. */
+typedef struct {
+    int64_t S;                 /* iterations */
+    const int32_t* batch_idx;  /* S * n * M minibatch indices, [t][i][m]; NULL for SYNTH */
+    const float* gamma;        /* S step sizes, or NULL: the handle's gamma */
+    const float* w_self;       /* n diagonal weights, or NULL: Metropolis weights (see below) */
+    const float* w_edge;       /* one weight per entry of the graph's col array; NULL with w_self.
+                                  Must be non-negative, symmetric, rows summing to 1 (|err| <= 1e-5) */
+} adpsgd_sync_schedule_t;
+
+/* Runs the iterations on the handle's stream (asynchronous, arrays reusable on return).  loss
+ * (device, S * n floats, [t][i], or NULL) receives the minibatch losses.  Needs at least n
+ * pending-gradient slots in the workspace (data models) and n <= 256; not available with momentum
+ * / weight decay.  Errors as adpsgd_run_events, with no state change. */
+int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* s, float* loss);
+
+/* Host-only: Metropolis mixing weights of a graph, w_edge[e] = 1 / (1 + max(deg i, deg j)) for the
+ * entry e = (i, j) of the CSR arrays, w_self[i] = 1 - sum of its edge weights (fp64, rounded once);
+ * on a regular graph of degree q every weight is 1 / (q + 1).  Outputs: n and rowptr[n] floats. */
+int adpsgd_metropolis_weights(const adpsgd_graph_t* graph, float* w_self, float* w_edge);
+
 /* Copy the n x d models to out (host or device, leading dimension ld_out >= d).
  * Synchronises the stream. */
 int adpsgd_get_models(adpsgd_t* h, float* out, int64_t ld_out, int32_t on_device);

@@ -21,7 +21,7 @@ EXPORTS = [
     "adpsgd_create", "adpsgd_destroy", "adpsgd_last_error", "adpsgd_load_data", "adpsgd_set_models",
     "adpsgd_run_events", "adpsgd_get_models", "adpsgd_get_mean_model", "adpsgd_consensus_distance",
     "adpsgd_get_bf16_models", "adpsgd_get_momentum", "adpsgd_get_stats", "adpsgd_make_schedule", "adpsgd_plan_rounds",
-    "adpsgd_synth_gradient",
+    "adpsgd_synth_gradient", "adpsgd_run_sync_steps", "adpsgd_metropolis_weights",
 ]
 
 
@@ -50,6 +50,11 @@ class Schedule(C.Structure):
                 ("tau", C.POINTER(C.c_int32)), ("batch_idx", C.POINTER(C.c_int32)),
                 ("gamma", C.POINTER(C.c_float)), ("extra_ptr", C.POINTER(C.c_int64)),
                 ("extra_a", C.POINTER(C.c_int32)), ("extra_b", C.POINTER(C.c_int32))]
+
+
+class SyncSchedule(C.Structure):
+    _fields_ = [("S", C.c_int64), ("batch_idx", C.POINTER(C.c_int32)), ("gamma", C.POINTER(C.c_float)),
+                ("w_self", C.POINTER(C.c_float)), ("w_edge", C.POINTER(C.c_float))]
 
 
 class SchedParams(C.Structure):
@@ -109,6 +114,8 @@ def lib():
         L.adpsgd_plan_rounds.argtypes = [i32, i64, P(i32), P(i32), P(i32), i32, i32, P(i32), P(i32), P(i32), P(i32),
                                          P(i64), P(i32), P(i32), i32, P(i64)]
         L.adpsgd_synth_gradient.argtypes = [u64, u64, C.c_float, i64, vp, vp]
+        L.adpsgd_run_sync_steps.argtypes = [vp, P(SyncSchedule), vp]
+        L.adpsgd_metropolis_weights.argtypes = [P(Graph), P(C.c_float), P(C.c_float)]
         _lib = L
     return _lib
 
@@ -173,6 +180,19 @@ def adpsgd_plan_rounds(n, worker, neighbour, tau, n_slots, with_gradients=True, 
     return r, u, s, nr.value
 
 
+def adpsgd_metropolis_weights(graph):
+    """Host-only: (w_self[n], w_edge[nnz]) aligned with the graph's CSR arrays."""
+    g, keep = _graph_struct(graph)
+    w_self = np.zeros(g.n, np.float32)
+    w_edge = np.zeros(max(int(np.asarray(graph[0])[-1]), 1), np.float32)
+    rc = lib().adpsgd_metropolis_weights(C.byref(g), w_self.ctypes.data_as(C.POINTER(C.c_float)),
+                                         w_edge.ctypes.data_as(C.POINTER(C.c_float)))
+    del keep
+    if rc != OK:
+        raise AdpsgdError(rc, "adpsgd_metropolis_weights failed")
+    return w_self, w_edge[:int(np.asarray(graph[0])[-1])]
+
+
 def adpsgd_synth_gradient(seed, k, std, d, out_ptr, stream=0):
     rc = lib().adpsgd_synth_gradient(seed, k, std, d, out_ptr, stream)
     if rc != OK:
@@ -231,6 +251,19 @@ class Handle:
                      None if gam is None else gam.ctypes.data_as(C.POINTER(C.c_float)),
                      None if ep is None else ep.ctypes.data_as(C.POINTER(C.c_int64)), _i32p(ea), _i32p(eb))
         _check(self._h, lib().adpsgd_run_events(self._h, C.byref(s), loss_ptr))
+
+    def run_sync_steps(self, steps, batch_idx=None, gamma=None, weights=None, loss_ptr=None):
+        """steps iterations of the synchronous comparison schedule; batch_idx (steps, n, M);
+        weights = (w_self, w_edge) or None for Metropolis weights."""
+        fp = lambda a: None if a is None else a.ctypes.data_as(C.POINTER(C.c_float))
+        batch = _as_i32(batch_idx)
+        gam = None if gamma is None else np.ascontiguousarray(gamma, dtype=np.float32)
+        ws = we = None
+        if weights is not None:
+            ws = np.ascontiguousarray(weights[0], dtype=np.float32)
+            we = np.ascontiguousarray(weights[1], dtype=np.float32)
+        s = SyncSchedule(steps, _i32p(batch), fp(gam), fp(ws), fp(we))
+        _check(self._h, lib().adpsgd_run_sync_steps(self._h, C.byref(s), loss_ptr))
 
     def get_models(self, out=None, ld_out=None, on_device=False):
         if on_device:

@@ -14,7 +14,7 @@ LIB = HERE / "libadpsgd.so"
 OBJ = HERE / "_build"
 
 SOURCES = ["api.cpp", "schedule.cpp", "planner.cpp", "kernels_fused.hip", "kernels_grad_linear.hip",
-           "kernels_mlp.hip", "kernels_diag.hip"]
+           "kernels_mlp.hip", "kernels_diag.hip", "kernels_sync.hip"]
 HEADERS = ["internal.hpp", "device_common.hpp"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -126,6 +126,26 @@ struct MlpGradArgs {
 size_t mlp_scratch_bytes(int32_t n_ops, int32_t M, int32_t in, int32_t hid, int32_t out);
 hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_launches);
 
+struct SyncArgs {
+    float* X;
+    int64_t ld;
+    int64_t d;
+    int32_t n;
+    const int32_t* rowptr;   // device
+    const int32_t* col;      // device
+    const float* w_self;     // device
+    const float* w_edge;     // device
+    const float* slots;      // gradient of worker i in slot i, or nullptr with synth
+    uint16_t* Xbf16;         // bf16 shadow to refresh, or nullptr
+    float gamma;
+    float synth_std;
+    uint64_t synth_seed;
+    uint64_t event0;         // synthetic gradients: worker i draws event event0 + i
+    bool synth;
+};
+int32_t sync_tile_cols(int32_t n);   // 0: n too large for the in-place mixing kernel
+hipError_t launch_sync_mix_apply(const SyncArgs& a, hipStream_t st);
+
 hipError_t launch_broadcast_rows(float* X, int64_t ld, int64_t d, int32_t n, const float* x0, hipStream_t st);
 hipError_t launch_refresh_bf16(const float* X, uint16_t* Xb, int64_t ld, int32_t n, hipStream_t st);
 hipError_t launch_mean_model(const float* X, int64_t ld, int64_t d, int32_t n, float* out, hipStream_t st);

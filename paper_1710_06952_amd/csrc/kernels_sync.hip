@@ -1,0 +1,125 @@
+// Synchronous comparison schedule: one iteration of decentralized parallel SGD
+// as the related-work section of the paper describes it -- every worker averages
+// its model with its neighbours while its gradient (taken at the model the
+// iteration started from) is computed, then applies that gradient:
+//     X[i] <- w_self[i] X[i] + sum_{j in N(i)} w_edge[i,j] X[j] - gamma g_i
+// with a symmetric doubly stochastic weight matrix on the graph's edges.
+//
+// Every column evolves independently of the others, so the iteration runs in
+// place: a block stages all n rows of a tile of columns in LDS (n x 4 kCols
+// bytes), then writes each row's mixture straight back to X.  HBM traffic is one
+// read and one write of X (plus one read of the gradients for the data models).
+#include "device_common.hpp"
+#include "internal.hpp"
+
+namespace adpsgd_impl {
+namespace {
+
+constexpr int kThreads = 256;
+
+struct SyncParams {
+    float* X;
+    int64_t ld;
+    int64_t d;
+    int32_t n;
+    int32_t cols;              // columns per block, a multiple of 4; cols / 4 divides kThreads
+    const int32_t* rowptr;     // device copies of the graph and its weights
+    const int32_t* col;
+    const float* w_self;
+    const float* w_edge;
+    const float* slots;        // gradient of worker i in slot i (data models)
+    uint16_t* Xbf16;
+    float gamma;
+    float synth_std;
+    uint32_t key0, key1;
+    uint64_t event0;           // synthetic gradients: worker i draws event event0 + i
+};
+
+// grid = ceil(d / cols); thread = (quad of 4 columns, row lane)
+template <bool SYNTH, bool SHADOW>
+__global__ __launch_bounds__(kThreads) void sync_mix_apply_kernel(const SyncParams p) {
+    extern __shared__ __attribute__((aligned(16))) float tile[];   // [n][cols]
+    const int quads = p.cols >> 2;
+    const int qx = threadIdx.x % quads, ry = threadIdx.x / quads, rows_per_pass = kThreads / quads;
+    const int64_t c = static_cast<int64_t>(blockIdx.x) * p.cols + 4 * qx;   // first of this thread's 4 columns
+    const bool live = c < p.d;     // d is padded to a multiple of 4 by the leading dimension
+    for (int r = ry; r < p.n; r += rows_per_pass) {
+        v4f v = {0, 0, 0, 0};
+        if (live) v = *reinterpret_cast<const v4f*>(p.X + static_cast<int64_t>(r) * p.ld + c);
+        *reinterpret_cast<v4f*>(tile + static_cast<int64_t>(r) * p.cols + 4 * qx) = v;
+    }
+    __syncthreads();
+    if (!live) return;
+    for (int i = ry; i < p.n; i += rows_per_pass) {
+        v4f acc = *reinterpret_cast<const v4f*>(tile + static_cast<int64_t>(i) * p.cols + 4 * qx) * p.w_self[i];
+        const int32_t e1 = p.rowptr[i + 1];
+        for (int32_t e = p.rowptr[i]; e < e1; ++e)
+            acc += *reinterpret_cast<const v4f*>(tile + static_cast<int64_t>(p.col[e]) * p.cols + 4 * qx) * p.w_edge[e];
+        v4f g;
+        if (SYNTH) {
+            const uint64_t k = p.event0 + static_cast<uint64_t>(i);
+            const uint64_t q = static_cast<uint64_t>(c) >> 2;
+            g = synth_normals4(static_cast<uint32_t>(q), static_cast<uint32_t>(q >> 32), static_cast<uint32_t>(k),
+                               static_cast<uint32_t>(k >> 32), p.key0, p.key1) * p.synth_std;
+        } else {
+            g = *reinterpret_cast<const v4f*>(p.slots + static_cast<int64_t>(i) * p.ld + c);
+        }
+        v4f out;
+        {
+#pragma clang fp contract(off)
+            const v4f step = g * p.gamma;
+            out = acc - step;
+        }
+        if (c + 4 > p.d) {     // keep the padding beyond d at zero
+            if (c + 1 >= p.d) out.y = 0.0f;
+            if (c + 2 >= p.d) out.z = 0.0f;
+            if (c + 3 >= p.d) out.w = 0.0f;
+        }
+        *reinterpret_cast<v4f*>(p.X + static_cast<int64_t>(i) * p.ld + c) = out;
+        if (SHADOW) {
+            v4h hb = {bf16_rne(out.x), bf16_rne(out.y), bf16_rne(out.z), bf16_rne(out.w)};
+            *reinterpret_cast<v4h*>(p.Xbf16 + static_cast<int64_t>(i) * p.ld + c) = hb;
+        }
+    }
+}
+
+}  // namespace
+
+int32_t sync_tile_cols(int32_t n) {
+    // the tile of n rows must fit 64 KiB of LDS: 256, 128 or 64 columns
+    for (int32_t cols = 256; cols >= 64; cols >>= 1)
+        if (static_cast<int64_t>(n) * cols * 4 <= 65536) return cols;
+    return 0;
+}
+
+hipError_t launch_sync_mix_apply(const SyncArgs& a, hipStream_t st) {
+    const int32_t cols = sync_tile_cols(a.n);
+    if (cols == 0 || a.n < 1) return hipErrorInvalidValue;
+    SyncParams p;
+    p.X = a.X;
+    p.ld = a.ld;
+    p.d = a.d;
+    p.n = a.n;
+    p.cols = cols;
+    p.rowptr = a.rowptr;
+    p.col = a.col;
+    p.w_self = a.w_self;
+    p.w_edge = a.w_edge;
+    p.slots = a.slots;
+    p.Xbf16 = a.Xbf16;
+    p.gamma = a.gamma;
+    p.synth_std = a.synth_std;
+    p.key0 = static_cast<uint32_t>(a.synth_seed);
+    p.key1 = static_cast<uint32_t>(a.synth_seed >> 32);
+    p.event0 = a.event0;
+    const int64_t blocks = (a.d + cols - 1) / cols;
+    if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const size_t lds = static_cast<size_t>(a.n) * cols * 4;
+    const dim3 grid(static_cast<uint32_t>(blocks));
+    if (a.synth) hipLaunchKernelGGL((sync_mix_apply_kernel<true, false>), grid, dim3(kThreads), lds, st, p);
+    else if (a.Xbf16) hipLaunchKernelGGL((sync_mix_apply_kernel<false, true>), grid, dim3(kThreads), lds, st, p);
+    else hipLaunchKernelGGL((sync_mix_apply_kernel<false, false>), grid, dim3(kThreads), lds, st, p);
+    return hipGetLastError();
+}
+
+}  // namespace adpsgd_impl

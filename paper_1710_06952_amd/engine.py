@@ -89,6 +89,14 @@ class Engine:
             loss_ptr = self.loss.data_ptr()
         self.h.run_events(schedule, loss_ptr)
 
+    def run_sync_steps(self, steps, batch_idx=None, gamma=None, weights=None, want_loss=False):
+        """The synchronous comparison schedule (all workers step together, mixing with all neighbours)."""
+        loss_ptr = None
+        if want_loss:
+            self.loss = self.torch.zeros(steps * self.n, dtype=self.torch.float32, device=self.device)
+            loss_ptr = self.loss.data_ptr()
+        self.h.run_sync_steps(steps, batch_idx, gamma, weights, loss_ptr)
+
     def get_loss(self):
         self.torch.cuda.synchronize(self.device)
         return self.loss.cpu().numpy()

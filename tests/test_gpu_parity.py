@@ -571,3 +571,107 @@ def test_waitfree_variant_is_refused_where_it_is_not_defined(P):
         P.Handle(ring_graph(4), 64, model=P.MODEL_LSQ, X_ptr=X.data_ptr(), ldx=64, M=2, gamma=0.1, momentum=0.9,
                  V_ptr=V.data_ptr(), workspace_ptr=W.data_ptr(), workspace_bytes=4 * 64 * 4, local_compensation=True)
     assert ei.value.code == -1
+
+
+# ------------------------------------------------------------------ synchronous comparison schedule (D-PSGD)
+def _dense_from_csr(g, w_self, w_edge):
+    n = len(g[0]) - 1
+    W = np.zeros((n, n), np.float32)
+    for i in range(n):
+        W[i, i] = w_self[i]
+        for e in range(g[0][i], g[0][i + 1]):
+            W[i, g[1][e]] = w_edge[e]
+    return W
+
+
+@pytest.mark.parametrize("n,d,S,graph", [(8, 5003, 40, "ring"), (16, 1030, 25, "reg4"), (128, 777, 10, "ring"),
+                                         (200, 130, 6, "ring"), (1, 100, 5, "ring")])
+def test_sync_steps_synthetic(P, n, d, S, graph):
+    """All workers step together: X <- W X - gamma G, W = Metropolis weights of the graph; spans the three
+    tile widths of the mixing kernel (n <= 64, <= 128, <= 256) and a ragged last tile."""
+    _say("sync steps, synth n=%d d=%d" % (n, d))
+    g = ring_graph(n) if graph == "ring" else random_regular4_graph(n, 2)
+    std = float(np.float32(0.05))
+    eng = P.Engine(g, d, "synth", gamma=0.2, T_max=2, synth_std=std, synth_seed=3)
+    x0 = np.random.default_rng(1).standard_normal((n, d)).astype(np.float32)
+    eng.set_models(x0, broadcast=False)
+    eng.run_sync_steps(S)
+    W = oracle.metropolis_weights(g)
+    Xr = x0.copy()
+    oracle.run_sync_steps(Xr, None, W, oracle.MODEL_SYNTH, 0.2, synth_std=std, synth_seed=3, steps=S)
+    assert rel_err(eng.get_models(), Xr) <= TOL
+    # asynchronous events continue on the same handle, with the event counter advanced by S n
+    if n > 1:
+        sched = oracle.make_schedule(g, 50, seed=4, T_max=2)
+        eng.run_events(sched)
+        oracle.run_events(Xr, sched, oracle.MODEL_SYNTH, 0.2, synth_std=std, synth_seed=3, event_base=S * n)
+        assert rel_err(eng.get_models(), Xr) <= TOL
+    eng.close()
+
+
+@pytest.mark.parametrize("model", ["lsq", "logreg"])
+def test_sync_steps_linear_models(P, model):
+    n, d, rows, M, S = 12, 4099, 24, 6, 30
+    _say("sync steps, %s" % model)
+    g = random_regular4_graph(n, 7)
+    if model == "lsq":
+        feats, targs, _ = lsq_data(n, rows, d, seed=3, feature_var=1.0 / d)
+        omodel, gamma, lam = oracle.MODEL_LSQ, 0.5, 0.0
+    else:
+        feats, targs, _ = logreg_data(n, rows, d, seed=3)
+        omodel, gamma, lam = oracle.MODEL_LOGREG, 4.0, 1e-3
+    rng = np.random.default_rng(2)
+    batch = rng.integers(0, rows, size=(S, n, M)).astype(np.int32)
+    gam = (gamma / (1 + np.arange(S) / 10)).astype(np.float32)
+    # caller-supplied weights: lazy Metropolis (half of the off-diagonal mass moved to the diagonal)
+    ws, we = P.adpsgd_metropolis_weights(g)
+    we = (we * np.float32(0.5)).astype(np.float32)
+    ws = (1.0 - np.add.reduceat(we.astype(np.float64), g[0][:-1])).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    eng = P.Engine(g, d, model, M=M, gamma=gamma, lam=lam, n_slots=n)
+    eng.load_data(feats, targs)
+    eng.set_models(x0)
+    eng.run_sync_steps(S, batch, gamma=gam, weights=(ws, we), want_loss=True)
+    Xr = np.tile(x0, (n, 1))
+    r = oracle.run_sync_steps(Xr, batch, _dense_from_csr(g, ws, we), omodel, gamma, M=M, gscale=1.0 / M, lam=lam,
+                              features=feats, targets=targs, gamma_s=gam, want_loss=True)
+    assert rel_err(eng.get_models(), Xr) <= TOL
+    assert np.allclose(eng.get_loss().reshape(S, n), r["loss"], rtol=2e-4, atol=1e-6)
+    eng.close()
+
+
+def test_sync_steps_mlp(P):
+    n, dims, rows, M, S = 6, (24, 64, 5), 40, 16, 20
+    _say("sync steps, mlp")
+    g = ring_graph(n)
+    from workloads import mixture_data, mlp_init, f32_to_bf16_bits
+    feats, labels, _ = mixture_data(n, rows, din=dims[0], classes=dims[2], seed=5)
+    d = dims[0] * dims[1] + dims[1] + dims[1] * dims[2] + dims[2]
+    x0 = mlp_init(*dims, seed=5)
+    batch = np.random.default_rng(6).integers(0, rows, size=(S, n, M)).astype(np.int32)
+    eng = P.Engine(g, d, "mlp", M=M, gamma=0.05, mlp=dims, n_slots=n)
+    eng.load_data(feats, labels)
+    eng.set_models(x0)
+    eng.run_sync_steps(S, batch)
+    Xr = np.tile(x0, (n, 1))
+    oracle.run_sync_steps(Xr, batch, oracle.metropolis_weights(g), oracle.MODEL_MLP, 0.05, M=M, gscale=1.0 / M,
+                          mlp=dims, features=feats, targets=labels)
+    Xg = eng.get_models()
+    assert rel_err(Xg, Xr) <= MLP_TOL_MASTER
+    assert np.array_equal(eng.get_bf16_models(), f32_to_bf16_bits(Xg))     # the shadow is RNE(master)
+    eng.close()
+
+
+def test_sync_steps_validation(P):
+    g = ring_graph(4)
+    eng = P.Engine(g, 64, "synth", gamma=0.1, synth_std=0.1)
+    eng.set_models(np.zeros(64, np.float32))
+    ws, we = P.adpsgd_metropolis_weights(g)
+    bad = we.copy()
+    bad[0] += 0.25                                  # breaks symmetry and the row sum
+    for weights in ((ws, bad), (ws * 0.5, we), (ws, -we)):
+        with pytest.raises(P.AdpsgdError) as ei:
+            eng.run_sync_steps(2, weights=weights)
+        assert ei.value.code == -3
+    assert not eng.get_models().any()               # nothing ran
+    eng.close()

@@ -277,3 +277,21 @@ def test_planner_for_the_waitfree_variant_reproduces_the_oracle():
     assert np.array_equal(X, X_ref)
     # without the switch the plan ignores the extra dependency
     assert len(P.adpsgd_plan_rounds(n, w, j, tau, T + 2, True)) == 4
+
+
+def test_metropolis_weights_agree_with_the_oracle_bit_for_bit():
+    for g in (ring_graph(8), random_regular4_graph(16, 3), ring_graph(2), ring_graph(1)):
+        w_self, w_edge = P.adpsgd_metropolis_weights(g)
+        W = oracle.metropolis_weights(g)
+        n = len(g[0]) - 1
+        assert np.array_equal(w_self, np.diag(W))
+        for i in range(n):
+            for e in range(g[0][i], g[0][i + 1]):
+                assert w_edge[e] == W[i, g[1][e]]
+        assert np.count_nonzero(W) == n + len(w_edge)
+    # an irregular graph: star with 4 leaves
+    rowptr = np.array([0, 4, 5, 6, 7, 8], np.int32)
+    col = np.array([1, 2, 3, 4, 0, 0, 0, 0], np.int32)
+    w_self, w_edge = P.adpsgd_metropolis_weights((rowptr, col))
+    assert np.array_equal(w_edge, np.full(8, np.float32(0.2))) and w_self[1] == np.float32(0.8)
+    assert np.array_equal(np.diag(oracle.metropolis_weights((rowptr, col))), w_self)
