@@ -1,0 +1,62 @@
+"""The slow-worker study: its schedule builder (CPU) and one tiny end-to-end run (GPU)."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_1710_06952_amd as P
+from paper_1710_06952_amd.studies import heterogeneity as H
+
+
+def test_clock_schedule_staleness_counts_the_events_since_the_workers_last_read():
+    n, K = 6, 500
+    g = H.ring(n)
+    mean = np.ones(n)
+    mean[2] = 10.0
+    s, when = H.clock_schedule(g, K, mean, M=3, rows=20, seed=1)
+    assert np.all(np.diff(when) >= 0)
+    last = {}
+    for k in range(K):
+        i = s["worker"][k]
+        assert s["tau"][k] == k - (last[i] + 1 if i in last else 0)
+        assert s["neighbour"][k] in ((i - 1) % n, (i + 1) % n)
+        last[i] = k
+    share = np.bincount(s["worker"], minlength=n) / K
+    assert share[2] < 0.05 and share[0] > 0.12          # the slow worker updates about ten times less often
+    assert s["batch_idx"].shape == (K, 3) and s["batch_idx"].min() >= 0 and s["batch_idx"].max() < 20
+    # the library's planner accepts it, and the oracle runs it
+    r_round, u_round, slot, R = P.adpsgd_plan_rounds(n, s["worker"], s["neighbour"], s["tau"], int(s["tau"].max()) + 1)
+    assert R <= K and (r_round <= u_round).all()
+
+
+def test_deterministic_equal_clocks_give_round_robin_with_staleness_n_minus_1():
+    n, K = 5, 60
+    s, when = H.clock_schedule(H.ring(n), K, np.ones(n), M=1, rows=4, seed=0, exponential=False)
+    assert np.array_equal(s["worker"], np.arange(K) % n)
+    assert np.array_equal(s["tau"][n:], np.full(K - n, n - 1))
+    assert np.allclose(when, 1 + np.arange(K) // n)
+    assert np.allclose(H.sync_clock(7, [1, 1, 3, 1], 0, exponential=False), 3 * np.arange(1, 8))
+
+
+def test_objective_and_smoothing_helpers():
+    feats, targs = H.make_problem(3, 16, 8, seed=2, noise=0.0)
+    assert all(f is feats[0] for f in feats) and len(feats) == 3          # shared data
+    xstar = np.linalg.lstsq(feats[0].astype(np.float64), targs[0].astype(np.float64), rcond=None)[0]
+    assert H.objective(xstar, feats, targs) < 1e-12 < H.objective(np.zeros(16), feats, targs)
+    assert np.allclose(H.smooth([1, 3, 5, 7], 2), [1, 2, 4, 6])
+    assert H.first_time_below(np.array([3.0, 2.0, 1.0]), np.array([10.0, 20.0, 30.0]), 2.0) == 20.0
+    assert H.first_time_below(np.array([3.0]), np.array([1.0]), 2.0) == float("inf")
+
+
+@pytest.mark.gpu
+def test_study_runs_end_to_end_on_a_tiny_problem():
+    res = H.run_study(n=4, d=256, rows=64, M=4, epochs=12, slowdowns=(1, 10), seed=0, target=0.1)
+    assert [r["slowdown"] for r in res["results"]] == [1, 10]
+    fast, slow = res["results"]
+    for r in res["results"]:
+        assert r["adpsgd_final_objective"] < 0.2 * res["initial_objective"]
+        assert r["sync_final_objective"] < 0.2 * res["initial_objective"]
+    # without a straggler both use the four workers; with one the synchronous schedule waits for it
+    assert fast["adpsgd_speedup"] > 2.5 and fast["sync_speedup"] > 1.5
+    assert slow["adpsgd_speedup"] > 2.5 > 1.0 > slow["sync_speedup"]
+    assert slow["adpsgd_time_to_target"] < slow["sync_time_to_target"]
+    assert "slowdown" in H.format_table(res)
