@@ -80,8 +80,6 @@ struct adpsgd {
     adpsgd_opts_t o{};
     std::vector<int32_t> rowptr, col;
     std::vector<WorkerData> data;
-    bool data_dirty = true;
-    DevBuf data_dev;
     int32_t n_slots = 0;
     hipStream_t stream = nullptr;
     bool streaming = false;
@@ -120,18 +118,6 @@ bool is_neighbour(const adpsgd_t* h, int32_t i, int32_t j) {
     for (int32_t t = b; t < e; ++t)
         if (h->col[t] == j) return true;
     return false;
-}
-
-// device copy of the per-worker data pointers, refreshed after adpsgd_load_data
-int upload_data_table(adpsgd_t* h) {
-    if (!h->data_dirty) return ADPSGD_OK;
-    std::vector<WorkerDataDev> tab(h->n);
-    for (int32_t i = 0; i < h->n; ++i) tab[i] = {h->data[i].features, h->data[i].targets, h->data[i].ld};
-    HIP_TRY(h, hipStreamSynchronize(h->stream));
-    HIP_TRY(h, h->data_dev.reserve(tab.size() * sizeof(WorkerDataDev)));
-    HIP_TRY(h, hipMemcpy(h->data_dev.p, tab.data(), tab.size() * sizeof(WorkerDataDev), hipMemcpyHostToDevice));
-    h->data_dirty = false;
-    return ADPSGD_OK;
 }
 
 void metropolis(const std::vector<int32_t>& rowptr, const std::vector<int32_t>& col, float* w_self, float* w_edge) {
@@ -267,7 +253,6 @@ extern "C" void adpsgd_destroy(adpsgd_t* h) {
     for (auto& pr : h->ev_fused) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
     for (auto& pr : h->ev_grad) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
     for (auto e : h->ev_pool) (void)hipEventDestroy(e);
-    h->data_dev.release();
     h->grad_scratch.release();
     h->diag.release();
     delete h;
@@ -290,7 +275,6 @@ extern "C" int adpsgd_load_data(adpsgd_t* h, int32_t worker, const void* feature
     w.targets = targets;
     w.rows = rows;
     w.ld = ld;
-    h->data_dirty = true;
     return ADPSGD_OK;
 }
 
@@ -387,7 +371,7 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
     }
     for (int32_t r = 0; r < R; ++r) { u_off[r + 1] += u_off[r]; r_off[r + 1] += r_off[r]; }
 
-    // ---- tables: [PairOp x K][GradOp x K][batch_idx K x M][WorkerDataDev x n] ----
+    // ---- tables: [PairOp x K][GradOp x K][batch_idx K x M] ----
     const size_t bytes_u = static_cast<size_t>(K + n_extra) * sizeof(PairOp);
     const size_t bytes_r = with_grad ? static_cast<size_t>(K) * sizeof(GradOp) : 0;
     const size_t bytes_b = with_grad ? static_cast<size_t>(K) * M * sizeof(int32_t) : 0;
@@ -431,7 +415,11 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
                 const int64_t kp = plan.prev[k];
                 g.comp_slot = kp >= 0 ? plan.slot[kp] : -1;
                 g.comp_gamma = kp >= 0 ? (s->gamma ? s->gamma[kp] : h->o.gamma) : 0.0f;
-                g.pad[0] = g.pad[1] = g.pad[2] = 0;
+                g.pad = 0;
+                const WorkerData& w = h->data[g.worker];
+                g.features = w.features;
+                g.targets = w.targets;
+                g.ld = w.ld;
             }
         }
     }
@@ -442,10 +430,6 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
     const GradOp* d_rops = reinterpret_cast<const GradOp*>(dev + off_r);
     const int32_t* d_batch = reinterpret_cast<const int32_t*>(dev + off_b);
 
-    if (with_grad) {
-        const int rc_tab = upload_data_table(h);
-        if (rc_tab != ADPSGD_OK) return rc_tab;
-    }
 
     // ---- gradient groups ----
     int32_t group = 1;
@@ -483,12 +467,12 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
             int launches = 0;
             if (h->o.model == ADPSGD_MODEL_MLP) {
                 MlpGradArgs a{h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, d_rops + g0, cnt, M,
-                              d_batch, static_cast<const WorkerDataDev*>(h->data_dev.p), slots, gscale, loss,
+                              d_batch, slots, gscale, loss,
                               h->grad_scratch.p};
                 HIP_TRY(h, launch_mlp_gradient(a, h->stream, &launches));
             } else {
                 LinearGradArgs a{h->o.model, h->o.X, h->o.ldx, h->d, d_rops + g0, cnt, M, d_batch,
-                                 static_cast<const WorkerDataDev*>(h->data_dev.p), slots, gscale, h->o.lambda,
+                                 slots, gscale, h->o.lambda,
                                  static_cast<float*>(h->grad_scratch.p),
                                  reinterpret_cast<float*>(static_cast<char*>(h->grad_scratch.p) + off_coef), loss};
                 HIP_TRY(h, launch_linear_gradient(a, h->stream, &launches));
@@ -605,7 +589,8 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
         GradOp* rops = reinterpret_cast<GradOp*>(stage);
         for (int64_t t = 0; t < S; ++t)
             for (int32_t i = 0; i < n; ++i)
-                rops[t * n + i] = GradOp{i, i, static_cast<int32_t>(t * n + i), -1, 0.0f, {0, 0, 0}};
+                rops[t * n + i] = GradOp{i, i, static_cast<int32_t>(t * n + i), -1, 0.0f, 0,
+                                         h->data[i].features, h->data[i].targets, h->data[i].ld};
         std::memcpy(stage + off_b, s->batch_idx, bytes_b);
     }
     std::memcpy(stage + off_ws, w_self.data(), static_cast<size_t>(n) * 4);
@@ -620,8 +605,6 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
     int32_t group = 1;
     size_t off_coef = 0;
     if (with_grad) {
-        const int rc_tab = upload_data_table(h);
-        if (rc_tab != ADPSGD_OK) return rc_tab;
         if (h->o.model == ADPSGD_MODEL_MLP) {
             group = std::min<int32_t>(n, 64);
             HIP_TRY(h, h->grad_scratch.reserve(mlp_scratch_bytes(group, M, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out)));
@@ -641,12 +624,12 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
             int launches = 0;
             if (h->o.model == ADPSGD_MODEL_MLP) {
                 MlpGradArgs a{h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, d_rops + t * n + g0, cnt, M,
-                              d_batch, static_cast<const WorkerDataDev*>(h->data_dev.p), slots, gscale, loss,
+                              d_batch, slots, gscale, loss,
                               h->grad_scratch.p};
                 HIP_TRY(h, launch_mlp_gradient(a, h->stream, &launches));
             } else {
                 LinearGradArgs a{h->o.model, h->o.X, h->o.ldx, h->d, d_rops + t * n + g0, cnt, M, d_batch,
-                                 static_cast<const WorkerDataDev*>(h->data_dev.p), slots, gscale, h->o.lambda,
+                                 slots, gscale, h->o.lambda,
                                  static_cast<float*>(h->grad_scratch.p),
                                  reinterpret_cast<float*>(static_cast<char*>(h->grad_scratch.p) + off_coef), loss};
                 HIP_TRY(h, launch_linear_gradient(a, h->stream, &launches));

@@ -30,7 +30,10 @@ struct GradOp {
     int32_t event;    // index into the call's batch_idx / loss arrays
     int32_t comp_slot;   // wait-free variant: slot of the worker's own pending gradient g_k', or -1
     float comp_gamma;    // its step size: the read is x^ = row - comp_gamma * g_k'
-    int32_t pad[3];
+    int32_t pad;
+    const void* features;   // the worker's local data (device), copied here so that a kernel reaches
+    const void* targets;    //   it with one load instead of a second table look-up
+    int64_t ld;             // leading dimension of features, in elements
 };
 
 struct WorkerData {
@@ -38,13 +41,6 @@ struct WorkerData {
     const void* targets = nullptr;
     int64_t rows = 0;
     int64_t ld = 0;
-};
-
-// Device-side table of the workers' local data (array of n entries).
-struct WorkerDataDev {
-    const void* features;
-    const void* targets;
-    int64_t ld;
 };
 
 struct Plan {
@@ -98,7 +94,6 @@ struct LinearGradArgs {
     int32_t n_ops;
     int32_t M;
     const int32_t* batch_idx;  // device, K x M
-    const WorkerDataDev* data; // device, n entries
     float* slots;
     float gscale;           // 1/M or 1
     float lambda;
@@ -117,7 +112,6 @@ struct MlpGradArgs {
     int32_t n_ops;
     int32_t M;
     const int32_t* batch_idx;
-    const WorkerDataDev* data;
     float* slots;
     float gscale;
     float* loss;

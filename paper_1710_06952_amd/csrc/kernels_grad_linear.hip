@@ -50,7 +50,6 @@ struct LinParams {
     const GradOp* ops;
     int32_t M;
     const int32_t* batch_idx;
-    const WorkerDataDev* data;
     float* slots;
     float gscale;
     float lambda;
@@ -88,8 +87,7 @@ template <bool STREAM>
 __global__ __launch_bounds__(kThreads) void linear_dots_kernel(const LinParams p) {
     __shared__ float red[kWaves][kRowsPerBlock];
     const GradOp op = p.ops[blockIdx.z];
-    const WorkerDataDev wd = p.data[op.worker];
-    const float* __restrict__ A = static_cast<const float*>(wd.features);
+    const float* __restrict__ A = static_cast<const float*>(op.features);
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const int64_t v0 = static_cast<int64_t>(blockIdx.x) * (kDotChunk / 4) + threadIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -108,7 +106,7 @@ __global__ __launch_bounds__(kThreads) void linear_dots_kernel(const LinParams p
         if (m == p.M && p.model != ADPSGD_MODEL_LOGREG) break;
         float acc = 0.0f;
         if (m < p.M) {
-            const float* __restrict__ row = A + static_cast<int64_t>(idx[m]) * wd.ld;
+            const float* __restrict__ row = A + static_cast<int64_t>(idx[m]) * op.ld;
 #pragma unroll
             for (int u = 0; u < kDotUnroll; ++u) {
                 const int64_t v = v0 + static_cast<int64_t>(u) * kThreads;
@@ -157,8 +155,7 @@ __device__ __forceinline__ float sum_chunks(const float* __restrict__ part, int6
 __global__ __launch_bounds__(kThreads) void linear_finalize_kernel(const LinParams p, const int L) {
     __shared__ float red[kWaves];
     const GradOp op = p.ops[blockIdx.x];
-    const WorkerDataDev wd = p.data[op.worker];
-    const float* __restrict__ tg = static_cast<const float*>(wd.targets);
+    const float* __restrict__ tg = static_cast<const float*>(op.targets);
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const float* __restrict__ part = p.partial + static_cast<int64_t>(blockIdx.x) * (p.M + 1) * p.n_chunks;
     const int sub = threadIdx.x & (L - 1), grp = threadIdx.x / L, groups = kThreads / L;
@@ -202,14 +199,13 @@ __global__ __launch_bounds__(kThreads) void linear_combine_kernel(const LinParam
     const GradOp op = p.ops[blockIdx.y];
     const int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
     if (v >= p.n_vec) return;
-    const WorkerDataDev wd = p.data[op.worker];
-    const float* __restrict__ A = static_cast<const float*>(wd.features);
+    const float* __restrict__ A = static_cast<const float*>(op.features);
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const float* __restrict__ cf = p.coef + static_cast<int64_t>(blockIdx.y) * p.M;
     v4f acc = {0, 0, 0, 0};
 #pragma unroll ADPSGD_COMBINE_UNROLL
     for (int m = 0; m < p.M; ++m) {
-        const v4f a = load4<STREAM>(A + static_cast<int64_t>(idx[m]) * wd.ld + 4 * v);
+        const v4f a = load4<STREAM>(A + static_cast<int64_t>(idx[m]) * op.ld + 4 * v);
         acc += a * cf[m];
     }
     if (p.model == ADPSGD_MODEL_LOGREG) {
@@ -236,7 +232,6 @@ hipError_t launch_linear_gradient(const LinearGradArgs& a, hipStream_t st, int* 
     p.ops = a.ops;
     p.M = a.M;
     p.batch_idx = a.batch_idx;
-    p.data = a.data;
     p.slots = a.slots;
     p.gscale = a.gscale;
     p.lambda = a.lambda;

@@ -10,8 +10,11 @@
 // before they enter those products.  The second layer (hid x out, out <= 16) is
 // small and stays on the vector ALUs in fp32.
 //
-// Four launches per group of gradient operations; every reduction has a fixed
-// order, so results do not depend on scheduling.
+// Three launches per group of gradient operations (forward; softmax with the
+// second-layer gradients and the hidden error; dW1); the kernels of a round form a
+// serial chain of small grids, so each one keeps all its global loads in flight
+// at once instead of looping over them.  Every reduction has a fixed order:
+// results do not depend on scheduling.
 #include "device_common.hpp"
 #include "internal.hpp"
 
@@ -33,15 +36,12 @@ struct MlpParams {
     const GradOp* ops;
     int M;
     const int32_t* batch_idx;
-    const WorkerDataDev* data;
     float* slots;
     float gscale;
     float* loss;
     uint16_t* Hb;    // [op][kMaxM][hid]  relu output, bf16
     uint16_t* dHb;   // [op][kMaxM][hid]  error at the hidden pre-activation, bf16, rows >= M zero
-    float* dlogit;   // [op][kMaxM][kMaxOut]  softmax - onehot
     float* logit_part;  // [op][hid / 32][kMaxM][kMaxOut]  second-layer products of one forward tile
-    float* loss_m;   // [op][kMaxM]
 };
 
 __device__ __forceinline__ v4f mfma_bf16(v8h a, v8h b, v4f c) {
@@ -53,37 +53,44 @@ __device__ __forceinline__ v4f mfma_bf16(v8h a, v8h b, v4f c) {
 //   lane l receives D[4 (l / 16) + v][l % 16] in element v of its 4 results.
 
 // ---- 1. forward: H = relu(Xb W1 + b1), grid = (hid / 32, n_ops) ----------------------
-// One block owns a 64 (minibatch) x 32 (hidden) tile of H.  The contraction over the input
-// features is split across the four wavefronts (k-steps of 32, step s goes to wavefront s % 4),
-// each with its own transposed W1 tile in LDS; the next step's operands are fetched into
-// registers while the current step's MFMAs run.  The four partial tiles are then added in a
-// fixed order through LDS.
+// One block (512 threads) owns a 64 (minibatch) x 32 (hidden) tile of H.  The contraction over
+// the input features is split across the eight wavefronts (k-steps of 32, step s goes to
+// wavefront s % 8), each with its own transposed W1 tile in LDS; the operands of up to kFwdDepth
+// steps of a wavefront (all of them for 784 inputs) are requested before the first MFMA, so the
+// kernel pays the memory latency once.  The eight partial tiles are added in a fixed order
+// through LDS -- (w, w + 4) first, then the four sums in sequence, every thread finishing four
+// elements of the tile -- and the block adds its share of the logits, one thread per two of them.
 constexpr int kFwdTileH = 32;
+constexpr int kFwdT = 512;
+constexpr int kFwdWaves = kFwdT / 64;
+constexpr int kFwdDepth = 4;
 
 struct FwdOperands {
     v8h w[2];   // W1 tile 32 (k) x 32 (h): lane holds 2 rows k, 8 columns each
     v8h a[4];   // input fragments of the four 16-row minibatch tiles
 };
 
-__global__ __launch_bounds__(kT) void mlp_forward_kernel(const MlpParams p) {
-    __shared__ __attribute__((aligned(16))) unsigned char smem[16384];
+__global__ __launch_bounds__(kFwdT) void mlp_forward_kernel(const MlpParams p) {
+    // per-wavefront W1 tiles during the contraction (8 x 2560 B), then four partial tiles (4 x 8 KiB)
+    __shared__ __attribute__((aligned(16))) unsigned char smem[32768];
     __shared__ float W2s[kFwdTileH][kMaxOut];     // this tile's rows of W2, zero beyond `out`
+    __shared__ float Hs[kMaxM][kFwdTileH + 1];     // the finished tile, as the next layer sees it
     const GradOp op = p.ops[blockIdx.y];
-    const WorkerDataDev wd = p.data[op.worker];
-    const uint16_t* __restrict__ feat = static_cast<const uint16_t*>(wd.features);
+    const uint16_t* __restrict__ feat = static_cast<const uint16_t*>(op.features);
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const uint16_t* __restrict__ W1 = p.Xb + static_cast<int64_t>(op.worker) * p.ld;
     const uint16_t* __restrict__ b1 = W1 + static_cast<int64_t>(p.in) * p.hid;
     const int h0 = blockIdx.x * kFwdTileH;
-    {
-        const uint16_t* __restrict__ W2 = b1 + p.hid;
-        for (int t = threadIdx.x; t < kFwdTileH * kMaxOut; t += kT) {
-            const int hh = t / kMaxOut, o = t % kMaxOut;
-            W2s[hh][o] = o < p.out ? bf16_to_float(W2[static_cast<int64_t>(h0 + hh) * p.out + o]) : 0.0f;
-        }
-    }
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int li = lane & 15, kb = 8 * (lane >> 4);
+    // small operands of the epilogue, requested now and used after the contraction
+    uint16_t w2raw;
+    const uint16_t b1raw = b1[h0 + 16 * ((wave >> 2) & 1) + li];   // bias of the hidden unit this thread finishes
+    {
+        const uint16_t* __restrict__ W2 = b1 + p.hid;
+        const int hh = threadIdx.x / kMaxOut, o = threadIdx.x % kMaxOut;     // 512 = 32 x 16
+        w2raw = o < p.out ? W2[static_cast<int64_t>(h0 + hh) * p.out + o] : static_cast<uint16_t>(0);
+    }
     uint16_t(*Bt)[40] = reinterpret_cast<uint16_t(*)[40]>(smem + wave * (kFwdTileH * 40 * 2));   // [h][k]
     float* red = reinterpret_cast<float*>(smem);
 
@@ -91,7 +98,7 @@ __global__ __launch_bounds__(kT) void mlp_forward_kernel(const MlpParams p) {
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
         const int m = 16 * mt + li;
-        rowp[mt] = m < p.M ? feat + static_cast<int64_t>(idx[m]) * wd.ld : nullptr;
+        rowp[mt] = m < p.M ? feat + static_cast<int64_t>(idx[m]) * op.ld : nullptr;
     }
     const int skk = lane >> 2, shh = (lane & 3) * 8;   // staging role inside the wavefront
     auto fetch = [&](int step, FwdOperands& f) {
@@ -113,204 +120,217 @@ __global__ __launch_bounds__(kT) void mlp_forward_kernel(const MlpParams p) {
 #pragma unroll
         for (int ht = 0; ht < 2; ++ht) acc[mt][ht] = v4f{0, 0, 0, 0};
 
-    const int steps = (p.in + 31) / 32, iters = (steps + 3) / 4;   // same trip count for every wavefront
-    FwdOperands cur, nxt;
-    fetch(wave, cur);            // steps beyond the last one fetch zeros
-    for (int it = 0; it < iters; ++it) {
+    const int steps = (p.in + 31) / 32, iters = (steps + kFwdWaves - 1) / kFwdWaves;   // same trip count for every wavefront
+    for (int it0 = 0; it0 < iters; it0 += kFwdDepth) {
+        FwdOperands f[kFwdDepth];
 #pragma unroll
-        for (int r = 0; r < 2; ++r)
+        for (int u = 0; u < kFwdDepth; ++u)
+            if (it0 + u < iters) fetch(wave + kFwdWaves * (it0 + u), f[u]);   // steps beyond the last one fetch zeros
 #pragma unroll
-            for (int e = 0; e < 8; ++e) Bt[shh + e][skk + 16 * r] = cur.w[r][e];
-        if (it + 1 < iters) fetch(wave + 4 * (it + 1), nxt);
-        __syncthreads();
-        v8h bfrag[2];
+        for (int u = 0; u < kFwdDepth; ++u) {
+            if (it0 + u < iters) {        // the same for every thread of the block
 #pragma unroll
-        for (int ht = 0; ht < 2; ++ht) bfrag[ht] = *reinterpret_cast<const v8h*>(&Bt[16 * ht + li][kb]);
+                for (int r = 0; r < 2; ++r)
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+                    for (int e = 0; e < 8; ++e) Bt[shh + e][skk + 16 * r] = f[u].w[r][e];
+                __syncthreads();
+                v8h bfrag[2];
 #pragma unroll
-            for (int ht = 0; ht < 2; ++ht) acc[mt][ht] = mfma_bf16(cur.a[mt], bfrag[ht], acc[mt][ht]);
-        __syncthreads();
-        cur = nxt;
-    }
-
-    // (wave0 + wave2) + (wave1 + wave3), element q of lane l at red[half][q][l]
-    auto spill = [&](int half) {
+                for (int ht = 0; ht < 2; ++ht) bfrag[ht] = *reinterpret_cast<const v8h*>(&Bt[16 * ht + li][kb]);
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+                for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-            for (int ht = 0; ht < 2; ++ht)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) red[(half * 32 + (mt * 2 + ht) * 4 + v) * 64 + lane] = acc[mt][ht][v];
-    };
-    auto absorb = [&](int half) {
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-            for (int ht = 0; ht < 2; ++ht)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) acc[mt][ht][v] += red[(half * 32 + (mt * 2 + ht) * 4 + v) * 64 + lane];
-    };
-    if (wave >= 2) spill(wave - 2);
-    __syncthreads();
-    if (wave < 2) absorb(wave);
-    __syncthreads();
-    if (wave == 1) spill(0);
-    __syncthreads();
-    float(*Hs)[kFwdTileH + 1] = reinterpret_cast<float(*)[kFwdTileH + 1]>(smem);   // the finished tile, as the next layer sees it
-    if (wave == 0) {
-        absorb(0);
-#pragma unroll
-        for (int ht = 0; ht < 2; ++ht) {
-            const int h = h0 + 16 * ht + li;
-            const float bias = bf16_to_float(b1[h]);
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int m = 16 * mt + 4 * (lane >> 4) + v;
-                    float hval = 0.0f;
-                    if (m < p.M) {
-                        const float pre = acc[mt][ht][v] + bias;
-                        const uint16_t hb = bf16_rne(pre > 0.0f ? pre : 0.0f);
-                        p.Hb[(static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h] = hb;
-                        hval = bf16_to_float(hb);
-                    }
-                    Hs[m][16 * ht + li] = hval;
-                }
+                    for (int ht = 0; ht < 2; ++ht) acc[mt][ht] = mfma_bf16(f[u].a[mt], bfrag[ht], acc[mt][ht]);
+                __syncthreads();
+            }
         }
     }
+    W2s[threadIdx.x / kMaxOut][threadIdx.x % kMaxOut] = bf16_to_float(w2raw);
+
+    // element q = (mt, ht, v) of lane l of partial tile w at red[(w * 32 + q) * 64 + l]
+    auto spill = [&](int w) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int ht = 0; ht < 2; ++ht)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) red[(w * 32 + (mt * 2 + ht) * 4 + v) * 64 + lane] = acc[mt][ht][v];
+    };
+    if (wave >= 4) spill(wave - 4);
     __syncthreads();
-    // this tile's share of the logits: thread (m, oq) sums over the 32 hidden units in order
+    if (wave < 4) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int ht = 0; ht < 2; ++ht)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[mt][ht][v] += red[((wave * 32) + (mt * 2 + ht) * 4 + v) * 64 + lane];
+    }
+    __syncthreads();
+    if (wave < 4) spill(wave);
+    __syncthreads();
+    // every thread finishes four elements: q = wave + 8 j
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int q = wave + kFwdWaves * j;
+        const float sum = ((red[(0 * 32 + q) * 64 + lane] + red[(1 * 32 + q) * 64 + lane]) + red[(2 * 32 + q) * 64 + lane]) +
+                          red[(3 * 32 + q) * 64 + lane];
+        const int mt = q >> 3, ht = (q >> 2) & 1, v = q & 3;
+        const int m = 16 * mt + 4 * (lane >> 4) + v, hh = 16 * ht + li;
+        float hval = 0.0f;
+        if (m < p.M) {
+            const float pre = sum + bf16_to_float(b1raw);
+            const uint16_t hb = bf16_rne(pre > 0.0f ? pre : 0.0f);
+            p.Hb[(static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h0 + hh] = hb;
+            hval = bf16_to_float(hb);
+        }
+        Hs[m][hh] = hval;
+    }
+    __syncthreads();
+    // this tile's share of the logits: thread (m, op) sums over the 32 hidden units in order
     {
-        const int m = threadIdx.x >> 2, oq = threadIdx.x & 3;
-        float part[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        const int m = threadIdx.x >> 3, o2 = threadIdx.x & 7;
+        float part[2] = {0.0f, 0.0f};
 #pragma unroll 8
         for (int hh = 0; hh < kFwdTileH; ++hh) {
             const float hv = Hs[m][hh];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) part[q] += hv * W2s[hh][oq + 4 * q];
+            for (int q = 0; q < 2; ++q) part[q] += hv * W2s[hh][o2 + 8 * q];
         }
         float* __restrict__ dst = p.logit_part + ((static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x) * kMaxM + m) * kMaxOut;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) dst[oq + 4 * q] = part[q];
+        for (int q = 0; q < 2; ++q) dst[o2 + 8 * q] = part[q];
     }
 }
 
-// ---- 2. logits, softmax, loss: grid = n_ops, one block per gradient --------------------
-// Thread (m, oq) adds the hid / 32 tile contributions of logits oq, oq + 4, oq + 8, oq + 12 of sample
-// m in tile order; one thread per sample then does the softmax.
-__global__ __launch_bounds__(kT) void mlp_softmax_kernel(const MlpParams p) {
-    __shared__ float logit_s[kMaxM][kMaxOut + 1];
-    const GradOp op = p.ops[blockIdx.x];
-    const WorkerDataDev wd = p.data[op.worker];
-    const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
-    const uint16_t* __restrict__ W = p.Xb + static_cast<int64_t>(op.worker) * p.ld;
-    const uint16_t* __restrict__ b2 = W + static_cast<int64_t>(p.in) * p.hid + p.hid + static_cast<int64_t>(p.hid) * p.out;
-    const int tiles = p.hid / kFwdTileH;
-    {
-        const int m = threadIdx.x >> 2, oq = threadIdx.x & 3;
-        const float* __restrict__ src = p.logit_part + (static_cast<int64_t>(blockIdx.x) * tiles * kMaxM + m) * kMaxOut + oq;
-        float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        for (int t0 = 0; t0 < tiles; t0 += 8) {
-            float buf[8][4];
-#pragma unroll
-            for (int t = 0; t < 8; ++t)
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    buf[t][q] = (t0 + t < tiles) ? src[static_cast<int64_t>(t0 + t) * kMaxM * kMaxOut + 4 * q] : 0.0f;
-#pragma unroll
-            for (int t = 0; t < 8; ++t)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) acc[q] += buf[t][q];
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) logit_s[m][oq + 4 * q] = acc[q];
-    }
-    __syncthreads();
-    if (threadIdx.x < p.M) {
-        const int m = threadIdx.x;
-        float logit[kMaxOut];
-        float zmax = -INFINITY;
-        for (int o = 0; o < p.out; ++o) {
-            logit[o] = logit_s[m][o] + bf16_to_float(b2[o]);
-            zmax = fmaxf(zmax, logit[o]);
-        }
-        float zsum = 0.0f;
-        for (int o = 0; o < p.out; ++o) zsum += expf(logit[o] - zmax);
-        const int label = static_cast<const int32_t*>(wd.targets)[idx[m]];
-        float* dl = p.dlogit + (static_cast<int64_t>(blockIdx.x) * kMaxM + m) * kMaxOut;
-        float lsel = 0.0f;
-        for (int o = 0; o < p.out; ++o) {
-            dl[o] = expf(logit[o] - zmax) / zsum - (o == label ? 1.0f : 0.0f);
-            if (o == label) lsel = logit[o];
-        }
-        p.loss_m[static_cast<int64_t>(blockIdx.x) * kMaxM + m] = -(lsel - zmax - logf(zsum));
-    }
-}
+// ---- 2. softmax, second-layer gradients and the hidden error: grid = (hid / 64, n_ops) ----
+// 1024 threads.  The grid is small and the work per block is a chain of short dependent steps,
+// so the block is wide: every step is spread over 16 wavefronts and every global operand is
+// requested before the first one is used.
+//   a. thread (m, o) finishes logit o of sample m (sum of the hid / 32 forward-tile contributions
+//      in tile order); the 16 lanes of a sample take the softmax together (butterfly max and sum).
+//      The 16 blocks of a gradient repeat this small step rather than wait for a kernel of its own.
+//   b. thread (hl, mg): hidden unit h = 64 blockIdx.x + hl, minibatch rows [4 mg, 4 mg + 4):
+//      its share of dW2 and db1, and the hidden error dH (rounded to bf16) of its four rows.
+//   c. the 16 row groups are added pairwise in a fixed tree through LDS.
+constexpr int kBwdT = 1024;
+constexpr int kBwdGroups = kBwdT / 64;            // 16 row groups
+constexpr int kBwdRows = kMaxM / kBwdGroups;      // 4 minibatch rows per thread
 
-// ---- 3. second-layer gradients and the hidden error: grid = (hid / 64, n_ops) ---------
-// Thread (hl, mg): hidden unit h = 64 blockIdx.x + hl, minibatch rows [16 mg, 16 mg + 16).
-// Sums over the minibatch are finished across the four row groups in a fixed order.
-__global__ __launch_bounds__(kT) void mlp_backward_small_kernel(const MlpParams p) {
-    __shared__ float dl_s[kMaxM][kMaxOut];
-    __shared__ float red[4][kMaxOut + 1][64];
+__global__ __launch_bounds__(kBwdT) void mlp_backward_small_kernel(const MlpParams p) {
+    __shared__ __attribute__((aligned(16))) float dl_s[kMaxM][kMaxOut];   // softmax - onehot, zero beyond M and out
+    __shared__ float loss_s[kMaxM];
+    __shared__ float red[kBwdGroups / 2][kMaxOut + 1][64];
     const GradOp op = p.ops[blockIdx.y];
+    const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const int hl = threadIdx.x & 63, mg = threadIdx.x >> 6;
     const int h = blockIdx.x * 64 + hl;
+    const int sm = threadIdx.x >> 4, so = threadIdx.x & 15;       // step a: sample and logit
     const uint16_t* __restrict__ W = p.Xb + static_cast<int64_t>(op.worker) * p.ld;
     const uint16_t* __restrict__ W2 = W + static_cast<int64_t>(p.in) * p.hid + p.hid;
+    const uint16_t* __restrict__ b2 = W2 + static_cast<int64_t>(p.hid) * p.out;
+
+    // ---- all global loads
+    int label = -1;
+    if (sm < p.M) label = static_cast<const int32_t*>(op.targets)[idx[sm]];
+    const int tiles = p.hid / kFwdTileH;
+    const float* __restrict__ src = p.logit_part + (static_cast<int64_t>(blockIdx.y) * tiles * kMaxM + sm) * kMaxOut + so;
+    constexpr int kTileBatch = 32;
+    float part[kTileBatch];
+#pragma unroll
+    for (int t = 0; t < kTileBatch; ++t) part[t] = t < tiles ? src[static_cast<int64_t>(t) * kMaxM * kMaxOut] : 0.0f;
+    const uint16_t b2raw = so < p.out ? b2[so] : static_cast<uint16_t>(0);
+    uint16_t w2raw[kMaxOut], hraw[kBwdRows];
+#pragma unroll
+    for (int o = 0; o < kMaxOut; ++o) w2raw[o] = o < p.out ? W2[static_cast<int64_t>(h) * p.out + o] : static_cast<uint16_t>(0);
+#pragma unroll
+    for (int r = 0; r < kBwdRows; ++r) {
+        const int m = kBwdRows * mg + r;
+        hraw[r] = m < p.M ? p.Hb[(static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h] : static_cast<uint16_t>(0);
+    }
+
+    // ---- a. logits and softmax
+    {
+        float z = 0.0f;
+#pragma unroll
+        for (int t = 0; t < kTileBatch; ++t) z += part[t];
+        for (int t0 = kTileBatch; t0 < tiles; t0 += kTileBatch) {      // hidden layers wider than 1024
+#pragma unroll
+            for (int t = 0; t < kTileBatch; ++t) part[t] = (t0 + t < tiles) ? src[static_cast<int64_t>(t0 + t) * kMaxM * kMaxOut] : 0.0f;
+#pragma unroll
+            for (int t = 0; t < kTileBatch; ++t) z += part[t];
+        }
+        const bool live = so < p.out;
+        const float logit = live ? z + bf16_to_float(b2raw) : -INFINITY;
+        float zmax = logit;
+#pragma unroll
+        for (int off = 8; off > 0; off >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, off, 64));
+        const float ez = live ? expf(logit - zmax) : 0.0f;
+        float zsum = ez;
+#pragma unroll
+        for (int off = 8; off > 0; off >>= 1) zsum += __shfl_xor(zsum, off, 64);
+        const int lsrc = (threadIdx.x & 48) + (label >= 0 && label < p.out ? label : 0);   // lane of the labelled class
+        const float lsel = __shfl(logit, lsrc, 64);
+        dl_s[sm][so] = (live && sm < p.M) ? ez / zsum - (so == label ? 1.0f : 0.0f) : 0.0f;
+        if (so == 0) loss_s[sm] = sm < p.M ? -(lsel - zmax - logf(zsum)) : 0.0f;
+    }
+    __syncthreads();
+
+    // ---- b. this thread's hidden unit and rows
     float* __restrict__ g = p.slots + static_cast<int64_t>(op.slot) * p.ld;
     float* __restrict__ gb1 = g + static_cast<int64_t>(p.in) * p.hid;
     float* __restrict__ gW2 = gb1 + p.hid;
     float* __restrict__ gb2 = gW2 + static_cast<int64_t>(p.hid) * p.out;
-    const float* __restrict__ dl0 = p.dlogit + static_cast<int64_t>(blockIdx.y) * kMaxM * kMaxOut;
-    for (int t = threadIdx.x; t < kMaxM * kMaxOut; t += kT) {
-        const int m = t / kMaxOut, o = t % kMaxOut;
-        dl_s[m][o] = (m < p.M && o < p.out) ? dl0[t] : 0.0f;
-    }
-    __syncthreads();
     float w2[kMaxOut], gw2[kMaxOut];
 #pragma unroll
     for (int o = 0; o < kMaxOut; ++o) {
-        w2[o] = o < p.out ? bf16_to_float(W2[static_cast<int64_t>(h) * p.out + o]) : 0.0f;
+        w2[o] = bf16_to_float(w2raw[o]);
         gw2[o] = 0.0f;
     }
     float sum_dh = 0.0f;
-    uint16_t hraw[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {      // all 16 activations of this thread in flight at once
-        const int m = 16 * mg + r;
-        hraw[r] = m < p.M ? p.Hb[(static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h] : static_cast<uint16_t>(0);
-    }
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int m = 16 * mg + r;
+    for (int r = 0; r < kBwdRows; ++r) {
+        const int m = kBwdRows * mg + r;
         const int64_t at = (static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h;
-        uint16_t dh = 0;
-        if (m < p.M) {
-            const float hv = bf16_to_float(hraw[r]);
-            float back = 0.0f;
+        float dl[kMaxOut];
 #pragma unroll
-            for (int o = 0; o < kMaxOut; ++o) {     // entries o >= out are zero in dl_s and w2
-                gw2[o] += hv * dl_s[m][o];
-                back += dl_s[m][o] * w2[o];
-            }
-            dh = bf16_rne(hv > 0.0f ? back * p.gscale : 0.0f);
-            sum_dh += bf16_to_float(dh);
+        for (int q = 0; q < kMaxOut / 4; ++q) {
+            const v4f t4 = *reinterpret_cast<const v4f*>(&dl_s[m][4 * q]);
+            dl[4 * q] = t4.x; dl[4 * q + 1] = t4.y; dl[4 * q + 2] = t4.z; dl[4 * q + 3] = t4.w;
         }
-        p.dHb[at] = dh;                              // rows m >= M are the zero padding of the dW1 product
-    }
+        const float hv = bf16_to_float(hraw[r]);       // zero for rows m >= M, whose dl is zero as well
+        float back = 0.0f;
 #pragma unroll
-    for (int o = 0; o < kMaxOut; ++o) red[mg][o][hl] = gw2[o];
-    red[mg][kMaxOut][hl] = sum_dh;
-    __syncthreads();
+        for (int o = 0; o < kMaxOut; ++o) {             // entries o >= out are zero in dl_s and w2
+            gw2[o] += hv * dl[o];
+            back += dl[o] * w2[o];
+        }
+        const uint16_t dh = (m < p.M && hv > 0.0f) ? bf16_rne(back * p.gscale) : static_cast<uint16_t>(0);
+        sum_dh += bf16_to_float(dh);
+        p.dHb[at] = dh;                                  // rows m >= M are the zero padding of the dW1 product
+    }
+
+    // ---- c. fixed pairwise tree over the 16 row groups: (g, g + 8), then (g, g + 4), (g, g + 2), (g, g + 1)
+#pragma unroll
+    for (int half = kBwdGroups / 2; half > 0; half >>= 1) {
+        if (mg >= half && mg < 2 * half) {
+#pragma unroll
+            for (int o = 0; o < kMaxOut; ++o) red[mg - half][o][hl] = gw2[o];
+            red[mg - half][kMaxOut][hl] = sum_dh;
+        }
+        __syncthreads();
+        if (mg < half) {
+#pragma unroll
+            for (int o = 0; o < kMaxOut; ++o) gw2[o] += red[mg][o][hl];
+            sum_dh += red[mg][kMaxOut][hl];
+        }
+        __syncthreads();
+    }
     if (mg == 0) {
 #pragma unroll
         for (int o = 0; o < kMaxOut; ++o)
-            if (o < p.out)
-                gW2[static_cast<int64_t>(h) * p.out + o] = ((red[0][o][hl] + red[1][o][hl]) + (red[2][o][hl] + red[3][o][hl])) * p.gscale;
-        gb1[h] = (red[0][kMaxOut][hl] + red[1][kMaxOut][hl]) + (red[2][kMaxOut][hl] + red[3][kMaxOut][hl]);
+            if (o < p.out) gW2[static_cast<int64_t>(h) * p.out + o] = gw2[o] * p.gscale;
+        gb1[h] = sum_dh;
     }
     if (blockIdx.x == 0 && mg == 1 && hl < p.out) {
         float sdl = 0.0f;
@@ -319,18 +339,17 @@ __global__ __launch_bounds__(kT) void mlp_backward_small_kernel(const MlpParams 
     }
     if (blockIdx.x == 0 && threadIdx.x == 128 && p.loss) {
         float sl = 0.0f;
-        for (int m = 0; m < p.M; ++m) sl += p.loss_m[static_cast<int64_t>(blockIdx.y) * kMaxM + m];
+        for (int m = 0; m < p.M; ++m) sl += loss_s[m];
         p.loss[op.event] = sl * p.gscale;
     }
 }
 
-// ---- 4. dW1 = Xb^T dH: grid = (hid / 64, ceil(in / 64), n_ops) -------------------------
+// ---- 3. dW1 = Xb^T dH: grid = (hid / 64, ceil(in / 64), n_ops) -------------------------
 __global__ __launch_bounds__(kT) void mlp_dw1_kernel(const MlpParams p) {
     __shared__ __attribute__((aligned(16))) uint16_t At[64][72];   // inputs transposed:  [i][m], 64 m + pad
     __shared__ __attribute__((aligned(16))) uint16_t Bt[64][72];   // hidden error transposed: [h][m]
     const GradOp op = p.ops[blockIdx.z];
-    const WorkerDataDev wd = p.data[op.worker];
-    const uint16_t* __restrict__ feat = static_cast<const uint16_t*>(wd.features);
+    const uint16_t* __restrict__ feat = static_cast<const uint16_t*>(op.features);
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const int h0 = blockIdx.x * kTileH, i0 = blockIdx.y * 64;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -342,7 +361,7 @@ __global__ __launch_bounds__(kT) void mlp_dw1_kernel(const MlpParams p) {
         for (int half = 0; half < 2; ++half) {
             const int c = seg + 8 * half;
             v8h xv = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (m < p.M && i0 + c < p.in) xv = *reinterpret_cast<const v8h*>(feat + static_cast<int64_t>(idx[m]) * wd.ld + i0 + c);
+            if (m < p.M && i0 + c < p.in) xv = *reinterpret_cast<const v8h*>(feat + static_cast<int64_t>(idx[m]) * op.ld + i0 + c);
             const v8h dv = *reinterpret_cast<const v8h*>(p.dHb + (static_cast<int64_t>(blockIdx.z) * kMaxM + m) * p.hid + h0 + c);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -385,7 +404,7 @@ size_t mlp_scratch_bytes(int32_t n_ops, int32_t M, int32_t in, int32_t hid, int3
         return 0;
     const size_t act = align256(static_cast<size_t>(n_ops) * kMaxM * hid * sizeof(uint16_t));
     const size_t lp = align256(static_cast<size_t>(n_ops) * (hid / kFwdTileH) * kMaxM * kMaxOut * 4);
-    return 2 * act + align256(static_cast<size_t>(n_ops) * kMaxM * kMaxOut * 4) + align256(static_cast<size_t>(n_ops) * kMaxM * 4) + lp;
+    return 2 * act + lp;
 }
 
 hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_launches) {
@@ -400,7 +419,6 @@ hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_laun
     p.ops = a.ops;
     p.M = a.M;
     p.batch_idx = a.batch_idx;
-    p.data = a.data;
     p.slots = a.slots;
     p.gscale = a.gscale;
     p.loss = a.loss;
@@ -408,20 +426,15 @@ hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_laun
     const size_t act = align256(static_cast<size_t>(a.n_ops) * kMaxM * a.hid * sizeof(uint16_t));
     p.Hb = reinterpret_cast<uint16_t*>(s);
     p.dHb = reinterpret_cast<uint16_t*>(s + act);
-    p.dlogit = reinterpret_cast<float*>(s + 2 * act);
-    p.loss_m = reinterpret_cast<float*>(s + 2 * act + align256(static_cast<size_t>(a.n_ops) * kMaxM * kMaxOut * 4));
-    p.logit_part = reinterpret_cast<float*>(s + 2 * act + align256(static_cast<size_t>(a.n_ops) * kMaxM * kMaxOut * 4) +
-                                            align256(static_cast<size_t>(a.n_ops) * kMaxM * 4));
+    p.logit_part = reinterpret_cast<float*>(s + 2 * act);
     const uint32_t hb = static_cast<uint32_t>(a.hid / kTileH);
-    hipLaunchKernelGGL(mlp_forward_kernel, dim3(a.hid / kFwdTileH, a.n_ops), dim3(kT), 0, st, p);
+    hipLaunchKernelGGL(mlp_forward_kernel, dim3(a.hid / kFwdTileH, a.n_ops), dim3(kFwdT), 0, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(mlp_softmax_kernel, dim3(a.n_ops), dim3(kT), 0, st, p);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(mlp_backward_small_kernel, dim3(a.hid / 64, a.n_ops), dim3(kT), 0, st, p);
+    hipLaunchKernelGGL(mlp_backward_small_kernel, dim3(a.hid / 64, a.n_ops), dim3(kBwdT), 0, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(mlp_dw1_kernel, dim3(hb, (a.in + 63) / 64, a.n_ops), dim3(kT), 0, st, p);
-    if (n_launches) *n_launches += 4;
+    if (n_launches) *n_launches += 3;
     return hipGetLastError();
 }
 
