@@ -212,7 +212,7 @@ typedef struct {
 
 /* Runs the iterations on the handle's stream (asynchronous, arrays reusable on return).  loss
  * (device, S * n floats, [t][i], or NULL) receives the minibatch losses.  Needs at least n
- * pending-gradient slots in the workspace (data models) and n <= 256; not available with momentum
+ * pending-gradient slots in the workspace (data models) and n <= 1024; not available with momentum
  * / weight decay.  Errors as adpsgd_run_events, with no state change. */
 int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* s, float* loss);
 

@@ -524,7 +524,7 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
     const int32_t M = with_grad ? h->o.M : 0;
     if (S * n > 0x7FFFFFF0) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: S * n must stay below 2^31 - 16");
     if (h->o.V) return fail(h, ADPSGD_ERR_STATE, "run_sync_steps: not available with momentum / weight decay");
-    if (sync_tile_cols(n) == 0) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: at most 256 workers");
+    if (sync_tile_cols(n) == 0) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: at most 1024 workers");
     if (with_grad && !s->batch_idx) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: batch_idx is NULL");
     if (with_grad && h->n_slots < n)
         return fail(h, ADPSGD_ERR_STATE, "run_sync_steps: the workspace must hold one gradient slot per worker");

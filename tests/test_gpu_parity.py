@@ -584,7 +584,7 @@ def _dense_from_csr(g, w_self, w_edge):
     return W
 
 
-@pytest.mark.parametrize("n,d,S,graph", [(8, 5003, 40, "ring"), (16, 1030, 25, "reg4"), (128, 777, 10, "ring"),
+@pytest.mark.parametrize("n,d,S,graph", [(8, 5003, 40, "ring"), (16, 1030, 25, "reg4"), (128, 777, 10, "ring"), (300, 100, 4, "ring"),
                                          (200, 130, 6, "ring"), (1, 100, 5, "ring")])
 def test_sync_steps_synthetic(P, n, d, S, graph):
     """All workers step together: X <- W X - gamma G, W = Metropolis weights of the graph; spans the three
