@@ -11,6 +11,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr int kConsensusBlocksMax = 2048;
+constexpr int64_t kStreamBytes = 256ll << 20;   // beyond this X cannot stay in the caches
 
 // grid = (ceil(ld/4 / kThreads), n): every row <- x0 on [0, d), zero on [d, ld)
 __global__ __launch_bounds__(kThreads) void broadcast_rows_kernel(float* X, int64_t ld, int64_t d, const float* x0) {
@@ -32,14 +33,24 @@ __global__ __launch_bounds__(kThreads) void refresh_bf16_kernel(const float* X, 
     *reinterpret_cast<v4h*>(Xb + off) = h;
 }
 
+constexpr int kRowBatch = 8;   // rows whose loads are in flight together
+
 // one thread per float4 of d: column sums over the n rows in a fixed order
+// STREAM: X does not fit the caches and is read once: non-temporal loads
+template <bool STREAM>
 __global__ __launch_bounds__(kThreads) void mean_model_kernel(const float* X, int64_t ld, int64_t d, int32_t n, float* out) {
     const int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
     if (4 * v >= d) return;
     double s[4] = {0, 0, 0, 0};
-    for (int32_t i = 0; i < n; ++i) {
-        const v4f x = *reinterpret_cast<const v4f*>(X + static_cast<int64_t>(i) * ld + 4 * v);
-        s[0] += x.x; s[1] += x.y; s[2] += x.z; s[3] += x.w;
+    for (int32_t i0 = 0; i0 < n; i0 += kRowBatch) {
+        v4f x[kRowBatch];
+#pragma unroll
+        for (int r = 0; r < kRowBatch; ++r)
+            x[r] = i0 + r < n ? load4<STREAM>(X + static_cast<int64_t>(i0 + r) * ld + 4 * v) : v4f{0, 0, 0, 0};
+#pragma unroll
+        for (int r = 0; r < kRowBatch; ++r) {
+            s[0] += x[r].x; s[1] += x[r].y; s[2] += x[r].z; s[3] += x[r].w;
+        }
     }
     for (int c = 0; c < 4; ++c)
         if (4 * v + c < d) out[4 * v + c] = static_cast<float>(s[c] / n);
@@ -49,6 +60,7 @@ __global__ __launch_bounds__(kThreads) void mean_model_kernel(const float* X, in
 // (shifting by row 0 keeps the subtraction exact when the replicas are close).
 // Grid-stride over float4 columns, fp64 accumulation, wavefront reduction, one
 // partial per block; a second single-block launch sums the partials in order.
+template <bool STREAM>
 __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(const float* X, int64_t ld, int64_t d, int32_t n,
                                                                     double* partial) {
     __shared__ double red[kWaves];
@@ -58,12 +70,20 @@ __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(const float
          v += static_cast<int64_t>(gridDim.x) * kThreads) {
         const v4f x0 = *reinterpret_cast<const v4f*>(X + 4 * v);
         double s1[4] = {0, 0, 0, 0}, s2[4] = {0, 0, 0, 0};
-        for (int32_t i = 1; i < n; ++i) {
-            const v4f x = *reinterpret_cast<const v4f*>(X + static_cast<int64_t>(i) * ld + 4 * v);
-            const float t[4] = {x.x - x0.x, x.y - x0.y, x.z - x0.z, x.w - x0.w};
-            for (int c = 0; c < 4; ++c) {
-                s1[c] += t[c];
-                s2[c] += static_cast<double>(t[c]) * t[c];
+        for (int32_t i0 = 1; i0 < n; i0 += kRowBatch) {
+            v4f xr[kRowBatch];
+#pragma unroll
+            for (int r = 0; r < kRowBatch; ++r)      // rows beyond n repeat row 0: their t is zero
+                xr[r] = i0 + r < n ? load4<STREAM>(X + static_cast<int64_t>(i0 + r) * ld + 4 * v) : x0;
+#pragma unroll
+            for (int r = 0; r < kRowBatch; ++r) {
+                const v4f x = xr[r];
+                const float t[4] = {x.x - x0.x, x.y - x0.y, x.z - x0.z, x.w - x0.w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    s1[c] += t[c];
+                    s2[c] += static_cast<double>(t[c]) * t[c];
+                }
             }
         }
         for (int c = 0; c < 4; ++c)
@@ -105,7 +125,10 @@ hipError_t launch_refresh_bf16(const float* X, uint16_t* Xb, int64_t ld, int32_t
 hipError_t launch_mean_model(const float* X, int64_t ld, int64_t d, int32_t n, float* out, hipStream_t st) {
     const int64_t blocks = ((d + 3) / 4 + kThreads - 1) / kThreads;
     if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(mean_model_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, st, X, ld, d, n, out);
+    if (static_cast<int64_t>(n) * ld * 4 > kStreamBytes)
+        hipLaunchKernelGGL(mean_model_kernel<true>, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, st, X, ld, d, n, out);
+    else
+        hipLaunchKernelGGL(mean_model_kernel<false>, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, st, X, ld, d, n, out);
     return hipGetLastError();
 }
 
@@ -117,7 +140,10 @@ int32_t consensus_blocks(int64_t d) {
 hipError_t launch_consensus(const float* X, int64_t ld, int64_t d, int32_t n, double* partial, double* result,
                             hipStream_t st) {
     const int32_t blocks = consensus_blocks(d);
-    hipLaunchKernelGGL(consensus_partial_kernel, dim3(blocks), dim3(kThreads), 0, st, X, ld, d, n, partial);
+    if (static_cast<int64_t>(n) * ld * 4 > kStreamBytes)
+        hipLaunchKernelGGL(consensus_partial_kernel<true>, dim3(blocks), dim3(kThreads), 0, st, X, ld, d, n, partial);
+    else
+        hipLaunchKernelGGL(consensus_partial_kernel<false>, dim3(blocks), dim3(kThreads), 0, st, X, ld, d, n, partial);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, st, partial, blocks, n, result);
