@@ -216,6 +216,115 @@ __global__ __launch_bounds__(kThreads) void linear_combine_kernel(const LinParam
     *reinterpret_cast<v4f*>(p.slots + static_cast<int64_t>(op.slot) * p.ld + 4 * v) = acc;
 }
 
+// ---- short models: the whole gradient of one operation in one block, one launch -----------
+// For d <= 4096 a round is a chain of launch-bound kernels, so the three steps above run in a
+// single block of 1024 threads per gradient: wavefront w takes the minibatch rows w, w + 16, ...
+// (lane l holds the float4 elements l, l + 64, ... of x^ in registers), the coefficients and the
+// loss are finished by M threads, and the rows (read again, from the cache) are combined by
+// 1024 / (64 U) thread groups that each take every G-th row of one float4 column and are added
+// in group order through LDS.  U = float4 elements of x^ per lane, R = rows of a wavefront
+// in flight (U (R + 1) float4 registers must fit the 128 a thread of a 1024-thread block has).
+constexpr int kSmallT = 1024;
+constexpr int kSmallWaves = kSmallT / 64;
+constexpr int kSmallMaxM = 256;
+constexpr int64_t kSmallMaxD = 2048;
+
+template <int U, int R>
+__global__ __launch_bounds__(kSmallT) void linear_small_kernel(const LinParams p) {
+    __shared__ float z_s[kSmallMaxM + 1];
+    __shared__ float coef_s[kSmallMaxM];
+    __shared__ float loss_s[kSmallMaxM];
+    __shared__ v4f part_s[kSmallT];        // [group][column]
+    const GradOp op = p.ops[blockIdx.x];
+    const float* __restrict__ A = static_cast<const float*>(op.features);
+    const float* __restrict__ tg = static_cast<const float*>(op.targets);
+    const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float target = 0.0f;
+    if (threadIdx.x < p.M) target = tg[idx[threadIdx.x]];      // requested now, used after the dots
+
+    v4f xh[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t v = lane + 64 * u;
+        xh[u] = v < p.n_vec ? zero_beyond(read_xhat(p, op, v), 4 * v, p.d) : v4f{0, 0, 0, 0};
+    }
+    const int n_rows = p.M + (p.model == ADPSGD_MODEL_LOGREG ? 1 : 0);   // row M: |x^|^2 for the regulariser
+    for (int m0 = wave; m0 < n_rows; m0 += R * kSmallWaves) {
+        float acc[R];
+        v4f a[R][U];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            acc[r] = 0.0f;
+            const int m = m0 + r * kSmallWaves;
+            if (m < p.M) {
+                const float* __restrict__ row = A + static_cast<int64_t>(idx[m]) * op.ld;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t v = lane + 64 * u;
+                    a[r][u] = v < p.n_vec ? zero_beyond(*reinterpret_cast<const v4f*>(row + 4 * v), 4 * v, p.d) : v4f{0, 0, 0, 0};
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) a[r][u] = xh[u];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc[r] += dot4(a[r][u], xh[u]);
+            acc[r] = wave_sum(acc[r]);
+            const int m = m0 + r * kSmallWaves;
+            if (lane == 0 && m < n_rows) z_s[m] = acc[r];
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < p.M) {
+        const int m = threadIdx.x;
+        const float z = z_s[m];
+        float c_m, l_m;
+        if (p.model == ADPSGD_MODEL_LSQ) {
+            const float r = z - target;              // a.x - b
+            l_m = 0.5f * r * r;
+            c_m = r;
+        } else {
+            const float s = -target * z;             // F = log(1 + e^s) + reg
+            l_m = (s > 0.0f ? s + log1pf(expf(-s)) : log1pf(expf(s))) + 0.5f * p.lambda * z_s[p.M];
+            c_m = -target / (1.0f + expf(-s));       // -y sigmoid(s)
+        }
+        coef_s[m] = c_m * p.gscale;
+        loss_s[m] = l_m;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && p.loss) {
+        float sl = 0.0f;
+        for (int m = 0; m < p.M; ++m) sl += loss_s[m];
+        p.loss[op.event] = sl * p.gscale;
+    }
+    constexpr int kCols = 64 * U, kGroups = kSmallT / kCols;
+    const int v = threadIdx.x % kCols, grp = threadIdx.x / kCols;
+    {
+        v4f acc = {0, 0, 0, 0};
+        if (v < p.n_vec) {
+#pragma unroll 8
+            for (int m = grp; m < p.M; m += kGroups) {
+                const v4f a = *reinterpret_cast<const v4f*>(A + static_cast<int64_t>(idx[m]) * op.ld + 4 * v);
+                acc += a * coef_s[m];
+            }
+        }
+        part_s[grp * kCols + v] = acc;
+    }
+    __syncthreads();
+    if (grp == 0 && v < p.n_vec) {
+        v4f acc = part_s[v];
+#pragma unroll
+        for (int g = 1; g < kGroups; ++g) acc += part_s[g * kCols + v];
+        if (p.model == ADPSGD_MODEL_LOGREG) acc += read_xhat(p, op, v) * (p.lambda * p.gscale * static_cast<float>(p.M));
+        acc = zero_beyond(acc, 4 * static_cast<int64_t>(v), p.d);
+        *reinterpret_cast<v4f*>(p.slots + static_cast<int64_t>(op.slot) * p.ld + 4 * v) = acc;
+    }
+}
+
 }  // namespace
 
 int64_t linear_grad_chunks(int64_t d) { return (d + kDotChunk - 1) / kDotChunk; }
@@ -238,6 +347,16 @@ hipError_t launch_linear_gradient(const LinearGradArgs& a, hipStream_t st, int* 
     p.partial = a.partial;
     p.coef = a.coef;
     p.loss = a.loss;
+    if (a.d <= kSmallMaxD && a.M <= kSmallMaxM && a.n_ops <= 0x7FFFFFFF) {
+        const int lanes_vec = static_cast<int>((p.n_vec + 63) / 64);      // float4 elements of x^ per lane
+        const dim3 grid(a.n_ops), block(kSmallT);
+        if (lanes_vec <= 1) hipLaunchKernelGGL((linear_small_kernel<1, 2>), grid, block, 0, st, p);
+        else if (lanes_vec <= 2) hipLaunchKernelGGL((linear_small_kernel<2, 2>), grid, block, 0, st, p);
+        else if (lanes_vec <= 4) hipLaunchKernelGGL((linear_small_kernel<4, 2>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((linear_small_kernel<8, 1>), grid, block, 0, st, p);
+        if (n_launches) *n_launches += 1;
+        return hipGetLastError();
+    }
     const int64_t out_blocks = (p.n_vec + kThreads - 1) / kThreads;
     if (p.n_chunks > 0x7FFFFFFF || out_blocks > 0x7FFFFFFF || a.n_ops > 65535) return hipErrorInvalidValue;
     const uint32_t row_groups = static_cast<uint32_t>((a.M + 1 + kRowsPerBlock - 1) / kRowsPerBlock);

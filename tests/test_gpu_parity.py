@@ -675,3 +675,21 @@ def test_sync_steps_validation(P):
         assert ei.value.code == -3
     assert not eng.get_models().any()               # nothing ran
     eng.close()
+
+
+# ------------------------------------------------------------------ short models: one launch per gradient set
+@pytest.mark.parametrize("model,n,d,rows,K,M,T", [("lsq", 6, 77, 20, 300, 3, 2), ("logreg", 8, 1030, 64, 300, 40, 3),
+                                                   ("logreg", 4, 2047, 50, 150, 200, 2), ("lsq", 8, 513, 32, 300, 17, 4),
+                                                   ("lsq", 5, 2048, 16, 200, 256, 1)])
+def test_short_models_take_the_single_block_gradient(P, model, n, d, rows, K, M, T):
+    """d <= 2048: the whole gradient of an operation is computed by one block (1, 2, 4 or 8 float4
+    elements of the model per lane, ragged tails, up to 256 samples); one launch per round."""
+    _say("short model %s d=%d M=%d" % (model, d, M))
+    gamma, lam = (0.3, 0.0) if model == "lsq" else (2.0, 1e-3)
+    eng, Xg, Xr, lg, lr, sched = _run_linear(P, model, n, d, rows, K, M, T, gamma, lam, "ring", 21,
+                                             feature_var=1.0 / d)
+    st = eng.get_stats()
+    assert 0 < st["grad_launches"] <= st["rounds"]          # one launch per round that has gradients
+    assert rel_err(Xg, Xr) <= TOL
+    assert np.allclose(lg, lr, rtol=2e-4, atol=1e-6)
+    eng.close()
