@@ -355,6 +355,9 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
         }
     }
 
+    // perceptron without momentum: dW1 stays in factored form until the update kernel
+    const bool factored = h->o.model == ADPSGD_MODEL_MLP && !h->o.V && mlp_can_factor(h->o.mlp_in, h->o.mlp_hidden, M);
+
     // ---- plan ----
     Plan plan;
     std::string perr;
@@ -400,11 +403,14 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
             u.k_hi = static_cast<uint32_t>(gk >> 32);
             u.gamma = s->gamma ? s->gamma[k] : h->o.gamma;
             u.slot = with_grad ? plan.slot[k] : 0;
-            u.flags = u.pad1 = 0;
+            u.flags = 0;
+            u.event = static_cast<int32_t>(k);
+            u.features = factored ? h->data[u.i].features : nullptr;
+            u.feat_ld = factored ? h->data[u.i].ld : 0;
             if (s->extra_ptr) {
                 for (int64_t q = s->extra_ptr[k]; q < s->extra_ptr[k + 1]; ++q) {
                     PairOp& x = uops[u_fill[plan.u_round[k]]++];
-                    x = PairOp{s->extra_a[q], s->extra_b[q], 0u, 0u, 0.0f, 0, 1, 0};
+                    x = PairOp{s->extra_a[q], s->extra_b[q], 0u, 0u, 0.0f, 0, 1, 0, nullptr, 0};
                 }
             }
             if (with_grad) {
@@ -468,7 +474,7 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
             if (h->o.model == ADPSGD_MODEL_MLP) {
                 MlpGradArgs a{h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, d_rops + g0, cnt, M,
                               d_batch, slots, gscale, loss,
-                              h->grad_scratch.p};
+                              h->grad_scratch.p, factored};
                 HIP_TRY(h, launch_mlp_gradient(a, h->stream, &launches));
             } else {
                 LinearGradArgs a{h->o.model, h->o.X, h->o.ldx, h->d, d_rops + g0, cnt, M, d_batch,
@@ -494,10 +500,16 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
             }
             bool has_solo = false;
             for (int64_t t = u_off[r]; t < u_off[r + 1] && !has_solo; ++t) has_solo = uops[t].i == uops[t].j;
-            FusedArgs a{h->o.X, h->o.ldx, h->d, d_uops + u_off[r], static_cast<int32_t>(nu), slots,
-                        h->o.model == ADPSGD_MODEL_MLP ? h->o.Xbf16 : nullptr, h->o.synth_std, h->o.synth_seed,
-                        !with_grad, h->streaming, has_solo, h->o.V, h->o.momentum, h->o.weight_decay};
-            HIP_TRY(h, launch_fused_gossip_apply(a, h->stream));
+            if (factored) {
+                MlpApplyArgs a{h->o.X, h->o.ldx, h->d, h->o.mlp_in, h->o.mlp_hidden, M, d_uops + u_off[r],
+                               static_cast<int32_t>(nu), slots, h->o.Xbf16, d_batch};
+                HIP_TRY(h, launch_mlp_apply_factored(a, h->stream));
+            } else {
+                FusedArgs a{h->o.X, h->o.ldx, h->d, d_uops + u_off[r], static_cast<int32_t>(nu), slots,
+                            h->o.model == ADPSGD_MODEL_MLP ? h->o.Xbf16 : nullptr, h->o.synth_std, h->o.synth_seed,
+                            !with_grad, h->streaming, has_solo, h->o.V, h->o.momentum, h->o.weight_decay};
+                HIP_TRY(h, launch_fused_gossip_apply(a, h->stream));
+            }
             ++h->stats.fused_launches;
             h->stats.max_round_pairs = std::max<int64_t>(h->stats.max_round_pairs, nu);
             if (profile) {
@@ -625,7 +637,7 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
             if (h->o.model == ADPSGD_MODEL_MLP) {
                 MlpGradArgs a{h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, d_rops + t * n + g0, cnt, M,
                               d_batch, slots, gscale, loss,
-                              h->grad_scratch.p};
+                              h->grad_scratch.p, false};
                 HIP_TRY(h, launch_mlp_gradient(a, h->stream, &launches));
             } else {
                 LinearGradArgs a{h->o.model, h->o.X, h->o.ldx, h->d, d_rops + t * n + g0, cnt, M, d_batch,

@@ -88,6 +88,16 @@ __device__ __forceinline__ float bf16_to_float(uint16_t h) {
     return __uint_as_float(static_cast<uint32_t>(h) << 16);
 }
 
+// The three fp32 operations of the update keep their separate roundings: the
+// product gamma*g and the subtraction must not be contracted into an FMA.
+__device__ __forceinline__ void average_then_apply(float a, float b, float g, float gamma, float& new_i, float& new_j) {
+#pragma clang fp contract(off)
+    const float avg = (a + b) * 0.5f;
+    const float step = g * gamma;
+    new_j = avg;
+    new_i = avg - step;
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);

@@ -20,7 +20,9 @@ struct alignas(32) PairOp {
     float gamma;
     int32_t slot;     // pending-gradient slot holding g_k (data models)
     int32_t flags;    // bit 0: average only (an extra pair of a general W_k): no gradient, no step
-    int32_t pad1;
+    int32_t event;    // index into the call's batch_idx array (perceptron, factored gradient)
+    const void* features;   // worker i's inputs (perceptron, factored gradient), else nullptr
+    int64_t feat_ld;
 };
 
 // One stale read / gradient evaluation as the gradient kernels see it.
@@ -116,8 +118,26 @@ struct MlpGradArgs {
     float gscale;
     float* loss;
     void* scratch;          // device scratch, mlp_scratch_bytes(n_ops, ...)
+    bool factored;          // leave dW1 as its factors: dH goes to the start of the slot, no dW1 launch
 };
 size_t mlp_scratch_bytes(int32_t n_ops, int32_t M, int32_t in, int32_t hid, int32_t out);
+bool mlp_can_factor(int32_t in, int32_t hid, int32_t M);
+
+// The perceptron's model update with the first-layer gradient still in factored form
+// (dW1 = Xb^T dH, rank <= M): the product is formed tile by tile on the matrix cores inside
+// the update kernel instead of being written to and read back from the pending slot.
+struct MlpApplyArgs {
+    float* X;
+    int64_t ld;
+    int64_t d;
+    int32_t in, hid, M;
+    const PairOp* ops;      // device
+    int32_t n_ops;
+    const float* slots;
+    uint16_t* Xbf16;
+    const int32_t* batch_idx;   // device, K x M
+};
+hipError_t launch_mlp_apply_factored(const MlpApplyArgs& a, hipStream_t st);
 hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_launches);
 
 struct SyncArgs {

@@ -45,16 +45,6 @@ __device__ __forceinline__ void store1(float* p, float v) {
     else *p = v;
 }
 
-// The three fp32 operations of the update keep their separate roundings: the
-// product gamma*g and the subtraction must not be contracted into an FMA.
-__device__ __forceinline__ void average_then_apply(float a, float b, float g, float gamma, float& new_i, float& new_j) {
-#pragma clang fp contract(off)
-    const float avg = (a + b) * 0.5f;
-    const float step = g * gamma;
-    new_j = avg;
-    new_i = avg - step;
-}
-
 // The event with the experiments' optimizer (Sec. 5.2): per-worker momentum buffer v, weight decay on
 // the averaged model;  u = g + wd * avg;  v <- mu * v + u;  x^i <- avg - gamma * v.  One rounding per
 // operation, in this order.
@@ -121,19 +111,10 @@ __global__ __launch_bounds__(kThreads) void fused_gossip_apply_kernel(const Fuse
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
         const int64_t eq = tile + (lane >> 4) * kThreads + 64 * wave + 4 * (lane & 15);
         const int64_t q = eq >> 2;
-#ifdef ADPSGD_EXPERIMENT_NO_RNG
-        const v4f z = v4f{1.0f, 1.0f, 1.0f, 1.0f} * p.synth_std;
-#else
         const v4f z = synth_normals4(static_cast<uint32_t>(q), static_cast<uint32_t>(q >> 32), op.k_lo, op.k_hi,
                                      p.key0, p.key1) * p.synth_std;
-#endif
         *reinterpret_cast<v4f*>(&zs[wave * 256 + 4 * lane]) = z;
-#ifdef ADPSGD_EXPERIMENT_WAVE_SYNC
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-#else
         __syncthreads();
-#endif
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) g[u] = zs[wave * 256 + 64 * u + lane];
     }

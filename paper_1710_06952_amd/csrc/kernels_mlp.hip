@@ -41,6 +41,8 @@ struct MlpParams {
     float* loss;
     uint16_t* Hb;    // [op][kMaxM][hid]  relu output, bf16
     uint16_t* dHb;   // [op][kMaxM][hid]  error at the hidden pre-activation, bf16, rows >= M zero
+    int factored;    // dH goes to the start of the operation's pending slot instead (and stays there
+                     // until the update kernel multiplies it with the inputs)
     float* logit_part;  // [op][hid / 32][kMaxM][kMaxOut]  second-layer products of one forward tile
 };
 
@@ -223,6 +225,8 @@ __global__ __launch_bounds__(kBwdT) void mlp_backward_small_kernel(const MlpPara
     __shared__ float red[kBwdGroups / 2][kMaxOut + 1][64];
     const GradOp op = p.ops[blockIdx.y];
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
+    uint16_t* __restrict__ dH = p.factored ? reinterpret_cast<uint16_t*>(p.slots + static_cast<int64_t>(op.slot) * p.ld)
+                                           : p.dHb + static_cast<int64_t>(blockIdx.y) * kMaxM * p.hid;
     const int hl = threadIdx.x & 63, mg = threadIdx.x >> 6;
     const int h = blockIdx.x * 64 + hl;
     const int sm = threadIdx.x >> 4, so = threadIdx.x & 15;       // step a: sample and logit
@@ -291,7 +295,6 @@ __global__ __launch_bounds__(kBwdT) void mlp_backward_small_kernel(const MlpPara
 #pragma unroll
     for (int r = 0; r < kBwdRows; ++r) {
         const int m = kBwdRows * mg + r;
-        const int64_t at = (static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h;
         float dl[kMaxOut];
 #pragma unroll
         for (int q = 0; q < kMaxOut / 4; ++q) {
@@ -307,7 +310,7 @@ __global__ __launch_bounds__(kBwdT) void mlp_backward_small_kernel(const MlpPara
         }
         const uint16_t dh = (m < p.M && hv > 0.0f) ? bf16_rne(back * p.gscale) : static_cast<uint16_t>(0);
         sum_dh += bf16_to_float(dh);
-        p.dHb[at] = dh;                                  // rows m >= M are the zero padding of the dW1 product
+        dH[static_cast<int64_t>(m) * p.hid + h] = dh;    // rows m >= M are the zero padding of the dW1 product
     }
 
     // ---- c. fixed pairwise tree over the 16 row groups: (g, g + 8), then (g, g + 4), (g, g + 2), (g, g + 1)
@@ -344,25 +347,24 @@ __global__ __launch_bounds__(kBwdT) void mlp_backward_small_kernel(const MlpPara
     }
 }
 
-// ---- 3. dW1 = Xb^T dH: grid = (hid / 64, ceil(in / 64), n_ops) -------------------------
-__global__ __launch_bounds__(kT) void mlp_dw1_kernel(const MlpParams p) {
-    __shared__ __attribute__((aligned(16))) uint16_t At[64][72];   // inputs transposed:  [i][m], 64 m + pad
-    __shared__ __attribute__((aligned(16))) uint16_t Bt[64][72];   // hidden error transposed: [h][m]
-    const GradOp op = p.ops[blockIdx.z];
-    const uint16_t* __restrict__ feat = static_cast<const uint16_t*>(op.features);
-    const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
-    const int h0 = blockIdx.x * kTileH, i0 = blockIdx.y * 64;
+// ---- 3. dW1 = Xb^T dH ------------------------------------------------------------------
+// One 64 (inputs) x 64 (hidden) tile of the product: the minibatch rows of the inputs and of dH
+// ([kMaxM][hid] bf16, rows >= M zero) are transposed through LDS, then wavefront w multiplies the
+// four 16-row input tiles with hidden columns [16 w, 16 w + 16).  Lane l ends up with
+// acc[it][v] = dW1[i0 + 16 it + 4 (l / 16) + v][h0 + 16 w + l % 16].
+__device__ __forceinline__ void dw1_tile(const uint16_t* __restrict__ feat, int64_t feat_ld, const int32_t* __restrict__ idx,
+                                         int M, int in, const uint16_t* __restrict__ dH, int hid, int h0, int i0,
+                                         uint16_t (*At)[72], uint16_t (*Bt)[72], v4f acc[4]) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int li = lane & 15, kb = 8 * (lane >> 4);
-
     {   // stage: thread handles one minibatch row m and 16 consecutive columns
         const int m = threadIdx.x >> 2, seg = (threadIdx.x & 3) * 16;
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             const int c = seg + 8 * half;
             v8h xv = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (m < p.M && i0 + c < p.in) xv = *reinterpret_cast<const v8h*>(feat + static_cast<int64_t>(idx[m]) * op.ld + i0 + c);
-            const v8h dv = *reinterpret_cast<const v8h*>(p.dHb + (static_cast<int64_t>(blockIdx.z) * kMaxM + m) * p.hid + h0 + c);
+            if (m < M && i0 + c < in) xv = *reinterpret_cast<const v8h*>(feat + static_cast<int64_t>(idx[m]) * feat_ld + i0 + c);
+            const v8h dv = *reinterpret_cast<const v8h*>(dH + static_cast<int64_t>(m) * hid + h0 + c);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 At[c + e][m] = xv[e];
@@ -371,7 +373,6 @@ __global__ __launch_bounds__(kT) void mlp_dw1_kernel(const MlpParams p) {
         }
     }
     __syncthreads();
-    v4f acc[4];
 #pragma unroll
     for (int it = 0; it < 4; ++it) acc[it] = v4f{0, 0, 0, 0};
 #pragma unroll
@@ -383,8 +384,20 @@ __global__ __launch_bounds__(kT) void mlp_dw1_kernel(const MlpParams p) {
             acc[it] = mfma_bf16(afrag, bfrag, acc[it]);
         }
     }
+}
+
+// dW1 written out as a dense gradient: grid = (hid / 64, ceil(in / 64), n_ops)
+__global__ __launch_bounds__(kT) void mlp_dw1_kernel(const MlpParams p) {
+    __shared__ __attribute__((aligned(16))) uint16_t At[64][72];   // inputs transposed:  [i][m], 64 m + pad
+    __shared__ __attribute__((aligned(16))) uint16_t Bt[64][72];   // hidden error transposed: [h][m]
+    const GradOp op = p.ops[blockIdx.z];
+    const int h0 = blockIdx.x * kTileH, i0 = blockIdx.y * 64;
+    v4f acc[4];
+    dw1_tile(static_cast<const uint16_t*>(op.features), op.ld, p.batch_idx + static_cast<int64_t>(op.event) * p.M, p.M, p.in,
+             p.dHb + static_cast<int64_t>(blockIdx.z) * kMaxM * p.hid, p.hid, h0, i0, At, Bt, acc);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     float* __restrict__ g = p.slots + static_cast<int64_t>(op.slot) * p.ld;
-    const int h = h0 + 16 * wave + li;
+    const int h = h0 + 16 * wave + (lane & 15);
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
 #pragma unroll
@@ -392,6 +405,111 @@ __global__ __launch_bounds__(kT) void mlp_dw1_kernel(const MlpParams p) {
             const int i = i0 + 16 * it + 4 * (lane >> 4) + v;
             if (i < p.in) g[static_cast<int64_t>(i) * p.hid + h] = acc[it][v];
         }
+    }
+}
+
+// ---- 4. model update with dW1 in factored form ----------------------------------------------
+// The event's update  avg = (x^i + x^j) / 2;  x^j <- avg;  x^i <- avg - gamma g  for the
+// perceptron, with the first-layer part of g formed here from its factors (the same tile product
+// as above, so the values are those of the dense gradient) and only the small remainder
+// (b1, W2, b2) read from the pending slot.  The bf16 shadow of both rows is rewritten.
+//   grid = (hid / 64, ceil(in / 64) + tail rows, events of the round)
+//   blockIdx.y <  ceil(in / 64): one 64 x 64 tile of W1.  The tile of g goes through LDS so that
+//                 each thread updates float4 pieces of contiguous rows (16 lanes per 256-byte row);
+//   blockIdx.y >= ceil(in / 64): 1024 consecutive floats of the remainder, elementwise.
+struct MlpApplyParams {
+    float* X;
+    int64_t ld;
+    int64_t d;
+    int in, hid, M;
+    const PairOp* ops;
+    const float* slots;
+    uint16_t* Xbf16;
+    const int32_t* batch_idx;
+};
+
+__device__ __forceinline__ void apply4(const MlpApplyParams& p, const PairOp& op, int64_t e, v4f a, v4f b, v4f g,
+                                       bool average_only, bool pair, int valid) {
+    float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w}, gv[4] = {g.x, g.y, g.z, g.w};
+    float ni[4], nj[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) average_then_apply(av[c], bv[c], average_only ? 0.0f : gv[c], average_only ? 0.0f : op.gamma, ni[c], nj[c]);
+    float* __restrict__ xi = p.X + static_cast<int64_t>(op.i) * p.ld + e;
+    float* __restrict__ xj = p.X + static_cast<int64_t>(op.j) * p.ld + e;
+    uint16_t* __restrict__ si = p.Xbf16 + static_cast<int64_t>(op.i) * p.ld + e;
+    uint16_t* __restrict__ sj = p.Xbf16 + static_cast<int64_t>(op.j) * p.ld + e;
+    if (valid == 4) {
+        *reinterpret_cast<v4f*>(xi) = v4f{ni[0], ni[1], ni[2], ni[3]};
+        *reinterpret_cast<v4h*>(si) = v4h{bf16_rne(ni[0]), bf16_rne(ni[1]), bf16_rne(ni[2]), bf16_rne(ni[3])};
+        if (pair) {
+            *reinterpret_cast<v4f*>(xj) = v4f{nj[0], nj[1], nj[2], nj[3]};
+            *reinterpret_cast<v4h*>(sj) = v4h{bf16_rne(nj[0]), bf16_rne(nj[1]), bf16_rne(nj[2]), bf16_rne(nj[3])};
+        }
+    } else {                      // ragged end of the parameter vector: entries at and beyond d stay untouched
+        for (int c = 0; c < valid; ++c) {
+            xi[c] = ni[c];
+            si[c] = bf16_rne(ni[c]);
+            if (pair) {
+                xj[c] = nj[c];
+                sj[c] = bf16_rne(nj[c]);
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(kT) void mlp_apply_factored_kernel(const MlpApplyParams p) {
+    __shared__ __attribute__((aligned(16))) uint16_t At[64][72];
+    __shared__ __attribute__((aligned(16))) uint16_t Bt[64][72];
+    __shared__ __attribute__((aligned(16))) float Gs[64][68];       // the tile of g, [input][hidden]
+    const PairOp op = p.ops[blockIdx.z];
+    const bool average_only = (op.flags & 1) != 0;    // extra pair of a general W_k: no gradient, no step
+    const bool pair = op.i != op.j;
+    const float* __restrict__ xi = p.X + static_cast<int64_t>(op.i) * p.ld;
+    const float* __restrict__ xj = p.X + static_cast<int64_t>(op.j) * p.ld;
+    const float* __restrict__ slot = p.slots + static_cast<int64_t>(op.slot) * p.ld;
+    const int in_tiles = (p.in + 63) / 64;
+    if (static_cast<int>(blockIdx.y) >= in_tiles) {
+        // remainder of the parameter vector (b1, W2, b2): dense gradient from the slot
+        const int64_t tb = static_cast<int64_t>(blockIdx.y - in_tiles) * gridDim.x + blockIdx.x;
+        const int64_t e = static_cast<int64_t>(p.in) * p.hid + 4 * (tb * kT + threadIdx.x);
+        if (e >= p.d) return;
+        const int valid = p.d - e >= 4 ? 4 : static_cast<int>(p.d - e);
+        const v4f a = *reinterpret_cast<const v4f*>(xi + e), b = *reinterpret_cast<const v4f*>(xj + e);   // rows are padded
+        v4f g = {0, 0, 0, 0};
+        if (!average_only) g = *reinterpret_cast<const v4f*>(slot + e);
+        apply4(p, op, e, a, b, g, average_only, pair, valid);
+        return;
+    }
+    const int h0 = blockIdx.x * kTileH, i0 = blockIdx.y * 64;
+    const int rr = threadIdx.x >> 4, hq = (threadIdx.x & 15) * 4;      // this thread's rows 16 r + rr, columns hq .. hq + 3
+    v4f a[4], b[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {        // the model rows are requested before the product is formed
+        const int i = i0 + 16 * r + rr;
+        if (i < p.in) {
+            const int64_t e = static_cast<int64_t>(i) * p.hid + h0 + hq;
+            a[r] = *reinterpret_cast<const v4f*>(xi + e);
+            b[r] = *reinterpret_cast<const v4f*>(xj + e);
+        }
+    }
+    if (!average_only) {                  // uniform over the block
+        v4f acc[4];
+        dw1_tile(static_cast<const uint16_t*>(op.features), op.feat_ld, p.batch_idx + static_cast<int64_t>(op.event) * p.M, p.M,
+                 p.in, reinterpret_cast<const uint16_t*>(slot), p.hid, h0, i0, At, Bt, acc);
+        const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+        for (int it = 0; it < 4; ++it)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Gs[16 * it + 4 * (lane >> 4) + v][16 * wave + (lane & 15)] = acc[it][v];
+        __syncthreads();
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int i = i0 + 16 * r + rr;
+        if (i >= p.in) continue;
+        v4f g = {0, 0, 0, 0};
+        if (!average_only) g = *reinterpret_cast<const v4f*>(&Gs[16 * r + rr][hq]);
+        apply4(p, op, static_cast<int64_t>(i) * p.hid + h0 + hq, a[r], b[r], g, average_only, pair, 4);
     }
 }
 
@@ -405,6 +523,35 @@ size_t mlp_scratch_bytes(int32_t n_ops, int32_t M, int32_t in, int32_t hid, int3
     const size_t act = align256(static_cast<size_t>(n_ops) * kMaxM * hid * sizeof(uint16_t));
     const size_t lp = align256(static_cast<size_t>(n_ops) * (hid / kFwdTileH) * kMaxM * kMaxOut * 4);
     return 2 * act + lp;
+}
+
+bool mlp_can_factor(int32_t in, int32_t hid, int32_t M) {
+    // dH (kMaxM x hid bf16) must fit the first-layer part of a pending slot (in x hid fp32)
+    return M >= 1 && M <= kMaxM && in >= 32 && (in & 7) == 0 && hid >= kTileH && hid % kTileH == 0;
+}
+
+hipError_t launch_mlp_apply_factored(const MlpApplyArgs& a, hipStream_t st) {
+    if (a.n_ops <= 0) return hipSuccess;
+    if (!mlp_can_factor(a.in, a.hid, a.M) || a.n_ops > 65535 || !a.Xbf16) return hipErrorInvalidValue;
+    MlpApplyParams p;
+    p.X = a.X;
+    p.ld = a.ld;
+    p.d = a.d;
+    p.in = a.in;
+    p.hid = a.hid;
+    p.M = a.M;
+    p.ops = a.ops;
+    p.slots = a.slots;
+    p.Xbf16 = a.Xbf16;
+    p.batch_idx = a.batch_idx;
+    const int64_t tail = a.d - static_cast<int64_t>(a.in) * a.hid;            // floats after W1
+    const uint32_t bx = static_cast<uint32_t>(a.hid / kTileH);
+    const int64_t per_row = static_cast<int64_t>(bx) * kT * 4;                  // floats one grid row of blocks covers
+    const int64_t tail_rows = tail > 0 ? (tail + per_row - 1) / per_row : 0;
+    const int64_t by = (a.in + 63) / 64 + tail_rows;
+    if (by > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(mlp_apply_factored_kernel, dim3(bx, static_cast<uint32_t>(by), a.n_ops), dim3(kT), 0, st, p);
+    return hipGetLastError();
 }
 
 hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_launches) {
@@ -422,6 +569,8 @@ hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_laun
     p.slots = a.slots;
     p.gscale = a.gscale;
     p.loss = a.loss;
+    p.factored = a.factored ? 1 : 0;
+    if (a.factored && !mlp_can_factor(a.in, a.hid, a.M)) return hipErrorInvalidValue;
     char* s = static_cast<char*>(a.scratch);
     const size_t act = align256(static_cast<size_t>(a.n_ops) * kMaxM * a.hid * sizeof(uint16_t));
     p.Hb = reinterpret_cast<uint16_t*>(s);
@@ -433,6 +582,10 @@ hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_laun
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(mlp_backward_small_kernel, dim3(a.hid / 64, a.n_ops), dim3(kBwdT), 0, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (a.factored) {
+        if (n_launches) *n_launches += 2;
+        return hipSuccess;
+    }
     hipLaunchKernelGGL(mlp_dw1_kernel, dim3(hb, (a.in + 63) / 64, a.n_ops), dim3(kT), 0, st, p);
     if (n_launches) *n_launches += 3;
     return hipGetLastError();
