@@ -63,7 +63,12 @@ enum {
 };
 
 enum {
-    ADPSGD_FLAG_PROFILE = 1  /* time every kernel launch with HIP events (see adpsgd_get_stats) */
+    ADPSGD_FLAG_PROFILE = 1, /* time every kernel launch with HIP events (see adpsgd_get_stats) */
+    ADPSGD_FLAG_DENSE_GRADIENT = 2  /* MLP: always write the first-layer gradient out as a dense matrix.
+                                       By default (no momentum) it stays in factored form, dH and the
+                                       minibatch inputs, until the update kernel multiplies the two; the
+                                       values are the same, the dense form costs one more launch and a
+                                       write and read-back of in x hidden floats per event */
 };
 
 /* Undirected communication graph (V, E) of Sec. 3.1 as CSR adjacency lists.

@@ -5,5 +5,5 @@ only what a caller needs around it: device buffers and a stream from PyTorch.
 """
 from .binding import (AdpsgdError, Handle, adpsgd_make_schedule, adpsgd_plan_rounds,  # noqa: F401
                       adpsgd_synth_gradient, adpsgd_metropolis_weights, lib, EXPORTS, LIB_PATH, MODEL_LSQ, MODEL_LOGREG,
-                      MODEL_SYNTH, MODEL_MLP, FLAG_PROFILE)
+                      MODEL_SYNTH, MODEL_MLP, FLAG_PROFILE, FLAG_DENSE_GRADIENT)
 from .engine import Engine  # noqa: F401

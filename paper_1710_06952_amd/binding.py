@@ -15,7 +15,7 @@ LIB_PATH = _HERE / "libadpsgd.so"
 
 OK, ERR_ARG, ERR_GRAPH, ERR_SCHEDULE, ERR_STATE, ERR_HIP = 0, -1, -2, -3, -4, -5
 MODEL_LSQ, MODEL_LOGREG, MODEL_SYNTH, MODEL_MLP = 0, 1, 2, 3
-FLAG_PROFILE = 1
+FLAG_PROFILE, FLAG_DENSE_GRADIENT = 1, 2
 
 EXPORTS = [
     "adpsgd_create", "adpsgd_destroy", "adpsgd_last_error", "adpsgd_load_data", "adpsgd_set_models",

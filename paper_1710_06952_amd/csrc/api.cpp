@@ -356,7 +356,8 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
     }
 
     // perceptron without momentum: dW1 stays in factored form until the update kernel
-    const bool factored = h->o.model == ADPSGD_MODEL_MLP && !h->o.V && mlp_can_factor(h->o.mlp_in, h->o.mlp_hidden, M);
+    const bool factored = h->o.model == ADPSGD_MODEL_MLP && !h->o.V && !(h->o.flags & ADPSGD_FLAG_DENSE_GRADIENT) &&
+                          mlp_can_factor(h->o.mlp_in, h->o.mlp_hidden, M);
 
     // ---- plan ----
     Plan plan;

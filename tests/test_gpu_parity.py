@@ -693,3 +693,28 @@ def test_short_models_take_the_single_block_gradient(P, model, n, d, rows, K, M,
     assert rel_err(Xg, Xr) <= TOL
     assert np.allclose(lg, lr, rtol=2e-4, atol=1e-6)
     eng.close()
+
+
+def test_mlp_factored_and_dense_first_layer_gradient_give_the_same_bits(P):
+    """The update kernel that forms dW1 from its factors must produce exactly what the dense path does,
+    also with extra averaging pairs and workers without a partner step mixed in."""
+    from workloads import mixture_data, mlp_init, random_extra_pairs
+    n, dims, rows, K, M, T = 8, (40, 128, 7), 48, 300, 24, 3
+    _say("mlp factored vs dense")
+    g = random_regular4_graph(n, 4)
+    d = dims[0] * dims[1] + dims[1] + dims[1] * dims[2] + dims[2]
+    feats, labels, _ = mixture_data(n, rows, din=dims[0], classes=dims[2], seed=9)
+    sched = oracle.make_schedule(g, K, seed=9, T_max=T, M=M, rows=[rows] * n)
+    sched["extra_pairs"] = random_extra_pairs(g, sched["worker"], sched["neighbour"], max_extra=2, seed=10)
+    x0 = mlp_init(*dims, seed=9)
+    out = []
+    for dense in (False, True):
+        eng = P.Engine(g, d, "mlp", M=M, gamma=0.05, T_max=T, mlp=dims, dense_gradient=dense)
+        eng.load_data(feats, labels)
+        eng.set_models(x0)
+        eng.run_events(sched, want_loss=True)
+        out.append((eng.get_models(), eng.get_bf16_models(), eng.get_loss(), eng.get_stats()["grad_launches"]))
+        eng.close()
+    assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
+    assert np.array_equal(out[0][2], out[1][2])
+    assert out[0][3] * 3 == out[1][3] * 2          # two launches per gradient set instead of three
