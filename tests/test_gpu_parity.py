@@ -718,3 +718,70 @@ def test_mlp_factored_and_dense_first_layer_gradient_give_the_same_bits(P):
     assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
     assert np.array_equal(out[0][2], out[1][2])
     assert out[0][3] * 3 == out[1][3] * 2          # two launches per gradient set instead of three
+
+
+# ------------------------------------------------------------------ seeded sweep over small random set-ups
+def _random_case(rng):
+    from workloads import hop_ring_graph, random_extra_pairs
+    model = ["synth", "lsq", "logreg"][rng.integers(3)]
+    n = int(rng.integers(1, 13))
+    d = int(rng.choice([1, 3, 64, 250, 1023, 1025, 2048, 2051, 4100, 9001]))
+    kind = "ring" if n < 6 else ["ring", "reg4", "hop"][rng.integers(3)]
+    g = ring_graph(n) if kind == "ring" else (random_regular4_graph(n, int(rng.integers(100))) if kind == "reg4" else hop_ring_graph(n))
+    T = int(rng.integers(0, 7))
+    K = int(rng.integers(1, 250))
+    M = int(rng.integers(1, 20)) if model != "synth" else 0
+    rows = int(rng.integers(M + 1, 40)) if M else 0
+    momentum = float(rng.choice([0.0, 0.0, 0.9]))
+    wd = float(rng.choice([0.0, 1e-3])) if momentum else 0.0
+    comp = bool(model != "synth" and momentum == 0.0 and rng.integers(2))
+    sched = oracle.make_schedule(g, K, seed=int(rng.integers(1 << 30)), T_max=T, M=M, rows=[rows] * n if M else None)
+    extra = None
+    if n >= 6 and rng.integers(2):
+        extra = random_extra_pairs(g, sched["worker"], sched["neighbour"], max_extra=2, seed=int(rng.integers(1000)))
+    gam = (0.05 * (1 + rng.integers(0, 4, size=K))).astype(np.float32) if rng.integers(2) else None
+    return dict(model=model, n=n, d=d, g=g, T=T, K=K, M=M, rows=rows, momentum=momentum, wd=wd, comp=comp,
+                sched=sched, extra=extra, gam=gam, seed=int(rng.integers(1 << 30)))
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_seeded_sweep_of_small_set_ups(P, block):
+    """Random combinations of model, graph, size (ragged and tiny d, both gradient paths), staleness, extra
+    averaging pairs, per-event step sizes, momentum and the wait-free variant, each against the oracle."""
+    rng = np.random.default_rng(1000 + block)
+    for case in range(10):
+        c = _random_case(rng)
+        _say("sweep %d/%d: %s n=%d d=%d K=%d M=%d T=%d mom=%g comp=%d extra=%d" % (
+            block, case, c["model"], c["n"], c["d"], c["K"], c["M"], c["T"], c["momentum"], c["comp"], c["extra"] is not None))
+        n, d, M = c["n"], c["d"], c["M"]
+        std = float(np.float32(0.1))
+        eng = P.Engine(c["g"], d, c["model"], M=M, gamma=0.1, lam=1e-3 if c["model"] == "logreg" else 0.0, T_max=c["T"],
+                       synth_std=std, synth_seed=c["seed"], momentum=c["momentum"], weight_decay=c["wd"],
+                       local_compensation=c["comp"])
+        x0 = np.random.default_rng(c["seed"]).standard_normal((n, d)).astype(np.float32)
+        kw = {}
+        if c["model"] != "synth":
+            if c["model"] == "lsq":          # unit-norm rows, so that every step size of the sweep is stable
+                feats, targs, _ = lsq_data(n, c["rows"], d, seed=c["seed"] % 1000, feature_var=1.0 / d)
+            else:
+                feats, targs, _ = logreg_data(n, c["rows"], d, seed=c["seed"] % 1000)
+            eng.load_data(feats, targs)
+            kw = dict(M=M, gscale=1.0 / M, lam=1e-3 if c["model"] == "logreg" else 0.0, features=feats, targets=targs)
+        eng.set_models(x0, broadcast=False)
+        gs = dict(c["sched"])
+        if c["extra"] is not None:
+            gs["extra_pairs"] = c["extra"]
+        if c["gam"] is not None:
+            gs["gamma"] = c["gam"]
+        eng.run_events(gs)
+        Xr = x0.copy()
+        V = np.zeros_like(Xr) if (c["momentum"] or c["wd"]) else None
+        omodel = {"synth": oracle.MODEL_SYNTH, "lsq": oracle.MODEL_LSQ, "logreg": oracle.MODEL_LOGREG}[c["model"]]
+        oracle.run_events(Xr, c["sched"], omodel, 0.1, gamma_k=c["gam"], synth_std=std, synth_seed=c["seed"],
+                          momentum=c["momentum"], weight_decay=c["wd"], V=V, extra_pairs=c["extra"],
+                          local_compensation=c["comp"], **kw)
+        assert np.isfinite(Xr).all()
+        assert rel_err(eng.get_models(), Xr) <= TOL, c
+        if V is not None:
+            assert np.abs(eng.get_momentum() - V).max() <= TOL * max(np.abs(V).max(), 1e-30), c
+        eng.close()
