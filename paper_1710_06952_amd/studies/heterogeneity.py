@@ -1,6 +1,7 @@
 """Simulated wall-clock study of a slow worker, shaped like the paper's robustness experiment
 (Sec. 5.4, "Robustness against slow computation": one of 16 workers slowed down 2x-100x, table of
-time per epoch and speed-up for AD-PSGD against the synchronous algorithms).
+time per epoch and speed-up for AD-PSGD against the synchronous algorithms; with --slow link the
+companion experiment, "Robustness against slow communication", where one network link is slowed).
 
 Nothing here needs the paper's data: the objective is a synthetic consistent least-squares problem
 whose samples every worker can draw (the shared-data strategy of the remark in Sec. 3.1, as in the
@@ -58,14 +59,25 @@ def draw_durations(rng, mean, exponential):
     return rng.exponential(mean) if exponential else np.asarray(mean, dtype=np.float64).copy()
 
 
-def clock_schedule(graph, K, mean_time, M, rows, seed, exponential=True):
+def clock_schedule(graph, K, mean_time, M, rows, seed, exponential=True, comm_time=0.0, slow_link=None, link_slowdown=1.0):
     """Event order of free-running workers.  Returns the schedule arrays and the simulated time of
-    every event.  mean_time[i] = mean duration of one gradient on worker i."""
+    every event.  mean_time[i] = mean duration of one gradient on worker i; an event also takes
+    comm_time for the exchange with its neighbour, times link_slowdown on the link slow_link = (a, b)."""
     rowptr, col = graph
     n = len(rowptr) - 1
     rng = np.random.default_rng([seed, 2])
     mean_time = np.asarray(mean_time, dtype=np.float64)
-    t_next = draw_durations(rng, mean_time, exponential)
+
+    def pick_neighbour(i):
+        deg = rowptr[i + 1] - rowptr[i]
+        return int(col[rowptr[i] + rng.integers(deg)]) if deg > 0 else i
+
+    def exchange(i, j):
+        slow = slow_link is not None and {i, j} == set(slow_link)
+        return comm_time * (link_slowdown if slow else 1.0)
+
+    nxt = np.array([pick_neighbour(i) for i in range(n)])            # partner of each worker's next event
+    t_next = draw_durations(rng, mean_time, exponential) + np.array([exchange(i, nxt[i]) for i in range(n)])
     last_read = np.zeros(n, dtype=np.int64)        # logical time at which the worker last read its model
     worker = np.zeros(K, np.int32)
     nbr = np.zeros(K, np.int32)
@@ -74,21 +86,22 @@ def clock_schedule(graph, K, mean_time, M, rows, seed, exponential=True):
     for k in range(K):
         i = int(np.argmin(t_next))
         worker[k] = i
+        nbr[k] = nxt[i]
         when[k] = t_next[i]
         tau[k] = k - last_read[i]
         last_read[i] = k + 1                        # it reads again right after its update
-        deg = rowptr[i + 1] - rowptr[i]
-        nbr[k] = col[rowptr[i] + rng.integers(deg)] if deg > 0 else i
-        t_next[i] += rng.exponential(mean_time[i]) if exponential else mean_time[i]
+        nxt[i] = pick_neighbour(i)
+        t_next[i] += (rng.exponential(mean_time[i]) if exponential else mean_time[i]) + exchange(i, nxt[i])
     batch = rng.integers(0, rows, size=(K, M)).astype(np.int32)
     return {"worker": worker, "neighbour": nbr, "tau": tau, "batch_idx": batch}, when
 
 
-def sync_clock(S, mean_time, seed, exponential=True):
-    """Simulated end time of every synchronous iteration: each lasts as long as its slowest worker."""
+def sync_clock(S, mean_time, seed, exponential=True, comm_time=0.0, link_slowdown=1.0):
+    """Simulated end time of every synchronous iteration: each lasts as long as its slowest worker
+    plus its slowest exchange (every link is used in every iteration)."""
     rng = np.random.default_rng([seed, 3])
     mean_time = np.asarray(mean_time, dtype=np.float64)
-    dur = np.array([draw_durations(rng, mean_time, exponential).max() for _ in range(S)])
+    dur = np.array([draw_durations(rng, mean_time, exponential).max() for _ in range(S)]) + comm_time * max(link_slowdown, 1.0)
     return np.cumsum(dur)
 
 
@@ -107,7 +120,10 @@ def first_time_below(curve, when, target):
 
 
 def run_study(n=16, d=4096, rows=1024, M=8, epochs=40, slowdowns=(1, 2, 10, 100), seed=0, exponential=True,
-              target=0.2, device="cuda:0"):
+              target=0.2, device="cuda:0", slow="worker", comm_time=0.25):
+    """slow = "worker": one worker's gradients take `slowdown` times longer (no exchange cost);
+    slow = "link": gradients take unit time everywhere, an exchange takes comm_time, and the link between
+    workers n/2 and n/2 + 1 is `slowdown` times slower."""
     from .. import Engine
     graph = ring(n)
     feats, targs = make_problem(n, d, rows, seed)
@@ -117,11 +133,16 @@ def run_study(n=16, d=4096, rows=1024, M=8, epochs=40, slowdowns=(1, 2, 10, 100)
     S = K // n
     f0 = objective(np.zeros(d), feats, targs)
     rows_out = []
-    for slow in slowdowns:
+    for slowdown in slowdowns:
         mean_time = np.ones(n)
-        mean_time[n // 2] = float(slow)              # the slowed worker
+        link_kw = {}
+        if slow == "worker":
+            mean_time[n // 2] = float(slowdown)      # the slowed worker
+        else:
+            link_kw = dict(comm_time=comm_time, link_slowdown=float(slowdown))
         # ---- AD-PSGD
-        sched, when = clock_schedule(graph, K, mean_time, M, rows, seed, exponential)
+        sched, when = clock_schedule(graph, K, mean_time, M, rows, seed, exponential,
+                                     slow_link=(n // 2, (n // 2 + 1) % n) if link_kw else None, **link_kw)
         T_max = int(sched["tau"].max())
         eng = Engine(graph, d, "lsq", M=M, gamma=gamma, T_max=T_max, n_slots=T_max + 1 + 2 * n, device=device)
         eng.load_data(feats, targs)
@@ -131,7 +152,7 @@ def run_study(n=16, d=4096, rows=1024, M=8, epochs=40, slowdowns=(1, 2, 10, 100)
         f_a = objective(eng.get_mean_model(), feats, targs)
         eng.close()
         # ---- synchronous iterations (all workers step together, mixing with both ring neighbours)
-        when_s = sync_clock(S, mean_time, seed, exponential)
+        when_s = sync_clock(S, mean_time, seed, exponential, **link_kw)
         batch = np.random.default_rng([seed, 4]).integers(0, rows, size=(S, n, M)).astype(np.int32)
         eng = Engine(graph, d, "lsq", M=M, gamma=gamma, n_slots=n, device=device)
         eng.load_data(feats, targs)
@@ -141,7 +162,7 @@ def run_study(n=16, d=4096, rows=1024, M=8, epochs=40, slowdowns=(1, 2, 10, 100)
         f_s = objective(eng.get_mean_model(), feats, targs)
         eng.close()
         rows_out.append({
-            "slowdown": slow,
+            "slowdown": slowdown,
             "adpsgd_time_per_epoch": float(when[-1] / epochs),
             "adpsgd_speedup": float(grads_per_epoch * epochs / when[-1]),       # against one worker of unit speed
             "sync_time_per_epoch": float(when_s[-1] / epochs),
@@ -153,7 +174,7 @@ def run_study(n=16, d=4096, rows=1024, M=8, epochs=40, slowdowns=(1, 2, 10, 100)
             "max_staleness": T_max,
         })
     return {"n": n, "d": d, "rows": rows, "M": M, "epochs": epochs, "gamma": gamma, "initial_objective": f0,
-            "target_objective": target * f0, "clock": "exponential" if exponential else "deterministic",
+            "target_objective": target * f0, "clock": "exponential" if exponential else "deterministic", "slow": slow,
             "results": rows_out}
 
 
@@ -176,9 +197,10 @@ def main(argv=None):
     ap.add_argument("--epochs", type=int, default=40)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--deterministic-clocks", action="store_true")
+    ap.add_argument("--slow", choices=["worker", "link"], default="worker", help="what is slowed down")
     ap.add_argument("--json", action="store_true", help="print the results as one JSON object")
     a = ap.parse_args(argv)
-    res = run_study(a.n, a.d, a.rows, a.M, a.epochs, seed=a.seed, exponential=not a.deterministic_clocks)
+    res = run_study(a.n, a.d, a.rows, a.M, a.epochs, seed=a.seed, exponential=not a.deterministic_clocks, slow=a.slow)
     print(json.dumps(res) if a.json else format_table(res))
 
 

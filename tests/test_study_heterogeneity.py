@@ -37,6 +37,24 @@ def test_deterministic_equal_clocks_give_round_robin_with_staleness_n_minus_1():
     assert np.allclose(H.sync_clock(7, [1, 1, 3, 1], 0, exponential=False), 3 * np.arange(1, 8))
 
 
+def test_slow_link_delays_only_the_events_that_use_it():
+    n, K = 6, 600
+    g = H.ring(n)
+    s, when = H.clock_schedule(g, K, np.ones(n), M=1, rows=4, seed=3, exponential=False, comm_time=0.5,
+                               slow_link=(2, 3), link_slowdown=20.0)
+    assert np.all(np.diff(when) >= 0)
+    prev = {}
+    for k in range(K):
+        i, j = int(s["worker"][k]), int(s["neighbour"][k])
+        took = when[k] - prev.get(i, 0.0)
+        assert np.isclose(took, 1.0 + (10.0 if {i, j} == {2, 3} else 0.5))
+        prev[i] = when[k]
+    share = np.bincount(s["worker"], minlength=n) / K
+    assert share[2] < share[0] and share[3] < share[5]          # the two ends of the slow link update less often
+    # a synchronous iteration waits for the slow link every time
+    assert np.allclose(H.sync_clock(5, np.ones(n), 0, exponential=False, comm_time=0.5, link_slowdown=20.0), 11.0 * np.arange(1, 6))
+
+
 def test_objective_and_smoothing_helpers():
     feats, targs = H.make_problem(3, 16, 8, seed=2, noise=0.0)
     assert all(f is feats[0] for f in feats) and len(feats) == 3          # shared data
@@ -60,3 +78,7 @@ def test_study_runs_end_to_end_on_a_tiny_problem():
     assert slow["adpsgd_speedup"] > 2.5 > 1.0 > slow["sync_speedup"]
     assert slow["adpsgd_time_to_target"] < slow["sync_time_to_target"]
     assert "slowdown" in H.format_table(res)
+    link = H.run_study(n=4, d=256, rows=64, M=4, epochs=6, slowdowns=(1, 50), seed=0, target=0.1, slow="link")
+    a, b = link["results"]
+    assert b["sync_speedup"] < 0.2 * a["sync_speedup"]          # every synchronous iteration waits for the link
+    assert b["adpsgd_speedup"] > 0.25 * a["adpsgd_speedup"]     # AD-PSGD only loses the exchanges that use it
