@@ -115,9 +115,9 @@ typedef struct {
      * to the copy it reads, and evaluates the next gradient there:
      *     x^_k = X_{k - tau_k}[i_k] - gamma_k' g_k'
      * where k' is the latest earlier event of worker i_k in the same call, taken when
-     * k' - tau_k' <= k - tau_k <= k' (else no compensation).  Linear models only (LSQ, LOGREG;
-     * ignored by SYNTH, whose gradients do not depend on the model); not with momentum or weight
-     * decay (ADPSGD_ERR_ARG). */
+     * k' - tau_k' <= k - tau_k <= k' (else no compensation).  Ignored by SYNTH, whose gradients do
+     * not depend on the model; the MLP reads bf16(x^_k) and keeps its pending gradients dense for
+     * it; not with momentum or weight decay (ADPSGD_ERR_ARG). */
     int32_t local_compensation;
 } adpsgd_opts_t;
 

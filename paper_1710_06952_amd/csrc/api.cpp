@@ -87,6 +87,7 @@ struct adpsgd {
     TableSet tables[2];
     int next_table = 0;
     DevBuf grad_scratch;     // dots partials + coefficients / MLP activations
+    DevBuf comp_rows;        // perceptron, wait-free variant: compensated bf16 copies of the rows a group of gradients reads
     DevBuf diag;             // consensus partials, result, mean / broadcast staging
     adpsgd_stats_t stats{};
     std::vector<hipEvent_t> ev_pool;                       // profiling events
@@ -209,8 +210,6 @@ extern "C" int adpsgd_create(adpsgd_t** out, const adpsgd_graph_t* graph, int64_
     if ((o.momentum != 0.0f || o.weight_decay != 0.0f) && (!o.V || !aligned16(o.V)))
         return fail(nullptr, ADPSGD_ERR_ARG, "create: momentum / weight decay need the buffer V (16-byte aligned)");
     if (o.local_compensation) {
-        if (o.model == ADPSGD_MODEL_MLP)
-            return fail(nullptr, ADPSGD_ERR_ARG, "create: local_compensation is implemented for the linear models only");
         if (o.momentum != 0.0f || o.weight_decay != 0.0f)
             return fail(nullptr, ADPSGD_ERR_ARG, "create: local_compensation cannot be combined with momentum or weight decay");
     }
@@ -254,6 +253,7 @@ extern "C" void adpsgd_destroy(adpsgd_t* h) {
     for (auto& pr : h->ev_grad) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
     for (auto e : h->ev_pool) (void)hipEventDestroy(e);
     h->grad_scratch.release();
+    h->comp_rows.release();
     h->diag.release();
     delete h;
 }
@@ -356,8 +356,10 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
     }
 
     // perceptron without momentum: dW1 stays in factored form until the update kernel
+    // (the wait-free variant reads the pending gradient as a dense vector, so it keeps the dense form)
+    const bool mlp_comp = h->o.model == ADPSGD_MODEL_MLP && h->o.local_compensation != 0;
     const bool factored = h->o.model == ADPSGD_MODEL_MLP && !h->o.V && !(h->o.flags & ADPSGD_FLAG_DENSE_GRADIENT) &&
-                          mlp_can_factor(h->o.mlp_in, h->o.mlp_hidden, M);
+                          !mlp_comp && mlp_can_factor(h->o.mlp_in, h->o.mlp_hidden, M);
 
     // ---- plan ----
     Plan plan;
@@ -374,6 +376,15 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
         if (with_grad) ++r_off[plan.r_round[k] + 1];
     }
     for (int32_t r = 0; r < R; ++r) { u_off[r + 1] += u_off[r]; r_off[r + 1] += r_off[r]; }
+
+    // gradients of a round are launched in groups of this many operations
+    int32_t group = 1;
+    if (with_grad) {
+        int64_t max_r = 0;
+        for (int32_t r = 0; r < R; ++r) max_r = std::max(max_r, r_off[r + 1] - r_off[r]);
+        group = static_cast<int32_t>(std::min<int64_t>(std::max<int64_t>(max_r, 1), h->o.model == ADPSGD_MODEL_MLP ? 64 : 65535));
+    }
+    if (mlp_comp) HIP_TRY(h, h->comp_rows.reserve(static_cast<size_t>(group) * h->o.ldx * sizeof(uint16_t)));
 
     // ---- tables: [PairOp x K][GradOp x K][batch_idx K x M] ----
     const size_t bytes_u = static_cast<size_t>(K + n_extra) * sizeof(PairOp);
@@ -415,7 +426,8 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
                 }
             }
             if (with_grad) {
-                GradOp& g = rops[r_fill[plan.r_round[k]]++];
+                const int64_t at = r_fill[plan.r_round[k]]++;
+                GradOp& g = rops[at];
                 g.worker = s->worker[k];
                 g.slot = plan.slot[k];
                 g.event = static_cast<int32_t>(k);
@@ -427,6 +439,9 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
                 g.features = w.features;
                 g.targets = w.targets;
                 g.ld = w.ld;
+                g.xrow_bf16 = nullptr;
+                if (mlp_comp && kp >= 0)      // one compensated row per operation of a launch group
+                    g.xrow_bf16 = static_cast<uint16_t*>(h->comp_rows.p) + ((at - r_off[plan.r_round[k]]) % group) * h->o.ldx;
             }
         }
     }
@@ -438,19 +453,14 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
     const int32_t* d_batch = reinterpret_cast<const int32_t*>(dev + off_b);
 
 
-    // ---- gradient groups ----
-    int32_t group = 1;
+    // ---- gradient scratch ----
     size_t off_coef = 0;
     if (with_grad) {
-        int64_t max_r = 0;
-        for (int32_t r = 0; r < R; ++r) max_r = std::max(max_r, r_off[r + 1] - r_off[r]);
         if (h->o.model == ADPSGD_MODEL_MLP) {
-            group = static_cast<int32_t>(std::min<int64_t>(std::max<int64_t>(max_r, 1), 64));
             HIP_TRY(h, h->grad_scratch.reserve(mlp_scratch_bytes(group, M, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out)));
         } else {
             // all gradients of a round go into one set of launches (measured: splitting a round so
             // that the gathered rows stay within the memory-side cache only adds launches)
-            group = static_cast<int32_t>(std::min<int64_t>(std::max<int64_t>(max_r, 1), 65535));
             const size_t partial_bytes = static_cast<size_t>(group) * (M + 1) * linear_grad_chunks(h->d) * 4;
             off_coef = (partial_bytes + 255) & ~size_t(255);
             HIP_TRY(h, h->grad_scratch.reserve(off_coef + static_cast<size_t>(group) * M * 4));
@@ -473,9 +483,9 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
             }
             int launches = 0;
             if (h->o.model == ADPSGD_MODEL_MLP) {
-                MlpGradArgs a{h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, d_rops + g0, cnt, M,
+                MlpGradArgs a{h->o.X, h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, d_rops + g0, cnt, M,
                               d_batch, slots, gscale, loss,
-                              h->grad_scratch.p, factored};
+                              h->grad_scratch.p, factored, mlp_comp};
                 HIP_TRY(h, launch_mlp_gradient(a, h->stream, &launches));
             } else {
                 LinearGradArgs a{h->o.model, h->o.X, h->o.ldx, h->d, d_rops + g0, cnt, M, d_batch,
@@ -603,7 +613,7 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
         for (int64_t t = 0; t < S; ++t)
             for (int32_t i = 0; i < n; ++i)
                 rops[t * n + i] = GradOp{i, i, static_cast<int32_t>(t * n + i), -1, 0.0f, 0,
-                                         h->data[i].features, h->data[i].targets, h->data[i].ld};
+                                         h->data[i].features, h->data[i].targets, h->data[i].ld, nullptr};
         std::memcpy(stage + off_b, s->batch_idx, bytes_b);
     }
     std::memcpy(stage + off_ws, w_self.data(), static_cast<size_t>(n) * 4);
@@ -636,9 +646,9 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
             const int32_t cnt = std::min<int32_t>(group, n - g0);
             int launches = 0;
             if (h->o.model == ADPSGD_MODEL_MLP) {
-                MlpGradArgs a{h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, d_rops + t * n + g0, cnt, M,
+                MlpGradArgs a{h->o.X, h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, d_rops + t * n + g0, cnt, M,
                               d_batch, slots, gscale, loss,
-                              h->grad_scratch.p, false};
+                              h->grad_scratch.p, false, false};
                 HIP_TRY(h, launch_mlp_gradient(a, h->stream, &launches));
             } else {
                 LinearGradArgs a{h->o.model, h->o.X, h->o.ldx, h->d, d_rops + t * n + g0, cnt, M, d_batch,

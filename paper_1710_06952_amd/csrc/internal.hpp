@@ -36,6 +36,8 @@ struct GradOp {
     const void* features;   // the worker's local data (device), copied here so that a kernel reaches
     const void* targets;    //   it with one load instead of a second table look-up
     int64_t ld;             // leading dimension of features, in elements
+    const void* xrow_bf16;  // perceptron, wait-free variant: bf16 row the gradient reads instead of the worker's
+                            //   shadow (the compensated copy x - gamma_k' g_k'), or nullptr
 };
 
 struct WorkerData {
@@ -107,6 +109,7 @@ int64_t linear_grad_chunks(int64_t d);
 hipError_t launch_linear_gradient(const LinearGradArgs& a, hipStream_t st, int* n_launches);
 
 struct MlpGradArgs {
+    const float* X;         // device fp32 master, n x ld (read by the wait-free variant only)
     const uint16_t* Xbf16;  // device bf16 shadow, n x ld
     int64_t ld;
     int32_t in, hid, out;
@@ -119,6 +122,7 @@ struct MlpGradArgs {
     float* loss;
     void* scratch;          // device scratch, mlp_scratch_bytes(n_ops, ...)
     bool factored;          // leave dW1 as its factors: dH goes to the start of the slot, no dW1 launch
+    bool compensate;        // wait-free variant: first build the compensated bf16 rows the operations name
 };
 size_t mlp_scratch_bytes(int32_t n_ops, int32_t M, int32_t in, int32_t hid, int32_t out);
 bool mlp_can_factor(int32_t in, int32_t hid, int32_t M);

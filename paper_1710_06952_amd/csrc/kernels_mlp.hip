@@ -30,6 +30,7 @@ constexpr int kMaxOut = 16;
 constexpr int kTileH = 64;       // hidden columns per block: 16 per wavefront
 
 struct MlpParams {
+    const float* X;
     const uint16_t* Xb;
     int64_t ld;
     int in, hid, out;
@@ -53,6 +54,27 @@ __device__ __forceinline__ v4f mfma_bf16(v8h a, v8h b, v4f c) {
 // Operand layout of v_mfma_f32_16x16x32_bf16 (D = A B + C, A 16x32, B 32x16):
 //   lane l supplies A[l % 16][8 (l / 16) .. +7] and B[8 (l / 16) .. +7][l % 16];
 //   lane l receives D[4 (l / 16) + v][l % 16] in element v of its 4 results.
+
+// ---- 0. wait-free variant: the compensated copy of the model a gradient reads ---------------
+// For operations that carry a pending gradient g_k' (dense, in slot comp_slot):
+//     xrow = bf16(x^i - gamma_k' g_k')        (two fp32 roundings, then round to nearest even)
+// grid = (ceil(ld / 1024), n_ops); operations without compensation return at once.
+__global__ __launch_bounds__(kT) void mlp_compensated_rows_kernel(const MlpParams p) {
+    const GradOp op = p.ops[blockIdx.y];
+    if (op.comp_slot < 0 || !op.xrow_bf16) return;
+    const int64_t e = 4 * (static_cast<int64_t>(blockIdx.x) * kT + threadIdx.x);
+    if (e >= p.ld) return;
+    const v4f x = *reinterpret_cast<const v4f*>(p.X + static_cast<int64_t>(op.worker) * p.ld + e);
+    const v4f g = *reinterpret_cast<const v4f*>(p.slots + static_cast<int64_t>(op.comp_slot) * p.ld + e);
+    v4f c;
+    {
+#pragma clang fp contract(off)
+        const v4f step = g * op.comp_gamma;
+        c = x - step;
+    }
+    uint16_t* __restrict__ dst = static_cast<uint16_t*>(const_cast<void*>(op.xrow_bf16)) + e;
+    *reinterpret_cast<v4h*>(dst) = v4h{bf16_rne(c.x), bf16_rne(c.y), bf16_rne(c.z), bf16_rne(c.w)};
+}
 
 // ---- 1. forward: H = relu(Xb W1 + b1), grid = (hid / 32, n_ops) ----------------------
 // One block (512 threads) owns a 64 (minibatch) x 32 (hidden) tile of H.  The contraction over
@@ -80,7 +102,8 @@ __global__ __launch_bounds__(kFwdT) void mlp_forward_kernel(const MlpParams p) {
     const GradOp op = p.ops[blockIdx.y];
     const uint16_t* __restrict__ feat = static_cast<const uint16_t*>(op.features);
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
-    const uint16_t* __restrict__ W1 = p.Xb + static_cast<int64_t>(op.worker) * p.ld;
+    const uint16_t* __restrict__ W1 = op.xrow_bf16 ? static_cast<const uint16_t*>(op.xrow_bf16)
+                                                   : p.Xb + static_cast<int64_t>(op.worker) * p.ld;
     const uint16_t* __restrict__ b1 = W1 + static_cast<int64_t>(p.in) * p.hid;
     const int h0 = blockIdx.x * kFwdTileH;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -230,7 +253,8 @@ __global__ __launch_bounds__(kBwdT) void mlp_backward_small_kernel(const MlpPara
     const int hl = threadIdx.x & 63, mg = threadIdx.x >> 6;
     const int h = blockIdx.x * 64 + hl;
     const int sm = threadIdx.x >> 4, so = threadIdx.x & 15;       // step a: sample and logit
-    const uint16_t* __restrict__ W = p.Xb + static_cast<int64_t>(op.worker) * p.ld;
+    const uint16_t* __restrict__ W = op.xrow_bf16 ? static_cast<const uint16_t*>(op.xrow_bf16)
+                                                  : p.Xb + static_cast<int64_t>(op.worker) * p.ld;
     const uint16_t* __restrict__ W2 = W + static_cast<int64_t>(p.in) * p.hid + p.hid;
     const uint16_t* __restrict__ b2 = W2 + static_cast<int64_t>(p.hid) * p.out;
 
@@ -558,6 +582,7 @@ hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_laun
     if (a.n_ops <= 0) return hipSuccess;
     if (mlp_scratch_bytes(a.n_ops, a.M, a.in, a.hid, a.out) == 0 || a.n_ops > 65535) return hipErrorInvalidValue;
     MlpParams p;
+    p.X = a.X;
     p.Xb = a.Xbf16;
     p.ld = a.ld;
     p.in = a.in;
@@ -577,6 +602,14 @@ hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_laun
     p.dHb = reinterpret_cast<uint16_t*>(s + act);
     p.logit_part = reinterpret_cast<float*>(s + 2 * act);
     const uint32_t hb = static_cast<uint32_t>(a.hid / kTileH);
+    if (a.compensate) {
+        if (!a.X || a.factored) return hipErrorInvalidValue;
+        const int64_t cb = (a.ld / 4 + kT - 1) / kT;
+        hipLaunchKernelGGL(mlp_compensated_rows_kernel, dim3(static_cast<uint32_t>(cb), a.n_ops), dim3(kT), 0, st, p);
+        const hipError_t ec = hipGetLastError();
+        if (ec != hipSuccess) return ec;
+        if (n_launches) *n_launches += 1;
+    }
     hipLaunchKernelGGL(mlp_forward_kernel, dim3(a.hid / kFwdTileH, a.n_ops), dim3(kFwdT), 0, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -562,6 +562,32 @@ def test_waitfree_local_compensation(P, model, n, d, rows, K, M, T, gamma, lam):
     eng.close()
 
 
+def test_waitfree_local_compensation_mlp(P):
+    """The perceptron reads the bf16 rounding of the compensated copy x - gamma g' of its master weights."""
+    from workloads import mixture_data, mlp_init
+    n, dims, rows, K, M, T = 4, (24, 64, 5), 40, 250, 16, 5
+    _say("wait-free variant, mlp")
+    g = ring_graph(n)
+    d = dims[0] * dims[1] + dims[1] + dims[1] * dims[2] + dims[2]
+    feats, labels, _ = mixture_data(n, rows, din=dims[0], classes=dims[2], seed=14)
+    sched = oracle.make_schedule(g, K, seed=15, T_max=T, M=M, rows=[rows] * n)
+    x0 = mlp_init(*dims, seed=14)
+    eng = P.Engine(g, d, "mlp", M=M, gamma=0.2, T_max=T, mlp=dims, local_compensation=True)
+    eng.load_data(feats, labels)
+    eng.set_models(x0)
+    eng.run_events(sched, want_loss=True)
+    Xg, loss_g = eng.get_models(), eng.get_loss()
+    kw = dict(M=M, gscale=1.0 / M, mlp=dims, features=feats, targets=labels, want_loss=True)
+    Xr = np.tile(x0, (n, 1))
+    r = oracle.run_events(Xr, sched, oracle.MODEL_MLP, 0.2, local_compensation=True, **kw)
+    assert rel_err(Xg, Xr) <= MLP_TOL_MASTER
+    assert np.allclose(loss_g, r["loss"], rtol=5e-3, atol=1e-4)
+    Xp = np.tile(x0, (n, 1))
+    oracle.run_events(Xp, sched, oracle.MODEL_MLP, 0.2, **kw)
+    assert rel_err(Xg, Xp) > 10 * MLP_TOL_MASTER           # not a no-op on this schedule
+    eng.close()
+
+
 def test_waitfree_variant_is_refused_where_it_is_not_defined(P):
     import torch
     X = torch.zeros((4, 64), device="cuda")
