@@ -245,6 +245,14 @@ int adpsgd_get_bf16_models(adpsgd_t* h, uint16_t* out, int64_t ld_out, int32_t o
 
 int adpsgd_get_stats(adpsgd_t* h, adpsgd_stats_t* out);
 
+/* Checkpoint and resume.  The state of a run is the models (adpsgd_get_models / adpsgd_set_models
+ * with ld_in > 0), the caller-owned momentum buffers, and the number of events executed so far,
+ * which addresses the synthetic-gradient generator (event k of the handle's life draws stream k).
+ * A new handle restored with these three continues bit for bit.  The count includes the n worker
+ * updates of every synchronous iteration. */
+int adpsgd_get_event_count(adpsgd_t* h, uint64_t* out);
+int adpsgd_set_event_count(adpsgd_t* h, uint64_t events);
+
 /* Host-only helpers (no GPU needed) ------------------------------------------ */
 
 /* The random choices of Algorithm 1 for events k_begin .. k_begin + K - 1 of the

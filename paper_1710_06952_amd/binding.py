@@ -22,6 +22,7 @@ EXPORTS = [
     "adpsgd_run_events", "adpsgd_get_models", "adpsgd_get_mean_model", "adpsgd_consensus_distance",
     "adpsgd_get_bf16_models", "adpsgd_get_momentum", "adpsgd_get_stats", "adpsgd_make_schedule", "adpsgd_plan_rounds",
     "adpsgd_synth_gradient", "adpsgd_run_sync_steps", "adpsgd_metropolis_weights",
+    "adpsgd_get_event_count", "adpsgd_set_event_count",
 ]
 
 
@@ -115,6 +116,8 @@ def lib():
                                          P(i64), P(i32), P(i32), i32, P(i64)]
         L.adpsgd_synth_gradient.argtypes = [u64, u64, C.c_float, i64, vp, vp]
         L.adpsgd_run_sync_steps.argtypes = [vp, P(SyncSchedule), vp]
+        L.adpsgd_get_event_count.argtypes = [vp, P(u64)]
+        L.adpsgd_set_event_count.argtypes = [vp, u64]
         L.adpsgd_metropolis_weights.argtypes = [P(Graph), P(C.c_float), P(C.c_float)]
         _lib = L
     return _lib
@@ -264,6 +267,14 @@ class Handle:
             we = np.ascontiguousarray(weights[1], dtype=np.float32)
         s = SyncSchedule(steps, _i32p(batch), fp(gam), fp(ws), fp(we))
         _check(self._h, lib().adpsgd_run_sync_steps(self._h, C.byref(s), loss_ptr))
+
+    def get_event_count(self):
+        out = C.c_uint64(0)
+        _check(self._h, lib().adpsgd_get_event_count(self._h, C.byref(out)))
+        return out.value
+
+    def set_event_count(self, events):
+        _check(self._h, lib().adpsgd_set_event_count(self._h, events))
 
     def get_models(self, out=None, ld_out=None, on_device=False):
         if on_device:

@@ -766,6 +766,19 @@ extern "C" int adpsgd_get_stats(adpsgd_t* h, adpsgd_stats_t* out) {
     return ADPSGD_OK;
 }
 
+extern "C" int adpsgd_get_event_count(adpsgd_t* h, uint64_t* out) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (!out) return fail(h, ADPSGD_ERR_ARG, "get_event_count: out is NULL");
+    *out = h->events_done;
+    return ADPSGD_OK;
+}
+
+extern "C" int adpsgd_set_event_count(adpsgd_t* h, uint64_t events) {
+    if (!h) return ADPSGD_ERR_ARG;
+    h->events_done = events;
+    return ADPSGD_OK;
+}
+
 extern "C" int adpsgd_synth_gradient(uint64_t seed, uint64_t k, float std, int64_t d, float* out_device, void* stream) {
     if (!out_device || d < 0) return ADPSGD_ERR_ARG;
     const hipError_t e = launch_synth_gradient(seed, k, std, d, out_device, static_cast<hipStream_t>(stream));

@@ -811,3 +811,37 @@ def test_seeded_sweep_of_small_set_ups(P, block):
         if V is not None:
             assert np.abs(eng.get_momentum() - V).max() <= TOL * max(np.abs(V).max(), 1e-30), c
         eng.close()
+
+
+def test_checkpoint_and_resume_continue_bit_for_bit(P):
+    """Models + momentum buffers + event count restore a run: a fresh handle continues exactly."""
+    import torch
+    n, d, T, K1, K2 = 6, 3001, 3, 150, 170
+    g = ring_graph(n)
+    std = float(np.float32(0.02))
+    mk = lambda: P.Engine(g, d, "synth", gamma=0.1, T_max=T, synth_std=std, synth_seed=4, momentum=0.9, weight_decay=1e-4)
+    a = P.adpsgd_make_schedule(g, K1, seed=1, T_max=T)
+    b = P.adpsgd_make_schedule(g, K2, seed=1, T_max=T, k_begin=K1)
+    e1 = mk()
+    e1.set_models(np.zeros(d, np.float32))
+    e1.run_events(a)
+    X_mid, V_mid, count = e1.get_models(), e1.get_momentum(), e1.h.get_event_count()
+    assert count == K1
+    e1.run_events(b)
+    X_end, V_end = e1.get_models(), e1.get_momentum()
+    e1.close()
+    e2 = mk()
+    e2.set_models(X_mid, broadcast=False)                         # zeroes the momentum buffers ...
+    e2.V[:, :d].copy_(torch.from_numpy(V_mid))                     # ... which the caller owns and restores
+    e2.h.set_event_count(count)
+    e2.run_events(b)
+    assert np.array_equal(e2.get_models(), X_end) and np.array_equal(e2.get_momentum(), V_end)
+    assert e2.h.get_event_count() == K1 + K2
+    # without the event count the synthetic gradients restart from stream 0 and the run differs
+    e3 = mk()
+    e3.set_models(X_mid, broadcast=False)
+    e3.V[:, :d].copy_(torch.from_numpy(V_mid))
+    e3.run_events(b)
+    assert not np.array_equal(e3.get_models(), X_end)
+    e2.close()
+    e3.close()
