@@ -64,6 +64,10 @@ enum {
 
 enum {
     ADPSGD_FLAG_PROFILE = 1, /* time every kernel launch with HIP events (see adpsgd_get_stats) */
+    ADPSGD_FLAG_VERIFY_PLAN = 4, /* check every plan of rounds against the serial semantics before anything is
+                                    launched (no two updates of a round share a row, every stale read sees exactly
+                                    the updates before its logical time, slots live long enough); a violation is a
+                                    library bug and returns ADPSGD_ERR_STATE.  O(K log K) host work per call */
     ADPSGD_FLAG_DENSE_GRADIENT = 2  /* MLP: always write the first-layer gradient out as a dense matrix.
                                        By default (no momentum) it stays in factored form, dH and the
                                        minibatch inputs, until the update kernel multiplies the two; the
@@ -280,6 +284,15 @@ int adpsgd_plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_
                        int32_t* r_round, int32_t* u_round, int32_t* slot, int32_t* n_rounds,
                        const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b,
                        int32_t local_compensation, int64_t* prev);
+
+/* The check behind ADPSGD_FLAG_VERIFY_PLAN on its own (host only): ADPSGD_OK when the plan
+ * (arrays as produced by adpsgd_plan_rounds; prev may be NULL) keeps the serial semantics of the
+ * events, ADPSGD_ERR_STATE when it does not. */
+int adpsgd_verify_plan(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
+                       const int32_t* tau, int32_t n_slots, int32_t with_gradients,
+                       const int32_t* r_round, const int32_t* u_round, const int32_t* slot, int32_t n_rounds,
+                       const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b,
+                       const int64_t* prev);
 
 /* Fill a device buffer with the synthetic gradient g_k[0..d) of global event k
  * (ADPSGD_MODEL_SYNTH's generator), on `stream`.  For tests of the generator. */

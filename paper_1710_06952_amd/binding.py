@@ -15,14 +15,14 @@ LIB_PATH = _HERE / "libadpsgd.so"
 
 OK, ERR_ARG, ERR_GRAPH, ERR_SCHEDULE, ERR_STATE, ERR_HIP = 0, -1, -2, -3, -4, -5
 MODEL_LSQ, MODEL_LOGREG, MODEL_SYNTH, MODEL_MLP = 0, 1, 2, 3
-FLAG_PROFILE, FLAG_DENSE_GRADIENT = 1, 2
+FLAG_PROFILE, FLAG_DENSE_GRADIENT, FLAG_VERIFY_PLAN = 1, 2, 4
 
 EXPORTS = [
     "adpsgd_create", "adpsgd_destroy", "adpsgd_last_error", "adpsgd_load_data", "adpsgd_set_models",
     "adpsgd_run_events", "adpsgd_get_models", "adpsgd_get_mean_model", "adpsgd_consensus_distance",
     "adpsgd_get_bf16_models", "adpsgd_get_momentum", "adpsgd_get_stats", "adpsgd_make_schedule", "adpsgd_plan_rounds",
     "adpsgd_synth_gradient", "adpsgd_run_sync_steps", "adpsgd_metropolis_weights",
-    "adpsgd_get_event_count", "adpsgd_set_event_count",
+    "adpsgd_get_event_count", "adpsgd_set_event_count", "adpsgd_verify_plan",
 ]
 
 
@@ -116,6 +116,8 @@ def lib():
                                          P(i64), P(i32), P(i32), i32, P(i64)]
         L.adpsgd_synth_gradient.argtypes = [u64, u64, C.c_float, i64, vp, vp]
         L.adpsgd_run_sync_steps.argtypes = [vp, P(SyncSchedule), vp]
+        L.adpsgd_verify_plan.argtypes = [i32, i64, P(i32), P(i32), P(i32), i32, i32, P(i32), P(i32), P(i32), i32,
+                                         P(i64), P(i32), P(i32), P(i64)]
         L.adpsgd_get_event_count.argtypes = [vp, P(u64)]
         L.adpsgd_set_event_count.argtypes = [vp, u64]
         L.adpsgd_metropolis_weights.argtypes = [P(Graph), P(C.c_float), P(C.c_float)]
@@ -181,6 +183,21 @@ def adpsgd_plan_rounds(n, worker, neighbour, tau, n_slots, with_gradients=True, 
     if local_compensation:
         return r, u, s, nr.value, prev
     return r, u, s, nr.value
+
+
+def adpsgd_verify_plan(n, worker, neighbour, tau, n_slots, r_round, u_round, slot, n_rounds, with_gradients=True,
+                       extra_pairs=None, prev=None):
+    """Host-only: True when the plan keeps the serial semantics of the events."""
+    worker, neighbour, tau, r_round, u_round, slot = map(_as_i32, (worker, neighbour, tau, r_round, u_round, slot))
+    ep, ea, eb = _extra_arrays(extra_pairs)
+    pv = None if prev is None else np.ascontiguousarray(prev, dtype=np.int64)
+    i64p = lambda a: None if a is None else a.ctypes.data_as(C.POINTER(C.c_int64))
+    rc = lib().adpsgd_verify_plan(n, worker.size, _i32p(worker), _i32p(neighbour), _i32p(tau), n_slots,
+                                  1 if with_gradients else 0, _i32p(r_round), _i32p(u_round), _i32p(slot), n_rounds,
+                                  i64p(ep), _i32p(ea), _i32p(eb), i64p(pv))
+    if rc not in (OK, ERR_STATE):
+        raise AdpsgdError(rc, "adpsgd_verify_plan: bad argument")
+    return rc == OK
 
 
 def adpsgd_metropolis_weights(graph):

@@ -367,6 +367,9 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
     int rc = plan_rounds(h->n, K, s->worker, s->neighbour, s->tau, h->n_slots, with_grad, plan, perr,
                          s->extra_ptr, s->extra_a, s->extra_b, h->o.local_compensation != 0);
     if (rc != ADPSGD_OK) return fail(h, rc, perr);
+    if ((h->o.flags & ADPSGD_FLAG_VERIFY_PLAN) &&
+        !verify_plan(h->n, K, s->worker, s->neighbour, s->tau, h->n_slots, with_grad, plan, perr, s->extra_ptr, s->extra_a, s->extra_b))
+        return fail(h, ADPSGD_ERR_STATE, perr);
     const int32_t R = plan.n_rounds;
 
     // counting sort of the operations by round

@@ -107,9 +107,97 @@ int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neig
     return ADPSGD_OK;
 }
 
+// Independent check of a plan against the serial semantics (the library's race detector):
+//   1. the updates of a round touch pairwise distinct rows;
+//   2. per row the updates keep their event order, in strictly increasing rounds;
+//   3. the read of event k sees exactly the updates of its row with index < s_k = k - tau_k: the last
+//      such update lies in an earlier round, the first update with index >= s_k in the same or a later one;
+//   4. a gradient is computed no later than the round that applies it, and a slot is rewritten only in
+//      a later round than the update that consumed it;
+//   5. wait-free variant: a compensated read runs after the gradient it uses and no later than the round
+//      that applies that gradient.
+bool verify_plan(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour, const int32_t* tau,
+                 int32_t n_slots, bool with_gradients, const Plan& plan, std::string& err,
+                 const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b) {
+    auto bad = [&](const std::string& what, int64_t k) {
+        err = "plan check: " + what + " at event " + std::to_string(k);
+        return false;
+    };
+    if (static_cast<int64_t>(plan.u_round.size()) != K) return bad("wrong size", 0);
+    // rows of every event, and per row the events that update it (in event order)
+    std::vector<std::vector<int64_t>> touches(n);
+    std::vector<int64_t> stamp_round(n, -1), stamp_event(n, -1);
+    auto rows_of = [&](int64_t k, std::vector<int32_t>& rows) {
+        rows.clear();
+        rows.push_back(worker[k]);
+        if (neighbour[k] != worker[k]) rows.push_back(neighbour[k]);
+        if (extra_ptr)
+            for (int64_t q = extra_ptr[k]; q < extra_ptr[k + 1]; ++q) {
+                rows.push_back(extra_a[q]);
+                rows.push_back(extra_b[q]);
+            }
+    };
+    std::vector<int32_t> rows;
+    for (int64_t k = 0; k < K; ++k) {
+        const int32_t u = plan.u_round[k];
+        if (u < 0 || u >= plan.n_rounds) return bad("update round out of range", k);
+        rows_of(k, rows);
+        for (int32_t r : rows) {
+            if (!touches[r].empty()) {
+                const int64_t m = touches[r].back();
+                if (m == k) return bad("an event names a row twice", k);
+                if (plan.u_round[m] >= u) return bad("updates of a row out of order or sharing a round", k);   // 1 and 2
+            }
+            touches[r].push_back(k);
+        }
+    }
+    if (!with_gradients) return true;
+    std::vector<int64_t> slot_last(n_slots, -1);      // event that last used the slot, in order of the rounds
+    std::vector<int64_t> order(K);
+    for (int64_t k = 0; k < K; ++k) order[k] = k;
+    std::stable_sort(order.begin(), order.end(), [&](int64_t a, int64_t b) { return plan.r_round[a] < plan.r_round[b]; });
+    for (int64_t k : order) {
+        const int32_t r = plan.r_round[k], i = worker[k];
+        if (r < 0 || r > plan.u_round[k]) return bad("gradient later than its update", k);                     // 4
+        const int64_t s = k - tau[k];
+        const auto& tv = touches[i];
+        const auto it = std::lower_bound(tv.begin(), tv.end(), s);      // first update of the row with index >= s
+        if (it != tv.begin() && plan.u_round[*(it - 1)] >= r) return bad("stale read misses an earlier update", k);   // 3
+        if (it != tv.end() && plan.u_round[*it] < r) return bad("stale read sees a later update", k);                // 3
+        const int32_t sl = plan.slot[k];
+        if (sl < 0 || sl >= n_slots) return bad("slot out of range", k);
+        if (slot_last[sl] >= 0 && plan.u_round[slot_last[sl]] >= r) return bad("slot rewritten before its gradient was applied", k);   // 4
+        slot_last[sl] = k;
+        const int64_t kp = plan.prev[k];
+        if (kp >= 0 && !(plan.r_round[kp] < r && r <= plan.u_round[kp])) return bad("compensated read outside the life of its gradient", k);   // 5
+    }
+    return true;
+}
+
 }  // namespace adpsgd_impl
 
 using namespace adpsgd_impl;
+
+extern "C" int adpsgd_verify_plan(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
+                                  const int32_t* tau, int32_t n_slots, int32_t with_gradients,
+                                  const int32_t* r_round, const int32_t* u_round, const int32_t* slot, int32_t n_rounds,
+                                  const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b,
+                                  const int64_t* prev) {
+    if (n < 1 || K < 0 || !worker || !neighbour || !tau || !r_round || !u_round || !slot) return ADPSGD_ERR_ARG;
+    for (int64_t k = 0; k < K; ++k)
+        if (worker[k] < 0 || worker[k] >= n || neighbour[k] < 0 || neighbour[k] >= n || tau[k] < 0 || tau[k] > k)
+            return ADPSGD_ERR_SCHEDULE;
+    Plan plan;
+    plan.r_round.assign(r_round, r_round + K);
+    plan.u_round.assign(u_round, u_round + K);
+    plan.slot.assign(slot, slot + K);
+    if (prev) plan.prev.assign(prev, prev + K);
+    else plan.prev.assign(static_cast<size_t>(K), -1);
+    plan.n_rounds = n_rounds;
+    std::string err;
+    return verify_plan(n, K, worker, neighbour, tau, n_slots, with_gradients != 0, plan, err, extra_ptr, extra_a, extra_b)
+               ? ADPSGD_OK : ADPSGD_ERR_STATE;
+}
 
 extern "C" int adpsgd_plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
                                   const int32_t* tau, int32_t n_slots, int32_t with_gradients,

@@ -783,7 +783,7 @@ def test_seeded_sweep_of_small_set_ups(P, block):
         std = float(np.float32(0.1))
         eng = P.Engine(c["g"], d, c["model"], M=M, gamma=0.1, lam=1e-3 if c["model"] == "logreg" else 0.0, T_max=c["T"],
                        synth_std=std, synth_seed=c["seed"], momentum=c["momentum"], weight_decay=c["wd"],
-                       local_compensation=c["comp"])
+                       local_compensation=c["comp"], verify_plan=True)
         x0 = np.random.default_rng(c["seed"]).standard_normal((n, d)).astype(np.float32)
         kw = {}
         if c["model"] != "synth":

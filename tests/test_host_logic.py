@@ -91,11 +91,11 @@ def test_create_validates_graph_and_buffers_before_touching_the_gpu():
 
 
 # ----------------------------------------------------------------------------- planner
-def _check_plan(n, sched, n_slots, with_grad=True):
+def _validate_plan(n, sched, n_slots, r_round, u_round, slot, R, with_grad=True):
+    """Executes the plan symbolically (row versions) and asserts that it equals the serial order."""
     w, j, tau = sched["worker"], sched["neighbour"], sched["tau"]
     K = len(w)
-    r_round, u_round, slot, R = P.adpsgd_plan_rounds(n, w, j, tau, n_slots, with_grad)
-    assert u_round.min() >= 0 and u_round.max() == R - 1
+    assert u_round.min() >= 0 and u_round.max() <= R - 1
     # serial reference: version of every row as seen by each read, order of updates per row
     version = np.zeros(n, np.int64)
     seen_serial = np.zeros(K, np.int64)
@@ -131,7 +131,7 @@ def _check_plan(n, sched, n_slots, with_grad=True):
                 last_u_event[row] = k
                 version[row] += 1
             pu += 1
-    assert pu == K
+    assert pu == K and (not with_grad or pr == K)
     if with_grad:
         assert slot.min() >= 0 and slot.max() < n_slots
         for s in range(n_slots):
@@ -139,6 +139,14 @@ def _check_plan(n, sched, n_slots, with_grad=True):
             ks = ks[np.argsort(r_round[ks], kind="stable")]
             for a, b in zip(ks[:-1], ks[1:]):
                 assert r_round[b] > u_round[a], "slot rewritten before its gradient was consumed"
+
+
+def _check_plan(n, sched, n_slots, with_grad=True):
+    w, j, tau = sched["worker"], sched["neighbour"], sched["tau"]
+    r_round, u_round, slot, R = P.adpsgd_plan_rounds(n, w, j, tau, n_slots, with_grad)
+    assert u_round.max() == R - 1
+    _validate_plan(n, sched, n_slots, r_round, u_round, slot, R, with_grad)
+    assert P.adpsgd_verify_plan(n, w, j, tau, n_slots, r_round, u_round, slot, R, with_grad)
     return R
 
 
@@ -295,3 +303,63 @@ def test_metropolis_weights_agree_with_the_oracle_bit_for_bit():
     w_self, w_edge = P.adpsgd_metropolis_weights((rowptr, col))
     assert np.array_equal(w_edge, np.full(8, np.float32(0.2))) and w_self[1] == np.float32(0.8)
     assert np.array_equal(np.diag(oracle.metropolis_weights((rowptr, col))), w_self)
+
+
+def test_plan_verifier_agrees_with_the_symbolic_execution_on_damaged_plans():
+    """The library's own plan check (its race detector) against this file's symbolic execution: single
+    entries of correct plans are perturbed; the two must reach the same verdict every time, and both
+    verdicts must occur."""
+    rng = np.random.default_rng(11)
+    verdicts = {True: 0, False: 0}
+    for trial in range(6):
+        n, T, K = int(rng.integers(3, 12)), int(rng.integers(0, 6)), 120
+        g = ring_graph(n) if trial % 2 else random_regular4_graph(max(n, 6), trial)
+        n = len(g[0]) - 1
+        sched = oracle.make_schedule(g, K, seed=trial, T_max=T)
+        w, j, tau = sched["worker"], sched["neighbour"], sched["tau"]
+        n_slots = T + 2
+        r0, u0, s0, R = P.adpsgd_plan_rounds(n, w, j, tau, n_slots, True)
+        for m in range(60):
+            r_round, u_round, slot = r0.copy(), u0.copy(), s0.copy()
+            k = int(rng.integers(K))
+            what = m % 4
+            if what == 0:
+                u_round[k] = max(0, u_round[k] - int(rng.integers(1, 3)))
+            elif what == 1:
+                u_round[k] = min(R - 1, u_round[k] + int(rng.integers(1, 3)))
+            elif what == 2:
+                r_round[k] = int(np.clip(r_round[k] + int(rng.integers(-2, 3)), 0, R - 1))
+            else:
+                slot[k] = int(rng.integers(n_slots))
+            try:
+                _validate_plan(n, sched, n_slots, r_round, u_round, slot, R, True)
+                mine = True
+            except AssertionError:
+                mine = False
+            theirs = P.adpsgd_verify_plan(n, w, j, tau, n_slots, r_round, u_round, slot, R, True)
+            assert mine == theirs, (trial, m, k, what)
+            verdicts[mine] += 1
+    assert verdicts[True] > 20 and verdicts[False] > 100
+
+
+def test_plan_verifier_covers_extra_pairs_and_the_waitfree_dependency():
+    from workloads import random_extra_pairs
+    n, K, T = 10, 300, 4
+    g = random_regular4_graph(n, 2)
+    sched = oracle.make_schedule(g, K, seed=3, T_max=T)
+    w, j, tau = sched["worker"], sched["neighbour"], sched["tau"]
+    extra = random_extra_pairs(g, w, j, max_extra=3, seed=4)
+    r, u, s, R = P.adpsgd_plan_rounds(n, w, j, tau, T + 2, True, extra_pairs=extra)
+    assert P.adpsgd_verify_plan(n, w, j, tau, T + 2, r, u, s, R, extra_pairs=extra)
+    # a plan made without the extra pairs lets them collide with other updates of the round
+    r2, u2, s2, R2 = P.adpsgd_plan_rounds(n, w, j, tau, T + 2, True)
+    assert not P.adpsgd_verify_plan(n, w, j, tau, T + 2, r2, u2, s2, R2, extra_pairs=extra)
+    # wait-free variant: the compensated read needs its pending gradient
+    n = 4
+    g = ring_graph(n)
+    sched = oracle.make_schedule(g, K, seed=5, T_max=6)
+    w, j, tau = sched["worker"], sched["neighbour"], sched["tau"]
+    r, u, s, R, prev = P.adpsgd_plan_rounds(n, w, j, tau, 8, True, local_compensation=True)
+    assert P.adpsgd_verify_plan(n, w, j, tau, 8, r, u, s, R, prev=prev)
+    r3, u3, s3, R3 = P.adpsgd_plan_rounds(n, w, j, tau, 8, True)           # planned without the dependency
+    assert (prev >= 0).any() and not P.adpsgd_verify_plan(n, w, j, tau, 8, r3, u3, s3, R3, prev=prev)
