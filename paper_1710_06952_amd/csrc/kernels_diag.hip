@@ -33,7 +33,7 @@ __global__ __launch_bounds__(kThreads) void refresh_bf16_kernel(const float* X, 
     *reinterpret_cast<v4h*>(Xb + off) = h;
 }
 
-constexpr int kRowBatch = 8;   // rows whose loads are in flight together
+constexpr int kRowBatch = 8;   // rows whose loads are in flight together (4 and 16 measure the same)
 
 // one thread per float4 of d: column sums over the n rows in a fixed order
 // STREAM: X does not fit the caches and is read once: non-temporal loads
