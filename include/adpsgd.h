@@ -241,6 +241,14 @@ int adpsgd_get_mean_model(adpsgd_t* h, float* out, int32_t on_device);
  * appendix with uniform p.  *out is host memory.  Synchronous. */
 int adpsgd_consensus_distance(adpsgd_t* h, double* out);
 
+/* The objective of the problem statement (Sec. 3.1, uniform p) at one point:
+ *     f(x) = (1/n) sum_i (1/rows_i) sum_{rows of worker i} F(x; row)
+ * over ALL local data, F as in ADPSGD_MODEL_* (the logistic loss includes lambda |x|^2 / 2).
+ * x: device, d floats, or NULL for the mean of the workers' models (Algorithm 1's output).
+ * *out is host memory.  LSQ and LOGREG only (ADPSGD_ERR_STATE otherwise, or when a worker has no
+ * data).  Synchronous; reads every local row once. */
+int adpsgd_objective(adpsgd_t* h, const float* x, double* out);
+
 /* Copy the n x d momentum buffers (only when opts.V was given). Synchronises the stream. */
 int adpsgd_get_momentum(adpsgd_t* h, float* out, int64_t ld_out, int32_t on_device);
 

@@ -22,7 +22,7 @@ EXPORTS = [
     "adpsgd_run_events", "adpsgd_get_models", "adpsgd_get_mean_model", "adpsgd_consensus_distance",
     "adpsgd_get_bf16_models", "adpsgd_get_momentum", "adpsgd_get_stats", "adpsgd_make_schedule", "adpsgd_plan_rounds",
     "adpsgd_synth_gradient", "adpsgd_run_sync_steps", "adpsgd_metropolis_weights",
-    "adpsgd_get_event_count", "adpsgd_set_event_count", "adpsgd_verify_plan",
+    "adpsgd_get_event_count", "adpsgd_set_event_count", "adpsgd_verify_plan", "adpsgd_objective",
 ]
 
 
@@ -118,6 +118,7 @@ def lib():
         L.adpsgd_run_sync_steps.argtypes = [vp, P(SyncSchedule), vp]
         L.adpsgd_verify_plan.argtypes = [i32, i64, P(i32), P(i32), P(i32), i32, i32, P(i32), P(i32), P(i32), i32,
                                          P(i64), P(i32), P(i32), P(i64)]
+        L.adpsgd_objective.argtypes = [vp, vp, P(C.c_double)]
         L.adpsgd_get_event_count.argtypes = [vp, P(u64)]
         L.adpsgd_set_event_count.argtypes = [vp, u64]
         L.adpsgd_metropolis_weights.argtypes = [P(Graph), P(C.c_float), P(C.c_float)]
@@ -315,6 +316,12 @@ class Handle:
         res = np.empty(self.d, dtype=np.float32)
         _check(self._h, lib().adpsgd_get_mean_model(self._h, res.ctypes.data, 0))
         return res
+
+    def objective(self, x_ptr=None):
+        """f at a device vector (integer pointer), or at the mean model when x_ptr is None."""
+        out = C.c_double(0.0)
+        _check(self._h, lib().adpsgd_objective(self._h, x_ptr, C.byref(out)))
+        return out.value
 
     def consensus_distance(self):
         out = C.c_double(0.0)

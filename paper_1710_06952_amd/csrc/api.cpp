@@ -760,6 +760,41 @@ extern "C" int adpsgd_consensus_distance(adpsgd_t* h, double* out) {
     return ADPSGD_OK;
 }
 
+extern "C" int adpsgd_objective(adpsgd_t* h, const float* x, double* out) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (!out) return fail(h, ADPSGD_ERR_ARG, "objective: out is NULL");
+    if (h->o.model != ADPSGD_MODEL_LSQ && h->o.model != ADPSGD_MODEL_LOGREG)
+        return fail(h, ADPSGD_ERR_STATE, "objective: defined for the least-squares and logistic models");
+    if (x && !aligned16(x)) return fail(h, ADPSGD_ERR_ARG, "objective: x is not 16-byte aligned");
+    std::vector<ObjectiveWorker> tab(h->n);
+    int64_t max_rows = 0;
+    for (int32_t i = 0; i < h->n; ++i) {
+        if (!h->data[i].features) return fail(h, ADPSGD_ERR_STATE, "objective: no data loaded for worker " + std::to_string(i));
+        tab[i] = {h->data[i].features, h->data[i].targets, h->data[i].rows, h->data[i].ld};
+        max_rows = std::max(max_rows, h->data[i].rows);
+    }
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    // diag buffer: [mean model d floats, 256-byte padded][worker table][partials][result]
+    const int64_t groups = objective_row_groups(max_rows);
+    const size_t off_tab = (static_cast<size_t>(h->d) * 4 + 255) & ~size_t(255);
+    const size_t off_part = (off_tab + tab.size() * sizeof(ObjectiveWorker) + 255) & ~size_t(255);
+    const size_t off_res = off_part + static_cast<size_t>(groups) * h->n * sizeof(double);
+    HIP_TRY(h, h->diag.reserve(off_res + sizeof(double)));
+    char* base = static_cast<char*>(h->diag.p);
+    const float* point = x;
+    if (!x) {
+        HIP_TRY(h, launch_mean_model(h->o.X, h->o.ldx, h->d, h->n, reinterpret_cast<float*>(base), h->stream));
+        point = reinterpret_cast<const float*>(base);
+    }
+    HIP_TRY(h, hipMemcpyAsync(base + off_tab, tab.data(), tab.size() * sizeof(ObjectiveWorker), hipMemcpyHostToDevice, h->stream));
+    HIP_TRY(h, launch_objective(h->o.model, point, h->d, h->n, reinterpret_cast<const ObjectiveWorker*>(base + off_tab), max_rows,
+                                h->o.lambda, reinterpret_cast<double*>(base + off_part), reinterpret_cast<double*>(base + off_res),
+                                h->stream));
+    HIP_TRY(h, hipMemcpyAsync(out, base + off_res, sizeof(double), hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    return ADPSGD_OK;
+}
+
 extern "C" int adpsgd_get_stats(adpsgd_t* h, adpsgd_stats_t* out) {
     if (!h) return ADPSGD_ERR_ARG;
     if (!out) return fail(h, ADPSGD_ERR_ARG, "get_stats: out is NULL");

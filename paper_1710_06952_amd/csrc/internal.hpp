@@ -173,6 +173,16 @@ hipError_t launch_mean_model(const float* X, int64_t ld, int64_t d, int32_t n, f
 int32_t consensus_blocks(int64_t d);
 hipError_t launch_consensus(const float* X, int64_t ld, int64_t d, int32_t n, double* partial,
                             double* result, hipStream_t st);
+// one worker's local data as the objective kernel sees it
+struct ObjectiveWorker {
+    const void* features;
+    const void* targets;
+    int64_t rows;
+    int64_t ld;
+};
+int64_t objective_row_groups(int64_t max_rows);
+hipError_t launch_objective(int model, const float* x, int64_t d, int32_t n, const ObjectiveWorker* workers, int64_t max_rows,
+                            float lambda, double* partial, double* result, hipStream_t st);
 hipError_t launch_synth_gradient(uint64_t seed, uint64_t k, float std, int64_t d, float* out, hipStream_t st);
 
 }  // namespace adpsgd_impl

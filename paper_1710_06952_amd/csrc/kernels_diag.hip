@@ -106,7 +106,87 @@ __global__ __launch_bounds__(kThreads) void consensus_final_kernel(const double*
     if (threadIdx.x == 0) *result = ((red[0] + red[1]) + (red[2] + red[3])) / n;
 }
 
+// ---- the objective at one point x: f(x) = (1/n) sum_i mean over worker i's rows of F(x; row) ----
+// (the problem statement of Sec. 3.1 with uniform p; F as in the gradient kernels, so the logistic
+// loss carries lambda |x|^2 / 2).  grid = (row groups, n): a wavefront takes one local row at a time,
+// lanes stride over d with four float4 loads in flight, the dot product is reduced with shuffles
+// and the loss terms are accumulated in fp64; one partial per block, summed in order by a second
+// single-block launch that also adds the regulariser.
+constexpr int kObjRowsPerBlock = 16;     // 4 per wavefront
+
+__global__ __launch_bounds__(kThreads) void objective_partial_kernel(int model, const float* __restrict__ x, int64_t d,
+                                                                    const ObjectiveWorker* __restrict__ workers, double* partial) {
+    __shared__ double red[kWaves];
+    const ObjectiveWorker w = workers[blockIdx.y];
+    const float* __restrict__ A = static_cast<const float*>(w.features);
+    const float* __restrict__ tg = static_cast<const float*>(w.targets);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t n_vec = d >> 2;            // full float4 groups; the ragged tail is handled separately
+    double acc = 0.0;
+    for (int r = 0; r < kObjRowsPerBlock / kWaves; ++r) {
+        const int64_t row = static_cast<int64_t>(blockIdx.x) * kObjRowsPerBlock + wave * (kObjRowsPerBlock / kWaves) + r;
+        if (row >= w.rows) break;            // uniform over the wavefront
+        const float* __restrict__ a = A + row * w.ld;
+        float z = 0.0f;
+        for (int64_t v0 = lane; v0 < n_vec; v0 += 64 * 4) {
+            v4f av[4], xv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t v = v0 + 64 * u;
+                av[u] = v < n_vec ? *reinterpret_cast<const v4f*>(a + 4 * v) : v4f{0, 0, 0, 0};
+                xv[u] = v < n_vec ? *reinterpret_cast<const v4f*>(x + 4 * v) : v4f{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) z += av[u].x * xv[u].x + av[u].y * xv[u].y + av[u].z * xv[u].z + av[u].w * xv[u].w;
+        }
+        for (int64_t e = 4 * n_vec + lane; e < d; e += 64) z += a[e] * x[e];
+        z = wave_sum(z);
+        if (lane == 0) {
+            const float t = tg[row];
+            if (model == ADPSGD_MODEL_LSQ) {
+                const double res = static_cast<double>(z) - t;
+                acc += 0.5 * res * res;
+            } else {
+                const double s = -static_cast<double>(t) * z;
+                acc += s > 0.0 ? s + log1p(exp(-s)) : log1p(exp(s));
+            }
+        }
+    }
+    if (lane == 0) red[wave] = acc / static_cast<double>(w.rows);
+    __syncthreads();
+    if (threadIdx.x == 0) partial[static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ __launch_bounds__(kThreads) void objective_final_kernel(const double* partial, int64_t count, int32_t n, const float* x,
+                                                                  int64_t d, double half_lambda, double* result) {
+    __shared__ double red[kWaves], red2[kWaves];
+    double acc = 0.0, sq = 0.0;
+    for (int64_t b = threadIdx.x; b < count; b += kThreads) acc += partial[b];
+    if (half_lambda != 0.0)
+        for (int64_t e = threadIdx.x; e < d; e += kThreads) sq += static_cast<double>(x[e]) * x[e];
+    acc = wave_sum(acc);
+    sq = wave_sum(sq);
+    if ((threadIdx.x & 63) == 0) { red[threadIdx.x >> 6] = acc; red2[threadIdx.x >> 6] = sq; }
+    __syncthreads();
+    if (threadIdx.x == 0)
+        *result = ((red[0] + red[1]) + (red[2] + red[3])) / n + half_lambda * ((red2[0] + red2[1]) + (red2[2] + red2[3]));
+}
+
 }  // namespace
+
+int64_t objective_row_groups(int64_t max_rows) { return (max_rows + kObjRowsPerBlock - 1) / kObjRowsPerBlock; }
+
+hipError_t launch_objective(int model, const float* x, int64_t d, int32_t n, const ObjectiveWorker* workers, int64_t max_rows,
+                            float lambda, double* partial, double* result, hipStream_t st) {
+    const int64_t groups = objective_row_groups(max_rows);
+    if (groups < 1 || groups > 0x7FFFFFFF || n > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(objective_partial_kernel, dim3(static_cast<uint32_t>(groups), n), dim3(kThreads), 0, st, model, x, d, workers, partial);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(objective_final_kernel, dim3(1), dim3(kThreads), 0, st, partial, groups * n, n, x, d,
+                       model == ADPSGD_MODEL_LOGREG ? 0.5 * static_cast<double>(lambda) : 0.0, result);
+    return hipGetLastError();
+}
 
 hipError_t launch_broadcast_rows(float* X, int64_t ld, int64_t d, int32_t n, const float* x0, hipStream_t st) {
     const int64_t blocks = (ld / 4 + kThreads - 1) / kThreads;

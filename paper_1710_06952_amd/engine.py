@@ -117,6 +117,13 @@ class Engine:
     def consensus_distance(self):
         return self.h.consensus_distance()
 
+    def objective(self, x=None):
+        """The objective over all local data at x (numpy vector or None = the mean model)."""
+        if x is None:
+            return self.h.objective(None)
+        xt = self.torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(self.device)
+        return self.h.objective(xt.data_ptr())
+
     def get_stats(self):
         return self.h.get_stats()
 

@@ -17,7 +17,8 @@ slowdown), and the time axis is simulated:
                maximum of the n clocks.
 
 Both schedules are executed by the HIP library (adpsgd_run_events / adpsgd_run_sync_steps); this file
-only builds schedules, keeps the simulated clock and evaluates the objective at the mean model.
+only builds schedules and keeps the simulated clock; the objective at the mean model comes from the
+library too (adpsgd_objective).
 
     python -m paper_1710_06952_amd.studies.heterogeneity [--n 16] [--d 4096] [--epochs 40]
 """
@@ -149,7 +150,7 @@ def run_study(n=16, d=4096, rows=1024, M=8, epochs=40, slowdowns=(1, 2, 10, 100)
         eng.set_models(np.zeros(d, np.float32))
         eng.run_events(sched, want_loss=True)
         loss_a = smooth(eng.get_loss(), 4 * n)
-        f_a = objective(eng.get_mean_model(), feats, targs)
+        f_a = eng.objective()                        # at the mean model, over all data, on the GPU
         eng.close()
         # ---- synchronous iterations (all workers step together, mixing with both ring neighbours)
         when_s = sync_clock(S, mean_time, seed, exponential, **link_kw)
@@ -159,7 +160,7 @@ def run_study(n=16, d=4096, rows=1024, M=8, epochs=40, slowdowns=(1, 2, 10, 100)
         eng.set_models(np.zeros(d, np.float32))
         eng.run_sync_steps(S, batch, want_loss=True)
         loss_s = smooth(eng.get_loss().reshape(S, n).mean(1), 4)
-        f_s = objective(eng.get_mean_model(), feats, targs)
+        f_s = eng.objective()
         eng.close()
         rows_out.append({
             "slowdown": slowdown,

@@ -845,3 +845,41 @@ def test_checkpoint_and_resume_continue_bit_for_bit(P):
     assert not np.array_equal(e3.get_models(), X_end)
     e2.close()
     e3.close()
+
+
+@pytest.mark.parametrize("model,n,d,lam", [("lsq", 5, 1030, 0.0), ("logreg", 4, 77, 1e-2), ("logreg", 3, 8192, 1e-4), ("lsq", 2, 3, 0.0)])
+def test_objective_over_all_local_data(P, model, n, d, lam):
+    """f(x) = (1/n) sum_i mean over worker i's rows of F(x; row), workers with different numbers of rows,
+    at a given point and at the mean model, against the oracle's loss over the full local data."""
+    _say("objective %s n=%d d=%d" % (model, n, d))
+    g = ring_graph(n)
+    data = lsq_data if model == "lsq" else logreg_data
+    feats, targs, _ = data(n, 40, d, seed=31)
+    rows = [40 - 7 * i for i in range(n)]
+    feats = [np.ascontiguousarray(f[:r]) for f, r in zip(feats, rows)]
+    targs = [np.ascontiguousarray(t[:r]) for t, r in zip(targs, rows)]
+    omodel = oracle.MODEL_LSQ if model == "lsq" else oracle.MODEL_LOGREG
+    eng = P.Engine(g, d, model, M=2, gamma=0.1, lam=lam)
+    eng.load_data(feats, targs)
+    X0 = (0.3 * np.random.default_rng(5).standard_normal((n, d))).astype(np.float32)
+    eng.set_models(X0, broadcast=False)
+
+    def f_ref(x):
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        return float(np.mean([oracle.minibatch_gradient(omodel, x, feats[i], targs[i], np.arange(rows[i]), 1.0 / rows[i], lam=lam)[1]
+                              for i in range(n)]))
+
+    xq = np.random.default_rng(6).standard_normal(d).astype(np.float32)
+    assert np.isclose(eng.objective(xq), f_ref(xq), rtol=1e-5)
+    mean32 = eng.get_mean_model()
+    assert np.isclose(eng.objective(), f_ref(mean32), rtol=1e-5)
+    assert abs(eng.objective(xq) - eng.objective()) > 1e-3          # the two points differ
+    eng.close()
+
+
+def test_objective_is_refused_without_a_data_model(P):
+    eng = P.Engine(ring_graph(4), 64, "synth", gamma=0.1, synth_std=0.1)
+    with pytest.raises(P.AdpsgdError) as ei:
+        eng.objective()
+    assert ei.value.code == -4
+    eng.close()

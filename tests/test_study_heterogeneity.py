@@ -78,6 +78,14 @@ def test_study_runs_end_to_end_on_a_tiny_problem():
     assert slow["adpsgd_speedup"] > 2.5 > 1.0 > slow["sync_speedup"]
     assert slow["adpsgd_time_to_target"] < slow["sync_time_to_target"]
     assert "slowdown" in H.format_table(res)
+    # the library's objective agrees with the plain numpy evaluation of the same problem
+    feats, targs = H.make_problem(4, 256, 64, 0)
+    eng = P.Engine(H.ring(4), 256, "lsq", M=4, gamma=0.1)
+    eng.load_data(feats, targs)
+    eng.set_models(np.zeros(256, np.float32))
+    assert np.isclose(eng.objective(), H.objective(np.zeros(256), feats, targs), rtol=1e-5)
+    assert np.isclose(eng.objective(), res["initial_objective"], rtol=1e-5)
+    eng.close()
     link = H.run_study(n=4, d=256, rows=64, M=4, epochs=6, slowdowns=(1, 50), seed=0, target=0.1, slow="link")
     a, b = link["results"]
     assert b["sync_speedup"] < 0.2 * a["sync_speedup"]          # every synchronous iteration waits for the link
