@@ -259,6 +259,14 @@ def main():
     out["diagnostics"] = {"consensus_distance": cd, "consensus_ms": (t1 - t0) * 1e3, "consensus_GBs": xbytes / (t1 - t0) / 1e9,
                           "mean_model_ms": (t2 - t1) * 1e3, "mean_model_GBs": xbytes / (t2 - t1) / 1e9}
     del mean_dev
+    if cfg["model"] in ("lsq", "logreg"):       # the objective reads every local row once
+        eng.objective()
+        t3 = time.perf_counter()
+        fval = eng.objective()
+        t4 = time.perf_counter()
+        dbytes = 4.0 * n * cfg["rows"] * d
+        out["diagnostics"].update({"objective_at_mean_model": fval, "objective_ms": (t4 - t3) * 1e3,
+                                   "objective_GBs": dbytes / (t4 - t3) / 1e9})
     if cpu_events > 0:
         if synth:
             eng.close()
