@@ -249,6 +249,11 @@ int adpsgd_consensus_distance(adpsgd_t* h, double* out);
  * data).  Synchronous; reads every local row once. */
 int adpsgd_objective(adpsgd_t* h, const float* x, double* out);
 
+/* Divergence check: the number of entries of the models that are NaN or infinite (0 for a healthy
+ * run; a step size beyond the stability limit shows up here long before anything else fails).
+ * *out is host memory.  Synchronous; reads X once. */
+int adpsgd_count_nonfinite(adpsgd_t* h, int64_t* out);
+
 /* Copy the n x d momentum buffers (only when opts.V was given). Synchronises the stream. */
 int adpsgd_get_momentum(adpsgd_t* h, float* out, int64_t ld_out, int32_t on_device);
 

@@ -22,7 +22,7 @@ EXPORTS = [
     "adpsgd_run_events", "adpsgd_get_models", "adpsgd_get_mean_model", "adpsgd_consensus_distance",
     "adpsgd_get_bf16_models", "adpsgd_get_momentum", "adpsgd_get_stats", "adpsgd_make_schedule", "adpsgd_plan_rounds",
     "adpsgd_synth_gradient", "adpsgd_run_sync_steps", "adpsgd_metropolis_weights",
-    "adpsgd_get_event_count", "adpsgd_set_event_count", "adpsgd_verify_plan", "adpsgd_objective",
+    "adpsgd_get_event_count", "adpsgd_set_event_count", "adpsgd_verify_plan", "adpsgd_objective", "adpsgd_count_nonfinite",
 ]
 
 
@@ -119,6 +119,7 @@ def lib():
         L.adpsgd_verify_plan.argtypes = [i32, i64, P(i32), P(i32), P(i32), i32, i32, P(i32), P(i32), P(i32), i32,
                                          P(i64), P(i32), P(i32), P(i64)]
         L.adpsgd_objective.argtypes = [vp, vp, P(C.c_double)]
+        L.adpsgd_count_nonfinite.argtypes = [vp, P(i64)]
         L.adpsgd_get_event_count.argtypes = [vp, P(u64)]
         L.adpsgd_set_event_count.argtypes = [vp, u64]
         L.adpsgd_metropolis_weights.argtypes = [P(Graph), P(C.c_float), P(C.c_float)]
@@ -321,6 +322,11 @@ class Handle:
         """f at a device vector (integer pointer), or at the mean model when x_ptr is None."""
         out = C.c_double(0.0)
         _check(self._h, lib().adpsgd_objective(self._h, x_ptr, C.byref(out)))
+        return out.value
+
+    def count_nonfinite(self):
+        out = C.c_int64(0)
+        _check(self._h, lib().adpsgd_count_nonfinite(self._h, C.byref(out)))
         return out.value
 
     def consensus_distance(self):

@@ -760,6 +760,22 @@ extern "C" int adpsgd_consensus_distance(adpsgd_t* h, double* out) {
     return ADPSGD_OK;
 }
 
+extern "C" int adpsgd_count_nonfinite(adpsgd_t* h, int64_t* out) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (!out) return fail(h, ADPSGD_ERR_ARG, "count_nonfinite: out is NULL");
+    const int32_t blocks = 2048;
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    HIP_TRY(h, h->diag.reserve(static_cast<size_t>(blocks) * sizeof(unsigned long long)));
+    HIP_TRY(h, launch_count_nonfinite(h->o.X, h->o.ldx, h->d, h->n, static_cast<unsigned long long*>(h->diag.p), blocks, h->stream));
+    std::vector<unsigned long long> part(blocks);
+    HIP_TRY(h, hipMemcpyAsync(part.data(), h->diag.p, part.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    unsigned long long total = 0;
+    for (unsigned long long v : part) total += v;
+    *out = static_cast<int64_t>(total);
+    return ADPSGD_OK;
+}
+
 extern "C" int adpsgd_objective(adpsgd_t* h, const float* x, double* out) {
     if (!h) return ADPSGD_ERR_ARG;
     if (!out) return fail(h, ADPSGD_ERR_ARG, "objective: out is NULL");

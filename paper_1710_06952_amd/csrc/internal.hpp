@@ -173,6 +173,8 @@ hipError_t launch_mean_model(const float* X, int64_t ld, int64_t d, int32_t n, f
 int32_t consensus_blocks(int64_t d);
 hipError_t launch_consensus(const float* X, int64_t ld, int64_t d, int32_t n, double* partial,
                             double* result, hipStream_t st);
+hipError_t launch_count_nonfinite(const float* X, int64_t ld, int64_t d, int32_t n, unsigned long long* partial,
+                                  int32_t blocks, hipStream_t st);
 // one worker's local data as the objective kernel sees it
 struct ObjectiveWorker {
     const void* features;

@@ -106,6 +106,28 @@ __global__ __launch_bounds__(kThreads) void consensus_final_kernel(const double*
     if (threadIdx.x == 0) *result = ((red[0] + red[1]) + (red[2] + red[3])) / n;
 }
 
+// ---- divergence check: number of entries of X that are NaN or infinite -----------------------
+// grid-stride over float4 pieces of all rows; one count per block, summed by the host.
+__global__ __launch_bounds__(kThreads) void count_nonfinite_kernel(const float* X, int64_t ld, int64_t d, int32_t n,
+                                                                  unsigned long long* partial) {
+    __shared__ unsigned long long red[kWaves];
+    const int64_t n_vec = (d + 3) / 4, total = n_vec * n;
+    unsigned long long bad = 0;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; t < total;
+         t += static_cast<int64_t>(gridDim.x) * kThreads) {
+        const int64_t row = t / n_vec, v = t % n_vec;
+        const v4f x = *reinterpret_cast<const v4f*>(X + row * ld + 4 * v);     // the padding beyond d is zero
+        bad += !isfinite(x.x);
+        bad += !isfinite(x.y);
+        bad += !isfinite(x.z);
+        bad += !isfinite(x.w);
+    }
+    for (int off = 32; off > 0; off >>= 1) bad += __shfl_xor(bad, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = bad;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+}
+
 // ---- the objective at one point x: f(x) = (1/n) sum_i mean over worker i's rows of F(x; row) ----
 // (the problem statement of Sec. 3.1 with uniform p; F as in the gradient kernels, so the logistic
 // loss carries lambda |x|^2 / 2).  grid = (row groups, n): a wavefront takes one local row at a time,
@@ -174,6 +196,12 @@ __global__ __launch_bounds__(kThreads) void objective_final_kernel(const double*
 }
 
 }  // namespace
+
+hipError_t launch_count_nonfinite(const float* X, int64_t ld, int64_t d, int32_t n, unsigned long long* partial,
+                                  int32_t blocks, hipStream_t st) {
+    hipLaunchKernelGGL(count_nonfinite_kernel, dim3(blocks), dim3(kThreads), 0, st, X, ld, d, n, partial);
+    return hipGetLastError();
+}
 
 int objective_rows_per_wave(int64_t max_rows) { return max_rows >= 4096 ? 4 : 1; }
 int64_t objective_row_groups(int64_t max_rows) {

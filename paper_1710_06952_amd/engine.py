@@ -124,6 +124,9 @@ class Engine:
         xt = self.torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(self.device)
         return self.h.objective(xt.data_ptr())
 
+    def count_nonfinite(self):
+        return self.h.count_nonfinite()
+
     def get_stats(self):
         return self.h.get_stats()
 

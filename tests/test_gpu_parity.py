@@ -883,3 +883,30 @@ def test_objective_is_refused_without_a_data_model(P):
         eng.objective()
     assert ei.value.code == -4
     eng.close()
+
+
+def test_divergence_check_counts_nonfinite_entries(P):
+    """A step size beyond the stability limit blows the least-squares run up; the check reports it."""
+    n, d, rows, M = 4, 1030, 16, 4
+    g = ring_graph(n)
+    feats, targs, _ = lsq_data(n, rows, d, seed=2)            # rows of norm ~ sqrt(d)
+    sched = oracle.make_schedule(g, 400, seed=2, T_max=1, M=M, rows=[rows] * n)
+    eng = P.Engine(g, d, "lsq", M=M, gamma=1e-4, T_max=1)
+    eng.load_data(feats, targs)
+    eng.set_models(np.zeros(d, np.float32))
+    eng.run_events(sched)
+    assert eng.count_nonfinite() == 0
+    X = eng.get_models()
+    X[1, 5] = np.inf
+    X[3, 1029] = np.nan
+    X[2, 7] = -np.inf
+    eng.set_models(X, broadcast=False)
+    assert eng.count_nonfinite() == 3
+    eng.close()
+    eng = P.Engine(g, d, "lsq", M=M, gamma=5.0, T_max=1)      # far beyond 2 / |a|^2
+    eng.load_data(feats, targs)
+    eng.set_models(np.full(d, 0.1, np.float32))
+    eng.run_events(sched)
+    bad = eng.count_nonfinite()
+    assert bad > 0 and bad == int((~np.isfinite(eng.get_models())).sum())
+    eng.close()
