@@ -241,7 +241,7 @@ __global__ __launch_bounds__(kSmallT) void linear_small_kernel(const LinParams p
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float target = 0.0f;
-    if (threadIdx.x < p.M) target = tg[idx[threadIdx.x]];      // requested now, used after the dots
+    if (static_cast<int>(threadIdx.x) < p.M) target = tg[idx[threadIdx.x]];      // requested now, used after the dots
 
     v4f xh[U];
 #pragma unroll
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(kSmallT) void linear_small_kernel(const LinParams p
         }
     }
     __syncthreads();
-    if (threadIdx.x < p.M) {
+    if (static_cast<int>(threadIdx.x) < p.M) {
         const int m = threadIdx.x;
         const float z = z_s[m];
         float c_m, l_m;
