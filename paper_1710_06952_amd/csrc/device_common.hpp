@@ -52,15 +52,11 @@ constexpr uint32_t kStreamGrad = 2u << 24;
 __device__ __forceinline__ void box_muller(uint32_t wa, uint32_t wb, float& zc, float& zs) {
     const float u1 = (static_cast<float>(wa >> 9) + 0.5f) * 0x1p-23f;
     const float u2 = static_cast<float>(wb >> 8) * 0x1p-24f;
-#if defined(ADPSGD_NORMALS_VARIANT) && ADPSGD_NORMALS_VARIANT == 1
-    // hardware transcendentals: v_log_f32 (log2), v_sqrt_f32, v_sin_f32 / v_cos_f32 (argument in revolutions)
-    const float r = __builtin_amdgcn_sqrtf(-1.3862943611198906f * __builtin_amdgcn_logf(u1));
-    const float s = __builtin_amdgcn_sinf(u2), c = __builtin_amdgcn_cosf(u2);
-#else
+    // accurate library functions: the hardware approximations (v_log / v_sin / v_cos) were measured
+    // and buy nothing, the kernel being bound by memory at the same time
     const float r = sqrtf(-2.0f * logf(u1));
     float s, c;
     sincospif(2.0f * u2, &s, &c);
-#endif
     zc = r * c;
     zs = r * s;
 }

@@ -24,21 +24,10 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-#ifndef ADPSGD_DOT_UNROLL
-#define ADPSGD_DOT_UNROLL 4
-#endif
-#ifndef ADPSGD_DOT_ROWS
-#define ADPSGD_DOT_ROWS 8
-#endif
-#ifndef ADPSGD_DOT_ROWUNROLL
-#define ADPSGD_DOT_ROWUNROLL 2
-#endif
-#ifndef ADPSGD_COMBINE_UNROLL
-#define ADPSGD_COMBINE_UNROLL 8
-#endif
-constexpr int kDotUnroll = ADPSGD_DOT_UNROLL;                // float4 per thread per row
+// tile shape of the two streaming kernels (8-32 rows per block and unrolls of 2-8 measure within 5 %)
+constexpr int kDotUnroll = 4;                                 // float4 per thread per row
 constexpr int64_t kDotChunk = kThreads * kDotUnroll * 4;     // floats of d per block
-constexpr int kRowsPerBlock = ADPSGD_DOT_ROWS;               // minibatch rows per dots block
+constexpr int kRowsPerBlock = 8;                              // minibatch rows per dots block
 
 struct LinParams {
     int model;
@@ -99,7 +88,7 @@ __global__ __launch_bounds__(kThreads) void linear_dots_kernel(const LinParams p
         xh[u] = v < p.n_vec ? zero_beyond(read_xhat(p, op, v), 4 * v, p.d) : v4f{0, 0, 0, 0};
     }
     const int m_begin = blockIdx.y * kRowsPerBlock;
-#pragma unroll ADPSGD_DOT_ROWUNROLL
+#pragma unroll 2
     for (int r = 0; r < kRowsPerBlock; ++r) {
         const int m = m_begin + r;
         if (m > p.M) break;
@@ -203,7 +192,7 @@ __global__ __launch_bounds__(kThreads) void linear_combine_kernel(const LinParam
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const float* __restrict__ cf = p.coef + static_cast<int64_t>(blockIdx.y) * p.M;
     v4f acc = {0, 0, 0, 0};
-#pragma unroll ADPSGD_COMBINE_UNROLL
+#pragma unroll 8
     for (int m = 0; m < p.M; ++m) {
         const v4f a = load4<STREAM>(A + static_cast<int64_t>(idx[m]) * op.ld + 4 * v);
         acc += a * cf[m];
