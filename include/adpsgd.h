@@ -245,8 +245,9 @@ int adpsgd_consensus_distance(adpsgd_t* h, double* out);
  *     f(x) = (1/n) sum_i (1/rows_i) sum_{rows of worker i} F(x; row)
  * over ALL local data, F as in ADPSGD_MODEL_* (the logistic loss includes lambda |x|^2 / 2).
  * x: device, d floats, or NULL for the mean of the workers' models (Algorithm 1's output).
- * *out is host memory.  LSQ and LOGREG only (ADPSGD_ERR_STATE otherwise, or when a worker has no
- * data).  Synchronous; reads every local row once. */
+ * *out is host memory.  Every data model (the MLP evaluates at the bf16 rounding of x, as its gradient
+ * does); ADPSGD_ERR_STATE for SYNTH or when a worker has no data.  Synchronous; reads every local
+ * row once. */
 int adpsgd_objective(adpsgd_t* h, const float* x, double* out);
 
 /* Divergence check: the number of entries of the models that are NaN or infinite (0 for a healthy

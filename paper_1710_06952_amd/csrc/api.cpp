@@ -437,7 +437,7 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
                 const int64_t kp = plan.prev[k];
                 g.comp_slot = kp >= 0 ? plan.slot[kp] : -1;
                 g.comp_gamma = kp >= 0 ? (s->gamma ? s->gamma[kp] : h->o.gamma) : 0.0f;
-                g.pad = 0;
+                g.count = 0;
                 const WorkerData& w = h->data[g.worker];
                 g.features = w.features;
                 g.targets = w.targets;
@@ -776,12 +776,79 @@ extern "C" int adpsgd_count_nonfinite(adpsgd_t* h, int64_t* out) {
     return ADPSGD_OK;
 }
 
+namespace {
+
+// The perceptron's objective: forward pass and cross-entropy over all local samples, in chunks of
+// M samples (the last chunk of a worker is padded with its last sample and counts only its own).
+int mlp_objective(adpsgd_t* h, const float* x, double* out) {
+    const int32_t n = h->n, M = h->o.M;
+    std::vector<int64_t> first(n + 1, 0);          // first operation of every worker
+    for (int32_t i = 0; i < n; ++i) {
+        if (!h->data[i].features) return fail(h, ADPSGD_ERR_STATE, "objective: no data loaded for worker " + std::to_string(i));
+        first[i + 1] = first[i] + (h->data[i].rows + M - 1) / M;
+    }
+    const int64_t n_ops = first[n];
+    if (n_ops > 0x7FFFFFF0) return fail(h, ADPSGD_ERR_ARG, "objective: too many samples");
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    const int32_t group = static_cast<int32_t>(std::min<int64_t>(n_ops, 64));
+    HIP_TRY(h, h->grad_scratch.reserve(mlp_scratch_bytes(group, M, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out)));
+    // diag buffer: [point fp32 ld][point bf16 ld][GradOp x n_ops][batch_idx n_ops x M][loss sums]
+    const size_t ld = static_cast<size_t>(h->o.ldx);
+    const size_t off_b16 = (ld * 4 + 255) & ~size_t(255);
+    const size_t off_ops = (off_b16 + ld * 2 + 255) & ~size_t(255);
+    const size_t off_idx = (off_ops + static_cast<size_t>(n_ops) * sizeof(GradOp) + 255) & ~size_t(255);
+    const size_t off_sum = (off_idx + static_cast<size_t>(n_ops) * M * 4 + 255) & ~size_t(255);
+    HIP_TRY(h, h->diag.reserve(off_sum + static_cast<size_t>(n_ops) * sizeof(double)));
+    char* base = static_cast<char*>(h->diag.p);
+    float* point = reinterpret_cast<float*>(base);
+    uint16_t* point_b16 = reinterpret_cast<uint16_t*>(base + off_b16);
+    HIP_TRY(h, hipMemsetAsync(point, 0, ld * 4, h->stream));
+    if (x) HIP_TRY(h, hipMemcpyAsync(point, x, static_cast<size_t>(h->d) * 4, hipMemcpyDeviceToDevice, h->stream));
+    else HIP_TRY(h, launch_mean_model(h->o.X, h->o.ldx, h->d, n, point, h->stream));
+    HIP_TRY(h, launch_refresh_bf16(point, point_b16, h->o.ldx, 1, h->stream));
+    std::vector<GradOp> ops(static_cast<size_t>(n_ops));
+    std::vector<int32_t> idx(static_cast<size_t>(n_ops) * M);
+    for (int32_t i = 0; i < n; ++i)
+        for (int64_t c = 0; c < first[i + 1] - first[i]; ++c) {
+            const int64_t o = first[i] + c, r0 = c * M;
+            const int64_t have = std::min<int64_t>(M, h->data[i].rows - r0);
+            ops[o] = GradOp{i, 0, static_cast<int32_t>(o), -1, 0.0f, static_cast<int32_t>(have),
+                            h->data[i].features, h->data[i].targets, h->data[i].ld, point_b16};
+            for (int32_t m = 0; m < M; ++m) idx[o * M + m] = static_cast<int32_t>(r0 + std::min<int64_t>(m, have - 1));
+        }
+    HIP_TRY(h, hipMemcpyAsync(base + off_ops, ops.data(), ops.size() * sizeof(GradOp), hipMemcpyHostToDevice, h->stream));
+    HIP_TRY(h, hipMemcpyAsync(base + off_idx, idx.data(), idx.size() * 4, hipMemcpyHostToDevice, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));      // the host vectors may go out of scope after this point
+    double* d_sum = reinterpret_cast<double*>(base + off_sum);
+    for (int64_t g0 = 0; g0 < n_ops; g0 += group) {
+        const int32_t cnt = static_cast<int32_t>(std::min<int64_t>(group, n_ops - g0));
+        MlpGradArgs a{nullptr, point_b16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out,
+                      reinterpret_cast<const GradOp*>(base + off_ops) + g0, cnt, M,
+                      reinterpret_cast<const int32_t*>(base + off_idx), nullptr, 1.0f, nullptr, h->grad_scratch.p, false, false};
+        HIP_TRY(h, launch_mlp_loss(a, d_sum + g0, h->stream));
+    }
+    std::vector<double> sums(static_cast<size_t>(n_ops));
+    HIP_TRY(h, hipMemcpyAsync(sums.data(), d_sum, sums.size() * sizeof(double), hipMemcpyDeviceToHost, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    double total = 0.0;
+    for (int32_t i = 0; i < n; ++i) {
+        double s = 0.0;
+        for (int64_t o = first[i]; o < first[i + 1]; ++o) s += sums[o];
+        total += s / static_cast<double>(h->data[i].rows);
+    }
+    *out = total / n;
+    return ADPSGD_OK;
+}
+
+}  // namespace
+
 extern "C" int adpsgd_objective(adpsgd_t* h, const float* x, double* out) {
     if (!h) return ADPSGD_ERR_ARG;
     if (!out) return fail(h, ADPSGD_ERR_ARG, "objective: out is NULL");
-    if (h->o.model != ADPSGD_MODEL_LSQ && h->o.model != ADPSGD_MODEL_LOGREG)
-        return fail(h, ADPSGD_ERR_STATE, "objective: defined for the least-squares and logistic models");
+    if (h->o.model == ADPSGD_MODEL_SYNTH)
+        return fail(h, ADPSGD_ERR_STATE, "objective: the synthetic-gradient model has no objective");
     if (x && !aligned16(x)) return fail(h, ADPSGD_ERR_ARG, "objective: x is not 16-byte aligned");
+    if (h->o.model == ADPSGD_MODEL_MLP) return mlp_objective(h, x, out);
     std::vector<ObjectiveWorker> tab(h->n);
     int64_t max_rows = 0;
     for (int32_t i = 0; i < h->n; ++i) {

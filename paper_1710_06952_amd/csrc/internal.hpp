@@ -32,7 +32,7 @@ struct GradOp {
     int32_t event;    // index into the call's batch_idx / loss arrays
     int32_t comp_slot;   // wait-free variant: slot of the worker's own pending gradient g_k', or -1
     float comp_gamma;    // its step size: the read is x^ = row - comp_gamma * g_k'
-    int32_t pad;
+    int32_t count;    // loss evaluation only: samples of the operation that count (the rest is padding)
     const void* features;   // the worker's local data (device), copied here so that a kernel reaches
     const void* targets;    //   it with one load instead of a second table look-up
     int64_t ld;             // leading dimension of features, in elements
@@ -128,6 +128,8 @@ struct MlpGradArgs {
     bool compensate;        // wait-free variant: first build the compensated bf16 rows the operations name
 };
 size_t mlp_scratch_bytes(int32_t n_ops, int32_t M, int32_t in, int32_t hid, int32_t out);
+// forward pass and cross-entropy only: loss_sum[op] = sum over the first `count` samples of the operation (fp64)
+hipError_t launch_mlp_loss(const MlpGradArgs& a, double* loss_sum, hipStream_t st);
 bool mlp_can_factor(int32_t in, int32_t hid, int32_t M);
 
 // The perceptron's model update with the first-layer gradient still in factored form

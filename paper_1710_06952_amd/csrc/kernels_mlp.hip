@@ -371,6 +371,49 @@ __global__ __launch_bounds__(kBwdT) void mlp_backward_small_kernel(const MlpPara
     }
 }
 
+// ---- 2b. loss only (evaluation of the objective): grid = n_ops, 1024 threads ------------------
+// Step a of the backward kernel without the rest: logits, softmax, cross-entropy of the first
+// `count` samples of each operation, summed in sample order in fp64.
+__global__ __launch_bounds__(kBwdT) void mlp_loss_kernel(const MlpParams p, double* loss_sum) {
+    __shared__ float loss_s[kMaxM];
+    const GradOp op = p.ops[blockIdx.x];
+    const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
+    const int sm = threadIdx.x >> 4, so = threadIdx.x & 15;
+    const uint16_t* __restrict__ W = op.xrow_bf16 ? static_cast<const uint16_t*>(op.xrow_bf16)
+                                                  : p.Xb + static_cast<int64_t>(op.worker) * p.ld;
+    const uint16_t* __restrict__ b2 = W + static_cast<int64_t>(p.in) * p.hid + p.hid + static_cast<int64_t>(p.hid) * p.out;
+    int label = -1;
+    if (sm < p.M) label = static_cast<const int32_t*>(op.targets)[idx[sm]];
+    const int tiles = p.hid / kFwdTileH;
+    const float* __restrict__ src = p.logit_part + (static_cast<int64_t>(blockIdx.x) * tiles * kMaxM + sm) * kMaxOut + so;
+    float z = 0.0f;
+    for (int t0 = 0; t0 < tiles; t0 += 32) {
+        float part[32];
+#pragma unroll
+        for (int t = 0; t < 32; ++t) part[t] = (t0 + t < tiles) ? src[static_cast<int64_t>(t0 + t) * kMaxM * kMaxOut] : 0.0f;
+#pragma unroll
+        for (int t = 0; t < 32; ++t) z += part[t];
+    }
+    const bool live = so < p.out;
+    const float logit = live ? z + bf16_to_float(b2[live ? so : 0]) : -INFINITY;
+    float zmax = logit;
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, off, 64));
+    float zsum = live ? expf(logit - zmax) : 0.0f;
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) zsum += __shfl_xor(zsum, off, 64);
+    const int lsrc = (threadIdx.x & 48) + (label >= 0 && label < p.out ? label : 0);
+    const float lsel = __shfl(logit, lsrc, 64);
+    if (so == 0) loss_s[sm] = -(lsel - zmax - logf(zsum));
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int count = op.count > 0 ? (op.count < p.M ? op.count : p.M) : p.M;
+        double s = 0.0;
+        for (int m = 0; m < count; ++m) s += loss_s[m];
+        loss_sum[blockIdx.x] = s;
+    }
+}
+
 // ---- 3. dW1 = Xb^T dH ------------------------------------------------------------------
 // One 64 (inputs) x 64 (hidden) tile of the product: the minibatch rows of the inputs and of dH
 // ([kMaxM][hid] bf16, rows >= M zero) are transposed through LDS, then wavefront w multiplies the
@@ -547,6 +590,34 @@ size_t mlp_scratch_bytes(int32_t n_ops, int32_t M, int32_t in, int32_t hid, int3
     const size_t act = align256(static_cast<size_t>(n_ops) * kMaxM * hid * sizeof(uint16_t));
     const size_t lp = align256(static_cast<size_t>(n_ops) * (hid / kFwdTileH) * kMaxM * kMaxOut * 4);
     return 2 * act + lp;
+}
+
+hipError_t launch_mlp_loss(const MlpGradArgs& a, double* loss_sum, hipStream_t st) {
+    if (a.n_ops <= 0) return hipSuccess;
+    if (mlp_scratch_bytes(a.n_ops, a.M, a.in, a.hid, a.out) == 0 || a.n_ops > 65535) return hipErrorInvalidValue;
+    MlpParams p{};
+    p.X = a.X;
+    p.Xb = a.Xbf16;
+    p.ld = a.ld;
+    p.in = a.in;
+    p.hid = a.hid;
+    p.out = a.out;
+    p.ops = a.ops;
+    p.M = a.M;
+    p.batch_idx = a.batch_idx;
+    p.slots = a.slots;
+    p.gscale = a.gscale;
+    p.loss = nullptr;
+    char* s = static_cast<char*>(a.scratch);
+    const size_t act = align256(static_cast<size_t>(a.n_ops) * kMaxM * a.hid * sizeof(uint16_t));
+    p.Hb = reinterpret_cast<uint16_t*>(s);
+    p.dHb = reinterpret_cast<uint16_t*>(s + act);
+    p.logit_part = reinterpret_cast<float*>(s + 2 * act);
+    hipLaunchKernelGGL(mlp_forward_kernel, dim3(a.hid / kFwdTileH, a.n_ops), dim3(kFwdT), 0, st, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(mlp_loss_kernel, dim3(a.n_ops), dim3(kBwdT), 0, st, p, loss_sum);
+    return hipGetLastError();
 }
 
 bool mlp_can_factor(int32_t in, int32_t hid, int32_t M) {

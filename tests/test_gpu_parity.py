@@ -910,3 +910,33 @@ def test_divergence_check_counts_nonfinite_entries(P):
     bad = eng.count_nonfinite()
     assert bad > 0 and bad == int((~np.isfinite(eng.get_models())).sum())
     eng.close()
+
+
+def test_objective_of_the_perceptron(P):
+    """Cross-entropy over all local samples (worker sizes that are not multiples of the minibatch) at a
+    given point and at the mean model, against the oracle's loss with the same bf16 roundings."""
+    from workloads import mixture_data, mlp_init
+    n, dims, M = 3, (24, 64, 5), 16
+    _say("objective mlp")
+    g = ring_graph(n)
+    d = dims[0] * dims[1] + dims[1] + dims[1] * dims[2] + dims[2]
+    feats, labels, _ = mixture_data(n, 90, din=dims[0], classes=dims[2], seed=8)
+    rows = [90, 37, 64]
+    feats = [np.ascontiguousarray(f[:r]) for f, r in zip(feats, rows)]
+    labels = [np.ascontiguousarray(t[:r]) for t, r in zip(labels, rows)]
+    eng = P.Engine(g, d, "mlp", M=M, gamma=0.05, mlp=dims)
+    eng.load_data(feats, labels)
+    rng = np.random.default_rng(3)
+    X0 = np.stack([mlp_init(*dims, seed=s) for s in range(n)]) + (0.05 * rng.standard_normal((n, d))).astype(np.float32)
+    eng.set_models(X0, broadcast=False)
+
+    def f_ref(x):
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        return float(np.mean([oracle.minibatch_gradient(oracle.MODEL_MLP, x, feats[i], labels[i], np.arange(rows[i]),
+                                                        1.0 / rows[i], mlp=dims)[1] for i in range(n)]))
+
+    xq = X0[1]
+    assert np.isclose(eng.objective(xq), f_ref(xq), rtol=2e-3)
+    assert np.isclose(eng.objective(), f_ref(eng.get_mean_model()), rtol=2e-3)
+    assert abs(eng.objective(xq) - eng.objective()) > 1e-3
+    eng.close()
