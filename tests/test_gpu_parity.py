@@ -940,3 +940,29 @@ def test_objective_of_the_perceptron(P):
     assert np.isclose(eng.objective(), f_ref(eng.get_mean_model()), rtol=2e-3)
     assert abs(eng.objective(xq) - eng.objective()) > 1e-3
     eng.close()
+
+
+def test_mlp_with_momentum_and_weight_decay(P):
+    """The perceptron with the experiments' optimizer: dense gradient path, bf16 shadow rewritten by the
+    momentum variant of the update kernel."""
+    from workloads import mixture_data, mlp_init, f32_to_bf16_bits
+    n, dims, rows, K, M, T = 6, (24, 64, 5), 40, 200, 16, 2
+    _say("mlp with momentum")
+    g = ring_graph(n)
+    d = dims[0] * dims[1] + dims[1] + dims[1] * dims[2] + dims[2]
+    feats, labels, _ = mixture_data(n, rows, din=dims[0], classes=dims[2], seed=21)
+    sched = oracle.make_schedule(g, K, seed=22, T_max=T, M=M, rows=[rows] * n)
+    x0 = mlp_init(*dims, seed=21)
+    eng = P.Engine(g, d, "mlp", M=M, gamma=0.02, T_max=T, mlp=dims, momentum=0.9, weight_decay=1e-4)
+    eng.load_data(feats, labels)
+    eng.set_models(x0)
+    eng.run_events(sched)
+    Xg, Vg = eng.get_models(), eng.get_momentum()
+    Xr = np.tile(x0, (n, 1))
+    V = np.zeros_like(Xr)
+    oracle.run_events(Xr, sched, oracle.MODEL_MLP, 0.02, M=M, gscale=1.0 / M, mlp=dims, features=feats, targets=labels,
+                      momentum=0.9, weight_decay=1e-4, V=V)
+    assert rel_err(Xg, Xr) <= MLP_TOL_MASTER
+    assert np.abs(Vg - V).max() <= MLP_TOL_MASTER * np.abs(V).max()
+    assert np.array_equal(eng.get_bf16_models(), f32_to_bf16_bits(Xg))
+    eng.close()
