@@ -290,7 +290,9 @@ def _run_mlp(P, n, dims, rows, K, M, T, gamma, seed, graph):
 @pytest.mark.parametrize("n,dims,rows,K,M,T,graph", [(5, (24, 64, 5), 40, 200, 16, 2, "reg4"),
                                                       (6, (40, 128, 10), 50, 300, 13, 4, "ring"),
                                                       (5, (8, 64, 16), 9, 60, 1, 0, "ring"),
-                                                      (7, (72, 192, 3), 70, 150, 64, 3, "reg4")])
+                                                      (7, (72, 192, 3), 70, 150, 64, 3, "reg4"),
+                                                      (1, (32, 64, 4), 30, 80, 8, 0, "ring"),
+                                                      (2, (48, 128, 6), 30, 120, 32, 2, "ring")])
 def test_mlp_small_shapes(P, n, dims, rows, K, M, T, graph):
     from workloads import bf16_bits_to_f32
     _say("mlp n=%d dims=%s K=%d M=%d" % (n, dims, K, M))
