@@ -10,11 +10,14 @@
 // before they enter those products.  The second layer (hid x out, out <= 16) is
 // small and stays on the vector ALUs in fp32.
 //
-// Three launches per group of gradient operations (forward; softmax with the
-// second-layer gradients and the hidden error; dW1); the kernels of a round form a
-// serial chain of small grids, so each one keeps all its global loads in flight
-// at once instead of looping over them.  Every reduction has a fixed order:
-// results do not depend on scheduling.
+// Launches per group of gradient operations: forward; softmax with the second-layer
+// gradients and the hidden error dH; and, only where a dense gradient is wanted
+// (momentum, the synchronous schedule, the wait-free variant), dW1.  By default dW1
+// is never written out: dH stays in the pending slot and the kernel that applies the
+// event (section 4 below) forms the rank-M product tile by tile while it updates the
+// model.  The kernels of a round form a serial chain of small grids, so each one
+// keeps all its global loads in flight at once instead of looping over them.  Every
+// reduction has a fixed order: results do not depend on scheduling.
 #include "device_common.hpp"
 #include "internal.hpp"
 
