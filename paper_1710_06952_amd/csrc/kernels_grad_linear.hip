@@ -13,9 +13,11 @@
 //   1. dots:     partial z[op][m][chunk] = A[idx_m, chunk] . x^[chunk]   (batched GEMV, HBM bound)
 //   2. finalize: z -> per-sample coefficient c_m and the minibatch loss
 //   3. combine:  g[chunk] = sum_m c_m A[idx_m, chunk] (+ reg * x^[chunk]) into the pending slot
-// The gathered rows are read twice; the group size is chosen by the host so
-// that the second read is served from the memory-side cache.  Partial sums are
-// combined in a fixed order: results do not depend on scheduling.
+// The gathered rows are read twice, both times from HBM (re-reading them from the
+// memory-side cache is no faster, and a one-pass variant needs a chip-wide
+// dependency that costs more than the second read).  Short models (d <= 2048)
+// take the single-block kernel at the end of this file instead.  Partial sums
+// are combined in a fixed order: results do not depend on scheduling.
 #include "device_common.hpp"
 #include "internal.hpp"
 
