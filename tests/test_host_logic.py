@@ -363,3 +363,20 @@ def test_plan_verifier_covers_extra_pairs_and_the_waitfree_dependency():
     assert P.adpsgd_verify_plan(n, w, j, tau, 8, r, u, s, R, prev=prev)
     r3, u3, s3, R3 = P.adpsgd_plan_rounds(n, w, j, tau, 8, True)           # planned without the dependency
     assert (prev >= 0).any() and not P.adpsgd_verify_plan(n, w, j, tau, 8, r3, u3, s3, R3, prev=prev)
+
+
+def test_the_abi_is_usable_from_plain_c(tmp_path):
+    """The header compiles as C11 with -Wall -Wextra -Werror, and a C program linked against the library runs
+    the host-only entry points (schedule generator, planner, plan check, Metropolis weights)."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    lib_dir = os.path.dirname(str(P.LIB_PATH))
+    exe = str(tmp_path / "host_only")
+    rocm_lib = "/opt/rocm/lib"
+    subprocess.check_call(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(root, "include"),
+                           os.path.join(root, "tests", "c_abi", "host_only.c"), "-o", exe, "-L", lib_dir, "-ladpsgd",
+                           "-Wl,-rpath," + lib_dir, "-Wl,-rpath," + rocm_lib])
+    env = dict(os.environ, LD_LIBRARY_PATH=rocm_lib + ":" + os.environ.get("LD_LIBRARY_PATH", ""))
+    out = subprocess.run([exe], env=env, capture_output=True, text=True, timeout=60)
+    assert out.returncode == 0, (out.returncode, out.stdout, out.stderr)
+    assert "c abi ok" in out.stdout
