@@ -968,3 +968,17 @@ def test_mlp_with_momentum_and_weight_decay(P):
     assert np.abs(Vg - V).max() <= MLP_TOL_MASTER * np.abs(V).max()
     assert np.array_equal(eng.get_bf16_models(), f32_to_bf16_bits(Xg))
     eng.close()
+
+
+def test_the_abi_drives_the_gpu_from_plain_c():
+    """tests/c_abi/gpu_gossip.c: device memory from the HIP runtime, the library's entry points, no Python in
+    between (the program is built by __graft_entry__.build(), like the libraries)."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi", "gpu_gossip")
+    if not os.path.exists(exe):          # one second of gcc, no GPU work
+        import __graft_entry__
+        exe = __graft_entry__.build_c_abi_program()
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=100)
+    assert out.returncode == 0, (out.returncode, out.stdout, out.stderr)
+    assert "c abi gpu ok" in out.stdout
