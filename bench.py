@@ -211,14 +211,18 @@ def main():
                 "kernel": "fused_gossip_apply_kernel<synth>", "avg_launch_ms": avg_launch_s * 1e3,
                 "events_per_launch": events_per_launch, "bytes_per_event": bytes_per_event}
     else:
-        # dominant kernels: the gradient launch set (the minibatch rows are the bulk of the traffic)
+        # the kernels of one event together: gradient launches + update (with a factored gradient the
+        # update kernel does part of the gradient's work, so the two are not separated here); bytes = the
+        # method's own traffic per event, minibatch rows counted once
         grad_rows_bytes = (M * cfg["mlp"][0] * 2.0 + 2.0 * d) if cfg["model"] == "mlp" else 4.0 * M * d
         per_grad_s = ps["grad_ms"] * 1e-3 / ps["events"]
-        achieved = grad_rows_bytes / per_grad_s / 1e9
+        per_update_s = ps["fused_ms"] * 1e-3 / ps["events"]
+        bytes_per_event = algorithmic_bytes_per_event(cfg)
+        achieved = bytes_per_event / (per_grad_s + per_update_s) / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                "kernel": "gradient launch set (per gradient)", "avg_gradient_us": per_grad_s * 1e6,
-                "fused_us_per_event": ps["fused_ms"] * 1e3 / ps["events"],
+                "kernel": "gradient + update kernels (per event)", "avg_gradient_us": per_grad_s * 1e6,
+                "fused_us_per_event": per_update_s * 1e6, "bytes_per_event": bytes_per_event,
                 "bytes_per_gradient": grad_rows_bytes, "events_per_launch": events_per_launch}
 
     out = {

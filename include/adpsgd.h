@@ -68,11 +68,12 @@ enum {
                                     launched (no two updates of a round share a row, every stale read sees exactly
                                     the updates before its logical time, slots live long enough); a violation is a
                                     library bug and returns ADPSGD_ERR_STATE.  O(K log K) host work per call */
-    ADPSGD_FLAG_DENSE_GRADIENT = 2  /* MLP: always write the first-layer gradient out as a dense matrix.
-                                       By default (no momentum) it stays in factored form, dH and the
-                                       minibatch inputs, until the update kernel multiplies the two; the
-                                       values are the same, the dense form costs one more launch and a
-                                       write and read-back of in x hidden floats per event */
+    ADPSGD_FLAG_DENSE_GRADIENT = 2  /* always write gradients out as dense vectors.  By default (no momentum, no
+                                       wait-free variant) low-rank gradients stay in factored form until the
+                                       update kernel applies them: the MLP's first layer as dH and the minibatch
+                                       inputs, least squares on long models as its M coefficients.  The values
+                                       are the same; the dense form costs one more launch and a write and
+                                       read-back of the gradient per event */
 };
 
 /* Undirected communication graph (V, E) of Sec. 3.1 as CSR adjacency lists.

@@ -361,6 +361,10 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
     const bool factored = h->o.model == ADPSGD_MODEL_MLP && !h->o.V && !(h->o.flags & ADPSGD_FLAG_DENSE_GRADIENT) &&
                           !mlp_comp && mlp_can_factor(h->o.mlp_in, h->o.mlp_hidden, M);
 
+    // least squares on long models: the gradient stays M coefficients until the update kernel applies it
+    const bool lin_factored = !h->o.V && !h->o.local_compensation && !(h->o.flags & ADPSGD_FLAG_DENSE_GRADIENT) &&
+                              with_grad && linear_can_factor(h->o.model, h->d, M, h->o.ldx);
+
     // ---- plan ----
     Plan plan;
     std::string perr;
@@ -420,8 +424,8 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
             u.slot = with_grad ? plan.slot[k] : 0;
             u.flags = 0;
             u.event = static_cast<int32_t>(k);
-            u.features = factored ? h->data[u.i].features : nullptr;
-            u.feat_ld = factored ? h->data[u.i].ld : 0;
+            u.features = (factored || lin_factored) ? h->data[u.i].features : nullptr;
+            u.feat_ld = (factored || lin_factored) ? h->data[u.i].ld : 0;
             if (s->extra_ptr) {
                 for (int64_t q = s->extra_ptr[k]; q < s->extra_ptr[k + 1]; ++q) {
                     PairOp& x = uops[u_fill[plan.u_round[k]]++];
@@ -494,7 +498,7 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
                 LinearGradArgs a{h->o.model, h->o.X, h->o.ldx, h->d, d_rops + g0, cnt, M, d_batch,
                                  slots, gscale, h->o.lambda,
                                  static_cast<float*>(h->grad_scratch.p),
-                                 reinterpret_cast<float*>(static_cast<char*>(h->grad_scratch.p) + off_coef), loss};
+                                 reinterpret_cast<float*>(static_cast<char*>(h->grad_scratch.p) + off_coef), loss, lin_factored};
                 HIP_TRY(h, launch_linear_gradient(a, h->stream, &launches));
             }
             h->stats.grad_launches += launches;
@@ -514,7 +518,11 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
             }
             bool has_solo = false;
             for (int64_t t = u_off[r]; t < u_off[r + 1] && !has_solo; ++t) has_solo = uops[t].i == uops[t].j;
-            if (factored) {
+            if (lin_factored) {
+                LinearApplyArgs a{h->o.X, h->o.ldx, h->d, d_uops + u_off[r], static_cast<int32_t>(nu), slots, d_batch, M,
+                                  h->streaming};
+                HIP_TRY(h, launch_linear_apply_factored(a, h->stream));
+            } else if (factored) {
                 MlpApplyArgs a{h->o.X, h->o.ldx, h->d, h->o.mlp_in, h->o.mlp_hidden, M, d_uops + u_off[r],
                                static_cast<int32_t>(nu), slots, h->o.Xbf16, d_batch};
                 HIP_TRY(h, launch_mlp_apply_factored(a, h->stream));
@@ -657,7 +665,7 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
                 LinearGradArgs a{h->o.model, h->o.X, h->o.ldx, h->d, d_rops + t * n + g0, cnt, M, d_batch,
                                  slots, gscale, h->o.lambda,
                                  static_cast<float*>(h->grad_scratch.p),
-                                 reinterpret_cast<float*>(static_cast<char*>(h->grad_scratch.p) + off_coef), loss};
+                                 reinterpret_cast<float*>(static_cast<char*>(h->grad_scratch.p) + off_coef), loss, false};
                 HIP_TRY(h, launch_linear_gradient(a, h->stream, &launches));
             }
             h->stats.grad_launches += launches;

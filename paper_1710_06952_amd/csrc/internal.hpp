@@ -107,8 +107,24 @@ struct LinearGradArgs {
     float* partial;         // device scratch: n_ops x (M + 1) x n_chunks
     float* coef;            // device scratch: n_ops x M
     float* loss;            // device, indexed by event, or nullptr
+    bool factored;          // least squares: leave g as its M coefficients (start of the slot), no combine launch
 };
 int64_t linear_grad_chunks(int64_t d);
+bool linear_can_factor(int model, int64_t d, int32_t M, int64_t ld);
+
+// The update of a round with the least-squares gradients still in factored form (see the kernel).
+struct LinearApplyArgs {
+    float* X;
+    int64_t ld;
+    int64_t d;
+    const PairOp* ops;      // device; features / feat_ld / event / slot name the factors
+    int32_t n_ops;
+    const float* slots;
+    const int32_t* batch_idx;
+    int32_t M;
+    bool streaming;         // X does not fit the caches
+};
+hipError_t launch_linear_apply_factored(const LinearApplyArgs& a, hipStream_t st);
 hipError_t launch_linear_gradient(const LinearGradArgs& a, hipStream_t st, int* n_launches);
 
 struct MlpGradArgs {

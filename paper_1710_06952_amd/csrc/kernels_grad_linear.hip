@@ -47,6 +47,8 @@ struct LinParams {
     float* partial;     // [op][M + 1][n_chunks]
     float* coef;        // [op][M]
     float* loss;
+    int factored;       // least squares: the coefficients go to the start of the operation's pending slot and
+                        // stay there; the update kernel forms g = sum_m c_m a_m while it applies the event
 };
 
 __device__ __forceinline__ v4f zero_beyond(v4f v, int64_t e, int64_t d) {
@@ -170,7 +172,9 @@ __global__ __launch_bounds__(kThreads) void linear_finalize_kernel(const LinPara
                 loss += (s > 0.0f ? s + log1pf(expf(-s)) : log1pf(expf(s))) + reg_loss;
                 c_m = -t / (1.0f + expf(-s));       // -y sigmoid(s)
             }
-            p.coef[static_cast<int64_t>(blockIdx.x) * p.M + m] = c_m * p.gscale;
+            float* __restrict__ dst = p.factored ? p.slots + static_cast<int64_t>(op.slot) * p.ld
+                                                 : p.coef + static_cast<int64_t>(blockIdx.x) * p.M;
+            dst[m] = c_m * p.gscale;
         }
     }
     loss = wave_sum(loss);
@@ -184,6 +188,20 @@ __global__ __launch_bounds__(kThreads) void linear_finalize_kernel(const LinPara
     }
 }
 
+// four elements of sum_m c_m a_m at vector index v (the one place this sum is written, so that the dense
+// and the factored path produce the same bits)
+template <bool STREAM>
+__device__ __forceinline__ v4f combine_rows(const float* __restrict__ A, int64_t lda, const int32_t* __restrict__ idx,
+                                            const float* __restrict__ cf, int M, int64_t v) {
+    v4f acc = {0, 0, 0, 0};
+#pragma unroll 8
+    for (int m = 0; m < M; ++m) {
+        const v4f a = load4<STREAM>(A + static_cast<int64_t>(idx[m]) * lda + 4 * v);
+        acc += a * cf[m];
+    }
+    return acc;
+}
+
 // grid = (ceil(n_vec / kThreads), n_ops)
 template <bool STREAM>
 __global__ __launch_bounds__(kThreads) void linear_combine_kernel(const LinParams p) {
@@ -193,18 +211,54 @@ __global__ __launch_bounds__(kThreads) void linear_combine_kernel(const LinParam
     const float* __restrict__ A = static_cast<const float*>(op.features);
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const float* __restrict__ cf = p.coef + static_cast<int64_t>(blockIdx.y) * p.M;
-    v4f acc = {0, 0, 0, 0};
-#pragma unroll 8
-    for (int m = 0; m < p.M; ++m) {
-        const v4f a = load4<STREAM>(A + static_cast<int64_t>(idx[m]) * op.ld + 4 * v);
-        acc += a * cf[m];
-    }
+    v4f acc = combine_rows<STREAM>(A, op.ld, idx, cf, p.M, v);
     if (p.model == ADPSGD_MODEL_LOGREG) {
         const v4f xh = read_xhat(p, op, v);
         acc += xh * (p.lambda * p.gscale * static_cast<float>(p.M));
     }
     acc = zero_beyond(acc, 4 * v, p.d);
     *reinterpret_cast<v4f*>(p.slots + static_cast<int64_t>(op.slot) * p.ld + 4 * v) = acc;
+}
+
+// ---- least squares, factored: the update of an event with g formed from its coefficients --------
+//     avg = (x^i + x^j) / 2;  x^j <- avg;  x^i <- avg - gamma * sum_m c_m a_m
+// The gradient of a linear model is a combination of its M minibatch rows, so the pending slot keeps
+// the M coefficients and the rows are read when the event is applied: the dense gradient is never
+// written to memory and read back (8 B per parameter and event less, and one launch per round less).
+// grid = (ceil(n_vec / kThreads), events of the round)
+struct LinApplyParams {
+    float* X;
+    int64_t ld;
+    int64_t d;
+    int64_t n_vec;
+    const PairOp* ops;
+    const float* slots;
+    const int32_t* batch_idx;
+    int32_t M;
+};
+
+template <bool STREAM_ROWS, bool STREAM_X>
+__global__ __launch_bounds__(kThreads) void linear_apply_factored_kernel(const LinApplyParams p) {
+    const PairOp op = p.ops[blockIdx.y];
+    const int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (v >= p.n_vec) return;
+    float* __restrict__ xi = p.X + static_cast<int64_t>(op.i) * p.ld + 4 * v;
+    float* __restrict__ xj = p.X + static_cast<int64_t>(op.j) * p.ld + 4 * v;
+    const v4f a = load4<STREAM_X>(xi), b = load4<STREAM_X>(xj);
+    const bool average_only = (op.flags & 1) != 0;      // extra pair of a general W_k: no gradient, no step
+    v4f g = {0, 0, 0, 0};
+    if (!average_only)
+        g = zero_beyond(combine_rows<STREAM_ROWS>(static_cast<const float*>(op.features), op.feat_ld,
+                                                  p.batch_idx + static_cast<int64_t>(op.event) * p.M,
+                                                  p.slots + static_cast<int64_t>(op.slot) * p.ld, p.M, v), 4 * v, p.d);
+    const float gamma = average_only ? 0.0f : op.gamma;
+    float ni[4], nj[4];
+    average_then_apply(a.x, b.x, g.x, gamma, ni[0], nj[0]);
+    average_then_apply(a.y, b.y, g.y, gamma, ni[1], nj[1]);
+    average_then_apply(a.z, b.z, g.z, gamma, ni[2], nj[2]);
+    average_then_apply(a.w, b.w, g.w, gamma, ni[3], nj[3]);
+    store4<STREAM_X>(xi, v4f{ni[0], ni[1], ni[2], ni[3]});     // the padding beyond d stays zero: g is zero there
+    if (op.i != op.j) store4<STREAM_X>(xj, v4f{nj[0], nj[1], nj[2], nj[3]});
 }
 
 // ---- short models: the whole gradient of one operation in one block, one launch -----------
@@ -320,6 +374,34 @@ __global__ __launch_bounds__(kSmallT) void linear_small_kernel(const LinParams p
 
 int64_t linear_grad_chunks(int64_t d) { return (d + kDotChunk - 1) / kDotChunk; }
 
+bool linear_can_factor(int model, int64_t d, int32_t M, int64_t ld) {
+    // least squares only (the logistic gradient carries lambda x^, which needs the stale read itself);
+    // long models only (short ones are bound by launches, not by bytes); the coefficients must fit a slot
+    return model == ADPSGD_MODEL_LSQ && d > kSmallMaxD && M >= 1 && M <= ld;
+}
+
+hipError_t launch_linear_apply_factored(const LinearApplyArgs& a, hipStream_t st) {
+    if (a.n_ops <= 0) return hipSuccess;
+    LinApplyParams p;
+    p.X = a.X;
+    p.ld = a.ld;
+    p.d = a.d;
+    p.n_vec = (a.d + 3) / 4;
+    p.ops = a.ops;
+    p.slots = a.slots;
+    p.batch_idx = a.batch_idx;
+    p.M = a.M;
+    const int64_t blocks = (p.n_vec + kThreads - 1) / kThreads;
+    if (blocks > 0x7FFFFFFF || a.n_ops > 65535) return hipErrorInvalidValue;
+    const dim3 grid(static_cast<uint32_t>(blocks), a.n_ops);
+    const bool stream_rows = static_cast<int64_t>(a.M) * a.d * 4 > (8ll << 20);
+    if (stream_rows && a.streaming) hipLaunchKernelGGL((linear_apply_factored_kernel<true, true>), grid, dim3(kThreads), 0, st, p);
+    else if (stream_rows) hipLaunchKernelGGL((linear_apply_factored_kernel<true, false>), grid, dim3(kThreads), 0, st, p);
+    else if (a.streaming) hipLaunchKernelGGL((linear_apply_factored_kernel<false, true>), grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((linear_apply_factored_kernel<false, false>), grid, dim3(kThreads), 0, st, p);
+    return hipGetLastError();
+}
+
 hipError_t launch_linear_gradient(const LinearGradArgs& a, hipStream_t st, int* n_launches) {
     if (a.n_ops <= 0) return hipSuccess;
     LinParams p;
@@ -338,6 +420,8 @@ hipError_t launch_linear_gradient(const LinearGradArgs& a, hipStream_t st, int* 
     p.partial = a.partial;
     p.coef = a.coef;
     p.loss = a.loss;
+    p.factored = a.factored ? 1 : 0;
+    if (a.factored && !linear_can_factor(a.model, a.d, a.M, a.ld)) return hipErrorInvalidValue;
     if (a.d <= kSmallMaxD && a.M <= kSmallMaxM && a.n_ops <= 0x7FFFFFFF) {
         const int lanes_vec = static_cast<int>((p.n_vec + 63) / 64);      // float4 elements of x^ per lane
         const dim3 grid(a.n_ops), block(kSmallT);
@@ -363,6 +447,10 @@ hipError_t launch_linear_gradient(const LinearGradArgs& a, hipStream_t st, int* 
     hipLaunchKernelGGL(linear_finalize_kernel, dim3(a.n_ops), dim3(kThreads), 0, st, p, lanes_per_row);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (a.factored) {
+        if (n_launches) *n_launches += 2;
+        return hipSuccess;
+    }
     const dim3 comb_grid(static_cast<uint32_t>(out_blocks), a.n_ops);
     if (stream_rows) hipLaunchKernelGGL(linear_combine_kernel<true>, comb_grid, dim3(kThreads), 0, st, p);
     else hipLaunchKernelGGL(linear_combine_kernel<false>, comb_grid, dim3(kThreads), 0, st, p);

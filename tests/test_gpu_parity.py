@@ -982,3 +982,31 @@ def test_the_abi_drives_the_gpu_from_plain_c():
     out = subprocess.run([exe], capture_output=True, text=True, timeout=100)
     assert out.returncode == 0, (out.returncode, out.stdout, out.stderr)
     assert "c abi gpu ok" in out.stdout
+
+
+def test_least_squares_factored_and_dense_gradient_give_the_same_bits(P):
+    """Long least-squares models keep the gradient as its M coefficients until the update kernel applies it;
+    the result must be exactly that of the dense path (also with extra averaging pairs and a ragged d)."""
+    from workloads import random_extra_pairs
+    n, d, rows, K, M, T = 10, 4099, 24, 400, 7, 4
+    _say("lsq factored vs dense")
+    g = random_regular4_graph(n, 6)
+    feats, targs, _ = lsq_data(n, rows, d, seed=17, feature_var=1.0 / d)
+    sched = oracle.make_schedule(g, K, seed=18, T_max=T, M=M, rows=[rows] * n)
+    sched["extra_pairs"] = random_extra_pairs(g, sched["worker"], sched["neighbour"], max_extra=2, seed=19)
+    sched["gamma"] = (0.3 * (1 + np.arange(K) % 3)).astype(np.float32)
+    x0 = np.random.default_rng(7).standard_normal((n, d)).astype(np.float32)
+    out = []
+    for dense in (False, True):
+        eng = P.Engine(g, d, "lsq", M=M, gamma=0.3, T_max=T, dense_gradient=dense, verify_plan=True)
+        eng.load_data(feats, targs)
+        eng.set_models(x0, broadcast=False)
+        eng.run_events(sched, want_loss=True)
+        out.append((eng.get_models(), eng.get_loss(), eng.get_stats()["grad_launches"]))
+        eng.close()
+    assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
+    assert out[0][2] * 3 == out[1][2] * 2          # two launches per gradient set instead of three
+    Xr = x0.copy()
+    oracle.run_events(Xr, sched, oracle.MODEL_LSQ, 0.3, M=M, gscale=1.0 / M, features=feats, targets=targs,
+                      gamma_k=sched["gamma"], extra_pairs=sched["extra_pairs"])
+    assert rel_err(out[0][0], Xr) <= TOL
