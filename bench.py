@@ -14,7 +14,9 @@ event: read and write the two averaged rows) and the CPU oracle timed on this ho
 
 ``--config 1|2|4|5`` times the other configurations the same way (data generated in GPU
 memory; a step is a tenth of the configuration's events); those lines are context for the
-gradient kernels, not the headline.
+gradient kernels, not the headline.  Their roofline object covers the kernels of one event
+together (gradient launches + update kernel) against the method's own traffic per event with
+the minibatch rows counted once.
 """
 from __future__ import annotations
 
