@@ -13,9 +13,9 @@ INCLUDE = HERE.parent / "include"
 LIB = HERE / "libadpsgd.so"
 OBJ = HERE / "_build"
 
-SOURCES = ["api.cpp", "schedule.cpp", "planner.cpp", "kernels_fused.hip", "kernels_grad_linear.hip",
+SOURCES = ["api.cpp", "api_sync.cpp", "api_diag.cpp", "schedule.cpp", "planner.cpp", "kernels_fused.hip", "kernels_grad_linear.hip",
            "kernels_mlp.hip", "kernels_diag.hip", "kernels_sync.hip"]
-HEADERS = ["internal.hpp", "device_common.hpp"]
+HEADERS = ["internal.hpp", "handle.hpp", "device_common.hpp"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 instructions
