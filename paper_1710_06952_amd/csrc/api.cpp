@@ -237,19 +237,12 @@ extern "C" int adpsgd_set_models(adpsgd_t* h, const float* x, int64_t ld_in, int
     return ADPSGD_OK;
 }
 
-extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float* loss) {
-    if (!h) return ADPSGD_ERR_ARG;
-    if (!s || s->K < 0) return fail(h, ADPSGD_ERR_ARG, "run_events: schedule is NULL or K < 0");
-    const int64_t K = s->K;
-    if (K == 0) return ADPSGD_OK;
-    if (K > 0x7FFFFFF0) return fail(h, ADPSGD_ERR_ARG, "run_events: at most 2^31 - 16 events per call");
-    if (!s->worker || !s->neighbour || !s->tau) return fail(h, ADPSGD_ERR_ARG, "run_events: null schedule array");
-    const bool with_grad = h->o.model != ADPSGD_MODEL_SYNTH;
-    const int32_t M = with_grad ? h->o.M : 0;
-    if (with_grad && !s->batch_idx) return fail(h, ADPSGD_ERR_ARG, "run_events: batch_idx is NULL");
+namespace {
 
-    // ---- validation: nothing is launched and no state changes on failure ----
-    const int64_t n_extra = s->extra_ptr ? s->extra_ptr[K] : 0;
+// Checks a schedule against the documented constraints; nothing is launched and no state changes
+// when it fails.
+int validate_schedule(adpsgd_t* h, const adpsgd_schedule_t* s, bool with_grad, int32_t M, int64_t n_extra) {
+    const int64_t K = s->K;
     if (s->extra_ptr) {
         if (s->extra_ptr[0] != 0 || n_extra < 0 || (n_extra > 0 && (!s->extra_a || !s->extra_b)))
             return fail(h, ADPSGD_ERR_ARG, "run_events: malformed extra-pair arrays");
@@ -288,6 +281,25 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
                     return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: batch index out of range at event " + std::to_string(k));
         }
     }
+    return ADPSGD_OK;
+}
+
+}  // namespace
+
+extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float* loss) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (!s || s->K < 0) return fail(h, ADPSGD_ERR_ARG, "run_events: schedule is NULL or K < 0");
+    const int64_t K = s->K;
+    if (K == 0) return ADPSGD_OK;
+    if (K > 0x7FFFFFF0) return fail(h, ADPSGD_ERR_ARG, "run_events: at most 2^31 - 16 events per call");
+    if (!s->worker || !s->neighbour || !s->tau) return fail(h, ADPSGD_ERR_ARG, "run_events: null schedule array");
+    const bool with_grad = h->o.model != ADPSGD_MODEL_SYNTH;
+    const int32_t M = with_grad ? h->o.M : 0;
+    if (with_grad && !s->batch_idx) return fail(h, ADPSGD_ERR_ARG, "run_events: batch_idx is NULL");
+
+    const int64_t n_extra = s->extra_ptr ? s->extra_ptr[K] : 0;
+    const int rc_valid = validate_schedule(h, s, with_grad, M, n_extra);
+    if (rc_valid != ADPSGD_OK) return rc_valid;
 
     // perceptron without momentum: dW1 stays in factored form until the update kernel
     // (the wait-free variant reads the pending gradient as a dense vector, so it keeps the dense form)
