@@ -68,7 +68,7 @@ enum {
                                     launched (no two updates of a round share a row, every stale read sees exactly
                                     the updates before its logical time, slots live long enough); a violation is a
                                     library bug and returns ADPSGD_ERR_STATE.  O(K log K) host work per call */
-    ADPSGD_FLAG_DENSE_GRADIENT = 2  /* always write gradients out as dense vectors.  By default (no momentum, no
+    ADPSGD_FLAG_DENSE_GRADIENT = 2  /* always write gradients out as dense vectors.  By default (without the
                                        wait-free variant) low-rank gradients stay in factored form until the
                                        update kernel applies them: the MLP's first layer as dH and the minibatch
                                        inputs, least squares on long models as its M coefficients.  The values

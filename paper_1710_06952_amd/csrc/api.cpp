@@ -301,14 +301,14 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
     const int rc_valid = validate_schedule(h, s, with_grad, M, n_extra);
     if (rc_valid != ADPSGD_OK) return rc_valid;
 
-    // perceptron without momentum: dW1 stays in factored form until the update kernel
+    // perceptron: dW1 stays in factored form until the update kernel
     // (the wait-free variant reads the pending gradient as a dense vector, so it keeps the dense form)
     const bool mlp_comp = h->o.model == ADPSGD_MODEL_MLP && h->o.local_compensation != 0;
-    const bool factored = h->o.model == ADPSGD_MODEL_MLP && !h->o.V && !(h->o.flags & ADPSGD_FLAG_DENSE_GRADIENT) &&
+    const bool factored = h->o.model == ADPSGD_MODEL_MLP && !(h->o.flags & ADPSGD_FLAG_DENSE_GRADIENT) &&
                           !mlp_comp && mlp_can_factor(h->o.mlp_in, h->o.mlp_hidden, M);
 
     // least squares on long models: the gradient stays M coefficients until the update kernel applies it
-    const bool lin_factored = !h->o.V && !h->o.local_compensation && !(h->o.flags & ADPSGD_FLAG_DENSE_GRADIENT) &&
+    const bool lin_factored = !h->o.local_compensation && !(h->o.flags & ADPSGD_FLAG_DENSE_GRADIENT) &&
                               with_grad && linear_can_factor(h->o.model, h->d, M, h->o.ldx);
 
     // ---- plan ----
@@ -466,11 +466,11 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
             for (int64_t t = u_off[r]; t < u_off[r + 1] && !has_solo; ++t) has_solo = uops[t].i == uops[t].j;
             if (lin_factored) {
                 LinearApplyArgs a{h->o.X, h->o.ldx, h->d, d_uops + u_off[r], static_cast<int32_t>(nu), slots, d_batch, M,
-                                  h->streaming};
+                                  h->streaming, h->o.V, h->o.momentum, h->o.weight_decay};
                 HIP_TRY(h, launch_linear_apply_factored(a, h->stream));
             } else if (factored) {
                 MlpApplyArgs a{h->o.X, h->o.ldx, h->d, h->o.mlp_in, h->o.mlp_hidden, M, d_uops + u_off[r],
-                               static_cast<int32_t>(nu), slots, h->o.Xbf16, d_batch};
+                               static_cast<int32_t>(nu), slots, h->o.Xbf16, d_batch, h->o.V, h->o.momentum, h->o.weight_decay};
                 HIP_TRY(h, launch_mlp_apply_factored(a, h->stream));
             } else {
                 FusedArgs a{h->o.X, h->o.ldx, h->d, d_uops + u_off[r], static_cast<int32_t>(nu), slots,

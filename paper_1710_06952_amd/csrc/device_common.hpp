@@ -94,6 +94,22 @@ __device__ __forceinline__ void average_then_apply(float a, float b, float g, fl
     new_i = avg - step;
 }
 
+// The event with the experiments' optimizer (Sec. 5.2): per-worker momentum buffer v, weight decay on
+// the averaged model;  u = g + wd * avg;  v <- mu * v + u;  x^i <- avg - gamma * v.  One rounding per
+// operation, in this order.
+__device__ __forceinline__ void average_then_apply_momentum(float a, float b, float g, float v_old, float gamma, float mu,
+                                                            float wd, float& new_i, float& new_j, float& v_new) {
+#pragma clang fp contract(off)
+    const float avg = (a + b) * 0.5f;
+    const float decay = wd * avg;
+    const float u = g + decay;
+    const float carried = mu * v_old;
+    v_new = carried + u;
+    const float step = gamma * v_new;
+    new_j = avg;
+    new_i = avg - step;
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);

@@ -123,6 +123,8 @@ struct LinearApplyArgs {
     const int32_t* batch_idx;
     int32_t M;
     bool streaming;         // X does not fit the caches
+    float* V;               // momentum buffers or nullptr
+    float momentum, weight_decay;
 };
 hipError_t launch_linear_apply_factored(const LinearApplyArgs& a, hipStream_t st);
 hipError_t launch_linear_gradient(const LinearGradArgs& a, hipStream_t st, int* n_launches);
@@ -161,6 +163,8 @@ struct MlpApplyArgs {
     const float* slots;
     uint16_t* Xbf16;
     const int32_t* batch_idx;   // device, K x M
+    float* V;                   // momentum buffers or nullptr
+    float momentum, weight_decay;
 };
 hipError_t launch_mlp_apply_factored(const MlpApplyArgs& a, hipStream_t st);
 hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_launches);

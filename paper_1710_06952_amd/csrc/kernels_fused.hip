@@ -45,22 +45,6 @@ __device__ __forceinline__ void store1(float* p, float v) {
     else *p = v;
 }
 
-// The event with the experiments' optimizer (Sec. 5.2): per-worker momentum buffer v, weight decay on
-// the averaged model;  u = g + wd * avg;  v <- mu * v + u;  x^i <- avg - gamma * v.  One rounding per
-// operation, in this order.
-__device__ __forceinline__ void average_then_apply_momentum(float a, float b, float g, float v_old, float gamma, float mu,
-                                                            float wd, float& new_i, float& new_j, float& v_new) {
-#pragma clang fp contract(off)
-    const float avg = (a + b) * 0.5f;
-    const float decay = wd * avg;
-    const float u = g + decay;
-    const float carried = mu * v_old;
-    v_new = carried + u;
-    const float step = gamma * v_new;
-    new_j = avg;
-    new_i = avg - step;
-}
-
 // grid = (ceil(d / 1024), events of the round).  Pass u of thread t touches element
 // 1024 blockIdx.x + 256 u + t of both rows.
 // SOLO = the round contains an event without a partner (i == j: a worker with no neighbour takes a

@@ -235,9 +235,11 @@ struct LinApplyParams {
     const float* slots;
     const int32_t* batch_idx;
     int32_t M;
+    float* V;               // momentum buffers (MOM), else nullptr
+    float momentum, weight_decay;
 };
 
-template <bool STREAM_ROWS, bool STREAM_X>
+template <bool STREAM_ROWS, bool STREAM_X, bool MOM>
 __global__ __launch_bounds__(kThreads) void linear_apply_factored_kernel(const LinApplyParams p) {
     const PairOp op = p.ops[blockIdx.y];
     const int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
@@ -252,13 +254,32 @@ __global__ __launch_bounds__(kThreads) void linear_apply_factored_kernel(const L
                                                   p.batch_idx + static_cast<int64_t>(op.event) * p.M,
                                                   p.slots + static_cast<int64_t>(op.slot) * p.ld, p.M, v), 4 * v, p.d);
     const float gamma = average_only ? 0.0f : op.gamma;
+    const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w}, gv[4] = {g.x, g.y, g.z, g.w};
     float ni[4], nj[4];
-    average_then_apply(a.x, b.x, g.x, gamma, ni[0], nj[0]);
-    average_then_apply(a.y, b.y, g.y, gamma, ni[1], nj[1]);
-    average_then_apply(a.z, b.z, g.z, gamma, ni[2], nj[2]);
-    average_then_apply(a.w, b.w, g.w, gamma, ni[3], nj[3]);
+    if (MOM && !average_only) {       // an averaging-only pair leaves the momentum buffers alone
+        float* __restrict__ vi = p.V + static_cast<int64_t>(op.i) * p.ld + 4 * v;
+        const v4f vo = load4<STREAM_X>(vi);
+        const float vold[4] = {vo.x, vo.y, vo.z, vo.w};
+        float vn[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            average_then_apply_momentum(av[c], bv[c], gv[c], vold[c], gamma, p.momentum, p.weight_decay, ni[c], nj[c], vn[c]);
+        store4<STREAM_X>(vi, v4f{vn[0], vn[1], vn[2], vn[3]});   // zero in the padding, as x and g are
+    } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) average_then_apply(av[c], bv[c], gv[c], gamma, ni[c], nj[c]);
+    }
     store4<STREAM_X>(xi, v4f{ni[0], ni[1], ni[2], ni[3]});     // the padding beyond d stays zero: g is zero there
     if (op.i != op.j) store4<STREAM_X>(xj, v4f{nj[0], nj[1], nj[2], nj[3]});
+}
+
+template <bool MOM>
+hipError_t launch_apply_variant(const LinApplyParams& p, dim3 grid, bool stream_rows, bool stream_x, hipStream_t st) {
+    if (stream_rows && stream_x) hipLaunchKernelGGL((linear_apply_factored_kernel<true, true, MOM>), grid, dim3(kThreads), 0, st, p);
+    else if (stream_rows) hipLaunchKernelGGL((linear_apply_factored_kernel<true, false, MOM>), grid, dim3(kThreads), 0, st, p);
+    else if (stream_x) hipLaunchKernelGGL((linear_apply_factored_kernel<false, true, MOM>), grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((linear_apply_factored_kernel<false, false, MOM>), grid, dim3(kThreads), 0, st, p);
+    return hipGetLastError();
 }
 
 // ---- short models: the whole gradient of one operation in one block, one launch -----------
@@ -391,15 +412,15 @@ hipError_t launch_linear_apply_factored(const LinearApplyArgs& a, hipStream_t st
     p.slots = a.slots;
     p.batch_idx = a.batch_idx;
     p.M = a.M;
+    p.V = a.V;
+    p.momentum = a.momentum;
+    p.weight_decay = a.weight_decay;
     const int64_t blocks = (p.n_vec + kThreads - 1) / kThreads;
     if (blocks > 0x7FFFFFFF || a.n_ops > 65535) return hipErrorInvalidValue;
     const dim3 grid(static_cast<uint32_t>(blocks), a.n_ops);
     const bool stream_rows = static_cast<int64_t>(a.M) * a.d * 4 > (8ll << 20);
-    if (stream_rows && a.streaming) hipLaunchKernelGGL((linear_apply_factored_kernel<true, true>), grid, dim3(kThreads), 0, st, p);
-    else if (stream_rows) hipLaunchKernelGGL((linear_apply_factored_kernel<true, false>), grid, dim3(kThreads), 0, st, p);
-    else if (a.streaming) hipLaunchKernelGGL((linear_apply_factored_kernel<false, true>), grid, dim3(kThreads), 0, st, p);
-    else hipLaunchKernelGGL((linear_apply_factored_kernel<false, false>), grid, dim3(kThreads), 0, st, p);
-    return hipGetLastError();
+    return a.V ? launch_apply_variant<true>(p, grid, stream_rows, a.streaming, st)
+               : launch_apply_variant<false>(p, grid, stream_rows, a.streaming, st);
 }
 
 hipError_t launch_linear_gradient(const LinearGradArgs& a, hipStream_t st, int* n_launches) {

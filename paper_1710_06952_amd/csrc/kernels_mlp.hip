@@ -496,14 +496,31 @@ struct MlpApplyParams {
     const float* slots;
     uint16_t* Xbf16;
     const int32_t* batch_idx;
+    float* V;                // momentum buffers (MOM), else nullptr
+    float momentum, weight_decay;
 };
 
-__device__ __forceinline__ void apply4(const MlpApplyParams& p, const PairOp& op, int64_t e, v4f a, v4f b, v4f g,
+// vold: the worker's momentum entries (MOM and not average_only), else unused
+template <bool MOM>
+__device__ __forceinline__ void apply4(const MlpApplyParams& p, const PairOp& op, int64_t e, v4f a, v4f b, v4f g, v4f vold,
                                        bool average_only, bool pair, int valid) {
     float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w}, gv[4] = {g.x, g.y, g.z, g.w};
     float ni[4], nj[4];
+    if (MOM && !average_only) {       // an averaging-only pair leaves the momentum buffers alone
+        const float vo[4] = {vold.x, vold.y, vold.z, vold.w};
+        float vn[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) average_then_apply(av[c], bv[c], average_only ? 0.0f : gv[c], average_only ? 0.0f : op.gamma, ni[c], nj[c]);
+        for (int c = 0; c < 4; ++c)
+            average_then_apply_momentum(av[c], bv[c], gv[c], vo[c], op.gamma, p.momentum, p.weight_decay, ni[c], nj[c], vn[c]);
+        float* __restrict__ vi = p.V + static_cast<int64_t>(op.i) * p.ld + e;
+        if (valid == 4) *reinterpret_cast<v4f*>(vi) = v4f{vn[0], vn[1], vn[2], vn[3]};
+        else
+            for (int c = 0; c < valid; ++c) vi[c] = vn[c];
+    } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            average_then_apply(av[c], bv[c], average_only ? 0.0f : gv[c], average_only ? 0.0f : op.gamma, ni[c], nj[c]);
+    }
     float* __restrict__ xi = p.X + static_cast<int64_t>(op.i) * p.ld + e;
     float* __restrict__ xj = p.X + static_cast<int64_t>(op.j) * p.ld + e;
     uint16_t* __restrict__ si = p.Xbf16 + static_cast<int64_t>(op.i) * p.ld + e;
@@ -527,6 +544,7 @@ __device__ __forceinline__ void apply4(const MlpApplyParams& p, const PairOp& op
     }
 }
 
+template <bool MOM>
 __global__ __launch_bounds__(kT) void mlp_apply_factored_kernel(const MlpApplyParams p) {
     __shared__ __attribute__((aligned(16))) uint16_t At[64][72];
     __shared__ __attribute__((aligned(16))) uint16_t Bt[64][72];
@@ -545,21 +563,24 @@ __global__ __launch_bounds__(kT) void mlp_apply_factored_kernel(const MlpApplyPa
         if (e >= p.d) return;
         const int valid = p.d - e >= 4 ? 4 : static_cast<int>(p.d - e);
         const v4f a = *reinterpret_cast<const v4f*>(xi + e), b = *reinterpret_cast<const v4f*>(xj + e);   // rows are padded
-        v4f g = {0, 0, 0, 0};
+        v4f g = {0, 0, 0, 0}, vold = {0, 0, 0, 0};
         if (!average_only) g = *reinterpret_cast<const v4f*>(slot + e);
-        apply4(p, op, e, a, b, g, average_only, pair, valid);
+        if (MOM && !average_only) vold = *reinterpret_cast<const v4f*>(p.V + static_cast<int64_t>(op.i) * p.ld + e);
+        apply4<MOM>(p, op, e, a, b, g, vold, average_only, pair, valid);
         return;
     }
     const int h0 = blockIdx.x * kTileH, i0 = blockIdx.y * 64;
     const int rr = threadIdx.x >> 4, hq = (threadIdx.x & 15) * 4;      // this thread's rows 16 r + rr, columns hq .. hq + 3
-    v4f a[4], b[4];
+    v4f a[4], b[4], vold[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {        // the model rows are requested before the product is formed
         const int i = i0 + 16 * r + rr;
+        vold[r] = v4f{0, 0, 0, 0};
         if (i < p.in) {
             const int64_t e = static_cast<int64_t>(i) * p.hid + h0 + hq;
             a[r] = *reinterpret_cast<const v4f*>(xi + e);
             b[r] = *reinterpret_cast<const v4f*>(xj + e);
+            if (MOM && !average_only) vold[r] = *reinterpret_cast<const v4f*>(p.V + static_cast<int64_t>(op.i) * p.ld + e);
         }
     }
     if (!average_only) {                  // uniform over the block
@@ -579,7 +600,7 @@ __global__ __launch_bounds__(kT) void mlp_apply_factored_kernel(const MlpApplyPa
         if (i >= p.in) continue;
         v4f g = {0, 0, 0, 0};
         if (!average_only) g = *reinterpret_cast<const v4f*>(&Gs[16 * r + rr][hq]);
-        apply4(p, op, static_cast<int64_t>(i) * p.hid + h0 + hq, a[r], b[r], g, average_only, pair, 4);
+        apply4<MOM>(p, op, static_cast<int64_t>(i) * p.hid + h0 + hq, a[r], b[r], g, vold[r], average_only, pair, 4);
     }
 }
 
@@ -642,13 +663,18 @@ hipError_t launch_mlp_apply_factored(const MlpApplyArgs& a, hipStream_t st) {
     p.slots = a.slots;
     p.Xbf16 = a.Xbf16;
     p.batch_idx = a.batch_idx;
+    p.V = a.V;
+    p.momentum = a.momentum;
+    p.weight_decay = a.weight_decay;
     const int64_t tail = a.d - static_cast<int64_t>(a.in) * a.hid;            // floats after W1
     const uint32_t bx = static_cast<uint32_t>(a.hid / kTileH);
     const int64_t per_row = static_cast<int64_t>(bx) * kT * 4;                  // floats one grid row of blocks covers
     const int64_t tail_rows = tail > 0 ? (tail + per_row - 1) / per_row : 0;
     const int64_t by = (a.in + 63) / 64 + tail_rows;
     if (by > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(mlp_apply_factored_kernel, dim3(bx, static_cast<uint32_t>(by), a.n_ops), dim3(kT), 0, st, p);
+    const dim3 grid(bx, static_cast<uint32_t>(by), a.n_ops);
+    if (a.V) hipLaunchKernelGGL(mlp_apply_factored_kernel<true>, grid, dim3(kT), 0, st, p);
+    else hipLaunchKernelGGL(mlp_apply_factored_kernel<false>, grid, dim3(kT), 0, st, p);
     return hipGetLastError();
 }
 

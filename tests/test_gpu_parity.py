@@ -723,12 +723,14 @@ def test_short_models_take_the_single_block_gradient(P, model, n, d, rows, K, M,
     eng.close()
 
 
-def test_mlp_factored_and_dense_first_layer_gradient_give_the_same_bits(P):
+@pytest.mark.parametrize("mu,wd", [(0.0, 0.0), (0.9, 1e-3)])
+def test_mlp_factored_and_dense_first_layer_gradient_give_the_same_bits(P, mu, wd):
     """The update kernel that forms dW1 from its factors must produce exactly what the dense path does,
-    also with extra averaging pairs and workers without a partner step mixed in."""
+    also with extra averaging pairs and workers without a partner step mixed in, and with the
+    experiments' optimizer (momentum buffers compared too)."""
     from workloads import mixture_data, mlp_init, random_extra_pairs
     n, dims, rows, K, M, T = 8, (40, 128, 7), 48, 300, 24, 3
-    _say("mlp factored vs dense")
+    _say("mlp factored vs dense mu=%g" % mu)
     g = random_regular4_graph(n, 4)
     d = dims[0] * dims[1] + dims[1] + dims[1] * dims[2] + dims[2]
     feats, labels, _ = mixture_data(n, rows, din=dims[0], classes=dims[2], seed=9)
@@ -737,14 +739,18 @@ def test_mlp_factored_and_dense_first_layer_gradient_give_the_same_bits(P):
     x0 = mlp_init(*dims, seed=9)
     out = []
     for dense in (False, True):
-        eng = P.Engine(g, d, "mlp", M=M, gamma=0.05, T_max=T, mlp=dims, dense_gradient=dense)
+        eng = P.Engine(g, d, "mlp", M=M, gamma=0.05 if mu == 0.0 else 0.01, T_max=T, mlp=dims, dense_gradient=dense,
+                       momentum=mu, weight_decay=wd)
         eng.load_data(feats, labels)
         eng.set_models(x0)
         eng.run_events(sched, want_loss=True)
-        out.append((eng.get_models(), eng.get_bf16_models(), eng.get_loss(), eng.get_stats()["grad_launches"]))
+        out.append((eng.get_models(), eng.get_bf16_models(), eng.get_loss(), eng.get_stats()["grad_launches"],
+                    eng.get_momentum() if mu else None))
         eng.close()
     assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
     assert np.array_equal(out[0][2], out[1][2])
+    if mu:
+        assert np.array_equal(out[0][4], out[1][4]) and np.any(out[0][4] != 0)
     assert out[0][3] * 3 == out[1][3] * 2          # two launches per gradient set instead of three
 
 
@@ -984,29 +990,38 @@ def test_the_abi_drives_the_gpu_from_plain_c():
     assert "c abi gpu ok" in out.stdout
 
 
-def test_least_squares_factored_and_dense_gradient_give_the_same_bits(P):
+@pytest.mark.parametrize("mu,wd", [(0.0, 0.0), (0.9, 1e-3)])
+def test_least_squares_factored_and_dense_gradient_give_the_same_bits(P, mu, wd):
     """Long least-squares models keep the gradient as its M coefficients until the update kernel applies it;
-    the result must be exactly that of the dense path (also with extra averaging pairs and a ragged d)."""
+    the result must be exactly that of the dense path (also with extra averaging pairs, a ragged d and the
+    experiments' optimizer), and agree with the oracle."""
     from workloads import random_extra_pairs
     n, d, rows, K, M, T = 10, 4099, 24, 400, 7, 4
-    _say("lsq factored vs dense")
+    _say("lsq factored vs dense mu=%g" % mu)
     g = random_regular4_graph(n, 6)
     feats, targs, _ = lsq_data(n, rows, d, seed=17, feature_var=1.0 / d)
     sched = oracle.make_schedule(g, K, seed=18, T_max=T, M=M, rows=[rows] * n)
     sched["extra_pairs"] = random_extra_pairs(g, sched["worker"], sched["neighbour"], max_extra=2, seed=19)
-    sched["gamma"] = (0.3 * (1 + np.arange(K) % 3)).astype(np.float32)
+    base = 0.3 if mu == 0.0 else 0.03
+    sched["gamma"] = (base * (1 + np.arange(K) % 3)).astype(np.float32)
     x0 = np.random.default_rng(7).standard_normal((n, d)).astype(np.float32)
     out = []
     for dense in (False, True):
-        eng = P.Engine(g, d, "lsq", M=M, gamma=0.3, T_max=T, dense_gradient=dense, verify_plan=True)
+        eng = P.Engine(g, d, "lsq", M=M, gamma=base, T_max=T, dense_gradient=dense, verify_plan=True,
+                       momentum=mu, weight_decay=wd)
         eng.load_data(feats, targs)
         eng.set_models(x0, broadcast=False)
         eng.run_events(sched, want_loss=True)
-        out.append((eng.get_models(), eng.get_loss(), eng.get_stats()["grad_launches"]))
+        out.append((eng.get_models(), eng.get_loss(), eng.get_stats()["grad_launches"],
+                    eng.get_momentum() if mu else None))
         eng.close()
     assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
     assert out[0][2] * 3 == out[1][2] * 2          # two launches per gradient set instead of three
     Xr = x0.copy()
-    oracle.run_events(Xr, sched, oracle.MODEL_LSQ, 0.3, M=M, gscale=1.0 / M, features=feats, targets=targs,
-                      gamma_k=sched["gamma"], extra_pairs=sched["extra_pairs"])
+    Vr = np.zeros_like(Xr) if mu else None
+    oracle.run_events(Xr, sched, oracle.MODEL_LSQ, base, M=M, gscale=1.0 / M, features=feats, targets=targs,
+                      gamma_k=sched["gamma"], extra_pairs=sched["extra_pairs"], momentum=mu, weight_decay=wd, V=Vr)
     assert rel_err(out[0][0], Xr) <= TOL
+    if mu:
+        assert np.array_equal(out[0][3], out[1][3])
+        assert rel_err(out[0][3], Vr) <= 5 * TOL
