@@ -128,8 +128,13 @@ typedef struct {
 
 /* A batch of K events, all arrays in host memory, read during the call only.
  * Constraints (else ADPSGD_ERR_SCHEDULE, with no state change):
- *   0 <= worker[k] < n;  neighbour[k] is a graph neighbour of worker[k]
- *   (or equals worker[k] when that worker has no neighbour: plain SGD step);
+ *   0 <= worker[k] < n;  neighbour[k] is a graph neighbour of worker[k], or
+ *   equals worker[k]: W_k = I, the worker applies the gradient without
+ *   averaging.  That is the step of a worker that has no neighbour, and it
+ *   expresses the gradient queue the wait-free appendix mentions (computation
+ *   thread): q gradients queued before one communication step are that step's
+ *   event followed by q - 1 such events of the same worker, each with the
+ *   staleness its gradient had;
  *   0 <= tau[k] <= min(k, T_max): a call is self-contained, staleness never
  *   reaches behind the first event of the call;
  *   0 <= batch_idx[k*M + m] < rows loaded for worker[k]. */

@@ -46,8 +46,8 @@ int hip_fail(adpsgd_t* h, hipError_t e, const char* what) {
 }
 
 bool is_neighbour(const adpsgd_t* h, int32_t i, int32_t j) {
+    if (j == i) return true;     // W_k = I: a gradient step without averaging
     const int32_t b = h->rowptr[i], e = h->rowptr[i + 1];
-    if (b == e) return j == i;
     for (int32_t t = b; t < e; ++t)
         if (h->col[t] == j) return true;
     return false;

@@ -728,13 +728,14 @@ def test_mlp_factored_and_dense_first_layer_gradient_give_the_same_bits(P, mu, w
     """The update kernel that forms dW1 from its factors must produce exactly what the dense path does,
     also with extra averaging pairs and workers without a partner step mixed in, and with the
     experiments' optimizer (momentum buffers compared too)."""
-    from workloads import mixture_data, mlp_init, random_extra_pairs
+    from workloads import mixture_data, mlp_init, random_extra_pairs, with_identity_events
     n, dims, rows, K, M, T = 8, (40, 128, 7), 48, 300, 24, 3
     _say("mlp factored vs dense mu=%g" % mu)
     g = random_regular4_graph(n, 4)
     d = dims[0] * dims[1] + dims[1] + dims[1] * dims[2] + dims[2]
     feats, labels, _ = mixture_data(n, rows, din=dims[0], classes=dims[2], seed=9)
     sched = oracle.make_schedule(g, K, seed=9, T_max=T, M=M, rows=[rows] * n)
+    sched["neighbour"] = with_identity_events(sched["worker"], sched["neighbour"], 0.2, seed=3)
     sched["extra_pairs"] = random_extra_pairs(g, sched["worker"], sched["neighbour"], max_extra=2, seed=10)
     x0 = mlp_init(*dims, seed=9)
     out = []
@@ -756,7 +757,7 @@ def test_mlp_factored_and_dense_first_layer_gradient_give_the_same_bits(P, mu, w
 
 # ------------------------------------------------------------------ seeded sweep over small random set-ups
 def _random_case(rng):
-    from workloads import hop_ring_graph, random_extra_pairs
+    from workloads import hop_ring_graph, random_extra_pairs, with_identity_events
     model = ["synth", "lsq", "logreg"][rng.integers(3)]
     n = int(rng.integers(1, 13))
     d = int(rng.choice([1, 3, 64, 250, 1023, 1025, 2048, 2051, 4100, 9001]))
@@ -774,19 +775,24 @@ def _random_case(rng):
     if n >= 6 and rng.integers(2):
         extra = random_extra_pairs(g, sched["worker"], sched["neighbour"], max_extra=2, seed=int(rng.integers(1000)))
     gam = (0.05 * (1 + rng.integers(0, 4, size=K))).astype(np.float32) if rng.integers(2) else None
-    return dict(model=model, n=n, d=d, g=g, T=T, K=K, M=M, rows=rows, momentum=momentum, wd=wd, comp=comp,
+    ident = bool(rng.integers(3) == 0)       # some events apply their gradient without averaging (W_k = I)
+    if ident:
+        sched["neighbour"] = with_identity_events(sched["worker"], sched["neighbour"], 0.3, seed=int(rng.integers(1000)))
+    return dict(ident=ident, model=model, n=n, d=d, g=g, T=T, K=K, M=M, rows=rows, momentum=momentum, wd=wd, comp=comp,
                 sched=sched, extra=extra, gam=gam, seed=int(rng.integers(1 << 30)))
 
 
 @pytest.mark.parametrize("block", range(4))
 def test_seeded_sweep_of_small_set_ups(P, block):
     """Random combinations of model, graph, size (ragged and tiny d, both gradient paths), staleness, extra
-    averaging pairs, per-event step sizes, momentum and the wait-free variant, each against the oracle."""
+    averaging pairs, events without averaging, per-event step sizes, momentum and the wait-free variant, each
+    against the oracle."""
     rng = np.random.default_rng(1000 + block)
     for case in range(10):
         c = _random_case(rng)
-        _say("sweep %d/%d: %s n=%d d=%d K=%d M=%d T=%d mom=%g comp=%d extra=%d" % (
-            block, case, c["model"], c["n"], c["d"], c["K"], c["M"], c["T"], c["momentum"], c["comp"], c["extra"] is not None))
+        _say("sweep %d/%d: %s n=%d d=%d K=%d M=%d T=%d mom=%g comp=%d extra=%d ident=%d" % (
+            block, case, c["model"], c["n"], c["d"], c["K"], c["M"], c["T"], c["momentum"], c["comp"], c["extra"] is not None,
+            c["ident"]))
         n, d, M = c["n"], c["d"], c["M"]
         std = float(np.float32(0.1))
         eng = P.Engine(c["g"], d, c["model"], M=M, gamma=0.1, lam=1e-3 if c["model"] == "logreg" else 0.0, T_max=c["T"],
@@ -995,12 +1001,13 @@ def test_least_squares_factored_and_dense_gradient_give_the_same_bits(P, mu, wd)
     """Long least-squares models keep the gradient as its M coefficients until the update kernel applies it;
     the result must be exactly that of the dense path (also with extra averaging pairs, a ragged d and the
     experiments' optimizer), and agree with the oracle."""
-    from workloads import random_extra_pairs
+    from workloads import random_extra_pairs, with_identity_events
     n, d, rows, K, M, T = 10, 4099, 24, 400, 7, 4
     _say("lsq factored vs dense mu=%g" % mu)
     g = random_regular4_graph(n, 6)
     feats, targs, _ = lsq_data(n, rows, d, seed=17, feature_var=1.0 / d)
     sched = oracle.make_schedule(g, K, seed=18, T_max=T, M=M, rows=[rows] * n)
+    sched["neighbour"] = with_identity_events(sched["worker"], sched["neighbour"], 0.2, seed=4)
     sched["extra_pairs"] = random_extra_pairs(g, sched["worker"], sched["neighbour"], max_extra=2, seed=19)
     base = 0.3 if mu == 0.0 else 0.03
     sched["gamma"] = (base * (1 + np.arange(K) % 3)).astype(np.float32)

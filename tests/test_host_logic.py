@@ -158,6 +158,10 @@ def test_planner_keeps_serial_semantics(n, T, graph):
     R_more = _check_plan(n, sched, 4 * (T + 1) + 8)
     assert R_more <= R_min
     _check_plan(n, sched, 0, with_grad=False)
+    from workloads import with_identity_events
+    ident = dict(sched, neighbour=with_identity_events(sched["worker"], sched["neighbour"], 0.3, seed=n))   # W_k = I events
+    assert (ident["neighbour"] == ident["worker"]).sum() > 500
+    assert _check_plan(n, ident, T + 1) <= R_min
     if T > 0:      # fewer slots than the largest staleness + 1 cannot hold the in-flight gradients
         with pytest.raises(P.AdpsgdError):
             P.adpsgd_plan_rounds(n, sched["worker"], sched["neighbour"], sched["tau"], T)
@@ -190,6 +194,8 @@ def test_planned_rounds_reproduce_the_oracle_bit_for_bit():
     g = ring_graph(n)
     feats, targs, _ = lsq_data(n, rows, d, seed=1)
     sched = oracle.make_schedule(g, K, seed=2, T_max=T, M=M, rows=[rows] * n)
+    from workloads import with_identity_events
+    sched["neighbour"] = with_identity_events(sched["worker"], sched["neighbour"], 0.2, seed=5)   # some events have W_k = I
     X_ref = np.zeros((n, d), np.float32)
     X_ref[:] = np.random.default_rng(0).standard_normal(d).astype(np.float32)
     X = X_ref.copy()

@@ -645,6 +645,41 @@ def test_multi_pair_events_keep_the_gradient_semantics():
                        rtol=0, atol=2e-5)
 
 
+def test_identity_events_are_plain_gradient_steps_and_express_a_gradient_queue():
+    """neighbour = worker (W_k = I) on a connected graph.  (1) With every event of that kind and no
+    staleness each worker is textbook minibatch SGD on its own data.  (2) Two gradients queued before one
+    communication step (wait-free appendix, computation thread): the averaging event followed by an
+    identity event that reads the same model gives  avg - gamma (g1 + g2)  with both gradients taken at
+    the worker's model from before the step."""
+    n, rows, d, M, K, gamma = 3, 20, 7, 4, 60, 0.05
+    feats, targs, _ = lsq_data(n, rows, d, seed=8)
+    g = ring_graph(n)
+    sched = oracle.make_schedule(g, K, seed=3, T_max=0, M=M, rows=[rows] * n)
+    sched["neighbour"] = sched["worker"].copy()
+    X0 = np.random.default_rng(2).standard_normal((n, d)).astype(np.float32)
+    X = X0.copy()
+    oracle.run_events(X, sched, LSQ, gamma, M=M, gscale=1.0 / M, features=feats, targets=targs)
+    for i in range(n):
+        x, A, b = X0[i].astype(np.float64), feats[i].astype(np.float64), targs[i].astype(np.float64)
+        for k in np.nonzero(sched["worker"] == i)[0]:
+            idx = sched["batch_idx"][k]
+            x = x - gamma * A[idx].T @ (A[idx] @ x - b[idx]) / M
+        assert np.allclose(X[i], x, rtol=1e-4, atol=1e-5)
+    # (2) worker 0 averages with worker 1 and applies g1 (event 0), then applies the queued g2 (event 1, tau = 1)
+    batch = np.array([[0, 1, 2, 3], [4, 5, 6, 7]], np.int32)
+    queue = {"worker": np.array([0, 0], np.int32), "neighbour": np.array([1, 0], np.int32),
+             "tau": np.array([0, 1], np.int32), "batch_idx": batch}
+    X = X0.copy()
+    oracle.run_events(X, queue, LSQ, gamma, M=M, gscale=1.0 / M, features=feats, targets=targs)
+    x0, A, b = X0[0].astype(np.float64), feats[0].astype(np.float64), targs[0].astype(np.float64)
+    grads = [A[idx].T @ (A[idx] @ x0 - b[idx]) / M for idx in batch]
+    avg = 0.5 * (X0[0].astype(np.float64) + X0[1])
+    assert np.allclose(X[0], avg - gamma * (grads[0] + grads[1]), rtol=1e-5, atol=1e-6)
+    assert np.allclose(X[1], avg, rtol=1e-6, atol=1e-7) and np.array_equal(X[2], X0[2])
+    fresh = A[batch[1]].T @ (A[batch[1]] @ (avg - gamma * grads[0]) - b[batch[1]]) / M
+    assert not np.allclose(X[0], avg - gamma * (grads[0] + fresh), rtol=1e-5, atol=1e-6)   # the pin can tell tau = 1 from 0
+
+
 def test_hop_ring_mixes_faster_than_the_ring():
     """The ring with extra 2^i + 1 hop links (Sec. 3.3.2) has a smaller rho = lambda_2(E W): closed
     form from the circulant Laplacian, and the oracle's gossip-only runs follow (E W)^K."""

@@ -9,4 +9,4 @@ from .graphs import ring_graph, random_regular4_graph, hop_ring_graph, graph_is_
 from .data import (lsq_data, logreg_data, mixture_data, mlp_init, f32_to_bf16_bits,  # noqa: F401
                    bf16_bits_to_f32, linear_data_on_device, mixture_data_on_device)
 from .configs import CONFIGS, get_config  # noqa: F401
-from .schedules import random_extra_pairs  # noqa: F401
+from .schedules import random_extra_pairs, with_identity_events  # noqa: F401

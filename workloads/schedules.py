@@ -35,3 +35,13 @@ def random_extra_pairs(graph, worker, neighbour, max_extra=3, seed=0):
             want -= 1
         ptr.append(len(a))
     return np.asarray(ptr, np.int64), np.asarray(a, np.int32), np.asarray(b, np.int32)
+
+
+def with_identity_events(worker, neighbour, fraction=0.25, seed=0):
+    """A copy of ``neighbour`` in which a random ``fraction`` of the events has neighbour = worker
+    (W_k = I: the gradient is applied without averaging, as for a gradient taken from a queue)."""
+    rng = np.random.default_rng([seed, 22])
+    out = np.array(neighbour, np.int32)
+    pick = rng.random(len(out)) < fraction
+    out[pick] = np.asarray(worker, np.int32)[pick]
+    return out
