@@ -386,3 +386,29 @@ def test_the_abi_is_usable_from_plain_c(tmp_path):
     out = subprocess.run([exe], env=env, capture_output=True, text=True, timeout=60)
     assert out.returncode == 0, (out.returncode, out.stdout, out.stderr)
     assert "c abi ok" in out.stdout
+
+
+# ------------------------------------------------------------------ step-size rules of the experiments (Sec. 5.2, 5.3)
+def test_step_size_rules_of_the_experiments():
+    from paper_1710_06952_amd import step_sizes as ss
+    epe = 40                                    # events per epoch
+    K = 130 * epe
+    halving = ss.step_decay(K, epe, 1.0, factor=0.5, every=25)               # start at 1, halve every 25 epochs
+    assert halving.dtype == np.float32 and len(halving) == K
+    assert halving[0] == 1.0 and halving[25 * epe - 1] == 1.0 and halving[25 * epe] == 0.5
+    assert halving[50 * epe] == 0.25 and halving[-1] == 2.0 ** -5
+    tenth = ss.step_decay(K, epe, 0.1, factor=0.1, milestones=(81, 122))     # /10 at the 81st and the 122nd epoch
+    assert np.all(tenth[:80 * epe] == np.float32(0.1)) and np.isclose(tenth[80 * epe], 0.01)
+    assert np.isclose(tenth[121 * epe - 1], 0.01) and np.isclose(tenth[121 * epe], 0.001)
+    # a run split into calls sees the same values
+    parts = np.concatenate([ss.step_decay(1000, epe, 1.0, k_begin=0), ss.step_decay(K - 1000, epe, 1.0, k_begin=1000)])
+    assert np.array_equal(parts, halving)
+    # warm-up: linear from 0.1 to the scaled step over 5 epochs, untouched afterwards
+    scaled = ss.step_decay(K, epe, 0.8, factor=0.1, milestones=(81, 122))
+    warm = ss.with_linear_warmup(scaled, epe, 5, 0.1)
+    assert warm[0] == np.float32(0.1) and np.all(np.diff(warm[:5 * epe]) > 0)
+    assert np.isclose(warm[5 * epe // 2], 0.45) and np.array_equal(warm[5 * epe:], scaled[5 * epe:])
+    late = ss.with_linear_warmup(ss.step_decay(300, epe, 0.8, k_begin=150), epe, 5, 0.1, k_begin=150)
+    assert np.allclose(late[:50], warm[150:200]) and np.all(late[50:] == np.float32(0.8))
+    with pytest.raises(ValueError):
+        ss.step_decay(10, 0, 1.0)
