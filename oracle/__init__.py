@@ -184,10 +184,13 @@ def run_events(X, schedule, model, gamma, *, M=0, gscale=1.0, lam=0.0, mlp=(0, 0
 
 def run_sync_steps(X, batch_idx, W, model, gamma, *, M=0, gscale=1.0, lam=0.0, mlp=(0, 0, 0),
                    features=None, targets=None, gamma_s=None, synth_std=0.0, synth_seed=0,
-                   event_base=0, coords=None, steps=None, want_loss=False, want_g=False):
+                   event_base=0, coords=None, steps=None, want_loss=False, want_g=False,
+                   momentum=0.0, weight_decay=0.0, V=None):
     """Synchronous comparison schedule (D-PSGD): X <- W X - gamma G(X), IN PLACE, for ``steps``
     iterations (default: batch_idx.shape[0]).  batch_idx is (S, n, M); W is n x n, symmetric and
-    doubly stochastic.  Returns a dict with optional 'loss' (S, n) and 'g' (S, n, d)."""
+    doubly stochastic.  With V (n x d momentum buffers, updated in place) the step uses the
+    experiments' optimizer on the mixed model.  Returns a dict with optional 'loss' (S, n) and
+    'g' (S, n, d)."""
     assert X.dtype == np.float32 and X.flags.c_contiguous and X.ndim == 2
     n, d = X.shape
     W = np.ascontiguousarray(W, dtype=np.float32)
@@ -211,6 +214,8 @@ def run_sync_steps(X, batch_idx, W, model, gamma, *, M=0, gscale=1.0, lam=0.0, m
         coords = np.ascontiguousarray(coords, dtype=np.int64)
         assert coords.size == d
     gs = None if gamma_s is None else np.ascontiguousarray(gamma_s, dtype=np.float32)
+    if V is not None:
+        assert V.dtype == np.float32 and V.flags.c_contiguous and V.shape == X.shape
     loss = np.zeros((S, n), dtype=np.float64) if want_loss else None
     glog = np.zeros((S, n, d), dtype=np.float32) if want_g else None
     rc = lib().oracle_run_sync_steps(
@@ -219,7 +224,7 @@ def run_sync_steps(X, batch_idx, W, model, gamma, *, M=0, gscale=1.0, lam=0.0, m
         fptr, _p(ldf, C.c_int64), tptr, C.c_float(gamma), _p(gs, C.c_float),
         C.c_double(synth_std), C.c_uint64(synth_seed), C.c_uint64(event_base),
         _p(coords, C.c_int64), C.c_int64(S), _p(batch_idx, C.c_int32), _p(W, C.c_float),
-        _p(loss, C.c_double), _p(glog, C.c_float))
+        _p(loss, C.c_double), _p(glog, C.c_float), C.c_float(momentum), C.c_float(weight_decay), _p(V, C.c_float))
     del keep
     if rc != 0:
         raise ValueError("oracle_run_sync_steps failed with code %d" % rc)

@@ -615,6 +615,9 @@ double oracle_consensus_distance(int32_t n, int64_t d, const float* X, int64_t l
 /* Synthetic gradients: worker i at step t uses event number                  */
 /* event_base + t * n + i.  batch_idx is S x n x M; loss (S x n) and g_log    */
 /* (S x n x d) may be NULL.                                                   */
+/* With the experiments' optimizer (V != NULL: n x ldx momentum buffers) the  */
+/* mixed model takes the place of the averaged one in the event's rule:       */
+/*     u = g_i + wd * mixed_i;  v^i <- mu * v^i + u;  X_{t+1}[i] = mixed_i - gamma * v^i */
 /* ------------------------------------------------------------------------- */
 int oracle_run_sync_steps(int32_t n, int64_t d, float* X, int64_t ldx, int model, int M,
                           double gscale, double lambda, int mlp_in, int mlp_hid, int mlp_out,
@@ -622,9 +625,11 @@ int oracle_run_sync_steps(int32_t n, int64_t d, float* X, int64_t ldx, int model
                           const void* const* targets, float gamma, const float* gamma_s,
                           double synth_std, uint64_t synth_seed, uint64_t event_base,
                           const int64_t* coords, int64_t S, const int32_t* batch_idx,
-                          const float* W, double* loss, float* g_log)
+                          const float* W, double* loss, float* g_log,
+                          float momentum, float weight_decay, float* V)
 {
     if (n < 1 || d < 1 || ldx < d || S < 0 || !W) return -1;
+    if (!V && (momentum != 0.0f || weight_decay != 0.0f)) return -1;
     grad_spec spec = { model, d, M, gscale, lambda, mlp_in, mlp_hid, mlp_out };
     data_spec data = { features, ldf, targets };
     float* G = (float*)malloc(sizeof(float) * (size_t)n * (size_t)d);
@@ -649,8 +654,18 @@ int oracle_run_sync_steps(int32_t n, int64_t d, float* X, int64_t ldx, int model
                 double mix = 0.0;
                 for (int32_t j = 0; j < n; ++j) mix += (double)W[(size_t)i * n + j] * (double)X[(size_t)j * ldx + e];
                 float mixed = (float)mix;
-                float step = gam * G[(size_t)i * d + e];
-                Xnew[(size_t)i * d + e] = mixed - step;
+                if (V) {
+                    float decay = weight_decay * mixed;
+                    float u = G[(size_t)i * d + e] + decay;
+                    float carried = momentum * V[(size_t)i * ldx + e];
+                    float v = carried + u;
+                    float step = gam * v;
+                    V[(size_t)i * ldx + e] = v;
+                    Xnew[(size_t)i * d + e] = mixed - step;
+                } else {
+                    float step = gam * G[(size_t)i * d + e];
+                    Xnew[(size_t)i * d + e] = mixed - step;
+                }
             }
         }
         for (int32_t i = 0; i < n; ++i) memcpy(X + (size_t)i * ldx, Xnew + (size_t)i * d, sizeof(float) * (size_t)d);

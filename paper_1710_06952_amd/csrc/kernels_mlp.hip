@@ -12,7 +12,7 @@
 //
 // Launches per group of gradient operations: forward; softmax with the second-layer
 // gradients and the hidden error dH; and, only where a dense gradient is wanted
-// (momentum, the synchronous schedule, the wait-free variant), dW1.  By default dW1
+// (the synchronous schedule, the wait-free variant), dW1.  By default dW1
 // is never written out: dH stays in the pending slot and the kernel that applies the
 // event (section 4 below) forms the rank-M product tile by tile while it updates the
 // model.  The kernels of a round form a serial chain of small grids, so each one

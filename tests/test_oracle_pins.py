@@ -742,6 +742,54 @@ def test_dpsgd_identity_mixing_is_n_independent_sgd_runs():
         assert np.array_equal(xi[0], X[i])
 
 
+def test_dpsgd_with_momentum_reduces_to_the_event_rule_and_to_a_closed_form():
+    """Synchronous schedule with the experiments' optimizer.  (1) W = I: worker i is the single-worker
+    event run with momentum (itself pinned against a library optimizer), bit for bit.  (2) Weight decay
+    acts on the mixed model: with zero gradients one step gives  W X_0 (1 - gamma wd)  and  v = wd W X_0.
+    (3) n = 1 with synthetic gradients: the recursion  v_t = mu v_{t-1} + g_t,  x_t = x_{t-1} - gamma v_t
+    rebuilt in fp64 from the generator's draws.  (4) Zero coefficients leave the plain step."""
+    n, d, rows, M, S, mu, wd = 3, 12, 20, 4, 30, 0.9, 1e-2
+    feats, targs, _ = lsq_data(n, rows, d, seed=4)
+    rng = np.random.default_rng(1)
+    batch = rng.integers(0, rows, size=(S, n, M)).astype(np.int32)
+    X0 = rng.standard_normal((n, d)).astype(np.float32)
+    X, V = X0.copy(), np.zeros_like(X0)
+    oracle.run_sync_steps(X, batch, np.eye(n, dtype=np.float32), LSQ, 0.05, M=M, gscale=1.0 / M,
+                          features=feats, targets=targs, momentum=mu, weight_decay=wd, V=V)
+    for i in range(n):
+        xi, vi = X0[i:i + 1].copy(), np.zeros((1, d), np.float32)
+        sched = {"worker": np.zeros(S, np.int32), "neighbour": np.zeros(S, np.int32), "tau": np.zeros(S, np.int32),
+                 "batch_idx": np.ascontiguousarray(batch[:, i, :])}
+        oracle.run_events(xi, sched, LSQ, 0.05, M=M, gscale=1.0 / M, features=[feats[i]], targets=[targs[i]],
+                          momentum=mu, weight_decay=wd, V=vi)
+        assert np.array_equal(xi[0], X[i]) and np.array_equal(vi[0], V[i])
+    # (2)
+    Wfull = np.full((n, n), 1.0 / n, np.float32)
+    X, V = X0.copy(), np.zeros_like(X0)
+    oracle.run_sync_steps(X, None, Wfull, SYNTH, 0.1, synth_std=0.0, steps=1, momentum=mu, weight_decay=wd, V=V)
+    mixed = Wfull.astype(np.float64) @ X0.astype(np.float64)
+    assert np.allclose(X, mixed * (1 - 0.1 * wd), rtol=1e-6, atol=1e-7)
+    assert np.allclose(V, wd * mixed, rtol=1e-6, atol=1e-9)
+    # (3)
+    S2, gam = 12, 0.05
+    Xs, Vs = np.zeros((1, d), np.float32), np.zeros((1, d), np.float32)
+    oracle.run_sync_steps(Xs, None, np.ones((1, 1), np.float32), SYNTH, gam, synth_std=0.3, synth_seed=5,
+                          event_base=7, steps=S2, momentum=mu, weight_decay=0.0, V=Vs)
+    xs, vs = np.zeros(d), np.zeros(d)
+    for t in range(S2):           # worker 0 of n = 1 draws event 7 + t in step t
+        vs = mu * vs + oracle.synth_grad(5, 7 + t, 0.3, np.arange(d)).astype(np.float64)
+        xs = xs - gam * vs
+    assert np.abs(xs).max() > 0.05
+    assert np.allclose(Xs[0], xs, rtol=1e-5, atol=1e-6) and np.allclose(Vs[0], vs, rtol=1e-5, atol=1e-6)
+    # (4)
+    Xa, Xb, Vb = X0.copy(), X0.copy(), np.zeros_like(X0)
+    Wm = oracle.metropolis_weights(ring_graph(n))
+    oracle.run_sync_steps(Xa, batch, Wm, LSQ, 0.05, M=M, gscale=1.0 / M, features=feats, targets=targs)
+    oracle.run_sync_steps(Xb, batch, Wm, LSQ, 0.05, M=M, gscale=1.0 / M, features=feats, targets=targs,
+                          momentum=0.0, weight_decay=0.0, V=Vb)
+    assert np.array_equal(Xa, Xb)
+
+
 def _path_plus_chord_graph():
     """A small irregular connected graph: path 0-1-2-3-4 plus the edges 1-3 and 1-4 (degrees 1..4)."""
     edges = [(0, 1), (1, 2), (2, 3), (3, 4), (1, 3), (1, 4)]
