@@ -227,8 +227,9 @@ typedef struct {
 
 /* Runs the iterations on the handle's stream (asynchronous, arrays reusable on return).  loss
  * (device, S * n floats, [t][i], or NULL) receives the minibatch losses.  Needs at least n
- * pending-gradient slots in the workspace (data models) and n <= 1024; not available with momentum
- * / weight decay.  Errors as adpsgd_run_events, with no state change. */
+ * pending-gradient slots in the workspace (data models) and n <= 1024.  With momentum / weight
+ * decay the optimizer rule of adpsgd_opts_t acts on the mixed model in place of x_{k+1/2}^i.
+ * Errors as adpsgd_run_events, with no state change. */
 int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* s, float* loss);
 
 /* Host-only: Metropolis mixing weights of a graph, w_edge[e] = 1 / (1 + max(deg i, deg j)) for the

@@ -15,7 +15,6 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
     const bool with_grad = h->o.model != ADPSGD_MODEL_SYNTH;
     const int32_t M = with_grad ? h->o.M : 0;
     if (S * n > 0x7FFFFFF0) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: S * n must stay below 2^31 - 16");
-    if (h->o.V) return fail(h, ADPSGD_ERR_STATE, "run_sync_steps: not available with momentum / weight decay");
     if (sync_tile_cols(n) == 0) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: at most 1024 workers");
     if (with_grad && !s->batch_idx) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: batch_idx is NULL");
     if (with_grad && h->n_slots < n)
@@ -140,7 +139,8 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
                    reinterpret_cast<const float*>(dev + off_ws), reinterpret_cast<const float*>(dev + off_we),
                    with_grad ? slots : nullptr, h->o.model == ADPSGD_MODEL_MLP ? h->o.Xbf16 : nullptr,
                    s->gamma ? s->gamma[t] : h->o.gamma, h->o.synth_std, h->o.synth_seed,
-                   h->events_done + static_cast<uint64_t>(t) * static_cast<uint64_t>(n), !with_grad};
+                   h->events_done + static_cast<uint64_t>(t) * static_cast<uint64_t>(n), !with_grad,
+                   h->o.V, h->o.momentum, h->o.weight_decay};
         HIP_TRY(h, launch_sync_mix_apply(a, h->stream));
         ++h->stats.fused_launches;
         if (profile) {

@@ -185,6 +185,8 @@ struct SyncArgs {
     uint64_t synth_seed;
     uint64_t event0;         // synthetic gradients: worker i draws event event0 + i
     bool synth;
+    float* V;                // momentum buffers or nullptr
+    float momentum, weight_decay;
 };
 int32_t sync_tile_cols(int32_t n);   // 0: n too large for the in-place mixing kernel
 hipError_t launch_sync_mix_apply(const SyncArgs& a, hipStream_t st);

@@ -3,12 +3,15 @@
 // its model with its neighbours while its gradient (taken at the model the
 // iteration started from) is computed, then applies that gradient:
 //     X[i] <- w_self[i] X[i] + sum_{j in N(i)} w_edge[i,j] X[j] - gamma g_i
-// with a symmetric doubly stochastic weight matrix on the graph's edges.
+// with a symmetric doubly stochastic weight matrix on the graph's edges.  With the
+// experiments' optimizer (Sec. 5.2) the mixed model takes the place of the event's
+// averaged model:  u = g_i + wd * mixed;  v_i <- mu v_i + u;  X[i] <- mixed - gamma v_i.
 //
 // Every column evolves independently of the others, so the iteration runs in
 // place: a block stages all n rows of a tile of 16..256 columns in LDS, then
 // writes each row's mixture straight back to X.  HBM traffic is one
-// read and one write of X (plus one read of the gradients for the data models).
+// read and one write of X (plus one read of the gradients for the data models, and a
+// read and a write of the momentum buffers when they are in use).
 #include "device_common.hpp"
 #include "internal.hpp"
 
@@ -33,10 +36,12 @@ struct SyncParams {
     float synth_std;
     uint32_t key0, key1;
     uint64_t event0;           // synthetic gradients: worker i draws event event0 + i
+    float* V;                  // momentum buffers (MOM), else nullptr
+    float momentum, weight_decay;
 };
 
 // grid = ceil(d / cols); thread = (quad of 4 columns, row lane)
-template <bool SYNTH, bool SHADOW>
+template <bool SYNTH, bool SHADOW, bool MOM>
 __global__ __launch_bounds__(kThreads) void sync_mix_apply_kernel(const SyncParams p) {
     extern __shared__ __attribute__((aligned(16))) float tile[];   // [n][cols]
     const int quads = p.cols >> 2;
@@ -65,7 +70,24 @@ __global__ __launch_bounds__(kThreads) void sync_mix_apply_kernel(const SyncPara
             g = *reinterpret_cast<const v4f*>(p.slots + static_cast<int64_t>(i) * p.ld + c);
         }
         v4f out;
-        {
+        if (MOM) {
+            float* __restrict__ vrow = p.V + static_cast<int64_t>(i) * p.ld + c;
+            const v4f vo = *reinterpret_cast<const v4f*>(vrow);
+            const float mixed[4] = {acc.x, acc.y, acc.z, acc.w}, gv[4] = {g.x, g.y, g.z, g.w}, vold[4] = {vo.x, vo.y, vo.z, vo.w};
+            float xn[4], unused[4], vn[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)      // the event's rule with both rows equal to the mixed model
+                average_then_apply_momentum(mixed[t], mixed[t], gv[t], vold[t], p.gamma, p.momentum, p.weight_decay,
+                                            xn[t], unused[t], vn[t]);
+            out = v4f{xn[0], xn[1], xn[2], xn[3]};
+            v4f vout = {vn[0], vn[1], vn[2], vn[3]};
+            if (c + 4 > p.d) {     // keep the padding beyond d at zero
+                if (c + 1 >= p.d) vout.y = 0.0f;
+                if (c + 2 >= p.d) vout.z = 0.0f;
+                if (c + 3 >= p.d) vout.w = 0.0f;
+            }
+            *reinterpret_cast<v4f*>(vrow) = vout;
+        } else {
 #pragma clang fp contract(off)
             const v4f step = g * p.gamma;
             out = acc - step;
@@ -81,6 +103,14 @@ __global__ __launch_bounds__(kThreads) void sync_mix_apply_kernel(const SyncPara
             *reinterpret_cast<v4h*>(p.Xbf16 + static_cast<int64_t>(i) * p.ld + c) = hb;
         }
     }
+}
+
+template <bool MOM>
+hipError_t launch_variant(const SyncParams& p, bool synth, dim3 grid, size_t lds, hipStream_t st) {
+    if (synth) hipLaunchKernelGGL((sync_mix_apply_kernel<true, false, MOM>), grid, dim3(kThreads), lds, st, p);
+    else if (p.Xbf16) hipLaunchKernelGGL((sync_mix_apply_kernel<false, true, MOM>), grid, dim3(kThreads), lds, st, p);
+    else hipLaunchKernelGGL((sync_mix_apply_kernel<false, false, MOM>), grid, dim3(kThreads), lds, st, p);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -120,10 +150,10 @@ hipError_t launch_sync_mix_apply(const SyncArgs& a, hipStream_t st) {
     if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
     const size_t lds = static_cast<size_t>(a.n) * cols * 4;
     const dim3 grid(static_cast<uint32_t>(blocks));
-    if (a.synth) hipLaunchKernelGGL((sync_mix_apply_kernel<true, false>), grid, dim3(kThreads), lds, st, p);
-    else if (a.Xbf16) hipLaunchKernelGGL((sync_mix_apply_kernel<false, true>), grid, dim3(kThreads), lds, st, p);
-    else hipLaunchKernelGGL((sync_mix_apply_kernel<false, false>), grid, dim3(kThreads), lds, st, p);
-    return hipGetLastError();
+    p.V = a.V;
+    p.momentum = a.momentum;
+    p.weight_decay = a.weight_decay;
+    return a.V ? launch_variant<true>(p, a.synth, grid, lds, st) : launch_variant<false>(p, a.synth, grid, lds, st);
 }
 
 }  // namespace adpsgd_impl

@@ -690,6 +690,65 @@ def test_sync_steps_mlp(P):
     eng.close()
 
 
+@pytest.mark.parametrize("model,n,d", [("synth", 16, 5003), ("synth", 200, 130), ("lsq", 12, 4099), ("mlp", 6, 0)])
+def test_sync_steps_with_momentum_and_weight_decay(P, model, n, d):
+    """The synchronous schedule with the experiments' optimizer: models and momentum buffers against the
+    oracle, followed by asynchronous events on the same buffers."""
+    from workloads import mixture_data, mlp_init
+    _say("sync steps with momentum, %s n=%d" % (model, n))
+    mu, wd, S, gamma = 0.9, 1e-3, 25, 0.05
+    g = ring_graph(n) if n > 100 else random_regular4_graph(n, 2) if n >= 8 else ring_graph(n)
+    rng = np.random.default_rng(3)
+    W = oracle.metropolis_weights(g)
+    std = float(np.float32(0.05))
+    if model == "synth":
+        eng = P.Engine(g, d, "synth", gamma=gamma, T_max=2, synth_std=std, synth_seed=3, momentum=mu, weight_decay=wd)
+        x0 = rng.standard_normal((n, d)).astype(np.float32)
+        eng.set_models(x0, broadcast=False)
+        eng.run_sync_steps(S)
+        Xr, Vr = x0.copy(), np.zeros_like(x0)
+        oracle.run_sync_steps(Xr, None, W, oracle.MODEL_SYNTH, gamma, synth_std=std, synth_seed=3, steps=S,
+                              momentum=mu, weight_decay=wd, V=Vr)
+        tol = TOL
+    elif model == "lsq":
+        rows, M = 24, 6
+        feats, targs, _ = lsq_data(n, rows, d, seed=3, feature_var=1.0 / d)
+        batch = rng.integers(0, rows, size=(S, n, M)).astype(np.int32)
+        x0 = rng.standard_normal((n, d)).astype(np.float32)
+        eng = P.Engine(g, d, "lsq", M=M, gamma=gamma, n_slots=n, T_max=2, momentum=mu, weight_decay=wd)
+        eng.load_data(feats, targs)
+        eng.set_models(x0, broadcast=False)
+        eng.run_sync_steps(S, batch)
+        Xr, Vr = x0.copy(), np.zeros_like(x0)
+        oracle.run_sync_steps(Xr, batch, W, oracle.MODEL_LSQ, gamma, M=M, gscale=1.0 / M, features=feats, targets=targs,
+                              momentum=mu, weight_decay=wd, V=Vr)
+        tol = TOL
+    else:
+        dims, rows, M = (24, 64, 5), 40, 16
+        feats, labels, _ = mixture_data(n, rows, din=dims[0], classes=dims[2], seed=5)
+        d = dims[0] * dims[1] + dims[1] + dims[1] * dims[2] + dims[2]
+        x0 = np.tile(mlp_init(*dims, seed=5), (n, 1))
+        batch = rng.integers(0, rows, size=(S, n, M)).astype(np.int32)
+        eng = P.Engine(g, d, "mlp", M=M, gamma=0.01, mlp=dims, n_slots=n, momentum=mu, weight_decay=wd)
+        eng.load_data(feats, labels)
+        eng.set_models(x0, broadcast=False)
+        eng.run_sync_steps(S, batch)
+        Xr, Vr = x0.copy(), np.zeros_like(x0)
+        oracle.run_sync_steps(Xr, batch, W, oracle.MODEL_MLP, 0.01, M=M, gscale=1.0 / M, mlp=dims, features=feats,
+                              targets=labels, momentum=mu, weight_decay=wd, V=Vr)
+        tol = MLP_TOL_MASTER
+    assert np.abs(Vr).max() > 0
+    assert rel_err(eng.get_models(), Xr) <= tol
+    assert rel_err(eng.get_momentum(), Vr) <= 5 * tol
+    if model == "synth":      # asynchronous events continue on the same models and buffers
+        sched = oracle.make_schedule(g, 60, seed=4, T_max=2)
+        eng.run_events(sched)
+        oracle.run_events(Xr, sched, oracle.MODEL_SYNTH, gamma, synth_std=std, synth_seed=3, event_base=S * n,
+                          momentum=mu, weight_decay=wd, V=Vr)
+        assert rel_err(eng.get_models(), Xr) <= TOL and rel_err(eng.get_momentum(), Vr) <= 5 * TOL
+    eng.close()
+
+
 def test_sync_steps_validation(P):
     g = ring_graph(4)
     eng = P.Engine(g, 64, "synth", gamma=0.1, synth_std=0.1)
