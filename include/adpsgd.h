@@ -122,7 +122,9 @@ typedef struct {
      * where k' is the latest earlier event of worker i_k in the same call, taken when
      * k' - tau_k' <= k - tau_k <= k' (else no compensation).  Ignored by SYNTH, whose gradients do
      * not depend on the model; the MLP reads bf16(x^_k) and keeps its pending gradients dense for
-     * it; not with momentum or weight decay (ADPSGD_ERR_ARG). */
+     * it.  With momentum or weight decay the compensation stays this line (the computation thread
+     * holds the buffered gradient and the step size, nothing of the optimizer); only the update
+     * follows the optimizer's rule. */
     int32_t local_compensation;
 } adpsgd_opts_t;
 

@@ -143,10 +143,6 @@ extern "C" int adpsgd_create(adpsgd_t** out, const adpsgd_graph_t* graph, int64_
         return fail(nullptr, ADPSGD_ERR_ARG, "create: momentum or weight_decay not finite");
     if ((o.momentum != 0.0f || o.weight_decay != 0.0f) && (!o.V || !aligned16(o.V)))
         return fail(nullptr, ADPSGD_ERR_ARG, "create: momentum / weight decay need the buffer V (16-byte aligned)");
-    if (o.local_compensation) {
-        if (o.momentum != 0.0f || o.weight_decay != 0.0f)
-            return fail(nullptr, ADPSGD_ERR_ARG, "create: local_compensation cannot be combined with momentum or weight decay");
-    }
     int count = 0;
     if (hipGetDeviceCount(&count) != hipSuccess || count < 1)
         return fail(nullptr, ADPSGD_ERR_HIP, "create: no HIP device available");

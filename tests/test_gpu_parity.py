@@ -590,15 +590,43 @@ def test_waitfree_local_compensation_mlp(P):
     eng.close()
 
 
-def test_waitfree_variant_is_refused_where_it_is_not_defined(P):
-    import torch
-    X = torch.zeros((4, 64), device="cuda")
-    V = torch.zeros((4, 64), device="cuda")
-    W = torch.zeros((4, 64), device="cuda")
-    with pytest.raises(P.AdpsgdError) as ei:
-        P.Handle(ring_graph(4), 64, model=P.MODEL_LSQ, X_ptr=X.data_ptr(), ldx=64, M=2, gamma=0.1, momentum=0.9,
-                 V_ptr=V.data_ptr(), workspace_ptr=W.data_ptr(), workspace_bytes=4 * 64 * 4, local_compensation=True)
-    assert ei.value.code == -1
+@pytest.mark.parametrize("model", ["lsq", "logreg", "mlp"])
+def test_waitfree_variant_with_momentum(P, model):
+    """Compensation with the buffered gradient, update with the optimizer's rule: models and momentum
+    buffers against the oracle, and not what either option gives alone."""
+    from workloads import mixture_data, mlp_init
+    _say("wait-free variant with momentum, %s" % model)
+    mu, wd = 0.9, 1e-3
+    if model == "mlp":
+        n, dims, rows, K, M, T, gamma, lam = 4, (24, 64, 5), 40, 250, 16, 5, 0.02, 0.0
+        d = dims[0] * dims[1] + dims[1] + dims[1] * dims[2] + dims[2]
+        feats, targs, _ = mixture_data(n, rows, din=dims[0], classes=dims[2], seed=14)
+        x0, omodel, tol = mlp_init(*dims, seed=14), oracle.MODEL_MLP, MLP_TOL_MASTER
+    else:
+        n, d, rows, K, M, T, dims = 6, 4099, 32, 300, 5, 4, (0, 0, 0)
+        if model == "lsq":
+            feats, targs, _ = lsq_data(n, rows, d, seed=12, feature_var=1.0 / d)
+            omodel, gamma, lam = oracle.MODEL_LSQ, 0.1, 0.0
+        else:
+            feats, targs, _ = logreg_data(n, rows, d, seed=12)
+            omodel, gamma, lam = oracle.MODEL_LOGREG, 0.5, 1e-3
+        x0, tol = np.random.default_rng(4).standard_normal(d).astype(np.float32), TOL
+    g = ring_graph(n)
+    sched = oracle.make_schedule(g, K, seed=13, T_max=T, M=M, rows=[rows] * n)
+    eng = P.Engine(g, d, model, M=M, gamma=gamma, lam=lam, T_max=T, mlp=dims, local_compensation=True,
+                   momentum=mu, weight_decay=wd)
+    eng.load_data(feats, targs)
+    eng.set_models(x0)
+    eng.run_events(sched)
+    Xg, Vg = eng.get_models(), eng.get_momentum()
+    kw = dict(M=M, gscale=1.0 / M, lam=lam, mlp=dims, features=feats, targets=targs, momentum=mu, weight_decay=wd)
+    Xr, Vr = np.tile(x0, (n, 1)), np.zeros((n, d), np.float32)
+    oracle.run_events(Xr, sched, omodel, gamma, local_compensation=True, V=Vr, **kw)
+    assert rel_err(Xg, Xr) <= tol and rel_err(Vg, Vr) <= 5 * tol
+    Xp, Vp = np.tile(x0, (n, 1)), np.zeros((n, d), np.float32)
+    oracle.run_events(Xp, sched, omodel, gamma, V=Vp, **kw)
+    assert rel_err(Xg, Xp) > 3 * tol           # the compensation is not a no-op on this schedule
+    eng.close()
 
 
 # ------------------------------------------------------------------ synchronous comparison schedule (D-PSGD)
@@ -828,7 +856,7 @@ def _random_case(rng):
     rows = int(rng.integers(M + 1, 40)) if M else 0
     momentum = float(rng.choice([0.0, 0.0, 0.9]))
     wd = float(rng.choice([0.0, 1e-3])) if momentum else 0.0
-    comp = bool(model != "synth" and momentum == 0.0 and rng.integers(2))
+    comp = bool(model != "synth" and rng.integers(2))
     sched = oracle.make_schedule(g, K, seed=int(rng.integers(1 << 30)), T_max=T, M=M, rows=[rows] * n if M else None)
     extra = None
     if n >= 6 and rng.integers(2):

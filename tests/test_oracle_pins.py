@@ -243,6 +243,25 @@ def test_waitfree_hand_expanded(golden_dir):
             assert (X[0, 0], X[1, 0]) == (e0, e1), (name, mode, X.ravel())
 
 
+def test_waitfree_compensation_with_momentum_uses_the_buffered_gradient():
+    """The computation thread of the wait-free appendix holds the buffered gradient g and the step size,
+    nothing of the optimizer: its compensation stays  x - gamma g  when the update itself uses momentum.
+    One worker, f(x) = x^2 / 2 (gradient x), gamma = mu = 1/2, x_0 = 1, tau = (0, 1, 1), by hand:
+      event 0: g = 1,    v = 1,    x = 1/2
+      event 1: reads 1,   compensated with g_0: 1/2;  g = 1/2;  v = 1/2 + 1/2 = 1;  x = 1/2 - 1/2 = 0
+      event 2: reads 1/2, compensated with g_1: 1/4;  g = 1/4;  v = 1/2 + 1/4 = 3/4;  x = 0 - 3/8 = -3/8
+    (compensating with gamma v_1 instead would read 0 and end at -1/4; without compensation event 1 has
+    g = 1, v = 3/2, x = -1/4 and event 2 has g = 1/2, v = 5/4, x = -7/8)."""
+    feats, targs = _unit_quadratic_data(1, [1.0])
+    sched = {"worker": [0, 0, 0], "neighbour": [0, 0, 0], "tau": [0, 1, 1], "batch_idx": np.zeros((3, 1), np.int32)}
+    for comp, want_x, want_v in ((True, -0.375, 0.75), (False, -0.875, 1.25)):
+        for mode in (0, 1):
+            X, V = np.array([[1.0]], np.float32), np.zeros((1, 1), np.float32)
+            oracle.run_events(X, sched, LSQ, 0.5, M=1, gscale=1.0, features=feats, targets=targs, mode=mode,
+                              momentum=0.5, weight_decay=0.0, V=V, local_compensation=comp)
+            assert (X[0, 0], V[0, 0]) == (want_x, want_v), (comp, mode, X, V)
+
+
 @pytest.mark.parametrize("model", [LSQ, LOGREG])
 def test_waitfree_single_worker_is_fresh_sgd(model):
     """One worker, no neighbour, every gradient one event stale: the compensated read
