@@ -842,6 +842,36 @@ def test_mlp_factored_and_dense_first_layer_gradient_give_the_same_bits(P, mu, w
     assert out[0][3] * 3 == out[1][3] * 2          # two launches per gradient set instead of three
 
 
+# ------------------------------------------------------------------ many workers: hundreds of operations per launch
+@pytest.mark.parametrize("model,n,d,K,T", [("synth", 1000, 300, 20000, 8), ("lsq", 500, 2100, 6000, 6), ("lsq", 600, 130, 6000, 6),
+                                           ("logreg", 400, 2500, 4000, 5)])
+def test_many_workers_fill_the_rounds(P, model, n, d, K, T):
+    """Large rings: a round carries a few hundred pairs and gradient operations (the second grid
+    dimension of every kernel), on each gradient path."""
+    _say("many workers %s n=%d d=%d" % (model, n, d))
+    g = ring_graph(n)
+    std = float(np.float32(0.05))
+    rows, M = (6, 3) if model != "synth" else (0, 0)
+    sched = oracle.make_schedule(g, K, seed=31, T_max=T, M=M, rows=[rows] * n if M else None)
+    lam = 1e-3 if model == "logreg" else 0.0
+    eng = P.Engine(g, d, model, M=M, gamma=0.1, lam=lam, T_max=T, synth_std=std, synth_seed=9, verify_plan=True)
+    x0 = np.random.default_rng(8).standard_normal((n, d)).astype(np.float32)
+    kw = {}
+    if model != "synth":
+        feats, targs, _ = (lsq_data(n, rows, d, seed=6, feature_var=1.0 / d) if model == "lsq" else logreg_data(n, rows, d, seed=6))
+        eng.load_data(feats, targs)
+        kw = dict(M=M, gscale=1.0 / M, lam=lam, features=feats, targets=targs)
+    eng.set_models(x0, broadcast=False)
+    eng.run_events(sched)
+    st = eng.get_stats()
+    assert st["max_round_pairs"] >= n // 8 and st["rounds"] < K // 20
+    Xr = x0.copy()
+    omodel = {"synth": oracle.MODEL_SYNTH, "lsq": oracle.MODEL_LSQ, "logreg": oracle.MODEL_LOGREG}[model]
+    oracle.run_events(Xr, sched, omodel, 0.1, synth_std=std, synth_seed=9, **kw)
+    assert rel_err(eng.get_models(), Xr) <= TOL
+    eng.close()
+
+
 # ------------------------------------------------------------------ seeded sweep over small random set-ups
 def _random_case(rng):
     from workloads import hop_ring_graph, random_extra_pairs, with_identity_events
