@@ -256,6 +256,33 @@ def test_config3_full_size_sampled_coordinates(P):
     eng.close()
 
 
+def test_parameter_index_beyond_32_bits(P):
+    """d = 2^31 + 4101: element indices and byte offsets inside one replica exceed 32 bits (25.8 GB of
+    models for 3 workers).  Models start at zero as allocated; the oracle follows sampled coordinates
+    around the 2^31 boundary, both ends and random places."""
+    import torch
+    n, d, K, T = 3, (1 << 31) + 4101, 40, 2
+    _say("d beyond 2^31: n=%d d=%d" % (n, d))
+    g = ring_graph(n)
+    std = float(np.float32(0.05))
+    eng = P.Engine(g, d, "synth", gamma=0.25, T_max=T, synth_std=std, synth_seed=77)
+    sched = oracle.make_schedule(g, K, seed=5, T_max=T)
+    eng.run_events(sched)
+    rng = np.random.default_rng(1)
+    edge = (1 << 31) + np.arange(-4, 5)
+    coords = np.unique(np.concatenate([[0, 1, 2, 3, 1023, 1024, d - 3, d - 2, d - 1], edge, rng.integers(0, d, 1500)])).astype(np.int64)
+    Xg = eng.X[:, torch.from_numpy(coords).to("cuda:0")].cpu().numpy()
+    Xr = np.zeros((n, coords.size), np.float32)
+    oracle.run_events(Xr, sched, oracle.MODEL_SYNTH, 0.25, synth_std=std, synth_seed=77, coords=coords)
+    assert np.abs(Xr).max() > 0.01
+    assert rel_err(Xg, Xr) <= TOL
+    assert not eng.X[:, d:].any().item()               # the padding of the rows stays zero
+    assert eng.count_nonfinite() == 0
+    eng.close()
+    del eng
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ two-layer perceptron (bf16 + MFMA)
 # Tolerances.  The hidden activations and their back-propagated error are rounded to bf16 before the
 # two matrix-core products.  The oracle accumulates the pre-activations in fp64, the kernel in fp32
