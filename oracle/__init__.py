@@ -44,6 +44,7 @@ def lib():
         _lib = C.CDLL(str(build()))
         _lib.oracle_minibatch_gradient.restype = C.c_double
         _lib.oracle_consensus_distance.restype = C.c_double
+        _lib.oracle_count_misclassified.restype = C.c_int64
     return _lib
 
 
@@ -118,6 +119,20 @@ def minibatch_gradient(model, xhat, features, targets, idx, gscale, lam=0.0, mlp
         C.c_void_p(features.ctypes.data), C.c_int64(features.shape[1]),
         C.c_void_p(targets.ctypes.data), _p(idx, C.c_int32), _p(g, C.c_float))
     return g, loss
+
+
+def count_misclassified(model, x, features, targets, mlp=(0, 0, 0)):
+    """Rows of one worker's data whose predicted label (sign of a.x, or the largest logit of the
+    perceptron) differs from the target."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    assert features.flags.c_contiguous and targets.flags.c_contiguous
+    wrong = lib().oracle_count_misclassified(
+        C.c_int(model), C.c_int64(x.size), C.c_int(mlp[0]), C.c_int(mlp[1]), C.c_int(mlp[2]), _p(x, C.c_float),
+        C.c_void_p(features.ctypes.data), C.c_int64(features.shape[1]), C.c_void_p(targets.ctypes.data),
+        C.c_int64(features.shape[0]))
+    if wrong < 0:
+        raise ValueError("count_misclassified: the model has no labels")
+    return int(wrong)
 
 
 def run_events(X, schedule, model, gamma, *, M=0, gscale=1.0, lam=0.0, mlp=(0, 0, 0),

@@ -385,6 +385,68 @@ double oracle_minibatch_gradient(int model, int64_t d, int M, double gscale, dou
 }
 
 /* ------------------------------------------------------------------------- */
+/* Classification error of a model on one worker's rows (the quantity behind   */
+/* the accuracy tables of the experiments section: error = 1 - accuracy).      */
+/*   logistic regression: predicted label = +1 if a.x >= 0 else -1;           */
+/*   perceptron: predicted class = the largest logit of the same forward pass  */
+/*   as the gradient's (bf16 weights and inputs, hidden activations rounded to */
+/*   bf16), the lowest class on ties.                                          */
+/* Returns the number of rows whose prediction differs from the target, or -1 */
+/* for a model without labels.                                                 */
+/* ------------------------------------------------------------------------- */
+int64_t oracle_count_misclassified(int model, int64_t d, int mlp_in, int mlp_hid, int mlp_out,
+                                   const float* x, const void* features, int64_t ldf,
+                                   const void* targets, int64_t rows)
+{
+    int64_t wrong = 0;
+    if (model == MODEL_LOGREG) {
+        const float* A = (const float*)features;
+        const float* y = (const float*)targets;
+        for (int64_t r = 0; r < rows; ++r) {
+            double z = 0.0;
+            for (int64_t e = 0; e < d; ++e) z += (double)A[r * ldf + e] * (double)x[e];
+            const float predicted = z >= 0.0 ? 1.0f : -1.0f;
+            wrong += predicted != y[r];
+        }
+        return wrong;
+    }
+    if (model != MODEL_MLP) return -1;
+    const int I = mlp_in, H = mlp_hid, O = mlp_out;
+    const uint16_t* Xin = (const uint16_t*)features;
+    const int32_t* label = (const int32_t*)targets;
+    float* wq = (float*)malloc(sizeof(float) * (size_t)d);
+    double* pre = (double*)malloc(sizeof(double) * (size_t)H);
+    float* hid = (float*)malloc(sizeof(float) * (size_t)H);
+    for (int64_t t = 0; t < d; ++t) wq[t] = round_bf16(x[t]);
+    const float* W1 = wq;
+    const float* b1 = W1 + (int64_t)I * H;
+    const float* W2 = b1 + H;
+    const float* b2 = W2 + (int64_t)H * O;
+    for (int64_t r = 0; r < rows; ++r) {
+        const uint16_t* xin = Xin + r * ldf;
+        for (int h = 0; h < H; ++h) pre[h] = 0.0;
+        for (int i = 0; i < I; ++i) {
+            const double xi = (double)bf16_to_f32(xin[i]);
+            for (int h = 0; h < H; ++h) pre[h] += xi * (double)W1[(int64_t)i * H + h];
+        }
+        for (int h = 0; h < H; ++h) {
+            float a = (float)(pre[h] + (double)b1[h]);
+            hid[h] = round_bf16(a > 0.0f ? a : 0.0f);
+        }
+        int best = 0;
+        double zbest = -INFINITY;
+        for (int o = 0; o < O; ++o) {
+            double acc = (double)b2[o];
+            for (int h = 0; h < H; ++h) acc += (double)hid[h] * (double)W2[(int64_t)h * O + o];
+            if (acc > zbest) { zbest = acc; best = o; }
+        }
+        wrong += best != label[r];
+    }
+    free(wq); free(pre); free(hid);
+    return wrong;
+}
+
+/* ------------------------------------------------------------------------- */
 /* One event's model update (Algorithm 1, averaging step then update step):   */
 /*   x_{k+1/2} = X_k W_k   : rows i and j both become (x^i + x^j)/2           */
 /*   x^i_{k+1} = x^i_{k+1/2} - gamma g_k ;  every other row = its k+1/2 value */

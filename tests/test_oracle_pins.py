@@ -192,6 +192,41 @@ def bf16_round_np(x):
     return oracle.round_bf16(x)
 
 
+def test_classification_error_counts():
+    """Predicted labels.  Logistic regression against numpy (sign of a.x, zero counts as +1).  The perceptron:
+    a hand-made 2-2-2 network whose logits are relu(x) (prediction = index of the larger positive input,
+    class 0 on ties), and the link to the loss on random data: a sample whose cross-entropy is below
+    ln 2 has more than half of the probability on its label, so it cannot be counted as misclassified,
+    and one whose loss exceeds ln(number of classes) has less than the uniform share, so it must be."""
+    from workloads import mixture_data, mlp_init, f32_to_bf16_bits
+    feats, targs, _ = logreg_data(1, 200, 33, seed=9)
+    x = np.random.default_rng(2).standard_normal(33).astype(np.float32)
+    want = int((np.where(feats[0].astype(np.float64) @ x.astype(np.float64) >= 0, 1.0, -1.0) != targs[0]).sum())
+    assert 0 < want < 200 and oracle.count_misclassified(LOGREG, x, feats[0], targs[0]) == want
+    assert oracle.count_misclassified(LOGREG, np.zeros(33, np.float32), feats[0], targs[0]) == int((targs[0] < 0).sum())
+    with pytest.raises(ValueError):
+        oracle.count_misclassified(LSQ, x, feats[0], targs[0])
+    # W1 = I, b1 = 0, W2 = I, b2 = 0
+    net = np.array([1, 0, 0, 1, 0, 0, 1, 0, 0, 1, 0, 0], np.float32)
+    pts = np.array([[2.0, 1.0], [1.0, 2.0], [-1.0, -3.0], [0.5, 0.5], [-1.0, 0.25], [3.0, -1.0]], np.float32)
+    predicted = np.array([0, 1, 0, 0, 1, 0], np.int32)
+    xin = f32_to_bf16_bits(pts)
+    assert oracle.count_misclassified(MLP, net, xin, predicted, mlp=(2, 2, 2)) == 0
+    for flip in range(len(pts)):
+        labels = predicted.copy()
+        labels[flip] ^= 1
+        assert oracle.count_misclassified(MLP, net, xin, labels, mlp=(2, 2, 2)) == 1
+    # link to the loss
+    dims = (8, 16, 4)
+    f, lab, _ = mixture_data(1, 120, din=dims[0], classes=dims[2], seed=3)
+    w = mlp_init(*dims, seed=3) * np.float32(3.0)
+    losses = np.array([oracle.minibatch_gradient(MLP, w, f[0], lab[0], np.array([r]), 1.0, mlp=dims)[1] for r in range(120)])
+    per_row = np.array([oracle.count_misclassified(MLP, w, f[0][r:r + 1], lab[0][r:r + 1], mlp=dims) for r in range(120)])
+    assert oracle.count_misclassified(MLP, w, f[0], lab[0], mlp=dims) == per_row.sum()
+    assert (losses < np.log(2)).any() and (losses > np.log(dims[2])).any()
+    assert not per_row[losses < np.log(2)].any() and per_row[losses > np.log(dims[2])].all()
+
+
 def test_bf16_rounding_is_nearest_even():
     import torch
     rng = np.random.default_rng(4)
