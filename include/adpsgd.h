@@ -259,6 +259,14 @@ int adpsgd_consensus_distance(adpsgd_t* h, double* out);
  * row once. */
 int adpsgd_objective(adpsgd_t* h, const float* x, double* out);
 
+/* Classification error at one point, 1 - accuracy (the quantity of the accuracy tables of the
+ * experiments section, here over the loaded local data):
+ *     (1/n) sum_i (1/rows_i) #{rows of worker i whose predicted label differs from the target}
+ * LOGREG predicts +1 when a.x >= 0 and -1 otherwise; the MLP predicts the class of its largest
+ * logit (the lowest class on ties), from the same forward pass as its gradient.  x, *out, cost and
+ * errors as for adpsgd_objective; ADPSGD_ERR_STATE for SYNTH and LSQ, which have no labels. */
+int adpsgd_classification_error(adpsgd_t* h, const float* x, double* out);
+
 /* Divergence check: the number of entries of the models that are NaN or infinite (0 for a healthy
  * run; a step size beyond the stability limit shows up here long before anything else fails).
  * *out is host memory.  Synchronous; reads X once. */

@@ -20,7 +20,7 @@ FLAG_PROFILE, FLAG_DENSE_GRADIENT, FLAG_VERIFY_PLAN = 1, 2, 4
 EXPORTS = [
     "adpsgd_create", "adpsgd_destroy", "adpsgd_last_error", "adpsgd_load_data", "adpsgd_set_models",
     "adpsgd_run_events", "adpsgd_get_models", "adpsgd_get_mean_model", "adpsgd_consensus_distance",
-    "adpsgd_get_bf16_models", "adpsgd_get_momentum", "adpsgd_get_stats", "adpsgd_make_schedule", "adpsgd_plan_rounds",
+    "adpsgd_get_bf16_models", "adpsgd_classification_error", "adpsgd_get_momentum", "adpsgd_get_stats", "adpsgd_make_schedule", "adpsgd_plan_rounds",
     "adpsgd_synth_gradient", "adpsgd_run_sync_steps", "adpsgd_metropolis_weights",
     "adpsgd_get_event_count", "adpsgd_set_event_count", "adpsgd_verify_plan", "adpsgd_objective", "adpsgd_count_nonfinite",
 ]
@@ -119,6 +119,7 @@ def lib():
         L.adpsgd_verify_plan.argtypes = [i32, i64, P(i32), P(i32), P(i32), i32, i32, P(i32), P(i32), P(i32), i32,
                                          P(i64), P(i32), P(i32), P(i64)]
         L.adpsgd_objective.argtypes = [vp, vp, P(C.c_double)]
+        L.adpsgd_classification_error.argtypes = [vp, vp, P(C.c_double)]
         L.adpsgd_count_nonfinite.argtypes = [vp, P(i64)]
         L.adpsgd_get_event_count.argtypes = [vp, P(u64)]
         L.adpsgd_set_event_count.argtypes = [vp, u64]
@@ -322,6 +323,12 @@ class Handle:
         """f at a device vector (integer pointer), or at the mean model when x_ptr is None."""
         out = C.c_double(0.0)
         _check(self._h, lib().adpsgd_objective(self._h, x_ptr, C.byref(out)))
+        return out.value
+
+    def classification_error(self, x_ptr=None):
+        """Fraction of the local samples misclassified at a device vector, or at the mean model."""
+        out = C.c_double(0.0)
+        _check(self._h, lib().adpsgd_classification_error(self._h, x_ptr, C.byref(out)))
         return out.value
 
     def count_nonfinite(self):

@@ -88,7 +88,7 @@ namespace {
 
 // The perceptron's objective: forward pass and cross-entropy over all local samples, in chunks of
 // M samples (the last chunk of a worker is padded with its last sample and counts only its own).
-int mlp_objective(adpsgd_t* h, const float* x, double* out) {
+int mlp_objective(adpsgd_t* h, const float* x, double* out, bool count_errors) {
     const int32_t n = h->n, M = h->o.M;
     std::vector<int64_t> first(n + 1, 0);          // first operation of every worker
     for (int32_t i = 0; i < n; ++i) {
@@ -133,7 +133,7 @@ int mlp_objective(adpsgd_t* h, const float* x, double* out) {
         MlpGradArgs a{nullptr, point_b16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out,
                       reinterpret_cast<const GradOp*>(base + off_ops) + g0, cnt, M,
                       reinterpret_cast<const int32_t*>(base + off_idx), nullptr, 1.0f, nullptr, h->grad_scratch.p, false, false};
-        HIP_TRY(h, launch_mlp_loss(a, d_sum + g0, h->stream));
+        HIP_TRY(h, launch_mlp_loss(a, d_sum + g0, count_errors, h->stream));
     }
     std::vector<double> sums(static_cast<size_t>(n_ops));
     HIP_TRY(h, hipMemcpyAsync(sums.data(), d_sum, sums.size() * sizeof(double), hipMemcpyDeviceToHost, h->stream));
@@ -148,15 +148,10 @@ int mlp_objective(adpsgd_t* h, const float* x, double* out) {
     return ADPSGD_OK;
 }
 
-}  // namespace
-
-extern "C" int adpsgd_objective(adpsgd_t* h, const float* x, double* out) {
-    if (!h) return ADPSGD_ERR_ARG;
-    if (!out) return fail(h, ADPSGD_ERR_ARG, "objective: out is NULL");
-    if (h->o.model == ADPSGD_MODEL_SYNTH)
-        return fail(h, ADPSGD_ERR_STATE, "objective: the synthetic-gradient model has no objective");
+// mean over the workers of the mean over their rows of the loss (or of the 0/1 classification error) at x
+int evaluate(adpsgd_t* h, const float* x, double* out, bool count_errors) {
     if (x && !aligned16(x)) return fail(h, ADPSGD_ERR_ARG, "objective: x is not 16-byte aligned");
-    if (h->o.model == ADPSGD_MODEL_MLP) return mlp_objective(h, x, out);
+    if (h->o.model == ADPSGD_MODEL_MLP) return mlp_objective(h, x, out, count_errors);
     std::vector<ObjectiveWorker> tab(h->n);
     int64_t max_rows = 0;
     for (int32_t i = 0; i < h->n; ++i) {
@@ -180,8 +175,26 @@ extern "C" int adpsgd_objective(adpsgd_t* h, const float* x, double* out) {
     HIP_TRY(h, hipMemcpyAsync(base + off_tab, tab.data(), tab.size() * sizeof(ObjectiveWorker), hipMemcpyHostToDevice, h->stream));
     HIP_TRY(h, launch_objective(h->o.model, point, h->d, h->n, reinterpret_cast<const ObjectiveWorker*>(base + off_tab), max_rows,
                                 h->o.lambda, reinterpret_cast<double*>(base + off_part), reinterpret_cast<double*>(base + off_res),
-                                h->stream));
+                                count_errors, h->stream));
     HIP_TRY(h, hipMemcpyAsync(out, base + off_res, sizeof(double), hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     return ADPSGD_OK;
+}
+
+}  // namespace
+
+extern "C" int adpsgd_objective(adpsgd_t* h, const float* x, double* out) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (!out) return fail(h, ADPSGD_ERR_ARG, "objective: out is NULL");
+    if (h->o.model == ADPSGD_MODEL_SYNTH)
+        return fail(h, ADPSGD_ERR_STATE, "objective: the synthetic-gradient model has no objective");
+    return evaluate(h, x, out, false);
+}
+
+extern "C" int adpsgd_classification_error(adpsgd_t* h, const float* x, double* out) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (!out) return fail(h, ADPSGD_ERR_ARG, "classification_error: out is NULL");
+    if (h->o.model != ADPSGD_MODEL_LOGREG && h->o.model != ADPSGD_MODEL_MLP)
+        return fail(h, ADPSGD_ERR_STATE, "classification_error: the model has no labels");
+    return evaluate(h, x, out, true);
 }

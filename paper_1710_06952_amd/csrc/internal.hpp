@@ -146,8 +146,9 @@ struct MlpGradArgs {
     bool compensate;        // wait-free variant: first build the compensated bf16 rows the operations name
 };
 size_t mlp_scratch_bytes(int32_t n_ops, int32_t M, int32_t in, int32_t hid, int32_t out);
-// forward pass and cross-entropy only: loss_sum[op] = sum over the first `count` samples of the operation (fp64)
-hipError_t launch_mlp_loss(const MlpGradArgs& a, double* loss_sum, hipStream_t st);
+// forward pass and cross-entropy only: loss_sum[op] = sum over the first `count` samples of the operation (fp64);
+// count_errors: the number of those samples whose largest logit (lowest class on ties) is not their label instead
+hipError_t launch_mlp_loss(const MlpGradArgs& a, double* loss_sum, bool count_errors, hipStream_t st);
 bool mlp_can_factor(int32_t in, int32_t hid, int32_t M);
 
 // The perceptron's model update with the first-layer gradient still in factored form
@@ -208,7 +209,7 @@ struct ObjectiveWorker {
 };
 int64_t objective_row_groups(int64_t max_rows);
 hipError_t launch_objective(int model, const float* x, int64_t d, int32_t n, const ObjectiveWorker* workers, int64_t max_rows,
-                            float lambda, double* partial, double* result, hipStream_t st);
+                            float lambda, double* partial, double* result, bool count_errors, hipStream_t st);
 hipError_t launch_synth_gradient(uint64_t seed, uint64_t k, float std, int64_t d, float* out, hipStream_t st);
 
 }  // namespace adpsgd_impl

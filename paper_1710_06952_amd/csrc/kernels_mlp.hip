@@ -376,8 +376,9 @@ __global__ __launch_bounds__(kBwdT) void mlp_backward_small_kernel(const MlpPara
 
 // ---- 2b. loss only (evaluation of the objective): grid = n_ops, 1024 threads ------------------
 // Step a of the backward kernel without the rest: logits, softmax, cross-entropy of the first
-// `count` samples of each operation, summed in sample order in fp64.
-__global__ __launch_bounds__(kBwdT) void mlp_loss_kernel(const MlpParams p, double* loss_sum) {
+// `count` samples of each operation, summed in sample order in fp64.  count_errors: a sample
+// contributes 1 when its largest logit (the lowest class on ties) is not its label, else 0.
+__global__ __launch_bounds__(kBwdT) void mlp_loss_kernel(const MlpParams p, double* loss_sum, int count_errors) {
     __shared__ float loss_s[kMaxM];
     const GradOp op = p.ops[blockIdx.x];
     const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
@@ -407,7 +408,10 @@ __global__ __launch_bounds__(kBwdT) void mlp_loss_kernel(const MlpParams p, doub
     for (int off = 8; off > 0; off >>= 1) zsum += __shfl_xor(zsum, off, 64);
     const int lsrc = (threadIdx.x & 48) + (label >= 0 && label < p.out ? label : 0);
     const float lsel = __shfl(logit, lsrc, 64);
-    if (so == 0) loss_s[sm] = -(lsel - zmax - logf(zsum));
+    int best = live && logit == zmax ? so : kMaxOut;
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) best = min(best, __shfl_xor(best, off, 64));
+    if (so == 0) loss_s[sm] = count_errors ? (best != label ? 1.0f : 0.0f) : -(lsel - zmax - logf(zsum));
     __syncthreads();
     if (threadIdx.x == 0) {
         const int count = op.count > 0 ? (op.count < p.M ? op.count : p.M) : p.M;
@@ -616,7 +620,7 @@ size_t mlp_scratch_bytes(int32_t n_ops, int32_t M, int32_t in, int32_t hid, int3
     return 2 * act + lp;
 }
 
-hipError_t launch_mlp_loss(const MlpGradArgs& a, double* loss_sum, hipStream_t st) {
+hipError_t launch_mlp_loss(const MlpGradArgs& a, double* loss_sum, bool count_errors, hipStream_t st) {
     if (a.n_ops <= 0) return hipSuccess;
     if (mlp_scratch_bytes(a.n_ops, a.M, a.in, a.hid, a.out) == 0 || a.n_ops > 65535) return hipErrorInvalidValue;
     MlpParams p{};
@@ -640,7 +644,7 @@ hipError_t launch_mlp_loss(const MlpGradArgs& a, double* loss_sum, hipStream_t s
     hipLaunchKernelGGL(mlp_forward_kernel, dim3(a.hid / kFwdTileH, a.n_ops), dim3(kFwdT), 0, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(mlp_loss_kernel, dim3(a.n_ops), dim3(kBwdT), 0, st, p, loss_sum);
+    hipLaunchKernelGGL(mlp_loss_kernel, dim3(a.n_ops), dim3(kBwdT), 0, st, p, loss_sum, count_errors ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -124,6 +124,13 @@ class Engine:
         xt = self.torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(self.device)
         return self.h.objective(xt.data_ptr())
 
+    def classification_error(self, x=None):
+        """Fraction of the local samples misclassified at x (numpy vector or None = the mean model)."""
+        if x is None:
+            return self.h.classification_error(None)
+        xt = self.torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(self.device)
+        return self.h.classification_error(xt.data_ptr())
+
     def count_nonfinite(self):
         return self.h.count_nonfinite()
 

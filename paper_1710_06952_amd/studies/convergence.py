@@ -19,7 +19,8 @@ all executed by the HIP library:
 
 An epoch is one pass over all workers' samples: n * rows / M gradient evaluations, i.e. that many
 events, or 1/n of that many synchronous iterations.  After every epoch the objective over all
-local data at the mean model (Algorithm 1's output) is read back with adpsgd_objective.
+local data at the mean model (Algorithm 1's output) is read back with adpsgd_objective, and the
+classification error (1 - accuracy) with adpsgd_classification_error.
 
     python -m paper_1710_06952_amd.studies.convergence [--n 16] [--epochs 12] [--json]
 """
@@ -84,7 +85,7 @@ def run_study(n=16, dims=(64, 256, 10), rows=2048, M=32, epochs=12, T_max=4, gam
     curves = {}
     for name, graph in (("complete", complete(n)), ("d-psgd", ring(n))):
         eng = engine(graph)
-        curve = [eng.objective()]
+        curve, errs = [eng.objective()], [eng.classification_error()]
         spread = 0.0
         rng = np.random.default_rng([seed, 12])
         for e in range(epochs):
@@ -94,11 +95,12 @@ def run_study(n=16, dims=(64, 256, 10), rows=2048, M=32, epochs=12, T_max=4, gam
                                       k_begin=e * events_per_epoch)[::n][:iters_per_epoch]
             eng.run_sync_steps(iters_per_epoch, batch, gamma=g)
             curve.append(eng.objective())
+            errs.append(eng.classification_error())
             spread = max(spread, eng.consensus_distance())
-        curves[name] = {"objective": curve, "max_consensus_distance": spread}
+        curves[name] = {"objective": curve, "error": errs, "max_consensus_distance": spread}
         eng.close()
     eng = engine(ring(n))
-    curve = [eng.objective()]
+    curve, errs = [eng.objective()], [eng.classification_error()]
     spread = 0.0
     for e in range(epochs):
         sched = adpsgd_make_schedule(ring(n), events_per_epoch, seed=seed, T_max=T_max, M=M, rows=[rows] * n,
@@ -107,8 +109,9 @@ def run_study(n=16, dims=(64, 256, 10), rows=2048, M=32, epochs=12, T_max=4, gam
                                                k_begin=e * events_per_epoch)
         eng.run_events(sched)
         curve.append(eng.objective())
+        errs.append(eng.classification_error())
         spread = max(spread, eng.consensus_distance())
-    curves["ad-psgd"] = {"objective": curve, "max_consensus_distance": spread}
+    curves["ad-psgd"] = {"objective": curve, "error": errs, "max_consensus_distance": spread}
     eng.close()
     return {"n": n, "dims": list(dims), "rows": rows, "M": M, "epochs": epochs, "T_max": T_max, "gamma": gamma,
             "halve_every": halve_every, "momentum": momentum, "weight_decay": weight_decay,
@@ -117,9 +120,10 @@ def run_study(n=16, dims=(64, 256, 10), rows=2048, M=32, epochs=12, T_max=4, gam
 
 def format_table(res):
     names = list(res["curves"])
-    lines = ["epoch | " + " | ".join("%12s" % m for m in names), "-" * (8 + 15 * len(names))]
+    lines = ["epoch | " + " | ".join("%20s" % (m + " loss / error") for m in names), "-" * (8 + 23 * len(names))]
     for e in range(res["epochs"] + 1):
-        lines.append("%5d | " % e + " | ".join("%12.5f" % res["curves"][m]["objective"][e] for m in names))
+        lines.append("%5d | " % e + " | ".join("%11.5f / %6.4f" % (res["curves"][m]["objective"][e], res["curves"][m]["error"][e])
+                                             for m in names))
     lines.append("max consensus distance: " + ", ".join("%s %.3g" % (m, res["curves"][m]["max_consensus_distance"]) for m in names))
     return "\n".join(lines)
 

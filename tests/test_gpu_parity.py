@@ -1035,6 +1035,58 @@ def test_objective_over_all_local_data(P, model, n, d, lam):
     eng.close()
 
 
+def test_classification_error_matches_the_oracle(P):
+    """1 - accuracy over all local data for the two models with labels, at given points and at the mean model;
+    a prediction may differ from the oracle's only where the fp32 and fp64 scores straddle a tie."""
+    from workloads import mixture_data, mlp_init
+    _say("classification error")
+    n, d = 4, 1030
+    g = ring_graph(n)
+    feats, targs, _ = logreg_data(n, 300, d, seed=31)
+    rows = [300, 200, 257, 64]
+    feats = [np.ascontiguousarray(f[:r]) for f, r in zip(feats, rows)]
+    targs = [np.ascontiguousarray(t[:r]) for t, r in zip(targs, rows)]
+    eng = P.Engine(g, d, "logreg", M=2, gamma=0.1, lam=1e-3)
+    eng.load_data(feats, targs)
+    rng = np.random.default_rng(5)
+    X0 = (0.3 * rng.standard_normal((n, d))).astype(np.float32)
+    eng.set_models(X0, broadcast=False)
+    ref = lambda x, mdl, kw: float(np.mean([oracle.count_misclassified(mdl, x, feats[i], targs[i], **kw) / rows[i] for i in range(n)]))
+    for x in (rng.standard_normal(d).astype(np.float32), None, np.zeros(d, np.float32)):
+        xr = eng.get_mean_model() if x is None else x
+        want = ref(xr, oracle.MODEL_LOGREG, {})
+        assert abs(eng.classification_error(x) - want) <= 1.0 / min(rows) / n + 1e-12 and 0.05 < want < 0.95
+    assert eng.classification_error(np.zeros(d, np.float32)) == ref(np.zeros(d, np.float32), oracle.MODEL_LOGREG, {})   # no ties to straddle
+    eng.close()
+    dims, M = (24, 64, 5), 16
+    d = dims[0] * dims[1] + dims[1] + dims[1] * dims[2] + dims[2]
+    feats, targs, _ = mixture_data(n, 120, din=dims[0], classes=dims[2], seed=8)
+    rows = [120, 37, 64, 16]
+    feats = [np.ascontiguousarray(f[:r]) for f, r in zip(feats, rows)]
+    targs = [np.ascontiguousarray(t[:r]) for t, r in zip(targs, rows)]
+    eng = P.Engine(g, d, "mlp", M=M, gamma=0.05, mlp=dims, T_max=2)
+    eng.load_data(feats, targs)
+    X0 = np.stack([mlp_init(*dims, seed=s) for s in range(n)])
+    eng.set_models(X0, broadcast=False)
+    for x in (X0[2], None):
+        xr = eng.get_mean_model() if x is None else x
+        want = ref(xr, oracle.MODEL_MLP, dict(mlp=dims))
+        assert abs(eng.classification_error(x) - want) <= 1.0 / min(rows) / n + 1e-12 and 0.2 < want < 0.99
+    # training lowers it
+    sched = oracle.make_schedule(g, 400, seed=3, T_max=2, M=M, rows=rows)
+    before = eng.classification_error()
+    eng.run_events(sched)
+    after = eng.classification_error()
+    assert after < 0.5 * before
+    assert abs(after - ref(eng.get_mean_model(), oracle.MODEL_MLP, dict(mlp=dims))) <= 1.0 / min(rows) / n + 1e-12
+    eng.close()
+    eng = P.Engine(g, 64, "lsq", M=2, gamma=0.1)
+    with pytest.raises(P.AdpsgdError) as ei:
+        eng.classification_error()
+    assert ei.value.code == -4
+    eng.close()
+
+
 def test_objective_is_refused_without_a_data_model(P):
     eng = P.Engine(ring_graph(4), 64, "synth", gamma=0.1, synth_std=0.1)
     with pytest.raises(P.AdpsgdError) as ei:

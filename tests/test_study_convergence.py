@@ -29,6 +29,8 @@ def test_the_three_schedules_converge_alike_per_epoch():
     for name, c in curves.items():
         assert c[0] == start and np.isfinite(c).all()
         assert c[-1] < 0.5 * start, (name, c)
+    for v in res["curves"].values():
+        assert v["error"][-1] < 0.5 * v["error"][0] and 0 <= v["error"][-1] < 0.5
     finals = np.array([c[-1] for c in curves.values()])
     assert finals.max() <= 1.3 * finals.min(), curves                  # about the same loss after the same epochs
     spread = {k: v["max_consensus_distance"] for k, v in res["curves"].items()}
