@@ -411,6 +411,43 @@ def test_config5_full_shape(P):
     assert np.allclose(lg, lr, rtol=2e-4, atol=1e-7)
 
 
+@pytest.mark.parametrize("cfg_idx,K", [(4, 600), (5, 250)])
+def test_full_shape_with_momentum_factored_equals_dense(P, cfg_idx, K):
+    """Full n, d, M of configurations 4 and 5 with the experiments' optimizer: the update kernels that
+    apply the gradient from its factors (the streaming variants at this size) give the bits of the dense
+    path, models and momentum buffers (compared on the GPU)."""
+    import torch
+    from workloads import linear_data_on_device, mixture_data_on_device, mlp_init
+    c = get_config(cfg_idx)
+    n, d, M = c["n"], c["d"], c["M"]
+    _say("config %d full shape with momentum: factored against dense" % cfg_idx)
+    g = random_regular4_graph(n, c["seed"])
+    if c["model"] == "mlp":
+        rows = 512
+        feats, targs = mixture_data_on_device(n, rows, din=c["mlp"][0], classes=c["mlp"][2], seed=c["seed"])
+        x0, kw = mlp_init(*c["mlp"], seed=c["seed"]), dict(mlp=c["mlp"])
+    else:
+        rows = 16
+        feats, targs = linear_data_on_device(c["model"], n, rows, d, seed=c["seed"], feature_var=c.get("feature_var"))
+        x0, kw = np.zeros(d, np.float32), {}
+    sched = P.adpsgd_make_schedule(g, K, seed=c["seed"], T_max=min(c["T_max"], 8), M=M, rows=[rows] * n)
+    out = []
+    for dense in (False, True):
+        eng = P.Engine(g, d, c["model"], M=M, gamma=0.1 * c["gamma"], T_max=min(c["T_max"], 8), momentum=0.9, weight_decay=1e-4,
+                       dense_gradient=dense, **kw)
+        eng.load_data(feats, targs)
+        eng.set_models(x0)
+        eng.run_events(sched)
+        torch.cuda.synchronize()
+        out.append((eng.X.clone(), eng.V.clone(), eng.get_stats()["grad_launches"], eng.count_nonfinite()))
+        eng.close()
+    assert out[0][3] == 0 and out[0][2] < out[1][2]          # finite, and one launch fewer per gradient set
+    assert torch.equal(out[0][0], out[1][0]) and torch.equal(out[0][1], out[1][1])
+    assert out[0][1].abs().max().item() > 0
+    del out, feats, targs
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ momentum and weight decay in the fused apply
 @pytest.mark.parametrize("n,d,K,T,mu,wd", [(8, 5003, 500, 5, 0.9, 1e-4), (5, 1030, 300, 2, 0.5, 0.0), (4, 77, 200, 1, 0.0, 0.01)])
 def test_synth_workload_with_momentum_and_weight_decay(P, n, d, K, T, mu, wd):
