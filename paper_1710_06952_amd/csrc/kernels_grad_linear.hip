@@ -283,7 +283,7 @@ hipError_t launch_apply_variant(const LinApplyParams& p, dim3 grid, bool stream_
 }
 
 // ---- short models: the whole gradient of one operation in one block, one launch -----------
-// For d <= 4096 a round is a chain of launch-bound kernels, so the three steps above run in a
+// For d <= 2048 a round is a chain of launch-bound kernels, so the three steps above run in a
 // single block of 1024 threads per gradient: wavefront w takes the minibatch rows w, w + 16, ...
 // (lane l holds the float4 elements l, l + 64, ... of x^ in registers), the coefficients and the
 // loss are finished by M threads, and the rows (read again, from the cache) are combined by
