@@ -49,7 +49,8 @@ enum {
     ADPSGD_ERR_GRAPH = -2,    /* graph not symmetric / simple / connected       */
     ADPSGD_ERR_SCHEDULE = -3, /* schedule violates a documented constraint      */
     ADPSGD_ERR_STATE = -4,    /* call not valid in the handle's current state   */
-    ADPSGD_ERR_HIP = -5       /* a HIP runtime call failed                      */
+    ADPSGD_ERR_HIP = -5,      /* a HIP runtime call failed                      */
+    ADPSGD_ERR_CALLBACK = -6  /* the caller's gradient function reported an error */
 };
 
 /* Local loss F_i(x; xi) of the problem statement  min_x sum_i p_i E_xi F_i(x; xi)
@@ -58,8 +59,11 @@ enum {
     ADPSGD_MODEL_LSQ = 0,    /* F = (a.x - b)^2 / 2                               */
     ADPSGD_MODEL_LOGREG = 1, /* F = log(1 + exp(-y a.x)) + lambda |x|^2 / 2        */
     ADPSGD_MODEL_SYNTH = 2,  /* no data: g_k[e] = synth_std * N(0,1)(seed, k, e)   */
-    ADPSGD_MODEL_MLP = 3     /* in -> hidden (ReLU) -> out, softmax cross-entropy, */
+    ADPSGD_MODEL_MLP = 3,    /* in -> hidden (ReLU) -> out, softmax cross-entropy, */
                              /* bf16 weights/inputs, fp32 master and accumulation  */
+    ADPSGD_MODEL_EXTERNAL = 4 /* F is the caller's: the gradient step of Algorithm 1 is a function the caller
+                                 passes to adpsgd_run_events_with; sampling, stale reads, averaging and the
+                                 update stay the library's.  No data is loaded; M, lambda, grad_sum unused */
 };
 
 enum {
@@ -226,6 +230,29 @@ typedef struct {
     const float* w_edge;       /* one weight per entry of the graph's col array; NULL with w_self.
                                   Must be non-negative, symmetric, rows summing to 1 (|err| <= 1e-5) */
 } adpsgd_sync_schedule_t;
+
+/* One gradient the library asks the caller for (ADPSGD_MODEL_EXTERNAL): evaluate the stochastic
+ * gradient of worker `worker` for event `event` of the call's schedule at the model xhat and write it to g. */
+typedef struct {
+    int32_t worker;     /* i_k: whose local data the gradient samples                              */
+    int32_t reserved;
+    int64_t event;      /* k, the index into the arrays of the schedule of this call               */
+    const float* xhat;  /* device, d floats, read only: row i_k of X as of logical time k - tau_k   */
+    float* g;           /* device, d floats: receives g_k (a pending-gradient slot of the workspace) */
+} adpsgd_grad_request_t;
+
+/* Called on the calling thread, once per group of gradients that may be evaluated together (the
+ * requests of one call are independent of each other).  It must enqueue all its GPU work on `stream`
+ * (the handle's stream), or finish it before returning; it must not call into the same handle.
+ * requests is host memory, valid during the call.  Return 0, or non-zero to abort the run. */
+typedef int (*adpsgd_gradient_fn)(void* user, int32_t n_requests, const adpsgd_grad_request_t* requests, void* stream);
+
+/* adpsgd_run_events for ADPSGD_MODEL_EXTERNAL (else ADPSGD_ERR_STATE): the same events, rounds and update
+ * kernel, with every stale gradient obtained from fn (batch_idx of the schedule is not read: the caller
+ * draws its own minibatches, e.g. from the event number).  If fn returns non-zero the call waits for the
+ * stream and returns ADPSGD_ERR_CALLBACK; the updates of the rounds already enqueued have happened, which
+ * is in general not a prefix of the serial order: restore the models before going on. */
+int adpsgd_run_events_with(adpsgd_t* h, const adpsgd_schedule_t* s, adpsgd_gradient_fn fn, void* user);
 
 /* Runs the iterations on the handle's stream (asynchronous, arrays reusable on return).  loss
  * (device, S * n floats, [t][i], or NULL) receives the minibatch losses.  Needs at least n

@@ -13,13 +13,13 @@ import numpy as np
 _HERE = Path(__file__).resolve().parent
 LIB_PATH = _HERE / "libadpsgd.so"
 
-OK, ERR_ARG, ERR_GRAPH, ERR_SCHEDULE, ERR_STATE, ERR_HIP = 0, -1, -2, -3, -4, -5
-MODEL_LSQ, MODEL_LOGREG, MODEL_SYNTH, MODEL_MLP = 0, 1, 2, 3
+OK, ERR_ARG, ERR_GRAPH, ERR_SCHEDULE, ERR_STATE, ERR_HIP, ERR_CALLBACK = 0, -1, -2, -3, -4, -5, -6
+MODEL_LSQ, MODEL_LOGREG, MODEL_SYNTH, MODEL_MLP, MODEL_EXTERNAL = 0, 1, 2, 3, 4
 FLAG_PROFILE, FLAG_DENSE_GRADIENT, FLAG_VERIFY_PLAN = 1, 2, 4
 
 EXPORTS = [
     "adpsgd_create", "adpsgd_destroy", "adpsgd_last_error", "adpsgd_load_data", "adpsgd_set_models",
-    "adpsgd_run_events", "adpsgd_get_models", "adpsgd_get_mean_model", "adpsgd_consensus_distance",
+    "adpsgd_run_events", "adpsgd_run_events_with", "adpsgd_get_models", "adpsgd_get_mean_model", "adpsgd_consensus_distance",
     "adpsgd_get_bf16_models", "adpsgd_classification_error", "adpsgd_get_momentum", "adpsgd_get_stats", "adpsgd_make_schedule", "adpsgd_plan_rounds",
     "adpsgd_synth_gradient", "adpsgd_run_sync_steps", "adpsgd_metropolis_weights",
     "adpsgd_get_event_count", "adpsgd_set_event_count", "adpsgd_verify_plan", "adpsgd_objective", "adpsgd_count_nonfinite",
@@ -51,6 +51,13 @@ class Schedule(C.Structure):
                 ("tau", C.POINTER(C.c_int32)), ("batch_idx", C.POINTER(C.c_int32)),
                 ("gamma", C.POINTER(C.c_float)), ("extra_ptr", C.POINTER(C.c_int64)),
                 ("extra_a", C.POINTER(C.c_int32)), ("extra_b", C.POINTER(C.c_int32))]
+
+
+class GradRequest(C.Structure):
+    _fields_ = [("worker", C.c_int32), ("reserved", C.c_int32), ("event", C.c_int64), ("xhat", C.c_void_p), ("g", C.c_void_p)]
+
+
+GRADIENT_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_int32, C.POINTER(GradRequest), C.c_void_p)
 
 
 class SyncSchedule(C.Structure):
@@ -119,6 +126,7 @@ def lib():
         L.adpsgd_verify_plan.argtypes = [i32, i64, P(i32), P(i32), P(i32), i32, i32, P(i32), P(i32), P(i32), i32,
                                          P(i64), P(i32), P(i32), P(i64)]
         L.adpsgd_objective.argtypes = [vp, vp, P(C.c_double)]
+        L.adpsgd_run_events_with.argtypes = [vp, P(Schedule), GRADIENT_FN, vp]
         L.adpsgd_classification_error.argtypes = [vp, vp, P(C.c_double)]
         L.adpsgd_count_nonfinite.argtypes = [vp, P(i64)]
         L.adpsgd_get_event_count.argtypes = [vp, P(u64)]
@@ -274,6 +282,33 @@ class Handle:
                      None if gam is None else gam.ctypes.data_as(C.POINTER(C.c_float)),
                      None if ep is None else ep.ctypes.data_as(C.POINTER(C.c_int64)), _i32p(ea), _i32p(eb))
         _check(self._h, lib().adpsgd_run_events(self._h, C.byref(s), loss_ptr))
+
+    def run_events_with(self, schedule, gradient_fn):
+        """MODEL_EXTERNAL: gradient_fn(requests, stream) gets a list of (worker, event, xhat_ptr, g_ptr)
+        tuples (device pointers as integers) and the stream as an integer; it enqueues the work that
+        writes every requested gradient.  An exception inside it aborts the run and is raised again here."""
+        worker, nbr, tau = (_as_i32(schedule[k]) for k in ("worker", "neighbour", "tau"))
+        gam = schedule.get("gamma")
+        gam = None if gam is None else np.ascontiguousarray(gam, dtype=np.float32)
+        ep, ea, eb = _extra_arrays(schedule.get("extra_pairs"))
+        s = Schedule(worker.size, _i32p(worker), _i32p(nbr), _i32p(tau), None,
+                     None if gam is None else gam.ctypes.data_as(C.POINTER(C.c_float)),
+                     None if ep is None else ep.ctypes.data_as(C.POINTER(C.c_int64)), _i32p(ea), _i32p(eb))
+        raised = []
+
+        def trampoline(_user, count, requests, stream):
+            try:
+                gradient_fn([(requests[t].worker, requests[t].event, requests[t].xhat, requests[t].g) for t in range(count)],
+                            stream or 0)
+                return 0
+            except BaseException as exc:      # must not propagate through the C frames
+                raised.append(exc)
+                return 1
+
+        rc = lib().adpsgd_run_events_with(self._h, C.byref(s), GRADIENT_FN(trampoline), None)
+        if raised:
+            raise raised[0]
+        _check(self._h, rc)
 
     def run_sync_steps(self, steps, batch_idx=None, gamma=None, weights=None, loss_ptr=None):
         """steps iterations of the synchronous comparison schedule; batch_idx (steps, n, M);

@@ -114,14 +114,17 @@ extern "C" int adpsgd_create(adpsgd_t** out, const adpsgd_graph_t* graph, int64_
     if (n > 65535) return fail(nullptr, ADPSGD_ERR_ARG, "create: at most 65535 workers");
     if (d < 1) return fail(nullptr, ADPSGD_ERR_ARG, "create: d < 1");
     const adpsgd_opts_t& o = *opts;
-    if (o.model < ADPSGD_MODEL_LSQ || o.model > ADPSGD_MODEL_MLP) return fail(nullptr, ADPSGD_ERR_ARG, "create: unknown model");
+    if (o.model < ADPSGD_MODEL_LSQ || o.model > ADPSGD_MODEL_EXTERNAL) return fail(nullptr, ADPSGD_ERR_ARG, "create: unknown model");
+    const bool external = o.model == ADPSGD_MODEL_EXTERNAL;
+    if (external && o.local_compensation)
+        return fail(nullptr, ADPSGD_ERR_ARG, "create: local_compensation is not available with caller-supplied gradients");
     if (!o.X || !aligned16(o.X)) return fail(nullptr, ADPSGD_ERR_ARG, "create: X is NULL or not 16-byte aligned");
     if (o.ldx < d || (o.ldx & 3)) return fail(nullptr, ADPSGD_ERR_ARG, "create: ldx must be >= d and a multiple of 4");
     if (o.T_max < 0) return fail(nullptr, ADPSGD_ERR_ARG, "create: T_max < 0");
     if (!std::isfinite(o.gamma)) return fail(nullptr, ADPSGD_ERR_ARG, "create: gamma not finite");
     int32_t n_slots = 0;
     if (o.model != ADPSGD_MODEL_SYNTH) {
-        if (o.M < 1 || o.M > 65536) return fail(nullptr, ADPSGD_ERR_ARG, "create: minibatch size M outside [1, 65536]");
+        if (!external && (o.M < 1 || o.M > 65536)) return fail(nullptr, ADPSGD_ERR_ARG, "create: minibatch size M outside [1, 65536]");
         if (!o.workspace || !aligned16(o.workspace)) return fail(nullptr, ADPSGD_ERR_ARG, "create: workspace is NULL or misaligned");
         const int64_t slot_bytes = o.ldx * 4;
         const int64_t have = o.workspace_bytes / slot_bytes;
@@ -191,7 +194,8 @@ extern "C" void adpsgd_destroy(adpsgd_t* h) {
 extern "C" int adpsgd_load_data(adpsgd_t* h, int32_t worker, const void* features, int64_t rows, int64_t ld,
                                 const void* targets) {
     if (!h) return ADPSGD_ERR_ARG;
-    if (h->o.model == ADPSGD_MODEL_SYNTH) return fail(h, ADPSGD_ERR_STATE, "load_data: the synthetic-gradient model takes no data");
+    if (h->o.model == ADPSGD_MODEL_SYNTH || h->o.model == ADPSGD_MODEL_EXTERNAL)
+        return fail(h, ADPSGD_ERR_STATE, "load_data: this model takes no data");
     if (worker < 0 || worker >= h->n) return fail(h, ADPSGD_ERR_ARG, "load_data: worker out of range");
     if (!features || !targets || rows < 1 || rows > 0x7FFFFFFF) return fail(h, ADPSGD_ERR_ARG, "load_data: null data or bad row count");
     if (!aligned16(features)) return fail(h, ADPSGD_ERR_ARG, "load_data: features not 16-byte aligned");
@@ -237,7 +241,7 @@ namespace {
 
 // Checks a schedule against the documented constraints; nothing is launched and no state changes
 // when it fails.
-int validate_schedule(adpsgd_t* h, const adpsgd_schedule_t* s, bool with_grad, int32_t M, int64_t n_extra) {
+int validate_schedule(adpsgd_t* h, const adpsgd_schedule_t* s, bool with_data, int32_t M, int64_t n_extra) {
     const int64_t K = s->K;
     if (s->extra_ptr) {
         if (s->extra_ptr[0] != 0 || n_extra < 0 || (n_extra > 0 && (!s->extra_a || !s->extra_b)))
@@ -268,7 +272,7 @@ int validate_schedule(adpsgd_t* h, const adpsgd_schedule_t* s, bool with_grad, i
             return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: tau outside [0, min(k, T_max)] at event " + std::to_string(k));
         if (s->gamma && !std::isfinite(s->gamma[k]))
             return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: gamma not finite at event " + std::to_string(k));
-        if (with_grad) {
+        if (with_data) {
             const WorkerData& w = h->data[i];
             if (!w.features) return fail(h, ADPSGD_ERR_STATE, "run_events: no data loaded for worker " + std::to_string(i));
             const int32_t* b = s->batch_idx + k * static_cast<int64_t>(M);
@@ -280,21 +284,21 @@ int validate_schedule(adpsgd_t* h, const adpsgd_schedule_t* s, bool with_grad, i
     return ADPSGD_OK;
 }
 
-}  // namespace
-
-extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float* loss) {
-    if (!h) return ADPSGD_ERR_ARG;
+// The events of one call: plan, tables, then per round the gradients (the library's kernels, or the
+// caller's function for ADPSGD_MODEL_EXTERNAL) and one update launch.
+int run_events_impl(adpsgd_t* h, const adpsgd_schedule_t* s, float* loss, adpsgd_gradient_fn fn, void* user) {
     if (!s || s->K < 0) return fail(h, ADPSGD_ERR_ARG, "run_events: schedule is NULL or K < 0");
     const int64_t K = s->K;
     if (K == 0) return ADPSGD_OK;
     if (K > 0x7FFFFFF0) return fail(h, ADPSGD_ERR_ARG, "run_events: at most 2^31 - 16 events per call");
     if (!s->worker || !s->neighbour || !s->tau) return fail(h, ADPSGD_ERR_ARG, "run_events: null schedule array");
+    const bool external = h->o.model == ADPSGD_MODEL_EXTERNAL;
     const bool with_grad = h->o.model != ADPSGD_MODEL_SYNTH;
-    const int32_t M = with_grad ? h->o.M : 0;
-    if (with_grad && !s->batch_idx) return fail(h, ADPSGD_ERR_ARG, "run_events: batch_idx is NULL");
+    const int32_t M = with_grad && !external ? h->o.M : 0;
+    if (with_grad && !external && !s->batch_idx) return fail(h, ADPSGD_ERR_ARG, "run_events: batch_idx is NULL");
 
     const int64_t n_extra = s->extra_ptr ? s->extra_ptr[K] : 0;
-    const int rc_valid = validate_schedule(h, s, with_grad, M, n_extra);
+    const int rc_valid = validate_schedule(h, s, with_grad && !external, M, n_extra);
     if (rc_valid != ADPSGD_OK) return rc_valid;
 
     // perceptron: dW1 stays in factored form until the update kernel
@@ -394,7 +398,7 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
             }
         }
     }
-    if (with_grad) std::memcpy(stage + off_b, s->batch_idx, bytes_b);
+    if (bytes_b > 0) std::memcpy(stage + off_b, s->batch_idx, bytes_b);
     HIP_TRY(h, hipMemcpyAsync(T.dev.p, T.stage.p, total, hipMemcpyHostToDevice, h->stream));
     const char* dev = static_cast<const char*>(T.dev.p);
     const PairOp* d_uops = reinterpret_cast<const PairOp*>(dev);
@@ -404,7 +408,7 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
 
     // ---- gradient scratch ----
     size_t off_coef = 0;
-    if (with_grad) {
+    if (with_grad && !external) {
         if (h->o.model == ADPSGD_MODEL_MLP) {
             HIP_TRY(h, h->grad_scratch.reserve(mlp_scratch_bytes(group, M, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out)));
         } else {
@@ -420,6 +424,7 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
     const bool profile = (h->o.flags & ADPSGD_FLAG_PROFILE) != 0;
     float* slots = static_cast<float*>(h->o.workspace);
     const float gscale = h->o.grad_sum ? 1.0f : 1.0f / static_cast<float>(std::max(M, 1));
+    std::vector<adpsgd_grad_request_t> requests;
     for (int32_t r = 0; r < R; ++r) {
         for (int64_t g0 = r_off[r]; g0 < r_off[r + 1]; g0 += group) {
             const int32_t cnt = static_cast<int32_t>(std::min<int64_t>(group, r_off[r + 1] - g0));
@@ -431,7 +436,19 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
                 HIP_TRY(h, hipEventRecord(e0, h->stream));
             }
             int launches = 0;
-            if (h->o.model == ADPSGD_MODEL_MLP) {
+            if (external) {
+                requests.resize(static_cast<size_t>(cnt));
+                for (int32_t t = 0; t < cnt; ++t) {
+                    const GradOp& g = rops[g0 + t];
+                    requests[t] = adpsgd_grad_request_t{g.worker, 0, g.event, h->o.X + static_cast<int64_t>(g.worker) * h->o.ldx,
+                                                        slots + static_cast<int64_t>(g.slot) * h->o.ldx};
+                }
+                if (fn(user, cnt, requests.data(), h->stream) != 0) {
+                    (void)hipStreamSynchronize(h->stream);      // the table upload and the rounds enqueued so far
+                    return fail(h, ADPSGD_ERR_CALLBACK, "run_events_with: the gradient function failed in round " + std::to_string(r));
+                }
+                launches = 1;
+            } else if (h->o.model == ADPSGD_MODEL_MLP) {
                 MlpGradArgs a{h->o.X, h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, d_rops + g0, cnt, M,
                               d_batch, slots, gscale, loss,
                               h->grad_scratch.p, factored, mlp_comp};
@@ -488,6 +505,23 @@ extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float*
     h->stats.events += K;
     h->stats.rounds += R;
     return ADPSGD_OK;
+}
+
+}  // namespace
+
+extern "C" int adpsgd_run_events(adpsgd_t* h, const adpsgd_schedule_t* s, float* loss) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (h->o.model == ADPSGD_MODEL_EXTERNAL)
+        return fail(h, ADPSGD_ERR_STATE, "run_events: caller-supplied gradients need adpsgd_run_events_with");
+    return run_events_impl(h, s, loss, nullptr, nullptr);
+}
+
+extern "C" int adpsgd_run_events_with(adpsgd_t* h, const adpsgd_schedule_t* s, adpsgd_gradient_fn fn, void* user) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (h->o.model != ADPSGD_MODEL_EXTERNAL)
+        return fail(h, ADPSGD_ERR_STATE, "run_events_with: the handle was not created with ADPSGD_MODEL_EXTERNAL");
+    if (!fn) return fail(h, ADPSGD_ERR_ARG, "run_events_with: fn is NULL");
+    return run_events_impl(h, s, nullptr, fn, user);
 }
 
 extern "C" int adpsgd_get_stats(adpsgd_t* h, adpsgd_stats_t* out) {

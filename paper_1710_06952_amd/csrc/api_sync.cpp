@@ -12,6 +12,8 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
     const int64_t S = s->S;
     if (S == 0) return ADPSGD_OK;
     const int32_t n = h->n;
+    if (h->o.model == ADPSGD_MODEL_EXTERNAL)
+        return fail(h, ADPSGD_ERR_STATE, "run_sync_steps: not available with caller-supplied gradients");
     const bool with_grad = h->o.model != ADPSGD_MODEL_SYNTH;
     const int32_t M = with_grad ? h->o.M : 0;
     if (S * n > 0x7FFFFFF0) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: S * n must stay below 2^31 - 16");

@@ -7,7 +7,8 @@ import numpy as np
 
 from . import binding as B
 
-_MODELS = {"lsq": B.MODEL_LSQ, "logreg": B.MODEL_LOGREG, "synth": B.MODEL_SYNTH, "mlp": B.MODEL_MLP}
+_MODELS = {"lsq": B.MODEL_LSQ, "logreg": B.MODEL_LOGREG, "synth": B.MODEL_SYNTH, "mlp": B.MODEL_MLP,
+           "external": B.MODEL_EXTERNAL}
 
 
 def _pad(d, mult=64):
@@ -89,6 +90,20 @@ class Engine:
             self.loss = self.torch.zeros(len(schedule["worker"]), dtype=self.torch.float32, device=self.device)
             loss_ptr = self.loss.data_ptr()
         self.h.run_events(schedule, loss_ptr)
+
+    def run_events_with(self, schedule, gradient_fn):
+        """Model "external": gradient_fn(worker, event, xhat, g) is called for every event with two views
+        of device memory, the model to evaluate at (d floats, read only) and the slot that receives the
+        gradient; it must work on PyTorch's current stream, which is the stream the engine was created on."""
+        ws, ld, d = self.workspace.view(-1, self.ld), self.ld, self.d
+        x_base, w_base = self.X.data_ptr(), self.workspace.data_ptr()
+
+        def per_group(requests, _stream):
+            for worker, event, xhat_ptr, g_ptr in requests:
+                assert xhat_ptr == x_base + worker * ld * 4
+                gradient_fn(worker, event, self.X[worker, :d], ws[(g_ptr - w_base) // (ld * 4), :d])
+
+        self.h.run_events_with(schedule, per_group)
 
     def run_sync_steps(self, steps, batch_idx=None, gamma=None, weights=None, want_loss=False):
         """The synchronous comparison schedule (all workers step together, mixing with all neighbours)."""

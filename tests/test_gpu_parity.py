@@ -936,6 +936,110 @@ def test_many_workers_fill_the_rounds(P, model, n, d, K, T):
     eng.close()
 
 
+# ------------------------------------------------------------------ caller-supplied gradients
+@pytest.mark.parametrize("mu,wd", [(0.0, 0.0), (0.9, 1e-3)])
+def test_external_gradients_reproduce_the_synthetic_model_bit_for_bit(P, mu, wd):
+    """Model "external" with a gradient function that writes the generator's gradient of the event:
+    the run must equal the built-in synthetic model exactly (same rounds, same update kernel), also with
+    extra averaging pairs, events without averaging and momentum."""
+    from workloads import random_extra_pairs, with_identity_events
+    n, d, K, T = 10, 3001, 500, 4
+    _say("external gradients against the synthetic model, mu=%g" % mu)
+    g = random_regular4_graph(n, 3)
+    std = float(np.float32(0.05))
+    sched = oracle.make_schedule(g, K, seed=6, T_max=T)
+    sched["neighbour"] = with_identity_events(sched["worker"], sched["neighbour"], 0.2, seed=1)
+    sched["extra_pairs"] = random_extra_pairs(g, sched["worker"], sched["neighbour"], max_extra=2, seed=2)
+    x0 = np.random.default_rng(3).standard_normal((n, d)).astype(np.float32)
+    ref = P.Engine(g, d, "synth", gamma=0.1, T_max=T, synth_std=std, synth_seed=11, momentum=mu, weight_decay=wd)
+    ref.set_models(x0, broadcast=False)
+    ref.run_events(sched)
+    ref.run_events(sched)
+    eng = P.Engine(g, d, "external", gamma=0.1, T_max=T, momentum=mu, weight_decay=wd, verify_plan=True)
+    eng.set_models(x0, broadcast=False)
+    seen = []
+
+    def generator_gradient(base):
+        def fn(requests, stream):
+            for worker, event, xhat_ptr, g_ptr in requests:
+                seen.append(event)
+                P.adpsgd_synth_gradient(11, base + event, std, d, g_ptr, stream)
+        return fn
+
+    eng.h.run_events_with(sched, generator_gradient(0))
+    eng.h.run_events_with(sched, generator_gradient(K))
+    assert sorted(seen) == sorted(list(range(K)) * 2)
+    assert np.array_equal(eng.get_models(), ref.get_models())
+    if mu:
+        assert np.array_equal(eng.get_momentum(), ref.get_momentum())
+    assert eng.get_stats()["rounds"] == ref.get_stats()["rounds"]
+    ref.close()
+    eng.close()
+
+
+def test_external_gradients_from_pytorch_follow_algorithm_1(P):
+    """A gradient function written with PyTorch (least squares, fp64 products) sees exactly the stale
+    models Algorithm 1 prescribes: the run agrees with the oracle's least-squares run.  An exception in
+    the function aborts the call and is raised again; the engine stays usable."""
+    import torch
+    n, d, rows, K, M, T = 6, 1500, 24, 300, 4, 5
+    _say("external gradients from PyTorch")
+    g = ring_graph(n)
+    feats, targs, _ = lsq_data(n, rows, d, seed=21, feature_var=1.0 / d)
+    sched = oracle.make_schedule(g, K, seed=22, T_max=T, M=M, rows=[rows] * n)
+    sched["gamma"] = (0.3 * (1 + np.arange(K) % 2)).astype(np.float32)
+    A = [torch.from_numpy(f).cuda().double() for f in feats]
+    b = [torch.from_numpy(t).cuda().double() for t in targs]
+    batch = torch.from_numpy(sched["batch_idx"]).cuda().long()
+    eng = P.Engine(g, d, "external", gamma=0.3, T_max=T, verify_plan=True)
+    x0 = np.random.default_rng(5).standard_normal(d).astype(np.float32)
+    eng.set_models(x0)
+
+    def lsq_gradient(worker, event, xhat, out):
+        rows_b = A[worker][batch[event]]
+        out.copy_((rows_b.T @ (rows_b @ xhat.double() - b[worker][batch[event]]) / M).float())
+
+    eng.run_events_with(sched, lsq_gradient)
+    Xr = np.tile(x0, (n, 1))
+    oracle.run_events(Xr, sched, oracle.MODEL_LSQ, 0.3, M=M, gscale=1.0 / M, features=feats, targets=targs,
+                      gamma_k=sched["gamma"])
+    assert rel_err(eng.get_models(), Xr) <= TOL
+    Xfresh = np.tile(x0, (n, 1))
+    oracle.run_events(Xfresh, dict(sched, tau=np.zeros(K, np.int32)), oracle.MODEL_LSQ, 0.3, M=M, gscale=1.0 / M,
+                      features=feats, targets=targs, gamma_k=sched["gamma"])
+    assert rel_err(eng.get_models(), Xfresh) > 100 * TOL        # the staleness matters on this schedule
+
+    calls = []
+
+    def failing(worker, event, xhat, out):
+        calls.append(event)
+        if len(calls) == 40:
+            raise RuntimeError("gradient function gave up")
+        lsq_gradient(worker, event, xhat, out)
+
+    with pytest.raises(RuntimeError, match="gave up"):
+        eng.run_events_with(sched, failing)
+    eng.set_models(x0)
+    eng.run_events_with(sched, lsq_gradient)
+    assert rel_err(eng.get_models(), Xr) <= TOL
+    # the entry points refuse the wrong kind of handle
+    with pytest.raises(P.AdpsgdError) as ei:
+        eng.run_events(sched)
+    assert ei.value.code == -4
+    with pytest.raises(P.AdpsgdError) as ei:
+        eng.run_sync_steps(2)
+    assert ei.value.code == -4
+    eng.close()
+    other = P.Engine(g, d, "synth", gamma=0.1, T_max=T, synth_std=0.1)
+    with pytest.raises(P.AdpsgdError) as ei:
+        other.h.run_events_with(sched, lambda requests, stream: None)
+    assert ei.value.code == -4
+    other.close()
+    with pytest.raises(P.AdpsgdError) as ei:
+        P.Engine(g, d, "external", gamma=0.1, T_max=T, local_compensation=True)
+    assert ei.value.code == -1
+
+
 # ------------------------------------------------------------------ seeded sweep over small random set-ups
 def _random_case(rng):
     from workloads import hop_ring_graph, random_extra_pairs, with_identity_events
