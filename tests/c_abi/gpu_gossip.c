@@ -12,6 +12,17 @@
 
 #define CHECK(cond, code) do { if (!(cond)) { fprintf(stderr, "check failed: %s (line %d): %s\n", #cond, __LINE__, h ? adpsgd_last_error(h) : adpsgd_last_error(NULL)); return code; } } while (0)
 
+/* caller-supplied gradient: g_k = xhat (the gradient of |x|^2 / 2), copied on the handle's stream */
+static int n_requested = 0;
+static int copy_gradient(void* user, int32_t n_requests, const adpsgd_grad_request_t* rq, void* stream) {
+    const size_t bytes = *(const size_t*)user;
+    for (int32_t t = 0; t < n_requests; ++t) {
+        if (hipMemcpyAsync(rq[t].g, rq[t].xhat, bytes, hipMemcpyDeviceToDevice, (hipStream_t)stream) != hipSuccess) return 1;
+        ++n_requested;
+    }
+    return 0;
+}
+
 int main(void) {
     enum { N = 6, D = 1000, LD = 1024, K = 400 };
     adpsgd_t* h = NULL;
@@ -67,8 +78,29 @@ int main(void) {
     nbr[0] = (worker[0] + 3) % N;
     CHECK(adpsgd_run_events(h, &s, NULL) == ADPSGD_ERR_SCHEDULE, 13);
     CHECK(adpsgd_get_event_count(h, &count) == ADPSGD_OK && count == K, 14);
-    printf("c abi gpu ok: consensus distance %.3e -> %.3e\n", c0, c1);
     adpsgd_destroy(h);
+    h = NULL;
+    /* the same events with the gradient step supplied by this program: f_i(x) = |x|^2 / 2, so every event
+     * shrinks the sum over the workers by the factor (1 - gamma) of the stale row: all models go to zero */
+    float* slots = NULL;
+    CHECK(hipMalloc((void**)&slots, sizeof(float) * 4 * LD) == hipSuccess, 15);
+    o.model = ADPSGD_MODEL_EXTERNAL;
+    o.workspace = slots;
+    o.workspace_bytes = (int64_t)sizeof(float) * 4 * LD;
+    CHECK(adpsgd_create(&h, &g, D, &o) == ADPSGD_OK, 16);
+    CHECK(adpsgd_set_models(h, x0, D, 0) == ADPSGD_OK, 17);
+    size_t row_bytes = sizeof(float) * D;
+    nbr[0] = (worker[0] + 1) % N;
+    CHECK(adpsgd_run_events(h, &s, NULL) == ADPSGD_ERR_STATE, 18);
+    CHECK(adpsgd_run_events_with(h, &s, copy_gradient, &row_bytes) == ADPSGD_OK, 19);
+    CHECK(adpsgd_get_models(h, x1, D, 0) == ADPSGD_OK, 20);
+    CHECK(n_requested == K, 21);
+    double biggest = 0.0;
+    for (int t = 0; t < N * D; ++t) biggest = fmax(biggest, fabs(x1[t]));
+    CHECK(biggest < 0.05, 22);                                    /* from entries of size 1 */
+    printf("c abi gpu ok: consensus distance %.3e -> %.3e; own gradients: largest entry %.3e\n", c0, c1, biggest);
+    adpsgd_destroy(h);
+    (void)hipFree(slots);
     (void)hipFree(X);
     free(x0); free(x1); free(worker); free(nbr); free(tau);
     return 0;
