@@ -237,7 +237,8 @@ typedef struct {
     int32_t worker;     /* i_k: whose local data the gradient samples                              */
     int32_t reserved;
     int64_t event;      /* k, the index into the arrays of the schedule of this call               */
-    const float* xhat;  /* device, d floats, read only: row i_k of X as of logical time k - tau_k   */
+    const float* xhat;  /* device, d floats, read only: row i_k of X as of logical time k - tau_k
+                           (the wait-free variant: a copy of it with the worker's pending gradient applied) */
     float* g;           /* device, d floats: receives g_k (a pending-gradient slot of the workspace) */
 } adpsgd_grad_request_t;
 

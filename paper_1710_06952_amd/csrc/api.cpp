@@ -116,8 +116,6 @@ extern "C" int adpsgd_create(adpsgd_t** out, const adpsgd_graph_t* graph, int64_
     const adpsgd_opts_t& o = *opts;
     if (o.model < ADPSGD_MODEL_LSQ || o.model > ADPSGD_MODEL_EXTERNAL) return fail(nullptr, ADPSGD_ERR_ARG, "create: unknown model");
     const bool external = o.model == ADPSGD_MODEL_EXTERNAL;
-    if (external && o.local_compensation)
-        return fail(nullptr, ADPSGD_ERR_ARG, "create: local_compensation is not available with caller-supplied gradients");
     if (!o.X || !aligned16(o.X)) return fail(nullptr, ADPSGD_ERR_ARG, "create: X is NULL or not 16-byte aligned");
     if (o.ldx < d || (o.ldx & 3)) return fail(nullptr, ADPSGD_ERR_ARG, "create: ldx must be >= d and a multiple of 4");
     if (o.T_max < 0) return fail(nullptr, ADPSGD_ERR_ARG, "create: T_max < 0");
@@ -338,6 +336,8 @@ int run_events_impl(adpsgd_t* h, const adpsgd_schedule_t* s, float* loss, adpsgd
         group = static_cast<int32_t>(std::min<int64_t>(std::max<int64_t>(max_r, 1), h->o.model == ADPSGD_MODEL_MLP ? 64 : 65535));
     }
     if (mlp_comp) HIP_TRY(h, h->comp_rows.reserve(static_cast<size_t>(group) * h->o.ldx * sizeof(uint16_t)));
+    const bool ext_comp = external && h->o.local_compensation != 0;      // the caller's function reads a compensated copy
+    if (ext_comp) HIP_TRY(h, h->comp_rows.reserve(static_cast<size_t>(group) * h->o.ldx * sizeof(float)));
 
     // ---- tables: [PairOp x K][GradOp x K][batch_idx K x M] ----
     const size_t bytes_u = static_cast<size_t>(K + n_extra) * sizeof(PairOp);
@@ -438,11 +438,20 @@ int run_events_impl(adpsgd_t* h, const adpsgd_schedule_t* s, float* loss, adpsgd
             int launches = 0;
             if (external) {
                 requests.resize(static_cast<size_t>(cnt));
+                bool any_comp = false;
                 for (int32_t t = 0; t < cnt; ++t) {
                     const GradOp& g = rops[g0 + t];
-                    requests[t] = adpsgd_grad_request_t{g.worker, 0, g.event, h->o.X + static_cast<int64_t>(g.worker) * h->o.ldx,
-                                                        slots + static_cast<int64_t>(g.slot) * h->o.ldx};
+                    const bool comp = ext_comp && g.comp_slot >= 0;
+                    any_comp |= comp;
+                    requests[t] = adpsgd_grad_request_t{
+                        g.worker, 0, g.event,
+                        comp ? static_cast<const float*>(h->comp_rows.p) + static_cast<int64_t>(t) * h->o.ldx
+                             : h->o.X + static_cast<int64_t>(g.worker) * h->o.ldx,
+                        slots + static_cast<int64_t>(g.slot) * h->o.ldx};
                 }
+                if (any_comp)
+                    HIP_TRY(h, launch_compensated_rows(h->o.X, h->o.ldx, d_rops + g0, cnt, slots, static_cast<float*>(h->comp_rows.p),
+                                                       h->stream));
                 if (fn(user, cnt, requests.data(), h->stream) != 0) {
                     (void)hipStreamSynchronize(h->stream);      // the table upload and the rounds enqueued so far
                     return fail(h, ADPSGD_ERR_CALLBACK, "run_events_with: the gradient function failed in round " + std::to_string(r));

@@ -199,7 +199,36 @@ __global__ __launch_bounds__(kThreads) void objective_final_kernel(const double*
         *result = ((red[0] + red[1]) + (red[2] + red[3])) / n + half_lambda * ((red2[0] + red2[1]) + (red2[2] + red2[3]));
 }
 
+// Wait-free variant with caller-supplied gradients: the copy the caller's function evaluates at,
+// out[t] = X[worker] - comp_gamma * slot[comp_slot] for the operations that are compensated (two
+// roundings, as in the update itself); the others are skipped and read their row of X directly.
+// grid = (ceil(ld / 4 / kThreads), n_ops)
+__global__ __launch_bounds__(kThreads) void compensated_rows_kernel(const float* __restrict__ X, int64_t ld, const GradOp* __restrict__ ops,
+                                                                   const float* __restrict__ slots, float* __restrict__ out) {
+    const GradOp op = ops[blockIdx.y];
+    if (op.comp_slot < 0) return;
+    const int64_t e = 4 * (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x);
+    if (e >= ld) return;
+    const v4f x = *reinterpret_cast<const v4f*>(X + static_cast<int64_t>(op.worker) * ld + e);
+    const v4f g = *reinterpret_cast<const v4f*>(slots + static_cast<int64_t>(op.comp_slot) * ld + e);
+    v4f c;
+    {
+#pragma clang fp contract(off)
+        const v4f step = g * op.comp_gamma;
+        c = x - step;
+    }
+    *reinterpret_cast<v4f*>(out + static_cast<int64_t>(blockIdx.y) * ld + e) = c;
+}
+
 }  // namespace
+
+hipError_t launch_compensated_rows(const float* X, int64_t ld, const GradOp* ops, int32_t n_ops, const float* slots, float* out,
+                                   hipStream_t st) {
+    const int64_t blocks = (ld / 4 + kThreads - 1) / kThreads;
+    if (blocks > 0x7FFFFFFF || n_ops > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(compensated_rows_kernel, dim3(static_cast<uint32_t>(blocks), n_ops), dim3(kThreads), 0, st, X, ld, ops, slots, out);
+    return hipGetLastError();
+}
 
 hipError_t launch_count_nonfinite(const float* X, int64_t ld, int64_t d, int32_t n, unsigned long long* partial,
                                   int32_t blocks, hipStream_t st) {

@@ -15,6 +15,17 @@ def _pad(d, mult=64):
     return (d + mult - 1) // mult * mult
 
 
+class _DeviceSpan:
+    """d fp32 values at a device address, for torch.as_tensor (no copy)."""
+
+    def __init__(self, ptr, d):
+        self.__cuda_array_interface__ = {"shape": (d,), "typestr": "<f4", "data": (ptr, False), "version": 2}
+
+
+def _device_vector(torch, ptr, d, device):
+    return torch.as_tensor(_DeviceSpan(ptr, d), device=device)
+
+
 class Engine:
     def __init__(self, graph, d, model, *, M=0, gamma=0.0, lam=0.0, grad_sum=False, T_max=0, synth_std=0.0,
                  synth_seed=0, mlp=(0, 0, 0), n_slots=None, profile=False, momentum=0.0, weight_decay=0.0,
@@ -100,8 +111,11 @@ class Engine:
 
         def per_group(requests, _stream):
             for worker, event, xhat_ptr, g_ptr in requests:
-                assert xhat_ptr == x_base + worker * ld * 4
-                gradient_fn(worker, event, self.X[worker, :d], ws[(g_ptr - w_base) // (ld * 4), :d])
+                if xhat_ptr == x_base + worker * ld * 4:
+                    xhat = self.X[worker, :d]
+                else:                       # wait-free variant: a compensated copy in the library's scratch memory
+                    xhat = _device_vector(self.torch, xhat_ptr, d, self.device)
+                gradient_fn(worker, event, xhat, ws[(g_ptr - w_base) // (ld * 4), :d])
 
         self.h.run_events_with(schedule, per_group)
 

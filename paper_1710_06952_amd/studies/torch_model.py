@@ -9,7 +9,8 @@ receives the gradient.  The function below views the row as the parameters of a 
 (torch.func.functional_call), draws the event's minibatch from the worker's local data with a generator
 seeded by the event number, and lets autograd write the flattened gradient.
 
-The example network is a small classifier with a normalisation layer and a tanh hidden layer, on the
+By default the run uses the wait-free variant (a worker evaluates its next gradient at its stale copy with
+its own pending gradient applied), the form the paper's implementation takes.  The example network is a small classifier with a normalisation layer and a tanh hidden layer, on the
 Gaussian mixture of the convergence study; any module whose parameters are fp32 works the same way.
 
     python -m paper_1710_06952_amd.studies.torch_model [--n 8] [--epochs 4] [--json]
@@ -68,7 +69,7 @@ class FlatModule:
 
 
 def run_study(n=8, dims=(32, 64, 6), rows=1024, M=32, epochs=4, T_max=3, gamma=0.05, momentum=0.9, weight_decay=1e-4,
-              seed=0, device="cuda:0"):
+              seed=0, device="cuda:0", wait_free=True):
     import torch
     from .. import Engine, adpsgd_make_schedule
     torch.manual_seed(seed)
@@ -78,7 +79,7 @@ def run_study(n=8, dims=(32, 64, 6), rows=1024, M=32, epochs=4, T_max=3, gamma=0
     Y = [torch.from_numpy(y).to(device).long() for y in labels]
     allX, allY = torch.cat(X), torch.cat(Y)
     eng = Engine(ring(n), flat.d, "external", gamma=gamma, T_max=T_max, momentum=momentum, weight_decay=weight_decay,
-                 device=device)
+                 local_compensation=wait_free, device=device)
     eng.set_models(flat.flatten_initial())
     events_per_epoch = n * rows // M
 
