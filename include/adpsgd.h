@@ -262,6 +262,12 @@ int adpsgd_run_events_with(adpsgd_t* h, const adpsgd_schedule_t* s, adpsgd_gradi
  * Errors as adpsgd_run_events, with no state change. */
 int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* s, float* loss);
 
+/* The same iterations for ADPSGD_MODEL_EXTERNAL (else ADPSGD_ERR_STATE): in iteration t the function is
+ * asked for the gradients of all n workers at once (request i: worker i, event t * n + i, xhat = row i
+ * of X as the iteration starts, g = slot i), then the mixing kernel runs.  batch_idx is not read.
+ * Failure of fn as in adpsgd_run_events_with. */
+int adpsgd_run_sync_steps_with(adpsgd_t* h, const adpsgd_sync_schedule_t* s, adpsgd_gradient_fn fn, void* user);
+
 /* Host-only: Metropolis mixing weights of a graph, w_edge[e] = 1 / (1 + max(deg i, deg j)) for the
  * entry e = (i, j) of the CSR arrays, w_self[i] = 1 - sum of its edge weights (fp64, rounded once);
  * on a regular graph of degree q every weight is 1 / (q + 1).  Outputs: n and rowptr[n] floats. */

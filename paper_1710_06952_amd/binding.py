@@ -21,7 +21,7 @@ EXPORTS = [
     "adpsgd_create", "adpsgd_destroy", "adpsgd_last_error", "adpsgd_load_data", "adpsgd_set_models",
     "adpsgd_run_events", "adpsgd_run_events_with", "adpsgd_get_models", "adpsgd_get_mean_model", "adpsgd_consensus_distance",
     "adpsgd_get_bf16_models", "adpsgd_classification_error", "adpsgd_get_momentum", "adpsgd_get_stats", "adpsgd_make_schedule", "adpsgd_plan_rounds",
-    "adpsgd_synth_gradient", "adpsgd_run_sync_steps", "adpsgd_metropolis_weights",
+    "adpsgd_synth_gradient", "adpsgd_run_sync_steps", "adpsgd_run_sync_steps_with", "adpsgd_metropolis_weights",
     "adpsgd_get_event_count", "adpsgd_set_event_count", "adpsgd_verify_plan", "adpsgd_objective", "adpsgd_count_nonfinite",
 ]
 
@@ -127,6 +127,7 @@ def lib():
                                          P(i64), P(i32), P(i32), P(i64)]
         L.adpsgd_objective.argtypes = [vp, vp, P(C.c_double)]
         L.adpsgd_run_events_with.argtypes = [vp, P(Schedule), GRADIENT_FN, vp]
+        L.adpsgd_run_sync_steps_with.argtypes = [vp, P(SyncSchedule), GRADIENT_FN, vp]
         L.adpsgd_classification_error.argtypes = [vp, vp, P(C.c_double)]
         L.adpsgd_count_nonfinite.argtypes = [vp, P(i64)]
         L.adpsgd_get_event_count.argtypes = [vp, P(u64)]
@@ -230,6 +231,23 @@ def adpsgd_synth_gradient(seed, k, std, d, out_ptr, stream=0):
         raise AdpsgdError(rc, "adpsgd_synth_gradient failed")
 
 
+def _gradient_trampoline(gradient_fn):
+    """The C callback around a Python gradient function, and the list that catches what it raises
+    (an exception must not propagate through the C frames)."""
+    raised = []
+
+    def trampoline(_user, count, requests, stream):
+        try:
+            gradient_fn([(requests[t].worker, requests[t].event, requests[t].xhat, requests[t].g) for t in range(count)],
+                        stream or 0)
+            return 0
+        except BaseException as exc:
+            raised.append(exc)
+            return 1
+
+    return GRADIENT_FN(trampoline), raised
+
+
 class Handle:
     """Owns one adpsgd_t*.  Methods mirror the C entry points one to one; device
     pointers are plain integers (e.g. ``tensor.data_ptr()``)."""
@@ -294,18 +312,8 @@ class Handle:
         s = Schedule(worker.size, _i32p(worker), _i32p(nbr), _i32p(tau), None,
                      None if gam is None else gam.ctypes.data_as(C.POINTER(C.c_float)),
                      None if ep is None else ep.ctypes.data_as(C.POINTER(C.c_int64)), _i32p(ea), _i32p(eb))
-        raised = []
-
-        def trampoline(_user, count, requests, stream):
-            try:
-                gradient_fn([(requests[t].worker, requests[t].event, requests[t].xhat, requests[t].g) for t in range(count)],
-                            stream or 0)
-                return 0
-            except BaseException as exc:      # must not propagate through the C frames
-                raised.append(exc)
-                return 1
-
-        rc = lib().adpsgd_run_events_with(self._h, C.byref(s), GRADIENT_FN(trampoline), None)
+        callback, raised = _gradient_trampoline(gradient_fn)
+        rc = lib().adpsgd_run_events_with(self._h, C.byref(s), callback, None)
         if raised:
             raise raised[0]
         _check(self._h, rc)
@@ -322,6 +330,21 @@ class Handle:
             we = np.ascontiguousarray(weights[1], dtype=np.float32)
         s = SyncSchedule(steps, _i32p(batch), fp(gam), fp(ws), fp(we))
         _check(self._h, lib().adpsgd_run_sync_steps(self._h, C.byref(s), loss_ptr))
+
+    def run_sync_steps_with(self, steps, gradient_fn, gamma=None, weights=None):
+        """MODEL_EXTERNAL: the synchronous comparison schedule with gradient_fn as in run_events_with."""
+        fp = lambda a: None if a is None else a.ctypes.data_as(C.POINTER(C.c_float))
+        gam = None if gamma is None else np.ascontiguousarray(gamma, dtype=np.float32)
+        ws = we = None
+        if weights is not None:
+            ws = np.ascontiguousarray(weights[0], dtype=np.float32)
+            we = np.ascontiguousarray(weights[1], dtype=np.float32)
+        s = SyncSchedule(steps, None, fp(gam), fp(ws), fp(we))
+        callback, raised = _gradient_trampoline(gradient_fn)
+        rc = lib().adpsgd_run_sync_steps_with(self._h, C.byref(s), callback, None)
+        if raised:
+            raise raised[0]
+        _check(self._h, rc)
 
     def get_event_count(self):
         out = C.c_uint64(0)

@@ -6,19 +6,20 @@
 
 using namespace adpsgd_impl;
 
-extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* s, float* loss) {
-    if (!h) return ADPSGD_ERR_ARG;
+namespace {
+
+int run_sync_steps_impl(adpsgd_t* h, const adpsgd_sync_schedule_t* s, float* loss, adpsgd_gradient_fn fn, void* user) {
     if (!s || s->S < 0) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: schedule is NULL or S < 0");
     const int64_t S = s->S;
     if (S == 0) return ADPSGD_OK;
     const int32_t n = h->n;
-    if (h->o.model == ADPSGD_MODEL_EXTERNAL)
-        return fail(h, ADPSGD_ERR_STATE, "run_sync_steps: not available with caller-supplied gradients");
+    const bool external = h->o.model == ADPSGD_MODEL_EXTERNAL;
     const bool with_grad = h->o.model != ADPSGD_MODEL_SYNTH;
-    const int32_t M = with_grad ? h->o.M : 0;
+    const bool with_data = with_grad && !external;
+    const int32_t M = with_data ? h->o.M : 0;
     if (S * n > 0x7FFFFFF0) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: S * n must stay below 2^31 - 16");
     if (sync_tile_cols(n) == 0) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: at most 1024 workers");
-    if (with_grad && !s->batch_idx) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: batch_idx is NULL");
+    if (with_data && !s->batch_idx) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: batch_idx is NULL");
     if (with_grad && h->n_slots < n)
         return fail(h, ADPSGD_ERR_STATE, "run_sync_steps: the workspace must hold one gradient slot per worker");
     if ((s->w_self == nullptr) != (s->w_edge == nullptr) && h->rowptr[n] > 0)
@@ -51,7 +52,7 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
     }
     for (int64_t t = 0; t < S; ++t)
         if (s->gamma && !std::isfinite(s->gamma[t])) return fail(h, ADPSGD_ERR_SCHEDULE, "run_sync_steps: gamma not finite");
-    if (with_grad) {
+    if (with_data) {
         for (int32_t i = 0; i < n; ++i)
             if (!h->data[i].features) return fail(h, ADPSGD_ERR_STATE, "run_sync_steps: no data loaded for worker " + std::to_string(i));
         for (int64_t t = 0; t < S; ++t)
@@ -64,8 +65,8 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
     }
 
     // ---- tables: [GradOp x S n][batch_idx S n M][w_self n][w_edge nnz][rowptr n + 1][col nnz] ----
-    const size_t bytes_r = with_grad ? static_cast<size_t>(S) * n * sizeof(GradOp) : 0;
-    const size_t bytes_b = with_grad ? static_cast<size_t>(S) * n * M * sizeof(int32_t) : 0;
+    const size_t bytes_r = with_data ? static_cast<size_t>(S) * n * sizeof(GradOp) : 0;
+    const size_t bytes_b = with_data ? static_cast<size_t>(S) * n * M * sizeof(int32_t) : 0;
     const size_t off_b = bytes_r, off_ws = (off_b + bytes_b + 15) & ~size_t(15);
     const size_t off_we = off_ws + static_cast<size_t>(n) * 4, off_rp = off_we + static_cast<size_t>(std::max(nnz, 1)) * 4;
     const size_t off_col = off_rp + static_cast<size_t>(n + 1) * 4, total = off_col + static_cast<size_t>(std::max(nnz, 1)) * 4;
@@ -78,7 +79,7 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
     HIP_TRY(h, T.stage.reserve(total));
     HIP_TRY(h, T.dev.reserve(total));
     char* stage = static_cast<char*>(T.stage.p);
-    if (with_grad) {
+    if (with_data) {
         GradOp* rops = reinterpret_cast<GradOp*>(stage);
         for (int64_t t = 0; t < S; ++t)
             for (int32_t i = 0; i < n; ++i)
@@ -97,7 +98,7 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
 
     int32_t group = 1;
     size_t off_coef = 0;
-    if (with_grad) {
+    if (with_data) {
         if (h->o.model == ADPSGD_MODEL_MLP) {
             group = std::min<int32_t>(n, 64);
             HIP_TRY(h, h->grad_scratch.reserve(mlp_scratch_bytes(group, M, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out)));
@@ -111,8 +112,19 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
     const bool profile = (h->o.flags & ADPSGD_FLAG_PROFILE) != 0;
     float* slots = static_cast<float*>(h->o.workspace);
     const float gscale = h->o.grad_sum ? 1.0f : 1.0f / static_cast<float>(std::max(M, 1));
+    std::vector<adpsgd_grad_request_t> requests(external ? n : 0);
     for (int64_t t = 0; t < S; ++t) {
-        for (int32_t g0 = 0; with_grad && g0 < n; g0 += group) {
+        if (external) {       // every worker's gradient at the model the iteration starts from, into slot i
+            for (int32_t i = 0; i < n; ++i)
+                requests[i] = adpsgd_grad_request_t{i, 0, t * n + i, h->o.X + static_cast<int64_t>(i) * h->o.ldx,
+                                                    slots + static_cast<int64_t>(i) * h->o.ldx};
+            if (fn(user, n, requests.data(), h->stream) != 0) {
+                (void)hipStreamSynchronize(h->stream);
+                return fail(h, ADPSGD_ERR_CALLBACK, "run_sync_steps_with: the gradient function failed in iteration " + std::to_string(t));
+            }
+            ++h->stats.grad_launches;
+        }
+        for (int32_t g0 = 0; with_data && g0 < n; g0 += group) {
             const int32_t cnt = std::min<int32_t>(group, n - g0);
             int launches = 0;
             if (h->o.model == ADPSGD_MODEL_MLP) {
@@ -156,6 +168,23 @@ extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* 
     h->stats.events += S * n;
     h->stats.rounds += S;
     return ADPSGD_OK;
+}
+
+}  // namespace
+
+extern "C" int adpsgd_run_sync_steps(adpsgd_t* h, const adpsgd_sync_schedule_t* s, float* loss) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (h->o.model == ADPSGD_MODEL_EXTERNAL)
+        return fail(h, ADPSGD_ERR_STATE, "run_sync_steps: caller-supplied gradients need adpsgd_run_sync_steps_with");
+    return run_sync_steps_impl(h, s, loss, nullptr, nullptr);
+}
+
+extern "C" int adpsgd_run_sync_steps_with(adpsgd_t* h, const adpsgd_sync_schedule_t* s, adpsgd_gradient_fn fn, void* user) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (h->o.model != ADPSGD_MODEL_EXTERNAL)
+        return fail(h, ADPSGD_ERR_STATE, "run_sync_steps_with: the handle was not created with ADPSGD_MODEL_EXTERNAL");
+    if (!fn) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps_with: fn is NULL");
+    return run_sync_steps_impl(h, s, nullptr, fn, user);
 }
 
 extern "C" int adpsgd_metropolis_weights(const adpsgd_graph_t* graph, float* w_self, float* w_edge) {

@@ -102,10 +102,9 @@ class Engine:
             loss_ptr = self.loss.data_ptr()
         self.h.run_events(schedule, loss_ptr)
 
-    def run_events_with(self, schedule, gradient_fn):
-        """Model "external": gradient_fn(worker, event, xhat, g) is called for every event with two views
-        of device memory, the model to evaluate at (d floats, read only) and the slot that receives the
-        gradient; it must work on PyTorch's current stream, which is the stream the engine was created on."""
+    def _per_group(self, gradient_fn):
+        """Wraps gradient_fn(worker, event, xhat, g), which takes two views of device memory, into the
+        binding's form (a list of requests with raw pointers)."""
         ws, ld, d = self.workspace.view(-1, self.ld), self.ld, self.d
         x_base, w_base = self.X.data_ptr(), self.workspace.data_ptr()
 
@@ -117,7 +116,17 @@ class Engine:
                     xhat = _device_vector(self.torch, xhat_ptr, d, self.device)
                 gradient_fn(worker, event, xhat, ws[(g_ptr - w_base) // (ld * 4), :d])
 
-        self.h.run_events_with(schedule, per_group)
+        return per_group
+
+    def run_events_with(self, schedule, gradient_fn):
+        """Model "external": gradient_fn(worker, event, xhat, g) is called for every event with two views
+        of device memory, the model to evaluate at (d floats, read only) and the slot that receives the
+        gradient; it must work on PyTorch's current stream, which is the stream the engine was created on."""
+        self.h.run_events_with(schedule, self._per_group(gradient_fn))
+
+    def run_sync_steps_with(self, steps, gradient_fn, gamma=None, weights=None):
+        """Model "external": the synchronous comparison schedule; event = iteration * n + worker."""
+        self.h.run_sync_steps_with(steps, self._per_group(gradient_fn), gamma, weights)
 
     def run_sync_steps(self, steps, batch_idx=None, gamma=None, weights=None, want_loss=False):
         """The synchronous comparison schedule (all workers step together, mixing with all neighbours)."""

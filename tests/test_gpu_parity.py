@@ -1023,6 +1023,25 @@ def test_external_gradients_from_pytorch_follow_algorithm_1(P):
     assert rel_err(wf.get_models(), Xn) > 20 * TOL             # the compensation is not a no-op here
     wf.close()
 
+    # the synchronous comparison schedule with the same kind of function
+    S = 20
+    sync_batch = np.random.default_rng(9).integers(0, rows, size=(S, n, M)).astype(np.int32)
+    sb = torch.from_numpy(sync_batch).cuda().long()
+
+    def sync_gradient(worker, event, xhat, out):
+        rows_b = A[worker][sb[event // n, worker]]
+        assert event % n == worker
+        out.copy_((rows_b.T @ (rows_b @ xhat.double() - b[worker][sb[event // n, worker]]) / M).float())
+
+    sy = P.Engine(g, d, "external", gamma=0.3, n_slots=n, momentum=0.9, weight_decay=1e-3)
+    sy.set_models(x0)
+    sy.run_sync_steps_with(S, sync_gradient)
+    Xs, Vs = np.tile(x0, (n, 1)), np.zeros((n, d), np.float32)
+    oracle.run_sync_steps(Xs, sync_batch, oracle.metropolis_weights(g), oracle.MODEL_LSQ, 0.3, M=M, gscale=1.0 / M,
+                          features=feats, targets=targs, momentum=0.9, weight_decay=1e-3, V=Vs)
+    assert rel_err(sy.get_models(), Xs) <= TOL and rel_err(sy.get_momentum(), Vs) <= 5 * TOL
+    sy.close()
+
     calls = []
 
     def failing(worker, event, xhat, out):
