@@ -282,67 +282,89 @@ int validate_schedule(adpsgd_t* h, const adpsgd_schedule_t* s, bool with_data, i
     return ADPSGD_OK;
 }
 
-// The events of one call: plan, tables, then per round the gradients (the library's kernels, or the
-// caller's function for ADPSGD_MODEL_EXTERNAL) and one update launch.
-int run_events_impl(adpsgd_t* h, const adpsgd_schedule_t* s, float* loss, adpsgd_gradient_fn fn, void* user) {
-    if (!s || s->K < 0) return fail(h, ADPSGD_ERR_ARG, "run_events: schedule is NULL or K < 0");
-    const int64_t K = s->K;
-    if (K == 0) return ADPSGD_OK;
-    if (K > 0x7FFFFFF0) return fail(h, ADPSGD_ERR_ARG, "run_events: at most 2^31 - 16 events per call");
-    if (!s->worker || !s->neighbour || !s->tau) return fail(h, ADPSGD_ERR_ARG, "run_events: null schedule array");
-    const bool external = h->o.model == ADPSGD_MODEL_EXTERNAL;
-    const bool with_grad = h->o.model != ADPSGD_MODEL_SYNTH;
-    const int32_t M = with_grad && !external ? h->o.M : 0;
-    if (with_grad && !external && !s->batch_idx) return fail(h, ADPSGD_ERR_ARG, "run_events: batch_idx is NULL");
+// What one call of run_events works with: the paths taken, the plan sorted by round, the tables.
+struct EventCall {
+    const adpsgd_schedule_t* s = nullptr;
+    int64_t K = 0, n_extra = 0;
+    int32_t M = 0;
+    bool external = false;      // gradients from the caller's function
+    bool with_grad = false;     // the events carry gradients held in pending slots (every model but SYNTH)
+    bool mlp_comp = false;      // perceptron, wait-free variant: compensated bf16 rows
+    bool ext_comp = false;      // caller's function, wait-free variant: compensated fp32 rows
+    bool factored = false;      // perceptron: dW1 stays in factored form until the update kernel
+    bool lin_factored = false;  // least squares on long models: the gradient stays M coefficients
+    Plan plan;
+    std::vector<int64_t> u_off, r_off;      // first update / gradient operation of every round
+    int32_t group = 1;                      // gradients of a round are launched in groups of this many operations
+    TableSet* T = nullptr;
+    PairOp* uops = nullptr;                 // pinned staging, sorted by round
+    GradOp* rops = nullptr;
+    const PairOp* d_uops = nullptr;         // the device copy
+    const GradOp* d_rops = nullptr;
+    const int32_t* d_batch = nullptr;
+    size_t off_coef = 0;                    // linear models: offset of the coefficients in the gradient scratch
+};
 
-    const int64_t n_extra = s->extra_ptr ? s->extra_ptr[K] : 0;
-    const int rc_valid = validate_schedule(h, s, with_grad && !external, M, n_extra);
+// Validation, choice of paths, plan of rounds, counting sort of the operations by round.
+int prepare_call(adpsgd_t* h, const adpsgd_schedule_t* s, EventCall& c) {
+    c.s = s;
+    c.K = s->K;
+    if (c.K > 0x7FFFFFF0) return fail(h, ADPSGD_ERR_ARG, "run_events: at most 2^31 - 16 events per call");
+    if (!s->worker || !s->neighbour || !s->tau) return fail(h, ADPSGD_ERR_ARG, "run_events: null schedule array");
+    c.external = h->o.model == ADPSGD_MODEL_EXTERNAL;
+    c.with_grad = h->o.model != ADPSGD_MODEL_SYNTH;
+    const bool with_data = c.with_grad && !c.external;
+    c.M = with_data ? h->o.M : 0;
+    if (with_data && !s->batch_idx) return fail(h, ADPSGD_ERR_ARG, "run_events: batch_idx is NULL");
+    c.n_extra = s->extra_ptr ? s->extra_ptr[c.K] : 0;
+    const int rc_valid = validate_schedule(h, s, with_data, c.M, c.n_extra);
     if (rc_valid != ADPSGD_OK) return rc_valid;
 
-    // perceptron: dW1 stays in factored form until the update kernel
-    // (the wait-free variant reads the pending gradient as a dense vector, so it keeps the dense form)
-    const bool mlp_comp = h->o.model == ADPSGD_MODEL_MLP && h->o.local_compensation != 0;
-    const bool factored = h->o.model == ADPSGD_MODEL_MLP && !(h->o.flags & ADPSGD_FLAG_DENSE_GRADIENT) &&
-                          !mlp_comp && mlp_can_factor(h->o.mlp_in, h->o.mlp_hidden, M);
+    // the wait-free variant reads the pending gradient as a dense vector, so it keeps the dense form
+    const bool comp = h->o.local_compensation != 0, dense = (h->o.flags & ADPSGD_FLAG_DENSE_GRADIENT) != 0;
+    c.mlp_comp = h->o.model == ADPSGD_MODEL_MLP && comp;
+    c.ext_comp = c.external && comp;
+    c.factored = h->o.model == ADPSGD_MODEL_MLP && !dense && !comp && mlp_can_factor(h->o.mlp_in, h->o.mlp_hidden, c.M);
+    c.lin_factored = with_data && !dense && !comp && linear_can_factor(h->o.model, h->d, c.M, h->o.ldx);
 
-    // least squares on long models: the gradient stays M coefficients until the update kernel applies it
-    const bool lin_factored = !h->o.local_compensation && !(h->o.flags & ADPSGD_FLAG_DENSE_GRADIENT) &&
-                              with_grad && linear_can_factor(h->o.model, h->d, M, h->o.ldx);
-
-    // ---- plan ----
-    Plan plan;
     std::string perr;
-    int rc = plan_rounds(h->n, K, s->worker, s->neighbour, s->tau, h->n_slots, with_grad, plan, perr,
-                         s->extra_ptr, s->extra_a, s->extra_b, h->o.local_compensation != 0);
+    const int rc = plan_rounds(h->n, c.K, s->worker, s->neighbour, s->tau, h->n_slots, c.with_grad, c.plan, perr,
+                               s->extra_ptr, s->extra_a, s->extra_b, comp);
     if (rc != ADPSGD_OK) return fail(h, rc, perr);
     if ((h->o.flags & ADPSGD_FLAG_VERIFY_PLAN) &&
-        !verify_plan(h->n, K, s->worker, s->neighbour, s->tau, h->n_slots, with_grad, plan, perr, s->extra_ptr, s->extra_a, s->extra_b))
+        !verify_plan(h->n, c.K, s->worker, s->neighbour, s->tau, h->n_slots, c.with_grad, c.plan, perr, s->extra_ptr, s->extra_a,
+                     s->extra_b))
         return fail(h, ADPSGD_ERR_STATE, perr);
-    const int32_t R = plan.n_rounds;
 
-    // counting sort of the operations by round
-    std::vector<int64_t> u_off(static_cast<size_t>(R) + 1, 0), r_off(static_cast<size_t>(R) + 1, 0);
-    for (int64_t k = 0; k < K; ++k) {
-        u_off[plan.u_round[k] + 1] += 1 + (s->extra_ptr ? s->extra_ptr[k + 1] - s->extra_ptr[k] : 0);
-        if (with_grad) ++r_off[plan.r_round[k] + 1];
+    const int32_t R = c.plan.n_rounds;
+    c.u_off.assign(static_cast<size_t>(R) + 1, 0);
+    c.r_off.assign(static_cast<size_t>(R) + 1, 0);
+    for (int64_t k = 0; k < c.K; ++k) {
+        c.u_off[c.plan.u_round[k] + 1] += 1 + (s->extra_ptr ? s->extra_ptr[k + 1] - s->extra_ptr[k] : 0);
+        if (c.with_grad) ++c.r_off[c.plan.r_round[k] + 1];
     }
-    for (int32_t r = 0; r < R; ++r) { u_off[r + 1] += u_off[r]; r_off[r + 1] += r_off[r]; }
-
-    // gradients of a round are launched in groups of this many operations
-    int32_t group = 1;
-    if (with_grad) {
-        int64_t max_r = 0;
-        for (int32_t r = 0; r < R; ++r) max_r = std::max(max_r, r_off[r + 1] - r_off[r]);
-        group = static_cast<int32_t>(std::min<int64_t>(std::max<int64_t>(max_r, 1), h->o.model == ADPSGD_MODEL_MLP ? 64 : 65535));
+    int64_t max_r = 0;
+    for (int32_t r = 0; r < R; ++r) {
+        max_r = std::max(max_r, c.r_off[r + 1]);
+        c.u_off[r + 1] += c.u_off[r];
+        c.r_off[r + 1] += c.r_off[r];
     }
-    if (mlp_comp) HIP_TRY(h, h->comp_rows.reserve(static_cast<size_t>(group) * h->o.ldx * sizeof(uint16_t)));
-    const bool ext_comp = external && h->o.local_compensation != 0;      // the caller's function reads a compensated copy
-    if (ext_comp) HIP_TRY(h, h->comp_rows.reserve(static_cast<size_t>(group) * h->o.ldx * sizeof(float)));
+    if (c.with_grad)
+        c.group = static_cast<int32_t>(std::min<int64_t>(std::max<int64_t>(max_r, 1), h->o.model == ADPSGD_MODEL_MLP ? 64 : 65535));
+    return ADPSGD_OK;
+}
 
-    // ---- tables: [PairOp x K][GradOp x K][batch_idx K x M] ----
-    const size_t bytes_u = static_cast<size_t>(K + n_extra) * sizeof(PairOp);
-    const size_t bytes_r = with_grad ? static_cast<size_t>(K) * sizeof(GradOp) : 0;
-    const size_t bytes_b = with_grad ? static_cast<size_t>(K) * M * sizeof(int32_t) : 0;
+// Tables [PairOp x (K + extra pairs)][GradOp x K][batch_idx K x M], filled in pinned memory in round
+// order and uploaded with one copy; scratch memory of the gradient kernels.
+int upload_tables(adpsgd_t* h, EventCall& c) {
+    const adpsgd_schedule_t* s = c.s;
+    const int64_t K = c.K;
+    const int32_t M = c.M;
+    if (c.mlp_comp) HIP_TRY(h, h->comp_rows.reserve(static_cast<size_t>(c.group) * h->o.ldx * sizeof(uint16_t)));
+    if (c.ext_comp) HIP_TRY(h, h->comp_rows.reserve(static_cast<size_t>(c.group) * h->o.ldx * sizeof(float)));
+    const size_t bytes_u = static_cast<size_t>(K + c.n_extra) * sizeof(PairOp);
+    const size_t bytes_r = c.with_grad ? static_cast<size_t>(K) * sizeof(GradOp) : 0;
+    const size_t bytes_b = static_cast<size_t>(K) * M * sizeof(int32_t);
     const size_t off_r = bytes_u, off_b = (off_r + bytes_r + 15) & ~size_t(15);
     const size_t total = off_b + bytes_b;
 
@@ -354,165 +376,186 @@ int run_events_impl(adpsgd_t* h, const adpsgd_schedule_t* s, float* loss, adpsgd
     }
     HIP_TRY(h, T.stage.reserve(total));
     HIP_TRY(h, T.dev.reserve(total));
+    c.T = &T;
     char* stage = static_cast<char*>(T.stage.p);
-    PairOp* uops = reinterpret_cast<PairOp*>(stage);
-    GradOp* rops = reinterpret_cast<GradOp*>(stage + off_r);
-    {
-        std::vector<int64_t> u_fill(u_off.begin(), u_off.end() - 1), r_fill(r_off.begin(), r_off.end() - 1);
-        for (int64_t k = 0; k < K; ++k) {
-            const uint64_t gk = h->events_done + static_cast<uint64_t>(k);
-            PairOp& u = uops[u_fill[plan.u_round[k]]++];
-            u.i = s->worker[k];
-            u.j = s->neighbour[k];
-            u.k_lo = static_cast<uint32_t>(gk);
-            u.k_hi = static_cast<uint32_t>(gk >> 32);
-            u.gamma = s->gamma ? s->gamma[k] : h->o.gamma;
-            u.slot = with_grad ? plan.slot[k] : 0;
-            u.flags = 0;
-            u.event = static_cast<int32_t>(k);
-            u.features = (factored || lin_factored) ? h->data[u.i].features : nullptr;
-            u.feat_ld = (factored || lin_factored) ? h->data[u.i].ld : 0;
-            if (s->extra_ptr) {
-                for (int64_t q = s->extra_ptr[k]; q < s->extra_ptr[k + 1]; ++q) {
-                    PairOp& x = uops[u_fill[plan.u_round[k]]++];
-                    x = PairOp{s->extra_a[q], s->extra_b[q], 0u, 0u, 0.0f, 0, 1, 0, nullptr, 0};
-                }
-            }
-            if (with_grad) {
-                const int64_t at = r_fill[plan.r_round[k]]++;
-                GradOp& g = rops[at];
-                g.worker = s->worker[k];
-                g.slot = plan.slot[k];
-                g.event = static_cast<int32_t>(k);
-                const int64_t kp = plan.prev[k];
-                g.comp_slot = kp >= 0 ? plan.slot[kp] : -1;
-                g.comp_gamma = kp >= 0 ? (s->gamma ? s->gamma[kp] : h->o.gamma) : 0.0f;
-                g.count = 0;
-                const WorkerData& w = h->data[g.worker];
-                g.features = w.features;
-                g.targets = w.targets;
-                g.ld = w.ld;
-                g.xrow_bf16 = nullptr;
-                if (mlp_comp && kp >= 0)      // one compensated row per operation of a launch group
-                    g.xrow_bf16 = static_cast<uint16_t*>(h->comp_rows.p) + ((at - r_off[plan.r_round[k]]) % group) * h->o.ldx;
-            }
-        }
+    c.uops = reinterpret_cast<PairOp*>(stage);
+    c.rops = reinterpret_cast<GradOp*>(stage + off_r);
+    const bool factors = c.factored || c.lin_factored;
+    std::vector<int64_t> u_fill(c.u_off.begin(), c.u_off.end() - 1), r_fill(c.r_off.begin(), c.r_off.end() - 1);
+    for (int64_t k = 0; k < K; ++k) {
+        const uint64_t gk = h->events_done + static_cast<uint64_t>(k);
+        const int32_t ur = c.plan.u_round[k];
+        PairOp& u = c.uops[u_fill[ur]++];
+        u.i = s->worker[k];
+        u.j = s->neighbour[k];
+        u.k_lo = static_cast<uint32_t>(gk);
+        u.k_hi = static_cast<uint32_t>(gk >> 32);
+        u.gamma = s->gamma ? s->gamma[k] : h->o.gamma;
+        u.slot = c.with_grad ? c.plan.slot[k] : 0;
+        u.flags = 0;
+        u.event = static_cast<int32_t>(k);
+        u.features = factors ? h->data[u.i].features : nullptr;
+        u.feat_ld = factors ? h->data[u.i].ld : 0;
+        if (s->extra_ptr)
+            for (int64_t q = s->extra_ptr[k]; q < s->extra_ptr[k + 1]; ++q)
+                c.uops[u_fill[ur]++] = PairOp{s->extra_a[q], s->extra_b[q], 0u, 0u, 0.0f, 0, 1, 0, nullptr, 0};
+        if (!c.with_grad) continue;
+        const int32_t rr = c.plan.r_round[k];
+        const int64_t at = r_fill[rr]++;
+        GradOp& g = c.rops[at];
+        g.worker = s->worker[k];
+        g.slot = c.plan.slot[k];
+        g.event = static_cast<int32_t>(k);
+        const int64_t kp = c.plan.prev[k];
+        g.comp_slot = kp >= 0 ? c.plan.slot[kp] : -1;
+        g.comp_gamma = kp >= 0 ? (s->gamma ? s->gamma[kp] : h->o.gamma) : 0.0f;
+        g.count = 0;
+        const WorkerData& w = h->data[g.worker];
+        g.features = w.features;
+        g.targets = w.targets;
+        g.ld = w.ld;
+        g.xrow_bf16 = nullptr;
+        if (c.mlp_comp && kp >= 0)      // one compensated row per operation of a launch group
+            g.xrow_bf16 = static_cast<uint16_t*>(h->comp_rows.p) + ((at - c.r_off[rr]) % c.group) * h->o.ldx;
     }
     if (bytes_b > 0) std::memcpy(stage + off_b, s->batch_idx, bytes_b);
     HIP_TRY(h, hipMemcpyAsync(T.dev.p, T.stage.p, total, hipMemcpyHostToDevice, h->stream));
     const char* dev = static_cast<const char*>(T.dev.p);
-    const PairOp* d_uops = reinterpret_cast<const PairOp*>(dev);
-    const GradOp* d_rops = reinterpret_cast<const GradOp*>(dev + off_r);
-    const int32_t* d_batch = reinterpret_cast<const int32_t*>(dev + off_b);
+    c.d_uops = reinterpret_cast<const PairOp*>(dev);
+    c.d_rops = reinterpret_cast<const GradOp*>(dev + off_r);
+    c.d_batch = reinterpret_cast<const int32_t*>(dev + off_b);
 
-
-    // ---- gradient scratch ----
-    size_t off_coef = 0;
-    if (with_grad && !external) {
+    if (c.with_grad && !c.external) {
         if (h->o.model == ADPSGD_MODEL_MLP) {
-            HIP_TRY(h, h->grad_scratch.reserve(mlp_scratch_bytes(group, M, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out)));
+            HIP_TRY(h, h->grad_scratch.reserve(mlp_scratch_bytes(c.group, M, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out)));
         } else {
             // all gradients of a round go into one set of launches (measured: splitting a round so
             // that the gathered rows stay within the memory-side cache only adds launches)
-            const size_t partial_bytes = static_cast<size_t>(group) * (M + 1) * linear_grad_chunks(h->d) * 4;
-            off_coef = (partial_bytes + 255) & ~size_t(255);
-            HIP_TRY(h, h->grad_scratch.reserve(off_coef + static_cast<size_t>(group) * M * 4));
+            const size_t partial_bytes = static_cast<size_t>(c.group) * (M + 1) * linear_grad_chunks(h->d) * 4;
+            c.off_coef = (partial_bytes + 255) & ~size_t(255);
+            HIP_TRY(h, h->grad_scratch.reserve(c.off_coef + static_cast<size_t>(c.group) * M * 4));
         }
     }
+    return ADPSGD_OK;
+}
 
-    // ---- rounds ----
-    const bool profile = (h->o.flags & ADPSGD_FLAG_PROFILE) != 0;
+// A pair of HIP events around a launch when per-launch timing is on (nullptr otherwise).
+int begin_timing(adpsgd_t* h, hipEvent_t& e0, hipEvent_t& e1) {
+    e0 = e1 = nullptr;
+    if (!(h->o.flags & ADPSGD_FLAG_PROFILE)) return ADPSGD_OK;
+    e0 = take_event(h);
+    e1 = take_event(h);
+    if (!e0 || !e1) return fail(h, ADPSGD_ERR_HIP, "run_events: hipEventCreate failed");
+    HIP_TRY(h, hipEventRecord(e0, h->stream));
+    return ADPSGD_OK;
+}
+int end_timing(adpsgd_t* h, hipEvent_t e0, hipEvent_t e1, std::vector<std::pair<hipEvent_t, hipEvent_t>>& into) {
+    if (!e0) return ADPSGD_OK;
+    HIP_TRY(h, hipEventRecord(e1, h->stream));
+    into.push_back({e0, e1});
+    return ADPSGD_OK;
+}
+
+// The stale gradients of round r: the library's kernels, or the caller's function.
+int launch_gradients(adpsgd_t* h, const EventCall& c, int32_t r, float* loss, adpsgd_gradient_fn fn, void* user,
+                     std::vector<adpsgd_grad_request_t>& requests) {
     float* slots = static_cast<float*>(h->o.workspace);
-    const float gscale = h->o.grad_sum ? 1.0f : 1.0f / static_cast<float>(std::max(M, 1));
-    std::vector<adpsgd_grad_request_t> requests;
-    for (int32_t r = 0; r < R; ++r) {
-        for (int64_t g0 = r_off[r]; g0 < r_off[r + 1]; g0 += group) {
-            const int32_t cnt = static_cast<int32_t>(std::min<int64_t>(group, r_off[r + 1] - g0));
-            hipEvent_t e0 = nullptr, e1 = nullptr;
-            if (profile) {
-                e0 = take_event(h);
-                e1 = take_event(h);
-                if (!e0 || !e1) return fail(h, ADPSGD_ERR_HIP, "run_events: hipEventCreate failed");
-                HIP_TRY(h, hipEventRecord(e0, h->stream));
+    const float gscale = h->o.grad_sum ? 1.0f : 1.0f / static_cast<float>(std::max(c.M, 1));
+    for (int64_t g0 = c.r_off[r]; g0 < c.r_off[r + 1]; g0 += c.group) {
+        const int32_t cnt = static_cast<int32_t>(std::min<int64_t>(c.group, c.r_off[r + 1] - g0));
+        hipEvent_t e0, e1;
+        int rc = begin_timing(h, e0, e1);
+        if (rc != ADPSGD_OK) return rc;
+        int launches = 0;
+        if (c.external) {
+            requests.resize(static_cast<size_t>(cnt));
+            bool any_comp = false;
+            for (int32_t t = 0; t < cnt; ++t) {
+                const GradOp& g = c.rops[g0 + t];
+                const bool comp = c.ext_comp && g.comp_slot >= 0;
+                any_comp |= comp;
+                requests[t] = adpsgd_grad_request_t{
+                    g.worker, 0, g.event,
+                    comp ? static_cast<const float*>(h->comp_rows.p) + static_cast<int64_t>(t) * h->o.ldx
+                         : h->o.X + static_cast<int64_t>(g.worker) * h->o.ldx,
+                    slots + static_cast<int64_t>(g.slot) * h->o.ldx};
             }
-            int launches = 0;
-            if (external) {
-                requests.resize(static_cast<size_t>(cnt));
-                bool any_comp = false;
-                for (int32_t t = 0; t < cnt; ++t) {
-                    const GradOp& g = rops[g0 + t];
-                    const bool comp = ext_comp && g.comp_slot >= 0;
-                    any_comp |= comp;
-                    requests[t] = adpsgd_grad_request_t{
-                        g.worker, 0, g.event,
-                        comp ? static_cast<const float*>(h->comp_rows.p) + static_cast<int64_t>(t) * h->o.ldx
-                             : h->o.X + static_cast<int64_t>(g.worker) * h->o.ldx,
-                        slots + static_cast<int64_t>(g.slot) * h->o.ldx};
-                }
-                if (any_comp)
-                    HIP_TRY(h, launch_compensated_rows(h->o.X, h->o.ldx, d_rops + g0, cnt, slots, static_cast<float*>(h->comp_rows.p),
-                                                       h->stream));
-                if (fn(user, cnt, requests.data(), h->stream) != 0) {
-                    (void)hipStreamSynchronize(h->stream);      // the table upload and the rounds enqueued so far
-                    return fail(h, ADPSGD_ERR_CALLBACK, "run_events_with: the gradient function failed in round " + std::to_string(r));
-                }
-                launches = 1;
-            } else if (h->o.model == ADPSGD_MODEL_MLP) {
-                MlpGradArgs a{h->o.X, h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, d_rops + g0, cnt, M,
-                              d_batch, slots, gscale, loss,
-                              h->grad_scratch.p, factored, mlp_comp};
-                HIP_TRY(h, launch_mlp_gradient(a, h->stream, &launches));
-            } else {
-                LinearGradArgs a{h->o.model, h->o.X, h->o.ldx, h->d, d_rops + g0, cnt, M, d_batch,
-                                 slots, gscale, h->o.lambda,
-                                 static_cast<float*>(h->grad_scratch.p),
-                                 reinterpret_cast<float*>(static_cast<char*>(h->grad_scratch.p) + off_coef), loss, lin_factored};
-                HIP_TRY(h, launch_linear_gradient(a, h->stream, &launches));
+            if (any_comp)
+                HIP_TRY(h, launch_compensated_rows(h->o.X, h->o.ldx, c.d_rops + g0, cnt, slots, static_cast<float*>(h->comp_rows.p),
+                                                   h->stream));
+            if (fn(user, cnt, requests.data(), h->stream) != 0) {
+                (void)hipStreamSynchronize(h->stream);      // the table upload and the rounds enqueued so far
+                return fail(h, ADPSGD_ERR_CALLBACK, "run_events_with: the gradient function failed in round " + std::to_string(r));
             }
-            h->stats.grad_launches += launches;
-            if (profile) {
-                HIP_TRY(h, hipEventRecord(e1, h->stream));
-                h->ev_grad.push_back({e0, e1});
-            }
+            launches = 1;
+        } else if (h->o.model == ADPSGD_MODEL_MLP) {
+            MlpGradArgs a{h->o.X, h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, c.d_rops + g0, cnt, c.M,
+                          c.d_batch, slots, gscale, loss, h->grad_scratch.p, c.factored, c.mlp_comp};
+            HIP_TRY(h, launch_mlp_gradient(a, h->stream, &launches));
+        } else {
+            LinearGradArgs a{h->o.model, h->o.X, h->o.ldx, h->d, c.d_rops + g0, cnt, c.M, c.d_batch, slots, gscale, h->o.lambda,
+                             static_cast<float*>(h->grad_scratch.p),
+                             reinterpret_cast<float*>(static_cast<char*>(h->grad_scratch.p) + c.off_coef), loss, c.lin_factored};
+            HIP_TRY(h, launch_linear_gradient(a, h->stream, &launches));
         }
-        const int64_t nu = u_off[r + 1] - u_off[r];
-        if (nu > 0) {
-            hipEvent_t e0 = nullptr, e1 = nullptr;
-            if (profile) {
-                e0 = take_event(h);
-                e1 = take_event(h);
-                if (!e0 || !e1) return fail(h, ADPSGD_ERR_HIP, "run_events: hipEventCreate failed");
-                HIP_TRY(h, hipEventRecord(e0, h->stream));
-            }
-            bool has_solo = false;
-            for (int64_t t = u_off[r]; t < u_off[r + 1] && !has_solo; ++t) has_solo = uops[t].i == uops[t].j;
-            if (lin_factored) {
-                LinearApplyArgs a{h->o.X, h->o.ldx, h->d, d_uops + u_off[r], static_cast<int32_t>(nu), slots, d_batch, M,
-                                  h->streaming, h->o.V, h->o.momentum, h->o.weight_decay};
-                HIP_TRY(h, launch_linear_apply_factored(a, h->stream));
-            } else if (factored) {
-                MlpApplyArgs a{h->o.X, h->o.ldx, h->d, h->o.mlp_in, h->o.mlp_hidden, M, d_uops + u_off[r],
-                               static_cast<int32_t>(nu), slots, h->o.Xbf16, d_batch, h->o.V, h->o.momentum, h->o.weight_decay};
-                HIP_TRY(h, launch_mlp_apply_factored(a, h->stream));
-            } else {
-                FusedArgs a{h->o.X, h->o.ldx, h->d, d_uops + u_off[r], static_cast<int32_t>(nu), slots,
-                            h->o.model == ADPSGD_MODEL_MLP ? h->o.Xbf16 : nullptr, h->o.synth_std, h->o.synth_seed,
-                            !with_grad, h->streaming, has_solo, h->o.V, h->o.momentum, h->o.weight_decay};
-                HIP_TRY(h, launch_fused_gossip_apply(a, h->stream));
-            }
-            ++h->stats.fused_launches;
-            h->stats.max_round_pairs = std::max<int64_t>(h->stats.max_round_pairs, nu);
-            if (profile) {
-                HIP_TRY(h, hipEventRecord(e1, h->stream));
-                h->ev_fused.push_back({e0, e1});
-            }
-        }
+        h->stats.grad_launches += launches;
+        rc = end_timing(h, e0, e1, h->ev_grad);
+        if (rc != ADPSGD_OK) return rc;
     }
-    HIP_TRY(h, hipEventRecord(T.done, h->stream));
-    T.in_flight = true;
-    h->events_done += static_cast<uint64_t>(K);
-    h->stats.events += K;
-    h->stats.rounds += R;
+    return ADPSGD_OK;
+}
+
+// The averaging and update operations of round r: one launch.
+int launch_updates(adpsgd_t* h, const EventCall& c, int32_t r) {
+    const int64_t nu = c.u_off[r + 1] - c.u_off[r];
+    if (nu <= 0) return ADPSGD_OK;
+    float* slots = static_cast<float*>(h->o.workspace);
+    const PairOp* d_ops = c.d_uops + c.u_off[r];
+    hipEvent_t e0, e1;
+    int rc = begin_timing(h, e0, e1);
+    if (rc != ADPSGD_OK) return rc;
+    if (c.lin_factored) {
+        LinearApplyArgs a{h->o.X, h->o.ldx, h->d, d_ops, static_cast<int32_t>(nu), slots, c.d_batch, c.M,
+                          h->streaming, h->o.V, h->o.momentum, h->o.weight_decay};
+        HIP_TRY(h, launch_linear_apply_factored(a, h->stream));
+    } else if (c.factored) {
+        MlpApplyArgs a{h->o.X, h->o.ldx, h->d, h->o.mlp_in, h->o.mlp_hidden, c.M, d_ops, static_cast<int32_t>(nu), slots, h->o.Xbf16,
+                       c.d_batch, h->o.V, h->o.momentum, h->o.weight_decay};
+        HIP_TRY(h, launch_mlp_apply_factored(a, h->stream));
+    } else {
+        bool has_solo = false;
+        for (int64_t t = c.u_off[r]; t < c.u_off[r + 1] && !has_solo; ++t) has_solo = c.uops[t].i == c.uops[t].j;
+        FusedArgs a{h->o.X, h->o.ldx, h->d, d_ops, static_cast<int32_t>(nu), slots,
+                    h->o.model == ADPSGD_MODEL_MLP ? h->o.Xbf16 : nullptr, h->o.synth_std, h->o.synth_seed,
+                    !c.with_grad, h->streaming, has_solo, h->o.V, h->o.momentum, h->o.weight_decay};
+        HIP_TRY(h, launch_fused_gossip_apply(a, h->stream));
+    }
+    ++h->stats.fused_launches;
+    h->stats.max_round_pairs = std::max<int64_t>(h->stats.max_round_pairs, nu);
+    return end_timing(h, e0, e1, h->ev_fused);
+}
+
+// The events of one call: plan, tables, then per round the gradients and one update launch.
+int run_events_impl(adpsgd_t* h, const adpsgd_schedule_t* s, float* loss, adpsgd_gradient_fn fn, void* user) {
+    if (!s || s->K < 0) return fail(h, ADPSGD_ERR_ARG, "run_events: schedule is NULL or K < 0");
+    if (s->K == 0) return ADPSGD_OK;
+    EventCall c;
+    int rc = prepare_call(h, s, c);
+    if (rc != ADPSGD_OK) return rc;
+    rc = upload_tables(h, c);
+    if (rc != ADPSGD_OK) return rc;
+    std::vector<adpsgd_grad_request_t> requests;
+    for (int32_t r = 0; r < c.plan.n_rounds; ++r) {
+        rc = launch_gradients(h, c, r, loss, fn, user, requests);
+        if (rc != ADPSGD_OK) return rc;
+        rc = launch_updates(h, c, r);
+        if (rc != ADPSGD_OK) return rc;
+    }
+    HIP_TRY(h, hipEventRecord(c.T->done, h->stream));
+    c.T->in_flight = true;
+    h->events_done += static_cast<uint64_t>(c.K);
+    h->stats.events += c.K;
+    h->stats.rounds += c.plan.n_rounds;
     return ADPSGD_OK;
 }
 
