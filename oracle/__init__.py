@@ -44,6 +44,7 @@ def lib():
         _lib = C.CDLL(str(build()))
         _lib.oracle_minibatch_gradient.restype = C.c_double
         _lib.oracle_consensus_distance.restype = C.c_double
+        _lib.oracle_consensus_distance_weighted.restype = C.c_double
         _lib.oracle_count_misclassified.restype = C.c_int64
     return _lib
 
@@ -268,3 +269,12 @@ def consensus_distance(X):
     n, d = X.shape
     return lib().oracle_consensus_distance(C.c_int32(n), C.c_int64(d), _p(X, C.c_float),
                                            C.c_int64(X.strides[0] // 4))
+
+
+def consensus_distance_weighted(X, p):
+    """sum_i p_i |mean - x^i|^2 with the workers' update probabilities p (the definition of the proofs appendix)."""
+    n, d = X.shape
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    assert p.shape == (n,)
+    return lib().oracle_consensus_distance_weighted(C.c_int32(n), C.c_int64(d), _p(X, C.c_float), C.c_int64(d),
+                                                    _p(p, C.c_double))

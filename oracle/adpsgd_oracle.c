@@ -664,6 +664,23 @@ double oracle_consensus_distance(int32_t n, int64_t d, const float* X, int64_t l
     return total / (double)n;
 }
 
+/* The same quantity with the workers' update probabilities as weights, as the */
+/* proofs appendix defines it: sum_i p_i |mean - x^i|^2 (mean = plain average). */
+double oracle_consensus_distance_weighted(int32_t n, int64_t d, const float* X, int64_t ldx, const double* p)
+{
+    double total = 0.0;
+    for (int64_t e = 0; e < d; ++e) {
+        double s = 0.0;
+        for (int32_t i = 0; i < n; ++i) s += (double)X[(size_t)i * ldx + e];
+        double mu = s / (double)n;
+        for (int32_t i = 0; i < n; ++i) {
+            double dv = (double)X[(size_t)i * ldx + e] - mu;
+            total += p[i] * dv * dv;
+        }
+    }
+    return total;
+}
+
 /* ------------------------------------------------------------------------- */
 /* Synchronous comparison schedule: decentralized parallel SGD (D-PSGD) as    */
 /* the related-work section describes it -- in each iteration every worker    */

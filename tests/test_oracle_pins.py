@@ -568,6 +568,13 @@ def test_diagnostics_against_numpy():
     mu = X.astype(np.float64).mean(0)
     assert np.allclose(oracle.mean_model(X), mu, rtol=1e-14)
     assert np.isclose(oracle.consensus_distance(X), np.mean(np.sum((X - mu) ** 2, axis=1)), rtol=1e-12)
+    p = rng.random(7)
+    p /= p.sum()
+    assert np.isclose(oracle.consensus_distance_weighted(X, p), np.sum(p * np.sum((X - mu) ** 2, axis=1)), rtol=1e-12)
+    assert np.isclose(oracle.consensus_distance_weighted(X, np.full(7, 1 / 7)), oracle.consensus_distance(X), rtol=1e-12)
+    only3 = np.zeros(7)
+    only3[3] = 1.0
+    assert np.isclose(oracle.consensus_distance_weighted(X, only3), np.sum((X[3] - mu) ** 2), rtol=1e-12)
 
 
 def test_coordinate_subset_of_synthetic_workload_follows_the_full_run():
