@@ -284,6 +284,11 @@ int adpsgd_get_mean_model(adpsgd_t* h, float* out, int32_t on_device);
  * appendix with uniform p.  *out is host memory.  Synchronous. */
 int adpsgd_consensus_distance(adpsgd_t* h, double* out);
 
+/* The same with the workers' update probabilities as weights, sum_i p_i |mean - x^i|^2 (mean = the
+ * plain average): M_k as the proofs appendix defines it when the workers are not equally fast.
+ * p: host, n non-negative values that sum to 1 (|err| <= 1e-9), else ADPSGD_ERR_ARG. */
+int adpsgd_consensus_distance_weighted(adpsgd_t* h, const double* p, double* out);
+
 /* The objective of the problem statement (Sec. 3.1, uniform p) at one point:
  *     f(x) = (1/n) sum_i (1/rows_i) sum_{rows of worker i} F(x; row)
  * over ALL local data, F as in ADPSGD_MODEL_* (the logistic loss includes lambda |x|^2 / 2).

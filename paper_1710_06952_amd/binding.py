@@ -19,7 +19,7 @@ FLAG_PROFILE, FLAG_DENSE_GRADIENT, FLAG_VERIFY_PLAN = 1, 2, 4
 
 EXPORTS = [
     "adpsgd_create", "adpsgd_destroy", "adpsgd_last_error", "adpsgd_load_data", "adpsgd_set_models",
-    "adpsgd_run_events", "adpsgd_run_events_with", "adpsgd_get_models", "adpsgd_get_mean_model", "adpsgd_consensus_distance",
+    "adpsgd_run_events", "adpsgd_run_events_with", "adpsgd_get_models", "adpsgd_get_mean_model", "adpsgd_consensus_distance", "adpsgd_consensus_distance_weighted",
     "adpsgd_get_bf16_models", "adpsgd_classification_error", "adpsgd_get_momentum", "adpsgd_get_stats", "adpsgd_make_schedule", "adpsgd_plan_rounds",
     "adpsgd_synth_gradient", "adpsgd_run_sync_steps", "adpsgd_run_sync_steps_with", "adpsgd_metropolis_weights",
     "adpsgd_get_event_count", "adpsgd_set_event_count", "adpsgd_verify_plan", "adpsgd_objective", "adpsgd_count_nonfinite",
@@ -115,6 +115,7 @@ def lib():
         L.adpsgd_get_models.argtypes = [vp, vp, i64, i32]
         L.adpsgd_get_mean_model.argtypes = [vp, vp, i32]
         L.adpsgd_consensus_distance.argtypes = [vp, P(C.c_double)]
+        L.adpsgd_consensus_distance_weighted.argtypes = [vp, P(C.c_double), P(C.c_double)]
         L.adpsgd_get_bf16_models.argtypes = [vp, vp, i64, i32]
         L.adpsgd_get_momentum.argtypes = [vp, vp, i64, i32]
         L.adpsgd_get_stats.argtypes = [vp, P(Stats)]
@@ -394,9 +395,16 @@ class Handle:
         _check(self._h, lib().adpsgd_count_nonfinite(self._h, C.byref(out)))
         return out.value
 
-    def consensus_distance(self):
+    def consensus_distance(self, p=None):
+        """(1/n) sum_i |mean - x^i|^2, or sum_i p_i |mean - x^i|^2 with update probabilities p."""
         out = C.c_double(0.0)
-        _check(self._h, lib().adpsgd_consensus_distance(self._h, C.byref(out)))
+        if p is None:
+            _check(self._h, lib().adpsgd_consensus_distance(self._h, C.byref(out)))
+        else:
+            p = np.ascontiguousarray(p, dtype=np.float64)
+            if p.shape != (self.n,):
+                raise ValueError("p must have one entry per worker")
+            _check(self._h, lib().adpsgd_consensus_distance_weighted(self._h, p.ctypes.data_as(C.POINTER(C.c_double)), C.byref(out)))
         return out.value
 
     def get_stats(self):

@@ -55,17 +55,45 @@ extern "C" int adpsgd_get_mean_model(adpsgd_t* h, float* out, int32_t on_device)
     return ADPSGD_OK;
 }
 
-extern "C" int adpsgd_consensus_distance(adpsgd_t* h, double* out) {
-    if (!h) return ADPSGD_ERR_ARG;
+namespace {
+
+int consensus(adpsgd_t* h, const double* p, double* out) {
     if (!out) return fail(h, ADPSGD_ERR_ARG, "consensus_distance: out is NULL");
+    double psum = 0.0;
+    if (p) {
+        for (int32_t i = 0; i < h->n; ++i) {
+            if (!(p[i] >= 0.0) || !std::isfinite(p[i])) return fail(h, ADPSGD_ERR_ARG, "consensus_distance: weight negative or not finite");
+            psum += p[i];
+        }
+        if (std::fabs(psum - 1.0) > 1e-9) return fail(h, ADPSGD_ERR_ARG, "consensus_distance: the weights do not sum to 1");
+    }
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     const int32_t blocks = consensus_blocks(h->d);
-    HIP_TRY(h, h->diag.reserve(static_cast<size_t>(blocks + 1) * sizeof(double)));
+    // diag buffer: [partials][result][weights]
+    HIP_TRY(h, h->diag.reserve(static_cast<size_t>(blocks + 1 + (p ? h->n : 0)) * sizeof(double)));
     double* partial = static_cast<double*>(h->diag.p);
-    HIP_TRY(h, launch_consensus(h->o.X, h->o.ldx, h->d, h->n, partial, partial + blocks, h->stream));
+    double* d_p = nullptr;
+    if (p) {
+        d_p = partial + blocks + 1;
+        HIP_TRY(h, hipMemcpyAsync(d_p, p, static_cast<size_t>(h->n) * sizeof(double), hipMemcpyHostToDevice, h->stream));
+    }
+    HIP_TRY(h, launch_consensus(h->o.X, h->o.ldx, h->d, h->n, partial, partial + blocks, d_p, psum, h->stream));
     HIP_TRY(h, hipMemcpyAsync(out, partial + blocks, sizeof(double), hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     return ADPSGD_OK;
+}
+
+}  // namespace
+
+extern "C" int adpsgd_consensus_distance(adpsgd_t* h, double* out) {
+    if (!h) return ADPSGD_ERR_ARG;
+    return consensus(h, nullptr, out);
+}
+
+extern "C" int adpsgd_consensus_distance_weighted(adpsgd_t* h, const double* p, double* out) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (!p) return fail(h, ADPSGD_ERR_ARG, "consensus_distance_weighted: p is NULL");
+    return consensus(h, p, out);
 }
 
 extern "C" int adpsgd_count_nonfinite(adpsgd_t* h, int64_t* out) {

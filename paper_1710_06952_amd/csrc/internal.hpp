@@ -196,8 +196,9 @@ hipError_t launch_broadcast_rows(float* X, int64_t ld, int64_t d, int32_t n, con
 hipError_t launch_refresh_bf16(const float* X, uint16_t* Xb, int64_t ld, int32_t n, hipStream_t st);
 hipError_t launch_mean_model(const float* X, int64_t ld, int64_t d, int32_t n, float* out, hipStream_t st);
 int32_t consensus_blocks(int64_t d);
+// p: device, n doubles (the workers' update probabilities, psum their sum), or nullptr for the uniform weights 1 / n
 hipError_t launch_consensus(const float* X, int64_t ld, int64_t d, int32_t n, double* partial,
-                            double* result, hipStream_t st);
+                            double* result, const double* p, double psum, hipStream_t st);
 hipError_t launch_count_nonfinite(const float* X, int64_t ld, int64_t d, int32_t n, unsigned long long* partial,
                                   int32_t blocks, hipStream_t st);
 // one worker's local data as the objective kernel sees it

@@ -60,16 +60,18 @@ __global__ __launch_bounds__(kThreads) void mean_model_kernel(const float* X, in
 // (shifting by row 0 keeps the subtraction exact when the replicas are close).
 // Grid-stride over float4 columns, fp64 accumulation, wavefront reduction, one
 // partial per block; a second single-block launch sums the partials in order.
-template <bool STREAM>
+// WEIGHTED: sum_i p_i (x_i - mean)^2 with the workers' update probabilities p (device, n doubles, psum
+// their sum): with tb = (sum_i t_i) / n it is  sum_i p_i t_i^2 - 2 tb sum_i p_i t_i + tb^2 psum.
+template <bool STREAM, bool WEIGHTED>
 __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(const float* X, int64_t ld, int64_t d, int32_t n,
-                                                                    double* partial) {
+                                                                    double* partial, const double* __restrict__ p, double psum) {
     __shared__ double red[kWaves];
     const int64_t n_vec = (d + 3) / 4;
     double acc = 0.0;
     for (int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; v < n_vec;
          v += static_cast<int64_t>(gridDim.x) * kThreads) {
         const v4f x0 = *reinterpret_cast<const v4f*>(X + 4 * v);
-        double s1[4] = {0, 0, 0, 0}, s2[4] = {0, 0, 0, 0};
+        double s1[4] = {0, 0, 0, 0}, s2[4] = {0, 0, 0, 0}, sp1[4] = {0, 0, 0, 0};
         for (int32_t i0 = 1; i0 < n; i0 += kRowBatch) {
             v4f xr[kRowBatch];
 #pragma unroll
@@ -79,15 +81,25 @@ __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(const float
             for (int r = 0; r < kRowBatch; ++r) {
                 const v4f x = xr[r];
                 const float t[4] = {x.x - x0.x, x.y - x0.y, x.z - x0.z, x.w - x0.w};
+                const double pi = WEIGHTED && i0 + r < n ? p[i0 + r] : 0.0;       // uniform address: a scalar load
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     s1[c] += t[c];
-                    s2[c] += static_cast<double>(t[c]) * t[c];
+                    if (WEIGHTED) {
+                        const double pt = pi * t[c];
+                        sp1[c] += pt;
+                        s2[c] += pt * t[c];
+                    } else {
+                        s2[c] += static_cast<double>(t[c]) * t[c];
+                    }
                 }
             }
         }
         for (int c = 0; c < 4; ++c)
-            if (4 * v + c < d) acc += s2[c] - s1[c] * s1[c] / n;
+            if (4 * v + c < d) {
+                const double tb = s1[c] / n;
+                acc += WEIGHTED ? s2[c] - 2.0 * tb * sp1[c] + tb * tb * psum : s2[c] - s1[c] * s1[c] / n;
+            }
     }
     acc = wave_sum(acc);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
@@ -95,7 +107,7 @@ __global__ __launch_bounds__(kThreads) void consensus_partial_kernel(const float
     if (threadIdx.x == 0) partial[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-__global__ __launch_bounds__(kThreads) void consensus_final_kernel(const double* partial, int32_t count, int32_t n,
+__global__ __launch_bounds__(kThreads) void consensus_final_kernel(const double* partial, int32_t count, int32_t divisor,
                                                                   double* result) {
     __shared__ double red[kWaves];
     double acc = 0.0;
@@ -103,7 +115,7 @@ __global__ __launch_bounds__(kThreads) void consensus_final_kernel(const double*
     acc = wave_sum(acc);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
     __syncthreads();
-    if (threadIdx.x == 0) *result = ((red[0] + red[1]) + (red[2] + red[3])) / n;
+    if (threadIdx.x == 0) *result = ((red[0] + red[1]) + (red[2] + red[3])) / divisor;
 }
 
 // ---- divergence check: number of entries of X that are NaN or infinite -----------------------
@@ -285,15 +297,17 @@ int32_t consensus_blocks(int64_t d) {
 }
 
 hipError_t launch_consensus(const float* X, int64_t ld, int64_t d, int32_t n, double* partial, double* result,
-                            hipStream_t st) {
+                            const double* p, double psum, hipStream_t st) {
     const int32_t blocks = consensus_blocks(d);
-    if (static_cast<int64_t>(n) * ld * 4 > kStreamBytes)
-        hipLaunchKernelGGL(consensus_partial_kernel<true>, dim3(blocks), dim3(kThreads), 0, st, X, ld, d, n, partial);
-    else
-        hipLaunchKernelGGL(consensus_partial_kernel<false>, dim3(blocks), dim3(kThreads), 0, st, X, ld, d, n, partial);
+    const bool stream = static_cast<int64_t>(n) * ld * 4 > kStreamBytes;
+    const dim3 grid(blocks), block(kThreads);
+    if (p && stream) hipLaunchKernelGGL((consensus_partial_kernel<true, true>), grid, block, 0, st, X, ld, d, n, partial, p, psum);
+    else if (p) hipLaunchKernelGGL((consensus_partial_kernel<false, true>), grid, block, 0, st, X, ld, d, n, partial, p, psum);
+    else if (stream) hipLaunchKernelGGL((consensus_partial_kernel<true, false>), grid, block, 0, st, X, ld, d, n, partial, p, psum);
+    else hipLaunchKernelGGL((consensus_partial_kernel<false, false>), grid, block, 0, st, X, ld, d, n, partial, p, psum);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, st, partial, blocks, n, result);
+    hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(kThreads), 0, st, partial, blocks, p ? 1 : n, result);
     return hipGetLastError();
 }
 

@@ -152,8 +152,8 @@ class Engine:
     def get_mean_model(self):
         return self.h.get_mean_model()
 
-    def consensus_distance(self):
-        return self.h.consensus_distance()
+    def consensus_distance(self, p=None):
+        return self.h.consensus_distance(p)
 
     def objective(self, x=None):
         """The objective over all local data at x (numpy vector or None = the mean model)."""

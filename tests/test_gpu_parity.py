@@ -543,6 +543,16 @@ def test_hop_ring_topology(P):
     oracle.run_events(Xr, ref, oracle.MODEL_SYNTH, 0.1, synth_std=std, synth_seed=1)
     assert rel_err(eng.get_models(), Xr) <= TOL
     assert np.isclose(eng.consensus_distance(), oracle.consensus_distance(Xr), rtol=1e-4)
+    # weighted by update probabilities (the appendix's definition): skewed weights, and the uniform special case
+    p = np.random.default_rng(3).random(n) ** 3
+    p /= p.sum()
+    Xg = eng.get_models()
+    assert np.isclose(eng.consensus_distance(p), oracle.consensus_distance_weighted(Xg, p), rtol=1e-9)
+    assert np.isclose(eng.consensus_distance(np.full(n, 1.0 / n)), eng.consensus_distance(), rtol=1e-12)
+    assert abs(eng.consensus_distance(p) / eng.consensus_distance() - 1) > 1e-3
+    with pytest.raises(P.AdpsgdError) as ei:
+        eng.consensus_distance(p * 0.5)
+    assert ei.value.code == -1
     eng.close()
 
 
