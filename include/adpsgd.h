@@ -141,8 +141,8 @@ typedef struct {
  *   thread): q gradients queued before one communication step are that step's
  *   event followed by q - 1 such events of the same worker, each with the
  *   staleness its gradient had;
- *   0 <= tau[k] <= min(k, T_max): a call is self-contained, staleness never
- *   reaches behind the first event of the call;
+ *   0 <= tau[k] <= min(k, T_max): staleness does not reach behind the first event of the
+ *   call, except for the events an earlier call has looked ahead to (see lookahead);
  *   0 <= batch_idx[k*M + m] < rows loaded for worker[k]. */
 typedef struct {
     int64_t K;
@@ -159,6 +159,16 @@ typedef struct {
     const int64_t* extra_ptr; /* K + 1 entries, extra_ptr[0] = 0                  */
     const int32_t* extra_a;
     const int32_t* extra_b;
+    /* A long run split into calls keeps Algorithm 1's staleness across the call boundaries when every
+     * call looks ahead: of the K events in the arrays the last `lookahead` are NOT applied by this call;
+     * they are the first events of the next call, named now so that those of their stale reads that fall
+     * before the end of this call (k - tau[k] < K - lookahead) are evaluated while the models they need
+     * exist.  Such a gradient stays pending in its slot.  The next call must then start with exactly these
+     * events (same worker, tau and batch indices, else ADPSGD_ERR_SCHEDULE); for them tau[k] > k is what
+     * is expected, up to T_max.  0 = none: the call is self-contained.  A loss array has K entries; the
+     * entry of an event is written by the call that evaluates its gradient.  adpsgd_set_models and
+     * adpsgd_set_event_count drop what is pending. */
+    int64_t lookahead;
 } adpsgd_schedule_t;
 
 /* Parameters of the built-in schedule generator (all host memory). */
@@ -348,12 +358,17 @@ int adpsgd_make_schedule(const adpsgd_sched_params_t* p, uint64_t seed, uint64_t
  * event k run in round u_round[k].  local_compensation != 0 plans the wait-free variant
  * (see adpsgd_opts_t): the gradient of event k then also waits for the gradient of the
  * event k' it compensates with, and prev (K entries, may be NULL) receives k' or -1.
- * Returns ADPSGD_ERR_SCHEDULE for tau[k] > k or n_slots <= max tau. */
+ * Looking ahead (see adpsgd_schedule_t): only the first n_apply events are applied (n_apply < 0 or
+ * > K means K); an event beyond them gets a read round and a slot when k - tau[k] < n_apply, else
+ * r_round = slot = -1, and u_round = -1 in both cases.  carried_slot (K entries or NULL) names, for the
+ * events whose gradient an earlier call has evaluated, the slot that holds it (else -1): such an event
+ * gets r_round = -1 and keeps that slot; it needs tau[k] > k.
+ * Returns ADPSGD_ERR_SCHEDULE for tau[k] > k on an event that is not carried, or n_slots <= max tau. */
 int adpsgd_plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
                        const int32_t* tau, int32_t n_slots, int32_t with_gradients,
                        int32_t* r_round, int32_t* u_round, int32_t* slot, int32_t* n_rounds,
                        const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b,
-                       int32_t local_compensation, int64_t* prev);
+                       int32_t local_compensation, int64_t* prev, int64_t n_apply, const int32_t* carried_slot);
 
 /* The check behind ADPSGD_FLAG_VERIFY_PLAN on its own (host only): ADPSGD_OK when the plan
  * (arrays as produced by adpsgd_plan_rounds; prev may be NULL) keeps the serial semantics of the
@@ -362,7 +377,7 @@ int adpsgd_verify_plan(int32_t n, int64_t K, const int32_t* worker, const int32_
                        const int32_t* tau, int32_t n_slots, int32_t with_gradients,
                        const int32_t* r_round, const int32_t* u_round, const int32_t* slot, int32_t n_rounds,
                        const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b,
-                       const int64_t* prev);
+                       const int64_t* prev, int64_t n_apply, const int32_t* carried_slot);
 
 /* Fill a device buffer with the synthetic gradient g_k[0..d) of global event k
  * (ADPSGD_MODEL_SYNTH's generator), on `stream`.  For tests of the generator. */

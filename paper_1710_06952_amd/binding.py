@@ -50,7 +50,7 @@ class Schedule(C.Structure):
     _fields_ = [("K", C.c_int64), ("worker", C.POINTER(C.c_int32)), ("neighbour", C.POINTER(C.c_int32)),
                 ("tau", C.POINTER(C.c_int32)), ("batch_idx", C.POINTER(C.c_int32)),
                 ("gamma", C.POINTER(C.c_float)), ("extra_ptr", C.POINTER(C.c_int64)),
-                ("extra_a", C.POINTER(C.c_int32)), ("extra_b", C.POINTER(C.c_int32))]
+                ("extra_a", C.POINTER(C.c_int32)), ("extra_b", C.POINTER(C.c_int32)), ("lookahead", C.c_int64)]
 
 
 class GradRequest(C.Structure):
@@ -121,11 +121,11 @@ def lib():
         L.adpsgd_get_stats.argtypes = [vp, P(Stats)]
         L.adpsgd_make_schedule.argtypes = [P(SchedParams), u64, u64, i64, P(i32), P(i32), P(i32), P(i32)]
         L.adpsgd_plan_rounds.argtypes = [i32, i64, P(i32), P(i32), P(i32), i32, i32, P(i32), P(i32), P(i32), P(i32),
-                                         P(i64), P(i32), P(i32), i32, P(i64)]
+                                         P(i64), P(i32), P(i32), i32, P(i64), i64, P(i32)]
         L.adpsgd_synth_gradient.argtypes = [u64, u64, C.c_float, i64, vp, vp]
         L.adpsgd_run_sync_steps.argtypes = [vp, P(SyncSchedule), vp]
         L.adpsgd_verify_plan.argtypes = [i32, i64, P(i32), P(i32), P(i32), i32, i32, P(i32), P(i32), P(i32), i32,
-                                         P(i64), P(i32), P(i32), P(i64)]
+                                         P(i64), P(i32), P(i32), P(i64), i64, P(i32)]
         L.adpsgd_objective.argtypes = [vp, vp, P(C.c_double)]
         L.adpsgd_run_events_with.argtypes = [vp, P(Schedule), GRADIENT_FN, vp]
         L.adpsgd_run_sync_steps_with.argtypes = [vp, P(SyncSchedule), GRADIENT_FN, vp]
@@ -178,9 +178,10 @@ def _extra_arrays(extra_pairs):
 
 
 def adpsgd_plan_rounds(n, worker, neighbour, tau, n_slots, with_gradients=True, extra_pairs=None,
-                       local_compensation=False):
+                       local_compensation=False, n_apply=-1, carried_slot=None):
     """Host-only: the round planner on its own; returns (r_round, u_round, slot, n_rounds), and with
-    local_compensation also prev (the event whose pending gradient each read is compensated with)."""
+    local_compensation also prev (the event whose pending gradient each read is compensated with).
+    n_apply / carried_slot: a call that looks ahead, or continues one that did (see the header)."""
     worker, neighbour, tau = map(_as_i32, (worker, neighbour, tau))
     K = worker.size
     r, u, s = (np.zeros(K, np.int32) for _ in range(3))
@@ -190,7 +191,8 @@ def adpsgd_plan_rounds(n, worker, neighbour, tau, n_slots, with_gradients=True, 
     rc = lib().adpsgd_plan_rounds(n, K, _i32p(worker), _i32p(neighbour), _i32p(tau), n_slots,
                                   1 if with_gradients else 0, _i32p(r), _i32p(u), _i32p(s), C.byref(nr),
                                   None if ep is None else ep.ctypes.data_as(C.POINTER(C.c_int64)), _i32p(ea), _i32p(eb),
-                                  1 if local_compensation else 0, prev.ctypes.data_as(C.POINTER(C.c_int64)))
+                                  1 if local_compensation else 0, prev.ctypes.data_as(C.POINTER(C.c_int64)),
+                                  n_apply, _i32p(_as_i32(carried_slot)))
     if rc != OK:
         raise AdpsgdError(rc, "adpsgd_plan_rounds failed")
     if local_compensation:
@@ -199,7 +201,7 @@ def adpsgd_plan_rounds(n, worker, neighbour, tau, n_slots, with_gradients=True, 
 
 
 def adpsgd_verify_plan(n, worker, neighbour, tau, n_slots, r_round, u_round, slot, n_rounds, with_gradients=True,
-                       extra_pairs=None, prev=None):
+                       extra_pairs=None, prev=None, n_apply=-1, carried_slot=None):
     """Host-only: True when the plan keeps the serial semantics of the events."""
     worker, neighbour, tau, r_round, u_round, slot = map(_as_i32, (worker, neighbour, tau, r_round, u_round, slot))
     ep, ea, eb = _extra_arrays(extra_pairs)
@@ -207,7 +209,7 @@ def adpsgd_verify_plan(n, worker, neighbour, tau, n_slots, r_round, u_round, slo
     i64p = lambda a: None if a is None else a.ctypes.data_as(C.POINTER(C.c_int64))
     rc = lib().adpsgd_verify_plan(n, worker.size, _i32p(worker), _i32p(neighbour), _i32p(tau), n_slots,
                                   1 if with_gradients else 0, _i32p(r_round), _i32p(u_round), _i32p(slot), n_rounds,
-                                  i64p(ep), _i32p(ea), _i32p(eb), i64p(pv))
+                                  i64p(ep), _i32p(ea), _i32p(eb), i64p(pv), n_apply, _i32p(_as_i32(carried_slot)))
     if rc not in (OK, ERR_STATE):
         raise AdpsgdError(rc, "adpsgd_verify_plan: bad argument")
     return rc == OK
@@ -299,7 +301,8 @@ class Handle:
         ep, ea, eb = _extra_arrays(schedule.get("extra_pairs"))
         s = Schedule(worker.size, _i32p(worker), _i32p(nbr), _i32p(tau), _i32p(batch),
                      None if gam is None else gam.ctypes.data_as(C.POINTER(C.c_float)),
-                     None if ep is None else ep.ctypes.data_as(C.POINTER(C.c_int64)), _i32p(ea), _i32p(eb))
+                     None if ep is None else ep.ctypes.data_as(C.POINTER(C.c_int64)), _i32p(ea), _i32p(eb),
+                     int(schedule.get("lookahead", 0)))
         _check(self._h, lib().adpsgd_run_events(self._h, C.byref(s), loss_ptr))
 
     def run_events_with(self, schedule, gradient_fn):
@@ -312,7 +315,8 @@ class Handle:
         ep, ea, eb = _extra_arrays(schedule.get("extra_pairs"))
         s = Schedule(worker.size, _i32p(worker), _i32p(nbr), _i32p(tau), None,
                      None if gam is None else gam.ctypes.data_as(C.POINTER(C.c_float)),
-                     None if ep is None else ep.ctypes.data_as(C.POINTER(C.c_int64)), _i32p(ea), _i32p(eb))
+                     None if ep is None else ep.ctypes.data_as(C.POINTER(C.c_int64)), _i32p(ea), _i32p(eb),
+                     int(schedule.get("lookahead", 0)))
         callback, raised = _gradient_trampoline(gradient_fn)
         rc = lib().adpsgd_run_events_with(self._h, C.byref(s), callback, None)
         if raised:

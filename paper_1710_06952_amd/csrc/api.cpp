@@ -213,6 +213,8 @@ extern "C" int adpsgd_load_data(adpsgd_t* h, int32_t worker, const void* feature
 extern "C" int adpsgd_set_models(adpsgd_t* h, const float* x, int64_t ld_in, int32_t on_device) {
     if (!h || !x) return h ? fail(h, ADPSGD_ERR_ARG, "set_models: x is NULL") : ADPSGD_ERR_ARG;
     if (ld_in != 0 && ld_in < h->d) return fail(h, ADPSGD_ERR_ARG, "set_models: ld_in < d");
+    h->pending.clear();      // gradients evaluated at the old models are dropped
+    h->pending_batch.clear();
     const hipMemcpyKind kind = on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
     if (ld_in == 0) {
         const float* src = x;
@@ -241,6 +243,20 @@ namespace {
 // when it fails.
 int validate_schedule(adpsgd_t* h, const adpsgd_schedule_t* s, bool with_data, int32_t M, int64_t n_extra) {
     const int64_t K = s->K;
+    const int64_t n_pending = static_cast<int64_t>(h->pending.size());
+    if (s->lookahead < 0 || s->lookahead > K) return fail(h, ADPSGD_ERR_ARG, "run_events: lookahead outside [0, K]");
+    if (s->lookahead > 0 && h->o.model == ADPSGD_MODEL_SYNTH)
+        return fail(h, ADPSGD_ERR_ARG, "run_events: the synthetic-gradient model has no stale reads to look ahead to");
+    if (K < n_pending)
+        return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: the call must start with the " + std::to_string(n_pending) +
+                                                " events the previous call looked ahead to");
+    for (int64_t k = 0; k < n_pending; ++k) {
+        const PendingEvent& e = h->pending[k];
+        bool same = s->worker[k] == e.worker && s->tau[k] == e.tau;
+        for (int32_t m = 0; same && m < M; ++m) same = s->batch_idx[k * static_cast<int64_t>(M) + m] == h->pending_batch[k * static_cast<int64_t>(M) + m];
+        if (!same)
+            return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: event " + std::to_string(k) + " differs from the event the previous call looked ahead to");
+    }
     if (s->extra_ptr) {
         if (s->extra_ptr[0] != 0 || n_extra < 0 || (n_extra > 0 && (!s->extra_a || !s->extra_b)))
             return fail(h, ADPSGD_ERR_ARG, "run_events: malformed extra-pair arrays");
@@ -266,7 +282,8 @@ int validate_schedule(adpsgd_t* h, const adpsgd_schedule_t* s, bool with_data, i
             return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: worker or neighbour out of range at event " + std::to_string(k));
         if (!is_neighbour(h, i, j))
             return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: neighbour is not adjacent to worker at event " + std::to_string(k));
-        if (s->tau[k] < 0 || s->tau[k] > k || s->tau[k] > h->o.T_max)
+        const bool carried = k < n_pending && h->pending[k].slot >= 0;      // read before this call began
+        if (s->tau[k] < 0 || s->tau[k] > h->o.T_max || (carried ? s->tau[k] <= k : s->tau[k] > k))
             return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: tau outside [0, min(k, T_max)] at event " + std::to_string(k));
         if (s->gamma && !std::isfinite(s->gamma[k]))
             return fail(h, ADPSGD_ERR_SCHEDULE, "run_events: gamma not finite at event " + std::to_string(k));
@@ -285,7 +302,9 @@ int validate_schedule(adpsgd_t* h, const adpsgd_schedule_t* s, bool with_data, i
 // What one call of run_events works with: the paths taken, the plan sorted by round, the tables.
 struct EventCall {
     const adpsgd_schedule_t* s = nullptr;
-    int64_t K = 0, n_extra = 0;
+    int64_t K = 0;              // events in the arrays
+    int64_t A = 0;              // of which this call applies the first A (the others are looked ahead to)
+    int64_t n_extra = 0;        // extra averaging pairs of the applied events
     int32_t M = 0;
     bool external = false;      // gradients from the caller's function
     bool with_grad = false;     // the events carry gradients held in pending slots (every model but SYNTH)
@@ -316,9 +335,16 @@ int prepare_call(adpsgd_t* h, const adpsgd_schedule_t* s, EventCall& c) {
     const bool with_data = c.with_grad && !c.external;
     c.M = with_data ? h->o.M : 0;
     if (with_data && !s->batch_idx) return fail(h, ADPSGD_ERR_ARG, "run_events: batch_idx is NULL");
-    c.n_extra = s->extra_ptr ? s->extra_ptr[c.K] : 0;
-    const int rc_valid = validate_schedule(h, s, with_data, c.M, c.n_extra);
+    const int rc_valid = validate_schedule(h, s, with_data, c.M, s->extra_ptr ? s->extra_ptr[c.K] : 0);
     if (rc_valid != ADPSGD_OK) return rc_valid;
+    c.A = c.K - s->lookahead;
+    c.n_extra = s->extra_ptr ? s->extra_ptr[c.A] : 0;
+    std::vector<int32_t> carried_slot;
+    if (!h->pending.empty()) {
+        carried_slot.assign(static_cast<size_t>(c.K), -1);
+        for (size_t k = 0; k < h->pending.size(); ++k) carried_slot[k] = h->pending[k].slot;
+    }
+    const int32_t* carried = carried_slot.empty() ? nullptr : carried_slot.data();
 
     // the wait-free variant reads the pending gradient as a dense vector, so it keeps the dense form
     const bool comp = h->o.local_compensation != 0, dense = (h->o.flags & ADPSGD_FLAG_DENSE_GRADIENT) != 0;
@@ -329,19 +355,19 @@ int prepare_call(adpsgd_t* h, const adpsgd_schedule_t* s, EventCall& c) {
 
     std::string perr;
     const int rc = plan_rounds(h->n, c.K, s->worker, s->neighbour, s->tau, h->n_slots, c.with_grad, c.plan, perr,
-                               s->extra_ptr, s->extra_a, s->extra_b, comp);
+                               s->extra_ptr, s->extra_a, s->extra_b, comp, c.A, carried);
     if (rc != ADPSGD_OK) return fail(h, rc, perr);
     if ((h->o.flags & ADPSGD_FLAG_VERIFY_PLAN) &&
         !verify_plan(h->n, c.K, s->worker, s->neighbour, s->tau, h->n_slots, c.with_grad, c.plan, perr, s->extra_ptr, s->extra_a,
-                     s->extra_b))
+                     s->extra_b, c.A, carried))
         return fail(h, ADPSGD_ERR_STATE, perr);
 
     const int32_t R = c.plan.n_rounds;
     c.u_off.assign(static_cast<size_t>(R) + 1, 0);
     c.r_off.assign(static_cast<size_t>(R) + 1, 0);
     for (int64_t k = 0; k < c.K; ++k) {
-        c.u_off[c.plan.u_round[k] + 1] += 1 + (s->extra_ptr ? s->extra_ptr[k + 1] - s->extra_ptr[k] : 0);
-        if (c.with_grad) ++c.r_off[c.plan.r_round[k] + 1];
+        if (k < c.A) c.u_off[c.plan.u_round[k] + 1] += 1 + (s->extra_ptr ? s->extra_ptr[k + 1] - s->extra_ptr[k] : 0);
+        if (c.with_grad && c.plan.r_round[k] >= 0) ++c.r_off[c.plan.r_round[k] + 1];      // not carried, not left to the next call
     }
     int64_t max_r = 0;
     for (int32_t r = 0; r < R; ++r) {
@@ -354,6 +380,50 @@ int prepare_call(adpsgd_t* h, const adpsgd_schedule_t* s, EventCall& c) {
     return ADPSGD_OK;
 }
 
+// The update operations of event k (its own pair and the extra pairs of its W_k), appended to the event's round.
+void fill_update(adpsgd_t* h, EventCall& c, int64_t k, std::vector<int64_t>& u_fill) {
+    const adpsgd_schedule_t* s = c.s;
+    const uint64_t gk = h->events_done + static_cast<uint64_t>(k);
+    const int32_t ur = c.plan.u_round[k];
+    const bool factors = c.factored || c.lin_factored;
+    PairOp& u = c.uops[u_fill[ur]++];
+    u.i = s->worker[k];
+    u.j = s->neighbour[k];
+    u.k_lo = static_cast<uint32_t>(gk);
+    u.k_hi = static_cast<uint32_t>(gk >> 32);
+    u.gamma = s->gamma ? s->gamma[k] : h->o.gamma;
+    u.slot = c.with_grad ? c.plan.slot[k] : 0;
+    u.flags = 0;
+    u.event = static_cast<int32_t>(k);
+    u.features = factors ? h->data[u.i].features : nullptr;
+    u.feat_ld = factors ? h->data[u.i].ld : 0;
+    if (s->extra_ptr)
+        for (int64_t q = s->extra_ptr[k]; q < s->extra_ptr[k + 1]; ++q)
+            c.uops[u_fill[ur]++] = PairOp{s->extra_a[q], s->extra_b[q], 0u, 0u, 0.0f, 0, 1, 0, nullptr, 0};
+}
+
+// The stale read and gradient of event k, appended to its round.
+void fill_gradient(adpsgd_t* h, EventCall& c, int64_t k, std::vector<int64_t>& r_fill) {
+    const adpsgd_schedule_t* s = c.s;
+    const int32_t rr = c.plan.r_round[k];
+    const int64_t at = r_fill[rr]++;
+    GradOp& g = c.rops[at];
+    g.worker = s->worker[k];
+    g.slot = c.plan.slot[k];
+    g.event = static_cast<int32_t>(k);
+    const int64_t kp = c.plan.prev[k];
+    g.comp_slot = kp >= 0 ? c.plan.slot[kp] : -1;
+    g.comp_gamma = kp >= 0 ? (s->gamma ? s->gamma[kp] : h->o.gamma) : 0.0f;
+    g.count = 0;
+    const WorkerData& w = h->data[g.worker];
+    g.features = w.features;
+    g.targets = w.targets;
+    g.ld = w.ld;
+    g.xrow_bf16 = nullptr;
+    if (c.mlp_comp && kp >= 0)      // one compensated row per operation of a launch group
+        g.xrow_bf16 = static_cast<uint16_t*>(h->comp_rows.p) + ((at - c.r_off[rr]) % c.group) * h->o.ldx;
+}
+
 // Tables [PairOp x (K + extra pairs)][GradOp x K][batch_idx K x M], filled in pinned memory in round
 // order and uploaded with one copy; scratch memory of the gradient kernels.
 int upload_tables(adpsgd_t* h, EventCall& c) {
@@ -362,7 +432,7 @@ int upload_tables(adpsgd_t* h, EventCall& c) {
     const int32_t M = c.M;
     if (c.mlp_comp) HIP_TRY(h, h->comp_rows.reserve(static_cast<size_t>(c.group) * h->o.ldx * sizeof(uint16_t)));
     if (c.ext_comp) HIP_TRY(h, h->comp_rows.reserve(static_cast<size_t>(c.group) * h->o.ldx * sizeof(float)));
-    const size_t bytes_u = static_cast<size_t>(K + c.n_extra) * sizeof(PairOp);
+    const size_t bytes_u = static_cast<size_t>(c.A + c.n_extra) * sizeof(PairOp);
     const size_t bytes_r = c.with_grad ? static_cast<size_t>(K) * sizeof(GradOp) : 0;
     const size_t bytes_b = static_cast<size_t>(K) * M * sizeof(int32_t);
     const size_t off_r = bytes_u, off_b = (off_r + bytes_r + 15) & ~size_t(15);
@@ -380,43 +450,10 @@ int upload_tables(adpsgd_t* h, EventCall& c) {
     char* stage = static_cast<char*>(T.stage.p);
     c.uops = reinterpret_cast<PairOp*>(stage);
     c.rops = reinterpret_cast<GradOp*>(stage + off_r);
-    const bool factors = c.factored || c.lin_factored;
     std::vector<int64_t> u_fill(c.u_off.begin(), c.u_off.end() - 1), r_fill(c.r_off.begin(), c.r_off.end() - 1);
     for (int64_t k = 0; k < K; ++k) {
-        const uint64_t gk = h->events_done + static_cast<uint64_t>(k);
-        const int32_t ur = c.plan.u_round[k];
-        PairOp& u = c.uops[u_fill[ur]++];
-        u.i = s->worker[k];
-        u.j = s->neighbour[k];
-        u.k_lo = static_cast<uint32_t>(gk);
-        u.k_hi = static_cast<uint32_t>(gk >> 32);
-        u.gamma = s->gamma ? s->gamma[k] : h->o.gamma;
-        u.slot = c.with_grad ? c.plan.slot[k] : 0;
-        u.flags = 0;
-        u.event = static_cast<int32_t>(k);
-        u.features = factors ? h->data[u.i].features : nullptr;
-        u.feat_ld = factors ? h->data[u.i].ld : 0;
-        if (s->extra_ptr)
-            for (int64_t q = s->extra_ptr[k]; q < s->extra_ptr[k + 1]; ++q)
-                c.uops[u_fill[ur]++] = PairOp{s->extra_a[q], s->extra_b[q], 0u, 0u, 0.0f, 0, 1, 0, nullptr, 0};
-        if (!c.with_grad) continue;
-        const int32_t rr = c.plan.r_round[k];
-        const int64_t at = r_fill[rr]++;
-        GradOp& g = c.rops[at];
-        g.worker = s->worker[k];
-        g.slot = c.plan.slot[k];
-        g.event = static_cast<int32_t>(k);
-        const int64_t kp = c.plan.prev[k];
-        g.comp_slot = kp >= 0 ? c.plan.slot[kp] : -1;
-        g.comp_gamma = kp >= 0 ? (s->gamma ? s->gamma[kp] : h->o.gamma) : 0.0f;
-        g.count = 0;
-        const WorkerData& w = h->data[g.worker];
-        g.features = w.features;
-        g.targets = w.targets;
-        g.ld = w.ld;
-        g.xrow_bf16 = nullptr;
-        if (c.mlp_comp && kp >= 0)      // one compensated row per operation of a launch group
-            g.xrow_bf16 = static_cast<uint16_t*>(h->comp_rows.p) + ((at - c.r_off[rr]) % c.group) * h->o.ldx;
+        if (k < c.A) fill_update(h, c, k, u_fill);
+        if (c.with_grad && c.plan.r_round[k] >= 0) fill_gradient(h, c, k, r_fill);
     }
     if (bytes_b > 0) std::memcpy(stage + off_b, s->batch_idx, bytes_b);
     HIP_TRY(h, hipMemcpyAsync(T.dev.p, T.stage.p, total, hipMemcpyHostToDevice, h->stream));
@@ -553,9 +590,15 @@ int run_events_impl(adpsgd_t* h, const adpsgd_schedule_t* s, float* loss, adpsgd
     }
     HIP_TRY(h, hipEventRecord(c.T->done, h->stream));
     c.T->in_flight = true;
-    h->events_done += static_cast<uint64_t>(c.K);
-    h->stats.events += c.K;
+    h->events_done += static_cast<uint64_t>(c.A);
+    h->stats.events += c.A;
     h->stats.rounds += c.plan.n_rounds;
+    // the events looked ahead to: the next call must start with them; some have their gradient pending already
+    h->pending.clear();
+    h->pending_batch.clear();
+    for (int64_t k = c.A; k < c.K; ++k) h->pending.push_back(PendingEvent{s->worker[k], s->tau[k], c.with_grad ? c.plan.slot[k] : -1});
+    if (c.M > 0 && c.A < c.K)
+        h->pending_batch.assign(s->batch_idx + c.A * static_cast<int64_t>(c.M), s->batch_idx + c.K * static_cast<int64_t>(c.M));
     return ADPSGD_OK;
 }
 
@@ -595,6 +638,8 @@ extern "C" int adpsgd_get_event_count(adpsgd_t* h, uint64_t* out) {
 extern "C" int adpsgd_set_event_count(adpsgd_t* h, uint64_t events) {
     if (!h) return ADPSGD_ERR_ARG;
     h->events_done = events;
+    h->pending.clear();
+    h->pending_batch.clear();
     return ADPSGD_OK;
 }
 

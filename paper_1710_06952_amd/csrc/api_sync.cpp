@@ -19,6 +19,8 @@ int run_sync_steps_impl(adpsgd_t* h, const adpsgd_sync_schedule_t* s, float* los
     const int32_t M = with_data ? h->o.M : 0;
     if (S * n > 0x7FFFFFF0) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: S * n must stay below 2^31 - 16");
     if (sync_tile_cols(n) == 0) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: at most 1024 workers");
+    if (!h->pending.empty())
+        return fail(h, ADPSGD_ERR_STATE, "run_sync_steps: the last run_events call looked ahead; finish it with a call without lookahead first");
     if (with_data && !s->batch_idx) return fail(h, ADPSGD_ERR_ARG, "run_sync_steps: batch_idx is NULL");
     if (with_grad && h->n_slots < n)
         return fail(h, ADPSGD_ERR_STATE, "run_sync_steps: the workspace must hold one gradient slot per worker");

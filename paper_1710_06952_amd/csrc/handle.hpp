@@ -42,6 +42,13 @@ struct TableSet {
     bool in_flight = false;
 };
 
+// An event the previous call has looked ahead to: the next call must start with these events.
+struct PendingEvent {
+    int32_t worker;
+    int32_t tau;
+    int32_t slot;      // pending-gradient slot that holds its gradient, or -1 when it is still to be evaluated
+};
+
 constexpr int64_t kStreamingThreshold = 256ll << 20;
 constexpr int32_t kMaxSlots = 4096;
 
@@ -57,6 +64,8 @@ struct adpsgd {
     hipStream_t stream = nullptr;
     bool streaming = false;
     uint64_t events_done = 0;
+    std::vector<adpsgd_impl::PendingEvent> pending;   // events looked ahead to by the last call, in order
+    std::vector<int32_t> pending_batch;               // their minibatch indices, M each
     adpsgd_impl::TableSet tables[2];
     int next_table = 0;
     adpsgd_impl::DevBuf grad_scratch;     // dots partials + coefficients / MLP activations

@@ -66,10 +66,12 @@ void philox4x32_10_host(const uint32_t ctr[4], const uint32_t key[2], uint32_t o
 int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
                 const int32_t* tau, int32_t n_slots, bool with_gradients, Plan& plan,
                 std::string& err, const int64_t* extra_ptr = nullptr, const int32_t* extra_a = nullptr,
-                const int32_t* extra_b = nullptr, bool local_compensation = false);
+                const int32_t* extra_b = nullptr, bool local_compensation = false,
+                int64_t n_apply = -1, const int32_t* carried_slot = nullptr);
 bool verify_plan(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour, const int32_t* tau,
                  int32_t n_slots, bool with_gradients, const Plan& plan, std::string& err,
-                 const int64_t* extra_ptr = nullptr, const int32_t* extra_a = nullptr, const int32_t* extra_b = nullptr);
+                 const int64_t* extra_ptr = nullptr, const int32_t* extra_a = nullptr, const int32_t* extra_b = nullptr,
+                 int64_t n_apply = -1, const int32_t* carried_slot = nullptr);
 bool graph_ok(const adpsgd_graph_t* g, std::string& err);
 
 // ---- kernel launchers (each returns the hipError_t of the launch) ------------

@@ -12,6 +12,11 @@
 // a slot is reused only in a later round than the update that consumed it.
 // Disjoint pairwise averages commute, so executing the rounds in order gives
 // exactly the serial result.
+//
+// A call may look ahead: of the K events in the arrays only the first n_apply are applied; the others
+// are the first events of the next call, named now so that those of their stale reads that fall before
+// event n_apply are evaluated while the models they need still exist.  Such a gradient stays in its
+// slot after the call ("carried"); the next call names it through carried_slot and plans no read for it.
 #include <algorithm>
 #include <queue>
 
@@ -22,7 +27,10 @@ namespace adpsgd_impl {
 int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour,
                 const int32_t* tau, int32_t n_slots, bool with_gradients, Plan& plan,
                 std::string& err, const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b,
-                bool local_compensation) {
+                bool local_compensation, int64_t n_apply, const int32_t* carried_slot) {
+    if (n_apply < 0 || n_apply > K) n_apply = K;
+    if (!with_gradients) carried_slot = nullptr;
+    auto carried = [&](int64_t k) { return carried_slot && carried_slot[k] >= 0; };
     plan.r_round.assign(static_cast<size_t>(K), -1);
     plan.u_round.assign(static_cast<size_t>(K), -1);
     plan.slot.assign(static_cast<size_t>(K), -1);
@@ -36,11 +44,23 @@ int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neig
     // events grouped by the logical time of their read, s_k = k - tau_k
     std::vector<int64_t> head(static_cast<size_t>(K) + 1, -1), next(static_cast<size_t>(K), -1);
     int32_t tau_max = 0;
+    std::vector<char> slot_taken(with_gradients ? static_cast<size_t>(std::max(n_slots, 0)) : 0, 0);
     if (with_gradients) {
         for (int64_t k = K - 1; k >= 0; --k) {
-            if (tau[k] < 0 || tau[k] > k) { err = "plan: tau[k] outside [0, k]"; return ADPSGD_ERR_SCHEDULE; }
+            if (tau[k] < 0) { err = "plan: tau[k] < 0"; return ADPSGD_ERR_SCHEDULE; }
             tau_max = std::max(tau_max, tau[k]);
+            if (carried(k)) {        // evaluated by an earlier call: no read here, the slot is in use from the start
+                const int32_t sl = carried_slot[k];
+                if (tau[k] <= k) { err = "plan: a carried gradient has its read time before this call"; return ADPSGD_ERR_SCHEDULE; }
+                if (sl >= n_slots || slot_taken[sl]) { err = "plan: carried slot out of range or named twice"; return ADPSGD_ERR_SCHEDULE; }
+                slot_taken[sl] = 1;
+                plan.slot[k] = sl;
+                plan.r_round[k] = 0;
+                continue;
+            }
+            if (tau[k] > k) { err = "plan: tau[k] outside [0, k]"; return ADPSGD_ERR_SCHEDULE; }
             const int64_t s = k - tau[k];
+            if (s >= n_apply) continue;      // a read of the next call
             next[k] = head[s];
             head[s] = k;
         }
@@ -57,7 +77,7 @@ int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neig
         std::vector<int64_t> last_of(n, -1);
         for (int64_t k = 0; k < K; ++k) {
             const int64_t kp = last_of[worker[k]], s = k - tau[k];
-            if (kp >= 0 && kp - tau[kp] <= s && s <= kp) plan.prev[k] = kp;
+            if (kp >= 0 && !carried(k) && s < n_apply && kp - tau[kp] <= s && s <= kp) plan.prev[k] = kp;
             last_of[worker[k]] = k;
         }
     }
@@ -65,10 +85,11 @@ int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neig
     using Free = std::pair<int32_t, int32_t>;  // (round of the consuming update, slot)
     std::priority_queue<Free, std::vector<Free>, std::greater<Free>> free_slots;
     if (with_gradients)
-        for (int32_t s = 0; s < n_slots; ++s) free_slots.push({0, s});
+        for (int32_t s = 0; s < n_slots; ++s)
+            if (!slot_taken[s]) free_slots.push({0, s});
 
     int32_t rounds = 0;
-    for (int64_t t = 0; t < K; ++t) {
+    for (int64_t t = 0; t < n_apply; ++t) {
         if (with_gradients) {
             for (int64_t k = head[t]; k >= 0; k = next[k]) {
                 const int32_t i = worker[k];
@@ -80,6 +101,7 @@ int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neig
                 plan.r_round[k] = r;
                 plan.slot[k] = f.second;
                 last_read[i] = std::max(last_read[i], r);
+                rounds = std::max(rounds, r);      // a looked-ahead read may come after the last update
             }
         }
         const int32_t i = worker[t], j = neighbour[t];
@@ -99,9 +121,9 @@ int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neig
         rounds = std::max(rounds, u);
         if (with_gradients) free_slots.push({u, plan.slot[t]});
     }
-    for (int64_t k = 0; k < K; ++k) {
-        plan.u_round[k] -= 1;
-        if (with_gradients) plan.r_round[k] -= 1;
+    for (int64_t k = 0; k < K; ++k) {      // to 0-based rounds; -1: no such operation in this call
+        plan.u_round[k] = k < n_apply ? plan.u_round[k] - 1 : -1;
+        if (with_gradients && plan.r_round[k] >= 0) plan.r_round[k] -= 1;
     }
     plan.n_rounds = rounds;
     return ADPSGD_OK;
@@ -115,10 +137,17 @@ int plan_rounds(int32_t n, int64_t K, const int32_t* worker, const int32_t* neig
 //   4. a gradient is computed no later than the round that applies it, and a slot is rewritten only in
 //      a later round than the update that consumed it;
 //   5. wait-free variant: a compensated read runs after the gradient it uses and no later than the round
-//      that applies that gradient.
+//      that applies that gradient;
+//   6. looking ahead: only the first n_apply events are updated; an event beyond them has a read in this
+//      call exactly when its read time lies before event n_apply, and its slot is not given away; a
+//      carried gradient keeps its slot and has no read.
 bool verify_plan(int32_t n, int64_t K, const int32_t* worker, const int32_t* neighbour, const int32_t* tau,
                  int32_t n_slots, bool with_gradients, const Plan& plan, std::string& err,
-                 const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b) {
+                 const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b,
+                 int64_t n_apply, const int32_t* carried_slot) {
+    if (n_apply < 0 || n_apply > K) n_apply = K;
+    if (!with_gradients) carried_slot = nullptr;
+    auto carried = [&](int64_t k) { return carried_slot && carried_slot[k] >= 0; };
     auto bad = [&](const std::string& what, int64_t k) {
         err = "plan check: " + what + " at event " + std::to_string(k);
         return false;
@@ -138,7 +167,9 @@ bool verify_plan(int32_t n, int64_t K, const int32_t* worker, const int32_t* nei
             }
     };
     std::vector<int32_t> rows;
-    for (int64_t k = 0; k < K; ++k) {
+    for (int64_t k = n_apply; k < K; ++k)
+        if (plan.u_round[k] != -1) return bad("update planned for an event that is only looked ahead to", k);        // 6
+    for (int64_t k = 0; k < n_apply; ++k) {
         const int32_t u = plan.u_round[k];
         if (u < 0 || u >= plan.n_rounds) return bad("update round out of range", k);
         rows_of(k, rows);
@@ -153,12 +184,26 @@ bool verify_plan(int32_t n, int64_t K, const int32_t* worker, const int32_t* nei
     }
     if (!with_gradients) return true;
     std::vector<int64_t> slot_last(n_slots, -1);      // event that last used the slot, in order of the rounds
-    std::vector<int64_t> order(K);
-    for (int64_t k = 0; k < K; ++k) order[k] = k;
+    std::vector<int64_t> order;
+    for (int64_t k = 0; k < K; ++k) {
+        const int32_t sl = plan.slot[k];
+        if (carried(k)) {                                                                                      // 6
+            if (sl != carried_slot[k] || plan.r_round[k] != -1) return bad("carried gradient moved or read again", k);
+            if (sl >= n_slots || slot_last[sl] >= 0) return bad("carried slot out of range or named twice", k);
+            if (tau[k] <= k) return bad("carried gradient with a read time inside this call", k);
+            slot_last[sl] = k;
+        } else if (k - tau[k] >= n_apply) {
+            if (sl != -1 || plan.r_round[k] != -1) return bad("read planned for an event of the next call", k);
+        } else {
+            order.push_back(k);
+        }
+    }
+    // an event that is not applied in this call never gives its slot away
+    auto applied_before = [&](int64_t m, int32_t r) { return m < n_apply && plan.u_round[m] < r; };
     std::stable_sort(order.begin(), order.end(), [&](int64_t a, int64_t b) { return plan.r_round[a] < plan.r_round[b]; });
     for (int64_t k : order) {
         const int32_t r = plan.r_round[k], i = worker[k];
-        if (r < 0 || r > plan.u_round[k]) return bad("gradient later than its update", k);                     // 4
+        if (r < 0 || r >= plan.n_rounds || (k < n_apply && r > plan.u_round[k])) return bad("gradient later than its update", k);   // 4
         const int64_t s = k - tau[k];
         const auto& tv = touches[i];
         const auto it = std::lower_bound(tv.begin(), tv.end(), s);      // first update of the row with index >= s
@@ -166,10 +211,11 @@ bool verify_plan(int32_t n, int64_t K, const int32_t* worker, const int32_t* nei
         if (it != tv.end() && plan.u_round[*it] < r) return bad("stale read sees a later update", k);                // 3
         const int32_t sl = plan.slot[k];
         if (sl < 0 || sl >= n_slots) return bad("slot out of range", k);
-        if (slot_last[sl] >= 0 && plan.u_round[slot_last[sl]] >= r) return bad("slot rewritten before its gradient was applied", k);   // 4
+        if (slot_last[sl] >= 0 && !applied_before(slot_last[sl], r)) return bad("slot rewritten before its gradient was applied", k);   // 4
         slot_last[sl] = k;
         const int64_t kp = plan.prev[k];
-        if (kp >= 0 && !(plan.r_round[kp] < r && r <= plan.u_round[kp])) return bad("compensated read outside the life of its gradient", k);   // 5
+        if (kp >= 0 && !(plan.r_round[kp] < r && plan.slot[kp] >= 0 && (kp >= n_apply || r <= plan.u_round[kp])))
+            return bad("compensated read outside the life of its gradient", k);   // 5
     }
     return true;
 }
@@ -182,10 +228,11 @@ extern "C" int adpsgd_verify_plan(int32_t n, int64_t K, const int32_t* worker, c
                                   const int32_t* tau, int32_t n_slots, int32_t with_gradients,
                                   const int32_t* r_round, const int32_t* u_round, const int32_t* slot, int32_t n_rounds,
                                   const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b,
-                                  const int64_t* prev) {
+                                  const int64_t* prev, int64_t n_apply, const int32_t* carried_slot) {
     if (n < 1 || K < 0 || !worker || !neighbour || !tau || !r_round || !u_round || !slot) return ADPSGD_ERR_ARG;
     for (int64_t k = 0; k < K; ++k)
-        if (worker[k] < 0 || worker[k] >= n || neighbour[k] < 0 || neighbour[k] >= n || tau[k] < 0 || tau[k] > k)
+        if (worker[k] < 0 || worker[k] >= n || neighbour[k] < 0 || neighbour[k] >= n || tau[k] < 0 ||
+            (tau[k] > k && !(carried_slot && carried_slot[k] >= 0)))
             return ADPSGD_ERR_SCHEDULE;
     Plan plan;
     plan.r_round.assign(r_round, r_round + K);
@@ -195,7 +242,8 @@ extern "C" int adpsgd_verify_plan(int32_t n, int64_t K, const int32_t* worker, c
     else plan.prev.assign(static_cast<size_t>(K), -1);
     plan.n_rounds = n_rounds;
     std::string err;
-    return verify_plan(n, K, worker, neighbour, tau, n_slots, with_gradients != 0, plan, err, extra_ptr, extra_a, extra_b)
+    return verify_plan(n, K, worker, neighbour, tau, n_slots, with_gradients != 0, plan, err, extra_ptr, extra_a, extra_b,
+                       n_apply, carried_slot)
                ? ADPSGD_OK : ADPSGD_ERR_STATE;
 }
 
@@ -203,7 +251,7 @@ extern "C" int adpsgd_plan_rounds(int32_t n, int64_t K, const int32_t* worker, c
                                   const int32_t* tau, int32_t n_slots, int32_t with_gradients,
                                   int32_t* r_round, int32_t* u_round, int32_t* slot, int32_t* n_rounds,
                                   const int64_t* extra_ptr, const int32_t* extra_a, const int32_t* extra_b,
-                                  int32_t local_compensation, int64_t* prev) {
+                                  int32_t local_compensation, int64_t* prev, int64_t n_apply, const int32_t* carried_slot) {
     if (n < 1 || K < 0 || !worker || !neighbour || !tau || !r_round || !u_round || !slot || !n_rounds)
         return ADPSGD_ERR_ARG;
     for (int64_t k = 0; k < K; ++k)
@@ -218,7 +266,7 @@ extern "C" int adpsgd_plan_rounds(int32_t n, int64_t K, const int32_t* worker, c
     Plan plan;
     std::string err;
     const int rc = plan_rounds(n, K, worker, neighbour, tau, n_slots, with_gradients != 0, plan, err, extra_ptr, extra_a, extra_b,
-                               local_compensation != 0);
+                               local_compensation != 0, n_apply, carried_slot);
     if (rc != ADPSGD_OK) return rc;
     std::copy(plan.r_round.begin(), plan.r_round.end(), r_round);
     std::copy(plan.u_round.begin(), plan.u_round.end(), u_round);

@@ -26,13 +26,13 @@ int main(void) {
             if (batch[k * M + m] < 0 || batch[k * M + m] >= 32) return 4;
     }
     int32_t *r = malloc(sizeof(int32_t) * K), *u = malloc(sizeof(int32_t) * K), *slot = malloc(sizeof(int32_t) * K), n_rounds = 0;
-    if (adpsgd_plan_rounds(N, K, worker, nbr, tau, T + 2, 1, r, u, slot, &n_rounds, NULL, NULL, NULL, 0, NULL) != ADPSGD_OK) return 5;
+    if (adpsgd_plan_rounds(N, K, worker, nbr, tau, T + 2, 1, r, u, slot, &n_rounds, NULL, NULL, NULL, 0, NULL, -1, NULL) != ADPSGD_OK) return 5;
     if (n_rounds < K / (N / 2) || n_rounds > K) return 6;
-    if (adpsgd_verify_plan(N, K, worker, nbr, tau, T + 2, 1, r, u, slot, n_rounds, NULL, NULL, NULL, NULL) != ADPSGD_OK) return 7;
+    if (adpsgd_verify_plan(N, K, worker, nbr, tau, T + 2, 1, r, u, slot, n_rounds, NULL, NULL, NULL, NULL, -1, NULL) != ADPSGD_OK) return 7;
     /* damage the plan: an update moved into the round of its predecessor on the same row must be caught */
     int damaged = 0;
     for (int k = 1; k < K && !damaged; ++k)
-        if (u[k] > 0) { u[k] -= 1; damaged = adpsgd_verify_plan(N, K, worker, nbr, tau, T + 2, 1, r, u, slot, n_rounds, NULL, NULL, NULL, NULL) == ADPSGD_ERR_STATE; u[k] += 1; }
+        if (u[k] > 0) { u[k] -= 1; damaged = adpsgd_verify_plan(N, K, worker, nbr, tau, T + 2, 1, r, u, slot, n_rounds, NULL, NULL, NULL, NULL, -1, NULL) == ADPSGD_ERR_STATE; u[k] += 1; }
     if (!damaged) return 8;
     float w_self[N], w_edge[2 * N];
     adpsgd_graph_t g = {N, rowptr, col};

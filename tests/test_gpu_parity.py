@@ -1080,6 +1080,116 @@ def test_external_gradients_from_pytorch_follow_algorithm_1(P):
     other.close()
 
 
+# ------------------------------------------------------------------ a run split into calls that look ahead
+@pytest.mark.parametrize("model,comp,mu", [("lsq", False, 0.0), ("lsq_short", True, 0.0), ("logreg", False, 0.9), ("mlp", False, 0.0),
+                                           ("mlp", True, 0.9), ("external", True, 0.9)])
+def test_calls_that_look_ahead_equal_one_long_run(P, model, comp, mu):
+    """The whole schedule in one call, and the same schedule cut into calls that look T_max events ahead
+    (so that staleness reaches across the cuts): the same bits on the GPU, and the oracle's single run within
+    the tolerance.  Self-contained calls (staleness clipped at every cut) give something else."""
+    import torch
+    from workloads import mixture_data, mlp_init
+    _say("calls that look ahead: %s comp=%d mu=%g" % (model, comp, mu))
+    n, K, T = 6, 420, 5
+    cuts = [0, 100, 103, 260, 420]
+    g = ring_graph(n)
+    wd = 1e-3 if mu else 0.0
+    dims, lam, tol = (0, 0, 0), 0.0, TOL
+    if model == "mlp":
+        dims, rows, M, gamma, omodel, tol = (24, 64, 5), 40, 16, 0.02, oracle.MODEL_MLP, MLP_TOL_MASTER
+        d = dims[0] * dims[1] + dims[1] + dims[1] * dims[2] + dims[2]
+        feats, targs, _ = mixture_data(n, rows, din=dims[0], classes=dims[2], seed=4)
+        x0 = mlp_init(*dims, seed=4)
+    else:
+        d = 700 if model == "lsq_short" else 4099
+        rows, M = 24, 5
+        if model == "logreg":
+            feats, targs, _ = logreg_data(n, rows, d, seed=4)
+            gamma, lam, omodel = 0.5, 1e-3, oracle.MODEL_LOGREG
+        else:
+            feats, targs, _ = lsq_data(n, rows, d, seed=4, feature_var=1.0 / d)
+            gamma, omodel = 0.1 if mu else 0.3, oracle.MODEL_LSQ
+        x0 = np.random.default_rng(4).standard_normal(d).astype(np.float32)
+    kind = {"lsq_short": "lsq"}.get(model, model)
+    sched = oracle.make_schedule(g, K, seed=14, T_max=T, M=M, rows=[rows] * n)
+    sched["gamma"] = (gamma * (1 + np.arange(K) % 2)).astype(np.float32)
+
+    def make():
+        eng = P.Engine(g, d, kind, M=M if kind != "external" else 0, gamma=gamma, lam=lam, T_max=T, mlp=dims,
+                       local_compensation=comp, momentum=mu, weight_decay=wd, verify_plan=True)
+        if kind != "external":
+            eng.load_data(feats, targs)
+        eng.set_models(x0)
+        return eng
+
+    if kind == "external":
+        A = [torch.from_numpy(f).cuda().double() for f in feats]
+        b = [torch.from_numpy(t).cuda().double() for t in targs]
+        batch = torch.from_numpy(sched["batch_idx"]).cuda().long()
+        first = {"event": 0}
+
+        def gradient(worker, event, xhat, out):
+            rows_b = A[worker][batch[first["event"] + event]]
+            out.copy_((rows_b.T @ (rows_b @ xhat.double() - b[worker][batch[first["event"] + event]]) / M).float())
+
+        run = lambda eng, sc: eng.run_events_with(sc, gradient)
+    else:
+        first = {"event": 0}
+        losses = {}
+
+        def run(eng, sc):             # the loss of an event is written by the call that evaluates its gradient
+            eng.run_events(sc, want_loss=True)
+            got = eng.get_loss()
+            losses.setdefault(id(eng), np.zeros(K + T, np.float32))
+            mine = losses[id(eng)][first["event"]:first["event"] + len(got)]
+            mine[got != 0] = got[got != 0]
+
+    def piece(a, end, look):
+        sc = {k: sched[k][a:end] for k in ("worker", "neighbour", "tau", "batch_idx", "gamma")}
+        sc["lookahead"] = look
+        return sc
+
+    whole = make()
+    run(whole, piece(0, K, 0))
+    Xw, Vw = whole.get_models(), (whole.get_momentum() if mu else None)
+    whole.close()
+    parts = make()
+    for a, b_ in zip(cuts[:-1], cuts[1:]):
+        end = min(b_ + T, K)
+        first["event"] = a
+        run(parts, piece(a, end, end - b_))
+    assert parts.get_stats()["events"] == K and parts.h.get_event_count() == K
+    assert np.array_equal(parts.get_models(), Xw)
+    if kind != "external":
+        assert np.array_equal(losses[id(parts)], losses[id(whole)]) and np.count_nonzero(losses[id(whole)][:K]) == K
+    if mu:
+        assert np.array_equal(parts.get_momentum(), Vw)
+    parts.close()
+    kw = dict(M=M, gscale=1.0 / M, lam=lam, mlp=dims, features=feats, targets=targs, gamma_k=sched["gamma"],
+              local_compensation=comp, momentum=mu, weight_decay=wd)
+    Xr = np.tile(x0, (n, 1))
+    oracle.run_events(Xr, sched, omodel, gamma, V=np.zeros_like(Xr) if mu else None, **kw)
+    assert rel_err(Xw, Xr) <= tol
+    call_start = np.array(cuts)[np.searchsorted(cuts, np.arange(K), side="right") - 1]
+    Xc = np.tile(x0, (n, 1))
+    oracle.run_events(Xc, dict(sched, tau=np.minimum(sched["tau"], np.arange(K) - call_start).astype(np.int32)), omodel, gamma,
+                      V=np.zeros_like(Xr) if mu else None, **kw)
+    assert rel_err(Xw, Xc) > 3 * TOL           # beyond rounding differences (only the events at the cuts differ)
+    # a call that does not start with the events looked ahead to is refused; set_models drops them
+    eng = make()
+    first["event"] = 0
+    run(eng, piece(0, 100 + T, T))
+    with pytest.raises(P.AdpsgdError) as ei:
+        run(eng, piece(101, 200, 0))
+    assert ei.value.code == -3
+    eng.set_models(x0)
+    first["event"] = 101
+    sc = piece(101, 200, 0)
+    sc["tau"] = np.minimum(sc["tau"], np.arange(99)).astype(np.int32)
+    run(eng, sc)
+    eng.close()
+
+
 # ------------------------------------------------------------------ seeded sweep over small random set-ups
 def _random_case(rng):
     from workloads import hop_ring_graph, random_extra_pairs, with_identity_events

@@ -293,6 +293,91 @@ def test_planner_for_the_waitfree_variant_reproduces_the_oracle():
     assert len(P.adpsgd_plan_rounds(n, w, j, tau, T + 2, True)) == 4
 
 
+@pytest.mark.parametrize("comp", [False, True])
+def test_calls_that_look_ahead_reproduce_one_long_run(comp):
+    """A run split into calls keeps the staleness across the boundaries when every call looks ahead to
+    the first events of the next one: their early stale reads are evaluated now and carried in their
+    slots.  The plans of the calls, executed one after another on the CPU, must give the oracle's single
+    run over the whole schedule bit for bit (also with calls shorter than the look-ahead, and for the
+    wait-free variant), every plan must pass the library's own check, and a call that does not look
+    ahead far enough is refused."""
+    n, d, rows, K, M, T = 6, 20, 16, 900, 3, 6
+    g = ring_graph(n)
+    feats, targs, _ = lsq_data(n, rows, d, seed=2)
+    sched = oracle.make_schedule(g, K, seed=9, T_max=T, M=M, rows=[rows] * n)
+    gam = (0.01 + 0.005 * (np.arange(K) % 4)).astype(np.float32)
+    X_ref = np.tile(np.random.default_rng(1).standard_normal(d).astype(np.float32), (n, 1))
+    X = X_ref.copy()
+    oracle.run_events(X_ref, sched, oracle.MODEL_LSQ, 0.0, M=M, gscale=1.0 / M, features=feats, targets=targs,
+                      gamma_k=gam, mode=0, local_compensation=comp)
+    W, J, TAU = sched["worker"], sched["neighbour"], sched["tau"]
+    n_slots = T + 3
+    cuts = [0, 130, 133, 137, 400, 403, 900]          # calls of 130, 3, 4, 263, 3 and 497 events
+    slots, pending, carried_reads = {}, {}, 0
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        end = min(b + T, K)                           # look T events ahead (nothing after the last call)
+        w, j, tau = W[a:end], J[a:end], TAU[a:end]
+        carried = np.array([pending.get(a + k, -1) for k in range(end - a)], np.int32)
+        carried_reads += int((carried >= 0).sum())
+        out = P.adpsgd_plan_rounds(n, w, j, tau, n_slots, True, local_compensation=comp, n_apply=b - a, carried_slot=carried)
+        r_round, u_round, slot, R = out[:4]
+        prev = out[4] if comp else np.full(end - a, -1)
+        assert P.adpsgd_verify_plan(n, w, j, tau, n_slots, r_round, u_round, slot, R, prev=prev if comp else None,
+                                    n_apply=b - a, carried_slot=carried)
+        assert np.all(u_round[b - a:] == -1) and np.all(u_round[:b - a] >= 0)
+        check = lambda rr, uu, ss: P.adpsgd_verify_plan(n, w, j, tau, n_slots, rr, uu, ss, R, prev=prev if comp else None,
+                                                        n_apply=b - a, carried_slot=carried)
+        if end > b:                                   # damaged plans of a call that looks ahead are caught
+            uu = u_round.copy()
+            uu[b - a] = 0                             # an update for an event that is only looked ahead to
+            assert not check(r_round, uu, slot)
+            kept = [k for k in range(b - a, end - a) if slot[k] >= 0]          # gradients this call leaves pending
+            fresh = [k for k in range(end - a) if r_round[k] >= 0 and (not kept or k != kept[0])]
+            if kept and fresh:
+                ss = slot.copy()
+                ss[fresh[-1]] = slot[kept[0]]         # their slot given to another gradient
+                assert not check(r_round, u_round, ss)
+            moved = [k for k in range(end - a) if carried[k] >= 0]
+            if moved:
+                rr = r_round.copy()
+                rr[moved[0]] = 0                      # a carried gradient evaluated again
+                assert not check(rr, u_round, slot)
+        for k in range(end - a):
+            s_k = k - tau[k]
+            if carried[k] >= 0:
+                assert slot[k] == carried[k] and r_round[k] == -1 and s_k < 0
+            elif s_k < b - a:
+                assert r_round[k] >= 0 and slot[k] >= 0
+            else:
+                assert r_round[k] == -1 and slot[k] == -1 and k >= b - a
+        for r in range(R):
+            at_start = dict(slots)
+            for k in np.where(r_round == r)[0]:
+                xh = X[w[k]]
+                if prev[k] >= 0:
+                    xh = xh - gam[a + prev[k]] * at_start[slot[prev[k]]]
+                slots[slot[k]] = oracle.minibatch_gradient(oracle.MODEL_LSQ, xh, feats[w[k]], targs[w[k]],
+                                                           sched["batch_idx"][a + k], 1.0 / M)[0]
+            for k in np.where(u_round == r)[0]:
+                avg = (X[w[k]] + X[j[k]]) * np.float32(0.5)
+                X[j[k]] = avg
+                X[w[k]] = avg - gam[a + k] * slots[slot[k]]
+        pending = {a + k: int(slot[k]) for k in range(b - a, end - a)}
+    assert carried_reads > 10
+    assert np.array_equal(X, X_ref)
+    # the staleness at the boundaries matters: self-contained calls (tau clipped at the start of a call) differ
+    call_start = np.array(cuts)[np.searchsorted(cuts, np.arange(K), side="right") - 1]
+    clipped = dict(sched, tau=np.minimum(TAU, np.arange(K) - call_start).astype(np.int32))
+    Xc = np.tile(np.random.default_rng(1).standard_normal(d).astype(np.float32), (n, 1))
+    oracle.run_events(Xc, clipped, oracle.MODEL_LSQ, 0.0, M=M, gscale=1.0 / M, features=feats, targets=targs,
+                      gamma_k=gam, mode=0, local_compensation=comp)
+    assert not np.array_equal(Xc, X_ref)
+    # an event whose read time lies before the call and that nobody carried is refused
+    k0 = next(k for k in range(131, K) if TAU[k] > 1)
+    with pytest.raises(P.AdpsgdError):
+        P.adpsgd_plan_rounds(n, W[k0 - 1:k0 + 50], J[k0 - 1:k0 + 50], TAU[k0 - 1:k0 + 50], n_slots, True)
+
+
 def test_metropolis_weights_agree_with_the_oracle_bit_for_bit():
     for g in (ring_graph(8), random_regular4_graph(16, 3), ring_graph(2), ring_graph(1)):
         w_self, w_edge = P.adpsgd_metropolis_weights(g)
