@@ -41,6 +41,7 @@ class Engine:
         self.ld = _pad(d)
         self.model = _MODELS[model] if isinstance(model, str) else model
         self.M = M
+        self.T_max = T_max
         self.X = torch.zeros((self.n, self.ld), dtype=torch.float32, device=self.device)
         self.Xbf16 = None
         self.workspace = None
@@ -101,6 +102,30 @@ class Engine:
             self.loss = self.torch.zeros(len(schedule["worker"]), dtype=self.torch.float32, device=self.device)
             loss_ptr = self.loss.data_ptr()
         self.h.run_events(schedule, loss_ptr)
+
+    def run_events_in_pieces(self, schedule, piece, between=None, gradient_fn=None):
+        """A long schedule as calls of ``piece`` events, each looking T_max events ahead, so that staleness
+        reaches across the cuts and the result is that of a single call.  ``between(events_applied)`` runs
+        after every call (logging, diagnostics).  gradient_fn: as in run_events_with, for model "external";
+        it is handed event numbers that count from the start of ``schedule``."""
+        K = len(schedule["worker"])
+        look = 0 if self.model == B.MODEL_SYNTH else self.T_max
+        extra = schedule.get("extra_pairs")
+        for a in range(0, K, piece):
+            b = min(a + piece, K)
+            end = min(b + look, K)
+            part = {k: (None if schedule.get(k) is None else schedule[k][a:end])
+                    for k in ("worker", "neighbour", "tau", "batch_idx", "gamma")}
+            if extra is not None:
+                ptr = np.asarray(extra[0], dtype=np.int64)
+                part["extra_pairs"] = (ptr[a:end + 1] - ptr[a], extra[1][ptr[a]:ptr[end]], extra[2][ptr[a]:ptr[end]])
+            part["lookahead"] = end - b
+            if gradient_fn is None:
+                self.run_events(part)
+            else:
+                self.run_events_with(part, lambda worker, event, xhat, g, a=a: gradient_fn(worker, a + event, xhat, g))
+            if between is not None:
+                between(b)
 
     def _per_group(self, gradient_fn):
         """Wraps gradient_fn(worker, event, xhat, g), which takes two views of device memory, into the

@@ -100,18 +100,18 @@ def run_study(n=16, dims=(64, 256, 10), rows=2048, M=32, epochs=12, T_max=4, gam
         curves[name] = {"objective": curve, "error": errs, "max_consensus_distance": spread}
         eng.close()
     eng = engine(ring(n))
-    curve, errs = [eng.objective()], [eng.classification_error()]
-    spread = 0.0
-    for e in range(epochs):
-        sched = adpsgd_make_schedule(ring(n), events_per_epoch, seed=seed, T_max=T_max, M=M, rows=[rows] * n,
-                                     k_begin=e * events_per_epoch)
-        sched["gamma"] = step_sizes.step_decay(events_per_epoch, events_per_epoch, gamma, 0.5, halve_every,
-                                               k_begin=e * events_per_epoch)
-        eng.run_events(sched)
+    curve, errs, spread = [eng.objective()], [eng.classification_error()], [0.0]
+    sched = adpsgd_make_schedule(ring(n), epochs * events_per_epoch, seed=seed, T_max=T_max, M=M, rows=[rows] * n)
+    sched["gamma"] = step_sizes.step_decay(epochs * events_per_epoch, events_per_epoch, gamma, 0.5, halve_every)
+
+    def after_epoch(_events):
         curve.append(eng.objective())
         errs.append(eng.classification_error())
-        spread = max(spread, eng.consensus_distance())
-    curves["ad-psgd"] = {"objective": curve, "error": errs, "max_consensus_distance": spread}
+        spread[0] = max(spread[0], eng.consensus_distance())
+
+    # one schedule for the whole run, executed an epoch per call; the calls look ahead, so the result is that of one call
+    eng.run_events_in_pieces(sched, events_per_epoch, between=after_epoch)
+    curves["ad-psgd"] = {"objective": curve, "error": errs, "max_consensus_distance": spread[0]}
     eng.close()
     return {"n": n, "dims": list(dims), "rows": rows, "M": M, "epochs": epochs, "T_max": T_max, "gamma": gamma,
             "halve_every": halve_every, "momentum": momentum, "weight_decay": weight_decay,

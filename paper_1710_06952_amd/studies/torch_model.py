@@ -83,21 +83,18 @@ def run_study(n=8, dims=(32, 64, 6), rows=1024, M=32, epochs=4, T_max=3, gamma=0
     eng.set_models(flat.flatten_initial())
     events_per_epoch = n * rows // M
 
-    first_event = {"of_call": 0}
-
     def gradient(worker, event, xhat, out):
         gen = torch.Generator(device=device)
-        gen.manual_seed(seed * 1_000_003 + first_event["of_call"] + event)
+        gen.manual_seed(seed * 1_000_003 + event)
         idx = torch.randint(0, rows, (M,), device=device, generator=gen)
         flat.loss_and_gradient(xhat, X[worker][idx], Y[worker][idx], out)
 
     mean = lambda: torch.from_numpy(eng.get_mean_model()).to(device)
     curve = [flat.evaluate(mean(), allX, allY)]
-    for e in range(epochs):
-        sched = adpsgd_make_schedule(ring(n), events_per_epoch, seed=seed, T_max=T_max, k_begin=e * events_per_epoch)
-        first_event["of_call"] = e * events_per_epoch
-        eng.run_events_with(sched, gradient)
-        curve.append(flat.evaluate(mean(), allX, allY))
+    sched = adpsgd_make_schedule(ring(n), epochs * events_per_epoch, seed=seed, T_max=T_max)
+    # an epoch per call; the calls look ahead, so staleness reaches across the epochs as in one long call
+    eng.run_events_in_pieces(sched, events_per_epoch, gradient_fn=gradient,
+                             between=lambda _events: curve.append(flat.evaluate(mean(), allX, allY)))
     res = {"n": n, "d": flat.d, "rows": rows, "M": M, "epochs": epochs, "T_max": T_max, "gamma": gamma,
            "momentum": momentum, "weight_decay": weight_decay, "loss": [c[0] for c in curve], "error": [c[1] for c in curve],
            "consensus_distance": eng.consensus_distance(), "rounds": eng.get_stats()["rounds"],

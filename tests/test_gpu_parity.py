@@ -1175,6 +1175,21 @@ def test_calls_that_look_ahead_equal_one_long_run(P, model, comp, mu):
     oracle.run_events(Xc, dict(sched, tau=np.minimum(sched["tau"], np.arange(K) - call_start).astype(np.int32)), omodel, gamma,
                       V=np.zeros_like(Xr) if mu else None, **kw)
     assert rel_err(Xw, Xc) > 3 * TOL           # beyond rounding differences (only the events at the cuts differ)
+    # the same through the engine's helper, with extra averaging pairs riding along
+    from workloads import random_extra_pairs
+    with_extras = dict(sched, extra_pairs=random_extra_pairs(g, sched["worker"], sched["neighbour"], max_extra=1, seed=3))
+    first["event"] = 0
+    one = make()
+    run(one, with_extras)
+    many, seen = make(), []
+    if kind == "external":
+        many.run_events_in_pieces(with_extras, 97, between=seen.append, gradient_fn=gradient)
+    else:
+        many.run_events_in_pieces(with_extras, 97, between=seen.append)
+    assert seen == [97, 194, 291, 388, 420] and np.array_equal(many.get_models(), one.get_models())
+    assert not np.array_equal(one.get_models(), Xw)
+    one.close()
+    many.close()
     # a call that does not start with the events looked ahead to is refused; set_models drops them
     eng = make()
     first["event"] = 0
