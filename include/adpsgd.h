@@ -308,6 +308,10 @@ int adpsgd_consensus_distance_weighted(adpsgd_t* h, const double* p, double* out
  * row once. */
 int adpsgd_objective(adpsgd_t* h, const float* x, double* out);
 
+/* The same with the workers' probabilities, f(x) = sum_i p_i f_i(x): the objective of Sec. 3.1 when the
+ * workers are not equally fast.  p: host, n non-negative values that sum to 1, else ADPSGD_ERR_ARG. */
+int adpsgd_objective_weighted(adpsgd_t* h, const float* x, const double* p, double* out);
+
 /* Classification error at one point, 1 - accuracy (the quantity of the accuracy tables of the
  * experiments section, here over the loaded local data):
  *     (1/n) sum_i (1/rows_i) #{rows of worker i whose predicted label differs from the target}

@@ -22,7 +22,7 @@ EXPORTS = [
     "adpsgd_run_events", "adpsgd_run_events_with", "adpsgd_get_models", "adpsgd_get_mean_model", "adpsgd_consensus_distance", "adpsgd_consensus_distance_weighted",
     "adpsgd_get_bf16_models", "adpsgd_classification_error", "adpsgd_get_momentum", "adpsgd_get_stats", "adpsgd_make_schedule", "adpsgd_plan_rounds",
     "adpsgd_synth_gradient", "adpsgd_run_sync_steps", "adpsgd_run_sync_steps_with", "adpsgd_metropolis_weights",
-    "adpsgd_get_event_count", "adpsgd_set_event_count", "adpsgd_verify_plan", "adpsgd_objective", "adpsgd_count_nonfinite",
+    "adpsgd_get_event_count", "adpsgd_set_event_count", "adpsgd_verify_plan", "adpsgd_objective", "adpsgd_objective_weighted", "adpsgd_count_nonfinite",
 ]
 
 
@@ -127,6 +127,7 @@ def lib():
         L.adpsgd_verify_plan.argtypes = [i32, i64, P(i32), P(i32), P(i32), i32, i32, P(i32), P(i32), P(i32), i32,
                                          P(i64), P(i32), P(i32), P(i64), i64, P(i32)]
         L.adpsgd_objective.argtypes = [vp, vp, P(C.c_double)]
+        L.adpsgd_objective_weighted.argtypes = [vp, vp, P(C.c_double), P(C.c_double)]
         L.adpsgd_run_events_with.argtypes = [vp, P(Schedule), GRADIENT_FN, vp]
         L.adpsgd_run_sync_steps_with.argtypes = [vp, P(SyncSchedule), GRADIENT_FN, vp]
         L.adpsgd_classification_error.argtypes = [vp, vp, P(C.c_double)]
@@ -382,10 +383,17 @@ class Handle:
         _check(self._h, lib().adpsgd_get_mean_model(self._h, res.ctypes.data, 0))
         return res
 
-    def objective(self, x_ptr=None):
-        """f at a device vector (integer pointer), or at the mean model when x_ptr is None."""
+    def objective(self, x_ptr=None, p=None):
+        """f at a device vector (integer pointer), or at the mean model when x_ptr is None; p: the workers'
+        probabilities (default 1 / n)."""
         out = C.c_double(0.0)
-        _check(self._h, lib().adpsgd_objective(self._h, x_ptr, C.byref(out)))
+        if p is None:
+            _check(self._h, lib().adpsgd_objective(self._h, x_ptr, C.byref(out)))
+        else:
+            p = np.ascontiguousarray(p, dtype=np.float64)
+            if p.shape != (self.n,):
+                raise ValueError("p must have one entry per worker")
+            _check(self._h, lib().adpsgd_objective_weighted(self._h, x_ptr, p.ctypes.data_as(C.POINTER(C.c_double)), C.byref(out)))
         return out.value
 
     def classification_error(self, x_ptr=None):

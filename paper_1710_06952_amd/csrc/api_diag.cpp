@@ -116,7 +116,7 @@ namespace {
 
 // The perceptron's objective: forward pass and cross-entropy over all local samples, in chunks of
 // M samples (the last chunk of a worker is padded with its last sample and counts only its own).
-int mlp_objective(adpsgd_t* h, const float* x, double* out, bool count_errors) {
+int mlp_objective(adpsgd_t* h, const float* x, double* out, bool count_errors, const double* p) {
     const int32_t n = h->n, M = h->o.M;
     std::vector<int64_t> first(n + 1, 0);          // first operation of every worker
     for (int32_t i = 0; i < n; ++i) {
@@ -170,16 +170,24 @@ int mlp_objective(adpsgd_t* h, const float* x, double* out, bool count_errors) {
     for (int32_t i = 0; i < n; ++i) {
         double s = 0.0;
         for (int64_t o = first[i]; o < first[i + 1]; ++o) s += sums[o];
-        total += s / static_cast<double>(h->data[i].rows);
+        total += (p ? p[i] : 1.0 / n) * (s / static_cast<double>(h->data[i].rows));
     }
-    *out = total / n;
+    *out = total;
     return ADPSGD_OK;
 }
 
 // mean over the workers of the mean over their rows of the loss (or of the 0/1 classification error) at x
-int evaluate(adpsgd_t* h, const float* x, double* out, bool count_errors) {
+int evaluate(adpsgd_t* h, const float* x, double* out, bool count_errors, const double* p = nullptr) {
     if (x && !aligned16(x)) return fail(h, ADPSGD_ERR_ARG, "objective: x is not 16-byte aligned");
-    if (h->o.model == ADPSGD_MODEL_MLP) return mlp_objective(h, x, out, count_errors);
+    if (p) {
+        double psum = 0.0;
+        for (int32_t i = 0; i < h->n; ++i) {
+            if (!(p[i] >= 0.0) || !std::isfinite(p[i])) return fail(h, ADPSGD_ERR_ARG, "objective: weight negative or not finite");
+            psum += p[i];
+        }
+        if (std::fabs(psum - 1.0) > 1e-9) return fail(h, ADPSGD_ERR_ARG, "objective: the weights do not sum to 1");
+    }
+    if (h->o.model == ADPSGD_MODEL_MLP) return mlp_objective(h, x, out, count_errors, p);
     std::vector<ObjectiveWorker> tab(h->n);
     int64_t max_rows = 0;
     for (int32_t i = 0; i < h->n; ++i) {
@@ -188,13 +196,15 @@ int evaluate(adpsgd_t* h, const float* x, double* out, bool count_errors) {
         max_rows = std::max(max_rows, h->data[i].rows);
     }
     HIP_TRY(h, hipStreamSynchronize(h->stream));
-    // diag buffer: [mean model d floats, 256-byte padded][worker table][partials][result]
+    // diag buffer: [mean model d floats, 256-byte padded][worker table][partials][result][weights]
     const int64_t groups = objective_row_groups(max_rows);
     const size_t off_tab = (static_cast<size_t>(h->d) * 4 + 255) & ~size_t(255);
     const size_t off_part = (off_tab + tab.size() * sizeof(ObjectiveWorker) + 255) & ~size_t(255);
     const size_t off_res = off_part + static_cast<size_t>(groups) * h->n * sizeof(double);
-    HIP_TRY(h, h->diag.reserve(off_res + sizeof(double)));
+    const size_t off_w = off_res + sizeof(double);
+    HIP_TRY(h, h->diag.reserve(off_w + (p ? static_cast<size_t>(h->n) * sizeof(double) : 0)));
     char* base = static_cast<char*>(h->diag.p);
+    if (p) HIP_TRY(h, hipMemcpyAsync(base + off_w, p, static_cast<size_t>(h->n) * sizeof(double), hipMemcpyHostToDevice, h->stream));
     const float* point = x;
     if (!x) {
         HIP_TRY(h, launch_mean_model(h->o.X, h->o.ldx, h->d, h->n, reinterpret_cast<float*>(base), h->stream));
@@ -203,7 +213,7 @@ int evaluate(adpsgd_t* h, const float* x, double* out, bool count_errors) {
     HIP_TRY(h, hipMemcpyAsync(base + off_tab, tab.data(), tab.size() * sizeof(ObjectiveWorker), hipMemcpyHostToDevice, h->stream));
     HIP_TRY(h, launch_objective(h->o.model, point, h->d, h->n, reinterpret_cast<const ObjectiveWorker*>(base + off_tab), max_rows,
                                 h->o.lambda, reinterpret_cast<double*>(base + off_part), reinterpret_cast<double*>(base + off_res),
-                                count_errors, h->stream));
+                                count_errors, p ? reinterpret_cast<const double*>(base + off_w) : nullptr, h->stream));
     HIP_TRY(h, hipMemcpyAsync(out, base + off_res, sizeof(double), hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     return ADPSGD_OK;
@@ -217,6 +227,14 @@ extern "C" int adpsgd_objective(adpsgd_t* h, const float* x, double* out) {
     if (h->o.model == ADPSGD_MODEL_SYNTH)
         return fail(h, ADPSGD_ERR_STATE, "objective: the synthetic-gradient model has no objective");
     return evaluate(h, x, out, false);
+}
+
+extern "C" int adpsgd_objective_weighted(adpsgd_t* h, const float* x, const double* p, double* out) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (!out || !p) return fail(h, ADPSGD_ERR_ARG, "objective_weighted: p or out is NULL");
+    if (h->o.model == ADPSGD_MODEL_SYNTH)
+        return fail(h, ADPSGD_ERR_STATE, "objective: the synthetic-gradient model has no objective");
+    return evaluate(h, x, out, false, p);
 }
 
 extern "C" int adpsgd_classification_error(adpsgd_t* h, const float* x, double* out) {

@@ -212,7 +212,8 @@ struct ObjectiveWorker {
 };
 int64_t objective_row_groups(int64_t max_rows);
 hipError_t launch_objective(int model, const float* x, int64_t d, int32_t n, const ObjectiveWorker* workers, int64_t max_rows,
-                            float lambda, double* partial, double* result, bool count_errors, hipStream_t st);
+                            float lambda, double* partial, double* result, bool count_errors, const double* weights,
+                            hipStream_t st);   // weights: device, n probabilities, or nullptr for 1 / n
 // out[t] (ld floats each) = X[ops[t].worker] - comp_gamma * slot[comp_slot] for the compensated operations of a group
 hipError_t launch_compensated_rows(const float* X, int64_t ld, const GradOp* ops, int32_t n_ops, const float* slots, float* out,
                                    hipStream_t st);

@@ -196,11 +196,14 @@ __global__ __launch_bounds__(kThreads) void objective_partial_kernel(int model, 
     if (threadIdx.x == 0) partial[static_cast<int64_t>(blockIdx.y) * gridDim.x + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+// weights: the workers' probabilities p_i (device, n doubles) or nullptr for 1 / n; a worker's partials are
+// the `groups` consecutive entries starting at worker * groups
 __global__ __launch_bounds__(kThreads) void objective_final_kernel(const double* partial, int64_t count, int32_t n, const float* x,
-                                                                  int64_t d, double half_lambda, double* result) {
+                                                                  int64_t d, double half_lambda, double* result,
+                                                                  const double* __restrict__ weights, int64_t groups) {
     __shared__ double red[kWaves], red2[kWaves];
     double acc = 0.0, sq = 0.0;
-    for (int64_t b = threadIdx.x; b < count; b += kThreads) acc += partial[b];
+    for (int64_t b = threadIdx.x; b < count; b += kThreads) acc += weights ? partial[b] * (weights[b / groups] * n) : partial[b];
     if (half_lambda != 0.0)
         for (int64_t e = threadIdx.x; e < d; e += kThreads) sq += static_cast<double>(x[e]) * x[e];
     acc = wave_sum(acc);
@@ -255,7 +258,8 @@ int64_t objective_row_groups(int64_t max_rows) {
 }
 
 hipError_t launch_objective(int model, const float* x, int64_t d, int32_t n, const ObjectiveWorker* workers, int64_t max_rows,
-                            float lambda, double* partial, double* result, bool count_errors, hipStream_t st) {
+                            float lambda, double* partial, double* result, bool count_errors, const double* weights,
+                            hipStream_t st) {
     const int64_t groups = objective_row_groups(max_rows);
     if (groups < 1 || groups > 0x7FFFFFFF || n > 65535) return hipErrorInvalidValue;
     hipLaunchKernelGGL(objective_partial_kernel, dim3(static_cast<uint32_t>(groups), n), dim3(kThreads), 0, st, model, x, d, workers, partial,
@@ -263,7 +267,7 @@ hipError_t launch_objective(int model, const float* x, int64_t d, int32_t n, con
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(objective_final_kernel, dim3(1), dim3(kThreads), 0, st, partial, groups * n, n, x, d,
-                       model == ADPSGD_MODEL_LOGREG && !count_errors ? 0.5 * static_cast<double>(lambda) : 0.0, result);
+                       model == ADPSGD_MODEL_LOGREG && !count_errors ? 0.5 * static_cast<double>(lambda) : 0.0, result, weights, groups);
     return hipGetLastError();
 }
 

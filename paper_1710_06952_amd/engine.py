@@ -180,12 +180,13 @@ class Engine:
     def consensus_distance(self, p=None):
         return self.h.consensus_distance(p)
 
-    def objective(self, x=None):
-        """The objective over all local data at x (numpy vector or None = the mean model)."""
+    def objective(self, x=None, p=None):
+        """The objective over all local data at x (numpy vector or None = the mean model), the workers
+        weighted equally or by the probabilities p."""
         if x is None:
-            return self.h.objective(None)
+            return self.h.objective(None, p)
         xt = self.torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(self.device)
-        return self.h.objective(xt.data_ptr())
+        return self.h.objective(xt.data_ptr(), p)
 
     def classification_error(self, x=None):
         """Fraction of the local samples misclassified at x (numpy vector or None = the mean model)."""

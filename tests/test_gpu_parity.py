@@ -1338,6 +1338,14 @@ def test_objective_over_all_local_data(P, model, n, d, lam):
     mean32 = eng.get_mean_model()
     assert np.isclose(eng.objective(), f_ref(mean32), rtol=1e-5)
     assert abs(eng.objective(xq) - eng.objective()) > 1e-3          # the two points differ
+    # weighted by the workers' probabilities: sum_i p_i f_i(x)
+    p = np.random.default_rng(7).random(n) ** 2
+    p /= p.sum()
+    f_i = [oracle.minibatch_gradient(omodel, xq, feats[i], targs[i], np.arange(rows[i]), 1.0 / rows[i], lam=lam)[1] for i in range(n)]
+    assert np.isclose(eng.objective(xq, p), float(np.dot(p, f_i)), rtol=1e-5)
+    assert np.isclose(eng.objective(xq, np.full(n, 1.0 / n)), eng.objective(xq), rtol=1e-12)
+    with pytest.raises(P.AdpsgdError):
+        eng.objective(xq, 2 * p)
     eng.close()
 
 
@@ -1453,6 +1461,10 @@ def test_objective_of_the_perceptron(P):
 
     xq = X0[1]
     assert np.isclose(eng.objective(xq), f_ref(xq), rtol=2e-3)
+    p = np.array([0.6, 0.1, 0.3])
+    f_i = [oracle.minibatch_gradient(oracle.MODEL_MLP, xq, feats[i], labels[i], np.arange(rows[i]), 1.0 / rows[i], mlp=dims)[1]
+           for i in range(n)]
+    assert np.isclose(eng.objective(xq, p), float(np.dot(p, f_i)), rtol=2e-3)
     assert np.isclose(eng.objective(), f_ref(eng.get_mean_model()), rtol=2e-3)
     assert abs(eng.objective(xq) - eng.objective()) > 1e-3
     eng.close()
