@@ -181,6 +181,9 @@ typedef struct {
     const int32_t* tau_den; /* n entries (tau_mode 1) */
     int32_t M;              /* minibatch size, 0 = no batch indices */
     const int32_t* rows;    /* n local sample counts (M > 0) */
+    int32_t piece_of_run;   /* 0: the K events stand alone, tau_k <= k - k_begin;  1: they are events k_begin .. of one
+                               long schedule, tau_k <= k: exactly the slice of the schedule generated in one go (for
+                               calls that look ahead, see adpsgd_schedule_t) */
 } adpsgd_sched_params_t;
 
 typedef struct {

@@ -62,7 +62,7 @@ def philox4x32_10(ctr, key):
 
 
 def make_schedule(graph, K, seed=0, k_begin=0, T_max=0, tau_mode=0, weight=None,
-                  tau_num=None, tau_den=None, M=0, rows=None):
+                  tau_num=None, tau_den=None, M=0, rows=None, piece_of_run=False):
     """Random choices of Algorithm 1 for K events: worker i_k, neighbour j_k,
     staleness tau_k and the M minibatch indices.  ``graph`` = (rowptr, col)."""
     rowptr = np.ascontiguousarray(graph[0], dtype=np.int32)
@@ -80,7 +80,8 @@ def make_schedule(graph, K, seed=0, k_begin=0, T_max=0, tau_mode=0, weight=None,
         C.c_int32(n), _p(rowptr, C.c_int32), _p(col, C.c_int32), _p(weight, C.c_int32),
         C.c_int32(tau_mode), C.c_int32(T_max), _p(tau_num, C.c_int32), _p(tau_den, C.c_int32),
         C.c_int32(M), _p(rows, C.c_int32), C.c_uint64(seed), C.c_uint64(k_begin), C.c_int64(K),
-        _p(worker, C.c_int32), _p(nbr, C.c_int32), _p(tau, C.c_int32), _p(batch, C.c_int32))
+        _p(worker, C.c_int32), _p(nbr, C.c_int32), _p(tau, C.c_int32), _p(batch, C.c_int32),
+        C.c_int32(1 if piece_of_run else 0))
     if rc != 0:
         raise ValueError("oracle_make_schedule: bad argument")
     return {"worker": worker, "neighbour": nbr, "tau": tau, "batch_idx": batch}

@@ -90,7 +90,8 @@ int oracle_make_schedule(int32_t n, const int32_t* rowptr, const int32_t* col,
                          const int32_t* weight, int32_t tau_mode, int32_t T_max,
                          const int32_t* tau_num, const int32_t* tau_den, int32_t M,
                          const int32_t* rows, uint64_t seed, uint64_t k_begin, int64_t K,
-                         int32_t* worker, int32_t* neighbour, int32_t* tau, int32_t* batch_idx)
+                         int32_t* worker, int32_t* neighbour, int32_t* tau, int32_t* batch_idx,
+                         int32_t piece_of_run)
 {
     if (n < 1 || K < 0 || T_max < 0 || M < 0) return -1;
     if (tau_mode != 0 && (!tau_num || !tau_den)) return -1;
@@ -138,7 +139,9 @@ int oracle_make_schedule(int32_t n, const int32_t* rowptr, const int32_t* col,
                 if ((uint64_t)w[2] < thr) t = s; else break;
             }
         }
-        if (t > kk) t = kk;
+        /* the read cannot lie before event 0 -- of these K events, or of the whole run when they are a piece of it */
+        if (piece_of_run) { if ((uint64_t)t > k) t = (int64_t)k; }
+        else if (t > kk) t = kk;
         tau[kk] = (int32_t)t;
 
         /* minibatch xi_k: M draws with replacement from the local rows */

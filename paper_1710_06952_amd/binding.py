@@ -68,7 +68,7 @@ class SyncSchedule(C.Structure):
 class SchedParams(C.Structure):
     _fields_ = [("graph", Graph), ("weight", C.POINTER(C.c_int32)), ("tau_mode", C.c_int32),
                 ("T_max", C.c_int32), ("tau_num", C.POINTER(C.c_int32)), ("tau_den", C.POINTER(C.c_int32)),
-                ("M", C.c_int32), ("rows", C.POINTER(C.c_int32))]
+                ("M", C.c_int32), ("rows", C.POINTER(C.c_int32)), ("piece_of_run", C.c_int32)]
 
 
 class Stats(C.Structure):
@@ -158,11 +158,12 @@ def _check(h, rc):
 
 
 def adpsgd_make_schedule(graph, K, seed=0, k_begin=0, T_max=0, tau_mode=0, weight=None, tau_num=None,
-                         tau_den=None, M=0, rows=None):
+                         tau_den=None, M=0, rows=None, piece_of_run=False):
     """Host-only: the random choices of Algorithm 1 for K events (see adpsgd.h)."""
     g, keep = _graph_struct(graph)
     weight, tau_num, tau_den, rows = map(_as_i32, (weight, tau_num, tau_den, rows))
-    p = SchedParams(g, _i32p(weight), tau_mode, T_max, _i32p(tau_num), _i32p(tau_den), M, _i32p(rows))
+    p = SchedParams(g, _i32p(weight), tau_mode, T_max, _i32p(tau_num), _i32p(tau_den), M, _i32p(rows),
+                    1 if piece_of_run else 0)
     worker, nbr, tau = (np.zeros(K, np.int32) for _ in range(3))
     batch = np.zeros((K, M), np.int32) if M > 0 else None
     rc = lib().adpsgd_make_schedule(C.byref(p), seed, k_begin, K, _i32p(worker), _i32p(nbr), _i32p(tau), _i32p(batch))

@@ -159,7 +159,9 @@ extern "C" int adpsgd_make_schedule(const adpsgd_sched_params_t* p, uint64_t see
             const std::vector<uint64_t>& th = thr[i];   // non-increasing in t
             while (t < p->T_max && static_cast<uint64_t>(w[2]) < th[t + 1]) ++t;
         }
-        tau[q] = static_cast<int32_t>(t < q ? t : q);
+        // staleness cannot reach behind event 0: of this call, or of the whole run when the call is a piece of it
+        const uint64_t behind = p->piece_of_run ? k : static_cast<uint64_t>(q);
+        tau[q] = static_cast<int32_t>(static_cast<uint64_t>(t) < behind ? static_cast<uint64_t>(t) : behind);
 
         if (p->M > 0) {
             int32_t* dst = batch_idx + q * static_cast<int64_t>(p->M);

@@ -52,7 +52,7 @@ int main(void) {
     CHECK(adpsgd_set_models(h, x0, D, 0) == ADPSGD_OK, 3);
     double c0 = 0.0, c1 = 0.0;
     CHECK(adpsgd_consensus_distance(h, &c0) == ADPSGD_OK, 4);
-    adpsgd_sched_params_t sp = {{N, rowptr, col}, NULL, 0, 2, NULL, NULL, 0, NULL};
+    adpsgd_sched_params_t sp = {{N, rowptr, col}, NULL, 0, 2, NULL, NULL, 0, NULL, 0};
     int32_t *worker = malloc(sizeof(int32_t) * K), *nbr = malloc(sizeof(int32_t) * K), *tau = malloc(sizeof(int32_t) * K);
     CHECK(adpsgd_make_schedule(&sp, 3, 0, K, worker, nbr, tau, NULL) == ADPSGD_OK, 5);
     adpsgd_schedule_t s = {0};

@@ -15,7 +15,7 @@ int main(void) {
         rows[i] = 32;
     }
     rowptr[N] = 2 * N;
-    adpsgd_sched_params_t sp = {{N, rowptr, col}, NULL, 0, T, NULL, NULL, M, rows};
+    adpsgd_sched_params_t sp = {{N, rowptr, col}, NULL, 0, T, NULL, NULL, M, rows, 0};
     int32_t *worker = malloc(sizeof(int32_t) * K), *nbr = malloc(sizeof(int32_t) * K), *tau = malloc(sizeof(int32_t) * K);
     int32_t* batch = malloc(sizeof(int32_t) * K * M);
     if (adpsgd_make_schedule(&sp, 7, 0, K, worker, nbr, tau, batch) != ADPSGD_OK) return 1;

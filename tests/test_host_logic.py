@@ -150,6 +150,27 @@ def _check_plan(n, sched, n_slots, with_grad=True):
     return R
 
 
+def test_pieces_of_one_schedule_are_its_slices():
+    """piece_of_run: events k_begin .. generated on their own are exactly the slice of the schedule generated in
+    one go (the generator is counter based; only the clipping of tau at the start differs), in both
+    implementations; without the flag the first events of a piece have their staleness cut at the piece's start."""
+    g = random_regular4_graph(12, 2)
+    kw = dict(seed=5, T_max=7, M=3, rows=[20] * 12)
+    full = oracle.make_schedule(g, 500, **kw)
+    clipped = 0
+    for a, b in ((0, 60), (60, 61), (61, 300), (300, 500)):
+        mine = P.adpsgd_make_schedule(g, b - a, k_begin=a, piece_of_run=True, **kw)
+        ref = oracle.make_schedule(g, b - a, k_begin=a, piece_of_run=True, **kw)
+        alone = P.adpsgd_make_schedule(g, b - a, k_begin=a, **kw)
+        for key in ("worker", "neighbour", "tau", "batch_idx"):
+            assert np.array_equal(mine[key], full[key][a:b]) and np.array_equal(ref[key], full[key][a:b])
+            if key != "tau":
+                assert np.array_equal(alone[key], full[key][a:b])
+        assert np.array_equal(alone["tau"], np.minimum(full["tau"][a:b], np.arange(b - a)))
+        clipped += int((alone["tau"] != full["tau"][a:b]).sum())
+    assert clipped > 0
+
+
 @pytest.mark.parametrize("n,T,graph", [(8, 3, "ring"), (64, 8, "ring"), (16, 4, "reg4"), (6, 0, "ring"), (1, 0, "ring")])
 def test_planner_keeps_serial_semantics(n, T, graph):
     g = ring_graph(n) if graph == "ring" else random_regular4_graph(n, 1)
