@@ -11,7 +11,10 @@
 // place: a block stages all n rows of a tile of 16..256 columns in LDS, then
 // writes each row's mixture straight back to X.  HBM traffic is one
 // read and one write of X (plus one read of the gradients for the data models, and a
-// read and a write of the momentum buffers when they are in use).
+// read and a write of the momentum buffers when they are in use).  When X exceeds the
+// memory-side cache these streams bypass the caches (STREAM: non-temporal accesses; measured with
+// gradients from slots on one box: 4.47 -> 4.60 TB/s at n = 128, d = 25.6 M and 4.45 -> 4.72 TB/s at
+// n = 32, d = 4.2 M; for cache-resident sizes the plain accesses are up to 25 % faster, so they stay).
 #include "device_common.hpp"
 #include "internal.hpp"
 
@@ -41,7 +44,7 @@ struct SyncParams {
 };
 
 // grid = ceil(d / cols); thread = (quad of 4 columns, row lane)
-template <bool SYNTH, bool SHADOW, bool MOM>
+template <bool SYNTH, bool SHADOW, bool MOM, bool STREAM>
 __global__ __launch_bounds__(kThreads) void sync_mix_apply_kernel(const SyncParams p) {
     extern __shared__ __attribute__((aligned(16))) float tile[];   // [n][cols]
     const int quads = p.cols >> 2;
@@ -50,7 +53,7 @@ __global__ __launch_bounds__(kThreads) void sync_mix_apply_kernel(const SyncPara
     const bool live = c < p.d;     // d is padded to a multiple of 4 by the leading dimension
     for (int r = ry; r < p.n; r += rows_per_pass) {
         v4f v = {0, 0, 0, 0};
-        if (live) v = *reinterpret_cast<const v4f*>(p.X + static_cast<int64_t>(r) * p.ld + c);
+        if (live) v = load4<STREAM>(p.X + static_cast<int64_t>(r) * p.ld + c);
         *reinterpret_cast<v4f*>(tile + static_cast<int64_t>(r) * p.cols + 4 * qx) = v;
     }
     __syncthreads();
@@ -67,12 +70,12 @@ __global__ __launch_bounds__(kThreads) void sync_mix_apply_kernel(const SyncPara
             g = synth_normals4(static_cast<uint32_t>(q), static_cast<uint32_t>(q >> 32), static_cast<uint32_t>(k),
                                static_cast<uint32_t>(k >> 32), p.key0, p.key1) * p.synth_std;
         } else {
-            g = *reinterpret_cast<const v4f*>(p.slots + static_cast<int64_t>(i) * p.ld + c);
+            g = load4<STREAM>(p.slots + static_cast<int64_t>(i) * p.ld + c);
         }
         v4f out;
         if (MOM) {
             float* __restrict__ vrow = p.V + static_cast<int64_t>(i) * p.ld + c;
-            const v4f vo = *reinterpret_cast<const v4f*>(vrow);
+            const v4f vo = load4<STREAM>(vrow);
             const float mixed[4] = {acc.x, acc.y, acc.z, acc.w}, gv[4] = {g.x, g.y, g.z, g.w}, vold[4] = {vo.x, vo.y, vo.z, vo.w};
             float xn[4], unused[4], vn[4];
 #pragma unroll
@@ -86,7 +89,7 @@ __global__ __launch_bounds__(kThreads) void sync_mix_apply_kernel(const SyncPara
                 if (c + 2 >= p.d) vout.z = 0.0f;
                 if (c + 3 >= p.d) vout.w = 0.0f;
             }
-            *reinterpret_cast<v4f*>(vrow) = vout;
+            store4<STREAM>(vrow, vout);
         } else {
 #pragma clang fp contract(off)
             const v4f step = g * p.gamma;
@@ -97,7 +100,7 @@ __global__ __launch_bounds__(kThreads) void sync_mix_apply_kernel(const SyncPara
             if (c + 2 >= p.d) out.z = 0.0f;
             if (c + 3 >= p.d) out.w = 0.0f;
         }
-        *reinterpret_cast<v4f*>(p.X + static_cast<int64_t>(i) * p.ld + c) = out;
+        store4<STREAM>(p.X + static_cast<int64_t>(i) * p.ld + c, out);
         if (SHADOW) {
             v4h hb = {bf16_rne(out.x), bf16_rne(out.y), bf16_rne(out.z), bf16_rne(out.w)};
             *reinterpret_cast<v4h*>(p.Xbf16 + static_cast<int64_t>(i) * p.ld + c) = hb;
@@ -105,11 +108,11 @@ __global__ __launch_bounds__(kThreads) void sync_mix_apply_kernel(const SyncPara
     }
 }
 
-template <bool MOM>
+template <bool MOM, bool STREAM>
 hipError_t launch_variant(const SyncParams& p, bool synth, dim3 grid, size_t lds, hipStream_t st) {
-    if (synth) hipLaunchKernelGGL((sync_mix_apply_kernel<true, false, MOM>), grid, dim3(kThreads), lds, st, p);
-    else if (p.Xbf16) hipLaunchKernelGGL((sync_mix_apply_kernel<false, true, MOM>), grid, dim3(kThreads), lds, st, p);
-    else hipLaunchKernelGGL((sync_mix_apply_kernel<false, false, MOM>), grid, dim3(kThreads), lds, st, p);
+    if (synth) hipLaunchKernelGGL((sync_mix_apply_kernel<true, false, MOM, STREAM>), grid, dim3(kThreads), lds, st, p);
+    else if (p.Xbf16) hipLaunchKernelGGL((sync_mix_apply_kernel<false, true, MOM, STREAM>), grid, dim3(kThreads), lds, st, p);
+    else hipLaunchKernelGGL((sync_mix_apply_kernel<false, false, MOM, STREAM>), grid, dim3(kThreads), lds, st, p);
     return hipGetLastError();
 }
 
@@ -153,7 +156,9 @@ hipError_t launch_sync_mix_apply(const SyncArgs& a, hipStream_t st) {
     p.V = a.V;
     p.momentum = a.momentum;
     p.weight_decay = a.weight_decay;
-    return a.V ? launch_variant<true>(p, a.synth, grid, lds, st) : launch_variant<false>(p, a.synth, grid, lds, st);
+    const bool stream = static_cast<int64_t>(a.n) * a.ld * 4 > (256ll << 20);      // X does not fit the memory-side cache
+    if (stream) return a.V ? launch_variant<true, true>(p, a.synth, grid, lds, st) : launch_variant<false, true>(p, a.synth, grid, lds, st);
+    return a.V ? launch_variant<true, false>(p, a.synth, grid, lds, st) : launch_variant<false, false>(p, a.synth, grid, lds, st);
 }
 
 }  // namespace adpsgd_impl
