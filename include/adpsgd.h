@@ -320,7 +320,9 @@ int adpsgd_objective_weighted(adpsgd_t* h, const float* x, const double* p, doub
  *     (1/n) sum_i (1/rows_i) #{rows of worker i whose predicted label differs from the target}
  * LOGREG predicts +1 when a.x >= 0 and -1 otherwise; the MLP predicts the class of its largest
  * logit (the lowest class on ties), from the same forward pass as its gradient.  x, *out, cost and
- * errors as for adpsgd_objective; ADPSGD_ERR_STATE for SYNTH and LSQ, which have no labels. */
+ * errors as for adpsgd_objective; ADPSGD_ERR_STATE for SYNTH and LSQ, which have no labels.
+ * For held-out data, create a second handle on the same X (models are borrowed, not owned) and load
+ * that data into it: its objective and classification error are the test loss and test error. */
 int adpsgd_classification_error(adpsgd_t* h, const float* x, double* out);
 
 /* Divergence check: the number of entries of the models that are NaN or infinite (0 for a healthy
