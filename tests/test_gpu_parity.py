@@ -1393,6 +1393,26 @@ def test_classification_error_matches_the_oracle(P):
     after = eng.classification_error()
     assert after < 0.5 * before
     assert abs(after - ref(eng.get_mean_model(), oracle.MODEL_MLP, dict(mlp=dims))) <= 1.0 / min(rows) / n + 1e-12
+    # held-out data: a second handle on the same models with other data loaded gives the test error
+    import torch
+    from workloads import f32_to_bf16_bits
+    test_f, test_y, _ = mixture_data(n, 80, din=dims[0], classes=dims[2], seed=8)      # same mixture (seed), ...
+    test_f = [np.ascontiguousarray(f[40:]) for f in test_f]                            # ... rows the training never saw
+    test_y = [np.ascontiguousarray(t[40:]) for t in test_y]
+    other = P.Handle(g, d, model=P.MODEL_MLP, X_ptr=eng.X.data_ptr(), ldx=eng.ld, M=M, gamma=0.05, mlp=dims,
+                     Xbf16_ptr=eng.Xbf16.data_ptr(), workspace_ptr=eng.workspace.data_ptr(),
+                     workspace_bytes=eng.workspace.numel() * 4, stream=torch.cuda.current_stream().cuda_stream)
+    keep = []
+    for i in range(n):
+        ft = torch.zeros((40, 32), dtype=torch.bfloat16, device="cuda:0")
+        ft[:, :dims[0]] = torch.from_numpy(test_f[i].view(np.int16)).cuda().view(torch.bfloat16)
+        yt = torch.from_numpy(test_y[i]).cuda()
+        keep.append((ft, yt))
+        other.load_data(i, ft.data_ptr(), 40, 32, yt.data_ptr())
+    want = float(np.mean([oracle.count_misclassified(oracle.MODEL_MLP, eng.get_mean_model(), test_f[i], test_y[i], mlp=dims) / 40
+                          for i in range(n)]))
+    assert abs(other.classification_error() - want) <= 1.0 / 40 / n + 1e-12 and want < 0.6
+    other.destroy()
     eng.close()
     eng = P.Engine(g, 64, "lsq", M=2, gamma=0.1)
     with pytest.raises(P.AdpsgdError) as ei:
