@@ -35,12 +35,14 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 
-def traffic_from_profiles():
-    """HBM bytes per event of the fused kernel measured with rocprofv3 --pmc (FETCH_SIZE and
-    WRITE_SIZE runs, scaled by a copy kernel of known size); kept as text under profiles/."""
-    path = os.path.join(ROOT, "profiles", "fused_gossip_apply_cfg3_pmc.txt")
+def traffic_from_profiles(config=3):
+    """HBM bytes per event measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy
+    kernel of known size); kept as text under profiles/: the fused kernel of configuration 3, or all
+    kernels of an event of the data configurations 2, 4 and 5."""
+    name, key = (("fused_gossip_apply_cfg3_pmc.txt", "traffic_bytes_per_event") if config == 3 else
+                 ("data_configurations_hbm_traffic_pmc.txt", "traffic_bytes_per_event_cfg%d" % config))
     try:
-        m = re.search(r"^traffic_bytes_per_event:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        m = re.search(r"^%s:\s*([0-9.eE+]+)" % key, open(os.path.join(ROOT, "profiles", name)).read(), re.M)
         return float(m.group(1)) if m else None
     except OSError:
         return None
@@ -222,7 +224,8 @@ def main():
         bytes_per_event = algorithmic_bytes_per_event(cfg)
         achieved = bytes_per_event / (per_grad_s + per_update_s) / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "frac": achieved / HBM_PEAK_GBS,
+                "traffic": traffic_from_profiles(args.config) if (not args.d and eng.V is None) else None,   # bytes per event, as `achieved` is
                 "kernel": "gradient + update kernels (per event)", "avg_gradient_us": per_grad_s * 1e6,
                 "fused_us_per_event": per_update_s * 1e6, "bytes_per_event": bytes_per_event,
                 "bytes_per_gradient": grad_rows_bytes, "events_per_launch": events_per_launch}
