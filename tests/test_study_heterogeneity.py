@@ -90,3 +90,59 @@ def test_study_runs_end_to_end_on_a_tiny_problem():
     a, b = link["results"]
     assert b["sync_speedup"] < 0.2 * a["sync_speedup"]          # every synchronous iteration waits for the link
     assert b["adpsgd_speedup"] > 0.25 * a["adpsgd_speedup"]     # AD-PSGD only loses the exchanges that use it
+
+
+def _rel_err(x_gpu, x_ref):
+    num = np.max(np.abs(x_gpu.astype(np.float64) - x_ref.astype(np.float64)), axis=1)
+    den = np.maximum(np.max(np.abs(x_ref.astype(np.float64)), axis=1), 1e-30)
+    return float(np.max(num / den))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("exponential", [True, False])
+def test_clock_derived_schedules_match_the_oracle(exponential):
+    """The study's two schedules for one worker slowed down ten times (Sec. 5.4, robustness against slow
+    computation): the events of free-running workers with the staleness their clocks imply, and the synchronous
+    iterations beside them, each executed by the HIP library and by the serial oracle on the same data, final
+    models and per-event losses compared at the fp32 parity bound."""
+    n, d, rows, M, epochs, seed = 16, 2051, 96, 4, 30, 3
+    graph = H.ring(n)
+    feats, targs = H.make_problem(n, d, rows, seed)
+    gamma = 0.5 * M
+    K = epochs * (rows // M)
+    mean_time = np.ones(n)
+    mean_time[n // 2] = 10.0
+    sched, when = H.clock_schedule(graph, K, mean_time, M, rows, seed, exponential)
+    T_max = int(sched["tau"].max())
+    share = np.bincount(sched["worker"], minlength=n) / K
+    assert share[n // 2] < 0.3 * share[0] and T_max >= n - 1        # the slow worker is rare and the reads are stale
+    print("clock schedule (%s): K=%d, T_max=%d" % ("exp" if exponential else "det", K, T_max), flush=True)
+    eng = P.Engine(graph, d, "lsq", M=M, gamma=gamma, T_max=T_max, n_slots=T_max + 1 + 2 * n)
+    eng.load_data(feats, targs)
+    eng.set_models(np.zeros(d, np.float32))
+    eng.run_events(sched, want_loss=True)
+    Xg, lg = eng.get_models(), eng.get_loss()
+    eng.close()
+    Xr = np.zeros((n, d), np.float32)
+    r = oracle.run_events(Xr, sched, oracle.MODEL_LSQ, gamma, M=M, gscale=1.0 / M, features=feats, targets=targs,
+                          want_loss=True)
+    assert _rel_err(Xg, Xr) <= 1e-5
+    assert np.allclose(lg, r["loss"], rtol=2e-4, atol=1e-7)
+    Xf = np.zeros((n, d), np.float32)                               # the same events with fresh reads differ
+    oracle.run_events(Xf, dict(sched, tau=np.zeros(K, np.int32)), oracle.MODEL_LSQ, gamma, M=M, gscale=1.0 / M,
+                      features=feats, targets=targs)
+    assert _rel_err(Xf, Xr) > 1e-3
+
+    S = K // n
+    batch = np.random.default_rng([seed, 4]).integers(0, rows, size=(S, n, M)).astype(np.int32)
+    eng = P.Engine(graph, d, "lsq", M=M, gamma=gamma, n_slots=n)
+    eng.load_data(feats, targs)
+    eng.set_models(np.zeros(d, np.float32))
+    eng.run_sync_steps(S, batch, want_loss=True)
+    Xg, lg = eng.get_models(), eng.get_loss().reshape(S, n)
+    eng.close()
+    Xr = np.zeros((n, d), np.float32)
+    r = oracle.run_sync_steps(Xr, batch, oracle.metropolis_weights(graph), oracle.MODEL_LSQ, gamma, M=M, gscale=1.0 / M,
+                              features=feats, targets=targs, want_loss=True)
+    assert _rel_err(Xg, Xr) <= 1e-5
+    assert np.allclose(lg, r["loss"], rtol=2e-4, atol=1e-7)
