@@ -353,7 +353,8 @@ int adpsgd_set_event_count(adpsgd_t* h, uint64_t events);
  * neighbours of i_k, staleness tau_k (clipped to the events available in this
  * window: tau_k <= k - k_begin), and M minibatch indices drawn with replacement.
  * Integer arithmetic on a counter-based generator (Philox4x32-10) only; outputs
- * are caller-allocated host arrays (batch_idx: K*M, may be NULL when M = 0). */
+ * are caller-allocated host arrays (batch_idx: K*M, may be NULL when M = 0).
+ * The graph is validated as by adpsgd_create (ADPSGD_ERR_GRAPH), the other parameters give ADPSGD_ERR_ARG. */
 int adpsgd_make_schedule(const adpsgd_sched_params_t* p, uint64_t seed, uint64_t k_begin, int64_t K,
                          int32_t* worker, int32_t* neighbour, int32_t* tau, int32_t* batch_idx);
 

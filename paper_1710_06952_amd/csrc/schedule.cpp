@@ -97,8 +97,10 @@ extern "C" int adpsgd_make_schedule(const adpsgd_sched_params_t* p, uint64_t see
                                     int64_t K, int32_t* worker, int32_t* neighbour, int32_t* tau,
                                     int32_t* batch_idx) {
     if (!p || K < 0 || !worker || !neighbour || !tau) return ADPSGD_ERR_ARG;
+    std::string graph_err;
+    if (!graph_ok(&p->graph, graph_err)) return ADPSGD_ERR_GRAPH;   // the arrays are indexed below
     const int32_t n = p->graph.n;
-    if (n < 1 || !p->graph.rowptr || p->T_max < 0 || p->M < 0) return ADPSGD_ERR_ARG;
+    if (p->T_max < 0 || p->M < 0) return ADPSGD_ERR_ARG;
     if (p->M > 0 && (!p->rows || !batch_idx)) return ADPSGD_ERR_ARG;
     if (p->tau_mode != 0 && p->tau_mode != 1) return ADPSGD_ERR_ARG;
     if (p->tau_mode == 1 && (!p->tau_num || !p->tau_den)) return ADPSGD_ERR_ARG;

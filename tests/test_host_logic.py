@@ -63,6 +63,13 @@ def test_schedule_generator_rejects_bad_arguments():
         P.adpsgd_make_schedule(g, 10, tau_mode=1, T_max=3)          # geometric without (num, den)
     with pytest.raises(P.AdpsgdError):
         P.adpsgd_make_schedule(g, 10, weight=[0, 0, 0, 0])
+    # the graph is checked before its arrays are indexed: neighbour out of range, not symmetric, rowptr not monotone,
+    # two components
+    for rowptr, col in (([0, 2, 4, 6, 8], [3, 1, 0, 2, 1, 3, 2, 9]), ([0, 1, 1], [1]), ([0, 2, 1, 2], [1, 2, 0]),
+                        ([0, 1, 2, 3, 4], [1, 0, 3, 2])):
+        with pytest.raises(P.AdpsgdError) as ei:
+            P.adpsgd_make_schedule((np.array(rowptr, np.int32), np.array(col, np.int32)), 10)
+        assert ei.value.code == -2
 
 
 def test_create_validates_graph_and_buffers_before_touching_the_gpu():
