@@ -611,7 +611,7 @@ int oracle_run_events(int32_t n, int64_t d, float* X, int64_t ldx, int model, in
         }
 
         /* general averaging matrix: W_k may average further disjoint pairs of workers in the same
-         * event (Sec. 3.2: "W can be an arbitrary doubly stochastic matrix"); a product of disjoint
+         * event (Sec. 3.2, the generalisation of the averaging step to any doubly stochastic W_k); a product of disjoint
          * pairwise averagings is symmetric and doubly stochastic.  Those pairs carry no gradient. */
         if (extra_ptr) {
             for (int64_t q = extra_ptr[k]; q < extra_ptr[k + 1]; ++q) {
