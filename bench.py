@@ -21,6 +21,7 @@ the minibatch rows counted once.
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import re
@@ -35,17 +36,52 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 
+KERNEL_SOURCES = ("device_common.hpp", "kernels_fused.hip", "kernels_grad_linear.hip", "kernels_mlp.hip")
+
+
+def kernel_sources_sha256():
+    """Fingerprint of the kernel sources a recorded counter run belongs to."""
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_1710_06952_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def traffic_from_profiles(config=3):
-    """HBM bytes per event measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy
-    kernel of known size); kept as text under profiles/: the fused kernel of configuration 3, or all
-    kernels of an event of the data configurations 2, 4 and 5."""
+    """HBM bytes per event RECORDED from rocprofv3 --pmc runs (FETCH_SIZE and WRITE_SIZE, scaled by a copy
+    kernel of known size) and kept as text under profiles/: the fused kernel of configuration 3, or all
+    kernels of an event of the data configurations 2, 4 and 5.  Counters cannot be read inside this run, so
+    the figure is a recorded one: it is returned with the name of its file, and only when the file carries the
+    fingerprint of the kernel sources as they are now (a kernel changed since the counter run gives None)."""
     name, key = (("fused_gossip_apply_cfg3_pmc.txt", "traffic_bytes_per_event") if config == 3 else
                  ("data_configurations_hbm_traffic_pmc.txt", "traffic_bytes_per_event_cfg%d" % config))
     try:
-        m = re.search(r"^%s:\s*([0-9.eE+]+)" % key, open(os.path.join(ROOT, "profiles", name)).read(), re.M)
-        return float(m.group(1)) if m else None
+        text = open(os.path.join(ROOT, "profiles", name)).read()
     except OSError:
-        return None
+        return None, None
+    m = re.search(r"^%s:\s*([0-9.eE+]+)" % key, text, re.M)
+    sha = re.search(r"^kernel_sources_sha256:\s*([0-9a-f]+)", text, re.M)
+    if not m or not sha or sha.group(1) != kernel_sources_sha256():
+        return None, None
+    return float(m.group(1)), "profiles/" + name
+
+
+def host_description():
+    """CPU model string and core counts of the host the oracle is timed on."""
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count()
+    return {"cpu_model": model, "nproc": os.cpu_count(), "usable_cores": usable}
 
 
 def cpu_baseline_synth(cfg, schedule, events):
@@ -59,7 +95,7 @@ def cpu_baseline_synth(cfg, schedule, events):
     dt = time.perf_counter() - t0
     return {"value": events / dt, "unit": "worker updates/s", "cores": 1, "kind": "oracle",
             "sample": "first %d events of the same schedule at full size (n=%d, d=%d), %.1f s"
-                      % (events, cfg["n"], cfg["d"], dt)}
+                      % (events, cfg["n"], cfg["d"], dt), **host_description()}
 
 
 def cpu_baseline_data(cfg, schedule, events, feats, targs, x0):
@@ -80,7 +116,7 @@ def cpu_baseline_data(cfg, schedule, events, feats, targs, x0):
                       mlp=cfg.get("mlp", (0, 0, 0)), features=hf, targets=ht, mode=1)
     dt = time.perf_counter() - t0
     return {"value": events / dt, "unit": "worker updates/s", "cores": 1, "kind": "oracle",
-            "sample": "first %d events of the same schedule at full size, %.1f s" % (events, dt)}
+            "sample": "first %d events of the same schedule at full size, %.1f s" % (events, dt), **host_description()}
 
 
 def schedule_kwargs(cfg):
@@ -114,7 +150,7 @@ def main():
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--events-per-step", type=int, default=0, help="default: a tenth of the configuration's events")
     ap.add_argument("--cpu-events", type=int, default=-1,
-                    help="events the CPU oracle is timed on (0 = skip; default 16 for config 3, 0 otherwise)")
+                    help="events the CPU oracle is timed on (0 = skip; default 50 for config 3, about a minute on one core; 0 otherwise)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
     ap.add_argument("--momentum", type=float, default=0.0,
@@ -137,7 +173,7 @@ def main():
     n, d, M = cfg["n"], cfg["d"], cfg["M"]
     graph = ring_graph(n) if cfg["graph"] == "ring" else random_regular4_graph(n, cfg["seed"])
     E = args.events_per_step or max(cfg["K"] // 10, 1)
-    cpu_events = args.cpu_events if args.cpu_events >= 0 else (16 if args.config == 3 else 0)
+    cpu_events = args.cpu_events if args.cpu_events >= 0 else (50 if args.config == 3 else 0)
     synth = cfg["model"] == "synth"
     std = float(np.float32(cfg.get("synth_std", 0.0)))
 
@@ -208,10 +244,13 @@ def main():
         bytes_per_event = (24.0 if eng.V is not None else 16.0) * d   # read x_i, x_j; write x_i, x_j (+ v_i read and written)
         avg_launch_s = ps["fused_ms"] * 1e-3 / ps["fused_launches"]
         achieved = bytes_per_event * events_per_launch / avg_launch_s / 1e9
-        traffic = traffic_from_profiles()               # measured bytes per event (rocprofv3 counters) ...
-        traffic = traffic * events_per_launch if (traffic is not None and d == 25_600_000 and eng.V is None) else None   # ... per launch
+        traffic, traffic_source = traffic_from_profiles()   # recorded bytes per event (rocprofv3 counters) ...
+        if traffic is not None and d == 25_600_000 and eng.V is None:
+            traffic = traffic * events_per_launch            # ... per launch of this run
+        else:
+            traffic = traffic_source = None
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                 "kernel": "fused_gossip_apply_kernel<synth>", "avg_launch_ms": avg_launch_s * 1e3,
                 "events_per_launch": events_per_launch, "bytes_per_event": bytes_per_event}
     else:
@@ -223,9 +262,10 @@ def main():
         per_update_s = ps["fused_ms"] * 1e-3 / ps["events"]
         bytes_per_event = algorithmic_bytes_per_event(cfg)
         achieved = bytes_per_event / (per_grad_s + per_update_s) / 1e9
+        traffic, traffic_source = traffic_from_profiles(args.config) if (not args.d and eng.V is None) else (None, None)
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS,
-                "traffic": traffic_from_profiles(args.config) if (not args.d and eng.V is None) else None,   # bytes per event, as `achieved` is
+                "traffic": traffic, "traffic_source": traffic_source,   # recorded bytes per event, as `achieved` is
                 "kernel": "gradient + update kernels (per event)", "avg_gradient_us": per_grad_s * 1e6,
                 "fused_us_per_event": per_update_s * 1e6, "bytes_per_event": bytes_per_event,
                 "bytes_per_gradient": grad_rows_bytes, "events_per_launch": events_per_launch}

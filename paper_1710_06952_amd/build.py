@@ -12,6 +12,7 @@ CSRC = HERE / "csrc"
 INCLUDE = HERE.parent / "include"
 LIB = HERE / "libadpsgd.so"
 OBJ = HERE / "_build"
+STREAM_BENCH = HERE / "stream_bench"       # stand-alone streaming microbenchmarks (csrc/stream_bench.hip)
 
 SOURCES = ["api.cpp", "api_sync.cpp", "api_diag.cpp", "schedule.cpp", "planner.cpp", "kernels_fused.hip", "kernels_grad_linear.hip",
            "kernels_mlp.hip", "kernels_diag.hip", "kernels_sync.hip"]
@@ -41,15 +42,29 @@ def _compile(src: str) -> Path:
     return obj
 
 
+def _build_stream_bench() -> Path:
+    tmp = STREAM_BENCH.with_suffix(".tmp%d" % os.getpid())
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wall", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-x", "hip", str(CSRC / "stream_bench.hip"), "-o", str(tmp)]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed on stream_bench.hip:\n%s" % r.stderr)
+    os.replace(tmp, STREAM_BENCH)
+    return STREAM_BENCH
+
+
 def build(force: bool = True) -> Path:
     """Compile every source and link the shared library.  force=False skips the
     work when the library is newer than all sources."""
-    deps = [CSRC / s for s in SOURCES + HEADERS] + [INCLUDE / "adpsgd.h"]
-    if not force and LIB.exists() and all(LIB.stat().st_mtime >= p.stat().st_mtime for p in deps):
+    deps = [CSRC / s for s in SOURCES + HEADERS] + [INCLUDE / "adpsgd.h", CSRC / "stream_bench.hip"]
+    if not force and LIB.exists() and STREAM_BENCH.exists() and all(
+            min(LIB.stat().st_mtime, STREAM_BENCH.stat().st_mtime) >= p.stat().st_mtime for p in deps):
         return LIB
     OBJ.mkdir(exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + 1)) as ex:
+        bench = ex.submit(_build_stream_bench)
         objs = list(ex.map(_compile, SOURCES))
+        bench.result()
     tmp = LIB.with_suffix(".so.tmp%d" % os.getpid())
     subprocess.check_call([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(tmp), *map(str, objs)])
     os.replace(tmp, LIB)
