@@ -36,6 +36,15 @@ def _say(msg):
     print(msg, flush=True)
 
 
+V_TOL = TOL          # the momentum buffers are held to the bound of the models (measured 2e-7 ... 3e-7 on MI355X)
+
+
+def v_err(v_gpu, v_ref):
+    e = rel_err(v_gpu, v_ref)
+    _say("momentum buffers: max rel err %.3e" % e)
+    return e
+
+
 # ------------------------------------------------------------------ synthetic-gradient workload
 def test_synthetic_gradient_generator_matches_oracle(P):
     import torch
@@ -510,7 +519,7 @@ def test_least_squares_with_momentum(P):
     Xr, Vr = np.zeros((n, d), np.float32), np.zeros((n, d), np.float32)
     r = oracle.run_events(Xr, sched, oracle.MODEL_LSQ, 0.2, M=M, gscale=1.0 / M, features=feats, targets=targs,
                           momentum=0.9, weight_decay=1e-4, V=Vr, want_loss=True)
-    assert rel_err(Xg, Xr) <= TOL and rel_err(Vg, Vr) <= 5 * TOL
+    assert rel_err(Xg, Xr) <= TOL and v_err(Vg, Vr) <= V_TOL
     assert np.allclose(lg, r["loss"], rtol=2e-4, atol=1e-7)
     assert r["loss"][-50:].mean() < 0.5 * r["loss"][:50].mean()
     eng.close()
@@ -696,7 +705,7 @@ def test_waitfree_variant_with_momentum(P, model):
     kw = dict(M=M, gscale=1.0 / M, lam=lam, mlp=dims, features=feats, targets=targs, momentum=mu, weight_decay=wd)
     Xr, Vr = np.tile(x0, (n, 1)), np.zeros((n, d), np.float32)
     oracle.run_events(Xr, sched, omodel, gamma, local_compensation=True, V=Vr, **kw)
-    assert rel_err(Xg, Xr) <= tol and rel_err(Vg, Vr) <= 5 * tol
+    assert rel_err(Xg, Xr) <= tol and v_err(Vg, Vr) <= (V_TOL if tol == TOL else tol)
     Xp, Vp = np.tile(x0, (n, 1)), np.zeros((n, d), np.float32)
     oracle.run_events(Xp, sched, omodel, gamma, V=Vp, **kw)
     assert rel_err(Xg, Xp) > 3 * tol           # the compensation is not a no-op on this schedule
@@ -841,13 +850,13 @@ def test_sync_steps_with_momentum_and_weight_decay(P, model, n, d):
         tol = MLP_TOL_MASTER
     assert np.abs(Vr).max() > 0
     assert rel_err(eng.get_models(), Xr) <= tol
-    assert rel_err(eng.get_momentum(), Vr) <= 5 * tol
+    assert v_err(eng.get_momentum(), Vr) <= (V_TOL if tol == TOL else tol)
     if model == "synth":      # asynchronous events continue on the same models and buffers
         sched = oracle.make_schedule(g, 60, seed=4, T_max=2)
         eng.run_events(sched)
         oracle.run_events(Xr, sched, oracle.MODEL_SYNTH, gamma, synth_std=std, synth_seed=3, event_base=S * n,
                           momentum=mu, weight_decay=wd, V=Vr)
-        assert rel_err(eng.get_models(), Xr) <= TOL and rel_err(eng.get_momentum(), Vr) <= 5 * TOL
+        assert rel_err(eng.get_models(), Xr) <= TOL and v_err(eng.get_momentum(), Vr) <= V_TOL
     eng.close()
 
 
@@ -1026,7 +1035,7 @@ def test_external_gradients_from_pytorch_follow_algorithm_1(P):
     Xw, Vw = np.tile(x0, (n, 1)), np.zeros((n, d), np.float32)
     oracle.run_events(Xw, sched, oracle.MODEL_LSQ, 0.3, M=M, gscale=1.0 / M, features=feats, targets=targs,
                       gamma_k=sched["gamma"], local_compensation=True, momentum=0.9, weight_decay=1e-3, V=Vw)
-    assert rel_err(wf.get_models(), Xw) <= TOL and rel_err(wf.get_momentum(), Vw) <= 5 * TOL
+    assert rel_err(wf.get_models(), Xw) <= TOL and v_err(wf.get_momentum(), Vw) <= V_TOL
     Xn, Vn = np.tile(x0, (n, 1)), np.zeros((n, d), np.float32)
     oracle.run_events(Xn, sched, oracle.MODEL_LSQ, 0.3, M=M, gscale=1.0 / M, features=feats, targets=targs,
                       gamma_k=sched["gamma"], momentum=0.9, weight_decay=1e-3, V=Vn)
@@ -1049,7 +1058,7 @@ def test_external_gradients_from_pytorch_follow_algorithm_1(P):
     Xs, Vs = np.tile(x0, (n, 1)), np.zeros((n, d), np.float32)
     oracle.run_sync_steps(Xs, sync_batch, oracle.metropolis_weights(g), oracle.MODEL_LSQ, 0.3, M=M, gscale=1.0 / M,
                           features=feats, targets=targs, momentum=0.9, weight_decay=1e-3, V=Vs)
-    assert rel_err(sy.get_models(), Xs) <= TOL and rel_err(sy.get_momentum(), Vs) <= 5 * TOL
+    assert rel_err(sy.get_models(), Xs) <= TOL and v_err(sy.get_momentum(), Vs) <= V_TOL
     sy.close()
 
     calls = []
@@ -1565,4 +1574,4 @@ def test_least_squares_factored_and_dense_gradient_give_the_same_bits(P, mu, wd)
     assert rel_err(out[0][0], Xr) <= TOL
     if mu:
         assert np.array_equal(out[0][3], out[1][3])
-        assert rel_err(out[0][3], Vr) <= 5 * TOL
+        assert v_err(out[0][3], Vr) <= V_TOL
