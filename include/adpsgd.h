@@ -325,6 +325,20 @@ int adpsgd_objective_weighted(adpsgd_t* h, const float* x, const double* p, doub
  * that data into it: its objective and classification error are the test loss and test error. */
 int adpsgd_classification_error(adpsgd_t* h, const float* x, double* out);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops that
+ * watch the consensus distance between events, harnesses that forbid hipMalloc.  The same quantity and the
+ * same kernels as adpsgd_consensus_distance (p = NULL) / adpsgd_consensus_distance_weighted (p: host, n
+ * probabilities), but the block partials and the weights live in a fixed device array inside the library
+ * (49 KB per GPU, held until the process ends) instead of a buffer the library allocates, and the result goes
+ * to out_device (DEVICE memory, one double, written asynchronously on the handle's stream; the call does
+ * not wait for it).  The call allocates and frees nothing.  Limits: the partials of any d fit (the grid is
+ * capped at the array's 2048 partials); with p the handle may have at most 4096 workers, more gives
+ * ADPSGD_ERR_ARG (as do invalid weights).  With p the weights are copied from host memory on the stream,
+ * which is not something a graph capture can record: capture the p = NULL form.  All calls on one GPU share
+ * the array and the last call's contents stay in it: calls that overlap on one GPU (two streams, two
+ * threads) race, calls on one stream do not. */
+int adpsgd_consensus_distance_static(adpsgd_t* h, const double* p, double* out_device);
+
 /* Divergence check: the number of entries of the models that are NaN or infinite (0 for a healthy
  * run; a step size beyond the stability limit shows up here long before anything else fails).
  * *out is host memory.  Synchronous; reads X once. */

@@ -20,6 +20,7 @@ FLAG_PROFILE, FLAG_DENSE_GRADIENT, FLAG_VERIFY_PLAN = 1, 2, 4
 EXPORTS = [
     "adpsgd_create", "adpsgd_destroy", "adpsgd_last_error", "adpsgd_load_data", "adpsgd_set_models",
     "adpsgd_run_events", "adpsgd_run_events_with", "adpsgd_get_models", "adpsgd_get_mean_model", "adpsgd_consensus_distance", "adpsgd_consensus_distance_weighted",
+    "adpsgd_consensus_distance_static",
     "adpsgd_get_bf16_models", "adpsgd_classification_error", "adpsgd_get_momentum", "adpsgd_get_stats", "adpsgd_make_schedule", "adpsgd_plan_rounds",
     "adpsgd_synth_gradient", "adpsgd_run_sync_steps", "adpsgd_run_sync_steps_with", "adpsgd_metropolis_weights",
     "adpsgd_get_event_count", "adpsgd_set_event_count", "adpsgd_verify_plan", "adpsgd_objective", "adpsgd_objective_weighted", "adpsgd_count_nonfinite",
@@ -116,6 +117,7 @@ def lib():
         L.adpsgd_get_mean_model.argtypes = [vp, vp, i32]
         L.adpsgd_consensus_distance.argtypes = [vp, P(C.c_double)]
         L.adpsgd_consensus_distance_weighted.argtypes = [vp, P(C.c_double), P(C.c_double)]
+        L.adpsgd_consensus_distance_static.argtypes = [vp, P(C.c_double), vp]
         L.adpsgd_get_bf16_models.argtypes = [vp, vp, i64, i32]
         L.adpsgd_get_momentum.argtypes = [vp, vp, i64, i32]
         L.adpsgd_get_stats.argtypes = [vp, P(Stats)]
@@ -419,6 +421,17 @@ class Handle:
                 raise ValueError("p must have one entry per worker")
             _check(self._h, lib().adpsgd_consensus_distance_weighted(self._h, p.ctypes.data_as(C.POINTER(C.c_double)), C.byref(out)))
         return out.value
+
+    def consensus_distance_static(self, out_device_ptr, p=None):
+        """The consensus distance without any allocation by the library: the result (one double) is written to
+        the device address out_device_ptr, asynchronously on the handle's stream."""
+        pp = None
+        if p is not None:
+            p = np.ascontiguousarray(p, dtype=np.float64)
+            if p.shape != (self.n,):
+                raise ValueError("p must have one entry per worker")
+            pp = p.ctypes.data_as(C.POINTER(C.c_double))
+        _check(self._h, lib().adpsgd_consensus_distance_static(self._h, pp, out_device_ptr))
 
     def get_stats(self):
         st = Stats()

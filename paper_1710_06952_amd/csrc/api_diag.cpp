@@ -96,6 +96,36 @@ extern "C" int adpsgd_consensus_distance_weighted(adpsgd_t* h, const double* p, 
     return consensus(h, p, out);
 }
 
+extern "C" int adpsgd_consensus_distance_static(adpsgd_t* h, const double* p, double* out_device) {
+    if (!h) return ADPSGD_ERR_ARG;
+    if (!out_device) return fail(h, ADPSGD_ERR_ARG, "consensus_distance_static: out_device is NULL");
+    const int32_t blocks = consensus_blocks(h->d);
+    if (blocks > kStaticPartials)
+        return fail(h, ADPSGD_ERR_ARG, "consensus_distance_static: d needs more block partials than the fixed array holds");
+    double psum = 0.0;
+    if (p) {
+        if (h->n > kStaticWeights)
+            return fail(h, ADPSGD_ERR_ARG, "consensus_distance_static: more than " + std::to_string(kStaticWeights) +
+                                               " workers: the weights do not fit the fixed array (pass p = NULL, or use "
+                                               "adpsgd_consensus_distance_weighted)");
+        for (int32_t i = 0; i < h->n; ++i) {
+            if (!(p[i] >= 0.0) || !std::isfinite(p[i])) return fail(h, ADPSGD_ERR_ARG, "consensus_distance_static: weight negative or not finite");
+            psum += p[i];
+        }
+        if (std::fabs(psum - 1.0) > 1e-9) return fail(h, ADPSGD_ERR_ARG, "consensus_distance_static: the weights do not sum to 1");
+    }
+    double* base = nullptr;                       // the fixed array's address on this GPU
+    HIP_TRY(h, static_scratch(&base));
+    double* d_p = nullptr;
+    if (p) {
+        d_p = base + kStaticPartials + 8;
+        HIP_TRY(h, hipMemcpyAsync(d_p, p, static_cast<size_t>(h->n) * sizeof(double), hipMemcpyHostToDevice, h->stream));
+    }
+    // every partial the final kernel reads is written by this launch: nothing has to start at zero
+    HIP_TRY(h, launch_consensus(h->o.X, h->o.ldx, h->d, h->n, base, out_device, d_p, psum, h->stream));
+    return ADPSGD_OK;
+}
+
 extern "C" int adpsgd_count_nonfinite(adpsgd_t* h, int64_t* out) {
     if (!h) return ADPSGD_ERR_ARG;
     if (!out) return fail(h, ADPSGD_ERR_ARG, "count_nonfinite: out is NULL");

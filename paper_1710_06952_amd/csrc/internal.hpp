@@ -198,6 +198,11 @@ hipError_t launch_broadcast_rows(float* X, int64_t ld, int64_t d, int32_t n, con
 hipError_t launch_refresh_bf16(const float* X, uint16_t* Xb, int64_t ld, int32_t n, hipStream_t st);
 hipError_t launch_mean_model(const float* X, int64_t ld, int64_t d, int32_t n, float* out, hipStream_t st);
 int32_t consensus_blocks(int64_t d);
+// adpsgd_consensus_distance_static: capacity of the library's fixed device array (block partials, worker
+// probabilities) and its address on the current GPU (resolved on the first call per device)
+constexpr int kStaticPartials = 2048;
+constexpr int kStaticWeights = 4096;
+hipError_t static_scratch(double** out);
 // p: device, n doubles (the workers' update probabilities, psum their sum), or nullptr for the uniform weights 1 / n
 hipError_t launch_consensus(const float* X, int64_t ld, int64_t d, int32_t n, double* partial,
                             double* result, const double* p, double psum, hipStream_t st);

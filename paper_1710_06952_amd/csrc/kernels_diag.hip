@@ -2,15 +2,23 @@
 // requirement), the bf16 shadow of the master weights, the mean model (the
 // algorithm's output) and the consensus distance (1/n) sum_i |mean - x^i|^2
 // (M_k of the proofs appendix with uniform p), reduced with wavefront shuffles.
+#include <mutex>
+
 #include "device_common.hpp"
 #include "internal.hpp"
+
+// Fixed device memory for adpsgd_consensus_distance_static (the entry point for callers that cannot allocate):
+// [0, kStaticPartials) block partials, then a spare result, then kStaticWeights worker probabilities.  Every GPU the
+// library runs on holds its own copy until the process ends; host code reaches it only through the address that
+// hipGetSymbolAddress returns on that GPU (static_scratch below), never through this name.
+static __device__ __align__(256) double scratch[adpsgd_impl::kStaticPartials + 8 + adpsgd_impl::kStaticWeights];
 
 namespace adpsgd_impl {
 namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr int kConsensusBlocksMax = 2048;
+constexpr int kConsensusBlocksMax = kStaticPartials;
 constexpr int64_t kStreamBytes = 256ll << 20;   // beyond this X cannot stay in the caches
 
 // grid = (ceil(ld/4 / kThreads), n): every row <- x0 on [0, d), zero on [d, ld)
@@ -298,6 +306,27 @@ hipError_t launch_mean_model(const float* X, int64_t ld, int64_t d, int32_t n, f
 int32_t consensus_blocks(int64_t d) {
     const int64_t want = ((d + 3) / 4 + kThreads - 1) / kThreads;
     return static_cast<int32_t>(want < kConsensusBlocksMax ? (want < 1 ? 1 : want) : kConsensusBlocksMax);
+}
+
+// The device address of `scratch` on the current GPU, resolved once per device.
+hipError_t static_scratch(double** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static double* address[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!address[dev]) {
+        double* ptr = nullptr;
+        e = hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        address[dev] = ptr;
+    }
+    *out = address[dev];
+    return hipSuccess;
 }
 
 hipError_t launch_consensus(const float* X, int64_t ld, int64_t d, int32_t n, double* partial, double* result,
