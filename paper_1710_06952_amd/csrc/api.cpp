@@ -321,6 +321,10 @@ struct EventCall {
     const PairOp* d_uops = nullptr;         // the device copy
     const GradOp* d_rops = nullptr;
     const int32_t* d_batch = nullptr;
+    int32_t* batch_r = nullptr;             // perceptron: the minibatch indices again, in the order of rops ...
+    int32_t* batch_u = nullptr;             // ... and of uops (pinned staging)
+    const int32_t* d_batch_r = nullptr;
+    const int32_t* d_batch_u = nullptr;
     size_t off_coef = 0;                    // linear models: offset of the coefficients in the gradient scratch
 };
 
@@ -386,6 +390,7 @@ void fill_update(adpsgd_t* h, EventCall& c, int64_t k, std::vector<int64_t>& u_f
     const uint64_t gk = h->events_done + static_cast<uint64_t>(k);
     const int32_t ur = c.plan.u_round[k];
     const bool factors = c.factored || c.lin_factored;
+    if (c.batch_u) std::memcpy(c.batch_u + u_fill[ur] * c.M, s->batch_idx + k * static_cast<int64_t>(c.M), static_cast<size_t>(c.M) * 4);
     PairOp& u = c.uops[u_fill[ur]++];
     u.i = s->worker[k];
     u.j = s->neighbour[k];
@@ -407,6 +412,7 @@ void fill_gradient(adpsgd_t* h, EventCall& c, int64_t k, std::vector<int64_t>& r
     const adpsgd_schedule_t* s = c.s;
     const int32_t rr = c.plan.r_round[k];
     const int64_t at = r_fill[rr]++;
+    if (c.batch_r) std::memcpy(c.batch_r + at * c.M, s->batch_idx + k * static_cast<int64_t>(c.M), static_cast<size_t>(c.M) * 4);
     GradOp& g = c.rops[at];
     g.worker = s->worker[k];
     g.slot = c.plan.slot[k];
@@ -436,7 +442,12 @@ int upload_tables(adpsgd_t* h, EventCall& c) {
     const size_t bytes_r = c.with_grad ? static_cast<size_t>(K) * sizeof(GradOp) : 0;
     const size_t bytes_b = static_cast<size_t>(K) * M * sizeof(int32_t);
     const size_t off_r = bytes_u, off_b = (off_r + bytes_r + 15) & ~size_t(15);
-    const size_t total = off_b + bytes_b;
+    // the perceptron's kernels read the indices by operation instead of by event: one copy in the order of the
+    // gradient operations, one in the order of the update operations (rows of averaging-only pairs stay zero)
+    const bool by_op = h->o.model == ADPSGD_MODEL_MLP;
+    const size_t bytes_br = by_op ? bytes_b : 0, bytes_bu = by_op ? static_cast<size_t>(c.A + c.n_extra) * M * sizeof(int32_t) : 0;
+    const size_t off_br = off_b + (by_op ? 0 : bytes_b), off_bu = off_br + bytes_br;
+    const size_t total = off_bu + bytes_bu;
 
     TableSet& T = h->tables[h->next_table];
     h->next_table ^= 1;
@@ -450,17 +461,24 @@ int upload_tables(adpsgd_t* h, EventCall& c) {
     char* stage = static_cast<char*>(T.stage.p);
     c.uops = reinterpret_cast<PairOp*>(stage);
     c.rops = reinterpret_cast<GradOp*>(stage + off_r);
+    if (by_op) {
+        c.batch_r = reinterpret_cast<int32_t*>(stage + off_br);
+        c.batch_u = reinterpret_cast<int32_t*>(stage + off_bu);
+        std::memset(stage + off_br, 0, bytes_br + bytes_bu);
+    }
     std::vector<int64_t> u_fill(c.u_off.begin(), c.u_off.end() - 1), r_fill(c.r_off.begin(), c.r_off.end() - 1);
     for (int64_t k = 0; k < K; ++k) {
         if (k < c.A) fill_update(h, c, k, u_fill);
         if (c.with_grad && c.plan.r_round[k] >= 0) fill_gradient(h, c, k, r_fill);
     }
-    if (bytes_b > 0) std::memcpy(stage + off_b, s->batch_idx, bytes_b);
+    if (bytes_b > 0 && !by_op) std::memcpy(stage + off_b, s->batch_idx, bytes_b);
     HIP_TRY(h, hipMemcpyAsync(T.dev.p, T.stage.p, total, hipMemcpyHostToDevice, h->stream));
     const char* dev = static_cast<const char*>(T.dev.p);
     c.d_uops = reinterpret_cast<const PairOp*>(dev);
     c.d_rops = reinterpret_cast<const GradOp*>(dev + off_r);
     c.d_batch = reinterpret_cast<const int32_t*>(dev + off_b);
+    c.d_batch_r = reinterpret_cast<const int32_t*>(dev + off_br);
+    c.d_batch_u = reinterpret_cast<const int32_t*>(dev + off_bu);
 
     if (c.with_grad && !c.external) {
         if (h->o.model == ADPSGD_MODEL_MLP) {
@@ -527,7 +545,7 @@ int launch_gradients(adpsgd_t* h, const EventCall& c, int32_t r, float* loss, ad
             launches = 1;
         } else if (h->o.model == ADPSGD_MODEL_MLP) {
             MlpGradArgs a{h->o.X, h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, c.d_rops + g0, cnt, c.M,
-                          c.d_batch, slots, gscale, loss, h->grad_scratch.p, c.factored, c.mlp_comp};
+                          c.d_batch_r + g0 * c.M, slots, gscale, loss, h->grad_scratch.p, c.factored, c.mlp_comp};
             HIP_TRY(h, launch_mlp_gradient(a, h->stream, &launches));
         } else {
             LinearGradArgs a{h->o.model, h->o.X, h->o.ldx, h->d, c.d_rops + g0, cnt, c.M, c.d_batch, slots, gscale, h->o.lambda,
@@ -557,7 +575,7 @@ int launch_updates(adpsgd_t* h, const EventCall& c, int32_t r) {
         HIP_TRY(h, launch_linear_apply_factored(a, h->stream));
     } else if (c.factored) {
         MlpApplyArgs a{h->o.X, h->o.ldx, h->d, h->o.mlp_in, h->o.mlp_hidden, c.M, d_ops, static_cast<int32_t>(nu), slots, h->o.Xbf16,
-                       c.d_batch, h->o.V, h->o.momentum, h->o.weight_decay};
+                       c.d_batch_u + c.u_off[r] * c.M, h->o.V, h->o.momentum, h->o.weight_decay};
         HIP_TRY(h, launch_mlp_apply_factored(a, h->stream));
     } else {
         bool has_solo = false;

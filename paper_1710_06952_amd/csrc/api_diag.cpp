@@ -190,7 +190,7 @@ int mlp_objective(adpsgd_t* h, const float* x, double* out, bool count_errors, c
         const int32_t cnt = static_cast<int32_t>(std::min<int64_t>(group, n_ops - g0));
         MlpGradArgs a{nullptr, point_b16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out,
                       reinterpret_cast<const GradOp*>(base + off_ops) + g0, cnt, M,
-                      reinterpret_cast<const int32_t*>(base + off_idx), nullptr, 1.0f, nullptr, h->grad_scratch.p, false, false};
+                      reinterpret_cast<const int32_t*>(base + off_idx) + g0 * static_cast<int64_t>(M), nullptr, 1.0f, nullptr, h->grad_scratch.p, false, false};
         HIP_TRY(h, launch_mlp_loss(a, d_sum + g0, count_errors, h->stream));
     }
     std::vector<double> sums(static_cast<size_t>(n_ops));

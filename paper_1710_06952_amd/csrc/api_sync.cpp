@@ -112,6 +112,10 @@ int run_sync_steps_impl(adpsgd_t* h, const adpsgd_sync_schedule_t* s, float* los
         }
     }
     const bool profile = (h->o.flags & ADPSGD_FLAG_PROFILE) != 0;
+    // a ring in canonical order: row i mixes with rows i - 1 and i + 1 only, listed in that order
+    bool ring = n >= 3 && nnz == 2 * n;
+    for (int32_t i = 0; ring && i < n; ++i)
+        ring = h->rowptr[i] == 2 * i && h->col[2 * i] == (i + n - 1) % n && h->col[2 * i + 1] == (i + 1) % n;
     float* slots = static_cast<float*>(h->o.workspace);
     const float gscale = h->o.grad_sum ? 1.0f : 1.0f / static_cast<float>(std::max(M, 1));
     std::vector<adpsgd_grad_request_t> requests(external ? n : 0);
@@ -131,7 +135,7 @@ int run_sync_steps_impl(adpsgd_t* h, const adpsgd_sync_schedule_t* s, float* los
             int launches = 0;
             if (h->o.model == ADPSGD_MODEL_MLP) {
                 MlpGradArgs a{h->o.X, h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, d_rops + t * n + g0, cnt, M,
-                              d_batch, slots, gscale, loss,
+                              d_batch + (t * n + g0) * static_cast<int64_t>(M), slots, gscale, loss,
                               h->grad_scratch.p, false, false};
                 HIP_TRY(h, launch_mlp_gradient(a, h->stream, &launches));
             } else {
@@ -156,7 +160,7 @@ int run_sync_steps_impl(adpsgd_t* h, const adpsgd_sync_schedule_t* s, float* los
                    with_grad ? slots : nullptr, h->o.model == ADPSGD_MODEL_MLP ? h->o.Xbf16 : nullptr,
                    s->gamma ? s->gamma[t] : h->o.gamma, h->o.synth_std, h->o.synth_seed,
                    h->events_done + static_cast<uint64_t>(t) * static_cast<uint64_t>(n), !with_grad,
-                   h->o.V, h->o.momentum, h->o.weight_decay};
+                   h->o.V, h->o.momentum, h->o.weight_decay, ring};
         HIP_TRY(h, launch_sync_mix_apply(a, h->stream));
         ++h->stats.fused_launches;
         if (profile) {

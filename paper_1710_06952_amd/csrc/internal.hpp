@@ -139,7 +139,8 @@ struct MlpGradArgs {
     const GradOp* ops;
     int32_t n_ops;
     int32_t M;
-    const int32_t* batch_idx;
+    const int32_t* batch_by_op;   // device, n_ops x M: row t holds the minibatch indices of ops[t] (a kernel finds them
+                                  //   from its block index, without waiting for the operation's descriptor)
     float* slots;
     float gscale;
     float* loss;
@@ -165,7 +166,7 @@ struct MlpApplyArgs {
     int32_t n_ops;
     const float* slots;
     uint16_t* Xbf16;
-    const int32_t* batch_idx;   // device, K x M
+    const int32_t* batch_by_op; // device, n_ops x M: row t holds the minibatch indices of the event of ops[t]
     float* V;                   // momentum buffers or nullptr
     float momentum, weight_decay;
 };
@@ -190,6 +191,7 @@ struct SyncArgs {
     bool synth;
     float* V;                // momentum buffers or nullptr
     float momentum, weight_decay;
+    bool ring;               // the graph is a ring with neighbour lists (i - 1, i + 1) mod n, n >= 3: no LDS staging needed
 };
 int32_t sync_tile_cols(int32_t n);   // 0: n too large for the in-place mixing kernel
 hipError_t launch_sync_mix_apply(const SyncArgs& a, hipStream_t st);

@@ -42,26 +42,31 @@ __global__ __launch_bounds__(kThreads) void refresh_bf16_kernel(const float* X, 
 }
 
 constexpr int kRowBatch = 8;   // rows whose loads are in flight together (4 and 16 measure the same)
+constexpr int kMeanBlocksMax = 4096;
 
-// one thread per float4 of d: column sums over the n rows in a fixed order
+// column means over the n rows in a fixed order, fp64 accumulation; a thread takes one float4 of d at a time and
+// the grid strides over d (a capped grid of 4096 blocks walks the rows in step and reads 6.25 TB/s at n = 128,
+// d = 25.6 M, against 6.0 TB/s for one thread per float4 and 3.7 TB/s for dword accesses)
 // STREAM: X does not fit the caches and is read once: non-temporal loads
 template <bool STREAM>
 __global__ __launch_bounds__(kThreads) void mean_model_kernel(const float* X, int64_t ld, int64_t d, int32_t n, float* out) {
-    const int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-    if (4 * v >= d) return;
-    double s[4] = {0, 0, 0, 0};
-    for (int32_t i0 = 0; i0 < n; i0 += kRowBatch) {
-        v4f x[kRowBatch];
+    const int64_t n_vec = (d + 3) / 4;
+    for (int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; v < n_vec;
+         v += static_cast<int64_t>(gridDim.x) * kThreads) {
+        double s[4] = {0, 0, 0, 0};
+        for (int32_t i0 = 0; i0 < n; i0 += kRowBatch) {
+            v4f x[kRowBatch];
 #pragma unroll
-        for (int r = 0; r < kRowBatch; ++r)
-            x[r] = i0 + r < n ? load4<STREAM>(X + static_cast<int64_t>(i0 + r) * ld + 4 * v) : v4f{0, 0, 0, 0};
+            for (int r = 0; r < kRowBatch; ++r)
+                x[r] = i0 + r < n ? load4<STREAM>(X + static_cast<int64_t>(i0 + r) * ld + 4 * v) : v4f{0, 0, 0, 0};
 #pragma unroll
-        for (int r = 0; r < kRowBatch; ++r) {
-            s[0] += x[r].x; s[1] += x[r].y; s[2] += x[r].z; s[3] += x[r].w;
+            for (int r = 0; r < kRowBatch; ++r) {
+                s[0] += x[r].x; s[1] += x[r].y; s[2] += x[r].z; s[3] += x[r].w;
+            }
         }
+        for (int c = 0; c < 4; ++c)
+            if (4 * v + c < d) out[4 * v + c] = static_cast<float>(s[c] / n);
     }
-    for (int c = 0; c < 4; ++c)
-        if (4 * v + c < d) out[4 * v + c] = static_cast<float>(s[c] / n);
 }
 
 // Per column e: sum_i (x_i - mean)^2 = sum_i t_i^2 - (sum_i t_i)^2 / n with t_i = x_i - x_0
@@ -245,6 +250,14 @@ __global__ __launch_bounds__(kThreads) void compensated_rows_kernel(const float*
 
 }  // namespace
 
+// Grid of at most `cap` blocks striding over `work` block-sized pieces such that every block gets the same number of
+// them (up to one): the last pass is then as full as the others.
+static int64_t balanced_grid(int64_t work, int64_t cap) {
+    if (work < 1) return 1;
+    const int64_t passes = (work + cap - 1) / cap;
+    return (work + passes - 1) / passes;
+}
+
 hipError_t launch_compensated_rows(const float* X, int64_t ld, const GradOp* ops, int32_t n_ops, const float* slots, float* out,
                                    hipStream_t st) {
     const int64_t blocks = (ld / 4 + kThreads - 1) / kThreads;
@@ -294,8 +307,7 @@ hipError_t launch_refresh_bf16(const float* X, uint16_t* Xb, int64_t ld, int32_t
 }
 
 hipError_t launch_mean_model(const float* X, int64_t ld, int64_t d, int32_t n, float* out, hipStream_t st) {
-    const int64_t blocks = ((d + 3) / 4 + kThreads - 1) / kThreads;
-    if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const int64_t blocks = balanced_grid(((d + 3) / 4 + kThreads - 1) / kThreads, kMeanBlocksMax);
     if (static_cast<int64_t>(n) * ld * 4 > kStreamBytes)
         hipLaunchKernelGGL(mean_model_kernel<true>, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, st, X, ld, d, n, out);
     else
@@ -304,8 +316,7 @@ hipError_t launch_mean_model(const float* X, int64_t ld, int64_t d, int32_t n, f
 }
 
 int32_t consensus_blocks(int64_t d) {
-    const int64_t want = ((d + 3) / 4 + kThreads - 1) / kThreads;
-    return static_cast<int32_t>(want < kConsensusBlocksMax ? (want < 1 ? 1 : want) : kConsensusBlocksMax);
+    return static_cast<int32_t>(balanced_grid(((d + 3) / 4 + kThreads - 1) / kThreads, kConsensusBlocksMax));
 }
 
 // The device address of `scratch` on the current GPU, resolved once per device.

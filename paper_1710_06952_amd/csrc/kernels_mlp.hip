@@ -39,7 +39,7 @@ struct MlpParams {
     int in, hid, out;
     const GradOp* ops;
     int M;
-    const int32_t* batch_idx;
+    const int32_t* batch_by_op;   // [op][M] minibatch indices, in the order of ops
     float* slots;
     float gscale;
     float* loss;
@@ -48,7 +48,20 @@ struct MlpParams {
     int factored;    // dH goes to the start of the operation's pending slot instead (and stays there
                      // until the update kernel multiplies it with the inputs)
     float* logit_part;  // [op][hid / 32][kMaxM][kMaxOut]  second-layer products of one forward tile
+    // Left by the forward kernel for the one that follows, so that its loads depend on nothing but its block index
+    // (a kernel of this chain is a few memory round trips long; each dependent load it sheds is one of them):
+    int32_t* labels;    // [op][kMaxM]  class of every sample of the minibatch, -1 beyond M
+    float* W2f;         // [op][hid][kMaxOut]  the second layer's weights as fp32, zero beyond `out`
+    float* b2f;         // [op][kMaxOut]
 };
+
+// all lanes of a wavefront have finished their LDS accesses before any of them goes on (LDS operations of one
+// wavefront execute in order; this only keeps the compiler from moving accesses across)
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 __device__ __forceinline__ v4f mfma_bf16(v8h a, v8h b, v4f c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
@@ -79,8 +92,10 @@ __global__ __launch_bounds__(kT) void mlp_compensated_rows_kernel(const MlpParam
     *reinterpret_cast<v4h*>(dst) = v4h{bf16_rne(c.x), bf16_rne(c.y), bf16_rne(c.z), bf16_rne(c.w)};
 }
 
-// ---- 1. forward: H = relu(Xb W1 + b1), grid = (hid / 32, n_ops) ----------------------
-// One block (512 threads) owns a 64 (minibatch) x 32 (hidden) tile of H.  The contraction over
+// ---- 1. forward: H = relu(Xb W1 + b1), grid = (hid / 32, n_ops, ceil(M / 32)) ----------------------
+// One block (512 threads) owns a 32 (minibatch) x 32 (hidden) tile of H (two blocks share a weight tile when the
+// minibatch has more than 32 samples: a block then pulls 100 KB of operands through its compute unit instead
+// of 150 KB, a round of four gradients fills the chip, and the two land on the same XCD).  The contraction over
 // the input features is split across the eight wavefronts (k-steps of 32, step s goes to
 // wavefront s % 8), each with its own transposed W1 tile in LDS; the operands of up to kFwdDepth
 // steps of a wavefront (all of them for 784 inputs) are requested before the first MFMA, so the
@@ -95,20 +110,25 @@ constexpr int kFwdTileH = 32;
 constexpr int kFwdT = 512;
 constexpr int kFwdWaves = kFwdT / 64;
 constexpr int kFwdDepth = 4;
+constexpr int kFwdMT = 2;                  // 16-row minibatch tiles per block
+constexpr int kFwdRows = 16 * kFwdMT;      // minibatch rows per block
+constexpr int kFwdElems = kFwdMT * 2 * 4;  // accumulator elements per lane: (mt, ht, v)
 
 struct FwdOperands {
-    v8h w[2];   // W1 tile 32 (k) x 32 (h): lane holds 2 rows k, 8 columns each
-    v8h a[4];   // input fragments of the four 16-row minibatch tiles
+    v8h w[2];        // W1 tile 32 (k) x 32 (h): lane holds 2 rows k, 8 columns each
+    v8h a[kFwdMT];   // input fragments of the block's 16-row minibatch tiles
 };
 
 __global__ __launch_bounds__(kFwdT) void mlp_forward_kernel(const MlpParams p) {
-    // per-wavefront W1 tiles during the contraction (8 x 2560 B), then four partial tiles (4 x 8 KiB)
-    __shared__ __attribute__((aligned(16))) unsigned char smem[32768];
+    // per-wavefront W1 tiles during the contraction (8 x 2560 B), then four partial tiles (4 x 4 KiB)
+    __shared__ __attribute__((aligned(16))) unsigned char smem[8 * kFwdTileH * 40 * 2];
     __shared__ float W2s[kFwdTileH][kMaxOut];     // this tile's rows of W2, zero beyond `out`
-    __shared__ float Hs[kMaxM][kFwdTileH + 1];     // the finished tile, as the next layer sees it
+    __shared__ float Hs[kFwdRows][kFwdTileH + 1];  // the finished tile, as the next layer sees it
+    const int m0 = kFwdRows * blockIdx.z;          // first minibatch row of this block
+    const bool first_rows = blockIdx.z == 0;       // this block also leaves what does not depend on the rows
     const GradOp op = p.ops[blockIdx.y];
     const uint16_t* __restrict__ feat = static_cast<const uint16_t*>(op.features);
-    const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
+    const int32_t* __restrict__ idx = p.batch_by_op + static_cast<int64_t>(blockIdx.y) * p.M;   // independent of op
     const uint16_t* __restrict__ W1 = op.xrow_bf16 ? static_cast<const uint16_t*>(op.xrow_bf16)
                                                    : p.Xb + static_cast<int64_t>(op.worker) * p.ld;
     const uint16_t* __restrict__ b1 = W1 + static_cast<int64_t>(p.in) * p.hid;
@@ -122,20 +142,27 @@ __global__ __launch_bounds__(kFwdT) void mlp_forward_kernel(const MlpParams p) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int li = lane & 15, kb = 8 * (lane >> 4);
     // small operands of the epilogue, requested now and used after the contraction
-    uint16_t w2raw;
+    uint16_t w2raw, b2raw = 0;
+    int32_t label = -1;
     const uint16_t b1raw = b1[h0 + 16 * ((wave >> 2) & 1) + li];   // bias of the hidden unit this thread finishes
     {
         const uint16_t* __restrict__ W2 = b1 + p.hid;
         const int hh = threadIdx.x / kMaxOut, o = threadIdx.x % kMaxOut;     // 512 = 32 x 16
         w2raw = o < p.out ? W2[static_cast<int64_t>(h0 + hh) * p.out + o] : static_cast<uint16_t>(0);
+        if (tile == 0 && first_rows) {   // one block also leaves the labels and the output bias for the next kernel
+            if (threadIdx.x < kMaxM && static_cast<int>(threadIdx.x) < p.M)
+                label = static_cast<const int32_t*>(op.targets)[idx[threadIdx.x]];
+            if (threadIdx.x < kMaxOut && static_cast<int>(threadIdx.x) < p.out)
+                b2raw = W2[static_cast<int64_t>(p.hid) * p.out + threadIdx.x];
+        }
     }
     uint16_t(*Bt)[40] = reinterpret_cast<uint16_t(*)[40]>(smem + wave * (kFwdTileH * 40 * 2));   // [h][k]
     float* red = reinterpret_cast<float*>(smem);
 
-    const uint16_t* rowp[4];
+    const uint16_t* rowp[kFwdMT];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
-        const int m = 16 * mt + li;
+    for (int mt = 0; mt < kFwdMT; ++mt) {
+        const int m = m0 + 16 * mt + li;
         rowp[mt] = m < p.M ? feat + static_cast<int64_t>(idx[m]) * op.ld : nullptr;
     }
     const int skk = lane >> 2, shh = (lane & 3) * 8;   // staging role inside the wavefront
@@ -148,13 +175,13 @@ __global__ __launch_bounds__(kFwdT) void mlp_forward_kernel(const MlpParams p) {
             f.w[r] = k < p.in ? *reinterpret_cast<const v8h*>(W1 + static_cast<int64_t>(k) * p.hid + h0 + shh) : zero;
         }
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+        for (int mt = 0; mt < kFwdMT; ++mt)
             f.a[mt] = (rowp[mt] && k0 + kb < p.in) ? *reinterpret_cast<const v8h*>(rowp[mt] + k0 + kb) : zero;
     };
 
-    v4f acc[4][2];
+    v4f acc[kFwdMT][2];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+    for (int mt = 0; mt < kFwdMT; ++mt)
 #pragma unroll
         for (int ht = 0; ht < 2; ++ht) acc[mt][ht] = v4f{0, 0, 0, 0};
 
@@ -171,50 +198,59 @@ __global__ __launch_bounds__(kFwdT) void mlp_forward_kernel(const MlpParams p) {
                 for (int r = 0; r < 2; ++r)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) Bt[shh + e][skk + 16 * r] = f[u].w[r][e];
-                __syncthreads();
+                wave_lds_sync();      // the tile is this wavefront's own: no other wavefront has to wait
                 v8h bfrag[2];
 #pragma unroll
                 for (int ht = 0; ht < 2; ++ht) bfrag[ht] = *reinterpret_cast<const v8h*>(&Bt[16 * ht + li][kb]);
 #pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
+                for (int mt = 0; mt < kFwdMT; ++mt)
 #pragma unroll
                     for (int ht = 0; ht < 2; ++ht) acc[mt][ht] = mfma_bf16(f[u].a[mt], bfrag[ht], acc[mt][ht]);
-                __syncthreads();
+                wave_lds_sync();
             }
         }
     }
-    W2s[threadIdx.x / kMaxOut][threadIdx.x % kMaxOut] = bf16_to_float(w2raw);
+    {
+        const float w2 = bf16_to_float(w2raw);
+        W2s[threadIdx.x / kMaxOut][threadIdx.x % kMaxOut] = w2;
+        if (first_rows) p.W2f[(static_cast<int64_t>(blockIdx.y) * p.hid + h0) * kMaxOut + threadIdx.x] = w2;     // 32 x 16 floats, contiguous
+        if (tile == 0 && first_rows) {
+            if (threadIdx.x < kMaxM) p.labels[static_cast<int64_t>(blockIdx.y) * kMaxM + threadIdx.x] = label;
+            if (threadIdx.x < kMaxOut) p.b2f[static_cast<int64_t>(blockIdx.y) * kMaxOut + threadIdx.x] = bf16_to_float(b2raw);
+        }
+    }
+    __syncthreads();      // the partial tiles below reuse the memory of the wavefronts' weight tiles
 
-    // element q = (mt, ht, v) of lane l of partial tile w at red[(w * 32 + q) * 64 + l]
+    // element q = (mt, ht, v) of lane l of partial tile w at red[(w * kFwdElems + q) * 64 + l]
     auto spill = [&](int w) {
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+        for (int mt = 0; mt < kFwdMT; ++mt)
 #pragma unroll
             for (int ht = 0; ht < 2; ++ht)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) red[(w * 32 + (mt * 2 + ht) * 4 + v) * 64 + lane] = acc[mt][ht][v];
+                for (int v = 0; v < 4; ++v) red[(w * kFwdElems + (mt * 2 + ht) * 4 + v) * 64 + lane] = acc[mt][ht][v];
     };
     if (wave >= 4) spill(wave - 4);
     __syncthreads();
     if (wave < 4) {
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+        for (int mt = 0; mt < kFwdMT; ++mt)
 #pragma unroll
             for (int ht = 0; ht < 2; ++ht)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) acc[mt][ht][v] += red[((wave * 32) + (mt * 2 + ht) * 4 + v) * 64 + lane];
+                for (int v = 0; v < 4; ++v) acc[mt][ht][v] += red[((wave * kFwdElems) + (mt * 2 + ht) * 4 + v) * 64 + lane];
     }
     __syncthreads();
     if (wave < 4) spill(wave);
     __syncthreads();
-    // every thread finishes four elements: q = wave + 8 j
+    // every thread finishes kFwdElems / 8 elements: q = wave + 8 j
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < kFwdElems / kFwdWaves; ++j) {
         const int q = wave + kFwdWaves * j;
-        const float sum = ((red[(0 * 32 + q) * 64 + lane] + red[(1 * 32 + q) * 64 + lane]) + red[(2 * 32 + q) * 64 + lane]) +
-                          red[(3 * 32 + q) * 64 + lane];
+        const float sum = ((red[(0 * kFwdElems + q) * 64 + lane] + red[(1 * kFwdElems + q) * 64 + lane]) +
+                           red[(2 * kFwdElems + q) * 64 + lane]) + red[(3 * kFwdElems + q) * 64 + lane];
         const int mt = q >> 3, ht = (q >> 2) & 1, v = q & 3;
-        const int m = 16 * mt + 4 * (lane >> 4) + v, hh = 16 * ht + li;
+        const int ml = 16 * mt + 4 * (lane >> 4) + v, m = m0 + ml, hh = 16 * ht + li;    // row inside the block, and of the minibatch
         float hval = 0.0f;
         if (m < p.M) {
             const float pre = sum + bf16_to_float(b1raw);
@@ -222,22 +258,16 @@ __global__ __launch_bounds__(kFwdT) void mlp_forward_kernel(const MlpParams p) {
             p.Hb[(static_cast<int64_t>(blockIdx.y) * kMaxM + m) * p.hid + h0 + hh] = hb;
             hval = bf16_to_float(hb);
         }
-        Hs[m][hh] = hval;
+        Hs[ml][hh] = hval;
     }
     __syncthreads();
-    // this tile's share of the logits: thread (m, op) sums over the 32 hidden units in order
+    // this tile's share of the logits: thread (m, o) sums over the 32 hidden units in order
     {
-        const int m = threadIdx.x >> 3, o2 = threadIdx.x & 7;
-        float part[2] = {0.0f, 0.0f};
+        const int ml = threadIdx.x >> 4, o = threadIdx.x & 15;       // 512 = 32 rows x 16 outputs
+        float part = 0.0f;
 #pragma unroll 8
-        for (int hh = 0; hh < kFwdTileH; ++hh) {
-            const float hv = Hs[m][hh];
-#pragma unroll
-            for (int q = 0; q < 2; ++q) part[q] += hv * W2s[hh][o2 + 8 * q];
-        }
-        float* __restrict__ dst = p.logit_part + ((static_cast<int64_t>(blockIdx.y) * gridDim.x + tile) * kMaxM + m) * kMaxOut;
-#pragma unroll
-        for (int q = 0; q < 2; ++q) dst[o2 + 8 * q] = part[q];
+        for (int hh = 0; hh < kFwdTileH; ++hh) part += Hs[ml][hh] * W2s[hh][o];
+        p.logit_part[((static_cast<int64_t>(blockIdx.y) * gridDim.x + tile) * kMaxM + m0 + ml) * kMaxOut + o] = part;
     }
 }
 
@@ -259,31 +289,29 @@ __global__ __launch_bounds__(kBwdT) void mlp_backward_small_kernel(const MlpPara
     __shared__ __attribute__((aligned(16))) float dl_s[kMaxM][kMaxOut];   // softmax - onehot, zero beyond M and out
     __shared__ float loss_s[kMaxM];
     __shared__ float red[kBwdGroups / 2][kMaxOut + 1][64];
-    const GradOp op = p.ops[blockIdx.y];
-    const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
+    const GradOp op = p.ops[blockIdx.y];     // needed for the stores only: no load below waits for it
     uint16_t* __restrict__ dH = p.factored ? reinterpret_cast<uint16_t*>(p.slots + static_cast<int64_t>(op.slot) * p.ld)
                                            : p.dHb + static_cast<int64_t>(blockIdx.y) * kMaxM * p.hid;
     const int hl = threadIdx.x & 63, mg = threadIdx.x >> 6;
     const int h = blockIdx.x * 64 + hl;
     const int sm = threadIdx.x >> 4, so = threadIdx.x & 15;       // step a: sample and logit
-    const uint16_t* __restrict__ W = op.xrow_bf16 ? static_cast<const uint16_t*>(op.xrow_bf16)
-                                                  : p.Xb + static_cast<int64_t>(op.worker) * p.ld;
-    const uint16_t* __restrict__ W2 = W + static_cast<int64_t>(p.in) * p.hid + p.hid;
-    const uint16_t* __restrict__ b2 = W2 + static_cast<int64_t>(p.hid) * p.out;
 
-    // ---- all global loads
-    int label = -1;
-    if (sm < p.M) label = static_cast<const int32_t*>(op.targets)[idx[sm]];
+    // ---- all global loads (everything the forward kernel left in the scratch memory, addressed by block index)
+    const int label = p.labels[static_cast<int64_t>(blockIdx.y) * kMaxM + sm];      // -1 beyond M
     const int tiles = p.hid / kFwdTileH;
     const float* __restrict__ src = p.logit_part + (static_cast<int64_t>(blockIdx.y) * tiles * kMaxM + sm) * kMaxOut + so;
     constexpr int kTileBatch = 32;
     float part[kTileBatch];
 #pragma unroll
     for (int t = 0; t < kTileBatch; ++t) part[t] = t < tiles ? src[static_cast<int64_t>(t) * kMaxM * kMaxOut] : 0.0f;
-    const uint16_t b2raw = so < p.out ? b2[so] : static_cast<uint16_t>(0);
-    uint16_t w2raw[kMaxOut], hraw[kBwdRows];
+    const float b2v = p.b2f[static_cast<int64_t>(blockIdx.y) * kMaxOut + so];         // zero beyond `out`
+    v4f w2q[kMaxOut / 4];
+    uint16_t hraw[kBwdRows];
+    {
+        const v4f* __restrict__ w2p = reinterpret_cast<const v4f*>(p.W2f + (static_cast<int64_t>(blockIdx.y) * p.hid + h) * kMaxOut);
 #pragma unroll
-    for (int o = 0; o < kMaxOut; ++o) w2raw[o] = o < p.out ? W2[static_cast<int64_t>(h) * p.out + o] : static_cast<uint16_t>(0);
+        for (int q = 0; q < kMaxOut / 4; ++q) w2q[q] = w2p[q];
+    }
 #pragma unroll
     for (int r = 0; r < kBwdRows; ++r) {
         const int m = kBwdRows * mg + r;
@@ -302,7 +330,7 @@ __global__ __launch_bounds__(kBwdT) void mlp_backward_small_kernel(const MlpPara
             for (int t = 0; t < kTileBatch; ++t) z += part[t];
         }
         const bool live = so < p.out;
-        const float logit = live ? z + bf16_to_float(b2raw) : -INFINITY;
+        const float logit = live ? z + b2v : -INFINITY;
         float zmax = logit;
 #pragma unroll
         for (int off = 8; off > 0; off >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, off, 64));
@@ -324,10 +352,11 @@ __global__ __launch_bounds__(kBwdT) void mlp_backward_small_kernel(const MlpPara
     float* __restrict__ gb2 = gW2 + static_cast<int64_t>(p.hid) * p.out;
     float w2[kMaxOut], gw2[kMaxOut];
 #pragma unroll
-    for (int o = 0; o < kMaxOut; ++o) {
-        w2[o] = bf16_to_float(w2raw[o]);
-        gw2[o] = 0.0f;
+    for (int q = 0; q < kMaxOut / 4; ++q) {
+        w2[4 * q] = w2q[q].x; w2[4 * q + 1] = w2q[q].y; w2[4 * q + 2] = w2q[q].z; w2[4 * q + 3] = w2q[q].w;
     }
+#pragma unroll
+    for (int o = 0; o < kMaxOut; ++o) gw2[o] = 0.0f;
     float sum_dh = 0.0f;
 #pragma unroll
     for (int r = 0; r < kBwdRows; ++r) {
@@ -391,13 +420,8 @@ __global__ __launch_bounds__(kBwdT) void mlp_backward_small_kernel(const MlpPara
 __global__ __launch_bounds__(kBwdT) void mlp_loss_kernel(const MlpParams p, double* loss_sum, int count_errors) {
     __shared__ float loss_s[kMaxM];
     const GradOp op = p.ops[blockIdx.x];
-    const int32_t* __restrict__ idx = p.batch_idx + static_cast<int64_t>(op.event) * p.M;
     const int sm = threadIdx.x >> 4, so = threadIdx.x & 15;
-    const uint16_t* __restrict__ W = op.xrow_bf16 ? static_cast<const uint16_t*>(op.xrow_bf16)
-                                                  : p.Xb + static_cast<int64_t>(op.worker) * p.ld;
-    const uint16_t* __restrict__ b2 = W + static_cast<int64_t>(p.in) * p.hid + p.hid + static_cast<int64_t>(p.hid) * p.out;
-    int label = -1;
-    if (sm < p.M) label = static_cast<const int32_t*>(op.targets)[idx[sm]];
+    const int label = p.labels[static_cast<int64_t>(blockIdx.x) * kMaxM + sm];       // left by the forward kernel, -1 beyond M
     const int tiles = p.hid / kFwdTileH;
     const float* __restrict__ src = p.logit_part + (static_cast<int64_t>(blockIdx.x) * tiles * kMaxM + sm) * kMaxOut + so;
     float z = 0.0f;
@@ -409,7 +433,7 @@ __global__ __launch_bounds__(kBwdT) void mlp_loss_kernel(const MlpParams p, doub
         for (int t = 0; t < 32; ++t) z += part[t];
     }
     const bool live = so < p.out;
-    const float logit = live ? z + bf16_to_float(b2[live ? so : 0]) : -INFINITY;
+    const float logit = live ? z + p.b2f[static_cast<int64_t>(blockIdx.x) * kMaxOut + so] : -INFINITY;
     float zmax = logit;
 #pragma unroll
     for (int off = 8; off > 0; off >>= 1) zmax = fmaxf(zmax, __shfl_xor(zmax, off, 64));
@@ -477,7 +501,7 @@ __global__ __launch_bounds__(kT) void mlp_dw1_kernel(const MlpParams p) {
     const GradOp op = p.ops[blockIdx.z];
     const int h0 = blockIdx.x * kTileH, i0 = blockIdx.y * 64;
     v4f acc[4];
-    dw1_tile(static_cast<const uint16_t*>(op.features), op.ld, p.batch_idx + static_cast<int64_t>(op.event) * p.M, p.M, p.in,
+    dw1_tile(static_cast<const uint16_t*>(op.features), op.ld, p.batch_by_op + static_cast<int64_t>(blockIdx.z) * p.M, p.M, p.in,
              p.dHb + static_cast<int64_t>(blockIdx.z) * kMaxM * p.hid, p.hid, h0, i0, At, Bt, acc);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     float* __restrict__ g = p.slots + static_cast<int64_t>(op.slot) * p.ld;
@@ -509,7 +533,7 @@ struct MlpApplyParams {
     const PairOp* ops;
     const float* slots;
     uint16_t* Xbf16;
-    const int32_t* batch_idx;
+    const int32_t* batch_by_op;   // [op][M]
     float* V;                // momentum buffers (MOM), else nullptr
     float momentum, weight_decay;
 };
@@ -599,7 +623,7 @@ __global__ __launch_bounds__(kT) void mlp_apply_factored_kernel(const MlpApplyPa
     }
     if (!average_only) {                  // uniform over the block
         v4f acc[4];
-        dw1_tile(static_cast<const uint16_t*>(op.features), op.feat_ld, p.batch_idx + static_cast<int64_t>(op.event) * p.M, p.M,
+        dw1_tile(static_cast<const uint16_t*>(op.features), op.feat_ld, p.batch_by_op + static_cast<int64_t>(blockIdx.z) * p.M, p.M,
                  p.in, reinterpret_cast<const uint16_t*>(slot), p.hid, h0, i0, At, Bt, acc);
         const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
@@ -620,14 +644,39 @@ __global__ __launch_bounds__(kT) void mlp_apply_factored_kernel(const MlpApplyPa
 
 size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
+// scratch memory of a launch group: [Hb][dHb][logit_part][W2f][labels][b2f]
+struct ScratchLayout {
+    size_t dHb, logit_part, W2f, labels, b2f, total;
+};
+ScratchLayout scratch_layout(int32_t n_ops, int32_t hid) {
+    const size_t ops = static_cast<size_t>(n_ops);
+    const size_t act = align256(ops * kMaxM * hid * sizeof(uint16_t));
+    ScratchLayout L;
+    L.dHb = act;
+    L.logit_part = 2 * act;
+    L.W2f = L.logit_part + align256(ops * (hid / kFwdTileH) * kMaxM * kMaxOut * 4);
+    L.labels = L.W2f + align256(ops * hid * kMaxOut * 4);
+    L.b2f = L.labels + align256(ops * kMaxM * 4);
+    L.total = L.b2f + align256(ops * kMaxOut * 4);
+    return L;
+}
+void set_scratch(MlpParams& p, void* scratch, int32_t n_ops, int32_t hid) {
+    const ScratchLayout L = scratch_layout(n_ops, hid);
+    char* s = static_cast<char*>(scratch);
+    p.Hb = reinterpret_cast<uint16_t*>(s);
+    p.dHb = reinterpret_cast<uint16_t*>(s + L.dHb);
+    p.logit_part = reinterpret_cast<float*>(s + L.logit_part);
+    p.W2f = reinterpret_cast<float*>(s + L.W2f);
+    p.labels = reinterpret_cast<int32_t*>(s + L.labels);
+    p.b2f = reinterpret_cast<float*>(s + L.b2f);
+}
+
 }  // namespace
 
 size_t mlp_scratch_bytes(int32_t n_ops, int32_t M, int32_t in, int32_t hid, int32_t out) {
     if (n_ops < 1 || M < 1 || M > kMaxM || in < 8 || (in & 7) || hid < kTileH || (hid % kTileH) || out < 1 || out > kMaxOut)
         return 0;
-    const size_t act = align256(static_cast<size_t>(n_ops) * kMaxM * hid * sizeof(uint16_t));
-    const size_t lp = align256(static_cast<size_t>(n_ops) * (hid / kFwdTileH) * kMaxM * kMaxOut * 4);
-    return 2 * act + lp;
+    return scratch_layout(n_ops, hid).total;
 }
 
 hipError_t launch_mlp_loss(const MlpGradArgs& a, double* loss_sum, bool count_errors, hipStream_t st) {
@@ -642,16 +691,12 @@ hipError_t launch_mlp_loss(const MlpGradArgs& a, double* loss_sum, bool count_er
     p.out = a.out;
     p.ops = a.ops;
     p.M = a.M;
-    p.batch_idx = a.batch_idx;
+    p.batch_by_op = a.batch_by_op;
     p.slots = a.slots;
     p.gscale = a.gscale;
     p.loss = nullptr;
-    char* s = static_cast<char*>(a.scratch);
-    const size_t act = align256(static_cast<size_t>(a.n_ops) * kMaxM * a.hid * sizeof(uint16_t));
-    p.Hb = reinterpret_cast<uint16_t*>(s);
-    p.dHb = reinterpret_cast<uint16_t*>(s + act);
-    p.logit_part = reinterpret_cast<float*>(s + 2 * act);
-    hipLaunchKernelGGL(mlp_forward_kernel, dim3(a.hid / kFwdTileH, a.n_ops), dim3(kFwdT), 0, st, p);
+    set_scratch(p, a.scratch, a.n_ops, a.hid);
+    hipLaunchKernelGGL(mlp_forward_kernel, dim3(a.hid / kFwdTileH, a.n_ops, (a.M + kFwdRows - 1) / kFwdRows), dim3(kFwdT), 0, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(mlp_loss_kernel, dim3(a.n_ops), dim3(kBwdT), 0, st, p, loss_sum, count_errors ? 1 : 0);
@@ -676,7 +721,7 @@ hipError_t launch_mlp_apply_factored(const MlpApplyArgs& a, hipStream_t st) {
     p.ops = a.ops;
     p.slots = a.slots;
     p.Xbf16 = a.Xbf16;
-    p.batch_idx = a.batch_idx;
+    p.batch_by_op = a.batch_by_op;
     p.V = a.V;
     p.momentum = a.momentum;
     p.weight_decay = a.weight_decay;
@@ -704,17 +749,13 @@ hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_laun
     p.out = a.out;
     p.ops = a.ops;
     p.M = a.M;
-    p.batch_idx = a.batch_idx;
+    p.batch_by_op = a.batch_by_op;
     p.slots = a.slots;
     p.gscale = a.gscale;
     p.loss = a.loss;
     p.factored = a.factored ? 1 : 0;
     if (a.factored && !mlp_can_factor(a.in, a.hid, a.M)) return hipErrorInvalidValue;
-    char* s = static_cast<char*>(a.scratch);
-    const size_t act = align256(static_cast<size_t>(a.n_ops) * kMaxM * a.hid * sizeof(uint16_t));
-    p.Hb = reinterpret_cast<uint16_t*>(s);
-    p.dHb = reinterpret_cast<uint16_t*>(s + act);
-    p.logit_part = reinterpret_cast<float*>(s + 2 * act);
+    set_scratch(p, a.scratch, a.n_ops, a.hid);
     const uint32_t hb = static_cast<uint32_t>(a.hid / kTileH);
     if (a.compensate) {
         if (!a.X || a.factored) return hipErrorInvalidValue;
@@ -724,7 +765,7 @@ hipError_t launch_mlp_gradient(const MlpGradArgs& a, hipStream_t st, int* n_laun
         if (ec != hipSuccess) return ec;
         if (n_launches) *n_launches += 1;
     }
-    hipLaunchKernelGGL(mlp_forward_kernel, dim3(a.hid / kFwdTileH, a.n_ops), dim3(kFwdT), 0, st, p);
+    hipLaunchKernelGGL(mlp_forward_kernel, dim3(a.hid / kFwdTileH, a.n_ops, (a.M + kFwdRows - 1) / kFwdRows), dim3(kFwdT), 0, st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(mlp_backward_small_kernel, dim3(a.hid / 64, a.n_ops), dim3(kBwdT), 0, st, p);
