@@ -48,7 +48,8 @@ constexpr int kMeanBlocksMax = 4096;
 // the grid strides over d (a capped grid of 4096 blocks walks the rows in step and reads 6.25 TB/s at n = 128,
 // d = 25.6 M, against 6.0 TB/s for one thread per float4 and 3.7 TB/s for dword accesses)
 // STREAM: X does not fit the caches and is read once: non-temporal loads
-template <bool STREAM>
+// VEC_OUT: out is 16-byte aligned and takes 128-bit stores
+template <bool STREAM, bool VEC_OUT>
 __global__ __launch_bounds__(kThreads) void mean_model_kernel(const float* X, int64_t ld, int64_t d, int32_t n, float* out) {
     const int64_t n_vec = (d + 3) / 4;
     for (int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; v < n_vec;
@@ -64,8 +65,15 @@ __global__ __launch_bounds__(kThreads) void mean_model_kernel(const float* X, in
                 s[0] += x[r].x; s[1] += x[r].y; s[2] += x[r].z; s[3] += x[r].w;
             }
         }
-        for (int c = 0; c < 4; ++c)
-            if (4 * v + c < d) out[4 * v + c] = static_cast<float>(s[c] / n);
+        const v4f mean = {static_cast<float>(s[0] / n), static_cast<float>(s[1] / n), static_cast<float>(s[2] / n),
+                          static_cast<float>(s[3] / n)};
+        if (4 * v + 4 <= d && VEC_OUT) {
+            store4<STREAM>(out + 4 * v, mean);         // out is 16-byte aligned
+        } else {
+            const float m[4] = {mean.x, mean.y, mean.z, mean.w};
+            for (int c = 0; c < 4; ++c)
+                if (4 * v + c < d) out[4 * v + c] = m[c];
+        }
     }
 }
 
@@ -308,10 +316,13 @@ hipError_t launch_refresh_bf16(const float* X, uint16_t* Xb, int64_t ld, int32_t
 
 hipError_t launch_mean_model(const float* X, int64_t ld, int64_t d, int32_t n, float* out, hipStream_t st) {
     const int64_t blocks = balanced_grid(((d + 3) / 4 + kThreads - 1) / kThreads, kMeanBlocksMax);
-    if (static_cast<int64_t>(n) * ld * 4 > kStreamBytes)
-        hipLaunchKernelGGL(mean_model_kernel<true>, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, st, X, ld, d, n, out);
-    else
-        hipLaunchKernelGGL(mean_model_kernel<false>, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, st, X, ld, d, n, out);
+    const bool stream = static_cast<int64_t>(n) * ld * 4 > kStreamBytes;
+    const bool vec = (reinterpret_cast<uintptr_t>(out) & 15u) == 0;
+    const dim3 grid(static_cast<uint32_t>(blocks)), block(kThreads);
+    if (stream && vec) hipLaunchKernelGGL((mean_model_kernel<true, true>), grid, block, 0, st, X, ld, d, n, out);
+    else if (stream) hipLaunchKernelGGL((mean_model_kernel<true, false>), grid, block, 0, st, X, ld, d, n, out);
+    else if (vec) hipLaunchKernelGGL((mean_model_kernel<false, true>), grid, block, 0, st, X, ld, d, n, out);
+    else hipLaunchKernelGGL((mean_model_kernel<false, false>), grid, block, 0, st, X, ld, d, n, out);
     return hipGetLastError();
 }
 

@@ -724,10 +724,12 @@ def _dense_from_csr(g, w_self, w_edge):
 
 
 @pytest.mark.parametrize("n,d,S,graph", [(8, 5003, 40, "ring"), (16, 1030, 25, "reg4"), (128, 777, 10, "ring"), (300, 100, 4, "ring"),
-                                         (200, 130, 6, "ring"), (1, 100, 5, "ring")])
+                                         (200, 130, 6, "ring"), (1, 100, 5, "ring"), (3, 7, 12, "ring"), (4, 1, 9, "ring"),
+                                         (2, 9, 5, "ring"), (5, 2049, 8, "ring")])
 def test_sync_steps_synthetic(P, n, d, S, graph):
     """All workers step together: X <- W X - gamma G, W = Metropolis weights of the graph; spans the three
-    tile widths of the mixing kernel (n <= 64, <= 128, <= 256) and a ragged last tile."""
+    tile widths of the mixing kernel (n <= 64, <= 128, <= 256), a ragged last tile, and the rings that take
+    the kernel without LDS (n >= 3 in the canonical neighbour order; n = 2 and the other graphs use the tiles)."""
     _say("sync steps, synth n=%d d=%d" % (n, d))
     g = ring_graph(n) if graph == "ring" else random_regular4_graph(n, 2)
     std = float(np.float32(0.05))
@@ -746,6 +748,32 @@ def test_sync_steps_synthetic(P, n, d, S, graph):
         oracle.run_events(Xr, sched, oracle.MODEL_SYNTH, 0.2, synth_std=std, synth_seed=3, event_base=S * n)
         assert rel_err(eng.get_models(), Xr) <= TOL
     eng.close()
+
+
+def test_sync_steps_ring_in_either_neighbour_order(P):
+    """The ring kernel without LDS takes rings whose neighbour lists read (i - 1, i + 1); the same ring listed
+    the other way round goes through the tile kernel.  Both must match the oracle, with caller-supplied weights
+    that differ from edge to edge (so that a swapped pair of weights would show)."""
+    n, d, S = 10, 1500, 12
+    rowptr, col = ring_graph(n)
+    flipped = (rowptr, np.ascontiguousarray(col.reshape(n, 2)[:, ::-1]).reshape(-1))
+    rng = np.random.default_rng(5)
+    edge = {}                                            # a symmetric weight per ring link, rows summing to one
+    for i in range(n):
+        edge[(i, (i + 1) % n)] = edge[((i + 1) % n, i)] = float(rng.uniform(0.1, 0.4))
+    x0 = rng.standard_normal((n, d)).astype(np.float32)
+    std = float(np.float32(0.05))
+    for g in ((rowptr, col), flipped):
+        _say("sync steps on a ring, neighbour order %s" % g[1][:2])
+        we = np.array([edge[(i, int(j))] for i in range(n) for j in g[1][2 * i:2 * i + 2]], np.float32)
+        ws = (1.0 - we.astype(np.float64).reshape(n, 2).sum(1)).astype(np.float32)
+        eng = P.Engine(g, d, "synth", gamma=0.2, synth_std=std, synth_seed=3)
+        eng.set_models(x0, broadcast=False)
+        eng.run_sync_steps(S, weights=(ws, we))
+        Xr = x0.copy()
+        oracle.run_sync_steps(Xr, None, _dense_from_csr(g, ws, we), oracle.MODEL_SYNTH, 0.2, synth_std=std, synth_seed=3, steps=S)
+        assert rel_err(eng.get_models(), Xr) <= TOL
+        eng.close()
 
 
 @pytest.mark.parametrize("model", ["lsq", "logreg"])
@@ -801,7 +829,7 @@ def test_sync_steps_mlp(P):
     eng.close()
 
 
-@pytest.mark.parametrize("model,n,d", [("synth", 16, 5003), ("synth", 200, 130), ("lsq", 12, 4099), ("mlp", 6, 0)])
+@pytest.mark.parametrize("model,n,d", [("synth", 16, 5003), ("synth", 200, 130), ("lsq", 12, 4099), ("lsq", 5, 2053), ("mlp", 6, 0)])
 def test_sync_steps_with_momentum_and_weight_decay(P, model, n, d):
     """The synchronous schedule with the experiments' optimizer: models and momentum buffers against the
     oracle, followed by asynchronous events on the same buffers."""
