@@ -525,3 +525,27 @@ def test_step_size_rules_of_the_experiments():
     assert np.allclose(late[:50], warm[150:200]) and np.all(late[50:] == np.float32(0.8))
     with pytest.raises(ValueError):
         ss.step_decay(10, 0, 1.0)
+
+
+def test_stored_long_run_references_match_their_recipe():
+    """tests/golden/long_run_cfg*.npz (the oracle's models along the full runs of configurations 2, 4, 5, written by
+    tests/golden/make_long_run_references.py) carry what the GPU test expects: the whole run in four calls, the
+    sampled coordinates the script's seed gives, one row per worker, finite values, losses that fall."""
+    import importlib.util
+    from workloads import get_config
+    gold = os.path.join(ROOT, "tests", "golden")
+    spec = importlib.util.spec_from_file_location("make_long_run_references", os.path.join(gold, "make_long_run_references.py"))
+    mk = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mk)
+    for idx in (2, 4, 5):
+        c = get_config(idx)
+        ref = np.load(os.path.join(gold, "long_run_cfg%d.npz" % idx), allow_pickle=False)
+        assert int(ref["events_per_call"]) * mk.CALLS == c["K"] and int(ref["rows"]) == mk.ROWS[idx]
+        coords = np.sort(np.random.default_rng([c["seed"], 77, idx]).choice(c["d"], size=mk.SAMPLED, replace=False))
+        assert np.array_equal(ref["coords"], coords)
+        for q in range(mk.CALLS):
+            x, amax = ref["x%d" % q], ref["amax%d" % q]
+            assert x.shape == (c["n"], mk.SAMPLED) and x.dtype == np.float32 and np.isfinite(x).all()
+            assert amax.shape == (c["n"],) and (amax > 0).all() and (np.abs(x).max(axis=1) <= amax).all()
+            assert (ref["l2_%d" % q] >= amax).all() and np.isfinite(ref["s%d" % q]).all()
+        assert float(ref["loss_tail%d" % (mk.CALLS - 1)]) < float(ref["loss_tail0"])
