@@ -144,8 +144,9 @@ __global__ __launch_bounds__(kThreads) void sync_mix_apply_kernel(const SyncPara
 // n = 128, d = 25.6 M: 5.0-5.15 TB/s against 4.6 TB/s for the tile kernel; n = 32, d = 4.2 M: 4.5-5.5 TB/s
 // against 4.9.  Nothing in the shape moves it: 2, 4 or 8 rows in flight, dwords or 128-bit pieces, blocks of
 // 256, 512 or 1024 threads, a grid of one block per tile or 512-8192 blocks striding over the tiles all land
-// within 3 % of each other, i.e. the three streams at different addresses are what the memory system gives
-// (an out-of-place copy streams 5.9 TB/s on the same box, a pure store stream 4.95).
+// within 3 % of each other.  The traversal binds: a plain in-place triad with the same two reads and one write
+// per element streams 6.6 TB/s when the grid covers the arrays in order, and 5.3 TB/s when every block walks down
+// the rows of its column tile, as a kernel must whose row i needs the old rows i - 1 and i + 1 (stream_bench).
 // The sums have the tile kernel's order (own row, then the neighbours as listed), so both give the same bits.
 constexpr int kRingThreads = 256;
 constexpr int kRingGridCap = 1024;

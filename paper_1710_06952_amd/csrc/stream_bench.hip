@@ -3,6 +3,7 @@
 //   - a read-only pass, a write-only pass and an out-of-place copy (the chip's plain streaming ceilings), and
 //   - the in-place update of a round of disjoint row pairs,  avg = (x_i + x_j) / 2;  x_j <- avg;  x_i <- avg - c,
 //     with 128-bit, 64-bit and 32-bit accesses per lane and 1 to 8 accesses per row in flight,
+//   - an in-place triad (two reads, one write) traversed flat and by walking down the rows of a column tile,
 // each as a kernel of its own name so that a kernel trace (rocprofv3 --kernel-trace --stats -- ./stream_bench)
 // lists them side by side.  The program also times every kernel with HIP events and prints GB/s of algorithmic
 // bytes.  Stand-alone: plain HIP runtime, no other file of the library.
@@ -106,6 +107,47 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const float* src_f, floa
         if (v0 + u * kThreads < n_vec) __builtin_nontemporal_store(x[u], dst + v0 + u * kThreads);
 }
 
+// In-place triad a <- a - c g (two reads and one write per element, the traffic of the synchronous mixing step with
+// gradients from memory), in the two traversal orders an update kernel can have:
+// flat: a block takes 1024 consecutive elements (one dword per lane, four in flight), the grid covers the array in order;
+__global__ __launch_bounds__(kThreads) void triad_flat_kernel(float* A, const float* G, int64_t n, float c) {
+    const int64_t e0 = static_cast<int64_t>(blockIdx.x) * (4 * kThreads) + threadIdx.x;
+    float a[4], g[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t e = e0 + u * kThreads;
+        if (e < n) {
+            a[u] = __builtin_nontemporal_load(A + e);
+            g[u] = __builtin_nontemporal_load(G + e);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t e = e0 + u * kThreads;
+        if (e < n) __builtin_nontemporal_store(a[u] - c * g[u], A + e);
+    }
+}
+// row-walking: a block owns 1024 columns and walks down the rows, ROWS of them in flight (the order a kernel needs
+// when the new row i depends on the old rows i - 1 and i + 1 and the update runs in place).
+template <int ROWS>
+__global__ __launch_bounds__(kThreads) void triad_rows_kernel(float* A, const float* G, int64_t ld, int64_t d, int rows, float c) {
+    typedef Vec<4>::type V;
+    const int64_t col = 4 * (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x);
+    if (col >= d) return;
+    for (int i0 = 0; i0 < rows; i0 += ROWS) {
+        V a[ROWS], g[ROWS];
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r)
+            if (i0 + r < rows) {
+                a[r] = __builtin_nontemporal_load(reinterpret_cast<const V*>(A + static_cast<int64_t>(i0 + r) * ld + col));
+                g[r] = __builtin_nontemporal_load(reinterpret_cast<const V*>(G + static_cast<int64_t>(i0 + r) * ld + col));
+            }
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r)
+            if (i0 + r < rows) __builtin_nontemporal_store(a[r] - c * g[r], reinterpret_cast<V*>(A + static_cast<int64_t>(i0 + r) * ld + col));
+    }
+}
+
 struct Timer {
     hipEvent_t a, b;
     Timer() { CHECK(hipEventCreate(&a)); CHECK(hipEventCreate(&b)); }
@@ -195,6 +237,27 @@ int main(int argc, char** argv) {
     measure_pairs<1, 2>(X, ld, d, pairs, n_pairs, launches);
     measure_pairs<1, 4>(X, ld, d, pairs, n_pairs, launches);
     measure_pairs<1, 8>(X, ld, d, pairs, n_pairs, launches);
+    // triad: the first half of the rows is updated in place with the second half as its "gradient"
+    {
+        const int half = rows / 2;
+        const int64_t n_half = static_cast<int64_t>(half) * ld;
+        float* G = X + n_half;
+        const double tbytes = 12.0 * n_half;
+        measure("triad in place, flat (dword x 4)", tbytes, launches, [&] {
+            hipLaunchKernelGGL(triad_flat_kernel, dim3(static_cast<uint32_t>((n_half + 4 * kThreads - 1) / (4 * kThreads))), dim3(kThreads), 0,
+                               nullptr, X, G, n_half, 1e-3f);
+        });
+        const dim3 rgrid(static_cast<uint32_t>((d / 4 + kThreads - 1) / kThreads));
+        measure("triad in place, row-walking, 2 rows in flight", tbytes, launches, [&] {
+            hipLaunchKernelGGL(triad_rows_kernel<2>, rgrid, dim3(kThreads), 0, nullptr, X, G, ld, d, half, 1e-3f);
+        });
+        measure("triad in place, row-walking, 4 rows in flight", tbytes, launches, [&] {
+            hipLaunchKernelGGL(triad_rows_kernel<4>, rgrid, dim3(kThreads), 0, nullptr, X, G, ld, d, half, 1e-3f);
+        });
+        measure("triad in place, row-walking, 8 rows in flight", tbytes, launches, [&] {
+            hipLaunchKernelGGL(triad_rows_kernel<8>, rgrid, dim3(kThreads), 0, nullptr, X, G, ld, d, half, 1e-3f);
+        });
+    }
     CHECK(hipFree(pairs));
     CHECK(hipFree(partial));
     CHECK(hipFree(X));
