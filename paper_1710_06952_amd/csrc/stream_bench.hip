@@ -3,7 +3,8 @@
 //   - a read-only pass, a write-only pass and an out-of-place copy (the chip's plain streaming ceilings), and
 //   - the in-place update of a round of disjoint row pairs,  avg = (x_i + x_j) / 2;  x_j <- avg;  x_i <- avg - c,
 //     with 128-bit, 64-bit and 32-bit accesses per lane and 1 to 8 accesses per row in flight,
-//   - an in-place triad (two reads, one write) traversed flat and by walking down the rows of a column tile,
+//   - an in-place triad (two reads, one write) traversed flat, by walking down the rows of a column tile, and by
+//     one-tile blocks over 8 .. 128 far-apart pieces of the array,
 // each as a kernel of its own name so that a kernel trace (rocprofv3 --kernel-trace --stats -- ./stream_bench)
 // lists them side by side.  The program also times every kernel with HIP events and prints GB/s of algorithmic
 // bytes.  Stand-alone: plain HIP runtime, no other file of the library.
@@ -147,6 +148,20 @@ __global__ __launch_bounds__(kThreads) void triad_rows_kernel(float* A, const fl
             if (i0 + r < rows) __builtin_nontemporal_store(a[r] - c * g[r], reinterpret_cast<V*>(A + static_cast<int64_t>(i0 + r) * ld + col));
     }
 }
+// pieces: one-tile blocks (one 128-bit access per lane) over the array cut into PIECES equal contiguous pieces, the
+// piece varying fastest with the block id: the chip then works on 2 x PIECES far-apart streams at a time.  Block ids go
+// round the 8 XCDs, so with `rotate` off an XCD meets PIECES / 8 of the pieces (one, for 8) and with it on all of them.
+__global__ __launch_bounds__(kThreads) void triad_pieces_kernel(float* A, const float* G, int64_t piece_len, int pieces, int rotate, float c) {
+    typedef Vec<4>::type V;
+    const int64_t tile = blockIdx.x / pieces;
+    const int piece = static_cast<int>((blockIdx.x % pieces + (rotate ? tile : 0)) % pieces);
+    const int64_t col = 4 * (tile * kThreads + threadIdx.x);
+    if (col >= piece_len) return;
+    const int64_t e = static_cast<int64_t>(piece) * piece_len + col;
+    const V a = __builtin_nontemporal_load(reinterpret_cast<const V*>(A + e));
+    const V g = __builtin_nontemporal_load(reinterpret_cast<const V*>(G + e));
+    __builtin_nontemporal_store(a - c * g, reinterpret_cast<V*>(A + e));
+}
 
 struct Timer {
     hipEvent_t a, b;
@@ -257,6 +272,20 @@ int main(int argc, char** argv) {
         measure("triad in place, row-walking, 8 rows in flight", tbytes, launches, [&] {
             hipLaunchKernelGGL(triad_rows_kernel<8>, rgrid, dim3(kThreads), 0, nullptr, X, G, ld, d, half, 1e-3f);
         });
+        // what costs the row-walking order its bandwidth: the number of far-apart streams the chip, and each XCD, works on
+        for (int rotate = 0; rotate < 2; ++rotate)
+            for (int pieces : {8, 16, 32, 64, 128}) {
+                if (n_half % (4 * static_cast<int64_t>(pieces)) != 0 || (rotate && pieces > 32)) continue;
+                const int64_t piece_len = n_half / pieces;
+                const int64_t tiles = (piece_len / 4 + kThreads - 1) / kThreads;
+                if (tiles * pieces > 0x7fffffffLL) continue;
+                char name[96];
+                std::snprintf(name, sizeof name, "triad, one-tile blocks, %3d pieces%s", pieces, rotate ? ", rotated" : "");
+                measure(name, tbytes, launches, [&] {
+                    hipLaunchKernelGGL(triad_pieces_kernel, dim3(static_cast<uint32_t>(tiles * pieces)), dim3(kThreads), 0, nullptr, X, G, piece_len,
+                                       pieces, rotate, 1e-3f);
+                });
+            }
     }
     CHECK(hipFree(pairs));
     CHECK(hipFree(partial));
