@@ -147,7 +147,9 @@ def sync_bench(args):
     neighbours) at the headline shape: --sync synth draws the gradients in registers (bound by the generator's
     arithmetic), --sync slots reads them from the pending slots as the data models do (bound by HBM: 12 B per
     parameter and worker update, 20 B with momentum buffers); the slots keep fixed values so that the mixing
-    kernel alone is timed.  Context for the update kernels, not the headline."""
+    kernel alone is timed.  An even number of --steps alternates between two matrices, an odd one starts with an
+    iteration in place; --sync-in-place keeps every iteration in place.  Context for the update kernels, not the
+    headline."""
     import torch
     import paper_1710_06952_amd as P
     from workloads import get_config, ring_graph
@@ -157,16 +159,18 @@ def sync_bench(args):
     mom = args.momentum != 0.0 or args.weight_decay != 0.0
     if args.sync == "synth":
         eng = P.Engine(graph, d, "synth", gamma=cfg["gamma"], synth_std=float(np.float32(cfg["synth_std"])), synth_seed=cfg["seed"],
-                       momentum=args.momentum, weight_decay=args.weight_decay)
+                       momentum=args.momentum, weight_decay=args.weight_decay, sync_in_place=args.sync_in_place)
         step = lambda S: eng.run_sync_steps(S)
         bytes_per_update = (16.0 if mom else 8.0) * d
     else:
-        eng = P.Engine(graph, d, "external", gamma=cfg["gamma"], n_slots=n, momentum=args.momentum, weight_decay=args.weight_decay)
+        eng = P.Engine(graph, d, "external", gamma=cfg["gamma"], n_slots=n, momentum=args.momentum, weight_decay=args.weight_decay,
+                       sync_in_place=args.sync_in_place)
         eng.workspace.normal_(0.0, 0.01)
         step = lambda S: eng.run_sync_steps_with(S, lambda worker, event, xhat, g: None)
         bytes_per_update = (20.0 if mom else 12.0) * d
     eng.set_models(np.zeros(d, np.float32))
-    step(max(args.warmup, 1))
+    warm = max(args.warmup, 2) + ((max(args.warmup, 2) ^ args.steps) & 1)      # the parity of the timed call, and >= 2:
+    step(warm)                                                                  # the handle's second matrix exists
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ev0.record()
@@ -177,12 +181,14 @@ def sync_bench(args):
     achieved = bytes_per_update * n * args.steps / t / 1e9
     print(json.dumps({
         "metric": "worker updates/s (synchronous comparison schedule, gradients: %s)" % args.sync, "value": n * args.steps / t,
-        "unit": "worker updates/s", "n_gpus": 1, "steps": args.steps, "warmup": max(args.warmup, 1), "ms_per_step": t / args.steps * 1e3,
+        "unit": "worker updates/s", "n_gpus": 1, "steps": args.steps, "warmup": warm, "ms_per_step": t / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "cfg3 shape, synchronous iterations on the ring", "n": n, "d": d, "momentum": args.momentum,
                    "weight_decay": args.weight_decay},
         "roofline": {"bound": "hbm" if args.sync == "slots" else "alu", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "sync_ring_apply_kernel",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "sync_ring_apply_kernel (in place)" if args.sync_in_place else
+                     "sync_ring_rows_kernel (pairs of iterations, out of place) + sync_ring_apply_kernel (an odd first one, in place)",
                      "bytes_per_worker_update": bytes_per_update}}), flush=True)
     eng.close()
 
@@ -204,6 +210,7 @@ def main():
     ap.add_argument("--d", type=int, default=0, help="override d (debugging only; the result is then not the headline)")
     ap.add_argument("--sync", choices=["synth", "slots"], default=None,
                     help="time the synchronous comparison schedule at the headline shape instead (a step is one iteration)")
+    ap.add_argument("--sync-in-place", action="store_true", help="with --sync: every iteration mixes in place (no second model matrix)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (all n workers are simulated in one GPU's HBM); "

@@ -15,7 +15,7 @@ LIB_PATH = _HERE / "libadpsgd.so"
 
 OK, ERR_ARG, ERR_GRAPH, ERR_SCHEDULE, ERR_STATE, ERR_HIP, ERR_CALLBACK = 0, -1, -2, -3, -4, -5, -6
 MODEL_LSQ, MODEL_LOGREG, MODEL_SYNTH, MODEL_MLP, MODEL_EXTERNAL = 0, 1, 2, 3, 4
-FLAG_PROFILE, FLAG_DENSE_GRADIENT, FLAG_VERIFY_PLAN = 1, 2, 4
+FLAG_PROFILE, FLAG_DENSE_GRADIENT, FLAG_VERIFY_PLAN, FLAG_SYNC_IN_PLACE = 1, 2, 4, 8
 
 EXPORTS = [
     "adpsgd_create", "adpsgd_destroy", "adpsgd_last_error", "adpsgd_load_data", "adpsgd_set_models",

@@ -186,6 +186,7 @@ extern "C" void adpsgd_destroy(adpsgd_t* h) {
     h->grad_scratch.release();
     h->comp_rows.release();
     h->diag.release();
+    h->sync_other.release();
     delete h;
 }
 

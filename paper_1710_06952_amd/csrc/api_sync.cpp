@@ -116,15 +116,31 @@ int run_sync_steps_impl(adpsgd_t* h, const adpsgd_sync_schedule_t* s, float* los
     bool ring = n >= 3 && nnz == 2 * n;
     for (int32_t i = 0; ring && i < n; ++i)
         ring = h->rowptr[i] == 2 * i && h->col[2 * i] == (i + n - 1) % n && h->col[2 * i + 1] == (i + 1) % n;
+    // On a ring, iterations that come in pairs write the new models to a second matrix and back (blocks in row
+    // order: faster than the in-place walk down the rows); an odd iteration runs in place first, so the models end
+    // where the caller keeps them.  Without memory for the second matrix every iteration runs in place.
+    float* other = nullptr;
+    if (ring && S >= 2 && !(h->o.flags & ADPSGD_FLAG_SYNC_IN_PLACE) && !h->sync_other_refused && sync_ring_out_of_place_ok(n, h->d)) {
+        if (h->sync_other.reserve(static_cast<size_t>(n) * static_cast<size_t>(h->o.ldx) * sizeof(float)) == hipSuccess) {
+            other = static_cast<float*>(h->sync_other.p);
+        } else {
+            (void)hipGetLastError();
+            h->sync_other_refused = true;
+        }
+    }
+    float* cur = h->o.X;
     float* slots = static_cast<float*>(h->o.workspace);
     const float gscale = h->o.grad_sum ? 1.0f : 1.0f / static_cast<float>(std::max(M, 1));
     std::vector<adpsgd_grad_request_t> requests(external ? n : 0);
     for (int64_t t = 0; t < S; ++t) {
         if (external) {       // every worker's gradient at the model the iteration starts from, into slot i
             for (int32_t i = 0; i < n; ++i)
-                requests[i] = adpsgd_grad_request_t{i, 0, t * n + i, h->o.X + static_cast<int64_t>(i) * h->o.ldx,
+                requests[i] = adpsgd_grad_request_t{i, 0, t * n + i, cur + static_cast<int64_t>(i) * h->o.ldx,
                                                     slots + static_cast<int64_t>(i) * h->o.ldx};
             if (fn(user, n, requests.data(), h->stream) != 0) {
+                if (cur != h->o.X)     // the models of the iterations done so far go back where the caller keeps them
+                    (void)hipMemcpyAsync(h->o.X, cur, static_cast<size_t>(n) * static_cast<size_t>(h->o.ldx) * sizeof(float),
+                                         hipMemcpyDeviceToDevice, h->stream);
                 (void)hipStreamSynchronize(h->stream);
                 return fail(h, ADPSGD_ERR_CALLBACK, "run_sync_steps_with: the gradient function failed in iteration " + std::to_string(t));
             }
@@ -134,12 +150,12 @@ int run_sync_steps_impl(adpsgd_t* h, const adpsgd_sync_schedule_t* s, float* los
             const int32_t cnt = std::min<int32_t>(group, n - g0);
             int launches = 0;
             if (h->o.model == ADPSGD_MODEL_MLP) {
-                MlpGradArgs a{h->o.X, h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, d_rops + t * n + g0, cnt, M,
+                MlpGradArgs a{cur, h->o.Xbf16, h->o.ldx, h->o.mlp_in, h->o.mlp_hidden, h->o.mlp_out, d_rops + t * n + g0, cnt, M,
                               d_batch + (t * n + g0) * static_cast<int64_t>(M), slots, gscale, loss,
                               h->grad_scratch.p, false, false};
                 HIP_TRY(h, launch_mlp_gradient(a, h->stream, &launches));
             } else {
-                LinearGradArgs a{h->o.model, h->o.X, h->o.ldx, h->d, d_rops + t * n + g0, cnt, M, d_batch,
+                LinearGradArgs a{h->o.model, cur, h->o.ldx, h->d, d_rops + t * n + g0, cnt, M, d_batch,
                                  slots, gscale, h->o.lambda,
                                  static_cast<float*>(h->grad_scratch.p),
                                  reinterpret_cast<float*>(static_cast<char*>(h->grad_scratch.p) + off_coef), loss, false};
@@ -154,14 +170,17 @@ int run_sync_steps_impl(adpsgd_t* h, const adpsgd_sync_schedule_t* s, float* los
             if (!e0 || !e1) return fail(h, ADPSGD_ERR_HIP, "run_sync_steps: hipEventCreate failed");
             HIP_TRY(h, hipEventRecord(e0, h->stream));
         }
-        SyncArgs a{h->o.X, h->o.ldx, h->d, n,
+        // in place while an odd number of iterations is left with the models at home, else into the other matrix
+        float* dst = other && !(cur == h->o.X && ((S - t) & 1)) ? (cur == h->o.X ? other : h->o.X) : nullptr;
+        SyncArgs a{cur, h->o.ldx, h->d, n,
                    reinterpret_cast<const int32_t*>(dev + off_rp), reinterpret_cast<const int32_t*>(dev + off_col),
                    reinterpret_cast<const float*>(dev + off_ws), reinterpret_cast<const float*>(dev + off_we),
                    with_grad ? slots : nullptr, h->o.model == ADPSGD_MODEL_MLP ? h->o.Xbf16 : nullptr,
                    s->gamma ? s->gamma[t] : h->o.gamma, h->o.synth_std, h->o.synth_seed,
                    h->events_done + static_cast<uint64_t>(t) * static_cast<uint64_t>(n), !with_grad,
-                   h->o.V, h->o.momentum, h->o.weight_decay, ring};
+                   h->o.V, h->o.momentum, h->o.weight_decay, ring, dst};
         HIP_TRY(h, launch_sync_mix_apply(a, h->stream));
+        if (dst) cur = dst;
         ++h->stats.fused_launches;
         if (profile) {
             HIP_TRY(h, hipEventRecord(e1, h->stream));

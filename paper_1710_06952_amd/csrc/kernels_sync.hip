@@ -41,6 +41,9 @@ struct SyncParams {
     uint64_t event0;           // synthetic gradients: worker i draws event event0 + i
     float* V;                  // momentum buffers (MOM), else nullptr
     float momentum, weight_decay;
+    float* Y;                  // the ring written out of place: the matrix that receives the new models (same ld)
+    int64_t tiles;             // ... its tiles of 1024 columns,
+    uint32_t band, band_last, bands;   // tiles per band of columns (multiples of 8), in the last band, and the bands
 };
 
 // grid = ceil(d / cols); thread = (quad of 4 columns, row lane)
@@ -146,8 +149,10 @@ __global__ __launch_bounds__(kThreads) void sync_mix_apply_kernel(const SyncPara
 // 256, 512 or 1024 threads, a grid of one block per tile or 512-8192 blocks striding over the tiles all land
 // within 3 % of each other.  The traversal binds: a plain in-place triad with the same two reads and one write
 // per element streams 6.6 TB/s when the grid covers the arrays in order, and 5.3 TB/s when every block walks down
-// the rows of its column tile, as a kernel must whose row i needs the old rows i - 1 and i + 1 (stream_bench).
-// The sums have the tile kernel's order (own row, then the neighbours as listed), so both give the same bits.
+// the rows of its column tile, as a kernel must that updates in place when row i needs the old rows i - 1 and i + 1
+// (stream_bench).  It runs an odd first iteration of a call, and every iteration when there is no second matrix;
+// pairs of iterations take the kernel in row order below.
+// The sums have the tile kernel's order (own row, then the neighbours as listed).
 constexpr int kRingThreads = 256;
 constexpr int kRingGridCap = 1024;
 
@@ -251,6 +256,105 @@ hipError_t launch_ring(const SyncParams& p, bool synth, hipStream_t st) {
     return hipGetLastError();
 }
 
+// ---- the ring, out of place, in row order ---------------------------------------------------------
+// What holds the walking kernel at 5.0-5.15 TB/s is its traversal, not its code: with every block somewhere else
+// on its way down the rows, the chip works on 2 x n far-apart address streams at a time and every XCD meets all
+// of them; one-tile blocks over 128 far-apart pieces of an array lose the same bandwidth with no loop at all
+// (stream_bench: 6.6 TB/s with 8 pieces, 5.0 with 128).  A traversal in row order cannot update in place, since
+// the old row i is still needed by rows i - 1 and i + 1.  So iterations that come in pairs write the new models to
+// a second matrix and back: a block is one tile of 1024 columns of ONE row (three loads of X, the gradient, one
+// store per lane), and the blocks are ordered (band of ~2048 tiles, row, tile).  The chip then works on about one
+// row of a band at a time; tile t of rows i - 1, i, i + 1 meets the same XCD (block ids go round the 8 XCDs and the
+// band widths are multiples of 8) 2048 and 4096 blocks apart, so two of the three loads of X hit that XCD's L2
+// (a band of three rows is 24 MB of the chip's 32 MB) and HBM sees the same 12 B per parameter and worker update as
+// in place (counters: 39.9 GB per iteration against 39.3 GB algorithmic).  Measured at n = 128, d = 25.6 M with
+// gradients from slots: 6.84-6.93 ms per iteration = 5.7 TB/s against 7.7 ms in place; with momentum buffers 12.0
+// against 13.1 ms; with gradients drawn in registers 5.6 against 6.0 ms.  A stand-alone kernel with this traversal
+// and nothing else ran 6.54 ms with bands of 2048 tiles, 6.68 / 6.57 / 6.62 / 7.66 ms with 1024 / 1536 / 2560 / 3072;
+// 7.3 / 7.6 ms with two / four rows per block (fewer loads through L2, more streams); 7.4 ms with one dword per lane
+// and four accesses.  The loads of X stay cached whatever the size; the sums have the order of the walking kernel
+// (own row, left, right), so both give the same bits.
+constexpr uint32_t kBandTiles = 2048;
+
+template <bool SYNTH, bool SHADOW, bool MOM, bool STREAM>
+__global__ __launch_bounds__(kRingThreads) void sync_ring_rows_kernel(const SyncParams p) {
+    const uint32_t per_band = static_cast<uint32_t>(p.n) * p.band;
+    uint32_t b = blockIdx.x / per_band;
+    if (b >= p.bands) b = p.bands - 1;
+    const uint32_t r = blockIdx.x - b * per_band;
+    const uint32_t width = b == p.bands - 1 ? p.band_last : p.band;
+    const int32_t i = static_cast<int32_t>(r / width);
+    const int64_t tile = static_cast<int64_t>(b) * p.band + r % width;
+    const int64_t c = 4 * (tile * kRingThreads + threadIdx.x);
+    if (i >= p.n || tile >= p.tiles || c >= p.d) return;
+    const int32_t im = i == 0 ? p.n - 1 : i - 1, ip = i == p.n - 1 ? 0 : i + 1;
+    float prev[4], cur[4], nxt[4], g[4], vo[4];
+    ring_load<false>(p.X + static_cast<int64_t>(ip) * p.ld, c, nxt);       // first touch of this tile: from HBM
+    ring_load<false>(p.X + static_cast<int64_t>(i) * p.ld, c, cur);
+    ring_load<false>(p.X + static_cast<int64_t>(im) * p.ld, c, prev);
+    if (SYNTH) {
+        const uint64_t k = p.event0 + static_cast<uint64_t>(i);
+        const uint64_t q = static_cast<uint64_t>(c) >> 2;
+        const v4f z = synth_normals4(static_cast<uint32_t>(q), static_cast<uint32_t>(q >> 32), static_cast<uint32_t>(k),
+                                     static_cast<uint32_t>(k >> 32), p.key0, p.key1) * p.synth_std;
+        g[0] = z.x; g[1] = z.y; g[2] = z.z; g[3] = z.w;
+    } else {
+        ring_load<STREAM>(p.slots + static_cast<int64_t>(i) * p.ld, c, g);
+    }
+    if (MOM) ring_load<STREAM>(p.V + static_cast<int64_t>(i) * p.ld, c, vo);
+    const float ws = p.w_self[i], wa = p.w_edge[2 * i], wb = p.w_edge[2 * i + 1];   // uniform: scalar loads
+    float out[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        float acc = cur[t] * ws;
+        acc += prev[t] * wa;
+        acc += nxt[t] * wb;
+        if (MOM) {
+            float unused, vn;      // the event's rule with both rows equal to the mixed model
+            average_then_apply_momentum(acc, acc, g[t], vo[t], p.gamma, p.momentum, p.weight_decay, out[t], unused, vn);
+            vo[t] = vn;
+        } else {
+#pragma clang fp contract(off)
+            const float step = g[t] * p.gamma;
+            out[t] = acc - step;
+        }
+    }
+    if (MOM) ring_store<STREAM>(p.V + static_cast<int64_t>(i) * p.ld, c, p.d, vo);
+    ring_store<STREAM>(p.Y + static_cast<int64_t>(i) * p.ld, c, p.d, out);
+    if (SHADOW) {
+        const v4h hb = {bf16_rne(out[0]), c + 1 < p.d ? bf16_rne(out[1]) : static_cast<uint16_t>(0),
+                        c + 2 < p.d ? bf16_rne(out[2]) : static_cast<uint16_t>(0),
+                        c + 3 < p.d ? bf16_rne(out[3]) : static_cast<uint16_t>(0)};
+        *reinterpret_cast<v4h*>(p.Xbf16 + static_cast<int64_t>(i) * p.ld + c) = hb;
+    }
+}
+
+// bands of at most kBandTiles tiles, all but the last of one width, every width a multiple of 8; false: too many blocks
+bool ring_rows_geometry(int32_t n, int64_t d, int64_t& tiles, uint32_t& band, uint32_t& band_last, uint32_t& bands, int64_t& blocks) {
+    tiles = (d + 4 * kRingThreads - 1) / (4 * kRingThreads);
+    const int64_t want = (tiles + kBandTiles - 1) / kBandTiles;
+    const int64_t width = ((tiles + want - 1) / want + 7) / 8 * 8;
+    const int64_t count = (tiles + width - 1) / width;
+    const int64_t last = (tiles - (count - 1) * width + 7) / 8 * 8;
+    blocks = static_cast<int64_t>(n) * ((count - 1) * width + last);
+    if (n < 3 || tiles < 1 || blocks > 0x7FFFFFFF || static_cast<int64_t>(n) * width > 0x7FFFFFFF) return false;
+    band = static_cast<uint32_t>(width);
+    band_last = static_cast<uint32_t>(last);
+    bands = static_cast<uint32_t>(count);
+    return true;
+}
+
+template <bool MOM, bool STREAM>
+hipError_t launch_ring_rows(SyncParams& p, bool synth, hipStream_t st) {
+    int64_t blocks = 0;
+    if (!ring_rows_geometry(p.n, p.d, p.tiles, p.band, p.band_last, p.bands, blocks)) return hipErrorInvalidValue;
+    const dim3 grid(static_cast<uint32_t>(blocks)), block(kRingThreads);
+    if (synth) hipLaunchKernelGGL((sync_ring_rows_kernel<true, false, MOM, STREAM>), grid, block, 0, st, p);
+    else if (p.Xbf16) hipLaunchKernelGGL((sync_ring_rows_kernel<false, true, MOM, STREAM>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((sync_ring_rows_kernel<false, false, MOM, STREAM>), grid, block, 0, st, p);
+    return hipGetLastError();
+}
+
 template <bool MOM, bool STREAM>
 hipError_t launch_variant(const SyncParams& p, bool synth, dim3 grid, size_t lds, hipStream_t st) {
     const bool wide = STREAM && p.cols >= 128;
@@ -273,6 +377,12 @@ int32_t sync_tile_cols(int32_t n) {
     for (int32_t cols = 256; cols >= 16; cols >>= 1)
         if (static_cast<int64_t>(n) * cols * 4 <= kTileBytes) return cols;
     return static_cast<int64_t>(n) * 16 * 4 <= 65536 ? 16 : 0;
+}
+
+bool sync_ring_out_of_place_ok(int32_t n, int64_t d) {
+    int64_t tiles = 0, blocks = 0;
+    uint32_t band = 0, band_last = 0, bands = 0;
+    return ring_rows_geometry(n, d, tiles, band, band_last, bands, blocks);
 }
 
 hipError_t launch_sync_mix_apply(const SyncArgs& a, hipStream_t st) {
@@ -303,6 +413,15 @@ hipError_t launch_sync_mix_apply(const SyncArgs& a, hipStream_t st) {
     p.momentum = a.momentum;
     p.weight_decay = a.weight_decay;
     const bool stream = static_cast<int64_t>(a.n) * a.ld * 4 > (256ll << 20);      // X does not fit the memory-side cache
+    p.Y = a.Xdst;
+    p.tiles = 0;
+    p.band = p.band_last = p.bands = 0;
+    if (a.ring && a.Xdst) {
+        if (a.Xdst == a.X) return hipErrorInvalidValue;
+        if (stream) return a.V ? launch_ring_rows<true, true>(p, a.synth, st) : launch_ring_rows<false, true>(p, a.synth, st);
+        return a.V ? launch_ring_rows<true, false>(p, a.synth, st) : launch_ring_rows<false, false>(p, a.synth, st);
+    }
+    if (a.Xdst) return hipErrorInvalidValue;
     if (a.ring) {
         if (stream) return a.V ? launch_ring<true, true>(p, a.synth, st) : launch_ring<false, true>(p, a.synth, st);
         return a.V ? launch_ring<true, false>(p, a.synth, st) : launch_ring<false, false>(p, a.synth, st);

@@ -29,7 +29,7 @@ def _device_vector(torch, ptr, d, device):
 class Engine:
     def __init__(self, graph, d, model, *, M=0, gamma=0.0, lam=0.0, grad_sum=False, T_max=0, synth_std=0.0,
                  synth_seed=0, mlp=(0, 0, 0), n_slots=None, profile=False, momentum=0.0, weight_decay=0.0,
-                 local_compensation=False, dense_gradient=False, verify_plan=False, device="cuda:0"):
+                 local_compensation=False, dense_gradient=False, verify_plan=False, sync_in_place=False, device="cuda:0"):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("Engine needs a GPU: the HIP library is the only implementation")
@@ -64,7 +64,7 @@ class Engine:
                           mlp=mlp, Xbf16_ptr=None if self.Xbf16 is None else self.Xbf16.data_ptr(),
                           workspace_ptr=ws_ptr, workspace_bytes=ws_bytes, stream=self.stream.cuda_stream,
                           flags=(B.FLAG_PROFILE if profile else 0) | (B.FLAG_DENSE_GRADIENT if dense_gradient else 0) |
-                          (B.FLAG_VERIFY_PLAN if verify_plan else 0), momentum=momentum, weight_decay=weight_decay,
+                          (B.FLAG_VERIFY_PLAN if verify_plan else 0) | (B.FLAG_SYNC_IN_PLACE if sync_in_place else 0), momentum=momentum, weight_decay=weight_decay,
                           V_ptr=None if self.V is None else self.V.data_ptr(),
                           local_compensation=local_compensation)
         self._data = []

@@ -725,11 +725,14 @@ def _dense_from_csr(g, w_self, w_edge):
 
 @pytest.mark.parametrize("n,d,S,graph", [(8, 5003, 40, "ring"), (16, 1030, 25, "reg4"), (128, 777, 10, "ring"), (300, 100, 4, "ring"),
                                          (200, 130, 6, "ring"), (1, 100, 5, "ring"), (3, 7, 12, "ring"), (4, 1, 9, "ring"),
-                                         (2, 9, 5, "ring"), (5, 2049, 8, "ring")])
+                                         (2, 9, 5, "ring"), (5, 2049, 8, "ring"), (3, 4196357, 3, "ring"), (4, 2101253, 2, "ring"),
+                                         (6, 1025, 1, "ring")])
 def test_sync_steps_synthetic(P, n, d, S, graph):
     """All workers step together: X <- W X - gamma G, W = Metropolis weights of the graph; spans the three
     tile widths of the mixing kernel (n <= 64, <= 128, <= 256), a ragged last tile, and the rings that take
-    the kernel without LDS (n >= 3 in the canonical neighbour order; n = 2 and the other graphs use the tiles)."""
+    the kernels without LDS (n >= 3 in the canonical neighbour order; n = 2 and the other graphs use the tiles):
+    on those an odd first iteration walks down the rows in place and the rest alternate between two matrices,
+    in bands of 2048 tiles of 1024 columns (the two longest models span three and two bands, ragged)."""
     _say("sync steps, synth n=%d d=%d" % (n, d))
     g = ring_graph(n) if graph == "ring" else random_regular4_graph(n, 2)
     std = float(np.float32(0.05))
@@ -774,6 +777,64 @@ def test_sync_steps_ring_in_either_neighbour_order(P):
         oracle.run_sync_steps(Xr, None, _dense_from_csr(g, ws, we), oracle.MODEL_SYNTH, 0.2, synth_std=std, synth_seed=3, steps=S)
         assert rel_err(eng.get_models(), Xr) <= TOL
         eng.close()
+
+
+@pytest.mark.parametrize("mu,wd", [(0.0, 0.0), (0.9, 1e-3)])
+def test_sync_steps_on_a_ring_in_place_and_between_two_matrices_give_the_same_bits(P, mu, wd):
+    """A call with one iteration mixes in place (the kernel that walks down the rows) and a call with an even number
+    alternates between two matrices (one-tile blocks in row order): both sum own row, left neighbour, right
+    neighbour, so models and momentum buffers agree bit for bit however the iterations are cut into calls.  The
+    same ring listed the other way round takes the tile kernel and sums in that other order: equal to rounding."""
+    n, d, S = 7, 3 * 1024 + 5, 6
+    rowptr, col = ring_graph(n)
+    flipped = (rowptr, np.ascontiguousarray(col.reshape(n, 2)[:, ::-1]).reshape(-1))
+    std = float(np.float32(0.05))
+    x0 = np.random.default_rng(8).standard_normal((n, d)).astype(np.float32)
+    got = []
+    for g, calls, flag in (((rowptr, col), [S], False), ((rowptr, col), [1] * S, False), ((rowptr, col), [3, 2, 1], False),
+                           (flipped, [S], False), ((rowptr, col), [S], True)):
+        _say("sync steps on a ring, calls %s%s" % (calls, ", in place by request" if flag else ""))
+        eng = P.Engine(g, d, "synth", gamma=0.2, synth_std=std, synth_seed=3, momentum=mu, weight_decay=wd, sync_in_place=flag)
+        eng.set_models(x0, broadcast=False)
+        for c in calls:
+            eng.run_sync_steps(c)
+        got.append((eng.get_models(), eng.get_momentum() if mu else None))
+        eng.close()
+    for X, V in got[1:3] + got[4:]:
+        assert np.array_equal(X, got[0][0])
+        assert V is None or np.array_equal(V, got[0][1])
+    assert not np.array_equal(got[3][0], got[0][0]) and rel_err(got[3][0], got[0][0]) <= TOL
+    Xr, Vr = x0.copy(), np.zeros_like(x0)
+    oracle.run_sync_steps(Xr, None, oracle.metropolis_weights((rowptr, col)), oracle.MODEL_SYNTH, 0.2, synth_std=std, synth_seed=3,
+                          steps=S, momentum=mu, weight_decay=wd, V=Vr if mu else None)
+    assert rel_err(got[0][0], Xr) <= TOL
+
+
+def test_sync_ring_full_size_sampled_coordinates(P):
+    """The synchronous schedule at the headline shape (n = 128, d = 25.6 M, ring, gradients drawn in the kernel), five
+    iterations in one call: one in place, then two pairs between the two matrices, 13 bands of columns.  Every
+    coordinate evolves independently, so the oracle follows 2048 sampled coordinates, among them both ends of
+    the model and both sides of tile and band boundaries."""
+    import torch
+    c = get_config(3)
+    n, d, S = c["n"], c["d"], 5
+    g = ring_graph(n)
+    std = float(np.float32(c["synth_std"]))
+    _say("sync ring full size: %d iterations" % S)
+    eng = P.Engine(g, d, "synth", gamma=c["gamma"], synth_std=std, synth_seed=c["seed"])
+    x0 = np.random.default_rng(4).standard_normal(d).astype(np.float32)
+    eng.set_models(x0)
+    eng.run_sync_steps(S)
+    band = 1928 * 1024            # 25 000 tiles in 13 bands of 1928 (the last: 1864)
+    rng = np.random.default_rng(0)
+    coords = np.unique(np.concatenate([[0, 1, 2, 3, 1023, 1024, band - 1, band, 12 * band - 1, 12 * band, d - 2, d - 1],
+                                       rng.integers(0, d, 2036)]))
+    Xg = eng.X[:, torch.from_numpy(coords).to("cuda:0")].cpu().numpy()
+    Xr = np.tile(x0[coords], (n, 1))
+    oracle.run_sync_steps(Xr, None, oracle.metropolis_weights(g), oracle.MODEL_SYNTH, c["gamma"], synth_std=std,
+                          synth_seed=c["seed"], steps=S, coords=coords)
+    assert rel_err(Xg, Xr) <= TOL
+    eng.close()
 
 
 @pytest.mark.parametrize("model", ["lsq", "logreg"])
@@ -1087,6 +1148,21 @@ def test_external_gradients_from_pytorch_follow_algorithm_1(P):
     oracle.run_sync_steps(Xs, sync_batch, oracle.metropolis_weights(g), oracle.MODEL_LSQ, 0.3, M=M, gscale=1.0 / M,
                           features=feats, targets=targs, momentum=0.9, weight_decay=1e-3, V=Vs)
     assert rel_err(sy.get_models(), Xs) <= TOL and v_err(sy.get_momentum(), Vs) <= V_TOL
+    # a function that gives up in iteration 1 or 2 of 4: X holds the models of the iterations done so far, whichever
+    # of the handle's two matrices they were in
+    for give_up_in in (1, 2):
+        def sync_failing(worker, event, xhat, out):
+            if event // n == give_up_in:
+                raise RuntimeError("sync gradient function gave up")
+            sync_gradient(worker, event, xhat, out)
+        sy.set_models(x0)
+        sy.V.zero_()
+        with pytest.raises(RuntimeError, match="gave up"):
+            sy.run_sync_steps_with(4, sync_failing)
+        Xp, Vp = np.tile(x0, (n, 1)), np.zeros((n, d), np.float32)
+        oracle.run_sync_steps(Xp, sync_batch[:give_up_in], oracle.metropolis_weights(g), oracle.MODEL_LSQ, 0.3, M=M, gscale=1.0 / M,
+                              features=feats, targets=targs, momentum=0.9, weight_decay=1e-3, V=Vp)
+        assert rel_err(sy.get_models(), Xp) <= TOL
     sy.close()
 
     calls = []
