@@ -152,10 +152,10 @@ def sync_bench(args):
     headline."""
     import torch
     import paper_1710_06952_amd as P
-    from workloads import get_config, ring_graph
+    from workloads import get_config, hop_ring_graph, random_regular4_graph, ring_graph
     cfg = get_config(3)
     n, d = cfg["n"], args.d or cfg["d"]
-    graph = ring_graph(n)
+    graph = {"ring": ring_graph, "reg4": lambda m: random_regular4_graph(m, cfg["seed"]), "hop": hop_ring_graph}[args.sync_graph](n)
     mom = args.momentum != 0.0 or args.weight_decay != 0.0
     if args.sync == "synth":
         eng = P.Engine(graph, d, "synth", gamma=cfg["gamma"], synth_std=float(np.float32(cfg["synth_std"])), synth_seed=cfg["seed"],
@@ -183,12 +183,16 @@ def sync_bench(args):
         "metric": "worker updates/s (synchronous comparison schedule, gradients: %s)" % args.sync, "value": n * args.steps / t,
         "unit": "worker updates/s", "n_gpus": 1, "steps": args.steps, "warmup": warm, "ms_per_step": t / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "cfg3 shape, synchronous iterations on the ring", "n": n, "d": d, "momentum": args.momentum,
+        "config": {"workload": "cfg3 shape, synchronous iterations on the %s" % {"ring": "ring", "reg4": "random 4-regular graph",
+                                                                               "hop": "ring with the 2^i + 1 hop links"}[args.sync_graph],
+                   "n": n, "d": d, "momentum": args.momentum,
                    "weight_decay": args.weight_decay},
         "roofline": {"bound": "hbm" if args.sync == "slots" else "alu", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "sync_ring_apply_kernel (in place)" if args.sync_in_place else
-                     "sync_ring_rows_kernel (pairs of iterations, out of place) + sync_ring_apply_kernel (an odd first one, in place)",
+                     "kernel": ("sync_ring_apply_kernel" if args.sync_graph == "ring" else "sync_mix_apply_kernel") + " (in place)"
+                     if args.sync_in_place else
+                     ("sync_ring_rows_kernel" if args.sync_graph == "ring" else "sync_graph_rows_kernel") +
+                     " (pairs of iterations, out of place; an odd first one in place)",
                      "bytes_per_worker_update": bytes_per_update}}), flush=True)
     eng.close()
 
@@ -210,6 +214,8 @@ def main():
     ap.add_argument("--d", type=int, default=0, help="override d (debugging only; the result is then not the headline)")
     ap.add_argument("--sync", choices=["synth", "slots"], default=None,
                     help="time the synchronous comparison schedule at the headline shape instead (a step is one iteration)")
+    ap.add_argument("--sync-graph", choices=["ring", "reg4", "hop"], default="ring",
+                    help="with --sync: the ring (default), a random 4-regular graph, or the ring with the paper's 2^i + 1 hop links")
     ap.add_argument("--sync-in-place", action="store_true", help="with --sync: every iteration mixes in place (no second model matrix)")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -73,8 +73,8 @@ enum {
                                     the updates before its logical time, slots live long enough); a violation is a
                                     library bug and returns ADPSGD_ERR_STATE.  O(K log K) host work per call */
     ADPSGD_FLAG_SYNC_IN_PLACE = 8,  /* adpsgd_run_sync_steps: never allocate the second model matrix that the iterations
-                                       on a ring otherwise alternate with; every iteration then mixes in place
-                                       (same results, about 12 % slower at n = 128, d = 25.6 M) */
+                                       otherwise alternate with; every iteration then mixes in place (same
+                                       results, 12 - 30 % slower at n = 128, d = 25.6 M depending on the graph) */
     ADPSGD_FLAG_DENSE_GRADIENT = 2  /* always write gradients out as dense vectors.  By default (without the
                                        wait-free variant) low-rank gradients stay in factored form until the
                                        update kernel applies them: the MLP's first layer as dH and the minibatch
@@ -275,7 +275,7 @@ int adpsgd_run_events_with(adpsgd_t* h, const adpsgd_schedule_t* s, adpsgd_gradi
  * (device, S * n floats, [t][i], or NULL) receives the minibatch losses.  Needs at least n
  * pending-gradient slots in the workspace (data models) and n <= 1024.  With momentum / weight
  * decay the optimizer rule of adpsgd_opts_t acts on the mixed model in place of x_{k+1/2}^i.
- * Memory: on a ring whose neighbour lists read (i - 1, i + 1) mod n, a call with S >= 2 lets the handle
+ * Memory: a call with S >= 2 lets the handle
  * allocate (once, kept until adpsgd_destroy) a second matrix of n * ldx floats: iterations then alternate
  * between X and that matrix, which is faster than mixing in place, and the models are back in X when the
  * call's work is done.  If that allocation fails, or with ADPSGD_FLAG_SYNC_IN_PLACE, the iterations run in

@@ -116,11 +116,11 @@ int run_sync_steps_impl(adpsgd_t* h, const adpsgd_sync_schedule_t* s, float* los
     bool ring = n >= 3 && nnz == 2 * n;
     for (int32_t i = 0; ring && i < n; ++i)
         ring = h->rowptr[i] == 2 * i && h->col[2 * i] == (i + n - 1) % n && h->col[2 * i + 1] == (i + 1) % n;
-    // On a ring, iterations that come in pairs write the new models to a second matrix and back (blocks in row
-    // order: faster than the in-place walk down the rows); an odd iteration runs in place first, so the models end
-    // where the caller keeps them.  Without memory for the second matrix every iteration runs in place.
+    // Iterations that come in pairs write the new models to a second matrix and back (blocks in row order: faster
+    // than mixing in place, on a ring and on any other graph); an odd iteration runs in place first, so the models
+    // end where the caller keeps them.  Without memory for the second matrix every iteration runs in place.
     float* other = nullptr;
-    if (ring && S >= 2 && !(h->o.flags & ADPSGD_FLAG_SYNC_IN_PLACE) && !h->sync_other_refused && sync_ring_out_of_place_ok(n, h->d)) {
+    if (S >= 2 && !(h->o.flags & ADPSGD_FLAG_SYNC_IN_PLACE) && !h->sync_other_refused && sync_out_of_place_ok(n, h->d)) {
         if (h->sync_other.reserve(static_cast<size_t>(n) * static_cast<size_t>(h->o.ldx) * sizeof(float)) == hipSuccess) {
             other = static_cast<float*>(h->sync_other.p);
         } else {

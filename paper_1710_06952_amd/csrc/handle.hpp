@@ -71,7 +71,7 @@ struct adpsgd {
     adpsgd_impl::DevBuf grad_scratch;     // dots partials + coefficients / MLP activations
     adpsgd_impl::DevBuf comp_rows;        // perceptron, wait-free variant: compensated bf16 copies of the rows a group of gradients reads
     adpsgd_impl::DevBuf diag;             // consensus partials, result, mean / broadcast staging
-    adpsgd_impl::DevBuf sync_other;       // synchronous schedule on a ring: the second model matrix of the out-of-place iterations
+    adpsgd_impl::DevBuf sync_other;       // synchronous schedule: the second model matrix of the out-of-place iterations
     bool sync_other_refused = false;      // ... its allocation failed once: the iterations run in place from then on
     adpsgd_stats_t stats{};
     std::vector<hipEvent_t> ev_pool;                       // profiling events

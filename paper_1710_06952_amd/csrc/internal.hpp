@@ -192,10 +192,10 @@ struct SyncArgs {
     float* V;                // momentum buffers or nullptr
     float momentum, weight_decay;
     bool ring;               // the graph is a ring with neighbour lists (i - 1, i + 1) mod n, n >= 3: no LDS staging needed
-    float* Xdst = nullptr;   // ring only: write the new models to this matrix (same ld, not X) instead of in place
+    float* Xdst = nullptr;   // write the new models to this matrix (same ld, not X) instead of in place
 };
 int32_t sync_tile_cols(int32_t n);   // 0: n too large for the in-place mixing kernel
-bool sync_ring_out_of_place_ok(int32_t n, int64_t d);   // the launch geometry of the out-of-place ring kernel exists
+bool sync_out_of_place_ok(int32_t n, int64_t d);   // the launch geometry of the out-of-place kernels exists
 hipError_t launch_sync_mix_apply(const SyncArgs& a, hipStream_t st);
 
 hipError_t launch_broadcast_rows(float* X, int64_t ld, int64_t d, int32_t n, const float* x0, hipStream_t st);

@@ -810,6 +810,37 @@ def test_sync_steps_on_a_ring_in_place_and_between_two_matrices_give_the_same_bi
     assert rel_err(got[0][0], Xr) <= TOL
 
 
+@pytest.mark.parametrize("graph,n,d,mu", [("reg4", 16, 800003, 0.0), ("hop", 24, 5003, 0.9), ("reg4", 9, 1025, 0.9), ("ring2", 2, 4100, 0.0),
+                                          ("hop", 130, 9000, 0.0)])
+def test_sync_steps_on_any_graph_in_place_and_between_two_matrices_give_the_same_bits(P, graph, n, d, mu):
+    """Graphs that are not a canonical ring: a call with one iteration stages tiles of all rows in LDS and mixes in
+    place, longer calls alternate between two matrices with one-tile blocks in row order (bands of 6144 / n tiles:
+    the longest model spans three of them).  Same order of the sum, same bits; and both match the oracle."""
+    from workloads import hop_ring_graph
+    g = {"reg4": lambda: random_regular4_graph(n, 3), "hop": lambda: hop_ring_graph(n), "ring2": lambda: ring_graph(2)}[graph]()
+    S, wd = 5, (1e-3 if mu else 0.0)
+    std = float(np.float32(0.05))
+    x0 = np.random.default_rng(8).standard_normal((n, d)).astype(np.float32)
+    got = []
+    for calls, flag in (([S], False), ([1] * S, False), ([S], True)):
+        _say("sync steps on %s n=%d, calls %s%s" % (graph, n, calls, ", in place by request" if flag else ""))
+        eng = P.Engine(g, d, "synth", gamma=0.2, synth_std=std, synth_seed=3, momentum=mu, weight_decay=wd, sync_in_place=flag)
+        eng.set_models(x0, broadcast=False)
+        for c in calls:
+            eng.run_sync_steps(c)
+        got.append((eng.get_models(), eng.get_momentum() if mu else None))
+        eng.close()
+    for X, V in got[1:]:
+        assert np.array_equal(X, got[0][0])
+        assert V is None or np.array_equal(V, got[0][1])
+    Xr, Vr = x0.copy(), np.zeros_like(x0)
+    oracle.run_sync_steps(Xr, None, oracle.metropolis_weights(g), oracle.MODEL_SYNTH, 0.2, synth_std=std, synth_seed=3,
+                          steps=S, momentum=mu, weight_decay=wd, V=Vr if mu else None)
+    assert rel_err(got[0][0], Xr) <= TOL
+    if mu:
+        assert v_err(got[0][1], Vr) <= V_TOL
+
+
 def test_sync_ring_full_size_sampled_coordinates(P):
     """The synchronous schedule at the headline shape (n = 128, d = 25.6 M, ring, gradients drawn in the kernel), five
     iterations in one call: one in place, then two pairs between the two matrices, 13 bands of columns.  Every
