@@ -265,6 +265,33 @@ def test_config3_full_size_sampled_coordinates(P):
     eng.close()
 
 
+def test_config3_full_size_with_the_experiments_optimizer_sampled_coordinates(P):
+    """The headline shape with momentum 0.9 and weight decay 1e-4 (`bench.py --momentum 0.9 --weight-decay 1e-4`:
+    24 B per parameter and event), all 100 000 events: models and momentum buffers on 1024 sampled coordinates."""
+    import torch
+    c = get_config(3)
+    n, d, K, mu, wd = c["n"], c["d"], c["K"], 0.9, 1e-4
+    g = ring_graph(n)
+    std = float(np.float32(c["synth_std"]))
+    eng = P.Engine(g, d, "synth", gamma=c["gamma"], T_max=c["T_max"], synth_std=std, synth_seed=c["seed"], momentum=mu, weight_decay=wd)
+    x0 = np.random.default_rng(11).standard_normal(d).astype(np.float32)
+    eng.set_models(x0)
+    step = 10000
+    rng = np.random.default_rng(0)
+    coords = np.unique(np.concatenate([[0, 1, 2, 3, 4095, 4096, d - 2, d - 1], rng.integers(0, d, 1016)]))
+    Xr, Vr = np.tile(x0[coords], (n, 1)), np.zeros((n, coords.size), np.float32)
+    for s in range(K // step):
+        _say("config 3 full size with momentum: events %d..%d" % (s * step, (s + 1) * step))
+        sc = P.adpsgd_make_schedule(g, step, seed=c["seed"], k_begin=s * step, T_max=c["T_max"])
+        eng.run_events(sc)
+        oracle.run_events(Xr, sc, oracle.MODEL_SYNTH, c["gamma"], synth_std=std, synth_seed=c["seed"], event_base=s * step,
+                          coords=coords, momentum=mu, weight_decay=wd, V=Vr)
+    idx = torch.from_numpy(coords).to("cuda:0")
+    assert rel_err(eng.X[:, idx].cpu().numpy(), Xr) <= TOL
+    assert v_err(eng.V[:, idx].cpu().numpy(), Vr) <= V_TOL
+    eng.close()
+
+
 def test_parameter_index_beyond_32_bits(P):
     """d = 2^31 + 4101: element indices and byte offsets inside one replica exceed 32 bits (25.8 GB of
     models for 3 workers).  Models start at zero as allocated; the oracle follows sampled coordinates
