@@ -47,7 +47,7 @@ struct SyncParams {
     float momentum, weight_decay;
     float* Y;                  // the ring written out of place: the matrix that receives the new models (same ld)
     int64_t tiles;             // ... its tiles of 1024 columns,
-    uint32_t band, band_last, bands;   // tiles per band of columns (multiples of 8), in the last band, and the bands
+    uint32_t band;             // and the tiles per band of columns, a multiple of 8 (grid = (band, n, bands))
 };
 
 // grid = ceil(d / cols); thread = (quad of 4 columns, row lane)
@@ -267,13 +267,14 @@ hipError_t launch_ring(const SyncParams& p, bool synth, hipStream_t st) {
 // (stream_bench: 6.6 TB/s with 8 pieces, 5.0 with 128).  A traversal in row order cannot update in place, since
 // the old row i is still needed by rows i - 1 and i + 1.  So iterations that come in pairs write the new models to
 // a second matrix and back: a block is one tile of 1024 columns of ONE row (three loads of X, the gradient, one
-// store per lane), and the blocks are ordered (band of ~2048 tiles, row, tile).  The chip then works on about one
+// store per lane), and the grid (tile in band, row, band) is dispatched x fastest, i.e. in the order (band of ~2048
+// tiles, row, tile).  The chip then works on about one
 // row of a band at a time; tile t of rows i - 1, i, i + 1 meets the same XCD (block ids go round the 8 XCDs and the
 // band widths are multiples of 8) 2048 and 4096 blocks apart, so two of the three loads of X hit that XCD's L2
 // (a band of three rows is 24 MB of the chip's 32 MB) and HBM sees the same 12 B per parameter and worker update as
 // in place (counters: 39.9 GB per iteration against 39.3 GB algorithmic).  Measured at n = 128, d = 25.6 M with
 // gradients from slots: 6.84-6.93 ms per iteration = 5.7 TB/s against 7.7 ms in place; with momentum buffers 12.0
-// against 13.1 ms; with gradients drawn in registers 5.6 against 6.0 ms.  A stand-alone kernel with this traversal
+// against 13.1 ms; with gradients drawn in registers 5.3 against 6.0 ms.  A stand-alone kernel with this traversal
 // and nothing else ran 6.54 ms with bands of 2048 tiles, 6.68 / 6.57 / 6.62 / 7.66 ms with 1024 / 1536 / 2560 / 3072;
 // 7.3 / 7.6 ms with two / four rows per block (fewer loads through L2, more streams); 7.4 ms with one dword per lane
 // and four accesses.  The loads of X stay cached whatever the size; the sums have the order of the walking kernel
@@ -282,15 +283,10 @@ constexpr uint32_t kBandTiles = 2048;
 
 template <bool SYNTH, bool SHADOW, bool MOM, bool STREAM>
 __global__ __launch_bounds__(kRingThreads) void sync_ring_rows_kernel(const SyncParams p) {
-    const uint32_t per_band = static_cast<uint32_t>(p.n) * p.band;
-    uint32_t b = blockIdx.x / per_band;
-    if (b >= p.bands) b = p.bands - 1;
-    const uint32_t r = blockIdx.x - b * per_band;
-    const uint32_t width = b == p.bands - 1 ? p.band_last : p.band;
-    const int32_t i = static_cast<int32_t>(r / width);
-    const int64_t tile = static_cast<int64_t>(b) * p.band + r % width;
+    const int32_t i = static_cast<int32_t>(blockIdx.y);     // blocks are dispatched x fastest: (band, row, tile) order
+    const int64_t tile = static_cast<int64_t>(blockIdx.z) * p.band + blockIdx.x;
     const int64_t c = 4 * (tile * kRingThreads + threadIdx.x);
-    if (i >= p.n || tile >= p.tiles || c >= p.d) return;
+    if (tile >= p.tiles || c >= p.d) return;
     const int32_t im = i == 0 ? p.n - 1 : i - 1, ip = i == p.n - 1 ? 0 : i + 1;
     float prev[4], cur[4], nxt[4], g[4], vo[4];
     ring_load<false>(p.X + static_cast<int64_t>(ip) * p.ld, c, nxt);       // first touch of this tile: from HBM
@@ -333,19 +329,17 @@ __global__ __launch_bounds__(kRingThreads) void sync_ring_rows_kernel(const Sync
     }
 }
 
-// bands of at most `limit` tiles, all but the last of one width, every width a multiple of 8; false: too many blocks
-bool rows_geometry(int32_t n, int64_t d, int64_t limit, int64_t& tiles, uint32_t& band, uint32_t& band_last, uint32_t& bands, int64_t& blocks) {
+// bands of one width of at most `limit` tiles, a multiple of 8 (the last band is cut short by at most 8 tiles per band
+// in all: those blocks leave at once); false: the grid does not exist
+bool rows_geometry(int32_t n, int64_t d, int64_t limit, int64_t& tiles, uint32_t& band, dim3& grid) {
     tiles = (d + 4 * kRingThreads - 1) / (4 * kRingThreads);
-    if (n < 1 || tiles < 1) return false;
+    if (n < 1 || n > 65535 || tiles < 1) return false;
     const int64_t want = (tiles + limit - 1) / limit;
     const int64_t width = ((tiles + want - 1) / want + 7) / 8 * 8;
     const int64_t count = (tiles + width - 1) / width;
-    const int64_t last = (tiles - (count - 1) * width + 7) / 8 * 8;
-    blocks = static_cast<int64_t>(n) * ((count - 1) * width + last);
-    if (blocks > 0x7FFFFFFF || static_cast<int64_t>(n) * width > 0x7FFFFFFF) return false;
+    if (count > 65535) return false;
     band = static_cast<uint32_t>(width);
-    band_last = static_cast<uint32_t>(last);
-    bands = static_cast<uint32_t>(count);
+    grid = dim3(static_cast<uint32_t>(width), static_cast<uint32_t>(n), static_cast<uint32_t>(count));
     return true;
 }
 // tiles per band so that `rows` rows of a band stay in L2 (about 3 of the 4 MB of each of the 8 XCDs, 4 KiB per tile and row)
@@ -356,9 +350,9 @@ int64_t band_limit(int64_t rows) {
 
 template <bool MOM, bool STREAM>
 hipError_t launch_ring_rows(SyncParams& p, bool synth, hipStream_t st) {
-    int64_t blocks = 0;
-    if (p.n < 3 || !rows_geometry(p.n, p.d, band_limit(3), p.tiles, p.band, p.band_last, p.bands, blocks)) return hipErrorInvalidValue;
-    const dim3 grid(static_cast<uint32_t>(blocks)), block(kRingThreads);
+    dim3 grid;
+    const dim3 block(kRingThreads);
+    if (p.n < 3 || !rows_geometry(p.n, p.d, band_limit(3), p.tiles, p.band, grid)) return hipErrorInvalidValue;
     if (synth) hipLaunchKernelGGL((sync_ring_rows_kernel<true, false, MOM, STREAM>), grid, block, 0, st, p);
     else if (p.Xbf16) hipLaunchKernelGGL((sync_ring_rows_kernel<false, true, MOM, STREAM>), grid, block, 0, st, p);
     else hipLaunchKernelGGL((sync_ring_rows_kernel<false, false, MOM, STREAM>), grid, block, 0, st, p);
@@ -375,15 +369,10 @@ hipError_t launch_ring_rows(SyncParams& p, bool synth, hipStream_t st) {
 // The sum has the tile kernel's order: own row, then the neighbours as listed.
 template <bool SYNTH, bool SHADOW, bool MOM, bool STREAM>
 __global__ __launch_bounds__(kRingThreads) void sync_graph_rows_kernel(const SyncParams p) {
-    const uint32_t per_band = static_cast<uint32_t>(p.n) * p.band;
-    uint32_t b = blockIdx.x / per_band;
-    if (b >= p.bands) b = p.bands - 1;
-    const uint32_t r = blockIdx.x - b * per_band;
-    const uint32_t width = b == p.bands - 1 ? p.band_last : p.band;
-    const int32_t i = static_cast<int32_t>(r / width);
-    const int64_t tile = static_cast<int64_t>(b) * p.band + r % width;
+    const int32_t i = static_cast<int32_t>(blockIdx.y);     // blocks are dispatched x fastest: (band, row, tile) order
+    const int64_t tile = static_cast<int64_t>(blockIdx.z) * p.band + blockIdx.x;
     const int64_t c = 4 * (tile * kRingThreads + threadIdx.x);
-    if (i >= p.n || tile >= p.tiles || c >= p.d) return;
+    if (tile >= p.tiles || c >= p.d) return;
     float own[4], g[4], vo[4];
     ring_load<false>(p.X + static_cast<int64_t>(i) * p.ld, c, own);
     if (SYNTH) {
@@ -445,9 +434,9 @@ __global__ __launch_bounds__(kRingThreads) void sync_graph_rows_kernel(const Syn
 
 template <bool MOM, bool STREAM>
 hipError_t launch_graph_rows(SyncParams& p, bool synth, hipStream_t st) {
-    int64_t blocks = 0;
-    if (!rows_geometry(p.n, p.d, band_limit(p.n), p.tiles, p.band, p.band_last, p.bands, blocks)) return hipErrorInvalidValue;
-    const dim3 grid(static_cast<uint32_t>(blocks)), block(kRingThreads);
+    dim3 grid;
+    const dim3 block(kRingThreads);
+    if (!rows_geometry(p.n, p.d, band_limit(p.n), p.tiles, p.band, grid)) return hipErrorInvalidValue;
     if (synth) hipLaunchKernelGGL((sync_graph_rows_kernel<true, false, MOM, STREAM>), grid, block, 0, st, p);
     else if (p.Xbf16) hipLaunchKernelGGL((sync_graph_rows_kernel<false, true, MOM, STREAM>), grid, block, 0, st, p);
     else hipLaunchKernelGGL((sync_graph_rows_kernel<false, false, MOM, STREAM>), grid, block, 0, st, p);
@@ -479,10 +468,10 @@ int32_t sync_tile_cols(int32_t n) {
 }
 
 bool sync_out_of_place_ok(int32_t n, int64_t d) {
-    int64_t tiles = 0, blocks = 0;
-    uint32_t band = 0, band_last = 0, bands = 0;
-    return rows_geometry(n, d, band_limit(n), tiles, band, band_last, bands, blocks) &&
-           rows_geometry(n, d, band_limit(3), tiles, band, band_last, bands, blocks);
+    int64_t tiles = 0;
+    uint32_t band = 0;
+    dim3 grid;
+    return rows_geometry(n, d, band_limit(n), tiles, band, grid) && rows_geometry(n, d, band_limit(3), tiles, band, grid);
 }
 
 hipError_t launch_sync_mix_apply(const SyncArgs& a, hipStream_t st) {
@@ -515,7 +504,7 @@ hipError_t launch_sync_mix_apply(const SyncArgs& a, hipStream_t st) {
     const bool stream = static_cast<int64_t>(a.n) * a.ld * 4 > (256ll << 20);      // X does not fit the memory-side cache
     p.Y = a.Xdst;
     p.tiles = 0;
-    p.band = p.band_last = p.bands = 0;
+    p.band = 0;
     if (a.Xdst) {
         if (a.Xdst == a.X) return hipErrorInvalidValue;
         if (a.ring) {
