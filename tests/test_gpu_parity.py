@@ -926,10 +926,13 @@ def test_sync_steps_linear_models(P, model):
     eng.close()
 
 
-def test_sync_steps_mlp(P):
-    n, dims, rows, M, S = 6, (24, 64, 5), 40, 16, 20
-    _say("sync steps, mlp")
-    g = ring_graph(n)
+@pytest.mark.parametrize("graph,S", [("ring", 20), ("reg4", 20), ("reg4", 1), ("ring", 3)])
+def test_sync_steps_mlp(P, graph, S):
+    """The perceptron under the synchronous schedule: every mixing kernel also rewrites the bf16 shadow (even numbers
+    of iterations between two matrices, a single one in place, on the ring and on another graph)."""
+    n, dims, rows, M = 6, (24, 64, 5), 40, 16
+    _say("sync steps, mlp, %s, %d iterations" % (graph, S))
+    g = ring_graph(n) if graph == "ring" else random_regular4_graph(n, 4)
     from workloads import mixture_data, mlp_init, f32_to_bf16_bits
     feats, labels, _ = mixture_data(n, rows, din=dims[0], classes=dims[2], seed=5)
     d = dims[0] * dims[1] + dims[1] + dims[1] * dims[2] + dims[2]
