@@ -360,17 +360,18 @@ def main():
             out["roofline"]["kernel"] = "fused_gossip_apply_kernel<synth, momentum>"
     # diagnostics (outside the timed region): consensus distance and mean model each read X once.  The second of two
     # calls is timed (the first one allocates the library's small result buffers), the output vector allocated before;
-    # HIP events on the library's stream bracket each call (its kernels, and for the consensus distance its 8-byte copy)
+    # HIP events on the library's stream bracket each call: for the consensus distance its kernels, its 8-byte copy and
+    # the wait for it; the mean model goes to device memory, which the call enqueues without waiting
     torch.cuda.synchronize()
     mean_dev = torch.empty(d, dtype=torch.float32, device="cuda:0")
     eng.consensus_distance()
-    P.binding._check(eng.h._h, P.lib().adpsgd_get_mean_model(eng.h._h, mean_dev.data_ptr(), 1))
+    eng.h.mean_model_to_device(mean_dev.data_ptr())
     torch.cuda.synchronize()
     dv = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
     dv[0].record()
     cd = eng.consensus_distance()
     dv[1].record()
-    P.binding._check(eng.h._h, P.lib().adpsgd_get_mean_model(eng.h._h, mean_dev.data_ptr(), 1))
+    eng.h.mean_model_to_device(mean_dev.data_ptr())
     dv[2].record()
     torch.cuda.synchronize()
     t_cons, t_mean = dv[0].elapsed_time(dv[1]) * 1e-3, dv[1].elapsed_time(dv[2]) * 1e-3

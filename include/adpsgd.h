@@ -299,7 +299,10 @@ int adpsgd_metropolis_weights(const adpsgd_graph_t* graph, float* w_self, float*
  * Synchronises the stream. */
 int adpsgd_get_models(adpsgd_t* h, float* out, int64_t ld_out, int32_t on_device);
 
-/* Algorithm 1's output: the average of all workers' models (d floats). Synchronous. */
+/* Algorithm 1's output: the average of all workers' models (d floats), column sums in row order accumulated in
+ * fp64.  out on the host (on_device == 0): the call waits for the stream and copies the result.  out on the device:
+ * the kernel is enqueued on the handle's stream and the call returns; the result is ready in stream order and out
+ * must stay valid until then. */
 int adpsgd_get_mean_model(adpsgd_t* h, float* out, int32_t on_device);
 
 /* Consensus distance (1/n) sum_i |mean - x^i|^2: the quantity M_k of the proofs

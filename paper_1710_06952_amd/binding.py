@@ -386,6 +386,10 @@ class Handle:
         _check(self._h, lib().adpsgd_get_mean_model(self._h, res.ctypes.data, 0))
         return res
 
+    def mean_model_to_device(self, out_device_ptr):
+        """The mean model into d floats of device memory, enqueued on the handle's stream (no wait)."""
+        _check(self._h, lib().adpsgd_get_mean_model(self._h, out_device_ptr, 1))
+
     def objective(self, x_ptr=None, p=None):
         """f at a device vector (integer pointer), or at the mean model when x_ptr is None; p: the workers'
         probabilities (default 1 / n)."""

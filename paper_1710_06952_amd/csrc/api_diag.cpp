@@ -49,8 +49,8 @@ extern "C" int adpsgd_get_mean_model(adpsgd_t* h, float* out, int32_t on_device)
         dst = static_cast<float*>(h->diag.p);
     }
     HIP_TRY(h, launch_mean_model(h->o.X, h->o.ldx, h->d, h->n, dst, h->stream));
-    if (!on_device)
-        HIP_TRY(h, hipMemcpyAsync(out, dst, static_cast<size_t>(h->d) * 4, hipMemcpyDeviceToHost, h->stream));
+    if (on_device) return ADPSGD_OK;      // ready in stream order: the caller goes on working on the stream
+    HIP_TRY(h, hipMemcpyAsync(out, dst, static_cast<size_t>(h->d) * 4, hipMemcpyDeviceToHost, h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));
     return ADPSGD_OK;
 }

@@ -1595,6 +1595,32 @@ def test_classification_error_matches_the_oracle(P):
     eng.close()
 
 
+@pytest.mark.parametrize("n,d", [(5, 1030), (128, 4099), (3, 7)])
+def test_mean_model_into_device_memory_is_stream_ordered(P, n, d):
+    """The mean model written to device memory (the call enqueues and returns) equals the host copy bit for bit, also
+    at an output address that is not 16-byte aligned, and follows the stream: events enqueued before it are in it."""
+    import torch
+    g = ring_graph(n)
+    std = float(np.float32(0.05))
+    eng = P.Engine(g, d, "synth", gamma=0.2, T_max=2, synth_std=std, synth_seed=3)
+    x0 = np.random.default_rng(1).standard_normal((n, d)).astype(np.float32)
+    eng.set_models(x0, broadcast=False)
+    sched = oracle.make_schedule(g, 40, seed=4, T_max=2)
+    buf = torch.zeros(d + 8, dtype=torch.float32, device="cuda:0")
+    eng.run_events(sched)                                   # enqueued, not waited for
+    eng.h.mean_model_to_device(buf.data_ptr())
+    eng.h.mean_model_to_device(buf[1:].data_ptr())          # 4 bytes past a 16-byte boundary: the dword-store path
+    torch.cuda.synchronize()
+    host = eng.get_mean_model()
+    Xr = x0.copy()
+    oracle.run_events(Xr, sched, oracle.MODEL_SYNTH, 0.2, synth_std=std, synth_seed=3)
+    assert np.allclose(host, oracle.mean_model(Xr), rtol=1e-5, atol=1e-6)
+    got = buf.cpu().numpy()
+    assert np.array_equal(got[1:d + 1], host)               # the second call wrote at an offset of one float
+    assert got[0] == host[0] and np.all(got[d + 1:] == 0)   # the first call's first element survives, nothing beyond d
+    eng.close()
+
+
 def test_objective_is_refused_without_a_data_model(P):
     eng = P.Engine(ring_graph(4), 64, "synth", gamma=0.1, synth_std=0.1)
     with pytest.raises(P.AdpsgdError) as ei:
